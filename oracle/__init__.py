@@ -1,0 +1,156 @@
+"""Python face of the CPU oracle (ctypes over oracle/bastion_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  The HIP package never imports this module, and this module never
+imports the HIP package.  Arrays in, arrays out; all arithmetic lives in the C file
+(and in bruteforce.py for the exhaustive pins).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bastion_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over (node, head) pairs)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.orc_tree_build.restype = C.c_int
+        _lib.orc_tree_attn.restype = C.c_int
+        _lib.orc_accept_greedy.restype = C.c_int
+        _lib.orc_accept_stochastic.restype = C.c_int
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def rank_tokens(marg: np.ndarray) -> np.ndarray:
+    marg = np.ascontiguousarray(marg, dtype=np.float32)
+    B, V = marg.shape
+    order = np.empty((B, V), dtype=np.int32)
+    _load().orc_rank_tokens(_p(marg, C.c_float), B, V, _p(order, C.c_int32))
+    return order
+
+
+def tree_build(marg: np.ndarray, N: int) -> dict:
+    """Best-first tree of N draft nodes from marginals [B, V] (Sec. 3.3, Prop. 3.3, Alg. 1 frontier rule)."""
+    marg = np.ascontiguousarray(marg, dtype=np.float32)
+    B, V = marg.shape
+    parent = np.empty(max(N, 1), dtype=np.int32)
+    token = np.empty_like(parent)
+    depth = np.empty_like(parent)
+    rank = np.empty_like(parent)
+    rho = np.empty(max(N, 1), dtype=np.float32)
+    ahat = C.c_double(0.0)
+    n = _load().orc_tree_build(_p(marg, C.c_float), B, V, N, _p(parent, C.c_int32), _p(token, C.c_int32),
+                               _p(depth, C.c_int32), _p(rho, C.c_float), _p(rank, C.c_int32), C.byref(ahat))
+    if n < 0:
+        raise ValueError("orc_tree_build: bad arguments")
+    return {"n": n, "parent": parent[:n], "token": token[:n], "depth": depth[:n], "rank": rank[:n],
+            "rho": rho[:n], "ahat": ahat.value}
+
+
+def tree_attn(Qf, Kf, Vf, parent, L: int, scale: float | None = None, pairs=None, block_table=None, page: int = 16,
+              nthreads: int = 0) -> np.ndarray:
+    """Tree-masked attention by its definition (App. C), fp64.
+
+    Qf [M,Hq,D], Kf/Vf [rows,Hkv,D] fp32 (exact stored values); rows = L+M when contiguous, or the flattened
+    page pool when block_table (1-D, for this sequence) is given.  Returns [M,Hq,D] or [npairs,D] fp64.
+    """
+    Qf = np.ascontiguousarray(Qf, dtype=np.float32)
+    Kf = np.ascontiguousarray(Kf, dtype=np.float32)
+    Vf = np.ascontiguousarray(Vf, dtype=np.float32)
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    M, Hq, D = Qf.shape
+    if Kf.ndim == 4:   # [num_blocks, page, Hkv, D]
+        Kf = Kf.reshape(-1, Kf.shape[2], Kf.shape[3])
+        Vf = Vf.reshape(-1, Vf.shape[2], Vf.shape[3])
+    Hkv = Kf.shape[1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    if block_table is None:
+        assert Kf.shape[0] >= L + M and Vf.shape[0] >= L + M
+        bt = None
+    else:
+        block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+        assert len(block_table) * page >= L + M
+        bt = _p(block_table, C.c_int32)
+    if pairs is None:
+        out = np.empty((M, Hq, D), dtype=np.float64)
+        pp, npairs = None, 0
+    else:
+        pairs = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        out = np.empty((len(pairs), D), dtype=np.float64)
+        pp, npairs = _p(pairs, C.c_int32), len(pairs)
+    if nthreads <= 0:
+        nthreads = num_threads()
+    rc = _load().orc_tree_attn(_p(Qf, C.c_float), _p(Kf, C.c_float), _p(Vf, C.c_float), _p(parent, C.c_int32),
+                               M, L, Hq, Hkv, D, C.c_double(scale), bt, page, pp, npairs, _p(out, C.c_double),
+                               nthreads)
+    if rc != 0:
+        raise ValueError(f"orc_tree_attn: bad arguments ({rc})")
+    return out
+
+
+def row_argmax(logits_f32: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(logits_f32, dtype=np.float32)
+    t = np.empty(x.shape[0], dtype=np.int32)
+    _load().orc_row_argmax(_p(x, C.c_float), x.shape[0], x.shape[1], _p(t, C.c_int32))
+    return t
+
+
+def accept_greedy(logits_f32, parent, token) -> dict:
+    """Greedy acceptance (App. C "Acceptance"): longest path matching the target's top-1 tokens."""
+    x = np.ascontiguousarray(logits_f32, dtype=np.float32)
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    token = np.ascontiguousarray(token, dtype=np.int32)
+    M = len(parent)
+    assert x.shape[0] == M + 1
+    path = np.empty(max(M, 1), dtype=np.int32)
+    t = np.empty(M + 1, dtype=np.int32)
+    bonus = C.c_int32(0)
+    n = _load().orc_accept_greedy(_p(x, C.c_float), _p(parent, C.c_int32), _p(token, C.c_int32), M, x.shape[1],
+                                  _p(path, C.c_int32), C.byref(bonus), _p(t, C.c_int32))
+    return {"n_acc": n, "path": path[:n].copy(), "bonus": int(bonus.value), "argmax": t}
+
+
+def accept_stochastic(logits_f32, marg, parent, token, depth, uniforms) -> dict:
+    """Token-level rejection walk at temperature 1 (the reading stated in the C file)."""
+    x = np.ascontiguousarray(logits_f32, dtype=np.float32)
+    marg = np.ascontiguousarray(marg, dtype=np.float32)
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    token = np.ascontiguousarray(token, dtype=np.int32)
+    depth = np.ascontiguousarray(depth, dtype=np.int32)
+    u = np.ascontiguousarray(uniforms, dtype=np.float32)
+    M = len(parent)
+    assert x.shape[0] == M + 1 and len(u) >= M + 1 and marg.shape[1] == x.shape[1]
+    path = np.empty(max(M, 1), dtype=np.int32)
+    bonus, used, margin = C.c_int32(0), C.c_int32(0), C.c_double(0.0)
+    n = _load().orc_accept_stochastic(_p(x, C.c_float), _p(marg, C.c_float), marg.shape[0], _p(parent, C.c_int32),
+                                      _p(token, C.c_int32), _p(depth, C.c_int32), M, x.shape[1], _p(u, C.c_float),
+                                      _p(path, C.c_int32), C.byref(bonus), C.byref(used), C.byref(margin))
+    return {"n_acc": n, "path": path[:n].copy(), "bonus": int(bonus.value), "n_uniforms": int(used.value),
+            "margin": float(margin.value)}

@@ -1,0 +1,327 @@
+/*
+ * CPU oracle for the tree-verify path of budget-aware tree speculative decoding.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow and meant to be checked against the paper by eye.
+ * It shares no code with the HIP library and must never be reached from the product path:
+ * only the tests, the smoke check and the benchmark's cpu_baseline leg may load it.
+ *
+ * Every function cites the passage of the paper it follows.  Floating point is fp64,
+ * except where a floating-point value decides an integer output that the HIP path must
+ * reproduce bit for bit (the path score rho, which orders the tree): there both sides
+ * use one IEEE fp32 multiply per tree edge, as stated below.
+ *
+ * Pins (tests/, run with -m "not gpu"):
+ *   orc_tree_build       brute-force enumeration of all prefixes (Prop. 3.3), closed forms,
+ *                        Monte-Carlo self-verification (Prop. 3.2)
+ *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
+ *   orc_accept_greedy    brute force over all root-to-node paths, planted paths
+ *   orc_accept_stochastic  closed-form special cases and an empirical chi-square test of the
+ *                        single-child case; the multi-child rule is not given by the paper:
+ *                        parity unpinned beyond those cases.
+ */
+#define _GNU_SOURCE
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------------------------
+ * Per-position ranking of the drafter's marginals (Sec. 3.3: candidate lattice of the top
+ * tokens at each position).  rank r of position k = r-th token when sorted by probability
+ * descending, token id ascending on equal probability.
+ * ---------------------------------------------------------------------------------------- */
+static int cmp_prob_desc_id_asc(const void *a, const void *b, void *ctx)
+{
+    const float *q = (const float *)ctx;
+    int32_t ia = *(const int32_t *)a, ib = *(const int32_t *)b;
+    if (q[ia] > q[ib]) return -1;
+    if (q[ia] < q[ib]) return 1;
+    return (ia > ib) - (ia < ib);
+}
+
+/* order[k*V + r] = token id of rank r at position k */
+void orc_rank_tokens(const float *marg, int B, int V, int32_t *order)
+{
+    for (int k = 0; k < B; ++k) {
+        int32_t *o = order + (size_t)k * V;
+        for (int v = 0; v < V; ++v) o[v] = v;
+        qsort_r(o, (size_t)V, sizeof(int32_t), cmp_prob_desc_id_asc, (void *)(marg + (size_t)k * V));
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Best-first expansion at a fixed budget N (Sec. 3.3 Prop. 3.3; Algorithm 1 without the
+ * early stop).  A candidate is a prefix of the lattice: (parent node, rank at its depth).
+ * Path score (Eq. 1): rho(root) = 1, rho(child) = rho(parent) * q_depth(token), evaluated as
+ * one fp32 multiply per edge.  N counts draft (non-root) nodes; Ahat = 1 + sum rho (Eq. 3,
+ * the root contributes 1).
+ *
+ * Selection order (the paper leaves ties open): rho descending, then depth ascending, then
+ * the rank path (r_1..r_d) lexicographically ascending.  The frontier is the set of prefixes
+ * whose parent is in the tree and whose previous sibling (rank-1) is in the tree; it is kept
+ * as a plain array and scanned linearly for the best element.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct { float rho; int32_t depth, parent, rank; } cand_t;
+
+static int rank_path(const int32_t *parent, const int32_t *rank, const int32_t *depth, int32_t p, int32_t r,
+                     int32_t *out)
+{   /* rank path of the candidate (parent node p, rank r); returns its length */
+    int d = (p < 0) ? 1 : depth[p] + 1;
+    out[d - 1] = r;
+    for (int32_t a = p; a >= 0; a = parent[a]) out[depth[a] - 1] = rank[a];
+    return d;
+}
+
+static int cand_before(const cand_t *a, const cand_t *b, const int32_t *parent, const int32_t *rank,
+                       const int32_t *depth, int B)
+{
+    if (a->rho != b->rho) return a->rho > b->rho;
+    if (a->depth != b->depth) return a->depth < b->depth;
+    int32_t pa[64], pb[64];
+    (void)B;
+    int d = rank_path(parent, rank, depth, a->parent, a->rank, pa);
+    rank_path(parent, rank, depth, b->parent, b->rank, pb);
+    for (int i = 0; i < d; ++i)
+        if (pa[i] != pb[i]) return pa[i] < pb[i];
+    return 0;
+}
+
+/* Returns the number of nodes emitted (= N unless the lattice has fewer prefixes), or -1 on bad arguments.
+ * parent[i] = -1 for children of the root; depth is 1-based; rank[i] = sibling rank of node i. */
+int orc_tree_build(const float *marg, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
+                   float *rho, int32_t *rank, double *ahat)
+{
+    if (B < 1 || B > 64 || V < 1 || N < 0) return -1;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * V);
+    cand_t *front = (cand_t *)malloc(sizeof(cand_t) * (size_t)(N + 2));
+    orc_rank_tokens(marg, B, V, order);
+    int nf = 0, n = 0;
+    double a = 1.0;
+    /* the root's best child */
+    front[nf++] = (cand_t){ 1.0f * marg[order[0]], 1, -1, 0 };
+    while (n < N && nf > 0) {
+        int best = 0;
+        for (int j = 1; j < nf; ++j)
+            if (cand_before(&front[j], &front[best], parent, rank, depth, B)) best = j;
+        cand_t u = front[best];
+        front[best] = front[--nf];
+        parent[n] = u.parent; rank[n] = u.rank; depth[n] = u.depth; rho[n] = u.rho;
+        token[n] = order[(size_t)(u.depth - 1) * V + u.rank];
+        a += (double)u.rho;
+        /* frontier update: best child of u, and u's next sibling */
+        if (u.depth < B) {
+            float q = marg[(size_t)u.depth * V + order[(size_t)u.depth * V + 0]];
+            volatile float r = u.rho * q;                 /* one rounded fp32 multiply */
+            front[nf++] = (cand_t){ r, u.depth + 1, n, 0 };
+        }
+        if (u.rank + 1 < V) {
+            float prho = (u.parent < 0) ? 1.0f : rho[u.parent];
+            float q = marg[(size_t)(u.depth - 1) * V + order[(size_t)(u.depth - 1) * V + u.rank + 1]];
+            volatile float r = prho * q;
+            front[nf++] = (cand_t){ r, u.depth, u.parent, u.rank + 1 };
+        }
+        ++n;
+    }
+    if (ahat) *ahat = a;
+    free(order); free(front);
+    return n;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Tree-masked attention (App. C, "Linearization and verification mask"): node i attends to
+ * the L prefix rows of the KV cache and to the tree rows of its own ancestors and itself,
+ * nothing else.  For query head h (KV head h / (Hq/Hkv)):
+ *     O[i,h] = sum_j softmax_j( scale * Q[i,h].K[j] ) V[j],   j over  0..L-1, then L+a for a on
+ *     the root-to-i path.
+ * Written as the definition: gather the visible rows, scores, max-subtracted softmax, weighted sum.
+ *
+ * Inputs are fp32 arrays holding the exact stored values (bf16-rounded when the HIP path runs in
+ * bf16).  K/V row j lives at physical row  j                       if block_table == NULL,
+ *                                          block_table[j/page]*page + j%page   otherwise.
+ * pairs: npairs x 2 (node, head) to evaluate, or NULL for all (node-major, head-minor).
+ * O: fp64 [npairs or M*Hq, D].
+ * ---------------------------------------------------------------------------------------- */
+static inline size_t phys_row(int j, const int32_t *block_table, int page)
+{
+    return block_table ? (size_t)block_table[j / page] * (size_t)page + (size_t)(j % page) : (size_t)j;
+}
+
+int orc_tree_attn(const float *Q, const float *K, const float *V, const int32_t *parent, int M, int L, int Hq,
+                  int Hkv, int D, double scale, const int32_t *block_table, int page, const int32_t *pairs,
+                  int npairs, double *O, int nthreads)
+{
+    if (M < 0 || L < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || D < 1) return -1;
+    for (int i = 0; i < M; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -2;
+    int total = pairs ? npairs : M * Hq;
+    int G = Hq / Hkv;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+#endif
+    for (int t = 0; t < total; ++t) {
+        int i = pairs ? pairs[2 * t] : t / Hq;
+        int h = pairs ? pairs[2 * t + 1] : t % Hq;
+        int g = h / G;
+        /* visible rows: the prefix, then the root-to-i path in path order */
+        int np = 0;
+        for (int a = i; a >= 0; a = parent[a]) ++np;
+        int nvis = L + np;
+        int *vis = (int *)malloc(sizeof(int) * (size_t)(nvis > 0 ? nvis : 1));
+        double *s = (double *)malloc(sizeof(double) * (size_t)(nvis > 0 ? nvis : 1));
+        for (int j = 0; j < L; ++j) vis[j] = j;
+        { int k = nvis; for (int a = i; a >= 0; a = parent[a]) vis[--k] = L + a; }
+        const float *q = Q + ((size_t)i * Hq + h) * D;
+        double m = -INFINITY;
+        for (int j = 0; j < nvis; ++j) {
+            const float *k = K + (phys_row(vis[j], block_table, page) * Hkv + g) * D;
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) acc += (double)q[d] * (double)k[d];
+            s[j] = acc * scale;
+            if (s[j] > m) m = s[j];
+        }
+        double z = 0.0;
+        for (int j = 0; j < nvis; ++j) { s[j] = exp(s[j] - m); z += s[j]; }
+        double *o = O + (size_t)t * D;
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int j = 0; j < nvis; ++j) {
+            const float *v = V + (phys_row(vis[j], block_table, page) * Hkv + g) * D;
+            double p = s[j] / z;
+            for (int d = 0; d < D; ++d) o[d] += p * (double)v[d];
+        }
+        free(vis); free(s);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Greedy acceptance (App. C, "Acceptance"; Sec. 3.1): the target's top-1 token at every tree
+ * row, then the longest root-to-node path whose tokens are what the target itself would have
+ * produced.  logits row 0 belongs to the root, row 1+i to node i.  Ties in the argmax go to
+ * the lowest token id (the paper is silent).  bonus = the target's token at the last accepted
+ * node (the token that seeds the next cycle).
+ * ---------------------------------------------------------------------------------------- */
+void orc_row_argmax(const float *logits, int rows, int V, int32_t *t)
+{
+    for (int r = 0; r < rows; ++r) {
+        const float *x = logits + (size_t)r * V;
+        int best = 0;
+        for (int v = 1; v < V; ++v)
+            if (x[v] > x[best]) best = v;
+        t[r] = best;
+    }
+}
+
+/* returns n_acc; path[0..n_acc) = accepted node ids in root-to-leaf order */
+int orc_accept_greedy(const float *logits, const int32_t *parent, const int32_t *token, int M, int V,
+                      int32_t *path, int32_t *bonus, int32_t *t_out /* [M+1] or NULL */)
+{
+    int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)(M + 1));
+    orc_row_argmax(logits, M + 1, V, t);
+    int cur = -1, n = 0;
+    for (;;) {
+        int next = -1;
+        for (int c = 0; c < M; ++c)
+            if (parent[c] == cur && token[c] == t[cur + 1]) { next = c; break; }
+        if (next < 0) break;
+        path[n++] = next;
+        cur = next;
+    }
+    *bonus = t[cur + 1];
+    if (t_out) memcpy(t_out, t, sizeof(int32_t) * (size_t)(M + 1));
+    free(t);
+    return n;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Stochastic acceptance at temperature 1.  The paper states only that decoding preserves the
+ * target distribution and cites standard speculative sampling (Sec. 2.1); the rule used here
+ * is the reading fixed for this build: token-level rejection of each child, in sibling order,
+ * of the target probability p against the draft marginal q of the child's depth, with the
+ * residual update on rejection and the bonus token drawn from what is left of p.
+ *
+ *   cur = root; d = 0
+ *   loop: p = softmax(logits[row(cur)]);  q = marginals[d] (copy)
+ *         for each child c of cur in node order (= sibling rank order):
+ *             x = token[c]; u = next uniform
+ *             accept c if  u * q[x] < p[x]           (u < min(1, p/q); q[x] == 0 accepts iff p[x] > 0)
+ *             else p = max(p - q, 0), renormalised (kept as is if it sums to 0);
+ *                  q[x] = 0, renormalised (left all-zero if it sums to 0)
+ *         no child accepted (or d == B): bonus = smallest v with cumsum(p)[v] > u (next uniform), stop.
+ *
+ * Uniforms are consumed strictly in order.  margin_out receives the smallest relative distance
+ * of any decision from its threshold, so a caller can discard inputs whose outcome depends on
+ * the last bits of a vocabulary-wide sum.
+ * ---------------------------------------------------------------------------------------- */
+int orc_accept_stochastic(const float *logits, const float *marg, int B, const int32_t *parent,
+                          const int32_t *token, const int32_t *depth, int M, int V, const float *uniforms,
+                          int32_t *path, int32_t *bonus, int32_t *n_uniforms_used, double *margin_out)
+{
+    double *p = (double *)malloc(sizeof(double) * (size_t)V);
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    double *r = (double *)malloc(sizeof(double) * (size_t)V);
+    int cur = -1, n = 0, ui = 0, d = 0;
+    double margin = INFINITY;
+    (void)depth;   /* the depth of cur is tracked by the walk itself */
+    for (;;) {
+        /* target distribution at the current node: softmax of its logits row */
+        const float *x = logits + (size_t)(cur + 1) * V;
+        double mx = -INFINITY, z = 0.0;
+        for (int v = 0; v < V; ++v) if ((double)x[v] > mx) mx = (double)x[v];
+        for (int v = 0; v < V; ++v) { p[v] = exp((double)x[v] - mx); z += p[v]; }
+        for (int v = 0; v < V; ++v) p[v] /= z;
+        int accepted = -1;
+        if (d < B) {
+            for (int v = 0; v < V; ++v) q[v] = (double)marg[(size_t)d * V + v];
+            for (int c = 0; c < M; ++c) {
+                if (parent[c] != cur) continue;
+                int tk = token[c];
+                double u = (double)uniforms[ui++];
+                double lhs = u * q[tk], rhs = p[tk];
+                if (!(lhs == 0.0 && rhs == 0.0)) {
+                    double rel = fabs(lhs - rhs) / (rhs > 0.0 ? rhs : lhs);
+                    if (rel < margin) margin = rel;
+                }
+                if (lhs < rhs) { accepted = c; break; }
+                /* rejected: residual target, and the draft without the tried token */
+                double zr = 0.0, zq = 0.0;
+                for (int v = 0; v < V; ++v) { double t = p[v] - q[v]; r[v] = t > 0.0 ? t : 0.0; zr += r[v]; }
+                if (zr > 0.0) for (int v = 0; v < V; ++v) p[v] = r[v] / zr;
+                q[tk] = 0.0;
+                for (int v = 0; v < V; ++v) zq += q[v];
+                if (zq > 0.0) for (int v = 0; v < V; ++v) q[v] /= zq;
+            }
+        }
+        if (accepted >= 0) { path[n++] = accepted; cur = accepted; ++d; continue; }
+        /* bonus token by inverse CDF of what is left of p */
+        double u = (double)uniforms[ui++], c = 0.0;
+        int b = -1, last_pos = 0;
+        for (int v = 0; v < V; ++v) {
+            if (p[v] > 0.0) last_pos = v;
+            double c2 = c + p[v];
+            if (b < 0 && c2 > u) {
+                b = v;
+                double gap = fmin(c2 - u, u - c);
+                if (gap < margin) margin = gap;
+            }
+            c = c2;
+        }
+        if (b < 0) b = last_pos;   /* u beyond the rounded total: last token with mass */
+        *bonus = b;
+        break;
+    }
+    if (n_uniforms_used) *n_uniforms_used = ui;
+    if (margin_out) *margin_out = margin;
+    free(p); free(q); free(r);
+    return n;
+}
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,186 @@
+"""Pins for the oracle's tree-masked attention (CPU only).
+
+The oracle gathers "prefix + root-to-node path" and applies softmax attention.  It is pinned to a
+library routine (torch scaled_dot_product_attention, fp64, CPU) on the cases where tree attention
+must reduce to ordinary causal attention, to a hand-worked example, and to invariants that break
+if a mask bit, the scale, the GQA grouping or an index is wrong.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from paper_2605_29727_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+KINDS = ["chain", "star", "binary", "caterpillar", "random", "deep"]
+
+
+def _sdpa_causal_last_rows(q, k, v, n_last):
+    """Library causal attention of the last n_last tokens of one sequence.  q [n_last,D], k/v [S,D]."""
+    S = k.shape[0]
+    mask = torch.ones(n_last, S, dtype=torch.bool).tril(diagonal=S - n_last)
+    out = F.scaled_dot_product_attention(torch.from_numpy(q)[None, None].double(), torch.from_numpy(k)[None, None].double(),
+                                         torch.from_numpy(v)[None, None].double(), attn_mask=mask)
+    return out[0, 0].numpy()
+
+
+def _path(parent, i):
+    p = []
+    while i >= 0:
+        p.append(i); i = int(parent[i])
+    return p[::-1]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("Hq,Hkv,D,L", [(1, 1, 64, 128), (4, 2, 32, 17), (8, 2, 16, 0)])
+def test_each_node_equals_causal_attention_over_its_path(oracle, kind, Hq, Hkv, D, L):
+    """The stated meaning of the mask: verifying node i inside the tree gives what plain causal
+    attention gives for the sequence prefix + path(i), at its last position."""
+    N = 21
+    parent = synth.tree_parents(3, N, kind)
+    t = synth.qkv(11, N, L, Hq, Hkv, D, "fp32", tag=kind)
+    O = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, L)
+    G = Hq // Hkv
+    for i in range(N):
+        rows = list(range(L)) + [L + a for a in _path(parent, i)]
+        for h in range(Hq):
+            k = t["Kf"][rows, h // G]
+            v = t["Vf"][rows, h // G]
+            ref = _sdpa_causal_last_rows(t["Qf"][i:i + 1, h], k, v, 1)[0]
+            np.testing.assert_allclose(O[i, h], ref, rtol=0, atol=1e-12)
+
+
+def test_chain_tree_is_causal_attention(oracle):
+    """A chain-shaped tree (one path) must reduce to causal attention of N new tokens over L cached ones."""
+    N, L, Hq, Hkv, D = 24, 40, 4, 2, 32
+    t = synth.qkv(12, N, L, Hq, Hkv, D, "fp32")
+    O = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], synth.tree_parents(0, N, "chain"), L)
+    for h in range(Hq):
+        ref = _sdpa_causal_last_rows(t["Qf"][:, h], t["Kf"][:, h // 2], t["Vf"][:, h // 2], N)
+        np.testing.assert_allclose(O[:, h], ref, rtol=0, atol=1e-12)
+
+
+def test_star_tree_is_independent_single_token_decodes(oracle):
+    N, L, D = 9, 33, 16
+    t = synth.qkv(13, N, L, 2, 1, D, "fp32")
+    O = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], synth.tree_parents(0, N, "star"), L)
+    for i in range(N):
+        rows = list(range(L)) + [L + i]
+        for h in range(2):
+            ref = _sdpa_causal_last_rows(t["Qf"][i:i + 1, h], t["Kf"][rows, 0], t["Vf"][rows, 0], 1)[0]
+            np.testing.assert_allclose(O[i, h], ref, rtol=0, atol=1e-12)
+
+
+def test_hand_worked_example(oracle):
+    g = json.load(open(os.path.join(GOLD, "attn_hand_two_keys.json")))
+    D, L = g["D"], g["L"]
+    parent = np.array(g["parent"], dtype=np.int32)
+    M = len(parent)
+    K = np.zeros((L + M, 1, D), dtype=np.float32)
+    V = np.zeros((L + M, 1, D), dtype=np.float32)
+    K[:, 0, 0] = np.array(g["k_first"]) * g["k_scale"]
+    V[:, 0, :] = np.array(g["v_value"])[:, None]
+    Q = np.zeros((M, 1, D), dtype=np.float32)
+    Q[:, 0, 0] = 1.0
+    O = oracle.tree_attn(Q, K, V, parent, L)
+    np.testing.assert_allclose(O[:, 0, :], np.array(g["expected"])[:, None] * np.ones((1, D)), rtol=0, atol=1e-6)
+
+
+def test_scale_override_and_default(oracle):
+    t = synth.qkv(14, 3, 5, 1, 1, 16, "fp32")
+    parent = synth.tree_parents(0, 3, "chain")
+    a = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, 5)
+    b = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, 5, scale=0.25)     # 1/sqrt(16)
+    c = oracle.tree_attn(t["Qf"] * 2, t["Kf"], t["Vf"], parent, 5, scale=0.125)
+    assert np.array_equal(a, b)
+    np.testing.assert_allclose(a, c, atol=1e-12)
+
+
+def test_gqa_grouping_is_contiguous(oracle):
+    """Query head h reads KV head h // (Hq/Hkv): make V constant per KV head and read it back."""
+    N, L, Hq, Hkv, D = 5, 7, 8, 4, 8
+    t = synth.qkv(15, N, L, Hq, Hkv, D, "fp32")
+    V = np.zeros_like(t["Vf"])
+    for g in range(Hkv):
+        V[:, g, :] = 10.0 * (g + 1)
+    O = oracle.tree_attn(t["Qf"], t["Kf"], V, synth.tree_parents(1, N, "random"), L)
+    for h in range(Hq):
+        np.testing.assert_allclose(O[:, h, :], 10.0 * (h // 2 + 1), atol=1e-10)
+
+
+@pytest.mark.parametrize("kind", ["random", "binary", "deep"])
+def test_no_leak_from_non_ancestors(oracle, kind):
+    """Changing K/V of a tree row changes exactly the outputs of that row's descendants (and itself)."""
+    N, L, D = 30, 12, 16
+    parent = synth.tree_parents(5, N, kind)
+    t = synth.qkv(16, N, L, 2, 1, D, "fp32")
+    base = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, L)
+    for a in (0, 3, 11, N - 1):
+        K2, V2 = t["Kf"].copy(), t["Vf"].copy()
+        K2[L + a] += 1.5
+        V2[L + a] -= 2.5
+        out = oracle.tree_attn(t["Qf"], K2, V2, parent, L)
+        for i in range(N):
+            if a in _path(parent, i):
+                assert not np.array_equal(out[i], base[i])
+            else:
+                assert np.array_equal(out[i], base[i])
+
+
+def test_relabelling_nodes_permutes_rows(oracle):
+    N, L, D = 16, 9, 8
+    parent = synth.tree_parents(8, N, "random")
+    t = synth.qkv(17, N, L, 2, 2, D, "fp32")
+    base = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, L)
+    # a different topological order of the same tree: sort by (depth, old index) -> breadth-first
+    depth = np.array([len(_path(parent, i)) for i in range(N)])
+    new_of_old = np.empty(N, dtype=np.int64)
+    old_of_new = np.lexsort((np.arange(N), depth))
+    new_of_old[old_of_new] = np.arange(N)
+    p2 = np.array([-1 if parent[o] < 0 else new_of_old[parent[o]] for o in old_of_new], dtype=np.int32)
+    assert np.all(p2 < np.arange(N))
+    sel = np.concatenate([np.arange(L), L + old_of_new])
+    out = oracle.tree_attn(t["Qf"][old_of_new], t["Kf"][sel], t["Vf"][sel], p2, L)
+    np.testing.assert_allclose(out, base[old_of_new], atol=1e-13)
+
+
+def test_constant_values_and_edge_sizes(oracle):
+    t = synth.qkv(18, 6, 10, 2, 1, 8, "fp32")
+    V = np.full_like(t["Vf"], 3.25)
+    O = oracle.tree_attn(t["Qf"], t["Kf"], V, synth.tree_parents(2, 6, "random"), 10)
+    np.testing.assert_allclose(O, 3.25, atol=1e-12)             # softmax weights sum to one
+    # L = 0, N = 1: the node sees only itself
+    t = synth.qkv(19, 1, 0, 1, 1, 8, "fp32")
+    O = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], np.array([-1], dtype=np.int32), 0)
+    np.testing.assert_allclose(O[0, 0], t["Vf"][0, 0].astype(np.float64), atol=1e-15)
+    with pytest.raises(ValueError):
+        oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], np.array([0], dtype=np.int32), 0)    # parent[i] >= i
+
+
+def test_paged_addressing_equals_contiguous(oracle):
+    N, L, Hq, Hkv, D = 13, 75, 4, 2, 16
+    parent = synth.tree_parents(4, N, "random")
+    t = synth.qkv(20, N, L, Hq, Hkv, D, "fp32")
+    bt, nb = synth.paged_layout(9, [L + N, 40])
+    Kp = np.full((nb, synth.PAGE, Hkv, D), np.nan, dtype=np.float32)
+    Vp = np.full_like(Kp, np.nan)
+    synth.scatter_to_pages(t["Kf"], bt[0], Kp)
+    synth.scatter_to_pages(t["Vf"], bt[0], Vp)
+    a = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, L)
+    b = oracle.tree_attn(t["Qf"], Kp, Vp, parent, L, block_table=bt[0], page=synth.PAGE)
+    assert np.array_equal(a, b)
+    pairs = np.array([[0, 0], [12, 3], [5, 1]], dtype=np.int32)
+    c = oracle.tree_attn(t["Qf"], Kp, Vp, parent, L, block_table=bt[0], page=synth.PAGE, pairs=pairs)
+    assert np.array_equal(c, a[pairs[:, 0], pairs[:, 1]])
+
+
+def test_thread_count_does_not_change_results(oracle):
+    t = synth.qkv(21, 8, 64, 4, 2, 32, "bf16")
+    parent = synth.tree_parents(6, 8, "random")
+    a = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, 64, nthreads=1)
+    b = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, 64, nthreads=4)
+    assert np.array_equal(a, b)
