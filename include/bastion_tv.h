@@ -1,0 +1,145 @@
+/*
+ * bastion_tv.h -- C ABI of the MI355X (gfx950) tree-verify library for budget-aware tree
+ * speculative decoding: best-first tree build, tree-masked attention, acceptance walk.
+ *
+ * Conventions shared by every entry point
+ *   - Unless a parameter says HOST, every pointer is a DEVICE pointer owned by the caller.
+ *     The library allocates no caller-visible memory; scratch space is the caller's `ws`
+ *     (size from the matching *_workspace() query, 256-byte aligned).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; outputs are valid once the caller has synchronised the stream.
+ *   - Return value: BTV_OK, or a negative btv_status.  All argument checks run on the host
+ *     before anything is launched; btv_last_error() returns a thread-local message.
+ *     Nothing throws, nothing aborts.
+ *   - Tree encoding: M draft nodes in best-first (topological) order, parent[i] in
+ *     {-1} u [0, i); -1 marks a child of the root.  The root is the last validated token
+ *     and already lives in the KV prefix.  Data-dependent violations cannot be seen by the
+ *     host: kernels treat an out-of-range parent as -1 (so no access leaves its buffer) and
+ *     raise a flag in the workspace that btv_workspace_status() reports.
+ *   - dtype: BTV_F32 or BTV_BF16 (storage type of Q, K, V, O or of the logits).
+ *   - Limits: 1 <= M <= BTV_MAX_NODES, D in {64, 128}, Hq % Hkv == 0, Hq/Hkv <= 16, L >= 0,
+ *     1 <= B <= BTV_MAX_DEPTH, V >= 1.
+ */
+#ifndef BASTION_TV_H
+#define BASTION_TV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BTV_OK = 0,
+    BTV_EINVAL = -1,      /* null pointer, bad shape, unsupported dtype or limit exceeded */
+    BTV_EWORKSPACE = -2,  /* workspace missing, misaligned or too small */
+    BTV_EHIP = -3,        /* a HIP runtime call or kernel launch failed */
+    BTV_EDATA = -4        /* btv_workspace_status(): a kernel saw invalid data (e.g. parent[i] >= i) */
+} btv_status;
+
+enum { BTV_F32 = 0, BTV_BF16 = 1 };
+enum { BTV_MAX_NODES = 256, BTV_MAX_DEPTH = 16, BTV_PAGE = 16, BTV_ANC_WORDS = 8 };
+
+const char *btv_last_error(void);
+int btv_version(void);
+
+/* Synchronises `stream`, reads the data-error flag that kernels of the last call using `ws`
+ * may have raised, clears it, and returns BTV_OK or BTV_EDATA.  Optional. */
+int btv_workspace_status(void *ws, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * tree_build -- best-first expansion at a fixed budget (Sec. 3.3, Prop. 3.3; Algorithm 1's
+ * frontier rule without the early stop; path score of Eq. 1; surrogate of Eq. 3).
+ *
+ * marginals [B,V] fp32 row-major: position-wise draft probabilities q_1..q_B (non-negative,
+ * finite).  Emits the N prefixes of the candidate lattice with the largest path score
+ * rho = prod_k q_k(x_k), in non-increasing order of rho; rho of a child is one fp32 multiply
+ * rho(parent) * q.  Ties: shallower first, then smaller rank path, where a token's rank at a
+ * position is its index in that position's list sorted by (probability desc, token id asc).
+ *
+ * Outputs (all [N] unless noted; entries past *n_out are left untouched):
+ *   parent  -1 = child of the root, else index of the parent node (< own index)
+ *   token   vocabulary id;  depth (optional, may be NULL) 1-based;  rho (optional) fp32 score
+ *   n_out   [1] = min(N, number of prefixes in the lattice)
+ *   ahat    [1] optional: 1 + sum of rho (the root counts 1), fp32
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_build_workspace(int B, int V, int N);
+int btv_tree_build(const float *marginals, int B, int V, int N,
+                   int32_t *parent, int32_t *token, int32_t *depth, float *rho,
+                   int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ancestor mask -- the verification mask of App. C ("Linearization and verification mask")
+ * as a bitset: bit a of anc[i] is set iff a is i or an ancestor of i.
+ * anc [M, BTV_ANC_WORDS] uint32, word w holds nodes 32w..32w+31.
+ * ------------------------------------------------------------------------------------------- */
+int btv_tree_ancestor_mask(const int32_t *parent, int M, uint32_t *anc, void *ws, size_t ws_bytes,
+                           void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * tree_verify_attn -- tree-masked attention of one layer (App. C): node i attends to the L
+ * prefix rows of the KV cache and to the tree rows of its ancestors and itself.
+ *   O[i,h,:] = sum_j softmax_j(scale * Q[i,h,:].K[j,g,:]) V[j,g,:],  g = h / (Hq/Hkv),
+ *   j over 0..L-1 and L+a for a in anc(i).
+ * Q, O [M,Hq,D]; K, V [L+M,Hkv,D] (tree node a at row L+a); all row-major, contiguous, of
+ * `dtype`; softmax and accumulation in fp32.  scale <= 0 selects 1/sqrt(D).
+ * Workspace: ancestor bitmasks and split-K partial results.
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_verify_attn_workspace(int M, int L, int Hq, int Hkv, int D, int dtype);
+int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int32_t *parent,
+                         int M, int L, int Hq, int Hkv, int D, int dtype, float scale,
+                         void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* Ragged batch over a paged KV cache (BTV_PAGE-token blocks), bf16 only.
+ *   Q, O        [total_M, Hq, D]; request r owns rows q_offset[r] .. q_offset[r+1]-1
+ *   Kpool,Vpool [num_blocks, BTV_PAGE, Hkv, D]
+ *   block_table [batch, max_blocks] int32: logical block b of request r is pool block
+ *               block_table[r*max_blocks + b]; sequence position j lives in block j/BTV_PAGE at
+ *               slot j%BTV_PAGE; tree node a of request r sits at position prefix_len[r] + a
+ *   q_offset    [batch+1] int32, prefix_len [batch] int32 (device)
+ *   parent      [total_M] int32, indices local to each request
+ *   M_max, L_max  HOST upper bounds on any request's node count / prefix length (they size the
+ *               grid and the workspace); a request exceeding them, or whose L+M exceeds
+ *               max_blocks*BTV_PAGE, is skipped and flagged (see btv_workspace_status).
+ * Block ids outside [0, num_blocks) are clamped, so no access leaves the pools. */
+size_t btv_tree_verify_attn_paged_workspace(int batch, int M_max, int L_max, int Hq, int Hkv, int D);
+int btv_tree_verify_attn_paged(const void *Q, const void *Kpool, const void *Vpool, int num_blocks,
+                               const int32_t *block_table, int max_blocks, const int32_t *q_offset,
+                               const int32_t *prefix_len, const int32_t *parent, int batch,
+                               int total_M, int M_max, int L_max, int Hq, int Hkv, int D,
+                               float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * tree_accept -- the walk that commits the longest accepted root-to-node path (App. C,
+ * "Acceptance"; Sec. 3.1).  logits [M+1,V] of `dtype`: row 0 is the root, row 1+i node i.
+ *
+ * greedy (temperature 0): t[r] = argmax_v logits[r,v] (lowest v on ties); from the root follow
+ * the child whose token equals t[row of the current node] until none does.
+ *   path [M] accepted node ids in root-to-leaf order (first *n_acc valid), n_acc [1],
+ *   bonus [1] = t[row of the last accepted node] (the token that seeds the next cycle),
+ *   argmax_out [M+1] optional.
+ *
+ * stochastic (temperature 1): token-level rejection sampling of the target distribution
+ * p = softmax(logits row) against the draft marginal q of the child's depth, children tried in
+ * node order, one uniform each: accept iff u*q[x] < p[x]; on rejection p <- norm(max(p-q,0))
+ * (unchanged if that is all zero) and q[x] <- 0, q renormalised; when no child is accepted the
+ * bonus token is the inverse-CDF sample of p with the next uniform.  uniforms [M+1] fp32 in
+ * [0,1), consumed in order.  marginals [B,V] fp32 as given to tree_build.
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_accept_workspace(int M, int V, int stochastic);
+int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token,
+                           int M, int V, int32_t *path, int32_t *n_acc, int32_t *bonus,
+                           int32_t *argmax_out, void *ws, size_t ws_bytes, void *stream);
+int btv_tree_accept_stochastic(const void *logits, int dtype, const float *marginals, int B,
+                               const int32_t *parent, const int32_t *token, int M, int V,
+                               const float *uniforms, int32_t *path, int32_t *n_acc, int32_t *bonus,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/* Tuning knob for experiments: number of key splits used by tree_verify_attn (0 = heuristic). */
+void btv_set_attn_splits(int nsplit);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BASTION_TV_H */

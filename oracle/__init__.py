@@ -36,6 +36,7 @@ def _load():
         _lib.orc_accept_greedy.restype = C.c_int
         _lib.orc_accept_stochastic.restype = C.c_int
         _lib.orc_num_threads.restype = C.c_int
+        _lib.orc_ancestor_mask.restype = C.c_int
     return _lib
 
 
@@ -115,6 +116,16 @@ def tree_attn(Qf, Kf, Vf, parent, L: int, scale: float | None = None, pairs=None
     return out
 
 
+def ancestor_mask(parent, words: int = 8) -> np.ndarray:
+    """anc[i] bitset of node i and its ancestors (App. C verification mask), uint32 [M, words]."""
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    anc = np.empty((len(parent), words), dtype=np.uint32)
+    rc = _load().orc_ancestor_mask(_p(parent, C.c_int32), len(parent), words, _p(anc, C.c_uint32))
+    if rc != 0:
+        raise ValueError(f"orc_ancestor_mask: bad arguments ({rc})")
+    return anc
+
+
 def row_argmax(logits_f32: np.ndarray) -> np.ndarray:
     x = np.ascontiguousarray(logits_f32, dtype=np.float32)
     t = np.empty(x.shape[0], dtype=np.int32)
@@ -148,9 +159,10 @@ def accept_stochastic(logits_f32, marg, parent, token, depth, uniforms) -> dict:
     M = len(parent)
     assert x.shape[0] == M + 1 and len(u) >= M + 1 and marg.shape[1] == x.shape[1]
     path = np.empty(max(M, 1), dtype=np.int32)
-    bonus, used, margin = C.c_int32(0), C.c_int32(0), C.c_double(0.0)
+    bonus, used, margin, gap = C.c_int32(0), C.c_int32(0), C.c_double(0.0), C.c_double(0.0)
     n = _load().orc_accept_stochastic(_p(x, C.c_float), _p(marg, C.c_float), marg.shape[0], _p(parent, C.c_int32),
                                       _p(token, C.c_int32), _p(depth, C.c_int32), M, x.shape[1], _p(u, C.c_float),
-                                      _p(path, C.c_int32), C.byref(bonus), C.byref(used), C.byref(margin))
+                                      _p(path, C.c_int32), C.byref(bonus), C.byref(used), C.byref(margin),
+                                      C.byref(gap))
     return {"n_acc": n, "path": path[:n].copy(), "bonus": int(bonus.value), "n_uniforms": int(used.value),
-            "margin": float(margin.value)}
+            "margin": float(margin.value), "bonus_gap": float(gap.value)}

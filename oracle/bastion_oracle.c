@@ -14,6 +14,7 @@
  *   orc_tree_build       brute-force enumeration of all prefixes (Prop. 3.3), closed forms,
  *                        Monte-Carlo self-verification (Prop. 3.2)
  *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
+ *   orc_ancestor_mask    reachability by explicit path enumeration
  *   orc_accept_greedy    brute force over all root-to-node paths, planted paths
  *   orc_accept_stochastic  closed-form special cases and an empirical chi-square test of the
  *                        single-child case; the multi-child rule is not given by the paper:
@@ -250,18 +251,20 @@ int orc_accept_greedy(const float *logits, const int32_t *parent, const int32_t 
  *         no child accepted (or d == B): bonus = smallest v with cumsum(p)[v] > u (next uniform), stop.
  *
  * Uniforms are consumed strictly in order.  margin_out receives the smallest relative distance
- * of any decision from its threshold, so a caller can discard inputs whose outcome depends on
+ * of any accept/reject decision from its threshold and gap_out the absolute distance of the
+ * bonus draw from the nearer CDF step, so a caller can discard inputs whose outcome depends on
  * the last bits of a vocabulary-wide sum.
  * ---------------------------------------------------------------------------------------- */
 int orc_accept_stochastic(const float *logits, const float *marg, int B, const int32_t *parent,
                           const int32_t *token, const int32_t *depth, int M, int V, const float *uniforms,
-                          int32_t *path, int32_t *bonus, int32_t *n_uniforms_used, double *margin_out)
+                          int32_t *path, int32_t *bonus, int32_t *n_uniforms_used, double *margin_out,
+                          double *gap_out)
 {
     double *p = (double *)malloc(sizeof(double) * (size_t)V);
     double *q = (double *)malloc(sizeof(double) * (size_t)V);
     double *r = (double *)malloc(sizeof(double) * (size_t)V);
     int cur = -1, n = 0, ui = 0, d = 0;
-    double margin = INFINITY;
+    double margin = INFINITY, bgap = INFINITY;
     (void)depth;   /* the depth of cur is tracked by the walk itself */
     for (;;) {
         /* target distribution at the current node: softmax of its logits row */
@@ -302,7 +305,7 @@ int orc_accept_stochastic(const float *logits, const float *marg, int B, const i
             if (b < 0 && c2 > u) {
                 b = v;
                 double gap = fmin(c2 - u, u - c);
-                if (gap < margin) margin = gap;
+                bgap = gap;
             }
             c = c2;
         }
@@ -312,8 +315,26 @@ int orc_accept_stochastic(const float *logits, const float *marg, int B, const i
     }
     if (n_uniforms_used) *n_uniforms_used = ui;
     if (margin_out) *margin_out = margin;
+    if (gap_out) *gap_out = bgap;
     free(p); free(q); free(r);
     return n;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Verification mask as a bitset (App. C, "Linearization and verification mask"): bit a of
+ * anc[i] is set iff tree node a is i itself or an ancestor of i.  words = 32-bit words per row.
+ * ---------------------------------------------------------------------------------------- */
+int orc_ancestor_mask(const int32_t *parent, int M, int words, uint32_t *anc)
+{
+    for (int i = 0; i < M; ++i) {
+        if (parent[i] < -1 || parent[i] >= i) return -2;
+        for (int w = 0; w < words; ++w) anc[(size_t)i * words + w] = 0u;
+        for (int a = i; a >= 0; a = parent[a]) {
+            if (a / 32 >= words) return -1;
+            anc[(size_t)i * words + a / 32] |= 1u << (a % 32);
+        }
+    }
+    return 0;
 }
 
 int orc_num_threads(void)

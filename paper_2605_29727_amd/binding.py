@@ -1,0 +1,166 @@
+"""Thin ctypes binding over libbastion_tv.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/bastion_tv.h); tensors are
+torch CUDA(ROCm) tensors used purely as device buffers, and the current torch stream is handed
+to the library.  There is no fallback: if the shared library is missing or a call fails, a
+BtvError is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbastion_tv.so")
+
+BTV_F32, BTV_BF16 = 0, 1
+BTV_MAX_NODES, BTV_MAX_DEPTH, BTV_PAGE, BTV_ANC_WORDS = 256, 16, 16, 8
+BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "btv_last_error", "btv_version", "btv_workspace_status", "btv_tree_build_workspace", "btv_tree_build",
+    "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
+    "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
+    "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_set_attn_splits",
+]
+
+
+class BtvError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libbastion_tv error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise BtvError(BTV_EHIP, f"{LIB_PATH} is not built; run __graft_entry__.build() "
+                                     "(python -m paper_2605_29727_amd.build)")
+        L = C.CDLL(LIB_PATH)
+        L.btv_last_error.restype = C.c_char_p
+        for n in ("btv_tree_build_workspace", "btv_tree_verify_attn_workspace",
+                  "btv_tree_verify_attn_paged_workspace", "btv_tree_accept_workspace"):
+            getattr(L, n).restype = C.c_size_t
+        for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_ancestor_mask",
+                  "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_accept_greedy",
+                  "btv_tree_accept_stochastic"):
+            getattr(L, n).restype = C.c_int
+        L.btv_set_attn_splits.restype = None
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != BTV_OK:
+        raise BtvError(rc, lib().btv_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t) -> int:
+    if t.dtype == torch.float32:
+        return BTV_F32
+    if t.dtype == torch.bfloat16:
+        return BTV_BF16
+    raise BtvError(BTV_EINVAL, f"unsupported dtype {t.dtype}")
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """A zero-initialised device buffer of at least nbytes (torch allocations are 256-byte aligned)."""
+    return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def btv_version() -> int:
+    return lib().btv_version()
+
+
+def btv_set_attn_splits(nsplit: int) -> None:
+    lib().btv_set_attn_splits(C.c_int(int(nsplit)))
+
+
+def btv_workspace_status(ws) -> int:
+    return lib().btv_workspace_status(_ptr(ws), _stream())
+
+
+# ---------------------------------------------------------------------------------------------
+
+def btv_tree_build_workspace(B: int, V: int, N: int) -> int:
+    return int(lib().btv_tree_build_workspace(B, V, N))
+
+
+def btv_tree_build(marginals, N: int, parent, token, depth, rho, n_out, ahat, ws) -> None:
+    B, V = marginals.shape
+    assert marginals.dtype == torch.float32
+    _check(lib().btv_tree_build(_ptr(marginals), B, V, N, _ptr(parent), _ptr(token), _ptr(depth), _ptr(rho),
+                                _ptr(n_out), _ptr(ahat), _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0),
+                                _stream()))
+
+
+def btv_tree_ancestor_mask(parent, anc, ws) -> None:
+    _check(lib().btv_tree_ancestor_mask(_ptr(parent), parent.numel(), _ptr(anc), _ptr(ws),
+                                        C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_verify_attn_workspace(M, L, Hq, Hkv, D, dtype_code) -> int:
+    return int(lib().btv_tree_verify_attn_workspace(M, L, Hq, Hkv, D, dtype_code))
+
+
+def btv_tree_verify_attn(Q, K, V, parent, L: int, O, ws, scale: float = 0.0) -> None:
+    M, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    assert K.shape[0] >= L + M and V.shape == K.shape and O.shape == Q.shape
+    _check(lib().btv_tree_verify_attn(_ptr(Q), _ptr(K), _ptr(V), _ptr(parent), M, L, Hq, Hkv, D, _dtype_code(Q),
+                                      C.c_float(scale), _ptr(O), _ptr(ws),
+                                      C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_verify_attn_paged_workspace(batch, M_max, L_max, Hq, Hkv, D) -> int:
+    return int(lib().btv_tree_verify_attn_paged_workspace(batch, M_max, L_max, Hq, Hkv, D))
+
+
+def btv_tree_verify_attn_paged(Q, Kpool, Vpool, block_table, q_offset, prefix_len, parent, M_max: int, L_max: int,
+                               O, ws, scale: float = 0.0) -> None:
+    total_M, Hq, D = Q.shape
+    num_blocks, page, Hkv, _ = Kpool.shape
+    assert page == BTV_PAGE and Q.dtype == torch.bfloat16
+    batch, max_blocks = block_table.shape
+    _check(lib().btv_tree_verify_attn_paged(_ptr(Q), _ptr(Kpool), _ptr(Vpool), num_blocks, _ptr(block_table),
+                                            max_blocks, _ptr(q_offset), _ptr(prefix_len), _ptr(parent), batch,
+                                            total_M, M_max, L_max, Hq, Hkv, D, C.c_float(scale), _ptr(O), _ptr(ws),
+                                            C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_accept_workspace(M: int, V: int, stochastic: bool) -> int:
+    return int(lib().btv_tree_accept_workspace(M, V, 1 if stochastic else 0))
+
+
+def btv_tree_accept_greedy(logits, parent, token, path, n_acc, bonus, argmax_out, ws) -> None:
+    rows, V = logits.shape
+    _check(lib().btv_tree_accept_greedy(_ptr(logits), _dtype_code(logits), _ptr(parent), _ptr(token), rows - 1, V,
+                                        _ptr(path), _ptr(n_acc), _ptr(bonus), _ptr(argmax_out), _ptr(ws),
+                                        C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_accept_stochastic(logits, marginals, parent, token, uniforms, path, n_acc, bonus, ws) -> None:
+    rows, V = logits.shape
+    B = marginals.shape[0]
+    assert marginals.shape[1] == V and uniforms.numel() >= rows
+    _check(lib().btv_tree_accept_stochastic(_ptr(logits), _dtype_code(logits), _ptr(marginals), B, _ptr(parent),
+                                            _ptr(token), rows - 1, V, _ptr(uniforms), _ptr(path), _ptr(n_acc),
+                                            _ptr(bonus), _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0),
+                                            _stream()))

@@ -1,0 +1,83 @@
+"""Helpers for the -m gpu tests: numpy <-> device marshalling and one-call wrappers over the binding."""
+import numpy as np
+import torch
+
+from paper_2605_29727_amd import binding as btv
+
+
+def dev(a: np.ndarray, bf16_bits: bool = False) -> torch.Tensor:
+    if bf16_bits:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+
+def run_verify_attn(t: dict, parent: np.ndarray, L: int, dtype: str, scale: float = 0.0, nsplit: int = 0,
+                    check_status: bool = True):
+    """t: dict from synth.qkv.  Returns O as float64 numpy [M,Hq,D]."""
+    bits = dtype == "bf16"
+    Q, K, V = dev(t["Q"], bits), dev(t["K"], bits), dev(t["V"], bits)
+    par = dev(np.asarray(parent, dtype=np.int32))
+    M, Hq, D = Q.shape
+    btv.btv_set_attn_splits(nsplit)
+    try:
+        ws = btv.alloc_workspace(btv.btv_tree_verify_attn_workspace(M, L, Hq, K.shape[1], D, btv._dtype_code(Q)))
+        O = torch.full_like(Q, float("nan"))
+        btv.btv_tree_verify_attn(Q, K, V, par, L, O, ws, scale)
+        torch.cuda.synchronize()
+        if check_status:
+            assert btv.btv_workspace_status(ws) == 0
+    finally:
+        btv.btv_set_attn_splits(0)
+    return host(O).astype(np.float64)
+
+
+def run_tree_build(marg: np.ndarray, N: int) -> dict:
+    m = dev(marg.astype(np.float32))
+    B, V = marg.shape
+    parent = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    token = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    depth = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    rho = torch.full((N,), -7.0, dtype=torch.float32, device="cuda")
+    n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ahat = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_build_workspace(B, V, N))
+    btv.btv_tree_build(m, N, parent, token, depth, rho, n_out, ahat, ws)
+    torch.cuda.synchronize()
+    n = int(n_out.item())
+    return {"n": n, "parent": parent.cpu().numpy()[:n], "token": token.cpu().numpy()[:n],
+            "depth": depth.cpu().numpy()[:n], "rho": rho.cpu().numpy()[:n], "ahat": float(ahat.item()),
+            "raw_parent": parent.cpu().numpy()}
+
+
+def run_accept_greedy(logits_store: np.ndarray, bf16_bits: bool, parent, token) -> dict:
+    x = dev(logits_store, bf16_bits)
+    M = len(parent)
+    par, tok = dev(np.asarray(parent, dtype=np.int32)), dev(np.asarray(token, dtype=np.int32))
+    path = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    am = torch.full((M + 1,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(M, x.shape[1], False))
+    btv.btv_tree_accept_greedy(x, par, tok, path, n_acc, bonus, am, ws)
+    torch.cuda.synchronize()
+    n = int(n_acc.item())
+    return {"n_acc": n, "path": path.cpu().numpy()[:n], "bonus": int(bonus.item()), "argmax": am.cpu().numpy()}
+
+
+def run_accept_stochastic(logits_store: np.ndarray, bf16_bits: bool, marg, parent, token, uniforms) -> dict:
+    x = dev(logits_store, bf16_bits)
+    M = len(parent)
+    par, tok = dev(np.asarray(parent, dtype=np.int32)), dev(np.asarray(token, dtype=np.int32))
+    m, u = dev(marg.astype(np.float32)), dev(np.asarray(uniforms, dtype=np.float32))
+    path = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(M, x.shape[1], True))
+    btv.btv_tree_accept_stochastic(x, m, par, tok, u, path, n_acc, bonus, ws)
+    torch.cuda.synchronize()
+    n = int(n_acc.item())
+    return {"n_acc": n, "path": path.cpu().numpy()[:n], "bonus": int(bonus.item())}

@@ -1,0 +1,90 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and rejects
+bad arguments on the host before anything is launched (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2605_29727_amd", "libbastion_tv.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2605_29727_amd import build
+        build.build()
+    L = C.CDLL(LIB)
+    L.btv_last_error.restype = C.c_char_p
+    for n in ("btv_tree_build_workspace", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn_paged_workspace",
+              "btv_tree_accept_workspace"):
+        getattr(L, n).restype = C.c_size_t
+    return L
+
+
+def _declared():
+    names = set()
+    for f in os.listdir(os.path.join(ROOT, "include")):
+        if f.endswith(".h"):
+            names |= set(re.findall(r"\b(btv_[a-z_0-9]+)\s*\(", open(os.path.join(ROOT, "include", f)).read()))
+    return sorted(names)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_binding_names_match_header():
+    from paper_2605_29727_amd import binding
+    assert sorted(binding.EXPORTS) == _declared()
+    for n in binding.EXPORTS:
+        if n != "btv_last_error":
+            assert hasattr(binding, n), n
+
+
+def test_version_and_workspace_queries(lib):
+    assert lib.btv_version() >= 1
+    assert lib.btv_tree_verify_attn_workspace(64, 8192, 32, 8, 128, 1) > 64 * 8 * 4
+    assert lib.btv_tree_verify_attn_workspace(16, 128, 1, 1, 64, 0) >= 256
+    assert lib.btv_tree_verify_attn_workspace(0, 128, 1, 1, 64, 0) == 0          # invalid shape -> 0
+    assert lib.btv_tree_verify_attn_workspace(16, 128, 3, 2, 64, 0) == 0
+    assert lib.btv_tree_build_workspace(16, 128256, 64) > 0
+    assert lib.btv_tree_build_workspace(17, 128256, 64) == 0
+    assert lib.btv_tree_accept_workspace(64, 128256, 0) > 0
+    assert lib.btv_tree_accept_workspace(64, 128256, 1) >= 2 * 128256 * 4
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    fake = C.c_void_p(4096)   # never dereferenced: every call below fails validation first
+    f0 = C.c_float(0.0)
+    rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 1000, 10, 8, 8, 128, 1, f0, fake, None, C.c_size_t(0), None)
+    assert rc == -1 and b"M=1000" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn(None, fake, fake, fake, 16, 10, 8, 8, 128, 1, f0, fake, None, C.c_size_t(0), None)
+    assert rc == -1
+    rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 16, 10, 8, 8, 96, 1, f0, fake, None, C.c_size_t(0), None)
+    assert rc == -1 and b"D=96" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 16, 10, 8, 8, 128, 7, f0, fake, None, C.c_size_t(0), None)
+    assert rc == -1
+    rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 16, 10, 8, 8, 128, 1, f0, fake, None, C.c_size_t(0), None)
+    assert rc == -2 and b"workspace" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 16, 10, 8, 8, 128, 1, f0, fake, C.c_void_p(4096 + 8),
+                                  C.c_size_t(1 << 20), None)
+    assert rc == -2 and b"aligned" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 16, 10, 8, 8, 128, 1, f0, fake, fake, C.c_size_t(16), None)
+    assert rc == -2 and b"too small" in lib.btv_last_error()
+    rc = lib.btv_tree_build(fake, 16, 128256, 1000, fake, fake, None, None, fake, None, fake, C.c_size_t(1 << 30), None)
+    assert rc == -1
+    rc = lib.btv_tree_build(fake, 99, 128256, 64, fake, fake, None, None, fake, None, fake, C.c_size_t(1 << 30), None)
+    assert rc == -1
+    rc = lib.btv_tree_accept_greedy(fake, 1, fake, fake, 0, 100, fake, fake, fake, None, fake, C.c_size_t(1 << 20), None)
+    assert rc == -1
+    rc = lib.btv_tree_accept_stochastic(fake, 0, None, 16, fake, fake, 8, 100, fake, fake, fake, fake, fake,
+                                        C.c_size_t(1 << 20), None)
+    assert rc == -1
+    rc = lib.btv_tree_verify_attn_paged(fake, fake, fake, 10, fake, 4, fake, fake, fake, 2, 10, 8, 1 << 20, 8, 8, 128,
+                                        f0, fake, fake, C.c_size_t(1 << 30), None)
+    assert rc == -1 and b"max_blocks" in lib.btv_last_error()

@@ -1,0 +1,143 @@
+"""Parity of the HIP acceptance walks with the CPU oracle: argmax, path, n_acc and bonus are bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2605_29727_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _depths(parent):
+    d = np.zeros(len(parent), dtype=np.int32)
+    for i in range(len(parent)):
+        d[i] = 1 if parent[i] < 0 else d[parent[i]] + 1
+    return d
+
+
+def _greedy_case(G, oracle, store, f32, bits, parent, token):
+    ref = oracle.accept_greedy(f32, parent, token)
+    got = G.run_accept_greedy(store, bits, parent, token)
+    assert np.array_equal(got["argmax"], ref["argmax"])
+    assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]) and got["bonus"] == ref["bonus"]
+    return ref
+
+
+def test_greedy_config1(G, oracle):
+    w = synth.C1
+    tree = oracle.tree_build(synth.marginals(w.seed, w.B, w.V, w.marg_sigma), w.N)
+    store, f = synth.target_logits(w.seed, w.N + 1, w.V, w.logit_sigma, "fp32")
+    _greedy_case(G, oracle, store, f, False, tree["parent"], tree["token"])
+    for leaf in range(w.N):
+        x = synth.plant_path(f, tree["parent"], tree["token"], leaf)
+        r = _greedy_case(G, oracle, x, x, False, tree["parent"], tree["token"])
+        assert r["n_acc"] >= tree["depth"][leaf]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_greedy_config2_full_vocab_with_planted_paths(G, oracle, dtype):
+    w = synth.C2
+    tree = oracle.tree_build(synth.marginals(w.seed, w.B, w.V, w.marg_sigma), w.N)
+    _, f = synth.target_logits(w.seed, w.N + 1, w.V, w.logit_sigma, "fp32")
+    deep = int(np.argmax(tree["depth"]))
+    for leaf in (-1, deep, 0, w.N // 2):
+        x = synth.plant_path(f, tree["parent"], tree["token"], leaf)
+        store, xf = synth.round_to_dtype(x.astype(np.float64), dtype)
+        r = _greedy_case(G, oracle, store, xf, dtype == "bf16", tree["parent"], tree["token"])
+        if leaf >= 0:
+            assert r["n_acc"] >= tree["depth"][leaf]
+    # bf16 logits tie often at 128k draws: the argmax must still be the lowest index
+    store, xf = synth.round_to_dtype(np.round(f.astype(np.float64) * 4) / 4, dtype)
+    _greedy_case(G, oracle, store, xf, dtype == "bf16", tree["parent"], tree["token"])
+
+
+@pytest.mark.parametrize("kind", ["chain", "star", "binary", "random", "deep"])
+@pytest.mark.parametrize("M,V", [(1, 1), (7, 13), (256, 1000), (100, 8193), (33, 128256)])
+def test_greedy_tree_kinds_and_odd_vocabularies(G, oracle, kind, M, V):
+    parent = synth.tree_parents(5, M, kind)
+    fan = max(np.bincount(parent + 1).max(), 1)
+    if fan > V:
+        pytest.skip("fan-out exceeds the vocabulary")
+    token = synth.sibling_distinct_tokens(5, parent, V)
+    for dtype in ("bf16", "fp32"):
+        _, f = synth.target_logits(6, M + 1, V, 1.0, "fp32", tag=f"{kind}{M}{V}")
+        leaf = int(np.argmax(_depths(parent)))
+        x = synth.plant_path(f, parent, token, leaf)
+        store, xf = synth.round_to_dtype(x.astype(np.float64), dtype)
+        _greedy_case(G, oracle, store, xf, dtype == "bf16", parent, token)
+
+
+def test_greedy_all_equal_and_neg_inf_rows(G, oracle):
+    M, V = 5, 300
+    parent = synth.tree_parents(0, M, "chain")
+    token = np.zeros(M, dtype=np.int32)
+    x = np.zeros((M + 1, V), dtype=np.float32)
+    r = _greedy_case(G, oracle, x, x, False, parent, token)     # every row ties everywhere: argmax 0 -> full chain
+    assert r["n_acc"] == M and r["bonus"] == 0
+    x[:] = -np.inf
+    _greedy_case(G, oracle, x, x, False, parent, token)
+
+
+AMBIGUOUS, AMBIGUOUS_GAP = 1e-4, 1e-6
+
+
+def _ambiguous(ref):
+    return ref["margin"] < AMBIGUOUS or ref["bonus_gap"] < AMBIGUOUS_GAP
+
+
+@pytest.mark.parametrize("logit_dtype", ["fp32", "bf16"])
+def test_stochastic_parity(G, oracle, logit_dtype):
+    """Seeds whose accept tests sit within AMBIGUOUS (relative) of the threshold, or whose bonus draw sits within
+    AMBIGUOUS_GAP (absolute) of a CDF step, are skipped: there the outcome
+    depends on the rounding of vocabulary-wide sums and either result is correct."""
+    B, V, N = 8, 5000, 48
+    checked = 0
+    for seed in range(12):
+        marg = synth.marginals(100 + seed, B, V, 2.0)
+        tree = oracle.tree_build(marg, N)
+        # target close to the draft so that acceptances and rejections both happen
+        z = np.log(np.maximum(marg[np.minimum(np.concatenate([[0], tree["depth"]]), B - 1)].astype(np.float64), 1e-30))
+        z += synth.normal(200 + seed, "noise", z.shape, 1.0)
+        store, xf = synth.round_to_dtype(z, logit_dtype)
+        u = synth.uniform(300 + seed, "u", (N + 1,)).astype(np.float32)
+        ref = oracle.accept_stochastic(xf, marg, tree["parent"], tree["token"], tree["depth"], u)
+        if _ambiguous(ref):
+            continue
+        got = G.run_accept_stochastic(store, logit_dtype == "bf16", marg, tree["parent"], tree["token"], u)
+        assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]), seed
+        assert got["bonus"] == ref["bonus"], seed
+        checked += 1
+    assert checked >= 8
+
+
+def test_stochastic_extremes(G, oracle):
+    B, V, N = 4, 640, 20
+    marg = synth.marginals(7, B, V, 2.0)
+    tree = oracle.tree_build(marg, N)
+    store, xf = synth.target_logits(8, N + 1, V, 1.0, "fp32")
+    for u in (np.zeros(N + 1, dtype=np.float32), np.full(N + 1, 0.999999, dtype=np.float32)):
+        ref = oracle.accept_stochastic(xf, marg, tree["parent"], tree["token"], tree["depth"], u)
+        got = G.run_accept_stochastic(store, False, marg, tree["parent"], tree["token"], u)
+        assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]) and got["bonus"] == ref["bonus"]
+
+
+def test_config5_stochastic_full_vocab(G, oracle):
+    w = synth.C5
+    marg = synth.marginals(w.seed, w.B, w.V, w.marg_sigma)
+    tree = oracle.tree_build(marg, w.N)
+    store, xf = synth.target_logits(w.seed, w.N + 1, w.V, w.logit_sigma, w.logit_dtype)
+    done = 0
+    for k in range(6):
+        u = synth.uniform(w.seed, f"uniforms{k}", (w.N + 1,)).astype(np.float32)
+        ref = oracle.accept_stochastic(xf, marg, tree["parent"], tree["token"], tree["depth"], u)
+        if _ambiguous(ref):
+            continue
+        got = G.run_accept_stochastic(store, False, marg, tree["parent"], tree["token"], u)
+        assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]) and got["bonus"] == ref["bonus"]
+        done += 1
+    assert done >= 3

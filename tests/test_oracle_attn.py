@@ -184,3 +184,13 @@ def test_thread_count_does_not_change_results(oracle):
     a = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, 64, nthreads=1)
     b = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, 64, nthreads=4)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_ancestor_mask_is_reachability(oracle, kind):
+    N = 70
+    parent = synth.tree_parents(9, N, kind)
+    anc = oracle.ancestor_mask(parent, words=8)
+    for i in range(N):
+        bits = {a for a in range(256) if (anc[i, a // 32] >> np.uint32(a % 32)) & np.uint32(1)}
+        assert bits == set(_path(parent, i))
