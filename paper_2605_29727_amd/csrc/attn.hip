@@ -6,14 +6,13 @@
 //
 // bf16 kernel layout.  For one KV head the G = Hq/Hkv query heads of every node are packed
 // into rows r = i*G + j, so the whole GQA group shares each K/V byte that is streamed.
-// A workgroup (4 wavefronts of 64 lanes) owns WR rows and a range of 64-key stages; K and V
-// stages are staged through LDS once per workgroup (double buffered, register prefetch).
+// A workgroup (4 wavefronts of 64 lanes) owns WR rows and a range of 32-key tiles; K and V
+// tiles are staged through LDS once per workgroup (ring of stages filled by direct-to-LDS loads).
 // Scores are computed transposed, S^T = K . Q^T with 32x32x16 bf16 MFMA: in the accumulator
 // layout a lane then holds ONE query column and 16 keys, so the running max / sum of the
 // online softmax are per-lane scalars (one cross-half exchange per tile), the P^T tile is
 // already in B-operand layout for O^T += V^T . P^T, and the O^T accumulator is rescaled by a
-// per-lane factor.  V is transposed on its way into LDS (pairs of keys per dword, XOR
-// swizzled) so V^T tiles are plain 16-byte LDS reads.  The tree mask is applied only on tiles
+// per-lane factor.  V^T operands come from transposing LDS reads.  The tree mask is applied only on tiles
 // that touch tree rows, from a 32-bit visibility word per (query, tile) built from the node's
 // ancestor bitmask.
 #include "btv_common.h"
@@ -24,10 +23,11 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TK = 64;          // keys per LDS stage
+constexpr int TK = 32;          // keys per tile = per LDS stage
 constexpr float NEG_BIG = -1.0e30f;
 
 struct AttnParams {
@@ -139,121 +139,97 @@ __global__ __launch_bounds__(256) void anc_mask_kernel(const int32_t *parent, co
 
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
+//
+// LDS holds a ring of NS stages; a stage is one 32-key tile: the K rows and the V rows exactly as
+// they lie in memory ([key][channel], 2*D bytes per row).  Stages are filled by direct-to-LDS
+// global loads (each lane moves 16 bytes, a wave instruction fills 1 KiB of LDS), so no staging
+// registers and no VALU work are spent on data movement and NS-1 stages stay in flight.
+// Bank conflicts are avoided by choosing which 16-byte chunk of a row each lane fetches: the chunk
+// stored at physical position pc of LDS row r is chunk pc ^ f(r) of the source row.
+//   K: LDS row i holds key kb + swap_bits_2_3(i) (the MFMA A-row order that makes a lane's 16 score
+//      registers two runs of 8 consecutive keys); A operands are 16-byte LDS reads.
+//   V: LDS row r holds key kb + r; the V^T A operand (one channel, 8 consecutive keys per lane) comes
+//      from two transposing LDS reads (ds_read_b64_tr_b16): a 16-lane group reads 4 keys x 16 channels
+//      and every lane receives the 4 keys of its own channel.
 // ------------------------------------------------------------------------------------------------
 template <int D>
 struct Lds {
-    static constexpr int KROW = D + 8;                       // bf16 elements per K row (16 B pad)
-    static constexpr int KBYTES = TK * KROW * 2;             // one K stage
-    static constexpr int VBYTES = D * TK * 2;                // one V^T stage: D rows of TK keys
-    static constexpr int STAGE = KBYTES + VBYTES;
-    static constexpr int TOTAL = 2 * STAGE;
+    static constexpr int ROWB = 2 * D;                       // bytes per K or V row
+    static constexpr int TILEB = 32 * ROWB;                  // one K (or V) tile
+    static constexpr int STAGE = 2 * TILEB;                  // K tile then V tile
+    static constexpr int LPW = STAGE / 1024 / 4;             // load instructions per wave per stage
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
-// dword index inside a V^T stage for (row d, key-pair kp): 32 dwords per row, 16-byte columns XOR-swizzled.
-__device__ __forceinline__ int vt_dword(int d, int kp)
-{
-    int sw = (d & 7) ^ ((d >> 3) & 7);
-    return d * (TK / 2) + ((((kp >> 2) ^ sw) & 7) << 2) + (kp & 3);
-}
+template <int D> __device__ __forceinline__ int swz_k(int row) { return row & (D / 8 - 1); }
+template <int D> __device__ __forceinline__ int swz_v(int row) { return (row & (D / 8 - 1)) ^ (((row >> 3) & 1) << 2); }
 
+#define BTV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 template <bool PAGED>
 struct StageCtx {
     const uint16_t *Kp, *Vp;
-    const int32_t *block_table;
-    int rq, max_blocks, num_blocks, Hkv, g, S;
-    __device__ __forceinline__ long long row(int j) const
-    {
-        if (!PAGED) return j;
-        int b = block_table[(long long)rq * max_blocks + (j >> 4)];
-        b = min(max(b, 0), num_blocks - 1);
-        return (long long)b * BTV_PAGE + (j & 15);
-    }
+    const int32_t *block_table;   // row of this request
+    int num_blocks, Hkv, g, S;
 };
 
-// Global -> registers for one 64-key stage: each thread fetches D/32 16-byte pieces of K and of V.
-// Keys past the end of the sequence re-read the last valid row (finite data; they are masked later).
+// Issue the direct-to-LDS loads of tile `st` (keys 32*st ..) into ring slot `slot`.  Keys past the end of
+// the sequence re-read the last valid row (finite data; their scores are masked).
 template <int D, bool PAGED>
-__device__ __forceinline__ void load_stage(const StageCtx<PAGED> &cx, int st, int tid, uint4 (&kreg)[D / 32],
-                                           uint4 (&vreg)[D / 32])
+__device__ __forceinline__ void issue_stage(const StageCtx<PAGED> &cx, unsigned char *smem, int slot, int st, int w, int l)
 {
-    constexpr int CH = D / 8, NP = CH / 4, KPI = 128 / CH;
-    const int kb = st * TK, w = tid >> 6, l = tid & 63;
-#pragma unroll
-    for (int r = 0; r < NP; ++r) {
-        int piece = r * 256 + tid;
-        int key = min(kb + piece / CH, cx.S - 1);
-        kreg[r] = *reinterpret_cast<const uint4 *>(cx.Kp + (cx.row(key) * cx.Hkv + cx.g) * D + (piece % CH) * 8);
-    }
-#pragma unroll
-    for (int r = 0; r < NP; ++r) {
-        int key = min(kb + r * (4 * KPI) + w * KPI + 2 * (l / (2 * CH)) + (l & 1), cx.S - 1);
-        vreg[r] = *reinterpret_cast<const uint4 *>(cx.Vp + (cx.row(key) * cx.Hkv + cx.g) * D + ((l >> 1) % CH) * 8);
-    }
-}
-
-// Registers -> LDS.  K rows are stored in MFMA A-row order (bits 2 and 3 of the key index swapped) so that
-// a lane's 16 score registers cover two runs of 8 consecutive keys; V is transposed: lanes 2x and 2x+1 hold
-// two consecutive keys of the same 8 channels, exchange halves, and each writes 4 (channel, key-pair) dwords.
-template <int D>
-__device__ __forceinline__ void store_stage(unsigned char *smem, int buf, int tid, const uint4 (&kreg)[D / 32],
-                                            const uint4 (&vreg)[D / 32])
-{
-    constexpr int CH = D / 8, NP = CH / 4, KPI = 128 / CH;
     using LD = Lds<D>;
-    const int w = tid >> 6, l = tid & 63;
-    uint16_t *Ks = reinterpret_cast<uint16_t *>(smem + buf * LD::STAGE);
-    uint32_t *Vt = reinterpret_cast<uint32_t *>(smem + buf * LD::STAGE + LD::KBYTES);
-#pragma unroll
-    for (int r = 0; r < NP; ++r) {
-        int piece = r * 256 + tid;
-        int kk = piece / CH;
-        int lrow = (kk & 32) | swap_bits_2_3(kk & 31);
-        *reinterpret_cast<uint4 *>(Ks + lrow * LD::KROW + (piece % CH) * 8) = kreg[r];
+    constexpr int CH = D / 8;                 // 16-byte chunks per row
+    constexpr int RPI = 1024 / LD::ROWB;      // rows filled by one wave instruction
+    const int kb = st * 32;
+    // a 32-key tile spans two 16-token pages; their ids are wave-uniform (scalar loads, so the vector-memory
+    // counter only ever counts the LDS fills)
+    long long page0 = 0, page1 = 0;
+    if (PAGED) {
+        const int last_page = (cx.S - 1) >> 4;
+        typedef const __attribute__((address_space(4))) int32_t *const_i32;   // constant space: scalar loads
+        const_i32 bt = reinterpret_cast<const_i32>(reinterpret_cast<uintptr_t>(cx.block_table));
+        const int i0 = __builtin_amdgcn_readfirstlane(min(2 * st, last_page));
+        const int i1 = __builtin_amdgcn_readfirstlane(min(2 * st + 1, last_page));
+        int b0 = bt[i0], b1 = bt[i1];
+        page0 = (long long)min(max(b0, 0), cx.num_blocks - 1) * BTV_PAGE;
+        page1 = (long long)min(max(b1, 0), cx.num_blocks - 1) * BTV_PAGE;
     }
 #pragma unroll
-    for (int r = 0; r < NP; ++r) {
-        const int par = l & 1;
-        uint4 v = vreg[r];
-        uint32_t s0 = par ? v.x : v.z, s1 = par ? v.y : v.w;
-        uint32_t r0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)s0, 0xB1, 0xF, 0xF, true);
-        uint32_t r1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)s1, 0xB1, 0xF, 0xF, true);
-        uint32_t a0 = par ? r0 : v.x, a1 = par ? r1 : v.y;      // even key of the pair
-        uint32_t b0 = par ? v.z : r0, b1 = par ? v.w : r1;      // odd key of the pair
-        uint32_t o0 = (a0 & 0xFFFFu) | (b0 << 16);
-        uint32_t o1 = (a0 >> 16) | (b0 & 0xFFFF0000u);
-        uint32_t o2 = (a1 & 0xFFFFu) | (b1 << 16);
-        uint32_t o3 = (a1 >> 16) | (b1 & 0xFFFF0000u);
-        int kp = (r * (4 * KPI) + w * KPI + 2 * (l / (2 * CH))) >> 1;
-        int d0 = ((l >> 1) % CH) * 8 + par * 4;
-        Vt[vt_dword(d0 + 0, kp)] = o0;
-        Vt[vt_dword(d0 + 1, kp)] = o1;
-        Vt[vt_dword(d0 + 2, kp)] = o2;
-        Vt[vt_dword(d0 + 3, kp)] = o3;
+    for (int jj = 0; jj < LD::LPW; ++jj) {
+        const int j = w * LD::LPW + jj;                       // instruction index within the stage
+        const bool isv = j >= LD::TILEB / 1024;
+        const int jt = isv ? j - LD::TILEB / 1024 : j;        // instruction index within the K or V tile
+        const int r = jt * RPI + l / CH, pc = l % CH;         // LDS row and physical chunk of this lane
+        const int key = min(kb + (isv ? r : swap_bits_2_3(r)), cx.S - 1);
+        const int chunk = pc ^ (isv ? swz_v<D>(r) : swz_k<D>(r));
+        const long long prow = PAGED ? (((key - kb) & 16) ? page1 : page0) + (key & 15) : (long long)key;
+        const uint16_t *src = (isv ? cx.Vp : cx.Kp) + (prow * cx.Hkv + cx.g) * D + chunk * 8;
+        __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + slot * LD::STAGE + j * 1024), 16, 0, 0);
     }
 }
 
 // One 32-key tile of one wave: S^T = K.Q^T, tree mask, online softmax, O^T += V^T.P^T.
 template <int D, int QB>
-__device__ __forceinline__ void do_tile(const unsigned char *stage, int t, int kb, int Lr, int c, int h, float sl2,
+__device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int Lr, int l, float sl2,
                                         const uint32_t *anc, int q0, const int (&node)[QB],
                                         const bf16x8 (&qreg)[QB][D / 16], float (&m_run)[QB], float (&l_run)[QB],
                                         f32x16 (&oacc)[D / 32][QB])
 {
     constexpr int DS = D / 16, DT = D / 32;
     using LD = Lds<D>;
-    const uint16_t *Ks = reinterpret_cast<const uint16_t *>(stage);
-    const uint32_t *Vt = reinterpret_cast<const uint32_t *>(stage + LD::KBYTES);
+    const int c = l & 31, h = l >> 5;
+    const unsigned char *Ks = stage, *Vs = stage + LD::TILEB;
     f32x16 sacc[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.f;
+    const int kswz = swz_k<D>(c);
 #pragma unroll
     for (int s = 0; s < DS; ++s) {
-        bf16x8 a = *reinterpret_cast<const bf16x8 *>(Ks + (t * 32 + c) * LD::KROW + s * 16 + h * 8);
+        bf16x8 a = *reinterpret_cast<const bf16x8 *>(Ks + c * LD::ROWB + (((2 * s + h) ^ kswz) << 4));
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
             sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s], sacc[qb], 0, 0, 0);
@@ -275,7 +251,10 @@ __device__ __forceinline__ void do_tile(const unsigned char *stage, int t, int k
         float tmax = sacc[qb][0];
 #pragma unroll
         for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sacc[qb][v]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        {   // other half of the wave holds the other 16 keys of the same query
+            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
         float mnew = fmaxf(m_run[qb], tmax);
         float alpha = __builtin_amdgcn_exp2f((m_run[qb] - mnew) * sl2);
         float mc = mnew * sl2;
@@ -297,30 +276,45 @@ __device__ __forceinline__ void do_tile(const unsigned char *stage, int t, int k
 #pragma unroll
             for (int e = 0; e < 8; ++e) pb[qb][mm][e] = (__bf16)pv[mm * 8 + e];
     }
+    // V^T operands: lane l sits in 16-lane group l/16 = 2h + dhalf; it supplies the address of key row
+    // 16mm + 8h + 4i + (l%16)/4, channels 32dt + 16dhalf + 4(l%4) .. +3, and receives keys 16mm + 8h + 4i .. +3
+    // of channel 32dt + (l%32).
+    const int dhalf = (l >> 4) & 1, rr = (l & 15) >> 2, q = l & 3;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int mm = 0; mm < 2; ++mm) {
-            int d = dt * 32 + c;
-            int gi = t * 4 + mm * 2 + h;
-            int sw = (d & 7) ^ ((d >> 3) & 7);
-            bf16x8 a = *reinterpret_cast<const bf16x8 *>(Vt + d * (TK / 2) + (((gi ^ sw) & 7) << 2));
+            bf16x4 lo, hi;
+            {
+                const int r0 = 16 * mm + 8 * h + rr, r1 = r0 + 4;
+                const int chunk = 4 * dt + 2 * dhalf + (q >> 1);
+                lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                    (__attribute__((address_space(3))) bf16x4 *)BTV_LDS_PTR(Vs + r0 * LD::ROWB + ((chunk ^ swz_v<D>(r0)) << 4) + ((q & 1) << 3)));
+                hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                    (__attribute__((address_space(3))) bf16x4 *)BTV_LDS_PTR(Vs + r1 * LD::ROWB + ((chunk ^ swz_v<D>(r1)) << 4) + ((q & 1) << 3)));
+            }
+            bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
                 oacc[dt][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][mm], oacc[dt][qb], 0, 0, 0);
         }
 }
 
-template <int D, int QB, int KW, bool PAGED>
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int D, int QB, int KW, int NS, bool PAGED>
 __global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
 {
     constexpr int RW = 4 / KW;
     constexpr int WR = RW * QB * 32;
     constexpr int DS = D / 16;
     constexpr int DT = D / 32;
-    constexpr int NP = D / 32;           // 16-byte pieces per thread per stage (K and V each)
     using LD = Lds<D>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 31, h = l >> 5;
     const int kw = w % KW, rw = w / KW;
@@ -333,15 +327,20 @@ __global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
     const int Mr = rq_.M, Lr = rq_.L, S = Lr + Mr;
     const int rows_g = Mr * p.G;
     if ((int)blockIdx.y * WR >= rows_g) return;
-    const int stages = (S + TK - 1) / TK;
-    const int nsplit_r = (stages + p.sps - 1) / p.sps;
+    const int tiles = (S + 31) / 32;
+    const int nsplit_r = (tiles + p.sps - 1) / p.sps;
     if ((int)blockIdx.x >= nsplit_r) return;
-    const int st0 = blockIdx.x * p.sps, st1 = min(st0 + p.sps, stages);
+    const int st0 = blockIdx.x * p.sps, st1 = min(st0 + p.sps, tiles);
 
     const uint16_t *Qp = static_cast<const uint16_t *>(p.Q);
-    const uint16_t *Kp = static_cast<const uint16_t *>(p.K);
-    const uint16_t *Vp = static_cast<const uint16_t *>(p.V);
+    const StageCtx<PAGED> cx = { static_cast<const uint16_t *>(p.K), static_cast<const uint16_t *>(p.V),
+                                 PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr, p.num_blocks, p.Hkv, g, S };
 
+    // ---- start filling the ring: NS-1 tiles in flight ------------------------------------------
+    int issued = st0, islot = 0;
+#pragma unroll
+    for (int k = 0; k < NS - 1; ++k)
+        if (issued < st1) { issue_stage<D, PAGED>(cx, smem, islot, issued, w, l); ++issued; ++islot; }
     // ---- per-lane query rows -------------------------------------------------------------------
     int node[QB];
     long long orow[QB];       // row index into Q/O viewed as [total_M*Hq, D]
@@ -362,6 +361,13 @@ __global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
         }
     }
 
+    // Pin the Q registers here: the compiler then waits for the Q loads in straight-line code, before the loop,
+    // instead of draining the whole vector-memory queue at their first use inside it.
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[qb][s]));
+
     float m_run[QB], l_run[QB];
     f32x16 oacc[DT][QB];
 #pragma unroll
@@ -373,64 +379,67 @@ __global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
             for (int v = 0; v < 16; ++v) oacc[dt][qb][v] = 0.f;
     }
 
-    // ---- main loop over the stages of this split -----------------------------------------------
-    uint4 kreg[NP], vreg[NP];
-    const StageCtx<PAGED> cx = { Kp, Vp, p.block_table, rq, p.max_blocks, p.num_blocks, p.Hkv, g, S };
-    load_stage<D, PAGED>(cx, st0, tid, kreg, vreg);
-    store_stage<D>(smem, 0, tid, kreg, vreg);
-    __syncthreads();
+    // ---- main loop: one barrier per tile --------------------------------------------------------
+    // At the top of iteration st the tiles st+1 .. issued-1 may still be in flight; the barrier also tells
+    // that every wave is done with tile st-1, whose ring slot the next issue overwrites.
+    int cslot = 0, turn = 0;
+    if (islot == NS) islot = 0;
     for (int st = st0; st < st1; ++st) {
-        const int buf = (st - st0) & 1;
-        const bool more = st + 1 < st1;
-        if (more) load_stage<D, PAGED>(cx, st + 1, tid, kreg, vreg);
-#pragma unroll
-        for (int t = 0; t < TK / 32; ++t) {
-            if (t % KW != kw) continue;
-            int kb = st * TK + t * 32;
-            if (kb < S)
-                do_tile<D, QB>(smem + buf * LD::STAGE, t, kb, Lr, c, h, p.scale_log2, p.anc, rq_.q0, node, qreg, m_run,
-                               l_run, oacc);
+        if (issued - st - 1 == NS - 2) wait_vmcnt<(NS - 2) * LD::LPW>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (issued < st1) {
+            issue_stage<D, PAGED>(cx, smem, islot, issued, w, l);
+            ++issued;
+            if (++islot == NS) islot = 0;
         }
-        if (more) store_stage<D>(smem, buf ^ 1, tid, kreg, vreg);
-        __syncthreads();
+        if (turn == kw)
+            do_tile<D, QB>(smem + cslot * LD::STAGE, st * 32, Lr, l, p.scale_log2, p.anc, rq_.q0, node, qreg, m_run, l_run,
+                           oacc);
+        if (++cslot == NS) cslot = 0;
+        if (++turn == KW) turn = 0;
     }
 
     // both halves of a wave hold partial row sums of the same queries
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32);
 
-    // ---- merge the key-split waves of this workgroup through LDS -----------------------------
+    // ---- merge the key-split waves of this workgroup through LDS, one donor wave at a time ----
     if (KW > 1) {
         constexpr int SLOT = (DT * QB * 16 + 2 * QB) * 64;    // floats per row-wave slot
         float *mg = reinterpret_cast<float *>(smem) + rw * SLOT;
-        if (kw == 1) {
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) mg[((dt * QB + qb) * 16 + v) * 64 + l] = oacc[dt][qb][v];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                mg[(DT * QB * 16 + qb) * 64 + l] = m_run[qb];
-                mg[(DT * QB * 16 + QB + qb) * 64 + l] = l_run[qb];
-            }
-        }
-        __syncthreads();
-        if (kw == 0) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float m1 = mg[(DT * QB * 16 + qb) * 64 + l], l1 = mg[(DT * QB * 16 + QB + qb) * 64 + l];
-                float mn = fmaxf(m_run[qb], m1);
-                float a0 = __builtin_amdgcn_exp2f((m_run[qb] - mn) * p.scale_log2);
-                float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
-                m_run[qb] = mn;
-                l_run[qb] = l_run[qb] * a0 + l1 * a1;
+        for (int donor = 1; donor < KW; ++donor) {
+            __syncthreads();
+            if (kw == donor) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        oacc[dt][qb][v] = oacc[dt][qb][v] * a0 + mg[((dt * QB + qb) * 16 + v) * 64 + l] * a1;
+                    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) mg[((dt * QB + qb) * 16 + v) * 64 + l] = oacc[dt][qb][v];
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    mg[(DT * QB * 16 + qb) * 64 + l] = m_run[qb];
+                    mg[(DT * QB * 16 + QB + qb) * 64 + l] = l_run[qb];
+                }
+            }
+            __syncthreads();
+            if (kw == 0) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    float m1 = mg[(DT * QB * 16 + qb) * 64 + l], l1 = mg[(DT * QB * 16 + QB + qb) * 64 + l];
+                    float mn = fmaxf(m_run[qb], m1);
+                    float a0 = __builtin_amdgcn_exp2f((m_run[qb] - mn) * p.scale_log2);
+                    float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
+                    m_run[qb] = mn;
+                    l_run[qb] = l_run[qb] * a0 + l1 * a1;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            oacc[dt][qb][v] = oacc[dt][qb][v] * a0 + mg[((dt * QB + qb) * 16 + v) * 64 + l] * a1;
+                }
             }
         }
     }
@@ -585,11 +594,14 @@ int g_split_override = 0;
 
 struct Plan { int qb, kw, wr, row_blocks, stages, sps, nsplit; };
 
+// Kernel shape by the number of packed rows per KV head (G*M): few rows -> all four waves share the rows and
+// split the keys (KW = 4 or 2); many rows -> four row-waves of 64 rows, workgroups tile the rows in blocks of 256.
 Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
 {
     Plan pl;
     int G = Hq / Hkv, rows_g = G * M;
-    if (rows_g <= 64) { pl.qb = 1; pl.kw = 2; }
+    if (rows_g <= 32) { pl.qb = 1; pl.kw = 4; }
+    else if (rows_g <= 64) { pl.qb = 2; pl.kw = 4; }
     else if (rows_g <= 128) { pl.qb = 2; pl.kw = 2; }
     else { pl.qb = 2; pl.kw = 1; }
     pl.wr = (4 / pl.kw) * pl.qb * 32;
@@ -597,8 +609,8 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
     pl.stages = (L + M + TK - 1) / TK;
     int base = Hkv * pl.row_blocks * batch;
     int want = g_split_override > 0 ? g_split_override : (256 + base - 1) / base;
-    // a split should stream at least 4 stages (256 keys) unless the caller forces it
-    if (g_split_override <= 0) want = std::min(want, std::max(1, pl.stages / 4));
+    // a split should stream at least 8 tiles (256 keys) unless the caller forces it
+    if (g_split_override <= 0) want = std::min(want, std::max(1, pl.stages / 8));
     want = std::max(1, std::min(want, pl.stages));
     pl.sps = (pl.stages + want - 1) / want;
     pl.nsplit = (pl.stages + pl.sps - 1) / pl.sps;
@@ -620,17 +632,21 @@ WsLayout ws_layout(int total_M, int Hq, int D, int nsplit)
     return w;
 }
 
-template <int D, int QB, int KW, bool PAGED>
+template <int D, int QB, int KW, int NS, bool PAGED>
 int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 {
+    constexpr int RING = NS * Lds<D>::STAGE;
+    constexpr int MERGE = KW > 1 ? (4 / KW) * ((D / 32) * QB * 16 + 2 * QB) * 64 * 4 : 0;
+    constexpr int LDS_BYTES = RING > MERGE ? RING : MERGE;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static bool configured = false;
-    auto kern = tv_attn_bf16<D, QB, KW, PAGED>;
+    auto kern = tv_attn_bf16<D, QB, KW, NS, PAGED>;
     if (!configured) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    Lds<D>::TOTAL));
+                                    LDS_BYTES));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), Lds<D>::TOTAL, st, p);
+    hipLaunchKernelGGL(kern, grid, dim3(256), LDS_BYTES, st, p);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -639,10 +655,10 @@ template <bool PAGED>
 int dispatch_bf16(const AttnParams &p, const Plan &pl, int D, int batch, hipStream_t st)
 {
     dim3 grid(pl.nsplit, pl.row_blocks, p.Hkv * batch);
-#define BTV_CASE(DD, QQ, KK) \
-    if (D == DD && pl.qb == QQ && pl.kw == KK) return launch_bf16<DD, QQ, KK, PAGED>(p, grid, st);
-    BTV_CASE(128, 1, 2) BTV_CASE(128, 2, 2) BTV_CASE(128, 2, 1)
-    BTV_CASE(64, 1, 2) BTV_CASE(64, 2, 2) BTV_CASE(64, 2, 1)
+#define BTV_CASE(DD, QQ, KK, NN) \
+    if (D == DD && pl.qb == QQ && pl.kw == KK) return launch_bf16<DD, QQ, KK, NN, PAGED>(p, grid, st);
+    BTV_CASE(128, 1, 4, 4) BTV_CASE(128, 2, 4, 6) BTV_CASE(128, 2, 2, 6) BTV_CASE(128, 2, 1, 6)
+    BTV_CASE(64, 1, 4, 4) BTV_CASE(64, 2, 4, 6) BTV_CASE(64, 2, 2, 6) BTV_CASE(64, 2, 1, 6)
 #undef BTV_CASE
     return btv_fail(BTV_EINVAL, "no kernel for D=%d", D);
 }
