@@ -49,6 +49,9 @@ struct AttnParams {
     int nsplit;                   // grid.x
     float scale;                  // softmax scale
     float scale_log2;             // scale * log2(e)
+#ifdef BTV_EXPERIMENT
+    unsigned long long *dbg;      // per-workgroup phase timestamps (experiment builds only)
+#endif
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
@@ -157,7 +160,7 @@ struct Lds {
     static constexpr int ROWB = 2 * D;                       // bytes per K or V row
     static constexpr int TILEB = 32 * ROWB;                  // one K (or V) tile
     static constexpr int STAGE = 2 * TILEB;                  // K tile then V tile
-    static constexpr int LPW = STAGE / 1024 / 4;             // load instructions per wave per stage
+    static constexpr int INSTR = STAGE / 1024;               // wave-wide 1 KiB fills per tile
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
@@ -174,14 +177,16 @@ struct StageCtx {
     int num_blocks, Hkv, g, S;
 };
 
-// Issue the direct-to-LDS loads of tile `st` (keys 32*st ..) into ring slot `slot`.  Keys past the end of
-// the sequence re-read the last valid row (finite data; their scores are masked).
-template <int D, bool PAGED>
-__device__ __forceinline__ void issue_stage(const StageCtx<PAGED> &cx, unsigned char *smem, int slot, int st, int w, int l)
+// Issue this wave's share of the direct-to-LDS loads of tile `st` (keys 32*st ..) into ring slot `slot`.
+// Keys past the end of the sequence re-read the last valid row (finite data; their scores are masked).
+template <int D, int WAVES, bool PAGED>
+__device__ __forceinline__ void issue_tile(const StageCtx<PAGED> &cx, unsigned char *smem, int slot, int st, int w, int l)
 {
     using LD = Lds<D>;
     constexpr int CH = D / 8;                 // 16-byte chunks per row
     constexpr int RPI = 1024 / LD::ROWB;      // rows filled by one wave instruction
+    constexpr int LPW = LD::INSTR / WAVES;    // fills per wave per tile
+    static_assert(LPW >= 1 && LPW * WAVES == LD::INSTR, "fills must divide evenly over the waves");
     const int kb = st * 32;
     // a 32-key tile spans two 16-token pages; their ids are wave-uniform (scalar loads, so the vector-memory
     // counter only ever counts the LDS fills)
@@ -197,10 +202,10 @@ __device__ __forceinline__ void issue_stage(const StageCtx<PAGED> &cx, unsigned 
         page1 = (long long)min(max(b1, 0), cx.num_blocks - 1) * BTV_PAGE;
     }
 #pragma unroll
-    for (int jj = 0; jj < LD::LPW; ++jj) {
-        const int j = w * LD::LPW + jj;                       // instruction index within the stage
+    for (int jj = 0; jj < LPW; ++jj) {
+        const int j = w * LPW + jj;                           // instruction index within the tile
         const bool isv = j >= LD::TILEB / 1024;
-        const int jt = isv ? j - LD::TILEB / 1024 : j;        // instruction index within the K or V tile
+        const int jt = isv ? j - LD::TILEB / 1024 : j;        // instruction index within the K or V part
         const int r = jt * RPI + l / CH, pc = l % CH;         // LDS row and physical chunk of this lane
         const int key = min(kb + (isv ? r : swap_bits_2_3(r)), cx.S - 1);
         const int chunk = pc ^ (isv ? swz_v<D>(r) : swz_k<D>(r));
@@ -210,93 +215,115 @@ __device__ __forceinline__ void issue_stage(const StageCtx<PAGED> &cx, unsigned 
     }
 }
 
-// One 32-key tile of one wave: S^T = K.Q^T, tree mask, online softmax, O^T += V^T.P^T.
-template <int D, int QB>
-__device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int Lr, int l, float sl2,
-                                        const uint32_t *anc, int q0, const int (&node)[QB],
-                                        const bf16x8 (&qreg)[QB][D / 16], float (&m_run)[QB], float (&l_run)[QB],
-                                        f32x16 (&oacc)[D / 32][QB])
+// ds_read_b64_tr_b16 as a raw instruction (see do_tile) and the wait that makes its results usable: the asm
+// takes every result register as an in/out operand, so no use can be scheduled above the wait.
+__device__ __forceinline__ bf16x4 lds_read_tr16(uint32_t lds_byte_addr)
+{
+    bf16x4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r) : "v"(lds_byte_addr));
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void lds_wait_tr(bf16x4 (&va)[DT][2][2])
+{
+    static_assert(DT == 2 || DT == 4, "D in {64,128}");
+    if constexpr (DT == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(va[0][0][0]), "+v"(va[0][0][1]), "+v"(va[0][1][0]), "+v"(va[0][1][1]), "+v"(va[1][0][0]),
+                       "+v"(va[1][0][1]), "+v"(va[1][1][0]), "+v"(va[1][1][1]), "+v"(va[2][0][0]), "+v"(va[2][0][1]),
+                       "+v"(va[2][1][0]), "+v"(va[2][1][1]), "+v"(va[3][0][0]), "+v"(va[3][0][1]), "+v"(va[3][1][0]),
+                       "+v"(va[3][1][1]));
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(va[0][0][0]), "+v"(va[0][0][1]), "+v"(va[0][1][0]), "+v"(va[0][1][1]), "+v"(va[1][0][0]),
+                       "+v"(va[1][0][1]), "+v"(va[1][1][0]), "+v"(va[1][1][1]));
+}
+
+// One 32-key tile of one wave (32 query rows): S^T = K.Q^T, tree mask, online softmax, O^T += V^T.P^T.
+// All K operands are fetched from LDS before the first MFMA and all V^T operands before the softmax, so the
+// LDS latency is paid once per phase and overlaps the arithmetic.
+template <int D>
+__device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int Lr, int l, float sl2, const uint32_t *anc_i,
+                                        const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
 {
     constexpr int DS = D / 16, DT = D / 32;
     using LD = Lds<D>;
     const int c = l & 31, h = l >> 5;
     const unsigned char *Ks = stage, *Vs = stage + LD::TILEB;
-    f32x16 sacc[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.f;
+    bf16x8 ka[DS];
     const int kswz = swz_k<D>(c);
 #pragma unroll
-    for (int s = 0; s < DS; ++s) {
-        bf16x8 a = *reinterpret_cast<const bf16x8 *>(Ks + c * LD::ROWB + (((2 * s + h) ^ kswz) << 4));
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-            sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s], sacc[qb], 0, 0, 0);
-    }
-    if (kb + 32 > Lr) {     // the tile touches tree rows (or the end of the sequence): apply the mask
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            uint32_t vis = vis_word(anc + (size_t)(q0 + node[qb]) * BTV_ANC_WORDS, kb, Lr);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int bit = 16 * (v >> 3) + 8 * h + (v & 7);
-                if (!((vis >> bit) & 1u)) sacc[qb][v] = -INFINITY;
-            }
-        }
-    }
-    bf16x8 pb[QB][2];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        float tmax = sacc[qb][0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sacc[qb][v]);
-        {   // other half of the wave holds the other 16 keys of the same query
-            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
-            tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        }
-        float mnew = fmaxf(m_run[qb], tmax);
-        float alpha = __builtin_amdgcn_exp2f((m_run[qb] - mnew) * sl2);
-        float mc = mnew * sl2;
-        m_run[qb] = mnew;
-        float rs = 0.f;
-        float pv[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            pv[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][v], sl2, -mc));
-            rs += pv[v];
-        }
-        l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[dt][qb][v] *= alpha;
-#pragma unroll
-        for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pb[qb][mm][e] = (__bf16)pv[mm * 8 + e];
-    }
+    for (int s = 0; s < DS; ++s)
+        ka[s] = *reinterpret_cast<const bf16x8 *>(Ks + c * LD::ROWB + (((2 * s + h) ^ kswz) << 4));
     // V^T operands: lane l sits in 16-lane group l/16 = 2h + dhalf; it supplies the address of key row
     // 16mm + 8h + 4i + (l%16)/4, channels 32dt + 16dhalf + 4(l%4) .. +3, and receives keys 16mm + 8h + 4i .. +3
     // of channel 32dt + (l%32).
-    const int dhalf = (l >> 4) & 1, rr = (l & 15) >> 2, q = l & 3;
+    // The reads are raw instructions: as a builtin they would make the compiler drain the whole vector-memory
+    // queue (the ring fills still in flight) in front of every tile.  lds_wait_tr() below is their counter wait.
+    bf16x4 va[DT][2][2];
+    {
+        const int dhalf = (l >> 4) & 1, rr = (l & 15) >> 2, q = l & 3;
+        const uint32_t vs_addr = (uint32_t)(uintptr_t)BTV_LDS_PTR(Vs);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int r = 16 * mm + 8 * h + 4 * i + rr;
+                    const int chunk = 4 * dt + 2 * dhalf + (q >> 1);
+                    va[dt][mm][i] = lds_read_tr16(vs_addr + r * LD::ROWB + ((chunk ^ swz_v<D>(r)) << 4) + ((q & 1) << 3));
+                }
+    }
+    f32x16 sacc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < DS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], sacc, 0, 0, 0);
+    if (kb + 32 > Lr) {     // the tile touches tree rows (or the end of the sequence): apply the mask
+        uint32_t vis = vis_word(anc_i, kb, Lr);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int bit = 16 * (v >> 3) + 8 * h + (v & 7);
+            if (!((vis >> bit) & 1u)) sacc[v] = -INFINITY;
+        }
+    }
+    float tmax = sacc[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sacc[v]);
+    {   // the other half of the wave holds the other 16 keys of the same query
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+        tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
+    const float mnew = fmaxf(m_run, tmax);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - mnew) * sl2);
+    const float mc = mnew * sl2;
+    m_run = mnew;
+    float rs = 0.f;
+    float pv[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        pv[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], sl2, -mc));
+        rs += pv[v];
+    }
+    l_run = l_run * alpha + rs;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+    bf16x8 pb[2];
+#pragma unroll
+    for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[mm][e] = (__bf16)pv[mm * 8 + e];
+    lds_wait_tr<DT>(va);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int mm = 0; mm < 2; ++mm) {
-            bf16x4 lo, hi;
-            {
-                const int r0 = 16 * mm + 8 * h + rr, r1 = r0 + 4;
-                const int chunk = 4 * dt + 2 * dhalf + (q >> 1);
-                lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (__attribute__((address_space(3))) bf16x4 *)BTV_LDS_PTR(Vs + r0 * LD::ROWB + ((chunk ^ swz_v<D>(r0)) << 4) + ((q & 1) << 3)));
-                hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (__attribute__((address_space(3))) bf16x4 *)BTV_LDS_PTR(Vs + r1 * LD::ROWB + ((chunk ^ swz_v<D>(r1)) << 4) + ((q & 1) << 3)));
-            }
-            bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                oacc[dt][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][mm], oacc[dt][qb], 0, 0, 0);
+            bf16x8 a = __builtin_shufflevector(va[dt][mm][0], va[dt][mm][1], 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[mm], oacc[dt], 0, 0, 0);
         }
 }
 
@@ -306,19 +333,31 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int QB, int KW, int NS, bool PAGED>
-__global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
+// Workgroup = RW row-waves x KW key-waves; wave (rw, kw) owns query rows [32 rw, 32 rw + 32) of the block and,
+// in every round of KW consecutive tiles, tile number kw.  LDS ring of NT tiles; one barrier per round.
+template <int D, int RW, int KW, int NT, bool PAGED>
+__global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 {
-    constexpr int RW = 4 / KW;
-    constexpr int WR = RW * QB * 32;
+    constexpr int WAVES = RW * KW;
+    constexpr int WR = RW * 32;
     constexpr int DS = D / 16;
     constexpr int DT = D / 32;
+    constexpr int LPW = Lds<D>::INSTR / WAVES;
+    constexpr int AHEAD = NT - 2 * KW;            // tiles still in flight when a round's tiles have landed
+    static_assert(AHEAD >= 0 && AHEAD * LPW < 64, "ring too small or too deep for the counter");
     using LD = Lds<D>;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 31, h = l >> 5;
     const int kw = w % KW, rw = w / KW;
     const int rq = blockIdx.z / p.Hkv, g = blockIdx.z % p.Hkv;
+#ifdef BTV_EXPERIMENT
+    unsigned long long ts[8];
+    ts[0] = __builtin_amdgcn_s_memtime();
+#define BTV_STAMP(i) ts[i] = __builtin_amdgcn_s_memtime()
+#else
+#define BTV_STAMP(i)
+#endif
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) {
         if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.flag, 2u);
@@ -336,78 +375,72 @@ __global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
     const StageCtx<PAGED> cx = { static_cast<const uint16_t *>(p.K), static_cast<const uint16_t *>(p.V),
                                  PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr, p.num_blocks, p.Hkv, g, S };
 
-    // ---- start filling the ring: NS-1 tiles in flight ------------------------------------------
+    // ---- start filling the ring: NT - KW tiles in flight ----------------------------------------
     int issued = st0, islot = 0;
 #pragma unroll
-    for (int k = 0; k < NS - 1; ++k)
-        if (issued < st1) { issue_stage<D, PAGED>(cx, smem, islot, issued, w, l); ++issued; ++islot; }
-    // ---- per-lane query rows -------------------------------------------------------------------
-    int node[QB];
-    long long orow[QB];       // row index into Q/O viewed as [total_M*Hq, D]
-    bool rvalid[QB];
-    bf16x8 qreg[QB][DS];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        int r = blockIdx.y * WR + (rw * QB + qb) * 32 + c;
-        rvalid[qb] = r < rows_g;
-        int rr = rvalid[qb] ? r : 0;
-        node[qb] = rr / p.G;
-        orow[qb] = (long long)(rq_.q0 + node[qb]) * p.Hq + g * p.G + (rr % p.G);
-#pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (rvalid[qb]) v = *reinterpret_cast<const uint4 *>(Qp + orow[qb] * D + s * 16 + h * 8);
-            qreg[qb][s] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
+    for (int k = 0; k < NT - KW; ++k)
+        if (issued < st1) { issue_tile<D, WAVES, PAGED>(cx, smem, islot, issued, w, l); ++issued; ++islot; }
+    if (islot >= NT) islot -= NT;
+    BTV_STAMP(5);
 
+    // ---- this lane's query row ---------------------------------------------------------------------
+    const int r = blockIdx.y * WR + rw * 32 + c;
+    const bool rvalid = r < rows_g;
+    const int rr = rvalid ? r : 0;
+    const int node = rr / p.G;
+    const long long orow = (long long)(rq_.q0 + node) * p.Hq + g * p.G + (rr % p.G);   // row of Q/O as [total_M*Hq, D]
+    const uint32_t *anc_i = p.anc + (size_t)(rq_.q0 + node) * BTV_ANC_WORDS;
+    bf16x8 qreg[DS];
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (rvalid) v = *reinterpret_cast<const uint4 *>(Qp + orow * D + s * 16 + h * 8);
+        qreg[s] = __builtin_bit_cast(bf16x8, v);
+    }
+    BTV_STAMP(6);
     // Pin the Q registers here: the compiler then waits for the Q loads in straight-line code, before the loop,
     // instead of draining the whole vector-memory queue at their first use inside it.
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[qb][s]));
+    for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[s]));
 
-    float m_run[QB], l_run[QB];
-    f32x16 oacc[DT][QB];
+    float m_run = NEG_BIG, l_run = 0.f;
+    f32x16 oacc[DT];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = NEG_BIG; l_run[qb] = 0.f;
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[dt][qb][v] = 0.f;
-    }
+        for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
 
-    // ---- main loop: one barrier per tile --------------------------------------------------------
-    // At the top of iteration st the tiles st+1 .. issued-1 may still be in flight; the barrier also tells
-    // that every wave is done with tile st-1, whose ring slot the next issue overwrites.
-    int cslot = 0, turn = 0;
-    if (islot == NS) islot = 0;
-    for (int st = st0; st < st1; ++st) {
-        if (issued - st - 1 == NS - 2) wait_vmcnt<(NS - 2) * LD::LPW>();
+    BTV_STAMP(1);
+    // ---- main loop: one barrier per round of KW tiles --------------------------------------------
+    // At the top of the round starting at tile st, tiles st+KW .. issued-1 may still be in flight.  The barrier
+    // also tells that every wave is done with the previous round, whose KW ring slots the next issues overwrite.
+    int cslot = kw;
+    for (int st = st0; st < st1; st += KW) {
+        if (issued - st - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (issued < st1) {
-            issue_stage<D, PAGED>(cx, smem, islot, issued, w, l);
-            ++issued;
-            if (++islot == NS) islot = 0;
-        }
-        if (turn == kw)
-            do_tile<D, QB>(smem + cslot * LD::STAGE, st * 32, Lr, l, p.scale_log2, p.anc, rq_.q0, node, qreg, m_run, l_run,
-                           oacc);
-        if (++cslot == NS) cslot = 0;
-        if (++turn == KW) turn = 0;
+#pragma unroll
+        for (int k = 0; k < KW; ++k)
+            if (issued < st1) {
+                issue_tile<D, WAVES, PAGED>(cx, smem, islot, issued, w, l);
+                ++issued;
+                if (++islot == NT) islot = 0;
+            }
+        if (st + kw < st1)
+            do_tile<D>(smem + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+        cslot += KW;
+        if (cslot >= NT) cslot -= NT;
     }
 
+    BTV_STAMP(2);
     // both halves of a wave hold partial row sums of the same queries
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32);
+    l_run += __shfl_xor(l_run, 32);
 
-    // ---- merge the key-split waves of this workgroup through LDS, one donor wave at a time ----
+    // ---- merge the key-waves of each row-wave through LDS, one donor at a time -------------------
     if (KW > 1) {
-        constexpr int SLOT = (DT * QB * 16 + 2 * QB) * 64;    // floats per row-wave slot
+        constexpr int SLOT = (DT * 16 + 2) * 64;    // floats per row-wave slot
         float *mg = reinterpret_cast<float *>(smem) + rw * SLOT;
+        wait_vmcnt<0>();
 #pragma unroll
         for (int donor = 1; donor < KW; ++donor) {
             __syncthreads();
@@ -415,67 +448,62 @@ __global__ __launch_bounds__(256, 1) void tv_attn_bf16(AttnParams p)
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) mg[((dt * QB + qb) * 16 + v) * 64 + l] = oacc[dt][qb][v];
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    mg[(DT * QB * 16 + qb) * 64 + l] = m_run[qb];
-                    mg[(DT * QB * 16 + QB + qb) * 64 + l] = l_run[qb];
-                }
+                    for (int v = 0; v < 16; ++v) mg[(dt * 16 + v) * 64 + l] = oacc[dt][v];
+                mg[(DT * 16) * 64 + l] = m_run;
+                mg[(DT * 16 + 1) * 64 + l] = l_run;
             }
             __syncthreads();
             if (kw == 0) {
+                const float m1 = mg[(DT * 16) * 64 + l], l1 = mg[(DT * 16 + 1) * 64 + l];
+                const float mn = fmaxf(m_run, m1);
+                const float a0 = __builtin_amdgcn_exp2f((m_run - mn) * p.scale_log2);
+                const float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
+                m_run = mn;
+                l_run = l_run * a0 + l1 * a1;
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    float m1 = mg[(DT * QB * 16 + qb) * 64 + l], l1 = mg[(DT * QB * 16 + QB + qb) * 64 + l];
-                    float mn = fmaxf(m_run[qb], m1);
-                    float a0 = __builtin_amdgcn_exp2f((m_run[qb] - mn) * p.scale_log2);
-                    float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
-                    m_run[qb] = mn;
-                    l_run[qb] = l_run[qb] * a0 + l1 * a1;
+                for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            oacc[dt][qb][v] = oacc[dt][qb][v] * a0 + mg[((dt * QB + qb) * 16 + v) * 64 + l] * a1;
-                }
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] = oacc[dt][v] * a0 + mg[(dt * 16 + v) * 64 + l] * a1;
             }
         }
     }
-    if (kw != 0) return;
+    BTV_STAMP(3);
+    if (kw != 0 || !rvalid) return;
 
     // ---- write: final bf16 rows when this request has a single split, fp32 partials otherwise ---
+    if (nsplit_r == 1) {
+        const float inv = 1.0f / l_run;
+        uint16_t *Op = static_cast<uint16_t *>(p.O) + orow * D;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        if (!rvalid[qb]) continue;
-        if (nsplit_r == 1) {
-            float inv = 1.0f / l_run[qb];
-            uint16_t *Op = static_cast<uint16_t *>(p.O) + orow[qb] * D;
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int q4 = 0; q4 < 4; ++q4) {
+                uint32_t lo = float_to_bf16_bits(oacc[dt][q4 * 4 + 0] * inv) | (float_to_bf16_bits(oacc[dt][q4 * 4 + 1] * inv) << 16);
+                uint32_t hi = float_to_bf16_bits(oacc[dt][q4 * 4 + 2] * inv) | (float_to_bf16_bits(oacc[dt][q4 * 4 + 3] * inv) << 16);
+                *reinterpret_cast<uint2 *>(Op + dt * 32 + q4 * 8 + h * 4) = make_uint2(lo, hi);
+            }
+    } else {
+        const size_t prow = (size_t)blockIdx.x * p.total_rows + orow;
+        float *Pp = p.Opart + prow * D;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    uint32_t lo = float_to_bf16_bits(oacc[dt][qb][q4 * 4 + 0] * inv) |
-                                  (float_to_bf16_bits(oacc[dt][qb][q4 * 4 + 1] * inv) << 16);
-                    uint32_t hi = float_to_bf16_bits(oacc[dt][qb][q4 * 4 + 2] * inv) |
-                                  (float_to_bf16_bits(oacc[dt][qb][q4 * 4 + 3] * inv) << 16);
-                    *reinterpret_cast<uint2 *>(Op + dt * 32 + q4 * 8 + h * 4) = make_uint2(lo, hi);
-                }
-        } else {
-            size_t prow = (size_t)blockIdx.x * p.total_rows + orow[qb];
-            float *Pp = p.Opart + prow * D;
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    f32x4 o = { oacc[dt][qb][q4 * 4 + 0], oacc[dt][qb][q4 * 4 + 1], oacc[dt][qb][q4 * 4 + 2],
-                                oacc[dt][qb][q4 * 4 + 3] };
-                    *reinterpret_cast<f32x4 *>(Pp + dt * 32 + q4 * 8 + h * 4) = o;
-                }
-            if (h == 0) *reinterpret_cast<float2 *>(p.ML + prow * 2) = make_float2(m_run[qb], l_run[qb]);
-        }
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 o = { oacc[dt][q4 * 4 + 0], oacc[dt][q4 * 4 + 1], oacc[dt][q4 * 4 + 2], oacc[dt][q4 * 4 + 3] };
+                *reinterpret_cast<f32x4 *>(Pp + dt * 32 + q4 * 8 + h * 4) = o;
+            }
+        if (h == 0) *reinterpret_cast<float2 *>(p.ML + prow * 2) = make_float2(m_run, l_run);
     }
+#ifdef BTV_EXPERIMENT
+    if (p.dbg && tid == 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        ts[4] = __builtin_amdgcn_s_memtime();
+        unsigned long long *d = p.dbg + 8 * (blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z));
+        for (int i = 0; i < 5; ++i) d[i] = ts[i];
+        d[7] = ts[5] - ts[0]; d[6] = ts[6] - ts[5];
+        d[5] = __builtin_amdgcn_s_getreg(((4 - 1) << 11) | (0 << 6) | 20);   // XCC_ID register
+    }
+#endif
 }
 
 // Split-K combine: O[row] = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e).
@@ -591,28 +619,36 @@ __global__ __launch_bounds__(256) void tv_attn_f32(AttnParams p)
 // host side
 // ------------------------------------------------------------------------------------------------
 int g_split_override = 0;
+#ifdef BTV_EXPERIMENT
+int g_cfg_rw = 0, g_cfg_kw = 0, g_cfg_nt = 0;
+unsigned long long *g_dbg = nullptr;
+#endif
 
-struct Plan { int qb, kw, wr, row_blocks, stages, sps, nsplit; };
+struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 
-// Kernel shape by the number of packed rows per KV head (G*M): few rows -> all four waves share the rows and
-// split the keys (KW = 4 or 2); many rows -> four row-waves of 64 rows, workgroups tile the rows in blocks of 256.
+// Kernel shape by the number of packed rows per KV head (G*M).  Every wave owns 32 rows; few rows -> fewer
+// row-waves, and pairs of waves alternate over the tiles (KW = 2).
 Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
 {
     Plan pl;
     int G = Hq / Hkv, rows_g = G * M;
-    if (rows_g <= 32) { pl.qb = 1; pl.kw = 4; }
-    else if (rows_g <= 64) { pl.qb = 2; pl.kw = 4; }
-    else if (rows_g <= 128) { pl.qb = 2; pl.kw = 2; }
-    else { pl.qb = 2; pl.kw = 1; }
-    pl.wr = (4 / pl.kw) * pl.qb * 32;
+    if (rows_g <= 64) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
+    else if (rows_g <= 128) { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
+    else { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
+#ifdef BTV_EXPERIMENT
+    if (g_cfg_rw) { pl.rw = g_cfg_rw; pl.kw = g_cfg_kw; pl.nt = g_cfg_nt; }
+#endif
+    pl.wr = pl.rw * 32;
     pl.row_blocks = (rows_g + pl.wr - 1) / pl.wr;
     pl.stages = (L + M + TK - 1) / TK;
     int base = Hkv * pl.row_blocks * batch;
-    int want = g_split_override > 0 ? g_split_override : (256 + base - 1) / base;
+    int target = pl.rw * pl.kw == 4 ? 512 : 256;          // two 4-wave workgroups fit a CU
+    int want = g_split_override > 0 ? g_split_override : (target + base - 1) / base;
     // a split should stream at least 8 tiles (256 keys) unless the caller forces it
     if (g_split_override <= 0) want = std::min(want, std::max(1, pl.stages / 8));
     want = std::max(1, std::min(want, pl.stages));
     pl.sps = (pl.stages + want - 1) / want;
+    pl.sps = (pl.sps + pl.kw - 1) / pl.kw * pl.kw;         // whole rounds of KW tiles
     pl.nsplit = (pl.stages + pl.sps - 1) / pl.sps;
     return pl;
 }
@@ -632,21 +668,21 @@ WsLayout ws_layout(int total_M, int Hq, int D, int nsplit)
     return w;
 }
 
-template <int D, int QB, int KW, int NS, bool PAGED>
+template <int D, int RW, int KW, int NT, bool PAGED>
 int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 {
-    constexpr int RING = NS * Lds<D>::STAGE;
-    constexpr int MERGE = KW > 1 ? (4 / KW) * ((D / 32) * QB * 16 + 2 * QB) * 64 * 4 : 0;
+    constexpr int RING = NT * Lds<D>::STAGE;
+    constexpr int MERGE = KW > 1 ? RW * ((D / 32) * 16 + 2) * 64 * 4 : 0;
     constexpr int LDS_BYTES = RING > MERGE ? RING : MERGE;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static bool configured = false;
-    auto kern = tv_attn_bf16<D, QB, KW, NS, PAGED>;
+    auto kern = tv_attn_bf16<D, RW, KW, NT, PAGED>;
     if (!configured) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     LDS_BYTES));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), LDS_BYTES, st, p);
+    hipLaunchKernelGGL(kern, grid, dim3(RW * KW * 64), LDS_BYTES, st, p);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -655,10 +691,15 @@ template <bool PAGED>
 int dispatch_bf16(const AttnParams &p, const Plan &pl, int D, int batch, hipStream_t st)
 {
     dim3 grid(pl.nsplit, pl.row_blocks, p.Hkv * batch);
-#define BTV_CASE(DD, QQ, KK, NN) \
-    if (D == DD && pl.qb == QQ && pl.kw == KK) return launch_bf16<DD, QQ, KK, NN, PAGED>(p, grid, st);
-    BTV_CASE(128, 1, 4, 4) BTV_CASE(128, 2, 4, 6) BTV_CASE(128, 2, 2, 6) BTV_CASE(128, 2, 1, 6)
-    BTV_CASE(64, 1, 4, 4) BTV_CASE(64, 2, 4, 6) BTV_CASE(64, 2, 2, 6) BTV_CASE(64, 2, 1, 6)
+#define BTV_CASE(DD, RR, KK, NN) \
+    if (D == DD && pl.rw == RR && pl.kw == KK && pl.nt == NN) return launch_bf16<DD, RR, KK, NN, PAGED>(p, grid, st);
+#ifdef BTV_EXPERIMENT
+    BTV_CASE(128, 2, 2, 4) BTV_CASE(128, 2, 4, 10) BTV_CASE(128, 4, 2, 10) BTV_CASE(128, 8, 1, 10) BTV_CASE(128, 4, 1, 4)
+    BTV_CASE(128, 4, 1, 5) BTV_CASE(128, 2, 1, 4) BTV_CASE(128, 1, 4, 10) BTV_CASE(128, 2, 2, 8) BTV_CASE(128, 1, 2, 5)
+    BTV_CASE(128, 1, 4, 8)
+#endif
+    BTV_CASE(128, 2, 2, 5) BTV_CASE(128, 4, 2, 8) BTV_CASE(128, 8, 1, 8)
+    BTV_CASE(64, 2, 2, 5) BTV_CASE(64, 4, 2, 8) BTV_CASE(64, 8, 1, 8)
 #undef BTV_CASE
     return btv_fail(BTV_EINVAL, "no kernel for D=%d", D);
 }
@@ -685,6 +726,11 @@ int btv_launch_anc_mask(const int32_t *parent, const int32_t *q_offset, int batc
 extern "C" {
 
 void btv_set_attn_splits(int nsplit) { g_split_override = nsplit > 0 ? nsplit : 0; }
+
+#ifdef BTV_EXPERIMENT
+void btv_exp_set_cfg(int rw, int kw, int nt) { g_cfg_rw = rw; g_cfg_kw = kw; g_cfg_nt = nt; }
+void btv_exp_set_dbg(void *ptr) { g_dbg = static_cast<unsigned long long *>(ptr); }
+#endif
 
 int btv_tree_ancestor_mask(const int32_t *parent, int M, uint32_t *anc, void *ws, size_t ws_bytes, void *stream)
 {
@@ -728,6 +774,9 @@ int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int3
     p.sps = pl.sps; p.nsplit = pl.nsplit;
     p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     p.scale_log2 = p.scale * 1.4426950408889634f;
+#ifdef BTV_EXPERIMENT
+    p.dbg = g_dbg;
+#endif
     rc = btv_launch_anc_mask(parent, nullptr, 1, M, M, const_cast<uint32_t *>(p.anc), p.flag, st);
     if (rc) return rc;
     if (dtype == BTV_F32) {
@@ -787,6 +836,9 @@ int btv_tree_verify_attn_paged(const void *Q, const void *Kpool, const void *Vpo
     p.sps = pl.sps; p.nsplit = pl.nsplit;
     p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     p.scale_log2 = p.scale * 1.4426950408889634f;
+#ifdef BTV_EXPERIMENT
+    p.dbg = g_dbg;
+#endif
     rc = btv_launch_anc_mask(parent, q_offset, batch, M_max, total_M, const_cast<uint32_t *>(p.anc), p.flag, st);
     if (rc) return rc;
     rc = dispatch_bf16<true>(p, pl, D, batch, st);
