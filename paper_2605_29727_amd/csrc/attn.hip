@@ -26,6 +26,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TK = 32;          // keys per tile = per LDS stage
 constexpr float NEG_BIG = -1.0e30f;
@@ -33,7 +34,8 @@ constexpr float NEG_BIG = -1.0e30f;
 struct AttnParams {
     const void *Q, *K, *V;
     void *O;
-    const uint32_t *anc;          // [total_M][BTV_ANC_WORDS]
+    const int32_t *parent;        // [total_M], indices local to each request
+    const uint32_t *anc;          // [total_M][BTV_ANC_WORDS], fp32 path only
     const int32_t *block_table;   // paged only
     const int32_t *q_offset;      // paged only, [batch+1]
     const int32_t *prefix_len;    // paged only, [batch]
@@ -46,7 +48,8 @@ struct AttnParams {
     int total_rows;               // rows of the partial buffers (>= total_M * Hq)
     int total_M;
     int sps;                      // stages per split
-    int nsplit;                   // grid.x
+    int nsplit;                   // key splits of the longest request
+    int row_blocks, units;        // row blocks per (split, head, request) unit; number of units
     float scale;                  // softmax scale
     float scale_log2;             // scale * log2(e)
 #ifdef BTV_EXPERIMENT
@@ -88,19 +91,29 @@ __device__ __forceinline__ long long phys_row(const AttnParams &p, int r, int j)
     return (long long)b * BTV_PAGE + (j & 15);
 }
 
-// Visibility of keys kb..kb+31 for node i: bit c set iff key kb+c is a prefix row, or a tree
-// row L+a with a in anc(i).  Bits of anc past the request's node count are zero.
-__device__ __forceinline__ uint32_t vis_word(const uint32_t *anc_i, int kb, int L)
+// Visibility of keys kb..kb+31 for a node: bit c set iff key kb+c is a prefix row, or a tree
+// row L+a with a in anc(node).  Bits of anc past the request's node count are zero.
+// AncT is either a pointer to the node's BTV_ANC_WORDS words or a register array of them.
+template <typename AncT>
+__device__ __forceinline__ uint32_t anc_word(const AncT &anc, int w)
+{
+    uint32_t r = 0u;
+#pragma unroll
+    for (int k = 0; k < BTV_ANC_WORDS; ++k) r = (k == w) ? anc[k] : r;
+    return r;
+}
+
+template <typename AncT>
+__device__ __forceinline__ uint32_t vis_word(const AncT &anc, int kb, int L)
 {
     int off = kb - L;
     if (off <= -32) return 0xFFFFFFFFu;
     if (off < 0) {
         int n = -off;
-        return ((1u << n) - 1u) | (anc_i[0] << n);
+        return ((1u << n) - 1u) | (anc_word(anc, 0) << n);
     }
     int w = off >> 5, sh = off & 31;
-    uint32_t lo = (w < BTV_ANC_WORDS) ? anc_i[w] : 0u;
-    uint32_t hi = (w + 1 < BTV_ANC_WORDS) ? anc_i[w + 1] : 0u;
+    uint32_t lo = anc_word(anc, w), hi = anc_word(anc, w + 1);
     return sh ? ((lo >> sh) | (hi << (32 - sh))) : lo;
 }
 
@@ -166,52 +179,90 @@ struct Lds {
 __device__ __forceinline__ int swap_bits_2_3(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
 template <int D> __device__ __forceinline__ int swz_k(int row) { return row & (D / 8 - 1); }
-template <int D> __device__ __forceinline__ int swz_v(int row) { return (row & (D / 8 - 1)) ^ (((row >> 3) & 1) << 2); }
+// V rows: the four rows a 16-lane group of a transposing read touches (row % 4 = 0..3) are moved 64 bytes apart.
+template <int D> __device__ __forceinline__ int swz_v(int row) { return ((row & 3) << 2) & (D / 8 - 1); }
 
 #define BTV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-template <bool PAGED>
-struct StageCtx {
-    const uint16_t *Kp, *Vp;
-    const int32_t *block_table;   // row of this request
-    int num_blocks, Hkv, g, S;
+// Per-wave, loop-invariant part of the ring fills.  A wave issues LPW fills per tile; fill jj of wave w is
+// instruction j = w*LPW + jj of the tile (K part first).  Lane l of it fills LDS row r, physical chunk pc, with
+// source row key_off (relative to the tile's first key) and source chunk pc ^ swizzle(r).
+template <int D, int WAVES, bool PAGED>
+struct Fill {
+    static constexpr int LPW = Lds<D>::INSTR / WAVES;
+    static_assert(LPW >= 1 && LPW * WAVES == Lds<D>::INSTR, "fills must divide evenly over the waves");
+    const unsigned char *base[LPW]; // K or V base of this KV head for fill jj (wave-uniform)
+    const int32_t *block_table;     // row of this request (paged)
+    int num_blocks, S;
+    uint32_t row_bytes;             // Hkv * D * 2: distance between consecutive keys
+    uint32_t lane_off[LPW];         // contiguous: key_off*row_bytes + chunk*16;  paged: (key_off & 15)*row_bytes + chunk*16
+    int key_off[LPW];
 };
+
+template <int D, int WAVES, bool PAGED>
+__device__ __forceinline__ Fill<D, WAVES, PAGED> make_fill(const void *K, const void *V, const int32_t *bt, int num_blocks,
+                                                           int Hkv, int g, int S, int w, int l)
+{
+    using LD = Lds<D>;
+    constexpr int CH = D / 8, RPI = 1024 / LD::ROWB;
+    Fill<D, WAVES, PAGED> f;
+    const uintptr_t Kb = reinterpret_cast<uintptr_t>(K) + (size_t)g * D * 2, Vb = reinterpret_cast<uintptr_t>(V) + (size_t)g * D * 2;
+    f.block_table = bt; f.num_blocks = num_blocks; f.S = S;
+    f.row_bytes = (uint32_t)Hkv * D * 2;
+#pragma unroll
+    for (int jj = 0; jj < f.LPW; ++jj) {
+        const int j = w * f.LPW + jj;
+        const bool isv = j >= LD::TILEB / 1024;      // wave-uniform: this fill belongs to the V part
+        f.base[jj] = reinterpret_cast<const unsigned char *>(isv ? Vb : Kb);
+        const int jt = isv ? j - LD::TILEB / 1024 : j;
+        const int r = jt * RPI + l / CH, pc = l % CH;
+        f.key_off[jj] = isv ? r : swap_bits_2_3(r);
+        const int chunk = pc ^ (isv ? swz_v<D>(r) : swz_k<D>(r));
+        f.lane_off[jj] = (uint32_t)(PAGED ? (f.key_off[jj] & 15) : f.key_off[jj]) * f.row_bytes + chunk * 16;
+    }
+    return f;
+}
 
 // Issue this wave's share of the direct-to-LDS loads of tile `st` (keys 32*st ..) into ring slot `slot`.
 // Keys past the end of the sequence re-read the last valid row (finite data; their scores are masked).
 template <int D, int WAVES, bool PAGED>
-__device__ __forceinline__ void issue_tile(const StageCtx<PAGED> &cx, unsigned char *smem, int slot, int st, int w, int l)
+__device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED> &f, unsigned char *smem, int slot, int st, int w)
 {
     using LD = Lds<D>;
-    constexpr int CH = D / 8;                 // 16-byte chunks per row
-    constexpr int RPI = 1024 / LD::ROWB;      // rows filled by one wave instruction
-    constexpr int LPW = LD::INSTR / WAVES;    // fills per wave per tile
-    static_assert(LPW >= 1 && LPW * WAVES == LD::INSTR, "fills must divide evenly over the waves");
     const int kb = st * 32;
-    // a 32-key tile spans two 16-token pages; their ids are wave-uniform (scalar loads, so the vector-memory
-    // counter only ever counts the LDS fills)
-    long long page0 = 0, page1 = 0;
-    if (PAGED) {
-        const int last_page = (cx.S - 1) >> 4;
+    const bool whole = kb + 32 <= f.S;       // uniform: no key of this tile needs clamping
+    if (!PAGED) {
+        const size_t tile_off = (size_t)kb * f.row_bytes;
+#pragma unroll
+        for (int jj = 0; jj < f.LPW; ++jj) {
+            const unsigned char *base = f.base[jj] + tile_off;          // uniform
+            uint32_t off = f.lane_off[jj];
+            if (!whole) off = off - (uint32_t)f.key_off[jj] * f.row_bytes + (uint32_t)(min(kb + f.key_off[jj], f.S - 1) - kb) * f.row_bytes;
+            __builtin_amdgcn_global_load_lds(base + off, BTV_LDS_PTR(smem + slot * LD::STAGE + (w * f.LPW + jj) * 1024), 16, 0, 0);
+        }
+    } else {
+        // a 32-key tile spans two 16-token pages; their ids are wave-uniform (scalar loads, so the vector-memory
+        // counter only ever counts the LDS fills)
+        const int last_page = (f.S - 1) >> 4;
         typedef const __attribute__((address_space(4))) int32_t *const_i32;   // constant space: scalar loads
-        const_i32 bt = reinterpret_cast<const_i32>(reinterpret_cast<uintptr_t>(cx.block_table));
+        const_i32 bt = reinterpret_cast<const_i32>(reinterpret_cast<uintptr_t>(f.block_table));
         const int i0 = __builtin_amdgcn_readfirstlane(min(2 * st, last_page));
         const int i1 = __builtin_amdgcn_readfirstlane(min(2 * st + 1, last_page));
-        int b0 = bt[i0], b1 = bt[i1];
-        page0 = (long long)min(max(b0, 0), cx.num_blocks - 1) * BTV_PAGE;
-        page1 = (long long)min(max(b1, 0), cx.num_blocks - 1) * BTV_PAGE;
-    }
+        const size_t page0 = (size_t)min(max(bt[i0], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
+        const size_t page1 = (size_t)min(max(bt[i1], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
 #pragma unroll
-    for (int jj = 0; jj < LPW; ++jj) {
-        const int j = w * LPW + jj;                           // instruction index within the tile
-        const bool isv = j >= LD::TILEB / 1024;
-        const int jt = isv ? j - LD::TILEB / 1024 : j;        // instruction index within the K or V part
-        const int r = jt * RPI + l / CH, pc = l % CH;         // LDS row and physical chunk of this lane
-        const int key = min(kb + (isv ? r : swap_bits_2_3(r)), cx.S - 1);
-        const int chunk = pc ^ (isv ? swz_v<D>(r) : swz_k<D>(r));
-        const long long prow = PAGED ? (((key - kb) & 16) ? page1 : page0) + (key & 15) : (long long)key;
-        const uint16_t *src = (isv ? cx.Vp : cx.Kp) + (prow * cx.Hkv + cx.g) * D + chunk * 8;
-        __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + slot * LD::STAGE + j * 1024), 16, 0, 0);
+        for (int jj = 0; jj < f.LPW; ++jj) {
+            const unsigned char *b = f.base[jj];
+            int ko = f.key_off[jj];
+            uint32_t off = f.lane_off[jj];
+            if (!whole) {
+                const int kc = min(kb + ko, f.S - 1) - kb;
+                off = off - (uint32_t)(ko & 15) * f.row_bytes + (uint32_t)(kc & 15) * f.row_bytes;
+                ko = kc;
+            }
+            const unsigned char *src = b + ((ko & 16) ? page1 : page0) + off;
+            __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + slot * LD::STAGE + (w * f.LPW + jj) * 1024), 16, 0, 0);
+        }
     }
 }
 
@@ -244,7 +295,8 @@ __device__ __forceinline__ void lds_wait_tr(bf16x4 (&va)[DT][2][2])
 // All K operands are fetched from LDS before the first MFMA and all V^T operands before the softmax, so the
 // LDS latency is paid once per phase and overlaps the arithmetic.
 template <int D>
-__device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int Lr, int l, float sl2, const uint32_t *anc_i,
+__device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int Lr, int l, float sl2,
+                                        const uint32_t (&anc_i)[BTV_ANC_WORDS],
                                         const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
 {
     constexpr int DS = D / 16, DT = D / 32;
@@ -296,10 +348,22 @@ __device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int 
         auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
         tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
     }
-    const float mnew = fmaxf(m_run, tmax);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - mnew) * sl2);
-    const float mc = mnew * sl2;
-    m_run = mnew;
+    // Lazy reference maximum: m_run only moves when the tile maximum exceeds it by more than LAZY (in log2
+    // units), so probabilities stay below 2^LAZY and the O^T / row-sum rescale is skipped on most tiles.
+    // The result is unchanged: numerator and denominator refer to the same m_run.
+    constexpr float LAZY = 8.0f;
+    const bool grow = (tmax - m_run) * sl2 > LAZY;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+        const float mnew = grow ? tmax : m_run;
+        const float alpha = __builtin_amdgcn_exp2f((m_run - mnew) * sl2);
+        m_run = mnew;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+    }
+    const float mc = m_run * sl2;
     float rs = 0.f;
     float pv[16];
 #pragma unroll
@@ -307,11 +371,7 @@ __device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int 
         pv[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], sl2, -mc));
         rs += pv[v];
     }
-    l_run = l_run * alpha + rs;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+    l_run += rs;
     bf16x8 pb[2];
 #pragma unroll
     for (int mm = 0; mm < 2; ++mm)
@@ -350,7 +410,13 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 31, h = l >> 5;
     const int kw = w % KW, rw = w / KW;
-    const int rq = blockIdx.z / p.Hkv, g = blockIdx.z % p.Hkv;
+    // Workgroups go to the 8 XCDs round-robin by their linear id.  A unit = (key split, KV head, request); the row
+    // blocks of one unit stream the same K/V bytes, so they get ids that are congruent mod 8 and share one L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int by = slot % p.row_blocks, unit = (slot / p.row_blocks) * 8 + xcd;
+    if (unit >= p.units) return;
+    const int bx = unit % p.nsplit, bz = unit / p.nsplit;
+    const int rq = bz / p.Hkv, g = bz % p.Hkv;
 #ifdef BTV_EXPERIMENT
     unsigned long long ts[8];
     ts[0] = __builtin_amdgcn_s_memtime();
@@ -360,48 +426,64 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #endif
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) {
-        if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.flag, 2u);
+        if (tid == 0 && bx == 0 && by == 0) atomicOr(p.flag, 2u);
         return;
     }
     const int Mr = rq_.M, Lr = rq_.L, S = Lr + Mr;
     const int rows_g = Mr * p.G;
-    if ((int)blockIdx.y * WR >= rows_g) return;
+    if (by * WR >= rows_g) return;
     const int tiles = (S + 31) / 32;
     const int nsplit_r = (tiles + p.sps - 1) / p.sps;
-    if ((int)blockIdx.x >= nsplit_r) return;
-    const int st0 = blockIdx.x * p.sps, st1 = min(st0 + p.sps, tiles);
+    if (bx >= nsplit_r) return;
+    const int st0 = bx * p.sps, st1 = min(st0 + p.sps, tiles);
 
-    const uint16_t *Qp = static_cast<const uint16_t *>(p.Q);
-    const StageCtx<PAGED> cx = { static_cast<const uint16_t *>(p.K), static_cast<const uint16_t *>(p.V),
-                                 PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr, p.num_blocks, p.Hkv, g, S };
+    // ---- this lane's query row: issue the Q loads first (raw loads; the first ring wait below covers them) ---
+    const int r = by * WR + rw * 32 + c;
+    const bool rvalid = r < rows_g;
+    const int rr = rvalid ? r : 0;              // padding rows recompute row 0 and are never written
+    const int node = rr / p.G;
+    const long long orow = (long long)(rq_.q0 + node) * p.Hq + g * p.G + (rr % p.G);   // row of Q/O as [total_M*Hq, D]
+    u32x4 qv[DS];
+    {
+        const uint16_t *qptr = static_cast<const uint16_t *>(p.Q) + orow * D + h * 8;
+#pragma unroll
+        for (int s = 0; s < DS; ++s)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qv[s]) : "v"(qptr), "n"(s * 32));
+    }
 
     // ---- start filling the ring: NT - KW tiles in flight ----------------------------------------
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const Fill<D, WAVES, PAGED> fill = make_fill<D, WAVES, PAGED>(p.K, p.V, PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr,
+                                                                  p.num_blocks, p.Hkv, g, S, wu, l);
     int issued = st0, islot = 0;
 #pragma unroll
     for (int k = 0; k < NT - KW; ++k)
-        if (issued < st1) { issue_tile<D, WAVES, PAGED>(cx, smem, islot, issued, w, l); ++issued; ++islot; }
+        if (issued < st1) { issue_tile<D, WAVES, PAGED>(fill, smem, islot, issued, wu); ++issued; ++islot; }
     if (islot >= NT) islot -= NT;
     BTV_STAMP(5);
 
-    // ---- this lane's query row ---------------------------------------------------------------------
-    const int r = blockIdx.y * WR + rw * 32 + c;
-    const bool rvalid = r < rows_g;
-    const int rr = rvalid ? r : 0;
-    const int node = rr / p.G;
-    const long long orow = (long long)(rq_.q0 + node) * p.Hq + g * p.G + (rr % p.G);   // row of Q/O as [total_M*Hq, D]
-    const uint32_t *anc_i = p.anc + (size_t)(rq_.q0 + node) * BTV_ANC_WORDS;
-    bf16x8 qreg[DS];
+    // ---- ancestor bitmask of this lane's node, only in workgroups whose keys reach the tree rows ----------
+    // parent[] is staged in the last ring slot, which no fill touches before the first barrier of the main loop.
+    uint32_t anc_i[BTV_ANC_WORDS];
 #pragma unroll
-    for (int s = 0; s < DS; ++s) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (rvalid) v = *reinterpret_cast<const uint4 *>(Qp + orow * D + s * 16 + h * 8);
-        qreg[s] = __builtin_bit_cast(bf16x8, v);
+    for (int k = 0; k < BTV_ANC_WORDS; ++k) anc_i[k] = 0u;
+    if (st1 * 32 > Lr) {
+        int *par = reinterpret_cast<int *>(smem + (NT - 1) * LD::STAGE);
+        bool bad = false;
+        for (int i = tid; i < Mr; i += WAVES * 64) {
+            int pa = p.parent[rq_.q0 + i];
+            if (pa < -1 || pa >= i) { bad = true; pa = -1; }
+            par[i] = pa;
+        }
+        if (bad) atomicOr(p.flag, 1u);
+        __syncthreads();
+        for (int a = node; a >= 0; a = par[a]) {
+#pragma unroll
+            for (int k = 0; k < BTV_ANC_WORDS; ++k)
+                if ((a >> 5) == k) anc_i[k] |= 1u << (a & 31);
+        }
     }
     BTV_STAMP(6);
-    // Pin the Q registers here: the compiler then waits for the Q loads in straight-line code, before the loop,
-    // instead of draining the whole vector-memory queue at their first use inside it.
-#pragma unroll
-    for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qreg[s]));
 
     float m_run = NEG_BIG, l_run = 0.f;
     f32x16 oacc[DT];
@@ -409,6 +491,16 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
+
+    // The first round's fills are younger than the Q loads, so waiting for them also lands Q.
+    if (issued - st0 - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
+    else wait_vmcnt<0>();
+    bf16x8 qreg[DS];
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+        asm volatile("" : "+v"(qv[s]));
+        qreg[s] = __builtin_bit_cast(bf16x8, qv[s]);
+    }
 
     BTV_STAMP(1);
     // ---- main loop: one barrier per round of KW tiles --------------------------------------------
@@ -422,7 +514,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
         for (int k = 0; k < KW; ++k)
             if (issued < st1) {
-                issue_tile<D, WAVES, PAGED>(cx, smem, islot, issued, w, l);
+                issue_tile<D, WAVES, PAGED>(fill, smem, islot, issued, wu);
                 ++issued;
                 if (++islot == NT) islot = 0;
             }
@@ -436,25 +528,27 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     // both halves of a wave hold partial row sums of the same queries
     l_run += __shfl_xor(l_run, 32);
 
-    // ---- merge the key-waves of each row-wave through LDS, one donor at a time -------------------
+    // ---- merge the key-waves of each row-wave through LDS: donors write side by side, wave kw = 0 reduces ----
     if (KW > 1) {
-        constexpr int SLOT = (DT * 16 + 2) * 64;    // floats per row-wave slot
-        float *mg = reinterpret_cast<float *>(smem) + rw * SLOT;
+        constexpr int SLOT = (DT * 16 + 2) * 64;    // floats per donor
+        float *mg = reinterpret_cast<float *>(smem) + (rw * (KW - 1)) * SLOT;
         wait_vmcnt<0>();
+        __syncthreads();                            // every wave is done with the ring
+        if (kw > 0) {
+            float *d = mg + (kw - 1) * SLOT;
 #pragma unroll
-        for (int donor = 1; donor < KW; ++donor) {
-            __syncthreads();
-            if (kw == donor) {
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
+                for (int v = 0; v < 16; ++v) d[(dt * 16 + v) * 64 + l] = oacc[dt][v];
+            d[(DT * 16) * 64 + l] = m_run;
+            d[(DT * 16 + 1) * 64 + l] = l_run;
+        }
+        __syncthreads();
+        if (kw == 0) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) mg[(dt * 16 + v) * 64 + l] = oacc[dt][v];
-                mg[(DT * 16) * 64 + l] = m_run;
-                mg[(DT * 16 + 1) * 64 + l] = l_run;
-            }
-            __syncthreads();
-            if (kw == 0) {
-                const float m1 = mg[(DT * 16) * 64 + l], l1 = mg[(DT * 16 + 1) * 64 + l];
+            for (int donor = 0; donor < KW - 1; ++donor) {
+                const float *d = mg + donor * SLOT;
+                const float m1 = d[(DT * 16) * 64 + l], l1 = d[(DT * 16 + 1) * 64 + l];
                 const float mn = fmaxf(m_run, m1);
                 const float a0 = __builtin_amdgcn_exp2f((m_run - mn) * p.scale_log2);
                 const float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
@@ -463,7 +557,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[dt][v] = oacc[dt][v] * a0 + mg[(dt * 16 + v) * 64 + l] * a1;
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] = oacc[dt][v] * a0 + d[(dt * 16 + v) * 64 + l] * a1;
             }
         }
     }
@@ -483,7 +577,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 *reinterpret_cast<uint2 *>(Op + dt * 32 + q4 * 8 + h * 4) = make_uint2(lo, hi);
             }
     } else {
-        const size_t prow = (size_t)blockIdx.x * p.total_rows + orow;
+        const size_t prow = (size_t)bx * p.total_rows + orow;
         float *Pp = p.Opart + prow * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -498,7 +592,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     if (p.dbg && tid == 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         ts[4] = __builtin_amdgcn_s_memtime();
-        unsigned long long *d = p.dbg + 8 * (blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z));
+        unsigned long long *d = p.dbg + 8 * blockIdx.x;
         for (int i = 0; i < 5; ++i) d[i] = ts[i];
         d[7] = ts[5] - ts[0]; d[6] = ts[6] - ts[5];
         d[5] = __builtin_amdgcn_s_getreg(((4 - 1) << 11) | (0 << 6) | 20);   // XCC_ID register
@@ -507,11 +601,14 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 }
 
 // Split-K combine: O[row] = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e).
-// 8 rows per workgroup, 32 lanes per row.
+// 8 rows per workgroup, 32 lanes per row, each lane owns D/32 consecutive channels.  The (m, l) pairs of all
+// splits are fetched by the row's lanes in parallel and the partial rows are read in batches of independent
+// loads, so the kernel costs a few memory round trips whatever the number of splits.
 template <int D, bool PAGED>
 __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
 {
     constexpr int E = D / 32;
+    constexpr int BATCH = 8;
     const int rq = blockIdx.y;
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) return;
@@ -521,24 +618,46 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
     const int lr = blockIdx.x * 8 + (threadIdx.x >> 5), lane = threadIdx.x & 31;
     if (lr >= rq_.M * p.Hq) return;
     const size_t row = (size_t)rq_.q0 * p.Hq + lr;
+    // per-split weights: lane j handles splits j, j+32, ...
     float mmax = NEG_BIG;
-    for (int s = 0; s < nsplit_r; ++s) mmax = fmaxf(mmax, p.ML[((size_t)s * p.total_rows + row) * 2]);
-    float acc[E], den = 0.f;
+    for (int s = lane; s < nsplit_r; s += 32) mmax = fmaxf(mmax, p.ML[((size_t)s * p.total_rows + row) * 2]);
+    for (int off = 16; off >= 1; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 32));
+    float den = 0.f;
+    for (int s = lane; s < nsplit_r; s += 32) {
+        float2 ml = *reinterpret_cast<const float2 *>(p.ML + ((size_t)s * p.total_rows + row) * 2);
+        den += __builtin_amdgcn_exp2f((ml.x - mmax) * p.scale_log2) * ml.y;
+    }
+    for (int off = 16; off >= 1; off >>= 1) den += __shfl_xor(den, off, 32);
+    float acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.f;
-    for (int s = 0; s < nsplit_r; ++s) {
-        size_t pr = (size_t)s * p.total_rows + row;
-        float2 ml = *reinterpret_cast<const float2 *>(p.ML + pr * 2);
-        float wgt = __builtin_amdgcn_exp2f((ml.x - mmax) * p.scale_log2);
-        den += wgt * ml.y;
-        const float *src = p.Opart + pr * D + lane * E;
+    for (int s0 = 0; s0 < nsplit_r; s0 += BATCH) {
+        float part[BATCH][E], mm[BATCH];
 #pragma unroll
-        for (int e = 0; e < E; ++e) acc[e] += wgt * src[e];
+        for (int b = 0; b < BATCH; ++b) {
+            const int s = min(s0 + b, nsplit_r - 1);
+            const size_t pr = (size_t)s * p.total_rows + row;
+            mm[b] = p.ML[pr * 2];
+            const float *src = p.Opart + pr * D + lane * E;
+#pragma unroll
+            for (int e = 0; e < E; ++e) part[b][e] = src[e];
+        }
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const float wgt = s0 + b < nsplit_r ? __builtin_amdgcn_exp2f((mm[b] - mmax) * p.scale_log2) : 0.f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] += wgt * part[b][e];
+        }
     }
-    float inv = 1.0f / den;
+    const float inv = 1.0f / den;
     uint16_t *dst = static_cast<uint16_t *>(p.O) + row * D + lane * E;
-#pragma unroll
-    for (int e = 0; e < E; ++e) dst[e] = (uint16_t)float_to_bf16_bits(acc[e] * inv);
+    if (E == 4) {
+        uint32_t lo = float_to_bf16_bits(acc[0] * inv) | (float_to_bf16_bits(acc[1] * inv) << 16);
+        uint32_t hi = float_to_bf16_bits(acc[E - 2] * inv) | (float_to_bf16_bits(acc[E - 1] * inv) << 16);
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+    } else {
+        *reinterpret_cast<uint32_t *>(dst) = float_to_bf16_bits(acc[0] * inv) | (float_to_bf16_bits(acc[E - 1] * inv) << 16);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -672,7 +791,7 @@ template <int D, int RW, int KW, int NT, bool PAGED>
 int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 {
     constexpr int RING = NT * Lds<D>::STAGE;
-    constexpr int MERGE = KW > 1 ? RW * ((D / 32) * 16 + 2) * 64 * 4 : 0;
+    constexpr int MERGE = RW * (KW - 1) * ((D / 32) * 16 + 2) * 64 * 4;
     constexpr int LDS_BYTES = RING > MERGE ? RING : MERGE;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static bool configured = false;
@@ -688,9 +807,12 @@ int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 }
 
 template <bool PAGED>
-int dispatch_bf16(const AttnParams &p, const Plan &pl, int D, int batch, hipStream_t st)
+int dispatch_bf16(AttnParams &p, const Plan &pl, int D, int batch, hipStream_t st)
 {
-    dim3 grid(pl.nsplit, pl.row_blocks, p.Hkv * batch);
+    p.row_blocks = pl.row_blocks;
+    p.units = pl.nsplit * p.Hkv * batch;
+    const int units = pl.nsplit * p.Hkv * batch;
+    dim3 grid(((units + 7) / 8) * pl.row_blocks * 8);
 #define BTV_CASE(DD, RR, KK, NN) \
     if (D == DD && pl.rw == RR && pl.kw == KK && pl.nt == NN) return launch_bf16<DD, RR, KK, NN, PAGED>(p, grid, st);
 #ifdef BTV_EXPERIMENT
@@ -777,9 +899,10 @@ int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int3
 #ifdef BTV_EXPERIMENT
     p.dbg = g_dbg;
 #endif
-    rc = btv_launch_anc_mask(parent, nullptr, 1, M, M, const_cast<uint32_t *>(p.anc), p.flag, st);
-    if (rc) return rc;
+    p.parent = parent;
     if (dtype == BTV_F32) {
+        rc = btv_launch_anc_mask(parent, nullptr, 1, M, M, const_cast<uint32_t *>(p.anc), p.flag, st);
+        if (rc) return rc;
         if (D == 64) hipLaunchKernelGGL(tv_attn_f32<64>, dim3(M, Hq), dim3(256), 0, st, p);
         else hipLaunchKernelGGL(tv_attn_f32<128>, dim3(M, Hq), dim3(256), 0, st, p);
         BTV_HIP(hipGetLastError());
@@ -839,8 +962,7 @@ int btv_tree_verify_attn_paged(const void *Q, const void *Kpool, const void *Vpo
 #ifdef BTV_EXPERIMENT
     p.dbg = g_dbg;
 #endif
-    rc = btv_launch_anc_mask(parent, q_offset, batch, M_max, total_M, const_cast<uint32_t *>(p.anc), p.flag, st);
-    if (rc) return rc;
+    p.parent = parent;
     rc = dispatch_bf16<true>(p, pl, D, batch, st);
     if (rc) return rc;
     if (pl.nsplit > 1) {
