@@ -266,17 +266,66 @@ __device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED> &f, unsig
     }
 }
 
-// ds_read_b64_tr_b16 as a raw instruction (see do_tile) and the wait that makes its results usable: the asm
-// takes every result register as an in/out operand, so no use can be scheduled above the wait.
-__device__ __forceinline__ bf16x4 lds_read_tr16(uint32_t lds_byte_addr)
+// ---- LDS operand reads ---------------------------------------------------------------------------
+// All operand reads are raw instructions with explicit counter waits: as ordinary loads / builtins the
+// compiler would drain the whole vector-memory queue (the ring fills still in flight) in front of every tile.
+// Each wait takes the registers it covers as in/out operands, so no use can be scheduled above it.
+//
+// K A-operands: lane (c = l%32, h = l/32) reads chunk (2s+h) ^ swz_k(c) of LDS row c for s = 0..D/16-1.  Row
+// starts are 2*D-byte aligned, so the address is  (tile + lane part) ^ (s << 5).
+template <int D> __device__ __forceinline__ uint32_t lane_k_off(int l)
 {
-    bf16x4 r;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r) : "v"(lds_byte_addr));
-    return r;
+    const int c = l & 31, h = l >> 5;
+    return (uint32_t)(c * Lds<D>::ROWB + ((h ^ swz_k<D>(c)) << 4));
+}
+
+template <int D> __device__ __forceinline__ void lds_read_k(uint32_t a, u32x4 (&ka)[D / 16])
+{
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        const uint32_t addr = a ^ (uint32_t)(s << 5);
+        asm volatile("ds_read_b128 %0, %1" : "=v"(ka[s]) : "v"(addr));
+    }
+}
+
+template <int DS, int YOUNGER> __device__ __forceinline__ void lds_wait_k(u32x4 (&ka)[DS])
+{
+    static_assert(DS == 4 || DS == 8, "D in {64,128}");
+    if constexpr (DS == 8)
+        asm volatile("s_waitcnt lgkmcnt(%8)"
+                     : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(ka[4]), "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7])
+                     : "n"(YOUNGER));
+    else
+        asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]) : "n"(YOUNGER));
+}
+
+// V^T A-operands (ds_read_b64_tr_b16): lane l sits in 16-lane group l/16 = 2h + dhalf; for (dt, mm, i) it
+// supplies the address of key row 16mm + 8h + 4i + (l%16)/4, channels 32dt + 16dhalf + 4(l%4) .. +3, and
+// receives keys 16mm + 8h + 4i .. +3 of channel 32dt + (l%32).  With the V swizzle the address is
+// ((tile + lane part) ^ (dt << 6)) + (16mm + 4i) * row bytes, the last term an immediate offset.
+template <int D> __device__ __forceinline__ uint32_t lane_v_off(int l)
+{
+    const int h = l >> 5, dhalf = (l >> 4) & 1, rr = (l & 15) >> 2, q = l & 3;
+    const int x = 2 * dhalf + (q >> 1);
+    return (uint32_t)((8 * h + rr) * Lds<D>::ROWB + ((swz_v<D>(rr) ^ x) << 4) + ((q & 1) << 3));
+}
+
+// The reads for keys 16*MM .. 16*MM + 15 (the operands of the PV MFMAs with index mm = MM): 2*D/32 instructions.
+template <int D, int MM> __device__ __forceinline__ void lds_read_vt(uint32_t a, bf16x4 (&va)[D / 32][2][2])
+{
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+        const uint32_t addr = a ^ (uint32_t)(dt << 6);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                         : "=v"(va[dt][MM][i])
+                         : "v"(addr), "n"((16 * MM + 4 * i) * Lds<D>::ROWB));
+    }
 }
 
 template <int DT>
-__device__ __forceinline__ void lds_wait_tr(bf16x4 (&va)[DT][2][2])
+__device__ __forceinline__ void lds_wait_vt(bf16x4 (&va)[DT][2][2])
 {
     static_assert(DT == 2 || DT == 4, "D in {64,128}");
     if constexpr (DT == 4)
@@ -291,66 +340,36 @@ __device__ __forceinline__ void lds_wait_tr(bf16x4 (&va)[DT][2][2])
                        "+v"(va[1][0][1]), "+v"(va[1][1][0]), "+v"(va[1][1][1]));
 }
 
-// One 32-key tile of one wave (32 query rows): S^T = K.Q^T, tree mask, online softmax, O^T += V^T.P^T.
-// All K operands are fetched from LDS before the first MFMA and all V^T operands before the softmax, so the
-// LDS latency is paid once per phase and overlaps the arithmetic.
-template <int D>
-__device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int Lr, int l, float sl2,
-                                        const uint32_t (&anc_i)[BTV_ANC_WORDS],
-                                        const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
+// ---- the arithmetic steps of one 32-key tile of one wave (32 query rows) ---------------------------------
+// S^T = K . Q^T
+template <int DS>
+__device__ __forceinline__ f32x16 qk_tile(const u32x4 (&ka)[DS], const bf16x8 (&qreg)[DS])
 {
-    constexpr int DS = D / 16, DT = D / 32;
-    using LD = Lds<D>;
-    const int c = l & 31, h = l >> 5;
-    const unsigned char *Ks = stage, *Vs = stage + LD::TILEB;
-    bf16x8 ka[DS];
-    const int kswz = swz_k<D>(c);
+    f32x16 s;
 #pragma unroll
-    for (int s = 0; s < DS; ++s)
-        ka[s] = *reinterpret_cast<const bf16x8 *>(Ks + c * LD::ROWB + (((2 * s + h) ^ kswz) << 4));
-    // V^T operands: lane l sits in 16-lane group l/16 = 2h + dhalf; it supplies the address of key row
-    // 16mm + 8h + 4i + (l%16)/4, channels 32dt + 16dhalf + 4(l%4) .. +3, and receives keys 16mm + 8h + 4i .. +3
-    // of channel 32dt + (l%32).
-    // The reads are raw instructions: as a builtin they would make the compiler drain the whole vector-memory
-    // queue (the ring fills still in flight) in front of every tile.  lds_wait_tr() below is their counter wait.
-    bf16x4 va[DT][2][2];
-    {
-        const int dhalf = (l >> 4) & 1, rr = (l & 15) >> 2, q = l & 3;
-        const uint32_t vs_addr = (uint32_t)(uintptr_t)BTV_LDS_PTR(Vs);
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+    for (int k = 0; k < DS; ++k)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[k]), qreg[k], s, 0, 0, 0);
+    return s;
+}
+
+// largest score of the lane's query over the 32 keys (the other half of the wave holds the other 16)
+__device__ __forceinline__ float tile_max(const f32x16 &s)
+{
+    float t = s[0];
 #pragma unroll
-            for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int r = 16 * mm + 8 * h + 4 * i + rr;
-                    const int chunk = 4 * dt + 2 * dhalf + (q >> 1);
-                    va[dt][mm][i] = lds_read_tr16(vs_addr + r * LD::ROWB + ((chunk ^ swz_v<D>(r)) << 4) + ((q & 1) << 3));
-                }
-    }
-    f32x16 sacc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
-#pragma unroll
-    for (int s = 0; s < DS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], sacc, 0, 0, 0);
-    if (kb + 32 > Lr) {     // the tile touches tree rows (or the end of the sequence): apply the mask
-        uint32_t vis = vis_word(anc_i, kb, Lr);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int bit = 16 * (v >> 3) + 8 * h + (v & 7);
-            if (!((vis >> bit) & 1u)) sacc[v] = -INFINITY;
-        }
-    }
-    float tmax = sacc[0];
-#pragma unroll
-    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sacc[v]);
-    {   // the other half of the wave holds the other 16 keys of the same query
-        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
-        tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    }
-    // Lazy reference maximum: m_run only moves when the tile maximum exceeds it by more than LAZY (in log2
-    // units), so probabilities stay below 2^LAZY and the O^T / row-sum rescale is skipped on most tiles.
-    // The result is unchanged: numerator and denominator refer to the same m_run.
+    for (int v = 1; v < 16; ++v) t = fmaxf(t, s[v]);
+    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+// Lazy reference maximum: m_run only moves when the tile maximum exceeds it by more than LAZY (in log2 units),
+// so probabilities stay below 2^LAZY and the O^T / row-sum rescale is skipped on most tiles.  The result is
+// unchanged: numerator and denominator refer to the same m_run.
+template <int DT>
+__device__ __forceinline__ void lazy_rescale(float tmax, float sl2, float &m_run, float &l_run, f32x16 (&oacc)[DT])
+{
     constexpr float LAZY = 8.0f;
     const bool grow = (tmax - m_run) * sl2 > LAZY;
     if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
@@ -363,34 +382,93 @@ __device__ __forceinline__ void do_tile(const unsigned char *stage, int kb, int 
 #pragma unroll
             for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
     }
+}
+
+// P^T = exp2(S^T * sl2 - m_run * sl2) as bf16 B-operands; the row sum adds the rounded values PV uses
+// (v_dot2c_f32_bf16 against (1, 1): two probabilities per instruction).
+__device__ __forceinline__ void softmax_tile(const f32x16 &s, float sl2, float m_run, float &l_run, bf16x8 (&pb)[2])
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     const float mc = m_run * sl2;
-    float rs = 0.f;
-    float pv[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        pv[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], sl2, -mc));
-        rs += pv[v];
-    }
-    l_run += rs;
-    bf16x8 pb[2];
+    const bf16x2 ones = { (__bf16)1.0f, (__bf16)1.0f };
+    float ls[2] = { l_run, 0.f };
 #pragma unroll
     for (int mm = 0; mm < 2; ++mm)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pb[mm][e] = (__bf16)pv[mm * 8 + e];
-    lds_wait_tr<DT>(va);
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mm * 8 + e], sl2, -mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mm * 8 + e + 1], sl2, -mc));
+            const bf16x2 pp = { (__bf16)p0, (__bf16)p1 };
+            pb[mm][e] = pp[0];
+            pb[mm][e + 1] = pp[1];
+            ls[mm] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ls[mm], false);
+        }
+    l_run = ls[0] + ls[1];
+}
+
+// O^T += V^T . P^T
+template <int DT>
+__device__ __forceinline__ void pv_tile(const bf16x4 (&va)[DT][2][2], const bf16x8 (&pb)[2], f32x16 (&oacc)[DT])
+{
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+    for (int mm = 0; mm < 2; ++mm)
 #pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-            bf16x8 a = __builtin_shufflevector(va[dt][mm][0], va[dt][mm][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        for (int dt = 0; dt < DT; ++dt) {
+            const bf16x8 a = __builtin_shufflevector(va[dt][mm][0], va[dt][mm][1], 0, 1, 2, 3, 4, 5, 6, 7);
             oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[mm], oacc[dt], 0, 0, 0);
         }
+}
+
+// tree mask of a tile that touches tree rows (or the end of the sequence)
+__device__ __forceinline__ void mask_tile(f32x16 &s, uint32_t vis, int h)
+{
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int bit = 16 * (v >> 3) + 8 * h + (v & 7);
+        if (!((vis >> bit) & 1u)) s[v] = -INFINITY;
+    }
+}
+
+// One whole tile, step after step (no overlap between the steps): used for the tiles that need the mask and
+// by the workgroup shapes whose wave pairs alternate over the tiles.
+template <int D>
+__device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l, float sl2,
+                                        const uint32_t (&anc_i)[BTV_ANC_WORDS],
+                                        const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
+{
+    constexpr int DS = D / 16, DT = D / 32;
+    u32x4 ka[DS];
+    bf16x4 va[DT][2][2];
+    const uint32_t va_addr = stage + Lds<D>::TILEB + lane_v_off<D>(l);
+    lds_read_k<D>(stage + lane_k_off<D>(l), ka);
+    lds_read_vt<D, 0>(va_addr, va);
+    lds_wait_k<DS, DT * 2>(ka);          // the counter completes in order: K has landed when 2*DT reads remain
+    lds_read_vt<D, 1>(va_addr, va);
+    f32x16 s = qk_tile<DS>(ka, qreg);
+    if (kb + 32 > Lr) mask_tile(s, vis_word(anc_i, kb, Lr), l >> 5);
+    lazy_rescale<DT>(tile_max(s), sl2, m_run, l_run, oacc);
+    bf16x8 pb[2];
+    softmax_tile(s, sl2, m_run, l_run, pb);
+    lds_wait_vt<DT>(va);
+    pv_tile<DT>(va, pb, oacc);
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt range");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Wait until at most `tiles` (wave-uniform, clamped to [0, MAXT]) tiles of LPW fills each are in flight.
+template <int LPW, int MAXT> __device__ __forceinline__ void wait_tiles(int tiles)
+{
+    static_assert(MAXT * LPW < 64, "vmcnt range");
+    if constexpr (MAXT > 0) {
+        if (tiles >= MAXT) { wait_vmcnt<MAXT * LPW>(); return; }
+        wait_tiles<LPW, MAXT - 1>(tiles);
+    } else {
+        wait_vmcnt<0>();
+    }
 }
 
 // Workgroup = RW row-waves x KW key-waves; wave (rw, kw) owns query rows [32 rw, 32 rw + 32) of the block and,
@@ -402,7 +480,11 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     constexpr int WR = RW * 32;
     constexpr int DS = D / 16;
     constexpr int DT = D / 32;
-    constexpr int LPW = Lds<D>::INSTR / WAVES;
+    // Waves that issue the ring fills.  With two waves per SIMD the hardware favours the older wave of each pair,
+    // which then idles at the round's barrier: those four waves issue every fill (an issue stalls its wave for
+    // about a hundred cycles), the younger four only compute.
+    constexpr int IW = WAVES;
+    constexpr int LPW = Lds<D>::INSTR / IW;
     constexpr int AHEAD = NT - 2 * KW;            // tiles still in flight when a round's tiles have landed
     static_assert(AHEAD >= 0 && AHEAD * LPW < 64, "ring too small or too deep for the counter");
     using LD = Lds<D>;
@@ -419,6 +501,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     const int rq = bz / p.Hkv, g = bz % p.Hkv;
 #ifdef BTV_EXPERIMENT
     unsigned long long ts[8];
+    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime();
     ts[0] = __builtin_amdgcn_s_memtime();
 #define BTV_STAMP(i) ts[i] = __builtin_amdgcn_s_memtime()
 #else
@@ -435,7 +518,12 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     const int tiles = (S + 31) / 32;
     const int nsplit_r = (tiles + p.sps - 1) / p.sps;
     if (bx >= nsplit_r) return;
-    const int st0 = bx * p.sps, st1 = min(st0 + p.sps, tiles);
+    const int st0 = bx * p.sps;
+    int st1 = min(st0 + p.sps, tiles);
+    {   // tree rows past the last node of this row block are invisible to all of its rows: their tiles are dropped
+        const int node_hi = (min((by + 1) * WR, rows_g) - 1) / p.G;
+        st1 = min(st1, max((Lr + node_hi + 1 + 31) / 32, st0 + 1));
+    }
 
     // ---- this lane's query row: issue the Q loads first (raw loads; the first ring wait below covers them) ---
     const int r = by * WR + rw * 32 + c;
@@ -453,12 +541,19 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 
     // ---- start filling the ring: NT - KW tiles in flight ----------------------------------------
     const int wu = __builtin_amdgcn_readfirstlane(w);
-    const Fill<D, WAVES, PAGED> fill = make_fill<D, WAVES, PAGED>(p.K, p.V, PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr,
-                                                                  p.num_blocks, p.Hkv, g, S, wu, l);
+    const bool issuer = wu < IW;
+    const Fill<D, IW, PAGED> fill = make_fill<D, IW, PAGED>(p.K, p.V, PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr,
+                                                            p.num_blocks, p.Hkv, g, S, issuer ? wu : 0, l);
+    // KW == 1: three tiles up front (the first compute needs two), the rest of the ring fills during the first
+    // rounds; an issue holds its wave for about a hundred cycles, so a full prefill would only delay the start.
+    constexpr int PREFILL = KW == 1 ? (NT - 1 < 3 ? NT - 1 : 3) : NT - KW;
     int issued = st0, islot = 0;
 #pragma unroll
-    for (int k = 0; k < NT - KW; ++k)
-        if (issued < st1) { issue_tile<D, WAVES, PAGED>(fill, smem, islot, issued, wu); ++issued; ++islot; }
+    for (int k = 0; k < PREFILL; ++k)
+        if (issued < st1) {
+            if (issuer) issue_tile<D, IW, PAGED>(fill, smem, islot, issued, wu);
+            ++issued; ++islot;
+        }
     if (islot >= NT) islot -= NT;
     BTV_STAMP(5);
 
@@ -493,7 +588,8 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
 
     // The first round's fills are younger than the Q loads, so waiting for them also lands Q.
-    if (issued - st0 - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
+    if constexpr (KW == 1) wait_tiles<LPW, NT - 2>(issuer ? issued - st0 - 1 : 0);
+    else if (issued - st0 - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
     else wait_vmcnt<0>();
     bf16x8 qreg[DS];
 #pragma unroll
@@ -503,25 +599,102 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     }
 
     BTV_STAMP(1);
-    // ---- main loop: one barrier per round of KW tiles --------------------------------------------
-    // At the top of the round starting at tile st, tiles st+KW .. issued-1 may still be in flight.  The barrier
-    // also tells that every wave is done with the previous round, whose KW ring slots the next issues overwrite.
-    int cslot = kw;
-    for (int st = st0; st < st1; st += KW) {
-        if (issued - st - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
+    const uint32_t ring = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem);
+    if constexpr (KW == 1) {
+        // ---- main loop, one tile per round, software-pipelined --------------------------------------------
+        // Round t: wait until tiles <= t+1 have landed, barrier (which also tells that every wave is done with
+        // tile t-1, whose ring slot the next fill overwrites), issue one more tile.  Inside a round a wave
+        // overlaps the score MFMAs of tile t+1 with the softmax arithmetic of tile t, and the row maximum of
+        // tile t+1 with the PV MFMAs of tile t.
+#ifdef BTV_EXPERIMENT
+        unsigned ph_acc[4] = {0, 0, 0, 0};
+        unsigned long long ph_t = __builtin_amdgcn_s_memtime();
+#define BTV_PHASE(i) { const unsigned long long n_ = __builtin_amdgcn_s_memtime(); ph_acc[i] += (unsigned)(n_ - ph_t); ph_t = n_; }
+#else
+#define BTV_PHASE(i)
+#endif
+        auto sync_round = [&](int t) {
+            BTV_PHASE(3);                                 // compute since the last round's issue
+            wait_tiles<LPW, NT - 3>(issuer ? issued - t - 2 : 0);     // tiles t+2 .. issued-1 may still be in flight
+            BTV_PHASE(0);
+            __builtin_amdgcn_s_barrier();
+            BTV_PHASE(1);
 #pragma unroll
-        for (int k = 0; k < KW; ++k)
-            if (issued < st1) {
-                issue_tile<D, WAVES, PAGED>(fill, smem, islot, issued, wu);
-                ++issued;
-                if (++islot == NT) islot = 0;
+            for (int k = 0; k < 2; ++k)                  // two per round until the ring is full, then one
+                if (issued < st1 && issued - t < NT) {
+                    if (issuer) issue_tile<D, IW, PAGED>(fill, smem, islot, issued, wu);
+                    ++issued;
+                    if (++islot == NT) islot = 0;
+                }
+            BTV_PHASE(2);
+        };
+        const uint32_t koff = lane_k_off<D>(l), voff = LD::TILEB + lane_v_off<D>(l);
+        uint32_t cur = ring;                                     // LDS address of tile t's stage
+        u32x4 ka[DS];
+        bf16x4 va[DT][2][2];
+        bf16x8 pb[2];
+        sync_round(st0);
+        lds_read_k<D>(cur + koff, ka);
+        lds_wait_k<DS, 0>(ka);
+        f32x16 s = qk_tile<DS>(ka, qreg);
+        if (st0 * 32 + 32 > Lr) mask_tile(s, vis_word(anc_i, st0 * 32, Lr), h);
+        float tmax = tile_max(s);
+        for (int t = st0; t < st1 - 1; ++t) {
+            lazy_rescale<DT>(tmax, p.scale_log2, m_run, l_run, oacc);
+            const uint32_t nxt = (cur + LD::STAGE == ring + NT * LD::STAGE) ? ring : cur + LD::STAGE;
+            lds_read_k<D>(nxt + koff, ka);
+            lds_read_vt<D, 0>(cur + voff, va);
+            lds_wait_k<DS, DT * 2>(ka);          // the counter completes in order: K has landed when 2*DT reads remain
+            lds_read_vt<D, 1>(cur + voff, va);
+            f32x16 s2 = qk_tile<DS>(ka, qreg);
+            softmax_tile(s, p.scale_log2, m_run, l_run, pb);
+            lds_wait_vt<DT>(va);
+            pv_tile<DT>(va, pb, oacc);
+            tmax = tile_max(s2);
+            if (t * 32 + 64 > Lr) {              // tile t+1 touches tree rows (or the end of the sequence)
+                mask_tile(s2, vis_word(anc_i, t * 32 + 32, Lr), h);
+                tmax = tile_max(s2);
             }
-        if (st + kw < st1)
-            do_tile<D>(smem + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
-        cslot += KW;
-        if (cslot >= NT) cslot -= NT;
+            s = s2;
+            cur = nxt;
+            sync_round(t + 1);
+        }
+        // last tile: nothing to overlap with
+        lazy_rescale<DT>(tmax, p.scale_log2, m_run, l_run, oacc);
+        lds_read_vt<D, 0>(cur + voff, va);
+        lds_read_vt<D, 1>(cur + voff, va);
+        softmax_tile(s, p.scale_log2, m_run, l_run, pb);
+        lds_wait_vt<DT>(va);
+        pv_tile<DT>(va, pb, oacc);
+#ifdef BTV_EXPERIMENT
+        BTV_PHASE(3);
+        if (p.dbg && l == 0) {
+            unsigned long long *d = p.dbg + 64 * blockIdx.x + 8 + 4 * w;
+            for (int i = 0; i < 4; ++i) d[i] = ph_acc[i];
+        }
+#endif
+    } else {
+        // ---- main loop: one barrier per round of KW tiles, wave kw takes tile number kw of the round ------
+        // At the top of the round starting at tile st, tiles st+KW .. issued-1 may still be in flight.  The
+        // barrier also tells that every wave is done with the previous round, whose KW ring slots the next
+        // issues overwrite.
+        int cslot = kw;
+        for (int st = st0; st < st1; st += KW) {
+            if (issued - st - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int k = 0; k < KW; ++k)
+                if (issued < st1) {
+                    issue_tile<D, IW, PAGED>(fill, smem, islot, issued, wu);
+                    ++issued;
+                    if (++islot == NT) islot = 0;
+                }
+            if (st + kw < st1)
+                do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+            cslot += KW;
+            if (cslot >= NT) cslot -= NT;
+        }
     }
 
     BTV_STAMP(2);
@@ -592,10 +765,10 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     if (p.dbg && tid == 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         ts[4] = __builtin_amdgcn_s_memtime();
-        unsigned long long *d = p.dbg + 8 * blockIdx.x;
+        unsigned long long *d = p.dbg + 64 * blockIdx.x;
         for (int i = 0; i < 5; ++i) d[i] = ts[i];
         d[7] = ts[5] - ts[0]; d[6] = ts[6] - ts[5];
-        d[5] = __builtin_amdgcn_s_getreg(((4 - 1) << 11) | (0 << 6) | 20);   // XCC_ID register
+        d[5] = __builtin_amdgcn_s_memrealtime() - rt0;                        // 100 MHz ticks
     }
 #endif
 }
@@ -760,13 +933,17 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
     pl.wr = pl.rw * 32;
     pl.row_blocks = (rows_g + pl.wr - 1) / pl.wr;
     pl.stages = (L + M + TK - 1) / TK;
+    // Tiles that hold tree rows cost about 1.7 plain tiles (mask, no overlap with the next tile's scores) and all sit
+    // in the last split: sizing the splits as if there were `extra` more tiles leaves the last one that much shorter.
+    const int tree_tiles = pl.stages - L / TK;
+    const int extra = (7 * tree_tiles + 9) / 10;
     int base = Hkv * pl.row_blocks * batch;
     int target = pl.rw * pl.kw == 4 ? 512 : 256;          // two 4-wave workgroups fit a CU
     int want = g_split_override > 0 ? g_split_override : (target + base - 1) / base;
     // a split should stream at least 8 tiles (256 keys) unless the caller forces it
     if (g_split_override <= 0) want = std::min(want, std::max(1, pl.stages / 8));
     want = std::max(1, std::min(want, pl.stages));
-    pl.sps = (pl.stages + want - 1) / want;
+    pl.sps = (pl.stages + (want > 1 ? extra : 0) + want - 1) / want;
     pl.sps = (pl.sps + pl.kw - 1) / pl.kw * pl.kw;         // whole rounds of KW tiles
     pl.nsplit = (pl.stages + pl.sps - 1) / pl.sps;
     return pl;
