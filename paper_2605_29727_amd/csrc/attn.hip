@@ -918,27 +918,30 @@ unsigned long long *g_dbg = nullptr;
 
 struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 
-// Kernel shape by the number of packed rows per KV head (G*M).  Every wave owns 32 rows; few rows -> fewer
-// row-waves, and pairs of waves alternate over the tiles (KW = 2).
+// Kernel shape by the number of packed rows per KV head (G*M).  Every wave owns 32 rows.  Measured on MI355X at
+// L = 8192 (8 KV heads): what counts is one workgroup per CU and as few key splits as that allows (the split
+// partials are written and read back), so few rows get small row blocks and many rows get 128-row blocks, both
+// with pairs of waves alternating over the tiles (KW = 2).
 Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
 {
     Plan pl;
     int G = Hq / Hkv, rows_g = G * M;
-    if (rows_g <= 64) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
-    else if (rows_g <= 128) { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
-    else { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
+    if (rows_g <= 128) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
+    else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
 #ifdef BTV_EXPERIMENT
     if (g_cfg_rw) { pl.rw = g_cfg_rw; pl.kw = g_cfg_kw; pl.nt = g_cfg_nt; }
 #endif
     pl.wr = pl.rw * 32;
     pl.row_blocks = (rows_g + pl.wr - 1) / pl.wr;
     pl.stages = (L + M + TK - 1) / TK;
-    // Tiles that hold tree rows cost about 1.7 plain tiles (mask, no overlap with the next tile's scores) and all sit
-    // in the last split: sizing the splits as if there were `extra` more tiles leaves the last one that much shorter.
+    // Tiles that hold tree rows cost more than plain tiles (mask; in the pipelined loop also a second row maximum)
+    // and all sit in the last split: sizing the splits as if there were `extra` more tiles leaves the last one
+    // that much shorter.
     const int tree_tiles = pl.stages - L / TK;
-    const int extra = (7 * tree_tiles + 9) / 10;
+    const int extra = pl.kw == 1 ? (7 * tree_tiles + 9) / 10 : (tree_tiles + 3) / 4;
     int base = Hkv * pl.row_blocks * batch;
-    int target = pl.rw * pl.kw == 4 ? 512 : 256;          // two 4-wave workgroups fit a CU
+    // 64 rows or fewer: finer splits still pay; ragged batches: finer units even out the requests' lengths
+    int target = (rows_g <= 64 || batch > 1) ? 512 : 256;
     int want = g_split_override > 0 ? g_split_override : (target + base - 1) / base;
     // a split should stream at least 8 tiles (256 keys) unless the caller forces it
     if (g_split_override <= 0) want = std::min(want, std::max(1, pl.stages / 8));
@@ -995,7 +998,7 @@ int dispatch_bf16(AttnParams &p, const Plan &pl, int D, int batch, hipStream_t s
 #ifdef BTV_EXPERIMENT
     BTV_CASE(128, 2, 2, 4) BTV_CASE(128, 2, 4, 10) BTV_CASE(128, 4, 2, 10) BTV_CASE(128, 8, 1, 10) BTV_CASE(128, 4, 1, 4)
     BTV_CASE(128, 4, 1, 5) BTV_CASE(128, 2, 1, 4) BTV_CASE(128, 1, 4, 10) BTV_CASE(128, 2, 2, 8) BTV_CASE(128, 1, 2, 5)
-    BTV_CASE(128, 1, 4, 8)
+    BTV_CASE(128, 1, 4, 8) BTV_CASE(128, 4, 1, 8) BTV_CASE(128, 2, 1, 8)
 #endif
     BTV_CASE(128, 2, 2, 5) BTV_CASE(128, 4, 2, 8) BTV_CASE(128, 8, 1, 8)
     BTV_CASE(64, 2, 2, 5) BTV_CASE(64, 4, 2, 8) BTV_CASE(64, 8, 1, 8)
