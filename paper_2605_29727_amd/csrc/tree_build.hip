@@ -2,18 +2,19 @@
 //
 // Sec. 3.3 / Prop. 3.3 / Algorithm 1's frontier rule at a fixed budget N: repeatedly emit the
 // frontier prefix with the largest path score rho (Eq. 1), then push its best child and its next
-// sibling.  Two steps:
-//   1. per-position exact top-K of the marginals (K = min(V, N): a rank-j token is preceded by its
-//      j earlier siblings, so ranks >= N can never be emitted), ordered (probability desc, id asc).
-//      Keys are 64-bit  prob_bits << 32 | ~id  (probabilities are non-negative, so the bit pattern
-//      orders like the value).  Every workgroup selects the K best of 2048 keys: LDS histogram of a
-//      12-bit digit, the digit of the K-th key, compaction, and a bitonic sort of the few survivors
-//      (exchanges in registers, by DPP / lane-permute instructions, and through LDS only across
-//      waves); rounds of the same kernel then merge the per-chunk winners.
-//   2. the expansion itself: one wavefront, the top lists and the frontier in LDS, a wave-wide
-//      arg-best per emitted node.
+// sibling.  Three kernels:
+//   1. tb_thread_max   per-thread maxima of the marginals (one pass over [B, V], all CUs);
+//   2. tb_compact      a bound below which no token can be among a position's K best
+//                      (K = min(V, N): a rank-j token is preceded by its j earlier siblings, so ranks >= N can
+//                      never be emitted), and the compaction of the tokens at or above it (a second pass, served
+//                      from cache): K plus a few candidates per position;
+//   3. tb_rank_expand  workgroup k ranks the candidates of position k (order: probability desc, token id asc);
+//                      the workgroup that finishes last runs the expansion on one wavefront, the frontier in
+//                      registers.
+// Keys are 64-bit  prob_bits << 32 | ~id  (probabilities are non-negative, so the bit pattern orders like
+// the value; keys are distinct).
 // rho(child) = rho(parent) * q is one fp32 multiply (never fused), the root has rho = 1.
-// Frontier order: rho desc, depth asc, rank path lexicographic asc (ranks < 256 pack into 16 bytes).
+// Frontier order: rho desc, depth asc, rank path lexicographic asc.
 #include "btv_common.h"
 
 #include <algorithm>
@@ -22,10 +23,9 @@ namespace {
 
 typedef unsigned long long u64;
 
-constexpr int CHUNK = 2048;      // keys merged per workgroup in the later rounds (256 threads x 8)
-constexpr int CHUNK0 = 4096;     // marginals scanned per workgroup in round 0 (256 threads x 16)
 constexpr int MAXB = BTV_MAX_DEPTH;
-constexpr int BINS = 4096;       // selection histogram: 12 bits below the sign bit of the probability
+constexpr int SCAN = 8192;        // marginals scanned per workgroup (256 threads x 32)
+constexpr int CAND_CAP = 4096;    // candidate keys kept per position
 
 __device__ __forceinline__ u64 make_key(float prob, uint32_t id)
 {
@@ -34,354 +34,495 @@ __device__ __forceinline__ u64 make_key(float prob, uint32_t id)
     return ((u64)b << 32) | (u64)(0xFFFFFFFFu - id);
 }
 
-__device__ __forceinline__ int key_bin(u64 key) { return (int)((key >> 51) & (BINS - 1)); }   // float bits [30:19]
+__device__ __forceinline__ uint32_t prob_bits(float p) { return __float_as_uint(p) & 0x7FFFFFFFu; }   // -0.0 counts as 0
 
-// value of lane (lane ^ MASK), by DPP / lane-permute instructions only (no LDS traffic)
-template <int MASK>
-__device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane)
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Wave-wide maximum as a wave-uniform value: quad swaps, row mirrors, then the row maxima travel down the rows
+// (row_bcast), so that lane 63 ends up with the maximum.  The DPP operand sits on the max instruction itself;
+// lanes whose source is masked out keep their value.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-    if constexpr (MASK == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);
-    else if constexpr (MASK == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false);
-    else if constexpr (MASK == 4) {
-        const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x104, 0xF, 0xF, false);   // lane + 4
-        const uint32_t dn = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, false);   // lane - 4
-        return (lane & 4) ? dn : up;
-    } else if constexpr (MASK == 8) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, false);
-    else if constexpr (MASK == 16) {
-        auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-        return (lane & 16) ? r[0] : r[1];
-    } else {
-        static_assert(MASK == 32, "lane mask");
-        auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-        return (lane & 32) ? r[0] : r[1];
-    }
+    uint32_t out;
+    asm volatile("s_nop 1\n"
+                 "v_max_u32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n s_nop 1\n"
+                 "v_max_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n s_nop 1\n"
+                 "v_max_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n s_nop 1\n"
+                 "v_max_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n s_nop 1\n"
+                 "v_max_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n s_nop 1\n"
+                 "v_max_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n s_nop 1\n"
+                 "v_readlane_b32 %1, %0, 63"
+                 : "+v"(v), "=s"(out));
+    return out;
 }
 
-template <int MASK>
-__device__ __forceinline__ u64 lane_xor64(u64 x, int lane)
-{
-    return ((u64)lane_xor<MASK>((uint32_t)(x >> 32), lane) << 32) | lane_xor<MASK>((uint32_t)x, lane);
-}
+// ------------------------------------------------------------------------------------------------
+// Step 1: per-thread maxima.  Workgroup (chunk, row) scans elements chunk*SCAN .. chunk*SCAN + SCAN - 1 of the
+// row; thread t looks at elements 4t..4t+3 of every 1024 and keeps the largest probability it saw:
+// part[row][chunk][t].
+// ------------------------------------------------------------------------------------------------
+struct TbCounters { int cnt[MAXB]; int done; };
 
-template <int EPT, int J>
-__device__ __forceinline__ void inthread_step(u64 (&x)[EPT], int tid, int k)
+template <typename F>
+__device__ __forceinline__ void scan_chunk(const float *src, bool aligned, int V, int chunk, int tid, F f)
 {
 #pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        const int p = i ^ J;
-        if (p > i) {
-            const bool desc = (((tid * EPT + i) & k) == 0);
-            const u64 a = x[i], b = x[p];
-            const bool sw = (a < b) == desc;
-            x[i] = sw ? b : a;
-            x[p] = sw ? a : b;
+    for (int j = 0; j < SCAN / 1024; ++j) {
+        const int v0 = chunk * SCAN + j * 1024 + tid * 4;        // coalesced: a wave reads 1 KiB per load
+        if (aligned && v0 + 4 <= V) {
+            const float4 a = *reinterpret_cast<const float4 *>(src + v0);
+            f(a.x, v0); f(a.y, v0 + 1); f(a.z, v0 + 2); f(a.w, v0 + 3);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (v0 + i < V) f(src[v0 + i], v0 + i);
         }
     }
 }
 
-template <int EPT, int TJ>
-__device__ __forceinline__ void wave_step(u64 (&x)[EPT], int tid, bool keep_max)
+__global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, int chunks, uint32_t *part, TbCounters *ctr)
 {
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) {
-        const u64 o = lane_xor64<TJ>(x[i], tid & 63);
-        x[i] = ((x[i] < o) == keep_max) ? o : x[i];      // keys are distinct (or both padding)
+    const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y;
+    const float *src = marg + (size_t)row * V;
+    const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
+    uint32_t mx = 0;
+    scan_chunk(src, aligned, V, chunk, tid, [&](float p, int) { mx = umax(mx, prob_bits(p)); });
+    part[((size_t)row * chunks + chunk) * 256 + tid] = mx;
+    if (chunk == 0 && tid == 0) {                              // the later kernels start after this one has ended
+        ctr->cnt[row] = 0;
+        if (row == 0) ctr->done = 0;
     }
 }
 
-// Descending bitonic sort of 256*EPT keys by 256 threads; thread t holds elements EPT*t .. EPT*t+EPT-1 in x[].
-// `lds` has room for 256*EPT keys.
-template <int EPT>
-__device__ __forceinline__ void sort_desc(u64 (&x)[EPT], u64 *lds, int tid)
+// ------------------------------------------------------------------------------------------------
+// Step 2: the bound and the candidates.  Every per-thread maximum is a different token of the row, so the K-th
+// largest of them (K <= 256 <= their number) is a lower bound of the row's K-th largest probability, and a tight
+// one: it only falls short by the few tokens of the K best that share a thread with a better one.  Every
+// workgroup finds the 12-bit bin (sign-less float bits [30:19]: an eighth of a binade) that holds it, from a
+// histogram of the chunks*256 values, and takes the lower edge of that bin as the bound; then it appends the keys
+// of its chunk at or above the bound to the row's candidate list (unordered): K plus a few candidates per row.
+// cnt[row] counts the candidates; a count above CAND_CAP (heavily tied or otherwise degenerate probabilities)
+// tells tb_rank_expand to select from the row itself.
+// ------------------------------------------------------------------------------------------------
+constexpr int TBINS = 4096;
+
+__global__ __launch_bounds__(256) void tb_compact(const float *marg, int V, int chunks, int K, const uint32_t *part,
+                                                  TbCounters *ctr, u64 *cand)
 {
-    constexpr int NKEYS = 256 * EPT;
-#pragma unroll 1
-    for (int k = 2; k <= NKEYS; k <<= 1) {
-#pragma unroll 1
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            if (j < EPT) {
-                // both elements live in this thread
-                if (EPT > 8 && j == 8) inthread_step<EPT, 8>(x, tid, k);
-                else if (EPT > 4 && j == 4) inthread_step<EPT, 4>(x, tid, k);
-                else if (EPT > 2 && j == 2) inthread_step<EPT, 2>(x, tid, k);
-                else inthread_step<EPT, 1>(x, tid, k);
-            } else {
-                const int tj = j / EPT;                                   // partner thread = tid ^ tj
-                const bool lower = (tid & tj) == 0;
-                const bool desc = ((tid * EPT) & k) == 0;                 // same for all elements of the thread here
-                const bool keep_max = lower == desc;
-                if (tj == 1) wave_step<EPT, 1>(x, tid, keep_max);
-                else if (tj == 2) wave_step<EPT, 2>(x, tid, keep_max);
-                else if (tj == 4) wave_step<EPT, 4>(x, tid, keep_max);
-                else if (tj == 8) wave_step<EPT, 8>(x, tid, keep_max);
-                else if (tj == 16) wave_step<EPT, 16>(x, tid, keep_max);
-                else if (tj == 32) wave_step<EPT, 32>(x, tid, keep_max);
-                else {
-                    __syncthreads();
+    __shared__ u64 keys[1024];
+    __shared__ int hist[TBINS];
+    __shared__ int wsum[4];
+    __shared__ int sel_s, ncand_s, base_s;
+    const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y, lane = tid & 63, w = tid >> 6;
+    const float *src = marg + (size_t)row * V;
+    const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
+    const uint32_t *pr = part + (size_t)row * chunks * 256 + tid;
+    {
+        uint32_t pv[16];                                       // the loads are in flight while the histogram is cleared
 #pragma unroll
-                    for (int i = 0; i < EPT; ++i) lds[i * 256 + tid] = x[i];      // element-major: conflict-free
-                    __syncthreads();
+        for (int j = 0; j < 16; ++j) pv[j] = j < chunks ? pr[(size_t)j * 256] : 0xFFFFFFFFu;
 #pragma unroll
-                    for (int i = 0; i < EPT; ++i) {
-                        const u64 o = lds[i * 256 + (tid ^ tj)];
-                        x[i] = ((x[i] < o) == keep_max) ? o : x[i];
+        for (int b = 0; b < TBINS / 256; ++b) hist[b * 256 + tid] = 0;
+        if (tid == 0) ncand_s = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 16; ++j) if (pv[j] != 0xFFFFFFFFu) atomicAdd(&hist[pv[j] >> 19], 1);
+        for (int j = 16; j < chunks; ++j) atomicAdd(&hist[pr[(size_t)j * 256] >> 19], 1);
+        __syncthreads();
+        int hb[16], own = 0;                                   // thread t owns bins 16t .. 16t+15
+#pragma unroll
+        for (int b = 0; b < 16; ++b) { hb[b] = hist[tid * 16 + b]; own += hb[b]; }
+        int suf = own;                                         // inclusive suffix sum over the higher threads
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_down(suf, off);
+            if (lane + off < 64) suf += o;
+        }
+        if (lane == 0) wsum[w] = suf;
+        __syncthreads();
+        int above = suf - own;
+        for (int ww = w + 1; ww < 4; ++ww) above += wsum[ww];
+        if (above < K && above + own >= K) {
+            int cum = above, sel = tid * 16;
+#pragma unroll
+            for (int b = 15; b >= 0; --b) {
+                if (cum < K && cum + hb[b] >= K) sel = tid * 16 + b;
+                cum += hb[b];
+            }
+            sel_s = sel;
+        }
+        __syncthreads();
+    }
+    const uint32_t tau = (uint32_t)sel_s << 19;
+    scan_chunk(src, aligned, V, chunk, tid, [&](float p, int v) {
+        if (prob_bits(p) >= tau) {
+            const int pos = atomicAdd(&ncand_s, 1);
+            if (pos < 1024) keys[pos] = make_key(p, (uint32_t)v);
+        }
+    });
+    __syncthreads();
+    const int total = ncand_s;
+    // More than 1024 candidates in one chunk only happen when the bound is useless (ties): the row is then marked
+    // as overflowed.
+    if (tid == 0) base_s = atomicAdd(&ctr->cnt[row], total <= 1024 ? total : CAND_CAP + 1);
+    __syncthreads();
+    const int base = base_s;
+    if (total <= 1024)
+        for (int i = tid; i < total && base + i < CAND_CAP; i += 256) cand[(size_t)row * CAND_CAP + base + i] = keys[i];
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 3, part A: wavefront `row` ranks the candidates of its position and writes the K best into LDS.
+// Usual case (at most SELCAP candidates): every candidate is ranked by counting the candidates above it.
+// Otherwise the K-th largest key is found first by radix selection, one byte of the key per pass (histogram of
+// 256 bins per wavefront), over the candidate list or, when that overflowed, over the row of marginals itself;
+// the K keys at or above it are then ranked the same way.
+// ------------------------------------------------------------------------------------------------
+constexpr int SELCAP = 512;
+
+struct RankLds {                            // ranking of one position
+    u64 sel[SELCAP];
+    int hist[256];
+    int nsel;
+    int last;
+};
+
+struct ExpandLds {                          // the expansion
+    float q[MAXB * BTV_MAX_NODES];          // q[k*KP + r]: probability of rank r at position k
+    uint32_t tok[MAXB * BTV_MAX_NODES];     // its token id
+    uint2 n_rec[BTV_MAX_NODES];             // emitted nodes: (meta, bits of rho)
+};
+
+// sel[0..n): distinct keys; those of rank < K (rank = number of keys above) go to q_row / tok_row (global).
+// Threads tid, tid + nthreads, ... take one key each.
+__device__ __forceinline__ void rank_keys(const u64 *sel, int n, int K, int KP, float *q_row, uint32_t *tok_row, int tid, int nthreads)
+{
+    for (int i0 = 0; i0 < n; i0 += 2 * nthreads) {            // two keys per thread at a time
+        u64 mine[2];
+        int rank[2] = { 0, 0 };
+#pragma unroll
+        for (int c = 0; c < 2; ++c) mine[c] = i0 + c * nthreads + tid < n ? sel[i0 + c * nthreads + tid] : ~0ull;
+        for (int j = 0; j < n; ++j) {
+            const u64 kj = sel[j];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) rank[c] += kj > mine[c] ? 1 : 0;
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            if (i0 + c * nthreads + tid < n && rank[c] < K) {
+                q_row[rank[c]] = __uint_as_float((uint32_t)(mine[c] >> 32));
+                tok_row[rank[c]] = 0xFFFFFFFFu - (uint32_t)mine[c];
+            }
+    }
+    for (int i = K + tid; i < KP; i += nthreads) { q_row[i] = 0.f; tok_row[i] = 0u; }
+}
+
+template <typename ForEach>
+__device__ __forceinline__ u64 wave_kth_largest(ForEach for_each, int K, int *hist, int lane)
+{
+    u64 prefix = 0;
+    int krem = K;
+    for (int byte = 7; byte >= 0; --byte) {
+        *reinterpret_cast<int4 *>(&hist[lane * 4]) = make_int4(0, 0, 0, 0);
+        __builtin_amdgcn_wave_barrier();
+        const int sh = 8 * byte;
+        for_each([&](u64 key) {
+            if (byte == 7 || (key >> (sh + 8)) == (prefix >> (sh + 8))) atomicAdd(&hist[(int)((key >> sh) & 255)], 1);
+        });
+        __builtin_amdgcn_wave_barrier();
+        const int4 h = *reinterpret_cast<const int4 *>(&hist[lane * 4]);
+        const int own = h.x + h.y + h.z + h.w;
+        int suf = own;                         // inclusive suffix sum over the higher lanes
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_down(suf, off);
+            if (lane + off < 64) suf += o;
+        }
+        const int above = suf - own;
+        int sel = 0, kn = 0;
+        const bool here = above < krem && above + own >= krem;
+        if (here) {
+            int cum = above;
+            const int hb[4] = { h.x, h.y, h.z, h.w };
+#pragma unroll
+            for (int b = 3; b >= 0; --b) {
+                if (kn == 0 && cum + hb[b] >= krem) { sel = lane * 4 + b; kn = krem - cum; }
+                cum += hb[b];
+            }
+        }
+        const int srcl = __builtin_ctzll(__builtin_amdgcn_ballot_w64(here));
+        sel = __builtin_amdgcn_readlane(sel, srcl);
+        krem = __builtin_amdgcn_readlane(kn, srcl);
+        prefix |= (u64)sel << sh;
+        __builtin_amdgcn_wave_barrier();
+    }
+    return prefix;
+}
+
+template <typename ForEach>
+__device__ __forceinline__ void wave_select_rank(ForEach for_each, int K, int KP, int *hist, u64 *sel, int *nsel, float *q_row,
+                                                 uint32_t *tok_row, int lane)
+{
+    const u64 kth = wave_kth_largest(for_each, K, hist, lane);
+    if (lane == 0) *nsel = 0;
+    __builtin_amdgcn_wave_barrier();
+    for_each([&](u64 key) {
+        if (key >= kth) {
+            const int pos = atomicAdd(nsel, 1);
+            if (pos < SELCAP) sel[pos] = key;                  // exactly K keys: they are distinct
+        }
+    });
+    __builtin_amdgcn_wave_barrier();
+    rank_keys(sel, K, K, KP, q_row, tok_row, lane, 64);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 3, part B: the expansion, one wavefront, the frontier in registers.
+// A single wavefront issues an instruction every few cycles at best, so the loop is written for few instructions
+// per emitted node rather than for parallel work.
+// A frontier entry stands for "the children of one node, from rank r on".  The entry for the children of node i
+// lives in slot i + 1 (slot 0: the children of the root), slot s = lane s % 64 of register row s / 64; slots are
+// never reused, so no search for a free one is needed and the parent of an entry is its slot number minus one.
+// Per entry: key = bits(rho of rank r) + 1 (0 = empty or exhausted), rho of the parent, dr = depth | r << 5,
+// qa = LDS address of the probability of rank r + 1, and qn = that probability (every lane re-reads qn after
+// every pop: one gather, whose latency is off the critical path because qn is used one pop later at the
+// earliest).  Popping an entry emits (parent, depth, r) and advances the entry in place to rank r + 1 (the next
+// sibling); the emitted node's own children become the entry of the next slot.
+// Order of emission: rho desc, depth asc, rank path lexicographic asc.  The wave maximum of the keys decides
+// almost always; on ties the depth decides, then the rank paths, rebuilt by walking the parents of the tied
+// entries through the emitted nodes.
+// ------------------------------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, int N, int lane, int32_t *parent, int32_t *token,
+                                            int32_t *depth, float *rho, int32_t *n_out, float *ahat)
+{
+    const float *q_s = S.q;
+    const uint32_t q_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)q_s;
+    const uint32_t qa_last = q_base + 4u * (uint32_t)(B * KP - 1);
+    const int first_sib = K > 1 ? 1 : 0;                       // rank of a new entry's second token (clamped: unused if K == 1)
+    const float qfirst = lane < B ? q_s[lane * KP] : 0.f;      // lane k: probability of the best token at position k
+    uint32_t e_key[R], e_dr[R], e_qa[R];
+    float e_prho[R], e_qn[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) { e_key[r] = 0u; e_dr[r] = 0u; e_prho[r] = 0.f; e_qn[r] = 0.f; e_qa[r] = q_base; }
+    if (lane == 0) {       // slot 0: the children of the root
+        e_key[0] = __float_as_uint(__fmul_rn(1.0f, q_s[0])) + 1u;
+        e_qa[0] = q_base + 4u * first_sib;
+        e_qn[0] = q_s[first_sib];
+        e_prho[0] = 1.0f;
+        e_dr[0] = 1u;
+    }
+    int n = 0;
+    double a = 1.0;                  // the surrogate is summed in fp64 and rounded once
+    while (n < N) {
+        uint32_t lm = e_key[0];
+#pragma unroll
+        for (int r = 1; r < R; ++r) lm = umax(lm, e_key[r]);
+        const uint32_t m = wave_max_u32(lm);
+        if (m == 0u) break;                                   // frontier empty: the lattice is exhausted
+        u64 al[R];
+        int cnt = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) { al[r] = __builtin_amdgcn_ballot_w64(e_key[r] == m); cnt += __builtin_popcountll(al[r]); }
+        if (cnt > 1) {
+            // ties on rho: shallower first ...
+            uint32_t cl = 0u;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if ((al[r] >> lane) & 1ull) cl = umax(cl, 0x100u - (e_dr[r] & 31u));
+            const uint32_t cm = wave_max_u32(cl);
+            cnt = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && 0x100u - (e_dr[r] & 31u) == cm);
+                cnt += __builtin_popcountll(al[r]);
+            }
+            if (cnt > 1) {
+                // ... then the smaller rank path: one byte per position, first position in the most significant
+                // byte of word 0; the walk reads the emitted ancestors from LDS
+                uint32_t path[R][4];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) path[r][w] = 0u;
+                    if ((al[r] >> lane) & 1ull) {
+                        uint32_t mm = e_dr[r];
+                        int node = r * 64 + lane - 1;          // the entry's parent
+                        while (true) {
+                            const int pos = (int)(mm & 31u) - 1, sh = 24 - 8 * (pos & 3);
+                            const uint32_t byte = ((mm >> 5) & 255u) << sh;
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) if (w == (pos >> 2)) path[r][w] |= byte;
+                            if (node < 0) break;
+                            mm = S.n_rec[node].x;
+                            node = (int)(mm >> 13) - 1;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    if (cnt <= 1) break;
+                    uint32_t pl = 0u;
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        if ((al[r] >> lane) & 1ull) pl = umax(pl, ~path[r][w]);
+                    const uint32_t pm = wave_max_u32(pl);
+                    cnt = 0;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && ~path[r][w] == pm);
+                        cnt += __builtin_popcountll(al[r]);
                     }
                 }
             }
         }
-    }
-}
-
-// One workgroup selects, in order, the KP largest of up to 256*EPT keys (EPT per thread, 0 = padding):
-// histogram of a 12-bit digit -> the digit of the KP-th largest key -> compaction of the keys at or above that
-// digit -> a bitonic sort of just those (512 slots when they fit, else all 256*EPT, which always fits).
-// Round 0 (EPT = 16, from marginals): keys come from chunk `blockIdx.x` of row `blockIdx.y` of the marginals.
-// Later rounds (EPT = 8): the keys are `per` lists of KP winners of the previous round.
-template <int EPT, bool FROM_MARGINALS>
-__global__ __launch_bounds__(256) void topk_round(const float *marg, int V, const u64 *in, int lists, int KP, u64 *out)
-{
-    constexpr int NKEYS = 256 * EPT;
-    __shared__ u64 lds[NKEYS];            // candidates, then sort exchange buffer
-    __shared__ int hist[BINS];
-    __shared__ int wsum[4];
-    __shared__ int sel_bin, ncand;
-    const int tid = threadIdx.x, grp = blockIdx.x, row = blockIdx.y, lane = tid & 63, w = tid >> 6;
-    u64 x[EPT];
-    if (FROM_MARGINALS) {
-        const float *src = marg + (size_t)row * V;
-        const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
+        int wr = 0;
 #pragma unroll
-        for (int q4 = 0; q4 < EPT / 4; ++q4) {
-            const int v0 = grp * NKEYS + q4 * 1024 + tid * 4;        // coalesced: a wave reads 1 KiB per load
-            if (aligned && v0 + 4 <= V) {
-                const float4 a = *reinterpret_cast<const float4 *>(src + v0);
-                x[q4 * 4 + 0] = make_key(a.x, v0); x[q4 * 4 + 1] = make_key(a.y, v0 + 1);
-                x[q4 * 4 + 2] = make_key(a.z, v0 + 2); x[q4 * 4 + 3] = make_key(a.w, v0 + 3);
-            } else {
+        for (int r = R - 1; r >= 1; --r) if (al[r] != 0ull) wr = r;
+        if (al[0] != 0ull) wr = 0;
+        u64 alw = al[0];
+        uint32_t s_dr = e_dr[0];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) x[q4 * 4 + i] = v0 + i < V ? make_key(src[v0 + i], (uint32_t)(v0 + i)) : 0ull;
+        for (int r = 1; r < R; ++r)
+            if (r == wr) { alw = al[r]; s_dr = e_dr[r]; }
+        const int wl = __builtin_ctzll(alw);
+        const uint32_t u_dr = __builtin_amdgcn_readlane(s_dr, wl);
+        const float u_rho = __uint_as_float(m - 1u);
+        const int d = u_dr & 31u, rank = (u_dr >> 5) & 255u;
+        // emit node n: every lane stores the same record (no lane selection needed)
+        S.n_rec[n] = make_uint2(u_dr | ((uint32_t)(wr * 64 + wl) << 13), m - 1u);      // parent + 1 = the entry's slot
+        a += (double)u_rho;
+        // the entry moves on to the next sibling, in its own lane
+        const bool has_next = rank + 1 < K;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (r == wr) {                                     // wave-uniform
+                const bool me = lane == wl;
+                const uint32_t nk = has_next ? __float_as_uint(__fmul_rn(e_prho[r], e_qn[r])) + 1u : 0u;
+                e_key[r] = me ? nk : e_key[r];
+                e_dr[r] += me ? 32u : 0u;
+                const uint32_t na = e_qa[r] + (me ? 4u : 0u);
+                e_qa[r] = na < qa_last ? na : qa_last;         // clamped: unused when there is no rank + 2
             }
-        }
-    } else {
-        const int per = NKEYS / KP;
-        const int first = grp * per, cnt = min(per, lists - first);
-        const u64 *src = in + ((size_t)row * lists + first) * KP;
+        // the emitted node's children: the entry of slot n + 1
+        if (d < B && n + 1 < N) {
+            const int cs = n + 1;
+            const float q_child = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qfirst), d));
+            const uint32_t key_child = __float_as_uint(__fmul_rn(u_rho, q_child)) + 1u;
+            const uint32_t qa_child = q_base + 4u * (uint32_t)(d * KP + first_sib);
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) x[i] = i * 256 + tid < cnt * KP ? src[i * 256 + tid] : 0ull;
-    }
-    // ---- histogram of the digit ------------------------------------------------------------------------
-    for (int b = tid; b < BINS; b += 256) hist[b] = 0;
-    if (tid == 0) { ncand = 0; sel_bin = 0; }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < EPT; ++i) atomicAdd(&hist[key_bin(x[i])], 1);
-    __syncthreads();
-    // ---- digit of the KP-th largest key: thread t owns bins 16t .. 16t+15; suffix sums over threads ----------
-    int own = 0;
-#pragma unroll
-    for (int b = 0; b < 16; ++b) own += hist[tid * 16 + b];
-    int suf = own;                         // inclusive suffix sum within the wave (over higher lanes)
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_down(suf, off);
-        if (lane + off < 64) suf += o;
-    }
-    if (lane == 0) wsum[w] = suf;
-    __syncthreads();
-    int above = suf - own;                 // keys in bins owned by higher threads
-    for (int ww = w + 1; ww < 4; ++ww) above += wsum[ww];
-    if (above < KP && above + own >= KP) {
-        int cum = above;
-        for (int b = 15; b >= 0; --b) {
-            const int hb = hist[tid * 16 + b];
-            if (cum + hb >= KP) { sel_bin = tid * 16 + b; break; }
-            cum += hb;
-        }
-    }
-    __syncthreads();
-    // ---- compaction of the keys at or above that digit -----------------------------------------------------
-    const int tb = sel_bin;
-#pragma unroll
-    for (int i = 0; i < EPT; ++i)
-        if (key_bin(x[i]) >= tb) lds[atomicAdd(&ncand, 1)] = x[i];
-    __syncthreads();
-    const int nc = ncand;
-    u64 *dst = out + ((size_t)row * gridDim.x + grp) * KP;
-    if (nc <= 512) {
-        u64 y[2];
-        y[0] = 2 * tid < nc ? lds[2 * tid] : 0ull;
-        y[1] = 2 * tid + 1 < nc ? lds[2 * tid + 1] : 0ull;
-        __syncthreads();
-        sort_desc<2>(y, lds, tid);
-        if (2 * tid < KP) dst[2 * tid] = y[0];
-        if (2 * tid + 1 < KP) dst[2 * tid + 1] = y[1];
-    } else {
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) x[i] = tid * EPT + i < nc ? lds[tid * EPT + i] : 0ull;
-        __syncthreads();
-        sort_desc<EPT>(x, lds, tid);
-#pragma unroll
-        for (int i = 0; i < EPT; ++i)
-            if (tid * EPT + i < KP) dst[tid * EPT + i] = x[i];
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Expansion: one wavefront.  top[k*KP + r] = key of rank r at position k (0 where V < KP).
-// ------------------------------------------------------------------------------------------------
-struct Cand {
-    float rho;
-    int depth, parent, rank;
-    uint32_t path[4];         // rank bytes, first rank in the most significant byte of path[0]
-};
-
-__device__ __forceinline__ bool cand_before(const Cand &a, const Cand &b)
-{
-    if (a.rho != b.rho) return a.rho > b.rho;
-    if (a.depth != b.depth) return a.depth < b.depth;
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-        if (a.path[w] != b.path[w]) return a.path[w] < b.path[w];
-    return false;
-}
-
-__global__ __launch_bounds__(64) void bestfirst_expand(const u64 *top, int B, int K, int KP, int N, int32_t *parent,
-                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat)
-{
-    constexpr int CAP = BTV_MAX_NODES + 2;
-    __shared__ float q_s[MAXB * BTV_MAX_NODES];   // probability of rank r at position k: q_s[k*KP + r]
-    __shared__ float f_rho[CAP];
-    __shared__ int f_meta[CAP];                   // depth | rank << 8 | (parent + 1) << 16
-    __shared__ uint32_t f_path[CAP][4];
-    __shared__ float n_rho[BTV_MAX_NODES];
-    __shared__ int n_meta[BTV_MAX_NODES];         // (depth - 1) * KP + rank of emitted node: index of its token in `top`
-    __shared__ int n_parent[BTV_MAX_NODES], n_depth[BTV_MAX_NODES];   // outputs are staged: no global store in the loop
-    const int lane = threadIdx.x;
-    for (int e = lane; e < B * KP; e += 64) q_s[e] = __uint_as_float((uint32_t)(top[e] >> 32));
-    if (lane == 0) {
-        f_meta[0] = 1;
-        f_path[0][0] = f_path[0][1] = f_path[0][2] = f_path[0][3] = 0u;
-    }
-    __syncthreads();
-    if (lane == 0) f_rho[0] = __fmul_rn(1.0f, q_s[0]);
-    __syncthreads();
-    int nf = 1, n = 0;
-    float a = 1.0f;
-    while (n < N && nf > 0) {
-        // lane-local best over entries lane, lane+64, ...
-        Cand best; int bj = -1;
-        best.rho = -1.f; best.depth = 0; best.parent = 0; best.rank = 0;
-        best.path[0] = best.path[1] = best.path[2] = best.path[3] = 0u;
-        for (int j = lane; j < nf; j += 64) {
-            Cand cnd;
-            cnd.rho = f_rho[j];
-            const int mt = f_meta[j];
-            cnd.depth = mt & 0xFF; cnd.rank = (mt >> 8) & 0xFF; cnd.parent = (mt >> 16) - 1;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) cnd.path[w] = f_path[j][w];
-            if (bj < 0 || cand_before(cnd, best)) { best = cnd; bj = j; }
-        }
-        // wave-wide best.  Primary key (rho desc, depth asc) as one 64-bit maximum; the rank path only decides
-        // when several lanes tie on it, which is rare.
-        const u64 pk = bj < 0 ? 0ull : (((u64)__float_as_uint(best.rho) << 32) | (u64)(0x100 - best.depth) << 8 | 1ull);
-        u64 mx = pk;
-        { u64 o;
-          o = lane_xor64<1>(mx, lane); mx = o > mx ? o : mx;   o = lane_xor64<2>(mx, lane); mx = o > mx ? o : mx;
-          o = lane_xor64<4>(mx, lane); mx = o > mx ? o : mx;   o = lane_xor64<8>(mx, lane); mx = o > mx ? o : mx;
-          o = lane_xor64<16>(mx, lane); mx = o > mx ? o : mx;  o = lane_xor64<32>(mx, lane); mx = o > mx ? o : mx; }
-        const u64 tied = __builtin_amdgcn_ballot_w64(pk == mx);
-        int src = __builtin_ctzll(tied);
-        if (__builtin_popcountll(tied) > 1) {
-            // lexicographic minimum of the rank paths among the tied lanes, word by word
-            u64 alive = tied;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                uint32_t v = ((alive >> lane) & 1ull) ? best.path[w] : 0xFFFFFFFFu;
-                uint32_t mn = v;
-                for (int off = 32; off >= 1; off >>= 1) { const uint32_t o = __shfl_xor(mn, off); mn = o < mn ? o : mn; }
-                alive &= __builtin_amdgcn_ballot_w64(v == mn && ((alive >> lane) & 1ull));
-            }
-            src = __builtin_ctzll(alive);
-        }
-        Cand u;    // broadcast of lane `src` (wave-uniform index: scalar lane reads)
-        u.rho = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(best.rho), src));
-        u.depth = __builtin_amdgcn_readlane(best.depth, src); u.parent = __builtin_amdgcn_readlane(best.parent, src);
-        u.rank = __builtin_amdgcn_readlane(best.rank, src);
-#pragma unroll
-        for (int w = 0; w < 4; ++w) u.path[w] = __builtin_amdgcn_readlane(best.path[w], src);
-        bj = __builtin_amdgcn_readlane(bj, src);
-        const bool has_child = u.depth < B, has_sib = u.rank + 1 < K;
-        if (lane == 0) {
-            n_rho[n] = u.rho;
-            n_meta[n] = (u.depth - 1) * KP + u.rank;
-            n_parent[n] = u.parent;
-            n_depth[n] = u.depth;
-            // the emitted entry's slot takes the child (or the sibling, or the last entry)
-            int slot = bj;
-            if (has_child) {
-                f_rho[slot] = __fmul_rn(u.rho, q_s[u.depth * KP]);
-                f_meta[slot] = (u.depth + 1) | (0 << 8) | ((n + 1) << 16);
-                // path unchanged: the child's own rank byte is 0
-                slot = nf;
-            }
-            if (has_sib) {
-                const float prho = u.parent < 0 ? 1.0f : n_rho[u.parent];
-                f_rho[slot] = __fmul_rn(prho, q_s[(u.depth - 1) * KP + u.rank + 1]);
-                f_meta[slot] = u.depth | ((u.rank + 1) << 8) | ((u.parent + 1) << 16);
-                const int pos = u.depth - 1, wd = pos >> 2, sh = 24 - 8 * (pos & 3);
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    uint32_t pw = u.path[w];
-                    if (w == wd) pw = (pw & ~(0xFFu << sh)) | ((uint32_t)(u.rank + 1) << sh);
-                    f_path[slot][w] = pw;
+            for (int r = 0; r < R; ++r)
+                if (r == (cs >> 6)) {                          // wave-uniform
+                    const bool me = lane == (cs & 63);
+                    e_key[r] = me ? key_child : e_key[r];
+                    e_prho[r] = me ? u_rho : e_prho[r];
+                    e_dr[r] = me ? (uint32_t)(d + 1) : e_dr[r];
+                    e_qa[r] = me ? qa_child : e_qa[r];
                 }
-            }
-            if (!has_child && !has_sib && bj != nf - 1) {
-                f_rho[bj] = f_rho[nf - 1]; f_meta[bj] = f_meta[nf - 1];
-#pragma unroll
-                for (int w = 0; w < 4; ++w) f_path[bj][w] = f_path[nf - 1][w];
-            }
         }
-        a += u.rho;
-        nf += (has_child ? 1 : 0) + (has_sib ? 1 : 0) - 1;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            e_qn[r] = *reinterpret_cast<const __attribute__((address_space(3))) float *>((uintptr_t)e_qa[r]);
         ++n;
-        __syncthreads();
     }
-    // token ids of the emitted nodes, read from the top lists in parallel
     for (int i = lane; i < n; i += 64) {
-        token[i] = (int32_t)(0xFFFFFFFFu - (uint32_t)top[n_meta[i]]);
-        parent[i] = n_parent[i];
-        if (depth) depth[i] = n_depth[i];
-        if (rho) rho[i] = n_rho[i];
+        const uint2 rec = S.n_rec[i];
+        const int dd = rec.x & 31u, rk = (rec.x >> 5) & 255u;
+        token[i] = (int32_t)S.tok[(dd - 1) * KP + rk];
+        parent[i] = (int32_t)(rec.x >> 13) - 1;
+        if (depth) depth[i] = dd;
+        if (rho) rho[i] = __uint_as_float(rec.y);
     }
     if (lane == 0) {
         *n_out = n;
-        if (ahat) *ahat = a;
+        if (ahat) *ahat = (float)a;
     }
+}
+
+// Workgroup `row` ranks the candidates of its position into top_q / top_tok (global, [B][KP]); the workgroup that
+// finishes last then runs the expansion on its first wavefront.
+__global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, int B, int K, int KP, int N, TbCounters *ctr,
+                                                      const u64 *cand, float *top_q, uint32_t *top_tok, int32_t *parent,
+                                                      int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                                                      unsigned long long *dbg)
+{
+    __shared__ RankLds RL;
+    __shared__ ExpandLds S;
+    const unsigned long long t0_ = __builtin_amdgcn_s_memtime();
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), row = blockIdx.x;
+    const int nc = ctr->cnt[row];
+    float *q_row = top_q + (size_t)row * KP;
+    uint32_t *tok_row = top_tok + (size_t)row * KP;
+    if (nc <= SELCAP) {
+        const u64 *src = cand + (size_t)row * CAND_CAP;
+        for (int j = tid; j < nc; j += 256) RL.sel[j] = src[j];
+        __syncthreads();
+        rank_keys(RL.sel, nc, K, KP, q_row, tok_row, tid, 256);
+    } else if (w == 0) {                       // rare: one wavefront selects the K best first
+        if (nc <= CAND_CAP) {
+            const u64 *src = cand + (size_t)row * CAND_CAP;
+            wave_select_rank([&](auto f) { for (int j = lane; j < nc; j += 64) f(src[j]); },
+                             K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
+        } else {
+            const float *src = marg + (size_t)row * V;
+            wave_select_rank([&](auto f) { for (int v = lane; v < V; v += 64) f(make_key(src[v], (uint32_t)v)); },
+                             K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
+        }
+    }
+    // ---- the workgroup that finishes last expands -------------------------------------------------------------
+    const unsigned long long tr_ = __builtin_amdgcn_s_memtime();
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) RL.last = atomicAdd(&ctr->done, 1) == B - 1;
+    __syncthreads();
+    if (!RL.last) return;
+    const unsigned long long ta_ = __builtin_amdgcn_s_memtime();
+    __threadfence();
+    for (int e = tid; e < B * KP; e += 256) {
+        S.q[e] = __builtin_nontemporal_load(top_q + e);
+        S.tok[e] = __builtin_nontemporal_load(top_tok + e);
+    }
+    __syncthreads();
+    if (w != 0) return;
+    const unsigned long long t1_ = __builtin_amdgcn_s_memtime();
+    if (dbg && lane == 0) { dbg[0] = t1_ - t0_; dbg[2] = tr_ - t0_; dbg[3] = ta_ - tr_; }
+    if (N <= 64) expand_wave<1>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat);
+    else if (N <= 128) expand_wave<2>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat);
+    else expand_wave<4>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat);
+    if (dbg && lane == 0) dbg[1] = __builtin_amdgcn_s_memtime() - t1_;
 }
 
 int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 
-struct TopkPlan { int K, KP, chunks; size_t buf_keys; };
+struct TopkPlan { int K, KP, chunks; size_t part_bytes, cand_bytes, top_bytes; };
 
 TopkPlan topk_plan(int B, int V, int N)
 {
     TopkPlan t;
     t.K = std::min(V, N);
     t.KP = std::max(next_pow2(t.K), 1);
-    t.chunks = (V + CHUNK0 - 1) / CHUNK0;
-    t.buf_keys = (size_t)B * t.chunks * t.KP;
+    t.chunks = (V + SCAN - 1) / SCAN;
+    t.part_bytes = btv_align_up((size_t)B * t.chunks * 256 * 4, BTV_WS_ALIGN);
+    t.cand_bytes = btv_align_up((size_t)B * CAND_CAP * 8, BTV_WS_ALIGN);
+    t.top_bytes = btv_align_up((size_t)B * t.KP * 4, BTV_WS_ALIGN);
     return t;
 }
+
+unsigned long long *g_tb_dbg = nullptr;   // phase cycle counts of tb_finish_expand (experiment builds set it)
 
 }  // namespace
 
 extern "C" {
 
+#ifdef BTV_EXPERIMENT
+void btv_exp_tb_dbg(unsigned long long *p) { g_tb_dbg = p; }
+#endif
+
 size_t btv_tree_build_workspace(int B, int V, int N)
 {
     if (B < 1 || B > MAXB || V < 1 || N < 1 || N > BTV_MAX_NODES) return 0;
     TopkPlan t = topk_plan(B, V, N);
-    return BTV_WS_HEADER + 2 * btv_align_up(t.buf_keys * 8, BTV_WS_ALIGN);
+    return BTV_WS_HEADER + t.part_bytes + t.cand_bytes + 2 * t.top_bytes;
 }
 
 int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
@@ -395,22 +536,19 @@ int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent,
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     TopkPlan t = topk_plan(B, V, N);
-    size_t half = btv_align_up(t.buf_keys * 8, BTV_WS_ALIGN);
-    u64 *bufA = reinterpret_cast<u64 *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
-    u64 *bufB = reinterpret_cast<u64 *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + half);
-    hipLaunchKernelGGL((topk_round<16, true>), dim3(t.chunks, B), dim3(256), 0, st, marginals, V, nullptr, 0, t.KP, bufA);
+    unsigned char *base = static_cast<unsigned char *>(ws);
+    static_assert(sizeof(TbCounters) + 64 <= BTV_WS_HEADER, "counters live in the workspace header");
+    TbCounters *ctr = reinterpret_cast<TbCounters *>(base + 64);
+    uint32_t *part = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER);
+    u64 *cand = reinterpret_cast<u64 *>(base + BTV_WS_HEADER + t.part_bytes);
+    hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, part, ctr);
     BTV_HIP(hipGetLastError());
-    int lists = t.chunks;
-    const int per = CHUNK / t.KP;
-    while (lists > 1) {
-        int groups = (lists + per - 1) / per;
-        hipLaunchKernelGGL((topk_round<8, false>), dim3(groups, B), dim3(256), 0, st, nullptr, 0, bufA, lists, t.KP, bufB);
-        BTV_HIP(hipGetLastError());
-        std::swap(bufA, bufB);
-        lists = groups;
-    }
-    hipLaunchKernelGGL(bestfirst_expand, dim3(1), dim3(64), 0, st, bufA, B, t.K, t.KP, N, parent, token, depth, rho,
-                       n_out, ahat);
+    hipLaunchKernelGGL(tb_compact, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, t.K, part, ctr, cand);
+    BTV_HIP(hipGetLastError());
+    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes);
+    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes + t.top_bytes);
+    hipLaunchKernelGGL(tb_rank_expand, dim3(B), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, ctr, cand, top_q, top_tok, parent,
+                       token, depth, rho, n_out, ahat, g_tb_dbg);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

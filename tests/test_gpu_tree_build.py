@@ -67,3 +67,19 @@ def test_tiny_scores_keep_their_bits(G, oracle):
     marg = np.full((16, 4), 1e-3, dtype=np.float32)
     marg[:, 0] = 3e-3
     _check(G, oracle, marg, 256)
+
+
+def test_more_candidates_than_the_selection_keeps(G, oracle):
+    """Rows whose probabilities tie heavily, or grow with the token id, defeat the cheap bound of the top-K
+    selection (most of the row stays a candidate): the exact byte-wise selection must take over."""
+    V = 20000
+    uniform = np.full((3, V), 1.0 / V, dtype=np.float32)                         # every key ties on the probability
+    ramp = np.tile(np.arange(1, V + 1, dtype=np.float64), (2, 1))                 # best tokens at the highest ids
+    ramp = (ramp / ramp.sum(axis=1, keepdims=True)).astype(np.float32)
+    steps = np.repeat(np.arange(1, 6, dtype=np.float64), V // 5)[None, :]        # five plateaus of 4000 equal values
+    steps = np.tile(steps / steps.sum(), (4, 1)).astype(np.float32)
+    mixed = synth.marginals(91, 4, V, 2.0)
+    mixed[1] = uniform[0]                                                         # only one row takes the slow path
+    for marg in (uniform, ramp, steps, mixed):
+        for N in (7, 64, 256):
+            _check(G, oracle, marg, N)
