@@ -188,9 +188,9 @@ struct RankLds {                            // ranking of one position
 };
 
 struct ExpandLds {                          // the expansion
-    float q[MAXB * BTV_MAX_NODES];          // q[k*KP + r]: probability of rank r at position k
+    float q[MAXB * BTV_MAX_NODES + 64];     // q[k*KP + r]: probability of rank r at position k (+ padding: q[..][r+1] is
+                                            // fetched, not used, also for the last rank of the last position)
     uint32_t tok[MAXB * BTV_MAX_NODES];     // its token id
-    uint2 n_rec[BTV_MAX_NODES];             // emitted nodes: (meta, bits of rho)
 };
 
 // sel[0..n): distinct keys; those of rank < K (rank = number of keys above) go to q_row / tok_row (global).
@@ -283,11 +283,12 @@ __device__ __forceinline__ void wave_select_rank(ForEach for_each, int K, int KP
 // A frontier entry stands for "the children of one node, from rank r on".  The entry for the children of node i
 // lives in slot i + 1 (slot 0: the children of the root), slot s = lane s % 64 of register row s / 64; slots are
 // never reused, so no search for a free one is needed and the parent of an entry is its slot number minus one.
-// Per entry: key = bits(rho of rank r) + 1 (0 = empty or exhausted), rho of the parent, dr = depth | r << 5,
-// qa = LDS address of the probability of rank r + 1, and qn = that probability (every lane re-reads qn after
-// every pop: one gather, whose latency is off the critical path because qn is used one pop later at the
-// earliest).  Popping an entry emits (parent, depth, r) and advances the entry in place to rank r + 1 (the next
-// sibling); the emitted node's own children become the entry of the next slot.
+// Per entry: key = bits(rho of rank r) + 1 (0 = empty or exhausted), rho of the parent, x = LDS address of
+// q[depth-1][r] (depth and r are read back from it: KP is a power of two), and qn = q[depth-1][r+1], the
+// probability of the next sibling (every lane re-reads qn after every pop: one gather, whose latency is off the
+// critical path because qn is used one pop later at the earliest).  Popping an entry emits (parent, depth, r)
+// and advances the entry in place to rank r + 1; the emitted node's own children become the entry of the next
+// slot.  Emitted node i is kept in lane i % 64 of row i / 64 as rec = index of q[depth-1][r] | slot << 13.
 // Order of emission: rho desc, depth asc, rank path lexicographic asc.  The wave maximum of the keys decides
 // almost always; on ties the depth decides, then the rank paths, rebuilt by walking the parents of the tied
 // entries through the emitted nodes.
@@ -298,22 +299,18 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 {
     const float *q_s = S.q;
     const uint32_t q_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)q_s;
-    const uint32_t qa_last = q_base + 4u * (uint32_t)(B * KP - 1);
-    const int first_sib = K > 1 ? 1 : 0;                       // rank of a new entry's second token (clamped: unused if K == 1)
+    const int lg = 31 - __builtin_clz((unsigned)KP);           // KP = 1 << lg
     const float qfirst = lane < B ? q_s[lane * KP] : 0.f;      // lane k: probability of the best token at position k
-    uint32_t e_key[R], e_dr[R], e_qa[R];
-    float e_prho[R], e_qn[R];
+    uint32_t e_key[R], e_x[R], o_rec[R];
+    float e_prho[R], e_qn[R], o_rho[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) { e_key[r] = 0u; e_dr[r] = 0u; e_prho[r] = 0.f; e_qn[r] = 0.f; e_qa[r] = q_base; }
+    for (int r = 0; r < R; ++r) { e_key[r] = 0u; e_prho[r] = 0.f; e_qn[r] = 0.f; e_x[r] = q_base; o_rec[r] = 0u; o_rho[r] = 0.f; }
     if (lane == 0) {       // slot 0: the children of the root
         e_key[0] = __float_as_uint(__fmul_rn(1.0f, q_s[0])) + 1u;
-        e_qa[0] = q_base + 4u * first_sib;
-        e_qn[0] = q_s[first_sib];
+        e_qn[0] = q_s[1];                                      // padding when K == 1: never used
         e_prho[0] = 1.0f;
-        e_dr[0] = 1u;
     }
     int n = 0;
-    double a = 1.0;                  // the surrogate is summed in fp64 and rounded once
     while (n < N) {
         uint32_t lm = e_key[0];
 #pragma unroll
@@ -325,38 +322,49 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 #pragma unroll
         for (int r = 0; r < R; ++r) { al[r] = __builtin_amdgcn_ballot_w64(e_key[r] == m); cnt += __builtin_popcountll(al[r]); }
         if (cnt > 1) {
-            // ties on rho: shallower first ...
+            // ties on rho: shallower first (x grows with the depth) ...
             uint32_t cl = 0u;
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                if ((al[r] >> lane) & 1ull) cl = umax(cl, 0x100u - (e_dr[r] & 31u));
+                if ((al[r] >> lane) & 1ull) cl = umax(cl, 0x100u - ((e_x[r] - q_base) >> (2 + lg)));
             const uint32_t cm = wave_max_u32(cl);
             cnt = 0;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && 0x100u - (e_dr[r] & 31u) == cm);
+                al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && 0x100u - ((e_x[r] - q_base) >> (2 + lg)) == cm);
                 cnt += __builtin_popcountll(al[r]);
             }
             if (cnt > 1) {
                 // ... then the smaller rank path: one byte per position, first position in the most significant
-                // byte of word 0; the walk reads the emitted ancestors from LDS
+                // byte of word 0; the walk fetches the emitted ancestors from the lanes that hold them
                 uint32_t path[R][4];
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
 #pragma unroll
                     for (int w = 0; w < 4; ++w) path[r][w] = 0u;
-                    if ((al[r] >> lane) & 1ull) {
-                        uint32_t mm = e_dr[r];
-                        int node = r * 64 + lane - 1;          // the entry's parent
-                        while (true) {
-                            const int pos = (int)(mm & 31u) - 1, sh = 24 - 8 * (pos & 3);
-                            const uint32_t byte = ((mm >> 5) & 255u) << sh;
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {                  // every lane walks, tied or not: the fetches are wave-wide
+                    uint32_t idx = (e_x[r] - q_base) >> 2;     // index of q[depth-1][rank]
+                    int node = r * 64 + lane - 1;              // the entry's parent
+                    bool live = (al[r] >> lane) & 1ull;
+                    while (__builtin_amdgcn_ballot_w64(live) != 0ull) {
+                        const int pos = (int)(idx >> lg), sh = 24 - 8 * (pos & 3);
+                        const uint32_t byte = (idx & (uint32_t)(KP - 1)) << sh;
+                        if (live) {
 #pragma unroll
                             for (int w = 0; w < 4; ++w) if (w == (pos >> 2)) path[r][w] |= byte;
-                            if (node < 0) break;
-                            mm = S.n_rec[node].x;
-                            node = (int)(mm >> 13) - 1;
                         }
+                        live = live && node >= 0;
+                        const int src = node >= 0 ? node : 0;
+                        uint32_t rec = 0u;
+#pragma unroll
+                        for (int rr = 0; rr < R; ++rr) {
+                            const uint32_t got = (uint32_t)__shfl((int)o_rec[rr], src & 63);
+                            if (rr == (src >> 6)) rec = got;
+                        }
+                        idx = rec & 0x1FFFu;
+                        node = (int)(rec >> 13) - 1;
                     }
                 }
 #pragma unroll
@@ -381,17 +389,25 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
         for (int r = R - 1; r >= 1; --r) if (al[r] != 0ull) wr = r;
         if (al[0] != 0ull) wr = 0;
         u64 alw = al[0];
-        uint32_t s_dr = e_dr[0];
+        uint32_t s_x = e_x[0];
 #pragma unroll
         for (int r = 1; r < R; ++r)
-            if (r == wr) { alw = al[r]; s_dr = e_dr[r]; }
+            if (r == wr) { alw = al[r]; s_x = e_x[r]; }
         const int wl = __builtin_ctzll(alw);
-        const uint32_t u_dr = __builtin_amdgcn_readlane(s_dr, wl);
+        const uint32_t u_idx = (__builtin_amdgcn_readlane(s_x, wl) - q_base) >> 2;
         const float u_rho = __uint_as_float(m - 1u);
-        const int d = u_dr & 31u, rank = (u_dr >> 5) & 255u;
-        // emit node n: every lane stores the same record (no lane selection needed)
-        S.n_rec[n] = make_uint2(u_dr | ((uint32_t)(wr * 64 + wl) << 13), m - 1u);      // parent + 1 = the entry's slot
-        a += (double)u_rho;
+        const int d = (int)(u_idx >> lg) + 1, rank = u_idx & (uint32_t)(KP - 1);
+        // emit node n into its lane
+        {
+            const uint32_t rec = u_idx | ((uint32_t)(wr * 64 + wl) << 13);     // parent + 1 = the entry's slot
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == (n >> 6)) {                           // wave-uniform
+                    const bool me = lane == (n & 63);
+                    o_rec[r] = me ? rec : o_rec[r];
+                    o_rho[r] = me ? u_rho : o_rho[r];
+                }
+        }
         // the entry moves on to the next sibling, in its own lane
         const bool has_next = rank + 1 < K;
 #pragma unroll
@@ -400,42 +416,46 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
                 const bool me = lane == wl;
                 const uint32_t nk = has_next ? __float_as_uint(__fmul_rn(e_prho[r], e_qn[r])) + 1u : 0u;
                 e_key[r] = me ? nk : e_key[r];
-                e_dr[r] += me ? 32u : 0u;
-                const uint32_t na = e_qa[r] + (me ? 4u : 0u);
-                e_qa[r] = na < qa_last ? na : qa_last;         // clamped: unused when there is no rank + 2
+                e_x[r] += me ? 4u : 0u;
             }
-        // the emitted node's children: the entry of slot n + 1
-        if (d < B && n + 1 < N) {
+        // the emitted node's children: the entry of slot n + 1 (a slot past the last row is simply not written)
+        if (d < B) {
             const int cs = n + 1;
             const float q_child = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qfirst), d));
             const uint32_t key_child = __float_as_uint(__fmul_rn(u_rho, q_child)) + 1u;
-            const uint32_t qa_child = q_base + 4u * (uint32_t)(d * KP + first_sib);
+            const uint32_t x_child = q_base + ((uint32_t)d << (2 + lg));
 #pragma unroll
             for (int r = 0; r < R; ++r)
                 if (r == (cs >> 6)) {                          // wave-uniform
                     const bool me = lane == (cs & 63);
                     e_key[r] = me ? key_child : e_key[r];
                     e_prho[r] = me ? u_rho : e_prho[r];
-                    e_dr[r] = me ? (uint32_t)(d + 1) : e_dr[r];
-                    e_qa[r] = me ? qa_child : e_qa[r];
+                    e_x[r] = me ? x_child : e_x[r];
                 }
         }
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            e_qn[r] = *reinterpret_cast<const __attribute__((address_space(3))) float *>((uintptr_t)e_qa[r]);
+            e_qn[r] = *reinterpret_cast<const __attribute__((address_space(3))) float *>((uintptr_t)(e_x[r] + 4u));
         ++n;
     }
-    for (int i = lane; i < n; i += 64) {
-        const uint2 rec = S.n_rec[i];
-        const int dd = rec.x & 31u, rk = (rec.x >> 5) & 255u;
-        token[i] = (int32_t)S.tok[(dd - 1) * KP + rk];
-        parent[i] = (int32_t)(rec.x >> 13) - 1;
-        if (depth) depth[i] = dd;
-        if (rho) rho[i] = __uint_as_float(rec.y);
+    double a = 0.0;                  // the surrogate: summed in fp64 and rounded once
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = r * 64 + lane;
+        if (i < n) {
+            const uint32_t idx = o_rec[r] & 0x1FFFu;
+            token[i] = (int32_t)S.tok[idx];
+            parent[i] = (int32_t)(o_rec[r] >> 13) - 1;
+            if (depth) depth[i] = (int)(idx >> lg) + 1;
+            if (rho) rho[i] = o_rho[r];
+            a += (double)o_rho[r];
+        }
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off);
     if (lane == 0) {
         *n_out = n;
-        if (ahat) *ahat = (float)a;
+        if (ahat) *ahat = (float)(1.0 + a);
     }
 }
 
