@@ -774,14 +774,15 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 }
 
 // Split-K combine: O[row] = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e).
-// 8 rows per workgroup, 32 lanes per row, each lane owns D/32 consecutive channels.  The (m, l) pairs of all
-// splits are fetched by the row's lanes in parallel and the partial rows are read in batches of independent
-// loads, so the kernel costs a few memory round trips whatever the number of splits.
+// 8 rows per workgroup, 32 lanes per row, each lane owns D/32 consecutive channels.  Lane j of a row fetches the
+// (m, l) pairs of splits j, j + 32, ... and computes their weights (handed to the other lanes by shuffles); the
+// partial rows of up to 32 splits are fetched by independent loads issued before anything is waited for, so the
+// kernel costs about one memory round trip whatever the number of splits.
 template <int D, bool PAGED>
 __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
 {
     constexpr int E = D / 32;
-    constexpr int BATCH = 8;
+    typedef float fvec __attribute__((ext_vector_type(E)));
     const int rq = blockIdx.y;
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) return;
@@ -791,37 +792,48 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
     const int lr = blockIdx.x * 8 + (threadIdx.x >> 5), lane = threadIdx.x & 31;
     if (lr >= rq_.M * p.Hq) return;
     const size_t row = (size_t)rq_.q0 * p.Hq + lr;
-    // per-split weights: lane j handles splits j, j+32, ...
+    const size_t sstride = (size_t)p.total_rows;
+    // reference maximum over all splits: with more than 32 of them it takes a round trip of its own
     float mmax = NEG_BIG;
-    for (int s = lane; s < nsplit_r; s += 32) mmax = fmaxf(mmax, p.ML[((size_t)s * p.total_rows + row) * 2]);
-    for (int off = 16; off >= 1; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 32));
-    float den = 0.f;
-    for (int s = lane; s < nsplit_r; s += 32) {
-        float2 ml = *reinterpret_cast<const float2 *>(p.ML + ((size_t)s * p.total_rows + row) * 2);
-        den += __builtin_amdgcn_exp2f((ml.x - mmax) * p.scale_log2) * ml.y;
-    }
-    for (int off = 16; off >= 1; off >>= 1) den += __shfl_xor(den, off, 32);
+    for (int s = lane + 32; s < nsplit_r; s += 32) mmax = fmaxf(mmax, p.ML[(s * sstride + row) * 2]);
     float acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.f;
-    for (int s0 = 0; s0 < nsplit_r; s0 += BATCH) {
-        float part[BATCH][E], mm[BATCH];
+    float den = 0.f;
+    for (int s0 = 0; s0 < nsplit_r; s0 += 32) {     // one pass for up to 32 splits
+        const int s_mine = s0 + lane;
+        const float2 ml = s_mine < nsplit_r ? *reinterpret_cast<const float2 *>(p.ML + (s_mine * sstride + row) * 2)
+                                            : make_float2(NEG_BIG, 0.f);
+        fvec part[32];
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int s = min(s0 + b, nsplit_r - 1);
-            const size_t pr = (size_t)s * p.total_rows + row;
-            mm[b] = p.ML[pr * 2];
-            const float *src = p.Opart + pr * D + lane * E;
+        for (int g = 0; g < 4; ++g)
+            if (s0 + 8 * g < nsplit_r) {             // uniform within the row's lanes: whole groups of 8 loads
 #pragma unroll
-            for (int e = 0; e < E; ++e) part[b][e] = src[e];
+                for (int b = 0; b < 8; ++b) {
+                    const int s = min(s0 + 8 * g + b, nsplit_r - 1);
+                    part[8 * g + b] = *reinterpret_cast<const fvec *>(p.Opart + (s * sstride + row) * D + lane * E);
+                }
+            }
+        if (s0 == 0) {
+            mmax = fmaxf(mmax, ml.x);
+#pragma unroll
+            for (int off = 16; off >= 1; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 32));
         }
+        const float w = s_mine < nsplit_r ? __builtin_amdgcn_exp2f((ml.x - mmax) * p.scale_log2) : 0.f;
+        den += w * ml.y;
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const float wgt = s0 + b < nsplit_r ? __builtin_amdgcn_exp2f((mm[b] - mmax) * p.scale_log2) : 0.f;
+        for (int g = 0; g < 4; ++g)
+            if (s0 + 8 * g < nsplit_r) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] += wgt * part[b][e];
-        }
+                for (int b = 0; b < 8; ++b) {
+                    const float wgt = __shfl(w, 8 * g + b, 32);      // 0 for splits past the last
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[e] += wgt * part[8 * g + b][e];
+                }
+            }
     }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) den += __shfl_xor(den, off, 32);
     const float inv = 1.0f / den;
     uint16_t *dst = static_cast<uint16_t *>(p.O) + row * D + lane * E;
     if (E == 4) {
