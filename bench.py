@@ -27,6 +27,19 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 RING_BYTES = 640 << 20        # > 2x the 256 MB Infinity Cache
 
 
+def measured_traffic(L, N):
+    """HBM bytes per tree_verify_attn call from the committed profiler summary (counter runs cannot be made from
+    inside this script); None when there is no summary for this workload."""
+    path = os.path.join(ROOT, "profiles", f"tree_verify_attn_L{L}_N{N}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_call:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def algorithmic_bytes(L, N, Hq, Hkv, D, e=2):
     return 2 * (L + N) * Hkv * D * e + 2 * N * Hq * D * e + 4 * N
 
@@ -134,6 +147,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the N in {16..256} latency curve")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-attn", action="store_true", help="time only tree_verify_attn (for profiler runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run plain 256 MiB device copies instead (to scale the profiler's HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1", file=sys.stderr)
@@ -147,6 +162,16 @@ def main():
         sys.exit(3)
     btv.lib()    # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        nbytes = 256 << 20
+        bufs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(i) for i in range(5)]   # > Infinity Cache
+        torch.cuda.synchronize()
+        for i in range(args.steps):
+            bufs[(i + 1) % 5].copy_(bufs[i % 5])
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "copies": args.steps}))
+        return
 
     Hq, Hkv, D, B, V, L, N = 32, 8, 128, 16, 128256, args.L, args.N
     w = synth.c3(N, sharp=True)
@@ -191,7 +216,7 @@ def main():
     fl = algorithmic_flops(L, N, Hq, D, path.depth_sum)
     gbps = ab / (attn_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(L, N),
                 "kernel": "tree_verify_attn (tv_attn_bf16 + tv_combine_bf16 + anc_mask_kernel)",
                 "algorithmic_bytes": ab, "us_per_launch": round(attn_ms * 1e3, 3),
                 "us_in_step": round(attn_ms_in_step * 1e3, 3), "us_warm_cache": round(attn_warm_ms * 1e3, 3),
