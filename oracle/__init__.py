@@ -37,6 +37,8 @@ def _load():
         _lib.orc_accept_stochastic.restype = C.c_int
         _lib.orc_num_threads.restype = C.c_int
         _lib.orc_ancestor_mask.restype = C.c_int
+        _lib.orc_tree_build_adaptive.restype = C.c_int
+        _lib.orc_verify_cost.restype = None
     return _lib
 
 
@@ -72,6 +74,35 @@ def tree_build(marg: np.ndarray, N: int) -> dict:
         raise ValueError("orc_tree_build: bad arguments")
     return {"n": n, "parent": parent[:n], "token": token[:n], "depth": depth[:n], "rank": rank[:n],
             "rho": rho[:n], "ahat": ahat.value}
+
+
+def tree_build_adaptive(marg: np.ndarray, N_max: int, cost, L_AR: float) -> dict:
+    """Algorithm 1 with its early stop: cost[N-1] = estimated cycle latency at budget N (Sec. 3.4, Eq. 6)."""
+    marg = np.ascontiguousarray(marg, dtype=np.float32)
+    cost = np.ascontiguousarray(cost, dtype=np.float64)
+    assert len(cost) >= N_max
+    B, V = marg.shape
+    parent = np.empty(max(N_max, 1), dtype=np.int32)
+    token = np.empty_like(parent); depth = np.empty_like(parent); rank = np.empty_like(parent)
+    rho = np.empty(max(N_max, 1), dtype=np.float32)
+    ahat, sbest, margin = C.c_double(0.0), C.c_double(0.0), C.c_double(0.0)
+    n = _load().orc_tree_build_adaptive(_p(marg, C.c_float), B, V, N_max, _p(cost, C.c_double), C.c_double(L_AR),
+                                        _p(parent, C.c_int32), _p(token, C.c_int32), _p(depth, C.c_int32),
+                                        _p(rho, C.c_float), _p(rank, C.c_int32), C.byref(ahat), C.byref(sbest),
+                                        C.byref(margin))
+    if n < 0:
+        raise ValueError("orc_tree_build_adaptive: bad arguments")
+    return {"n": n, "parent": parent[:n], "token": token[:n], "depth": depth[:n], "rank": rank[:n], "rho": rho[:n],
+            "ahat": ahat.value, "s_best": sbest.value, "margin": margin.value}
+
+
+def verify_cost(s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale=1.0,
+                calib_offset=0.0) -> dict:
+    """App. E cost model: FLOPs, bytes, roofline time and calibrated latency of one verifier pass."""
+    out = (C.c_double * 4)()
+    _load().orc_verify_cost(*[C.c_double(float(x)) for x in (s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops,
+                                                              bandwidth, calib_scale, calib_offset)], out)
+    return {"flops": out[0], "bytes": out[1], "roofline_s": out[2], "latency_s": out[3]}
 
 
 def tree_attn(Qf, Kf, Vf, parent, L: int, scale: float | None = None, pairs=None, block_table=None, page: int = 16,

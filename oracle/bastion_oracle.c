@@ -13,6 +13,9 @@
  * Pins (tests/, run with -m "not gpu"):
  *   orc_tree_build       brute-force enumeration of all prefixes (Prop. 3.3), closed forms,
  *                        Monte-Carlo self-verification (Prop. 3.2)
+ *   orc_tree_build_adaptive  exhaustive argmax of the estimated speedup over all budgets on concave/convex
+ *                        inputs (Prop. 3.4), prefix property against orc_tree_build, hand-made cost curves
+ *   orc_verify_cost      the per-module tables of App. E summed by hand for a small configuration
  *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
  *   orc_ancestor_mask    reachability by explicit path enumeration
  *   orc_accept_greedy    brute force over all root-to-node paths, planted paths
@@ -87,17 +90,22 @@ static int cand_before(const cand_t *a, const cand_t *b, const int32_t *parent, 
     return 0;
 }
 
-/* Returns the number of nodes emitted (= N unless the lattice has fewer prefixes), or -1 on bad arguments.
- * parent[i] = -1 for children of the root; depth is 1-based; rank[i] = sibling rank of node i. */
-int orc_tree_build(const float *marg, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
-                   float *rho, int32_t *rank, double *ahat)
+/* Core of both builders.  cost == NULL: fixed budget N.  Otherwise Algorithm 1 with its early stop (Sec. 3.4,
+ * Eq. 6): after popping the N-th node u, Ahat <- Ahat + rho(u) and S <- Ahat * L_AR / cost[N-1], where cost[N-1]
+ * is the estimated cycle latency C(N) = T_draft + T_aux + T_verify(N) supplied by the caller; the node is kept
+ * if S exceeds the best S so far (strictly), otherwise the loop ends and the tree without u is returned.
+ * All of this in fp64.  s_best: best estimated speedup (-inf when no node was kept); margin: the smallest
+ * relative distance |S - S*| / |S| over all comparisons made (how close any decision was to flipping). */
+static int tree_build_core(const float *marg, int B, int V, int N, const double *cost, double L_AR, int32_t *parent,
+                           int32_t *token, int32_t *depth, float *rho, int32_t *rank, double *ahat, double *s_best,
+                           double *margin)
 {
     if (B < 1 || B > 64 || V < 1 || N < 0) return -1;
     int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * V);
     cand_t *front = (cand_t *)malloc(sizeof(cand_t) * (size_t)(N + 2));
     orc_rank_tokens(marg, B, V, order);
     int nf = 0, n = 0;
-    double a = 1.0;
+    double a = 1.0, sb = -INFINITY, mg = INFINITY;
     /* the root's best child */
     front[nf++] = (cand_t){ 1.0f * marg[order[0]], 1, -1, 0 };
     while (n < N && nf > 0) {
@@ -106,6 +114,15 @@ int orc_tree_build(const float *marg, int B, int V, int N, int32_t *parent, int3
             if (cand_before(&front[j], &front[best], parent, rank, depth, B)) best = j;
         cand_t u = front[best];
         front[best] = front[--nf];
+        if (cost) {
+            double s = (a + (double)u.rho) * L_AR / cost[n];
+            if (sb > -INFINITY) {
+                double rel = fabs(s - sb) / fmax(fabs(s), 1e-300);
+                if (rel < mg) mg = rel;
+            }
+            if (!(s > sb)) break;
+            sb = s;
+        }
         parent[n] = u.parent; rank[n] = u.rank; depth[n] = u.depth; rho[n] = u.rho;
         token[n] = order[(size_t)(u.depth - 1) * V + u.rank];
         a += (double)u.rho;
@@ -124,8 +141,59 @@ int orc_tree_build(const float *marg, int B, int V, int N, int32_t *parent, int3
         ++n;
     }
     if (ahat) *ahat = a;
+    if (s_best) *s_best = sb;
+    if (margin) *margin = mg;
     free(order); free(front);
     return n;
+}
+
+/* Returns the number of nodes emitted (= N unless the lattice has fewer prefixes), or -1 on bad arguments.
+ * parent[i] = -1 for children of the root; depth is 1-based; rank[i] = sibling rank of node i. */
+int orc_tree_build(const float *marg, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
+                   float *rho, int32_t *rank, double *ahat)
+{
+    return tree_build_core(marg, B, V, N, NULL, 0.0, parent, token, depth, rho, rank, ahat, NULL, NULL);
+}
+
+/* Algorithm 1: budget chosen online, at most N_max nodes.  cost[0..N_max-1] > 0.  Returns N*. */
+int orc_tree_build_adaptive(const float *marg, int B, int V, int N_max, const double *cost, double L_AR,
+                            int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *rank,
+                            double *ahat, double *s_best, double *margin)
+{
+    if (!cost || !(L_AR > 0.0)) return -1;
+    for (int i = 0; i < N_max; ++i)
+        if (!(cost[i] > 0.0)) return -1;
+    return tree_build_core(marg, B, V, N_max, cost, L_AR, parent, token, depth, rho, rank, ahat, s_best, margin);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Verifier cost model (App. E): FLOPs and memory traffic of one target forward pass over s newly
+ * verified tokens with c cached tokens, as the sums of the per-module entries of the appendix's two
+ * tables (a multiply-accumulate counts 2 FLOPs; elementwise work is left out; non-fused attention,
+ * so the score matrix counts as activation traffic), the roofline time
+ *     R = max(FLOPs / peak_flops, Bytes / bandwidth)
+ * and the statically calibrated estimate  T = calib_scale * R + calib_offset  (Sec. 3.4: "a linear
+ * calibration").  hq = nq*d, hkv = nkv*d.  out[0] = FLOPs, out[1] = Bytes, out[2] = R, out[3] = T.
+ * ---------------------------------------------------------------------------------------- */
+void orc_verify_cost(double s, double c, double layers, double h, double nq, double nkv, double d, double hffn,
+                     double V, double bp, double peak_flops, double bandwidth, double calib_scale,
+                     double calib_offset, double *out)
+{
+    double hq = nq * d, hkv = nkv * d;
+    /* FLOPs per layer, module by module */
+    double f_qproj = 2 * s * h * hq, f_kvproj = 4 * s * h * hkv, f_scores = 2 * s * (c + s) * hq;
+    double f_pv = 2 * s * (c + s) * hq, f_oproj = 2 * s * hq * h, f_gateup = 4 * s * h * hffn, f_down = 2 * s * hffn * h;
+    double f_lmhead = 2 * s * h * V;
+    double flops = layers * (f_qproj + f_kvproj + f_scores + f_pv + f_oproj + f_gateup + f_down) + f_lmhead;
+    /* traffic in elements, module by module */
+    double w_embed_lm = V * h + h * V, w_attn = 2 * h * hq + 2 * h * hkv, w_ffn = 3 * h * hffn;
+    double kv_read = 2 * c * hkv, kv_write = 2 * s * hkv;
+    double a_attn = 2 * s * h + 4 * s * hq + 2 * s * hkv + 2 * nq * s * (c + s), a_ffn = 2 * s * h + 4 * s * hffn;
+    double a_lm = s * h + s * V;
+    double bytes = bp * (w_embed_lm + layers * (w_attn + w_ffn) + layers * (kv_read + kv_write) +
+                         layers * (a_attn + a_ffn) + a_lm);
+    double r = fmax(flops / peak_flops, bytes / bandwidth);
+    out[0] = flops; out[1] = bytes; out[2] = r; out[3] = calib_scale * r + calib_offset;
 }
 
 /* ------------------------------------------------------------------------------------------
