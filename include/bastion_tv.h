@@ -70,6 +70,39 @@ int btv_tree_build(const float *marginals, int B, int V, int N,
                    int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * tree_build_adaptive -- Algorithm 1 with its early stop: the budget is chosen online (Sec. 3.4,
+ * Eq. 6, Prop. 3.4).  Same expansion and outputs as btv_tree_build with N = N_max, but after the
+ * N-th node is popped the estimated speedup  S(N) = Ahat(T_N) * L_AR / C(N)  is compared with the
+ * best so far: the node is kept while S strictly improves, and the tree before the first
+ * non-improvement is returned (*n_out = N*).  The first node is always kept.
+ *   cost   [N_max] fp64 DEVICE: cost[N-1] = C(N) = T_draft + T_aux + T_verify(N), the estimated
+ *          latency of one cycle at budget N, any unit, positive and finite (btv_verify_cost gives
+ *          the T_verify term).  A non-positive or NaN entry stops the expansion there and raises
+ *          the data flag (btv_workspace_status).
+ *   L_AR   HOST: latency of one autoregressive target step, same unit, > 0.
+ *   s_best [1] fp64 DEVICE, optional: S(N*).
+ * The comparison is made in fp64 as  Ahat(N) * C(N*) > Ahat(N*) * C(N)  (no division per node).
+ * Workspace: btv_tree_build_workspace(B, V, N_max).
+ * ------------------------------------------------------------------------------------------- */
+int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, const double *cost,
+                            double L_AR, int32_t *parent, int32_t *token, int32_t *depth, float *rho,
+                            int32_t *n_out, float *ahat, double *s_best, void *ws, size_t ws_bytes,
+                            void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * verify_cost -- HOST function, no GPU work: the verifier cost model of App. E.  FLOPs and
+ * memory traffic of one target forward pass over s newly verified tokens with c cached tokens
+ * (non-fused attention: the score matrix counts as activation traffic; elementwise work is
+ * left out), the roofline time R = max(FLOPs / peak_flops, Bytes / bandwidth) and the
+ * statically calibrated estimate calib_scale * R + calib_offset (Sec. 3.4).
+ *   layers, h (hidden), nq, nkv (heads), d (head dim), hffn, V (vocabulary), bp (bytes/element)
+ *   out [4] HOST: FLOPs, Bytes, R, calibrated latency.  Returns BTV_OK or BTV_EINVAL.
+ * ------------------------------------------------------------------------------------------- */
+int btv_verify_cost(double s, double c, double layers, double h, double nq, double nkv, double d,
+                    double hffn, double V, double bp, double peak_flops, double bandwidth,
+                    double calib_scale, double calib_offset, double *out);
+
+/* ---------------------------------------------------------------------------------------------
  * ancestor mask -- the verification mask of App. C ("Linearization and verification mask")
  * as a bitset: bit a of anc[i] is set iff a is i or an ancestor of i.
  * anc [M, BTV_ANC_WORDS] uint32, word w holds nodes 32w..32w+31.

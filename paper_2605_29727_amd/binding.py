@@ -21,6 +21,7 @@ BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "btv_last_error", "btv_version", "btv_workspace_status", "btv_tree_build_workspace", "btv_tree_build",
+    "btv_tree_build_adaptive", "btv_verify_cost",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
     "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_set_attn_splits",
@@ -109,6 +110,23 @@ def btv_tree_build(marginals, N: int, parent, token, depth, rho, n_out, ahat, ws
     _check(lib().btv_tree_build(_ptr(marginals), B, V, N, _ptr(parent), _ptr(token), _ptr(depth), _ptr(rho),
                                 _ptr(n_out), _ptr(ahat), _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0),
                                 _stream()))
+
+
+def btv_tree_build_adaptive(marginals, N_max: int, cost, L_AR: float, parent, token, depth, rho, n_out, ahat, s_best, ws) -> None:
+    B, V = marginals.shape
+    assert marginals.dtype == torch.float32 and cost.dtype == torch.float64 and cost.numel() >= N_max
+    _check(lib().btv_tree_build_adaptive(_ptr(marginals), B, V, N_max, _ptr(cost), C.c_double(L_AR), _ptr(parent),
+                                         _ptr(token), _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(s_best),
+                                         _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_verify_cost(s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale=1.0,
+                    calib_offset=0.0) -> dict:
+    """Host-side cost model (no GPU work): FLOPs, bytes, roofline time and calibrated latency of a verifier pass."""
+    out = (C.c_double * 4)()
+    _check(lib().btv_verify_cost(*[C.c_double(float(x)) for x in (s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops,
+                                                                  bandwidth, calib_scale, calib_offset)], out))
+    return {"flops": out[0], "bytes": out[1], "roofline_s": out[2], "latency_s": out[3]}
 
 
 def btv_tree_ancestor_mask(parent, anc, ws) -> None:

@@ -35,4 +35,27 @@ int btv_workspace_status(void *ws, void *stream)
     return BTV_OK;
 }
 
+// Verifier cost model (App. E), host arithmetic only.  The two totals are the appendix's displayed sums: FLOPs =
+// layers * (projections + scores and PV + FFN) + LM head; traffic = weights (embedding and LM head counted apart)
+// + KV cache read and write + activations, in elements times bytes per element.
+int btv_verify_cost(double s, double c, double layers, double h, double nq, double nkv, double d, double hffn, double V,
+                    double bp, double peak_flops, double bandwidth, double calib_scale, double calib_offset, double *out)
+{
+    BTV_REQUIRE(out != nullptr, "null pointer");
+    BTV_REQUIRE(s >= 0 && c >= 0 && layers >= 0 && h > 0 && nq > 0 && nkv > 0 && d > 0 && hffn >= 0 && V > 0 && bp > 0,
+                "negative or zero model dimension");
+    BTV_REQUIRE(peak_flops > 0 && bandwidth > 0, "peak_flops and bandwidth must be positive");
+    const double hq = nq * d, hkv = nkv * d;
+    const double flops = layers * (4.0 * s * h * hq + 4.0 * s * h * hkv + 4.0 * s * (c + s) * hq + 6.0 * s * h * hffn) +
+                         2.0 * s * h * V;
+    const double elems = 2.0 * V * h + s * (h + V) +
+                         layers * (2.0 * h * (hq + hkv) + 3.0 * h * hffn + 2.0 * hkv * (c + 2.0 * s) +
+                                   4.0 * s * (h + hq + hffn) + 2.0 * nq * s * (c + s));
+    const double bytes = bp * elems;
+    const double tf = flops / peak_flops, tb = bytes / bandwidth;
+    const double r = tf > tb ? tf : tb;
+    out[0] = flops; out[1] = bytes; out[2] = r; out[3] = calib_scale * r + calib_offset;
+    return BTV_OK;
+}
+
 }  // extern "C"

@@ -191,6 +191,14 @@ struct ExpandLds {                          // the expansion
     float q[MAXB * BTV_MAX_NODES + 64];     // q[k*KP + r]: probability of rank r at position k (+ padding: q[..][r+1] is
                                             // fetched, not used, also for the last rank of the last position)
     uint32_t tok[MAXB * BTV_MAX_NODES];     // its token id
+    double cost[BTV_MAX_NODES];             // adaptive budget: estimated cycle latency at budget n + 1
+};
+
+struct Adaptive {                           // Algorithm 1's early stop (cost == nullptr: fixed budget)
+    const double *cost;
+    double L_AR;
+    double *s_best;
+    uint32_t *flag;
 };
 
 // sel[0..n): distinct keys; those of rank < K (rank = number of keys above) go to q_row / tok_row (global).
@@ -293,9 +301,11 @@ __device__ __forceinline__ void wave_select_rank(ForEach for_each, int K, int KP
 // almost always; on ties the depth decides, then the rank paths, rebuilt by walking the parents of the tied
 // entries through the emitted nodes.
 // ------------------------------------------------------------------------------------------------
-template <int R>
+// ADAPT: the budget is chosen online (Sec. 3.4, Eq. 6): with Ahat summed in fp64 in emission order, the popped node
+// is kept only while Ahat(N) * L_AR / C(N) strictly improves, compared as Ahat(N) * C(N*) > Ahat(N*) * C(N).
+template <int R, bool ADAPT>
 __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, int N, int lane, int32_t *parent, int32_t *token,
-                                            int32_t *depth, float *rho, int32_t *n_out, float *ahat)
+                                            int32_t *depth, float *rho, int32_t *n_out, float *ahat, const Adaptive &ad)
 {
     const float *q_s = S.q;
     const uint32_t q_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)q_s;
@@ -311,12 +321,24 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
         e_prho[0] = 1.0f;
     }
     int n = 0;
+    double run_a = 1.0, best_a = 0.0, best_c = 0.0;            // Ahat so far; Ahat and cost at the best budget so far
     while (n < N) {
+        double c_n = 0.0;
+        if (ADAPT) c_n = S.cost[n];                            // fetched early: used after the wave maximum
         uint32_t lm = e_key[0];
 #pragma unroll
         for (int r = 1; r < R; ++r) lm = umax(lm, e_key[r]);
         const uint32_t m = wave_max_u32(lm);
         if (m == 0u) break;                                   // frontier empty: the lattice is exhausted
+        if (ADAPT) {
+            const double a_new = run_a + (double)__uint_as_float(m - 1u);
+            if (!(c_n > 0.0)) {                                // invalid cost: stop here and tell
+                if (lane == 0) atomicOr(ad.flag, 4u);
+                break;
+            }
+            if (n > 0 && !(a_new * best_c > best_a * c_n)) break;      // the estimated speedup did not improve
+            run_a = a_new; best_a = a_new; best_c = c_n;
+        }
         u64 al[R];
         int cnt = 0;
 #pragma unroll
@@ -455,7 +477,8 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
     for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off);
     if (lane == 0) {
         *n_out = n;
-        if (ahat) *ahat = (float)(1.0 + a);
+        if (ahat) *ahat = ADAPT ? (float)run_a : (float)(1.0 + a);
+        if (ADAPT && ad.s_best) *ad.s_best = n > 0 ? best_a * ad.L_AR / best_c : -INFINITY;
     }
 }
 
@@ -464,7 +487,7 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, int B, int K, int KP, int N, TbCounters *ctr,
                                                       const u64 *cand, float *top_q, uint32_t *top_tok, int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
-                                                      unsigned long long *dbg)
+                                                      Adaptive ad, unsigned long long *dbg)
 {
     __shared__ RankLds RL;
     __shared__ ExpandLds S;
@@ -502,13 +525,21 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
         S.q[e] = __builtin_nontemporal_load(top_q + e);
         S.tok[e] = __builtin_nontemporal_load(top_tok + e);
     }
+    if (ad.cost)
+        for (int e = tid; e < N; e += 256) S.cost[e] = ad.cost[e];
     __syncthreads();
     if (w != 0) return;
     const unsigned long long t1_ = __builtin_amdgcn_s_memtime();
     if (dbg && lane == 0) { dbg[0] = t1_ - t0_; dbg[2] = tr_ - t0_; dbg[3] = ta_ - tr_; }
-    if (N <= 64) expand_wave<1>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat);
-    else if (N <= 128) expand_wave<2>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat);
-    else expand_wave<4>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat);
+    if (ad.cost) {
+        if (N <= 64) expand_wave<1, true>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
+        else if (N <= 128) expand_wave<2, true>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
+        else expand_wave<4, true>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
+    } else {
+        if (N <= 64) expand_wave<1, false>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
+        else if (N <= 128) expand_wave<2, false>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
+        else expand_wave<4, false>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
+    }
     if (dbg && lane == 0) dbg[1] = __builtin_amdgcn_s_memtime() - t1_;
 }
 
@@ -545,8 +576,8 @@ size_t btv_tree_build_workspace(int B, int V, int N)
     return BTV_WS_HEADER + t.part_bytes + t.cand_bytes + 2 * t.top_bytes;
 }
 
-int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
-                   float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
+static int tree_build_launch(const float *marginals, int B, int V, int N, const Adaptive &ad_in, int32_t *parent, int32_t *token,
+                             int32_t *depth, float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
 {
     BTV_REQUIRE(marginals && parent && token && n_out, "null pointer");
     BTV_REQUIRE(B >= 1 && B <= MAXB, "B=%d outside [1,%d]", B, MAXB);
@@ -561,16 +592,35 @@ int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent,
     TbCounters *ctr = reinterpret_cast<TbCounters *>(base + 64);
     uint32_t *part = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER);
     u64 *cand = reinterpret_cast<u64 *>(base + BTV_WS_HEADER + t.part_bytes);
+    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes);
+    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes + t.top_bytes);
+    Adaptive ad = ad_in;
+    ad.flag = reinterpret_cast<uint32_t *>(base);
     hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, part, ctr);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(tb_compact, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, t.K, part, ctr, cand);
     BTV_HIP(hipGetLastError());
-    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes);
-    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes + t.top_bytes);
     hipLaunchKernelGGL(tb_rank_expand, dim3(B), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, ctr, cand, top_q, top_tok, parent,
-                       token, depth, rho, n_out, ahat, g_tb_dbg);
+                       token, depth, rho, n_out, ahat, ad, g_tb_dbg);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
+}
+
+int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
+                   float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
+{
+    const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
+    return tree_build_launch(marginals, B, V, N, none, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+}
+
+int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, const double *cost, double L_AR,
+                            int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                            double *s_best, void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(cost != nullptr, "null pointer");
+    BTV_REQUIRE(L_AR > 0.0, "L_AR must be positive");
+    const Adaptive ad = { cost, L_AR, s_best, nullptr };
+    return tree_build_launch(marginals, B, V, N_max, ad, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

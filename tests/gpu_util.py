@@ -53,6 +53,27 @@ def run_tree_build(marg: np.ndarray, N: int) -> dict:
             "raw_parent": parent.cpu().numpy()}
 
 
+def run_tree_build_adaptive(marg: np.ndarray, N_max: int, cost: np.ndarray, L_AR: float) -> dict:
+    m = dev(marg.astype(np.float32))
+    B, V = marg.shape
+    c = torch.from_numpy(np.ascontiguousarray(cost, dtype=np.float64)).cuda()
+    parent = torch.full((N_max,), -7, dtype=torch.int32, device="cuda")
+    token = torch.full((N_max,), -7, dtype=torch.int32, device="cuda")
+    depth = torch.full((N_max,), -7, dtype=torch.int32, device="cuda")
+    rho = torch.full((N_max,), -7.0, dtype=torch.float32, device="cuda")
+    n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ahat = torch.zeros(1, dtype=torch.float32, device="cuda")
+    s_best = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_build_workspace(B, V, N_max))
+    btv.btv_tree_build_adaptive(m, N_max, c, L_AR, parent, token, depth, rho, n_out, ahat, s_best, ws)
+    torch.cuda.synchronize()
+    n = int(n_out.item())
+    status = int(btv.btv_workspace_status(ws))
+    return {"n": n, "parent": parent.cpu().numpy()[:n], "token": token.cpu().numpy()[:n],
+            "depth": depth.cpu().numpy()[:n], "rho": rho.cpu().numpy()[:n], "ahat": float(ahat.item()),
+            "s_best": float(s_best.item()), "status": status, "raw_parent": parent.cpu().numpy()}
+
+
 def run_accept_greedy(logits_store: np.ndarray, bf16_bits: bool, parent, token) -> dict:
     x = dev(logits_store, bf16_bits)
     M = len(parent)

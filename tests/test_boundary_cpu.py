@@ -88,3 +88,20 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     rc = lib.btv_tree_verify_attn_paged(fake, fake, fake, 10, fake, 4, fake, fake, fake, 2, 10, 8, 1 << 20, 8, 8, 128,
                                         f0, fake, fake, C.c_size_t(1 << 30), None)
     assert rc == -1 and b"max_blocks" in lib.btv_last_error()
+
+
+def test_host_cost_model_matches_the_oracle(oracle):
+    """btv_verify_cost is host arithmetic only (App. E), so it is compared here, without a GPU."""
+    from paper_2605_29727_amd import binding as btv
+    cfgs = [(64, 8192, 32, 4096, 32, 8, 128, 14336, 128256, 2, 2.5e15, 8e12, 1.0, 0.0),
+            (128, 32768, 80, 8192, 64, 8, 128, 28672, 128256, 2, 2.5e15, 8e12, 1.3, 2e-4),
+            (1, 2, 1, 2, 1, 1, 2, 3, 5, 1, 56.0, 37.0, 2.0, 0.5),
+            (0, 100, 2, 16, 2, 1, 8, 32, 50, 4, 1e9, 1e9, 1.0, 0.0)]
+    for cfg in cfgs:
+        got, ref = btv.btv_verify_cost(*cfg), oracle.verify_cost(*cfg)
+        for k in ("flops", "bytes", "roofline_s", "latency_s"):
+            assert got[k] == pytest.approx(ref[k], rel=1e-14), (cfg, k)
+    with pytest.raises(btv.BtvError):
+        btv.btv_verify_cost(1, 1, 1, 0, 1, 1, 1, 1, 1, 1, 1.0, 1.0)          # zero hidden size
+    with pytest.raises(btv.BtvError):
+        btv.btv_verify_cost(1, 1, 1, 8, 1, 1, 1, 1, 1, 1, 0.0, 1.0)          # zero peak

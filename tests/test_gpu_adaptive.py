@@ -1,0 +1,89 @@
+"""Parity of the HIP adaptive tree build (Algorithm 1 with its early stop) with the CPU oracle: the chosen budget,
+the tree (bit-exact), the surrogate and the estimated speedup."""
+import numpy as np
+import pytest
+
+from paper_2605_29727_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+AMBIGUOUS = 1e-11      # a stop decision closer than this (relative) may legitimately differ: fp64 quotients on the
+                       # CPU, cross-multiplied products on the GPU
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _check(G, oracle, marg, N_max, cost, L_AR):
+    ref = oracle.tree_build_adaptive(marg, N_max, cost, L_AR)
+    got = G.run_tree_build_adaptive(marg, N_max, cost, L_AR)
+    assert got["status"] == 0
+    if ref["margin"] < AMBIGUOUS:
+        return ref, got, False
+    assert got["n"] == ref["n"]
+    for k in ("parent", "token", "depth"):
+        assert np.array_equal(got[k], ref[k]), k
+    assert np.array_equal(got["rho"].view(np.uint32), ref["rho"].view(np.uint32))
+    assert abs(got["ahat"] - ref["ahat"]) <= 2e-7 * ref["ahat"]
+    assert got["s_best"] == pytest.approx(ref["s_best"], rel=1e-13)
+    assert np.all(got["raw_parent"][got["n"]:] == -7)              # nothing written past the chosen budget
+    return ref, got, True
+
+
+def _cost(kind, N_max, scale=1.0):
+    N = np.arange(1, N_max + 1, dtype=np.float64)
+    return scale * {"affine": 2.0 + 0.07 * N, "quadratic": 5.0 + 0.01 * N + 5e-4 * N ** 2,
+                    "kink": np.maximum(4.0 + 0.001 * N, 0.2 * N - 3.0), "flat": np.ones_like(N),
+                    "steep": N}[kind]
+
+
+@pytest.mark.parametrize("sigma,seed", [(3.0, 2), (5.0, 3), (1.0, 4), (8.0, 9)])
+@pytest.mark.parametrize("N_max", [16, 64, 100, 256])
+@pytest.mark.parametrize("kind", ["affine", "quadratic", "kink"])
+def test_full_vocabulary(G, oracle, sigma, seed, N_max, kind):
+    marg = synth.marginals(seed, 16, 128256, sigma)
+    _check(G, oracle, marg, N_max, _cost(kind, N_max), 1.0)
+
+
+def test_stops_span_the_range(G, oracle):
+    """Flat cost: runs to N_max; cost proportional to N: stops after the first node; in between for the others."""
+    marg = synth.marginals(3, 16, 128256, 5.0)
+    seen = set()
+    for kind, scale in (("flat", 1.0), ("steep", 1.0), ("affine", 1.0), ("affine", 1e-3), ("quadratic", 3.0), ("kink", 0.5)):
+        ref, got, compared = _check(G, oracle, marg, 256, _cost(kind, 256, scale), 2.5)
+        if compared:
+            seen.add(ref["n"])
+    assert 1 in seen and 256 in seen and len(seen) >= 4
+
+
+def test_model_cost_curve(G, oracle):
+    """The cost of the paper's own form: C(N) = T_draft + T_aux + calibrated roofline of the verifier (App. E) for an
+    8B-shaped target at an 8k context, on datasheet numbers."""
+    N_max = 256
+    tv = np.array([oracle.verify_cost(n, 8192, 32, 4096, 32, 8, 128, 14336, 128256, 2, 2.5e15, 8e12, 1.2, 3e-4)["latency_s"]
+                   for n in range(1, N_max + 1)])
+    cost = 2e-3 + 1e-4 + tv
+    L_AR = oracle.verify_cost(1, 8192, 32, 4096, 32, 8, 128, 14336, 128256, 2, 2.5e15, 8e12, 1.2, 3e-4)["latency_s"]
+    for sigma, seed in ((5.0, 3), (3.0, 2), (1.0, 4)):
+        _check(G, oracle, synth.marginals(seed, 16, 128256, sigma), N_max, cost, L_AR)
+
+
+@pytest.mark.parametrize("B,V,N_max", [(1, 1, 1), (2, 3, 12), (4, 64, 200), (3, 5000, 77)])
+def test_small_vocabularies_and_exhausted_lattices(G, oracle, B, V, N_max):
+    for seed in range(3):
+        marg = synth.marginals(60 + seed, B, V, 2.5)
+        _check(G, oracle, marg, N_max, _cost("affine", N_max, 0.1), 1.0)
+        _check(G, oracle, marg, N_max, _cost("flat", N_max), 1.0)
+
+
+def test_invalid_cost_is_flagged(G, oracle):
+    marg = synth.marginals(5, 4, 100, 2.0)
+    cost = np.ones(32)
+    cost[5] = 0.0
+    got = G.run_tree_build_adaptive(marg, 32, cost, 1.0)
+    assert got["status"] != 0 and got["n"] == 5          # the five nodes before the bad entry stand
+    ref = oracle.tree_build(marg, 5)
+    assert np.array_equal(got["parent"], ref["parent"]) and np.array_equal(got["token"], ref["token"])
