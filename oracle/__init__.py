@@ -39,6 +39,7 @@ def _load():
         _lib.orc_ancestor_mask.restype = C.c_int
         _lib.orc_tree_build_adaptive.restype = C.c_int
         _lib.orc_verify_cost.restype = None
+        _lib.orc_kv_commit.restype = C.c_longlong
     return _lib
 
 
@@ -197,3 +198,25 @@ def accept_stochastic(logits_f32, marg, parent, token, depth, uniforms) -> dict:
                                       C.byref(gap))
     return {"n_acc": n, "path": path[:n].copy(), "bonus": int(bonus.value), "n_uniforms": int(used.value),
             "margin": float(margin.value), "bonus_gap": float(gap.value)}
+
+
+def kv_commit(cache: np.ndarray, L: int, M: int, path, block_table=None, page: int = 16) -> int:
+    """Reorder one cache (K or V) in place: position L+j takes the row of position L+path[j] (App. C "Acceptance").
+
+    cache [layers, rows, ...] (contiguous) or [layers, num_blocks, page, ...] with a block table; any dtype.
+    Returns the new sequence length L + len(path)."""
+    assert cache.flags["C_CONTIGUOUS"]
+    path = np.ascontiguousarray(path, dtype=np.int32)
+    layers = cache.shape[0]
+    layer_stride = cache.strides[0]
+    row_bytes = int(np.prod(cache.shape[2:])) * cache.itemsize if block_table is None else \
+        int(np.prod(cache.shape[3:])) * cache.itemsize
+    bt = None
+    if block_table is not None:
+        block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+        bt = _p(block_table, C.c_int32)
+    rc = _load().orc_kv_commit(cache.ctypes.data_as(C.POINTER(C.c_ubyte)), layers, C.c_longlong(layer_stride), L, M,
+                               row_bytes, _p(path, C.c_int32), len(path), bt, page)
+    if rc < 0:
+        raise ValueError("orc_kv_commit: bad arguments")
+    return int(rc)

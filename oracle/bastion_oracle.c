@@ -16,6 +16,7 @@
  *   orc_tree_build_adaptive  exhaustive argmax of the estimated speedup over all budgets on concave/convex
  *                        inputs (Prop. 3.4), prefix property against orc_tree_build, hand-made cost curves
  *   orc_verify_cost      the per-module tables of App. E summed by hand for a small configuration
+ *   orc_kv_commit        array gather by a library routine (numpy indexing), identity and chain cases
  *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
  *   orc_ancestor_mask    reachability by explicit path enumeration
  *   orc_accept_greedy    brute force over all root-to-node paths, planted paths
@@ -413,4 +414,35 @@ int orc_num_threads(void)
 #else
     return 1;
 #endif
+}
+
+/* ------------------------------------------------------------------------------------------
+ * KV commit (App. C, "Acceptance": the cache is reordered and cropped so that it holds the shared
+ * prefix followed only by the accepted path).  Sequence position L + j takes the row of position
+ * L + path[j] for j < n_acc, in every layer, for K and for V alike; positions from L + n_acc on are
+ * dead afterwards.  Written as the definition: the accepted rows are first copied out, then written
+ * back, so the order of the moves cannot matter.
+ * cache: [layers][layer_stride bytes]; position p of a layer lives at byte offset
+ *     p * row_bytes                                                  if block_table == NULL,
+ *     (block_table[p / page] * page + p % page) * row_bytes          otherwise.
+ * Returns the new length L + n_acc, or -1 on bad arguments.
+ * ---------------------------------------------------------------------------------------- */
+long long orc_kv_commit(unsigned char *cache, int layers, long long layer_stride, int L, int M, int row_bytes,
+                        const int32_t *path, int n_acc, const int32_t *block_table, int page)
+{
+    if (layers < 0 || L < 0 || M < 0 || row_bytes < 1 || n_acc < 0 || n_acc > M) return -1;
+    for (int j = 0; j < n_acc; ++j)
+        if (path[j] < 0 || path[j] >= M) return -1;
+    unsigned char *tmp = (unsigned char *)malloc((size_t)(n_acc > 0 ? n_acc : 1) * (size_t)row_bytes);
+    for (int l = 0; l < layers; ++l) {
+        unsigned char *base = cache + (size_t)l * (size_t)layer_stride;
+        for (int j = 0; j < n_acc; ++j)
+            memcpy(tmp + (size_t)j * row_bytes, base + phys_row(L + path[j], block_table, page) * (size_t)row_bytes,
+                   (size_t)row_bytes);
+        for (int j = 0; j < n_acc; ++j)
+            memcpy(base + phys_row(L + j, block_table, page) * (size_t)row_bytes, tmp + (size_t)j * row_bytes,
+                   (size_t)row_bytes);
+    }
+    free(tmp);
+    return (long long)L + n_acc;
 }
