@@ -228,6 +228,20 @@ def main():
     build_ms = time_loop(torch, path.build, args.steps, args.warmup)
     attn_ms = time_loop(torch, path.attn, args.steps, args.warmup)
     accept_ms = time_loop(torch, path.accept, args.steps, args.warmup)
+    # KV commit of a 32-layer cache of this shape (bf16), an accepted path of 8 of the N nodes
+    kvc = {}
+    try:
+        Kc = torch.zeros((32, L + N, Hkv, D), dtype=torch.bfloat16, device="cuda")
+        Vc = torch.zeros_like(Kc)
+        cpath = torch.zeros(N, dtype=torch.int32, device="cuda")
+        cpath[:8] = torch.tensor([0, 3, 9, 17, 30, 41, 52, 63], dtype=torch.int32)[:8].clamp(max=N - 1)
+        cn = torch.tensor([min(8, N)], dtype=torch.int32, device="cuda")
+        kv_ms = time_loop(torch, lambda: btv.btv_kv_commit(Kc, Vc, L, N, cpath, cn), args.steps, args.warmup)
+        moved = 2 * 32 * int(cn.item()) * Hkv * D * 2
+        kvc = {"kv_commit_us": round(kv_ms * 1e3, 3), "layers": 32, "n_acc": int(cn.item()), "bytes_moved": moved}
+        del Kc, Vc
+    except RuntimeError as e:        # not enough memory beside the KV ring
+        kvc = {"kv_commit_us": None, "error": str(e)[:80]}
     path.setup_adaptive(256)
     adaptive_ms = time_loop(torch, path.build_adaptive, args.steps, args.warmup)
     adaptive = {"tree_build_adaptive_us": round(adaptive_ms * 1e3, 3), "N_max": 256, "N_star": int(path.ad_n.item()),
@@ -280,7 +294,7 @@ def main():
                    "kv_ring_sets": ring_sets, "kv_ring_MB": round(ring_sets * set_bytes / 2 ** 20, 1)},
         "step_breakdown_us": {"tree_build": round(build_ms * 1e3, 3), "tree_verify_attn": round(attn_ms * 1e3, 3),
                               "tree_accept_greedy": round(accept_ms * 1e3, 3), "host_wall_per_step": round(wall_ms * 1e3, 3)},
-        "roofline": roofline, "cpu_baseline": cpu, "curve_L8192": curve, "adaptive_budget": adaptive,
+        "roofline": roofline, "cpu_baseline": cpu, "curve_L8192": curve, "adaptive_budget": adaptive, "kv_commit": kvc,
         "context": "paper reports only end-to-end speedups (6.61x over autoregressive decoding, Qwen3-8B, A100) and a "
                    "whole-model T_verify of 22.0 ms at |T|=32 to 55.9 ms at |T|=1024; no number for this path exists",
     }

@@ -169,6 +169,30 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
                                const float *uniforms, int32_t *path, int32_t *n_acc, int32_t *bonus,
                                void *ws, size_t ws_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * kv_commit -- after acceptance the KV cache keeps the shared prefix followed only by the
+ * accepted path (App. C, "Acceptance").  In every layer, for K and V alike, sequence position
+ * L + j takes the row of position L + path[j] for j < *n_acc; positions from L + *n_acc on are
+ * dead afterwards.  In place.
+ *   K, V     [layers][>= L+M rows][row_bytes]; layer l starts layer_stride_bytes * l after the base;
+ *            row_bytes = Hkv * D * element size, a multiple of 16, at most 32768; 16-byte aligned
+ *   path     [M] int32, n_acc [1] int32 (device): as written by tree_accept (node ids in
+ *            root-to-leaf order, hence increasing, path[j] >= j).  A path that breaks this
+ *            gives unspecified rows L .. L+M-1, nothing else is touched (ids are clamped).
+ *   new_len  [1] int32 optional: L + *n_acc
+ * The paged form does the same for a batch of requests over block pools laid out
+ * [layers][num_blocks][BTV_PAGE][row_bytes] with the block table, prefix lengths and per-request
+ * paths ([batch][M_max], n_acc [batch]) of btv_tree_verify_attn_paged; ws (optional) receives
+ * the data flag when a request's n_acc or prefix length is out of range (that request is
+ * left untouched).
+ * ------------------------------------------------------------------------------------------- */
+int btv_kv_commit(void *K, void *V, int layers, long long layer_stride_bytes, int L, int M, int row_bytes,
+                  const int32_t *path, const int32_t *n_acc, int32_t *new_len, void *stream);
+int btv_kv_commit_paged(void *Kpool, void *Vpool, int layers, long long layer_stride_bytes, int num_blocks,
+                        const int32_t *block_table, int max_blocks, const int32_t *prefix_len,
+                        const int32_t *path, const int32_t *n_acc, int batch, int M_max, int row_bytes,
+                        int32_t *new_len, void *ws, void *stream);
+
 /* Tuning knob for experiments: number of key splits used by tree_verify_attn (0 = heuristic). */
 void btv_set_attn_splits(int nsplit);
 

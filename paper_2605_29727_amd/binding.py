@@ -21,7 +21,7 @@ BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "btv_last_error", "btv_version", "btv_workspace_status", "btv_tree_build_workspace", "btv_tree_build",
-    "btv_tree_build_adaptive", "btv_verify_cost",
+    "btv_tree_build_adaptive", "btv_verify_cost", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
     "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_set_attn_splits",
@@ -182,3 +182,23 @@ def btv_tree_accept_stochastic(logits, marginals, parent, token, uniforms, path,
                                             _ptr(token), rows - 1, V, _ptr(uniforms), _ptr(path), _ptr(n_acc),
                                             _ptr(bonus), _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0),
                                             _stream()))
+
+
+def btv_kv_commit(K, V, L: int, M: int, path, n_acc, new_len=None) -> None:
+    """K, V [layers, rows >= L+M, ...] contiguous tensors of one dtype; reordered in place."""
+    assert K.shape == V.shape and K.is_contiguous() and V.is_contiguous() and K.dim() >= 3
+    layers = K.shape[0]
+    row_bytes = K[0, 0].numel() * K.element_size()
+    _check(lib().btv_kv_commit(_ptr(K), _ptr(V), layers, C.c_longlong(K.stride(0) * K.element_size()), L, M, row_bytes,
+                               _ptr(path), _ptr(n_acc), _ptr(new_len), _stream()))
+
+
+def btv_kv_commit_paged(Kpool, Vpool, block_table, prefix_len, path, n_acc, new_len=None, ws=None) -> None:
+    """Kpool, Vpool [layers, num_blocks, PAGE, ...]; block_table [batch, max_blocks]; path [batch, M_max]."""
+    assert Kpool.shape == Vpool.shape and Kpool.is_contiguous() and Vpool.is_contiguous() and Kpool.dim() >= 4
+    layers, num_blocks = Kpool.shape[0], Kpool.shape[1]
+    row_bytes = Kpool[0, 0, 0].numel() * Kpool.element_size()
+    batch, max_blocks = block_table.shape
+    _check(lib().btv_kv_commit_paged(_ptr(Kpool), _ptr(Vpool), layers, C.c_longlong(Kpool.stride(0) * Kpool.element_size()),
+                                     num_blocks, _ptr(block_table), max_blocks, _ptr(prefix_len), _ptr(path), _ptr(n_acc),
+                                     batch, path.shape[1], row_bytes, _ptr(new_len), _ptr(ws), _stream()))

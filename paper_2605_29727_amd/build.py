@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libbastion_tv.so")
-SOURCES = ["api.hip", "attn.hip", "tree_build.hip", "accept.hip"]
+SOURCES = ["api.hip", "attn.hip", "tree_build.hip", "accept.hip", "kv_commit.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 VALU ops on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
