@@ -18,6 +18,7 @@
 #include "btv_common.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace {
 
@@ -303,6 +304,11 @@ __device__ __forceinline__ void wave_select_rank(ForEach for_each, int K, int KP
 // ------------------------------------------------------------------------------------------------
 // ADAPT: the budget is chosen online (Sec. 3.4, Eq. 6): with Ahat summed in fp64 in emission order, the popped node
 // is kept only while Ahat(N) * L_AR / C(N) strictly improves, compared as Ahat(N) * C(N*) > Ahat(N*) * C(N).
+// An empty volatile asm in the body of a wave-uniform `if` keeps it a real (scalar) branch: with several register
+// rows the compiler would otherwise turn the row selection into select chains over every row, which costs more
+// instructions than the branches do.
+#define BTV_KEEP_BRANCH() asm volatile("" ::: "memory")
+
 template <int R, bool ADAPT>
 __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, int N, int lane, int32_t *parent, int32_t *token,
                                             int32_t *depth, float *rho, int32_t *n_out, float *ahat, const Adaptive &ad)
@@ -322,144 +328,159 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
     }
     int n = 0;
     double run_a = 1.0, best_a = 0.0, best_c = 0.0;            // Ahat so far; Ahat and cost at the best budget so far
-    while (n < N) {
-        double c_n = 0.0;
-        if (ADAPT) c_n = S.cost[n];                            // fetched early: used after the wave maximum
-        uint32_t lm = e_key[0];
-#pragma unroll
-        for (int r = 1; r < R; ++r) lm = umax(lm, e_key[r]);
-        const uint32_t m = wave_max_u32(lm);
-        if (m == 0u) break;                                   // frontier empty: the lattice is exhausted
-        if (ADAPT) {
-            const double a_new = run_a + (double)__uint_as_float(m - 1u);
-            if (!(c_n > 0.0)) {                                // invalid cost: stop here and tell
-                if (lane == 0) atomicOr(ad.flag, 4u);
-                break;
+    bool stop = false;
+    // Slots are handed out in node order, so before node 64*RA - 1 is emitted only the first RA register rows can
+    // hold anything: the loop runs in phases over RA = 1..R, each compiled for its number of live rows.
+    auto phase = [&](auto ra_c, int n_end) {
+        constexpr int RA = decltype(ra_c)::value;
+        while (n < n_end) {
+            double c_n = 0.0;
+            if (ADAPT) c_n = S.cost[n];                            // fetched early: used after the wave maximum
+            uint32_t lm = e_key[0];
+    #pragma unroll
+            for (int r = 1; r < RA; ++r) lm = umax(lm, e_key[r]);
+            const uint32_t m = wave_max_u32(lm);
+            if (m == 0u) { stop = true; break; }                   // frontier empty: the lattice is exhausted
+            if (ADAPT) {
+                const double a_new = run_a + (double)__uint_as_float(m - 1u);
+                if (!(c_n > 0.0)) {                                // invalid cost: stop here and tell
+                    if (lane == 0) atomicOr(ad.flag, 4u);
+                    stop = true;
+                    break;
+                }
+                if (n > 0 && !(a_new * best_c > best_a * c_n)) { stop = true; break; }   // the estimated speedup did not improve
+                run_a = a_new; best_a = a_new; best_c = c_n;
             }
-            if (n > 0 && !(a_new * best_c > best_a * c_n)) break;      // the estimated speedup did not improve
-            run_a = a_new; best_a = a_new; best_c = c_n;
-        }
-        u64 al[R];
-        int cnt = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) { al[r] = __builtin_amdgcn_ballot_w64(e_key[r] == m); cnt += __builtin_popcountll(al[r]); }
-        if (cnt > 1) {
-            // ties on rho: shallower first (x grows with the depth) ...
-            uint32_t cl = 0u;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if ((al[r] >> lane) & 1ull) cl = umax(cl, 0x100u - ((e_x[r] - q_base) >> (2 + lg)));
-            const uint32_t cm = wave_max_u32(cl);
-            cnt = 0;
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && 0x100u - ((e_x[r] - q_base) >> (2 + lg)) == cm);
-                cnt += __builtin_popcountll(al[r]);
-            }
+            u64 al[RA];
+            int cnt = 0;
+    #pragma unroll
+            for (int r = 0; r < RA; ++r) { al[r] = __builtin_amdgcn_ballot_w64(e_key[r] == m); cnt += __builtin_popcountll(al[r]); }
             if (cnt > 1) {
-                // ... then the smaller rank path: one byte per position, first position in the most significant
-                // byte of word 0; the walk fetches the emitted ancestors from the lanes that hold them
-                uint32_t path[R][4];
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) path[r][w] = 0u;
+                // ties on rho: shallower first (x grows with the depth) ...
+                uint32_t cl = 0u;
+    #pragma unroll
+                for (int r = 0; r < RA; ++r)
+                    if ((al[r] >> lane) & 1ull) cl = umax(cl, 0x100u - ((e_x[r] - q_base) >> (2 + lg)));
+                const uint32_t cm = wave_max_u32(cl);
+                cnt = 0;
+    #pragma unroll
+                for (int r = 0; r < RA; ++r) {
+                    al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && 0x100u - ((e_x[r] - q_base) >> (2 + lg)) == cm);
+                    cnt += __builtin_popcountll(al[r]);
                 }
-#pragma unroll
-                for (int r = 0; r < R; ++r) {                  // every lane walks, tied or not: the fetches are wave-wide
-                    uint32_t idx = (e_x[r] - q_base) >> 2;     // index of q[depth-1][rank]
-                    int node = r * 64 + lane - 1;              // the entry's parent
-                    bool live = (al[r] >> lane) & 1ull;
-                    while (__builtin_amdgcn_ballot_w64(live) != 0ull) {
-                        const int pos = (int)(idx >> lg), sh = 24 - 8 * (pos & 3);
-                        const uint32_t byte = (idx & (uint32_t)(KP - 1)) << sh;
-                        if (live) {
-#pragma unroll
-                            for (int w = 0; w < 4; ++w) if (w == (pos >> 2)) path[r][w] |= byte;
-                        }
-                        live = live && node >= 0;
-                        const int src = node >= 0 ? node : 0;
-                        uint32_t rec = 0u;
-#pragma unroll
-                        for (int rr = 0; rr < R; ++rr) {
-                            const uint32_t got = (uint32_t)__shfl((int)o_rec[rr], src & 63);
-                            if (rr == (src >> 6)) rec = got;
-                        }
-                        idx = rec & 0x1FFFu;
-                        node = (int)(rec >> 13) - 1;
+                if (cnt > 1) {
+                    // ... then the smaller rank path: one byte per position, first position in the most significant
+                    // byte of word 0; the walk fetches the emitted ancestors from the lanes that hold them
+                    uint32_t path[RA][4];
+    #pragma unroll
+                    for (int r = 0; r < RA; ++r) {
+    #pragma unroll
+                        for (int w = 0; w < 4; ++w) path[r][w] = 0u;
                     }
-                }
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    if (cnt <= 1) break;
-                    uint32_t pl = 0u;
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-                        if ((al[r] >> lane) & 1ull) pl = umax(pl, ~path[r][w]);
-                    const uint32_t pm = wave_max_u32(pl);
-                    cnt = 0;
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && ~path[r][w] == pm);
-                        cnt += __builtin_popcountll(al[r]);
+    #pragma unroll
+                    for (int r = 0; r < RA; ++r) {                  // every lane walks, tied or not: the fetches are wave-wide
+                        uint32_t idx = (e_x[r] - q_base) >> 2;     // index of q[depth-1][rank]
+                        int node = r * 64 + lane - 1;              // the entry's parent
+                        bool live = (al[r] >> lane) & 1ull;
+                        while (__builtin_amdgcn_ballot_w64(live) != 0ull) {
+                            const int pos = (int)(idx >> lg), sh = 24 - 8 * (pos & 3);
+                            const uint32_t byte = (idx & (uint32_t)(KP - 1)) << sh;
+                            if (live) {
+    #pragma unroll
+                                for (int w = 0; w < 4; ++w) if (w == (pos >> 2)) path[r][w] |= byte;
+                            }
+                            live = live && node >= 0;
+                            const int src = node >= 0 ? node : 0;
+                            uint32_t rec = 0u;
+    #pragma unroll
+                            for (int rr = 0; rr < RA; ++rr) {
+                                const uint32_t got = (uint32_t)__shfl((int)o_rec[rr], src & 63);
+                                if (rr == (src >> 6)) rec = got;
+                            }
+                            idx = rec & 0x1FFFu;
+                            node = (int)(rec >> 13) - 1;
+                        }
+                    }
+    #pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        if (cnt <= 1) break;
+                        uint32_t pl = 0u;
+    #pragma unroll
+                        for (int r = 0; r < RA; ++r)
+                            if ((al[r] >> lane) & 1ull) pl = umax(pl, ~path[r][w]);
+                        const uint32_t pm = wave_max_u32(pl);
+                        cnt = 0;
+    #pragma unroll
+                        for (int r = 0; r < RA; ++r) {
+                            al[r] = __builtin_amdgcn_ballot_w64(((al[r] >> lane) & 1ull) && ~path[r][w] == pm);
+                            cnt += __builtin_popcountll(al[r]);
+                        }
                     }
                 }
             }
-        }
-        int wr = 0;
-#pragma unroll
-        for (int r = R - 1; r >= 1; --r) if (al[r] != 0ull) wr = r;
-        if (al[0] != 0ull) wr = 0;
-        u64 alw = al[0];
-        uint32_t s_x = e_x[0];
-#pragma unroll
-        for (int r = 1; r < R; ++r)
-            if (r == wr) { alw = al[r]; s_x = e_x[r]; }
-        const int wl = __builtin_ctzll(alw);
-        const uint32_t u_idx = (__builtin_amdgcn_readlane(s_x, wl) - q_base) >> 2;
-        const float u_rho = __uint_as_float(m - 1u);
-        const int d = (int)(u_idx >> lg) + 1, rank = u_idx & (uint32_t)(KP - 1);
-        // emit node n into its lane
-        {
-            const uint32_t rec = u_idx | ((uint32_t)(wr * 64 + wl) << 13);     // parent + 1 = the entry's slot
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == (n >> 6)) {                           // wave-uniform
-                    const bool me = lane == (n & 63);
-                    o_rec[r] = me ? rec : o_rec[r];
-                    o_rho[r] = me ? u_rho : o_rho[r];
-                }
-        }
-        // the entry moves on to the next sibling, in its own lane
-        const bool has_next = rank + 1 < K;
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (r == wr) {                                     // wave-uniform
-                const bool me = lane == wl;
-                const uint32_t nk = has_next ? __float_as_uint(__fmul_rn(e_prho[r], e_qn[r])) + 1u : 0u;
-                e_key[r] = me ? nk : e_key[r];
-                e_x[r] += me ? 4u : 0u;
+            int wr = 0;
+    #pragma unroll
+            for (int r = RA - 1; r >= 1; --r) if (al[r] != 0ull) wr = r;
+            if (al[0] != 0ull) wr = 0;
+            u64 alw = al[0];
+            uint32_t s_x = e_x[0];
+    #pragma unroll
+            for (int r = 1; r < RA; ++r)
+                if (r == wr) { alw = al[r]; s_x = e_x[r]; }
+            const int wl = __builtin_ctzll(alw);
+            const uint32_t u_idx = (__builtin_amdgcn_readlane(s_x, wl) - q_base) >> 2;
+            const float u_rho = __uint_as_float(m - 1u);
+            const int d = (int)(u_idx >> lg) + 1, rank = u_idx & (uint32_t)(KP - 1);
+            // emit node n into its lane
+            {
+                const uint32_t rec = u_idx | ((uint32_t)(wr * 64 + wl) << 13);     // parent + 1 = the entry's slot
+    #pragma unroll
+                for (int r = 0; r < RA; ++r)
+                    if (r == (n >> 6)) {                           // wave-uniform
+                        BTV_KEEP_BRANCH();
+                        const bool me = lane == (n & 63);
+                        o_rec[r] = me ? rec : o_rec[r];
+                        o_rho[r] = me ? u_rho : o_rho[r];
+                    }
             }
-        // the emitted node's children: the entry of slot n + 1 (a slot past the last row is simply not written)
-        if (d < B) {
-            const int cs = n + 1;
-            const float q_child = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qfirst), d));
-            const uint32_t key_child = __float_as_uint(__fmul_rn(u_rho, q_child)) + 1u;
-            const uint32_t x_child = q_base + ((uint32_t)d << (2 + lg));
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == (cs >> 6)) {                          // wave-uniform
-                    const bool me = lane == (cs & 63);
-                    e_key[r] = me ? key_child : e_key[r];
-                    e_prho[r] = me ? u_rho : e_prho[r];
-                    e_x[r] = me ? x_child : e_x[r];
+            // the entry moves on to the next sibling, in its own lane
+            const bool has_next = rank + 1 < K;
+    #pragma unroll
+            for (int r = 0; r < RA; ++r)
+                if (r == wr) {                                     // wave-uniform
+                    BTV_KEEP_BRANCH();
+                    const bool me = lane == wl;
+                    const uint32_t nk = has_next ? __float_as_uint(__fmul_rn(e_prho[r], e_qn[r])) + 1u : 0u;
+                    e_key[r] = me ? nk : e_key[r];
+                    e_x[r] += me ? 4u : 0u;
                 }
+            // the emitted node's children: the entry of slot n + 1 (a slot past the last row is simply not written)
+            if (d < B) {
+                const int cs = n + 1;
+                const float q_child = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(qfirst), d));
+                const uint32_t key_child = __float_as_uint(__fmul_rn(u_rho, q_child)) + 1u;
+                const uint32_t x_child = q_base + ((uint32_t)d << (2 + lg));
+    #pragma unroll
+                for (int r = 0; r < RA; ++r)
+                    if (r == (cs >> 6)) {                          // wave-uniform
+                        BTV_KEEP_BRANCH();
+                        const bool me = lane == (cs & 63);
+                        e_key[r] = me ? key_child : e_key[r];
+                        e_prho[r] = me ? u_rho : e_prho[r];
+                        e_x[r] = me ? x_child : e_x[r];
+                    }
+            }
+    #pragma unroll
+            for (int r = 0; r < RA; ++r)
+                e_qn[r] = *reinterpret_cast<const __attribute__((address_space(3))) float *>((uintptr_t)(e_x[r] + 4u));
+            ++n;
         }
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            e_qn[r] = *reinterpret_cast<const __attribute__((address_space(3))) float *>((uintptr_t)(e_x[r] + 4u));
-        ++n;
-    }
+    };
+    phase(std::integral_constant<int, 1>{}, min(N, 63));
+    if (R >= 2 && !stop) phase(std::integral_constant<int, (R >= 2 ? 2 : 1)>{}, min(N, 127));
+    if (R >= 3 && !stop) phase(std::integral_constant<int, (R >= 3 ? 3 : 1)>{}, min(N, 191));
+    if (R >= 4 && !stop) phase(std::integral_constant<int, (R >= 4 ? 4 : 1)>{}, N);
+    if (R < 4 && !stop) phase(std::integral_constant<int, R>{}, N);
     double a = 0.0;                  // the surrogate: summed in fp64 and rounded once
 #pragma unroll
     for (int r = 0; r < R; ++r) {
