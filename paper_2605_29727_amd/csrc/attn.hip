@@ -933,12 +933,14 @@ struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 // Kernel shape by the number of packed rows per KV head (G*M).  Every wave owns 32 rows.  Measured on MI355X at
 // L = 8192 (8 KV heads): what counts is one workgroup per CU and as few key splits as that allows (the split
 // partials are written and read back), so few rows get small row blocks and many rows get 128-row blocks, both
-// with pairs of waves alternating over the tiles (KW = 2).
+// with pairs of waves alternating over the tiles (KW = 2); very many rows over a very long prefix take the
+// 256-row software-pipelined shape (KW = 1), which measures the same there within run-to-run noise.
 Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
 {
     Plan pl;
     int G = Hq / Hkv, rows_g = G * M;
     if (rows_g <= 128) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
+    else if (rows_g >= 1024 && L >= 16384) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }     // 70B shape at 32k: on par with (4,2,8)
     else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
 #ifdef BTV_EXPERIMENT
     if (g_cfg_rw) { pl.rw = g_cfg_rw; pl.kw = g_cfg_kw; pl.nt = g_cfg_nt; }
