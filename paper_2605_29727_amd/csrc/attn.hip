@@ -39,8 +39,8 @@ struct AttnParams {
     const int32_t *block_table;   // paged only
     const int32_t *q_offset;      // paged only, [batch+1]
     const int32_t *prefix_len;    // paged only, [batch]
-    float *Opart;                 // [nsplit][total_rows][D]
-    float *ML;                    // [nsplit][total_rows][2]
+    _Float16 *Opart;              // [nsplit][total_rows][D]: split partial of O^T's row, divided by its largest magnitude
+    float *ML;                    // [nsplit][total_rows][4]: reference max, row sum, that magnitude, unused
     uint32_t *flag;
     int M, L;                     // contiguous: actual sizes; paged: host upper bounds
     int Hq, Hkv, G;
@@ -737,7 +737,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     BTV_STAMP(3);
     if (kw != 0 || !rvalid) return;
 
-    // ---- write: final bf16 rows when this request has a single split, fp32 partials otherwise ---
+    // ---- write: final bf16 rows when this request has a single split, scaled fp16 partials otherwise ---
     if (nsplit_r == 1) {
         const float inv = 1.0f / l_run;
         uint16_t *Op = static_cast<uint16_t *>(p.O) + orow * D;
@@ -750,16 +750,29 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 *reinterpret_cast<uint2 *>(Op + dt * 32 + q4 * 8 + h * 4) = make_uint2(lo, hi);
             }
     } else {
+        // Partials travel as fp16 relative to the row's largest magnitude (kept in fp32 beside m and l): half the
+        // bytes of fp32 to write, flush at the end of the kernel and read back, at a relative error of 2^-11 of that
+        // magnitude, well below the final bf16 rounding.
+        float amax = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) amax = fmaxf(amax, fabsf(oacc[dt][v]));
+        amax = fmaxf(amax, __shfl_xor(amax, 32));           // the other half of the wave holds the row's other channels
+        const float sc = amax > 0.f ? 1.0f / amax : 0.f;
         const size_t prow = (size_t)bx * p.total_rows + orow;
-        float *Pp = p.Opart + prow * D;
+        _Float16 *Pp = p.Opart + prow * D;
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                f32x4 o = { oacc[dt][q4 * 4 + 0], oacc[dt][q4 * 4 + 1], oacc[dt][q4 * 4 + 2], oacc[dt][q4 * 4 + 3] };
-                *reinterpret_cast<f32x4 *>(Pp + dt * 32 + q4 * 8 + h * 4) = o;
+                const h2 lo = { (_Float16)(oacc[dt][q4 * 4 + 0] * sc), (_Float16)(oacc[dt][q4 * 4 + 1] * sc) };
+                const h2 hi = { (_Float16)(oacc[dt][q4 * 4 + 2] * sc), (_Float16)(oacc[dt][q4 * 4 + 3] * sc) };
+                *reinterpret_cast<uint2 *>(Pp + dt * 32 + q4 * 8 + h * 4) =
+                    make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
             }
-        if (h == 0) *reinterpret_cast<float2 *>(p.ML + prow * 2) = make_float2(m_run, l_run);
+        if (h == 0) *reinterpret_cast<float4 *>(p.ML + prow * 4) = make_float4(m_run, l_run, amax, 0.f);
     }
 #ifdef BTV_EXPERIMENT
     if (p.dbg && tid == 0) {
@@ -773,7 +786,8 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #endif
 }
 
-// Split-K combine: O[row] = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e).
+// Split-K combine: O[row] = sum_s w_s a_s O'_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e), O'_s the
+// fp16 partial and a_s the magnitude it was divided by.
 // 8 rows per workgroup, 32 lanes per row, each lane owns D/32 consecutive channels.  Lane j of a row fetches the
 // (m, l) pairs of splits j, j + 32, ... and computes their weights (handed to the other lanes by shuffles); the
 // partial rows of up to 32 splits are fetched by independent loads issued before anything is waited for, so the
@@ -782,7 +796,7 @@ template <int D, bool PAGED>
 __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
 {
     constexpr int E = D / 32;
-    typedef float fvec __attribute__((ext_vector_type(E)));
+    typedef _Float16 hvec __attribute__((ext_vector_type(E)));
     const int rq = blockIdx.y;
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) return;
@@ -795,23 +809,23 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
     const size_t sstride = (size_t)p.total_rows;
     // reference maximum over all splits: with more than 32 of them it takes a round trip of its own
     float mmax = NEG_BIG;
-    for (int s = lane + 32; s < nsplit_r; s += 32) mmax = fmaxf(mmax, p.ML[(s * sstride + row) * 2]);
+    for (int s = lane + 32; s < nsplit_r; s += 32) mmax = fmaxf(mmax, p.ML[(s * sstride + row) * 4]);
     float acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.f;
     float den = 0.f;
     for (int s0 = 0; s0 < nsplit_r; s0 += 32) {     // one pass for up to 32 splits
         const int s_mine = s0 + lane;
-        const float2 ml = s_mine < nsplit_r ? *reinterpret_cast<const float2 *>(p.ML + (s_mine * sstride + row) * 2)
-                                            : make_float2(NEG_BIG, 0.f);
-        fvec part[32];
+        const float4 ml = s_mine < nsplit_r ? *reinterpret_cast<const float4 *>(p.ML + (s_mine * sstride + row) * 4)
+                                            : make_float4(NEG_BIG, 0.f, 0.f, 0.f);
+        hvec part[32];
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             if (s0 + 8 * g < nsplit_r) {             // uniform within the row's lanes: whole groups of 8 loads
 #pragma unroll
                 for (int b = 0; b < 8; ++b) {
                     const int s = min(s0 + 8 * g + b, nsplit_r - 1);
-                    part[8 * g + b] = *reinterpret_cast<const fvec *>(p.Opart + (s * sstride + row) * D + lane * E);
+                    part[8 * g + b] = *reinterpret_cast<const hvec *>(p.Opart + (s * sstride + row) * D + lane * E);
                 }
             }
         if (s0 == 0) {
@@ -821,14 +835,15 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
         }
         const float w = s_mine < nsplit_r ? __builtin_amdgcn_exp2f((ml.x - mmax) * p.scale_log2) : 0.f;
         den += w * ml.y;
+        const float wz = w * ml.z;                             // weight times the partial's magnitude
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             if (s0 + 8 * g < nsplit_r) {
 #pragma unroll
                 for (int b = 0; b < 8; ++b) {
-                    const float wgt = __shfl(w, 8 * g + b, 32);      // 0 for splits past the last
+                    const float wgt = __shfl(wz, 8 * g + b, 32);     // 0 for splits past the last
 #pragma unroll
-                    for (int e = 0; e < E; ++e) acc[e] += wgt * part[8 * g + b][e];
+                    for (int e = 0; e < E; ++e) acc[e] += wgt * (float)part[8 * g + b][e];
                 }
             }
     }
@@ -975,8 +990,8 @@ WsLayout ws_layout(int total_M, int Hq, int D, int nsplit)
     w.anc = off; off += btv_align_up((size_t)total_M * BTV_ANC_WORDS * 4, BTV_WS_ALIGN);
     size_t rows = (size_t)total_M * Hq;
     size_t ns = nsplit > 1 ? nsplit : 0;
-    w.ml = off; off += btv_align_up(ns * rows * 2 * 4, BTV_WS_ALIGN);
-    w.opart = off; off += btv_align_up(ns * rows * D * 4, BTV_WS_ALIGN);
+    w.ml = off; off += btv_align_up(ns * rows * 4 * 4, BTV_WS_ALIGN);
+    w.opart = off; off += btv_align_up(ns * rows * D * 2, BTV_WS_ALIGN);
     w.total = off;
     return w;
 }
@@ -1083,7 +1098,7 @@ int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int3
     p.Q = Q; p.K = K; p.V = V; p.O = O;
     p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
     p.ML = reinterpret_cast<float *>(w8 + wl.ml);
-    p.Opart = reinterpret_cast<float *>(w8 + wl.opart);
+    p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
     p.flag = reinterpret_cast<uint32_t *>(w8);
     p.M = M; p.L = L; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
     p.total_rows = M * Hq; p.total_M = M;
@@ -1143,7 +1158,7 @@ int btv_tree_verify_attn_paged(const void *Q, const void *Kpool, const void *Vpo
     p.Q = Q; p.K = Kpool; p.V = Vpool; p.O = O;
     p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
     p.ML = reinterpret_cast<float *>(w8 + wl.ml);
-    p.Opart = reinterpret_cast<float *>(w8 + wl.opart);
+    p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
     p.flag = reinterpret_cast<uint32_t *>(w8);
     p.block_table = block_table; p.q_offset = q_offset; p.prefix_len = prefix_len;
     p.max_blocks = max_blocks; p.num_blocks = num_blocks;
