@@ -106,6 +106,35 @@ def verify_cost(s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth,
     return {"flops": out[0], "bytes": out[1], "roofline_s": out[2], "latency_s": out[3]}
 
 
+def calib_fit(pred, obs) -> tuple[float, float]:
+    """Sec. 5.2 static calibration: least-squares line obs ~ scale * pred + offset."""
+    pred = np.ascontiguousarray(pred, dtype=np.float64)
+    obs = np.ascontiguousarray(obs, dtype=np.float64)
+    assert pred.shape == obs.shape and pred.ndim == 1
+    a, b = C.c_double(), C.c_double()
+    rc = _load().orc_calib_fit(_p(pred, C.c_double), _p(obs, C.c_double), len(pred), C.byref(a), C.byref(b))
+    if rc != 0:
+        raise ValueError("calibration fit is undetermined")
+    return a.value, b.value
+
+
+def calib_ema(c: float, alpha: float, obs: float, pred: float) -> float:
+    """Sec. 5.2 online calibration: c <- (1 - alpha) c + alpha obs / pred."""
+    f = _load().orc_calib_ema
+    f.restype = C.c_double
+    return f(C.c_double(c), C.c_double(alpha), C.c_double(obs), C.c_double(pred))
+
+
+def cost_curve(N_max, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale=1.0, calib_offset=0.0,
+               c_ema=1.0, t_other=0.0) -> np.ndarray:
+    """C(N), N = 1..N_max, for the budget controller (Eq. 6): T_other + c_ema * calibrated T_verify(N + 1 tokens)."""
+    out = np.zeros(N_max, dtype=np.float64)
+    _load().orc_cost_curve(int(N_max), *[C.c_double(float(x)) for x in (c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops,
+                                                                         bandwidth, calib_scale, calib_offset, c_ema,
+                                                                         t_other)], _p(out, C.c_double))
+    return out
+
+
 def tree_attn(Qf, Kf, Vf, parent, L: int, scale: float | None = None, pairs=None, block_table=None, page: int = 16,
               nthreads: int = 0) -> np.ndarray:
     """Tree-masked attention by its definition (App. C), fp64.

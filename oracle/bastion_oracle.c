@@ -16,6 +16,9 @@
  *   orc_tree_build_adaptive  exhaustive argmax of the estimated speedup over all budgets on concave/convex
  *                        inputs (Prop. 3.4), prefix property against orc_tree_build, hand-made cost curves
  *   orc_verify_cost      the per-module tables of App. E summed by hand for a small configuration
+ *   orc_calib_fit        exact recovery of a planted line, numpy's polynomial fit, zero-gradient of the residual
+ *   orc_calib_ema        closed form of the geometric approach to a constant ratio
+ *   orc_cost_curve       assembled by hand from orc_verify_cost's pinned totals
  *   orc_kv_commit        array gather by a library routine (numpy indexing), identity and chain cases
  *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
  *   orc_ancestor_mask    reachability by explicit path enumeration
@@ -195,6 +198,53 @@ void orc_verify_cost(double s, double c, double layers, double h, double nq, dou
                          layers * (a_attn + a_ffn) + a_lm);
     double r = fmax(flops / peak_flops, bytes / bandwidth);
     out[0] = flops; out[1] = bytes; out[2] = r; out[3] = calib_scale * r + calib_offset;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Calibration of the latency estimate (Sec. 5.2).
+ *
+ * Static: "a per-(GPU, target) linear calibration" of the roofline prediction against measured latency.  The
+ * paper does not name the fit; it is read as the ordinary least-squares line  obs ~ scale * pred + offset,
+ * written here from the normal equations with centred sums.  Fewer than two points, or predictions that are all
+ * equal, leave the slope undetermined: return -1.
+ *
+ * Online: one multiplicative bias updated as  c <- (1 - alpha) c + alpha (obs / pred);  the corrected estimate
+ * is c * pred, where pred is the bare roofline time (EMA) or the statically calibrated one (EMA+Calib).  The
+ * start value is not given; callers pass it (1 = no correction).
+ * ---------------------------------------------------------------------------------------- */
+int orc_calib_fit(const double *pred, const double *obs, int n, double *scale, double *offset)
+{
+    if (n < 2) return -1;
+    double mp = 0, mo = 0;
+    for (int i = 0; i < n; ++i) { mp += pred[i]; mo += obs[i]; }
+    mp /= n; mo /= n;
+    double spp = 0, spo = 0;
+    for (int i = 0; i < n; ++i) { spp += (pred[i] - mp) * (pred[i] - mp); spo += (pred[i] - mp) * (obs[i] - mo); }
+    if (!(spp > 0)) return -1;
+    *scale = spo / spp;
+    *offset = mo - *scale * mp;
+    return 0;
+}
+
+double orc_calib_ema(double c, double alpha, double obs, double pred)
+{
+    return (1.0 - alpha) * c + alpha * (obs / pred);
+}
+
+/* Cost curve handed to the budget controller (Eq. 6 denominator): for N = 1..N_max,
+ *     C(N) = T_other + c_ema * (calib_scale * R(N + 1) + calib_offset),
+ * where R is the roofline time of the model above.  N counts draft nodes, the verifier also processes the root,
+ * hence s = N + 1 new tokens.  T_other = T_draft + T_aux. */
+void orc_cost_curve(int N_max, double c, double layers, double h, double nq, double nkv, double d, double hffn,
+                    double V, double bp, double peak_flops, double bandwidth, double calib_scale, double calib_offset,
+                    double c_ema, double t_other, double *cost)
+{
+    for (int n = 1; n <= N_max; ++n) {
+        double out[4];
+        orc_verify_cost((double)n + 1.0, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale,
+                        calib_offset, out);
+        cost[n - 1] = t_other + c_ema * out[3];
+    }
 }
 
 /* ------------------------------------------------------------------------------------------
