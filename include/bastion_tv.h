@@ -103,6 +103,27 @@ int btv_verify_cost(double s, double c, double layers, double h, double nq, doub
                     double calib_scale, double calib_offset, double *out);
 
 /* ---------------------------------------------------------------------------------------------
+ * Latency calibration -- HOST functions, no GPU work (Sec. 5.2).
+ * calib_fit_linear: the static per-(GPU, target) calibration, read as the least-squares line
+ *   obs ~ calib_scale * pred + calib_offset  through n >= 2 (roofline prediction, measured
+ *   latency) pairs; pred, obs HOST [n].  BTV_EINVAL when the predictions are all equal.
+ * calib_ema_update: the online bias  *c <- (1 - alpha) * *c + alpha * obs / pred,  alpha in
+ *   [0, 1], pred > 0; the caller keeps c (start at 1) and passes pred = bare roofline time for
+ *   the EMA variant or the statically calibrated time for the EMA+Calib variant.
+ * verify_cost_curve: the controller's cost curve (Eq. 6 denominator) for N = 1..N_max draft
+ *   nodes:  cost[N-1] = t_other + c_ema * (calib_scale * R(N + 1) + calib_offset),  R as in
+ *   btv_verify_cost with s = N + 1 (the verifier also processes the root); t_other =
+ *   T_draft + T_aux.  cost HOST [N_max]; copy it to the device for btv_tree_build_adaptive.
+ * ------------------------------------------------------------------------------------------- */
+int btv_calib_fit_linear(const double *pred, const double *obs, int n, double *calib_scale,
+                         double *calib_offset);
+int btv_calib_ema_update(double *c, double alpha, double obs, double pred);
+int btv_verify_cost_curve(int N_max, double c, double layers, double h, double nq, double nkv,
+                          double d, double hffn, double V, double bp, double peak_flops,
+                          double bandwidth, double calib_scale, double calib_offset, double c_ema,
+                          double t_other, double *cost);
+
+/* ---------------------------------------------------------------------------------------------
  * ancestor mask -- the verification mask of App. C ("Linearization and verification mask")
  * as a bitset: bit a of anc[i] is set iff a is i or an ancestor of i.
  * anc [M, BTV_ANC_WORDS] uint32, word w holds nodes 32w..32w+31.

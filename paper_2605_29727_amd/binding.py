@@ -21,7 +21,8 @@ BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "btv_last_error", "btv_version", "btv_workspace_status", "btv_tree_build_workspace", "btv_tree_build",
-    "btv_tree_build_adaptive", "btv_verify_cost", "btv_kv_commit", "btv_kv_commit_paged",
+    "btv_tree_build_adaptive", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
+    "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
     "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_set_attn_splits",
@@ -127,6 +128,34 @@ def btv_verify_cost(s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwi
     _check(lib().btv_verify_cost(*[C.c_double(float(x)) for x in (s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops,
                                                                   bandwidth, calib_scale, calib_offset)], out))
     return {"flops": out[0], "bytes": out[1], "roofline_s": out[2], "latency_s": out[3]}
+
+
+def btv_calib_fit_linear(pred, obs) -> tuple:
+    """Host-side static calibration: (calib_scale, calib_offset) of the least-squares line obs ~ scale * pred + offset."""
+    n = len(pred)
+    assert len(obs) == n
+    p = (C.c_double * n)(*[float(x) for x in pred])
+    o = (C.c_double * n)(*[float(x) for x in obs])
+    a, b = C.c_double(), C.c_double()
+    _check(lib().btv_calib_fit_linear(p, o, n, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def btv_calib_ema_update(c: float, alpha: float, obs: float, pred: float) -> float:
+    """Host-side online calibration: returns (1 - alpha) c + alpha obs / pred."""
+    cc = C.c_double(float(c))
+    _check(lib().btv_calib_ema_update(C.byref(cc), C.c_double(float(alpha)), C.c_double(float(obs)),
+                                      C.c_double(float(pred))))
+    return cc.value
+
+
+def btv_verify_cost_curve(N_max, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale=1.0,
+                          calib_offset=0.0, c_ema=1.0, t_other=0.0) -> list:
+    """Host-side cost curve C(N), N = 1..N_max, for btv_tree_build_adaptive (a list of floats)."""
+    out = (C.c_double * max(int(N_max), 1))()
+    _check(lib().btv_verify_cost_curve(int(N_max), *[C.c_double(float(x)) for x in (
+        c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale, calib_offset, c_ema, t_other)], out))
+    return [out[i] for i in range(int(N_max))]
 
 
 def btv_tree_ancestor_mask(parent, anc, ws) -> None:

@@ -58,4 +58,56 @@ int btv_verify_cost(double s, double c, double layers, double h, double nq, doub
     return BTV_OK;
 }
 
+// Static calibration (Sec. 5.2): least-squares line through (pred, obs), two passes (means, then centred moments).
+int btv_calib_fit_linear(const double *pred, const double *obs, int n, double *calib_scale, double *calib_offset)
+{
+    BTV_REQUIRE(pred != nullptr && obs != nullptr && calib_scale != nullptr && calib_offset != nullptr, "null pointer");
+    BTV_REQUIRE(n >= 2, "a line needs at least two points");
+    double sum_p = 0.0, sum_o = 0.0;
+    for (int i = 0; i < n; ++i) {
+        BTV_REQUIRE(std::isfinite(pred[i]) && std::isfinite(obs[i]), "non-finite sample");
+        sum_p += pred[i];
+        sum_o += obs[i];
+    }
+    const double mean_p = sum_p / n, mean_o = sum_o / n;
+    double var = 0.0, cov = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const double dp = pred[i] - mean_p;
+        var += dp * dp;
+        cov += dp * (obs[i] - mean_o);
+    }
+    BTV_REQUIRE(var > 0.0, "all predictions are equal: the slope is undetermined");
+    *calib_scale = cov / var;
+    *calib_offset = mean_o - (cov / var) * mean_p;
+    return BTV_OK;
+}
+
+// Online calibration (Sec. 5.2): exponential moving average of the observed / predicted latency ratio.
+int btv_calib_ema_update(double *c, double alpha, double obs, double pred)
+{
+    BTV_REQUIRE(c != nullptr, "null pointer");
+    BTV_REQUIRE(alpha >= 0.0 && alpha <= 1.0, "alpha outside [0, 1]");
+    BTV_REQUIRE(pred > 0.0 && obs >= 0.0 && std::isfinite(obs) && std::isfinite(pred), "latencies must be positive and finite");
+    *c = (1.0 - alpha) * *c + alpha * (obs / pred);
+    return BTV_OK;
+}
+
+// Cost curve for the budget controller (Eq. 6): C(N) = t_other + c_ema * (calibrated T_verify of N + 1 tokens).
+int btv_verify_cost_curve(int N_max, double c, double layers, double h, double nq, double nkv, double d, double hffn,
+                          double V, double bp, double peak_flops, double bandwidth, double calib_scale,
+                          double calib_offset, double c_ema, double t_other, double *cost)
+{
+    BTV_REQUIRE(cost != nullptr, "null pointer");
+    BTV_REQUIRE(N_max >= 0 && N_max <= BTV_MAX_NODES, "N_max outside [0, BTV_MAX_NODES]");
+    BTV_REQUIRE(std::isfinite(c_ema) && std::isfinite(t_other), "non-finite calibration state");
+    for (int n = 1; n <= N_max; ++n) {
+        double out[4];
+        const int rc = btv_verify_cost(n + 1.0, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale,
+                                       calib_offset, out);
+        if (rc != BTV_OK) return rc;
+        cost[n - 1] = t_other + c_ema * out[3];
+    }
+    return BTV_OK;
+}
+
 }  // extern "C"

@@ -105,3 +105,33 @@ def test_host_cost_model_matches_the_oracle(oracle):
         btv.btv_verify_cost(1, 1, 1, 0, 1, 1, 1, 1, 1, 1, 1.0, 1.0)          # zero hidden size
     with pytest.raises(btv.BtvError):
         btv.btv_verify_cost(1, 1, 1, 8, 1, 1, 1, 1, 1, 1, 0.0, 1.0)          # zero peak
+
+
+def test_host_calibration_matches_the_oracle(oracle):
+    """The calibration entry points (Sec. 5.2) and the controller's cost curve (Eq. 6) are host arithmetic only."""
+    import numpy as np
+    from paper_2605_29727_amd import binding as btv, synth
+    for seed in range(3):
+        pred = 1e-3 * (1.0 + 10.0 * synth.uniform(seed, "calib_pred", (30,)))
+        obs = 1.4 * pred + 3e-4 + 1e-4 * synth.uniform(seed, "calib_noise", (30,))
+        got, ref = btv.btv_calib_fit_linear(pred, obs), oracle.calib_fit(pred, obs)
+        assert got[0] == pytest.approx(ref[0], rel=1e-11) and got[1] == pytest.approx(ref[1], rel=1e-11)
+    with pytest.raises(btv.BtvError):
+        btv.btv_calib_fit_linear([2.0, 2.0], [1.0, 3.0])
+    with pytest.raises(btv.BtvError):
+        btv.btv_calib_fit_linear([2.0], [1.0])
+    c_lib = c_orc = 1.0
+    for i in range(20):
+        obs, pred = 2.0 + 0.1 * i, 1.5 + 0.05 * i
+        c_lib, c_orc = btv.btv_calib_ema_update(c_lib, 0.2, obs, pred), oracle.calib_ema(c_orc, 0.2, obs, pred)
+        assert c_lib == pytest.approx(c_orc, rel=1e-14)
+    with pytest.raises(btv.BtvError):
+        btv.btv_calib_ema_update(1.0, 1.5, 1.0, 1.0)                           # alpha outside [0, 1]
+    with pytest.raises(btv.BtvError):
+        btv.btv_calib_ema_update(1.0, 0.5, 1.0, 0.0)                           # zero prediction
+    args = (8192, 32, 4096, 32, 8, 128, 14336, 128256, 2, 2.5e15, 8e12, 1.3, 2e-4, 0.9, 1e-3)
+    got, ref = np.array(btv.btv_verify_cost_curve(256, *args)), oracle.cost_curve(256, *args)
+    assert np.allclose(got, ref, rtol=1e-14, atol=0)
+    assert btv.btv_verify_cost_curve(0, *args) == []
+    with pytest.raises(btv.BtvError):
+        btv.btv_verify_cost_curve(257, *args)
