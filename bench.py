@@ -272,7 +272,7 @@ def main():
             ms = time_loop(torch, pn.attn, args.steps, args.warmup)
             abn, fln = algorithmic_bytes(L, n, Hq, Hkv, D), algorithmic_flops(L, n, Hq, D, pn.depth_sum)
             t_hbm, t_mfma = abn / (HBM_PEAK_GBPS * 1e9), fln / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-            curve.append({"N": n, "attn_us": round(ms * 1e3, 3), "GBps": round(abn / (ms * 1e-3) / 1e9, 1),
+            curve.append({"N": n, "attn_us": round(ms * 1e3, 3), "roofline_us": round(max(t_hbm, t_mfma) * 1e6, 3), "GBps": round(abn / (ms * 1e-3) / 1e9, 1),
                           "frac_hbm": round(abn / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                           "tflops": round(fln / (ms * 1e-3) / 1e12, 1),
                           "frac_roofline": round(max(t_hbm, t_mfma) / (ms * 1e-3), 4),
@@ -283,14 +283,14 @@ def main():
     # Static and online calibration (Sec. 5.2) of the attention layer's roofline prediction against the curve above
     calib = None
     if len(curve) >= 2:
-        pred = [algorithmic_bytes(L, c["N"], Hq, Hkv, D) / (HBM_PEAK_GBPS * 1e9) * 1e6 for c in curve]
+        pred = [c["roofline_us"] for c in curve]
         obs = [c["attn_us"] for c in curve]
         a, b = btv.btv_calib_fit_linear(pred, obs)
         ema = 1.0
         for p_, o_ in zip(pred, obs):
             ema = btv.btv_calib_ema_update(ema, 0.3, o_, p_)
         rmse = lambda f: round((sum((o_ - f(p_)) ** 2 for p_, o_ in zip(pred, obs)) / len(obs)) ** 0.5, 3)
-        calib = {"what": "tree_verify_attn us vs its HBM-roofline time, N = 16..256", "calib_scale": round(a, 4),
+        calib = {"what": "tree_verify_attn us vs its roofline time max(bytes/HBM peak, flops/MFMA peak), N = 16..256", "calib_scale": round(a, 4),
                  "calib_offset_us": round(b, 3), "rmse_raw_us": rmse(lambda x: x), "rmse_static_us": rmse(lambda x: a * x + b),
                  "ema_bias_alpha0.3": round(ema, 4)}
 
