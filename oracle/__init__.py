@@ -209,6 +209,20 @@ def accept_greedy(logits_f32, parent, token) -> dict:
     return {"n_acc": n, "path": path[:n].copy(), "bonus": int(bonus.value), "argmax": t}
 
 
+def lm_head_argmax(hidden_f32, W_f32, nthreads: int = 0) -> dict:
+    """Target tokens from hidden states (App. E LM head + App. C top-1): argmax_v of hidden @ W^T in fp64."""
+    x = np.ascontiguousarray(hidden_f32, dtype=np.float32)
+    w = np.ascontiguousarray(W_f32, dtype=np.float32)
+    R, h = x.shape
+    V = w.shape[0]
+    assert w.shape[1] == h
+    t = np.empty(R, dtype=np.int32)
+    margin = np.empty(R, dtype=np.float64)
+    _load().orc_lm_head_argmax(_p(x, C.c_float), _p(w, C.c_float), R, h, V, _p(t, C.c_int32), _p(margin, C.c_double),
+                               int(nthreads) if nthreads else num_threads())
+    return {"argmax": t, "margin": margin}
+
+
 def accept_stochastic(logits_f32, marg, parent, token, depth, uniforms) -> dict:
     """Token-level rejection walk at temperature 1 (the reading stated in the C file)."""
     x = np.ascontiguousarray(logits_f32, dtype=np.float32)

@@ -23,6 +23,7 @@
  *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
  *   orc_ancestor_mask    reachability by explicit path enumeration
  *   orc_accept_greedy    brute force over all root-to-node paths, planted paths
+ *   orc_lm_head_argmax   library matrix product + argmax (numpy, fp64), planted winners, exact ties, one-hot rows
  *   orc_accept_stochastic  closed-form special cases and an empirical chi-square test of the
  *                        single-child case; the multi-child rule is not given by the paper:
  *                        parity unpinned beyond those cases.
@@ -329,6 +330,37 @@ void orc_row_argmax(const float *logits, int rows, int V, int32_t *t)
         for (int v = 1; v < V; ++v)
             if (x[v] > x[best]) best = v;
         t[r] = best;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Target tokens straight from the final hidden states (the LM head of App. E, 2*s*h*V FLOPs, followed by the
+ * top-1 of App. C "Acceptance"):  logit[r, v] = sum_k hidden[r, k] * W[v, k],  t[r] = argmax_v logit[r, v], lowest
+ * v on ties.  hidden [R, h] and W [V, h] are fp32 arrays holding the exact stored values (bf16-rounded when the
+ * HIP path runs in bf16); every logit is accumulated in fp64 in index order.  margin[r] (optional) = best logit
+ * minus the best logit of any other token (0 on an exact tie): rows with a margin below the other side's rounding
+ * error have no unique answer and parity tests leave them out.
+ * ---------------------------------------------------------------------------------------- */
+void orc_lm_head_argmax(const float *hidden, const float *W, int R, int h, int V, int32_t *t, double *margin,
+                        int nthreads)
+{
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+#endif
+    for (int r = 0; r < R; ++r) {
+        const float *x = hidden + (size_t)r * h;
+        double best = -INFINITY, second = -INFINITY;
+        int arg = 0;
+        for (int v = 0; v < V; ++v) {
+            const float *w = W + (size_t)v * h;
+            double z = 0.0;
+            for (int k = 0; k < h; ++k) z += (double)x[k] * (double)w[k];
+            if (z > best) { second = best; best = z; arg = v; }
+            else if (z > second) second = z;
+        }
+        t[r] = arg;
+        if (margin) margin[r] = (V > 1) ? best - second : INFINITY;
     }
 }
 

@@ -133,6 +133,32 @@ def target_logits(seed: int, rows: int, V: int, sigma: float, dtype: str, tag: s
     return st, f
 
 
+def lm_head(seed: int, rows: int, h: int, V: int, dtype: str = "bf16", tag: str = "lmhead", chunk: int = 8192):
+    """Final hidden states [rows, h] ~ N(0,1) and LM-head weights [V, h] ~ N(0, 1/h), each rounded once to `dtype`.
+    Returns (hidden storage, hidden fp32, W storage, W fp32); W is generated `chunk` vocabulary rows at a time."""
+    hs, hf = round_to_dtype(normal(seed, tag + "_x", (rows, h)), dtype)
+    ws = np.empty((V, h), dtype=hs.dtype)
+    wf = np.empty((V, h), dtype=np.float32)
+    for v0 in range(0, V, chunk):
+        v1 = min(v0 + chunk, V)
+        z = normal(seed, f"{tag}_w{v0}", (v1 - v0, h), 1.0 / np.sqrt(h))
+        ws[v0:v1], wf[v0:v1] = round_to_dtype(z, dtype)
+    return hs, hf, ws, wf
+
+
+def plant_hidden(hidden_f32: np.ndarray, W_f32: np.ndarray, parent: np.ndarray, token: np.ndarray, leaf: int,
+                 boost: float = 12.0) -> np.ndarray:
+    """Turn the hidden state at the parent's row of every node on the root-to-`leaf` path towards that node's
+    LM-head row, so that the target's top-1 token there is the node's token (row 0 = root, row 1+i = node i)."""
+    out = hidden_f32.astype(np.float64).copy()
+    i = int(leaf)
+    while i >= 0:
+        w = W_f32[int(token[i])].astype(np.float64)
+        out[int(parent[i]) + 1] += boost * w / max(float(np.sqrt((w * w).sum())), 1e-30) * np.sqrt(out.shape[1])
+        i = int(parent[i])
+    return out
+
+
 # ----------------------------------------------------------------------------------------------
 # tree shapes for property tests (parent[i] in {-1} u [0, i); -1 = child of the root)
 # ----------------------------------------------------------------------------------------------
