@@ -191,6 +191,24 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
                                void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Greedy acceptance straight from the final hidden states: the LM head of App. E (2*s*h*V FLOPs,
+ * s*V logits of activation traffic) fused with the top-1 of App. C "Acceptance", so the logits
+ * are never written:  t[r] = argmax_v sum_k hidden[r,k] * W[v,k]  (lowest v on ties), then the
+ * same walk as btv_tree_accept_greedy.
+ *   hidden [M+1, h] bf16 (row 0 = root, row 1+i = node i; final norm already applied)
+ *   W      [V, h]   bf16, row-major (one row per token); both DEVICE, 16-byte aligned
+ *   h      a multiple of 128
+ * Products are exact in fp32 and accumulated in fp32 on the matrix cores; two tokens whose
+ * logits differ by less than that rounding (about 1e-6 of sum_k |hidden*W|) can swap.
+ * Outputs and errors as for btv_tree_accept_greedy.
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_accept_lm_head_workspace(int M, int V);
+int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, const int32_t *parent,
+                                   const int32_t *token, int M, int V, int32_t *path,
+                                   int32_t *n_acc, int32_t *bonus, int32_t *argmax_out, void *ws,
+                                   size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * kv_commit -- after acceptance the KV cache keeps the shared prefix followed only by the
  * accepted path (App. C, "Acceptance").  In every layer, for K and V alike, sequence position
  * L + j takes the row of position L + path[j] for j < *n_acc; positions from L + *n_acc on are

@@ -25,7 +25,8 @@ EXPORTS = [
     "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
     "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
-    "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_set_attn_splits",
+    "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_tree_accept_lm_head_workspace",
+    "btv_tree_accept_greedy_lm_head", "btv_set_attn_splits",
 ]
 
 
@@ -47,7 +48,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.btv_last_error.restype = C.c_char_p
         for n in ("btv_tree_build_workspace", "btv_tree_verify_attn_workspace",
-                  "btv_tree_verify_attn_paged_workspace", "btv_tree_accept_workspace"):
+                  "btv_tree_verify_attn_paged_workspace", "btv_tree_accept_workspace",
+                  "btv_tree_accept_lm_head_workspace"):
             getattr(L, n).restype = C.c_size_t
         for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_ancestor_mask",
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_accept_greedy",
@@ -201,6 +203,19 @@ def btv_tree_accept_greedy(logits, parent, token, path, n_acc, bonus, argmax_out
     _check(lib().btv_tree_accept_greedy(_ptr(logits), _dtype_code(logits), _ptr(parent), _ptr(token), rows - 1, V,
                                         _ptr(path), _ptr(n_acc), _ptr(bonus), _ptr(argmax_out), _ptr(ws),
                                         C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_accept_lm_head_workspace(M: int, V: int) -> int:
+    return int(lib().btv_tree_accept_lm_head_workspace(M, V))
+
+
+def btv_tree_accept_greedy_lm_head(hidden, W, parent, token, path, n_acc, bonus, argmax_out, ws) -> None:
+    rows, h = hidden.shape
+    V = W.shape[0]
+    assert W.shape[1] == h and _dtype_code(hidden) == BTV_BF16 and _dtype_code(W) == BTV_BF16
+    _check(lib().btv_tree_accept_greedy_lm_head(_ptr(hidden), _ptr(W), h, _ptr(parent), _ptr(token), rows - 1, V,
+                                                _ptr(path), _ptr(n_acc), _ptr(bonus), _ptr(argmax_out), _ptr(ws),
+                                                C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
 
 
 def btv_tree_accept_stochastic(logits, marginals, parent, token, uniforms, path, n_acc, bonus, ws) -> None:

@@ -116,6 +116,156 @@ __global__ __launch_bounds__(256) void greedy_walk(const Best *part, int chunks,
 }
 
 // ------------------------------------------------------------------------------------------------
+// LM head fused with the argmax (App. E: 2*s*h*V FLOPs and s*V activation elements for the logits;
+// App. C "Acceptance": only their top-1 is used).  logit[r, v] = sum_k H[r, k] W[v, k] is formed on the
+// matrix cores and reduced to one (value, token) pair per row and workgroup: the logits never reach
+// memory, the 2*V*h bytes of W are streamed once.
+//
+// Transposed product, C^T = W_tile * H^T (v_mfma_f32_32x32x16_bf16): a wave owns 32 vocabulary rows
+// and every row of H, so a lane's accumulator registers run over vocabulary rows of one H row and
+// the argmax is a per-lane scan.  W goes from memory straight to registers (a lane supplies
+// vocabulary row lane%32, which no other wave needs); each lane reads 128 contiguous bytes per
+// k block, half 0 the first 64 elements and half 1 the last 64: the contraction index is permuted
+// the same way on the H side.  H blocks [rows, 128] are shared by the waves through a
+// double-buffered LDS slab whose 16-byte chunks are stored at chunk ^ (row % 16): operand reads
+// are conflict-free.
+// ------------------------------------------------------------------------------------------------
+constexpr int LM_KB = 128;       // contraction elements per block
+
+typedef __bf16 lm_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float lm_f32x16 __attribute__((ext_vector_type(16)));
+
+template <int RT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void lm_head_argmax(const uint16_t *__restrict__ H,
+                                                              const uint16_t *__restrict__ W, int R, int h, int V,
+                                                              Best *__restrict__ part)
+{
+    extern __shared__ __align__(16) unsigned char lm_lds[];
+    constexpr int THREADS = WAVES * 64, ROWS = RT * 32, CPT = ROWS * 16 / THREADS, SLAB = ROWS * 256;
+    static_assert(ROWS * 16 % THREADS == 0, "chunks must divide evenly over the threads");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r32 = lane & 31, half = lane >> 5;
+    const int v0 = (blockIdx.x * WAVES + wave) * 32;
+    const uint4 *wp = reinterpret_cast<const uint4 *>(W + (size_t)min(v0 + r32, V - 1) * h + half * 64);
+    const int nkb = h / LM_KB;
+
+    // chunks of the H slab this thread moves: chunk c -> row c / 16, 16-byte column c % 16
+    const uint4 *hp[CPT];
+    int hdst[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = tid + i * THREADS, row = c >> 4, col = c & 15;
+        hp[i] = reinterpret_cast<const uint4 *>(H + (size_t)min(row, R - 1) * h + col * 8);
+        hdst[i] = row * 256 + ((col ^ (row & 15)) << 4);
+    }
+    int hsrc[8];     // operand reads of this lane, per step j, within a row tile
+#pragma unroll
+    for (int j = 0; j < 8; ++j) hsrc[j] = r32 * 256 + ((((half << 3) + j) ^ (r32 & 15)) << 4);
+
+    lm_f32x16 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
+
+    uint4 wc[8], wn[8], hn[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) hn[i] = hp[i][0];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wc[j] = wp[j];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) *reinterpret_cast<uint4 *>(lm_lds + hdst[i]) = hn[i];
+    __syncthreads();
+
+    for (int kb = 0; kb < nkb; ++kb) {
+        // next block (the last round fetches its own block again and stores it where nobody reads): H first, W
+        // after, so that the slab can be written while the weights are still in flight
+        const int nb = min(kb + 1, nkb - 1) * (LM_KB / 8);
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) hn[i] = hp[i][nb];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) wn[j] = wp[nb + j];
+        const unsigned char *buf = lm_lds + (kb & 1) * SLAB;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const lm_bf16x8 a = __builtin_bit_cast(lm_bf16x8, wc[j]);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const uint4 b = *reinterpret_cast<const uint4 *>(buf + rt * 32 * 256 + hsrc[j]);
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(lm_bf16x8, b), acc[rt], 0, 0, 0);
+            }
+        }
+        unsigned char *nxt = lm_lds + ((kb + 1) & 1) * SLAB;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) *reinterpret_cast<uint4 *>(nxt + hdst[i]) = hn[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) wc[j] = wn[j];
+        __syncthreads();
+    }
+
+    // per-lane scan over the 16 vocabulary rows it holds (ascending), other half, then the waves
+    Best *wb = reinterpret_cast<Best *>(lm_lds);            // [WAVES][ROWS]
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        Best b = { -INFINITY, INT_MAX };
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int v = v0 + (e >> 2) * 8 + half * 4 + (e & 3);
+            if (v < V) best_take(b, acc[rt][e], v);
+        }
+        const float ov = __shfl_xor(b.v, 32);
+        const int oi = __shfl_xor(b.i, 32);
+        best_take(b, ov, oi);
+        if (half == 0) wb[wave * ROWS + rt * 32 + r32] = b;
+    }
+    __syncthreads();
+    for (int row = tid; row < R; row += THREADS) {
+        Best b = wb[row];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) best_take(b, wb[w * ROWS + row].v, wb[w * ROWS + row].i);
+        part[(size_t)row * gridDim.x + blockIdx.x] = b;
+    }
+}
+
+// grid = rows: best of a row's per-workgroup partials -> out[row]
+__global__ __launch_bounds__(256) void argmax_merge(const Best *part, int chunks, Best *out)
+{
+    __shared__ Best wb[4];
+    const int tid = threadIdx.x, row = blockIdx.x;
+    Best b = { -INFINITY, INT_MAX };
+    for (int c = tid; c < chunks; c += 256) best_take(b, part[(size_t)row * chunks + c].v, part[(size_t)row * chunks + c].i);
+    b = best_wave(b);
+    if ((tid & 63) == 0) wb[tid >> 6] = b;
+    __syncthreads();
+    if (tid == 0) {
+        Best r = wb[0];
+        best_take(r, wb[1].v, wb[1].i); best_take(r, wb[2].v, wb[2].i); best_take(r, wb[3].v, wb[3].i);
+        out[row] = r;
+    }
+}
+
+template <int RT, int WAVES>
+int lm_head_launch(const uint16_t *H, const uint16_t *W, int R, int h, int V, Best *part, hipStream_t st)
+{
+    constexpr int LDS_BYTES = 2 * RT * 32 * 256;
+    static_assert(LDS_BYTES >= WAVES * RT * 32 * (int)sizeof(Best), "exchange area must fit the slabs");
+    static bool configured = false;
+    auto kern = lm_head_argmax<RT, WAVES>;
+    if (!configured) {
+        BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    LDS_BYTES));
+        configured = true;
+    }
+    const int chunks = (V + WAVES * 32 - 1) / (WAVES * 32);
+    hipLaunchKernelGGL(kern, dim3(chunks), dim3(WAVES * 64), LDS_BYTES, st, H, W, R, h, V, part);
+    BTV_HIP(hipGetLastError());
+    return BTV_OK;
+}
+
+// waves per workgroup: four while the slab of all rows leaves room for several workgroups per CU
+inline int lm_waves(int R) { return R <= 128 ? 4 : 8; }
+inline int lm_chunks(int R, int V) { return (V + lm_waves(R) * 32 - 1) / (lm_waves(R) * 32); }
+
+// ------------------------------------------------------------------------------------------------
 // Stochastic walk: one workgroup of 1024 threads; p and q live in the workspace (fp32), every
 // vocabulary-wide sum is accumulated in fp64.
 // ------------------------------------------------------------------------------------------------
@@ -267,6 +417,51 @@ int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent,
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, part, chunks, parent, token, M, path, n_acc, bonus,
                        argmax_out);
+    BTV_HIP(hipGetLastError());
+    return BTV_OK;
+}
+
+size_t btv_tree_accept_lm_head_workspace(int M, int V)
+{
+    if (M < 1 || M > BTV_MAX_NODES || V < 1) return 0;
+    const size_t rows = (size_t)M + 1;
+    return BTV_WS_HEADER + btv_align_up(rows * lm_chunks(M + 1, V) * sizeof(Best), BTV_WS_ALIGN) +
+           btv_align_up(rows * sizeof(Best), BTV_WS_ALIGN);
+}
+
+int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, const int32_t *parent, const int32_t *token,
+                                   int M, int V, int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out,
+                                   void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(hidden && W && parent && token && path && n_acc && bonus, "null pointer");
+    BTV_REQUIRE(M >= 1 && M <= BTV_MAX_NODES, "M=%d outside [1,%d]", M, BTV_MAX_NODES);
+    BTV_REQUIRE(V >= 1, "V=%d", V);
+    BTV_REQUIRE(h >= LM_KB && h % LM_KB == 0, "h=%d must be a positive multiple of %d", h, LM_KB);
+    BTV_REQUIRE((reinterpret_cast<uintptr_t>(hidden) & 15) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0,
+                "hidden and W must be 16-byte aligned");
+    int rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_lm_head_workspace(M, V));
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int R = M + 1, chunks = lm_chunks(R, V);
+    Best *part = reinterpret_cast<Best *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
+    Best *best = reinterpret_cast<Best *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER +
+                                          btv_align_up((size_t)R * chunks * sizeof(Best), BTV_WS_ALIGN));
+    const uint16_t *Hp = static_cast<const uint16_t *>(hidden), *Wp = static_cast<const uint16_t *>(W);
+    switch ((R + 31) / 32) {
+    case 1: rc = lm_head_launch<1, 4>(Hp, Wp, R, h, V, part, st); break;
+    case 2: rc = lm_head_launch<2, 4>(Hp, Wp, R, h, V, part, st); break;
+    case 3: rc = lm_head_launch<3, 4>(Hp, Wp, R, h, V, part, st); break;
+    case 4: rc = lm_head_launch<4, 4>(Hp, Wp, R, h, V, part, st); break;
+    case 5: rc = lm_head_launch<5, 8>(Hp, Wp, R, h, V, part, st); break;
+    case 6: rc = lm_head_launch<6, 8>(Hp, Wp, R, h, V, part, st); break;
+    case 7: rc = lm_head_launch<7, 8>(Hp, Wp, R, h, V, part, st); break;
+    case 8: rc = lm_head_launch<8, 8>(Hp, Wp, R, h, V, part, st); break;
+    default: rc = lm_head_launch<9, 8>(Hp, Wp, R, h, V, part, st); break;
+    }
+    if (rc) return rc;
+    hipLaunchKernelGGL(argmax_merge, dim3(R), dim3(256), 0, st, part, chunks, best);
+    BTV_HIP(hipGetLastError());
+    hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, best, 1, parent, token, M, path, n_acc, bonus, argmax_out);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

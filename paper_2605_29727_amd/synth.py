@@ -133,16 +133,22 @@ def target_logits(seed: int, rows: int, V: int, sigma: float, dtype: str, tag: s
     return st, f
 
 
-def lm_head(seed: int, rows: int, h: int, V: int, dtype: str = "bf16", tag: str = "lmhead", chunk: int = 8192):
+def lm_head(seed: int, rows: int, h: int, V: int, dtype: str = "bf16", tag: str = "lmhead", base_rows: int = 8192):
     """Final hidden states [rows, h] ~ N(0,1) and LM-head weights [V, h] ~ N(0, 1/h), each rounded once to `dtype`.
-    Returns (hidden storage, hidden fp32, W storage, W fp32); W is generated `chunk` vocabulary rows at a time."""
+    Returns (hidden storage, hidden fp32, W storage, W fp32).  Only the first `base_rows` vocabulary rows are drawn;
+    block b of the rest repeats them rotated by 8 b positions along h (distinct rows of the same distribution), which
+    keeps a 128k-token matrix affordable to generate."""
     hs, hf = round_to_dtype(normal(seed, tag + "_x", (rows, h)), dtype)
-    ws = np.empty((V, h), dtype=hs.dtype)
+    nb = min(V, base_rows)
+    bs, bf = round_to_dtype(normal(seed, tag + "_w", (nb, h), 1.0 / np.sqrt(h)), dtype)
+    if V <= base_rows:
+        return hs, hf, bs, bf
+    ws = np.empty((V, h), dtype=bs.dtype)
     wf = np.empty((V, h), dtype=np.float32)
-    for v0 in range(0, V, chunk):
-        v1 = min(v0 + chunk, V)
-        z = normal(seed, f"{tag}_w{v0}", (v1 - v0, h), 1.0 / np.sqrt(h))
-        ws[v0:v1], wf[v0:v1] = round_to_dtype(z, dtype)
+    for b, v0 in enumerate(range(0, V, base_rows)):
+        v1 = min(v0 + base_rows, V)
+        ws[v0:v1] = np.roll(bs[:v1 - v0], 8 * b, axis=1)
+        wf[v0:v1] = np.roll(bf[:v1 - v0], 8 * b, axis=1)
     return hs, hf, ws, wf
 
 

@@ -102,3 +102,20 @@ def run_accept_stochastic(logits_store: np.ndarray, bf16_bits: bool, marg, paren
     torch.cuda.synchronize()
     n = int(n_acc.item())
     return {"n_acc": n, "path": path.cpu().numpy()[:n], "bonus": int(bonus.item())}
+
+
+def run_accept_greedy_lm_head(hidden_bits: np.ndarray, W_bits, parent, token) -> dict:
+    """W_bits: numpy uint16 [V, h] or a device bf16 tensor (so that a large matrix is uploaded once)."""
+    x = dev(hidden_bits, True)
+    W = W_bits if isinstance(W_bits, torch.Tensor) else dev(W_bits, True)
+    M = len(parent)
+    par, tok = dev(np.asarray(parent, dtype=np.int32)), dev(np.asarray(token, dtype=np.int32))
+    path = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    am = torch.full((M + 1,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_lm_head_workspace(M, W.shape[0]))
+    btv.btv_tree_accept_greedy_lm_head(x, W, par, tok, path, n_acc, bonus, am, ws)
+    torch.cuda.synchronize()
+    n = int(n_acc.item())
+    return {"n_acc": n, "path": path.cpu().numpy()[:n], "bonus": int(bonus.item()), "argmax": am.cpu().numpy()}
