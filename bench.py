@@ -242,6 +242,25 @@ def main():
         del Kc, Vc
     except RuntimeError as e:        # not enough memory beside the KV ring
         kvc = {"kv_commit_us": None, "error": str(e)[:80]}
+    # greedy acceptance straight from hidden states (LM head fused with the argmax), 8B shape: h = 4096
+    lmh = {}
+    try:
+        hdim = 4096
+        Wl = torch.randn((V, hdim), dtype=torch.float32, device="cuda").mul_(hdim ** -0.5).to(torch.bfloat16)
+        Xl = torch.randn((N + 1, hdim), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+        ws_l = btv.alloc_workspace(btv.btv_tree_accept_lm_head_workspace(N, V))
+        lm_ms = time_loop(torch, lambda: btv.btv_tree_accept_greedy_lm_head(Xl, Wl, path.parent, path.token, path.path,
+                                                                            path.n_acc, path.bonus, None, ws_l),
+                          max(args.steps // 4, 5), max(args.warmup // 4, 2))
+        lm_bytes = 2 * V * hdim + 2 * (N + 1) * hdim
+        lm_flops = 2 * (N + 1) * hdim * V
+        lmh = {"accept_greedy_lm_head_us": round(lm_ms * 1e3, 3), "h": hdim, "algorithmic_bytes": lm_bytes,
+               "GBps": round(lm_bytes / (lm_ms * 1e-3) / 1e9, 1),
+               "frac_hbm": round(lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+               "tflops": round(lm_flops / (lm_ms * 1e-3) / 1e12, 1)}
+        del Wl, Xl
+    except RuntimeError as e:
+        lmh = {"accept_greedy_lm_head_us": None, "error": str(e)[:80]}
     path.setup_adaptive(256)
     adaptive_ms = time_loop(torch, path.build_adaptive, args.steps, args.warmup)
     adaptive = {"tree_build_adaptive_us": round(adaptive_ms * 1e3, 3), "N_max": 256, "N_star": int(path.ad_n.item()),
@@ -309,7 +328,7 @@ def main():
         "step_breakdown_us": {"tree_build": round(build_ms * 1e3, 3), "tree_verify_attn": round(attn_ms * 1e3, 3),
                               "tree_accept_greedy": round(accept_ms * 1e3, 3), "host_wall_per_step": round(wall_ms * 1e3, 3)},
         "roofline": roofline, "cpu_baseline": cpu, "curve_L8192": curve, "adaptive_budget": adaptive, "latency_calibration": calib,
-        "kv_commit": kvc,
+        "kv_commit": kvc, "lm_head": lmh,
         "context": "paper reports only end-to-end speedups (6.61x over autoregressive decoding, Qwen3-8B, A100) and a "
                    "whole-model T_verify of 22.0 ms at |T|=32 to 55.9 ms at |T|=1024; no number for this path exists",
     }

@@ -123,43 +123,73 @@ __global__ __launch_bounds__(256) void greedy_walk(const Best *part, int chunks,
 //
 // Transposed product, C^T = W_tile * H^T (v_mfma_f32_32x32x16_bf16): a wave owns 32 vocabulary rows
 // and every row of H, so a lane's accumulator registers run over vocabulary rows of one H row and
-// the argmax is a per-lane scan.  W goes from memory straight to registers (a lane supplies
-// vocabulary row lane%32, which no other wave needs); each lane reads 128 contiguous bytes per
-// k block, half 0 the first 64 elements and half 1 the last 64: the contraction index is permuted
-// the same way on the H side.  H blocks [rows, 128] are shared by the waves through a
-// double-buffered LDS slab whose 16-byte chunks are stored at chunk ^ (row % 16): operand reads
-// are conflict-free.
+// the argmax is a per-lane scan.  The operand layout wants lane l to hold row l % 32, which as a
+// direct load would touch 64 cache lines per instruction and use 16 bytes of each; instead every
+// load instruction fetches four whole 256-byte row segments (16 lanes per row), and the block is
+// turned round through a wave-private LDS tile.  H blocks [rows, KB] are shared by the waves through
+// a double-buffered LDS slab.  All tiles store the 16-byte chunks of a row XOR-permuted by the row
+// number, so operand reads (ds_read_b128, 16 lanes = 16 different rows) are conflict-free.
 // ------------------------------------------------------------------------------------------------
-constexpr int LM_KB = 128;       // contraction elements per block
-
 typedef __bf16 lm_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float lm_f32x16 __attribute__((ext_vector_type(16)));
 
-template <int RT, int WAVES>
+template <int RT, int WAVES, int KB>
+struct LmShape {
+    static constexpr int THREADS = WAVES * 64, ROWS = RT * 32;
+    static constexpr int RB = KB * 2;                     // bytes of a tile row
+    static constexpr int CPR = RB / 16;                   // 16-byte chunks per row
+    static constexpr int WTILE = 32 * RB, SLAB = ROWS * RB;
+    static constexpr int LDS_BYTES = WAVES * WTILE + 2 * SLAB;
+    static constexpr int WLD = 32 * CPR / 64;             // load instructions per wave and block for W
+    static constexpr int HLD = (ROWS * CPR + THREADS - 1) / THREADS;   // chunks of the H slab per thread and block
+    static constexpr bool HEVEN = ROWS * CPR % THREADS == 0;
+    static_assert(CPR == 8 || CPR == 16, "KB is 64 or 128");
+    // byte offset of 16-byte chunk `col` of tile row `row`: 16 lanes reading one chunk index of 16 consecutive
+    // rows must land in 16 different 16-byte bank groups of the 256-byte bank line
+    __device__ static constexpr int at(int row, int col)
+    {
+        return row * RB + ((col ^ (CPR == 16 ? (row & 15) : ((row >> 1) & 7))) << 4);
+    }
+};
+
+template <int RT, int WAVES, int KB>
 __global__ __launch_bounds__(WAVES * 64) void lm_head_argmax(const uint16_t *__restrict__ H,
                                                               const uint16_t *__restrict__ W, int R, int h, int V,
                                                               Best *__restrict__ part)
 {
+    using S = LmShape<RT, WAVES, KB>;
     extern __shared__ __align__(16) unsigned char lm_lds[];
-    constexpr int THREADS = WAVES * 64, ROWS = RT * 32, CPT = ROWS * 16 / THREADS, SLAB = ROWS * 256;
-    static_assert(ROWS * 16 % THREADS == 0, "chunks must divide evenly over the threads");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r32 = lane & 31, half = lane >> 5;
     const int v0 = (blockIdx.x * WAVES + wave) * 32;
-    const uint4 *wp = reinterpret_cast<const uint4 *>(W + (size_t)min(v0 + r32, V - 1) * h + half * 64);
-    const int nkb = h / LM_KB;
+    unsigned char *wtile = lm_lds + wave * S::WTILE;
+    unsigned char *slab = lm_lds + WAVES * S::WTILE;
+    const int nkb = h / KB;
 
-    // chunks of the H slab this thread moves: chunk c -> row c / 16, 16-byte column c % 16
-    const uint4 *hp[CPT];
-    int hdst[CPT];
+    // W: instruction i moves rows i*(64/CPR) .. of the wave's tile, CPR lanes per row
+    constexpr int RPI = 64 / S::CPR;                       // rows per load instruction
+    const int wcol = lane % S::CPR, wrow0 = lane / S::CPR;
+    const uint4 *wp[S::WLD];
+    int wdst[S::WLD];
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-        const int c = tid + i * THREADS, row = c >> 4, col = c & 15;
-        hp[i] = reinterpret_cast<const uint4 *>(H + (size_t)min(row, R - 1) * h + col * 8);
-        hdst[i] = row * 256 + ((col ^ (row & 15)) << 4);
+    for (int i = 0; i < S::WLD; ++i) {
+        const int row = i * RPI + wrow0;
+        wp[i] = reinterpret_cast<const uint4 *>(W + (size_t)min(v0 + row, V - 1) * h + wcol * 8);
+        wdst[i] = S::at(row, wcol);
     }
-    int hsrc[8];     // operand reads of this lane, per step j, within a row tile
+    // H: chunk c of the slab -> row c / CPR, column c % CPR
+    const uint4 *hp[S::HLD];
+    int hdst[S::HLD];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) hsrc[j] = r32 * 256 + ((((half << 3) + j) ^ (r32 & 15)) << 4);
+    for (int i = 0; i < S::HLD; ++i) {
+        const int c = tid + i * S::THREADS, row = c / S::CPR, col = c % S::CPR;
+        hp[i] = reinterpret_cast<const uint4 *>(H + (size_t)min(row, R - 1) * h + col * 8);
+        hdst[i] = S::at(row, col);
+        if (!S::HEVEN && row >= S::ROWS) hdst[i] = -1;    // past the slab: fetched (row clamped), never stored
+    }
+    // operand reads: step j of a block uses chunk 2j + half of row r32 (same chunk on both sides)
+    int osrc[KB / 16];
+#pragma unroll
+    for (int j = 0; j < KB / 16; ++j) osrc[j] = S::at(r32, 2 * j + half);
 
     lm_f32x16 acc[RT];
 #pragma unroll
@@ -167,43 +197,54 @@ __global__ __launch_bounds__(WAVES * 64) void lm_head_argmax(const uint16_t *__r
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
 
-    uint4 wc[8], wn[8], hn[CPT];
+    // Workgroups start at different blocks of the contraction and wrap round: rows of W are a multiple of 4 KB
+    // apart, so workgroups marching in step would all hit the same few memory channels.
+    int cur = (blockIdx.x * 5) % nkb;
+    uint4 wn[S::WLD], hn[S::HLD];
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) hn[i] = hp[i][0];
+    for (int i = 0; i < S::HLD; ++i) hn[i] = hp[i][cur * (KB / 8)];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) wc[j] = wp[j];
+    for (int i = 0; i < S::WLD; ++i) wn[i] = wp[i][cur * (KB / 8)];
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) *reinterpret_cast<uint4 *>(lm_lds + hdst[i]) = hn[i];
+    for (int i = 0; i < S::HLD; ++i)
+        if (S::HEVEN || hdst[i] >= 0) *reinterpret_cast<uint4 *>(slab + hdst[i]) = hn[i];
+#pragma unroll
+    for (int i = 0; i < S::WLD; ++i) *reinterpret_cast<uint4 *>(wtile + wdst[i]) = wn[i];
     __syncthreads();
 
     for (int kb = 0; kb < nkb; ++kb) {
-        // next block (the last round fetches its own block again and stores it where nobody reads): H first, W
-        // after, so that the slab can be written while the weights are still in flight
-        const int nb = min(kb + 1, nkb - 1) * (LM_KB / 8);
+        // next block into registers (the last round fetches the first block again; it lands where nobody reads)
+        cur = cur + 1 == nkb ? 0 : cur + 1;
+        const int nb = cur * (KB / 8);
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) hn[i] = hp[i][nb];
+        for (int i = 0; i < S::HLD; ++i) hn[i] = hp[i][nb];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) wn[j] = wp[nb + j];
-        const unsigned char *buf = lm_lds + (kb & 1) * SLAB;
+        for (int i = 0; i < S::WLD; ++i) wn[i] = wp[i][nb];
+        const unsigned char *buf = slab + (kb & 1) * S::SLAB;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const lm_bf16x8 a = __builtin_bit_cast(lm_bf16x8, wc[j]);
+        for (int j = 0; j < KB / 16; ++j) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(wtile + osrc[j]);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
-                const uint4 b = *reinterpret_cast<const uint4 *>(buf + rt * 32 * 256 + hsrc[j]);
-                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(lm_bf16x8, b), acc[rt], 0, 0, 0);
+                const uint4 b = *reinterpret_cast<const uint4 *>(buf + rt * 32 * S::RB + osrc[j]);
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a),
+                                                                  __builtin_bit_cast(lm_bf16x8, b), acc[rt], 0, 0, 0);
             }
         }
-        unsigned char *nxt = lm_lds + ((kb + 1) & 1) * SLAB;
+        // the wave's own W tile has been consumed (its reads precede these writes in program order); the H slab
+        // written is the one nobody reads in this round
+        unsigned char *nxt = slab + ((kb + 1) & 1) * S::SLAB;
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) *reinterpret_cast<uint4 *>(nxt + hdst[i]) = hn[i];
+        for (int i = 0; i < S::HLD; ++i)
+            if (S::HEVEN || hdst[i] >= 0) *reinterpret_cast<uint4 *>(nxt + hdst[i]) = hn[i];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) wc[j] = wn[j];
+        for (int i = 0; i < S::WLD; ++i) *reinterpret_cast<uint4 *>(wtile + wdst[i]) = wn[i];
         __syncthreads();
     }
 
     // per-lane scan over the 16 vocabulary rows it holds (ascending), other half, then the waves
     Best *wb = reinterpret_cast<Best *>(lm_lds);            // [WAVES][ROWS]
+    static_assert(S::LDS_BYTES >= WAVES * S::ROWS * (int)sizeof(Best), "exchange area must fit");
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         Best b = { -INFINITY, INT_MAX };
@@ -215,13 +256,13 @@ __global__ __launch_bounds__(WAVES * 64) void lm_head_argmax(const uint16_t *__r
         const float ov = __shfl_xor(b.v, 32);
         const int oi = __shfl_xor(b.i, 32);
         best_take(b, ov, oi);
-        if (half == 0) wb[wave * ROWS + rt * 32 + r32] = b;
+        if (half == 0) wb[wave * S::ROWS + rt * 32 + r32] = b;
     }
     __syncthreads();
-    for (int row = tid; row < R; row += THREADS) {
+    for (int row = tid; row < R; row += S::THREADS) {
         Best b = wb[row];
 #pragma unroll
-        for (int w = 1; w < WAVES; ++w) best_take(b, wb[w * ROWS + row].v, wb[w * ROWS + row].i);
+        for (int w = 1; w < WAVES; ++w) best_take(b, wb[w * S::ROWS + row].v, wb[w * S::ROWS + row].i);
         part[(size_t)row * gridDim.x + blockIdx.x] = b;
     }
 }
@@ -243,26 +284,26 @@ __global__ __launch_bounds__(256) void argmax_merge(const Best *part, int chunks
     }
 }
 
-template <int RT, int WAVES>
+template <int RT, int WAVES, int KB>
 int lm_head_launch(const uint16_t *H, const uint16_t *W, int R, int h, int V, Best *part, hipStream_t st)
 {
-    constexpr int LDS_BYTES = 2 * RT * 32 * 256;
-    static_assert(LDS_BYTES >= WAVES * RT * 32 * (int)sizeof(Best), "exchange area must fit the slabs");
+    using S = LmShape<RT, WAVES, KB>;
     static bool configured = false;
-    auto kern = lm_head_argmax<RT, WAVES>;
+    auto kern = lm_head_argmax<RT, WAVES, KB>;
     if (!configured) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    LDS_BYTES));
+                                    S::LDS_BYTES));
         configured = true;
     }
     const int chunks = (V + WAVES * 32 - 1) / (WAVES * 32);
-    hipLaunchKernelGGL(kern, dim3(chunks), dim3(WAVES * 64), LDS_BYTES, st, H, W, R, h, V, part);
+    hipLaunchKernelGGL(kern, dim3(chunks), dim3(WAVES * 64), S::LDS_BYTES, st, H, W, R, h, V, part);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
 
-// waves per workgroup: four while the slab of all rows leaves room for several workgroups per CU
-inline int lm_waves(int R) { return R <= 128 ? 4 : 8; }
+// Shapes: up to 96 rows two workgroups of four waves share a CU (80 KB of LDS each); above that one workgroup of
+// eight waves, with half-length blocks from 224 rows on so that the slabs still fit.
+inline int lm_waves(int R) { return R <= 96 ? 4 : 8; }
 inline int lm_chunks(int R, int V) { return (V + lm_waves(R) * 32 - 1) / (lm_waves(R) * 32); }
 
 // ------------------------------------------------------------------------------------------------
@@ -436,7 +477,7 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
     BTV_REQUIRE(hidden && W && parent && token && path && n_acc && bonus, "null pointer");
     BTV_REQUIRE(M >= 1 && M <= BTV_MAX_NODES, "M=%d outside [1,%d]", M, BTV_MAX_NODES);
     BTV_REQUIRE(V >= 1, "V=%d", V);
-    BTV_REQUIRE(h >= LM_KB && h % LM_KB == 0, "h=%d must be a positive multiple of %d", h, LM_KB);
+    BTV_REQUIRE(h >= 128 && h % 128 == 0, "h=%d must be a positive multiple of 128", h);
     BTV_REQUIRE((reinterpret_cast<uintptr_t>(hidden) & 15) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0,
                 "hidden and W must be 16-byte aligned");
     int rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_lm_head_workspace(M, V));
@@ -448,15 +489,15 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
                                           btv_align_up((size_t)R * chunks * sizeof(Best), BTV_WS_ALIGN));
     const uint16_t *Hp = static_cast<const uint16_t *>(hidden), *Wp = static_cast<const uint16_t *>(W);
     switch ((R + 31) / 32) {
-    case 1: rc = lm_head_launch<1, 4>(Hp, Wp, R, h, V, part, st); break;
-    case 2: rc = lm_head_launch<2, 4>(Hp, Wp, R, h, V, part, st); break;
-    case 3: rc = lm_head_launch<3, 4>(Hp, Wp, R, h, V, part, st); break;
-    case 4: rc = lm_head_launch<4, 4>(Hp, Wp, R, h, V, part, st); break;
-    case 5: rc = lm_head_launch<5, 8>(Hp, Wp, R, h, V, part, st); break;
-    case 6: rc = lm_head_launch<6, 8>(Hp, Wp, R, h, V, part, st); break;
-    case 7: rc = lm_head_launch<7, 8>(Hp, Wp, R, h, V, part, st); break;
-    case 8: rc = lm_head_launch<8, 8>(Hp, Wp, R, h, V, part, st); break;
-    default: rc = lm_head_launch<9, 8>(Hp, Wp, R, h, V, part, st); break;
+    case 1: rc = lm_head_launch<1, 4, 128>(Hp, Wp, R, h, V, part, st); break;
+    case 2: rc = lm_head_launch<2, 4, 128>(Hp, Wp, R, h, V, part, st); break;
+    case 3: rc = lm_head_launch<3, 4, 128>(Hp, Wp, R, h, V, part, st); break;
+    case 4: rc = lm_head_launch<4, 8, 128>(Hp, Wp, R, h, V, part, st); break;
+    case 5: rc = lm_head_launch<5, 8, 128>(Hp, Wp, R, h, V, part, st); break;
+    case 6: rc = lm_head_launch<6, 8, 128>(Hp, Wp, R, h, V, part, st); break;
+    case 7: rc = lm_head_launch<7, 8, 64>(Hp, Wp, R, h, V, part, st); break;
+    case 8: rc = lm_head_launch<8, 8, 64>(Hp, Wp, R, h, V, part, st); break;
+    default: rc = lm_head_launch<9, 8, 64>(Hp, Wp, R, h, V, part, st); break;
     }
     if (rc) return rc;
     hipLaunchKernelGGL(argmax_merge, dim3(R), dim3(256), 0, st, part, chunks, best);
