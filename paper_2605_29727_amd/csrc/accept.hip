@@ -121,29 +121,32 @@ __global__ __launch_bounds__(256) void greedy_walk(const Best *part, int chunks,
 // matrix cores and reduced to one (value, token) pair per row and workgroup: the logits never reach
 // memory, the 2*V*h bytes of W are streamed once.
 //
-// Transposed product, C^T = W_tile * H^T (v_mfma_f32_32x32x16_bf16): a wave owns 32 vocabulary rows
-// and every row of H, so a lane's accumulator registers run over vocabulary rows of one H row and
-// the argmax is a per-lane scan.  The operand layout wants lane l to hold row l % 32, which as a
-// direct load would touch 64 cache lines per instruction and use 16 bytes of each; instead every
-// load instruction fetches four whole 256-byte row segments (16 lanes per row), and the block is
-// turned round through a wave-private LDS tile.  H blocks [rows, KB] are shared by the waves through
-// a double-buffered LDS slab.  All tiles store the 16-byte chunks of a row XOR-permuted by the row
-// number, so operand reads (ds_read_b128, 16 lanes = 16 different rows) are conflict-free.
+// Transposed product, C^T = W_tile * H^T (v_mfma_f32_32x32x16_bf16): a wave owns TV tiles of 32
+// vocabulary rows and every row of H, so a lane's accumulator registers run over vocabulary rows of
+// one H row and the argmax is a per-lane scan.  The operand layout wants lane l to hold row l % 32,
+// which as a direct load would touch 64 cache lines per instruction and use 16 bytes of each;
+// instead every load instruction fetches whole row segments (8 or 16 lanes per row), and the block
+// is turned round through a wave-private LDS tile.  H blocks [rows, KB] are shared by the waves
+// through a double-buffered LDS slab.  All tiles store the 16-byte chunks of a row XOR-permuted by
+// the row number, so operand reads (ds_read_b128, 16 lanes = 16 different rows) are conflict-free.
 // ------------------------------------------------------------------------------------------------
 typedef __bf16 lm_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float lm_f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int lm_u32x4 __attribute__((ext_vector_type(4)));
 
-template <int RT, int WAVES, int KB>
+template <int RT, int WAVES, int KB, int TV>
 struct LmShape {
     static constexpr int THREADS = WAVES * 64, ROWS = RT * 32;
+    static constexpr int VROWS = TV * 32;                 // vocabulary rows of a wave
     static constexpr int RB = KB * 2;                     // bytes of a tile row
     static constexpr int CPR = RB / 16;                   // 16-byte chunks per row
-    static constexpr int WTILE = 32 * RB, SLAB = ROWS * RB;
+    static constexpr int WTILE = VROWS * RB, SLAB = ROWS * RB;
     static constexpr int LDS_BYTES = WAVES * WTILE + 2 * SLAB;
-    static constexpr int WLD = 32 * CPR / 64;             // load instructions per wave and block for W
+    static constexpr int WLD = VROWS * CPR / 64;          // load instructions per wave and block for W
     static constexpr int HLD = (ROWS * CPR + THREADS - 1) / THREADS;   // chunks of the H slab per thread and block
     static constexpr bool HEVEN = ROWS * CPR % THREADS == 0;
     static_assert(CPR == 8 || CPR == 16, "KB is 64 or 128");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of a CU");
     // byte offset of 16-byte chunk `col` of tile row `row`: 16 lanes reading one chunk index of 16 consecutive
     // rows must land in 16 different 16-byte bank groups of the 256-byte bank line
     __device__ static constexpr int at(int row, int col)
@@ -152,107 +155,217 @@ struct LmShape {
     }
 };
 
-template <int RT, int WAVES, int KB>
-__global__ __launch_bounds__(WAVES * 64) void lm_head_argmax(const uint16_t *__restrict__ H,
-                                                              const uint16_t *__restrict__ W, int R, int h, int V,
-                                                              Best *__restrict__ part)
+// One block of the contraction for a wave: KB / 16 steps of TV + RT operand reads and TV * RT MFMAs.  Here the
+// reads are raw instructions with hand-placed waits (as ordinary loads each is waited for right before its MFMA,
+// which leaves the matrix core idle for an LDS round trip): the reads of step j + 1 are issued before the MFMAs
+// of step j, and the in-order counter tells when step j's have landed.
+template <int RT, int TV>
+__device__ __forceinline__ void lm_read_step(uint32_t wt, uint32_t hb, int tile_bytes, lm_u32x4 (&a)[TV], lm_u32x4 (&b)[RT])
 {
-    using S = LmShape<RT, WAVES, KB>;
+#pragma unroll
+    for (int tv = 0; tv < TV; ++tv)
+        asm volatile("ds_read_b128 %0, %1" : "=v"(a[tv]) : "v"(wt + (uint32_t)(tv * tile_bytes)) : "memory");
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+        asm volatile("ds_read_b128 %0, %1" : "=v"(b[rt]) : "v"(hb + (uint32_t)(rt * tile_bytes)) : "memory");
+}
+
+template <int RT, int TV, int YOUNGER>
+__device__ __forceinline__ void lm_wait_step(lm_u32x4 (&a)[TV], lm_u32x4 (&b)[RT])
+{
+    static_assert(YOUNGER >= 0 && YOUNGER <= 15, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(YOUNGER) : "memory");
+#pragma unroll
+    for (int tv = 0; tv < TV; ++tv) asm volatile("" : "+v"(a[tv]));     // uses below may not move above the wait
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) asm volatile("" : "+v"(b[rt]));
+}
+
+// ob = offset of this lane's operand chunk at step 0 within a 32-row tile; step j sits at ob ^ (j << 5)
+template <int RT, int TV, int KB, int RB>
+__device__ __forceinline__ void lm_multiply(uint32_t wt, uint32_t hb, uint32_t ob, lm_f32x16 (&acc)[TV][RT])
+{
+    constexpr int STEPS = KB / 16, N = TV + RT;
+    static_assert(N <= 15, "lgkmcnt range");
+    lm_u32x4 a[2][TV], b[2][RT];
+    lm_read_step<RT, TV>(wt + ob, hb + ob, 32 * RB, a[0], b[0]);
+#pragma unroll
+    for (int j = 0; j < STEPS; ++j) {
+        if (j + 1 < STEPS) {
+            const uint32_t o = ob ^ (uint32_t)((j + 1) << 5);
+            lm_read_step<RT, TV>(wt + o, hb + o, 32 * RB, a[(j + 1) & 1], b[(j + 1) & 1]);
+            lm_wait_step<RT, TV, N>(a[j & 1], b[j & 1]);
+        } else {
+            lm_wait_step<RT, TV, 0>(a[j & 1], b[j & 1]);
+        }
+#pragma unroll
+        for (int tv = 0; tv < TV; ++tv)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+                acc[tv][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[j & 1][tv]),
+                                                                      __builtin_bit_cast(lm_bf16x8, b[j & 1][rt]),
+                                                                      acc[tv][rt], 0, 0, 0);
+    }
+}
+
+// The same block with ordinary loads, scheduled by the compiler: leaner in registers, used when the accumulators
+// of many row tiles leave no room for a second set of operands.
+template <int RT, int TV, int KB, int RB>
+__device__ __forceinline__ void lm_multiply_plain(const unsigned char *wt, const unsigned char *hb, uint32_t ob,
+                                                  lm_f32x16 (&acc)[TV][RT])
+{
+#pragma unroll
+    for (int j = 0; j < KB / 16; ++j) {
+        const uint32_t o = ob ^ (uint32_t)(j << 5);
+        lm_u32x4 a[TV];
+#pragma unroll
+        for (int tv = 0; tv < TV; ++tv) a[tv] = *reinterpret_cast<const lm_u32x4 *>(wt + tv * 32 * RB + o);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const lm_u32x4 b = *reinterpret_cast<const lm_u32x4 *>(hb + rt * 32 * RB + o);
+#pragma unroll
+            for (int tv = 0; tv < TV; ++tv)
+                acc[tv][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a[tv]),
+                                                                      __builtin_bit_cast(lm_bf16x8, b), acc[tv][rt], 0, 0, 0);
+        }
+    }
+}
+
+template <int RT, int WAVES, int KB, int TV, bool RAW>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_head_argmax(
+    const uint16_t *__restrict__ H, const uint16_t *__restrict__ W, int R, int h, int V, Best *__restrict__ part)
+{
+    using S = LmShape<RT, WAVES, KB, TV>;
     extern __shared__ __align__(16) unsigned char lm_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r32 = lane & 31, half = lane >> 5;
-    const int v0 = (blockIdx.x * WAVES + wave) * 32;
+    const int vwg = blockIdx.x * WAVES * S::VROWS, v0 = vwg + wave * S::VROWS;
     unsigned char *wtile = lm_lds + wave * S::WTILE;
     unsigned char *slab = lm_lds + WAVES * S::WTILE;
     const int nkb = h / KB;
 
+    // Addresses are a wave-uniform base (block of the contraction, first row of the workgroup) plus a 32-bit
+    // per-lane offset that never changes.
     // W: instruction i moves rows i*(64/CPR) .. of the wave's tile, CPR lanes per row
     constexpr int RPI = 64 / S::CPR;                       // rows per load instruction
     const int wcol = lane % S::CPR, wrow0 = lane / S::CPR;
-    const uint4 *wp[S::WLD];
-    int wdst[S::WLD];
+    const unsigned char *wbase = reinterpret_cast<const unsigned char *>(W) + (size_t)vwg * h * 2;
+    const unsigned char *hbase = reinterpret_cast<const unsigned char *>(H);
+    uint32_t woff[S::WLD], hoff[S::HLD];
+    // LDS destinations: rows 16 apart share the swizzle, so only the first 16 / RPI of a tile's store addresses
+    // differ by more than a constant
+    constexpr int WDN = 16 / RPI < S::WLD ? 16 / RPI : S::WLD;
+    int wdst[WDN];
 #pragma unroll
     for (int i = 0; i < S::WLD; ++i) {
         const int row = i * RPI + wrow0;
-        wp[i] = reinterpret_cast<const uint4 *>(W + (size_t)min(v0 + row, V - 1) * h + wcol * 8);
-        wdst[i] = S::at(row, wcol);
+        woff[i] = (uint32_t)(min(v0 + row, V - 1) - vwg) * (uint32_t)(h * 2) + wcol * 16;
+        if (i < WDN) wdst[i] = S::at(row, wcol);
     }
     // H: chunk c of the slab -> row c / CPR, column c % CPR
-    const uint4 *hp[S::HLD];
-    int hdst[S::HLD];
 #pragma unroll
     for (int i = 0; i < S::HLD; ++i) {
         const int c = tid + i * S::THREADS, row = c / S::CPR, col = c % S::CPR;
-        hp[i] = reinterpret_cast<const uint4 *>(H + (size_t)min(row, R - 1) * h + col * 8);
-        hdst[i] = S::at(row, col);
-        if (!S::HEVEN && row >= S::ROWS) hdst[i] = -1;    // past the slab: fetched (row clamped), never stored
+        hoff[i] = (uint32_t)min(row, R - 1) * (uint32_t)(h * 2) + col * 16;
     }
-    // operand reads: step j of a block uses chunk 2j + half of row r32 (same chunk on both sides)
-    int osrc[KB / 16];
-#pragma unroll
-    for (int j = 0; j < KB / 16; ++j) osrc[j] = S::at(r32, 2 * j + half);
+    // a thread's chunks are THREADS / CPR rows apart, a multiple of 16: same swizzle, constant distance
+    constexpr int HSTEP = S::THREADS / S::CPR;
+    static_assert(HSTEP % 16 == 0, "H chunks of a thread must share the swizzle");
+    const int hrow0 = tid / S::CPR, hdst0 = S::at(hrow0, tid % S::CPR);
+    // operand reads: step j of a block uses chunk 2j + half of row r32 (same chunk on both sides), which sits at
+    // at(r32, half) ^ (j << 5): the swizzle is an XOR and 2j + half = 2j ^ half
+    const uint32_t ob = (uint32_t)S::at(r32, half);
 
-    lm_f32x16 acc[RT];
+    lm_f32x16 acc[TV][RT];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int tv = 0; tv < TV; ++tv)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[tv][rt][e] = 0.f;
 
     // Workgroups start at different blocks of the contraction and wrap round: rows of W are a multiple of 4 KB
     // apart, so workgroups marching in step would all hit the same few memory channels.
-    int cur = (blockIdx.x * 5) % nkb;
-    uint4 wn[S::WLD], hn[S::HLD];
-#pragma unroll
-    for (int i = 0; i < S::HLD; ++i) hn[i] = hp[i][cur * (KB / 8)];
-#pragma unroll
-    for (int i = 0; i < S::WLD; ++i) wn[i] = wp[i][cur * (KB / 8)];
-#pragma unroll
-    for (int i = 0; i < S::HLD; ++i)
-        if (S::HEVEN || hdst[i] >= 0) *reinterpret_cast<uint4 *>(slab + hdst[i]) = hn[i];
-#pragma unroll
-    for (int i = 0; i < S::WLD; ++i) *reinterpret_cast<uint4 *>(wtile + wdst[i]) = wn[i];
-    __syncthreads();
-
-    for (int kb = 0; kb < nkb; ++kb) {
-        // next block into registers (the last round fetches the first block again; it lands where nobody reads)
-        cur = cur + 1 == nkb ? 0 : cur + 1;
-        const int nb = cur * (KB / 8);
-#pragma unroll
-        for (int i = 0; i < S::HLD; ++i) hn[i] = hp[i][nb];
-#pragma unroll
-        for (int i = 0; i < S::WLD; ++i) wn[i] = wp[i][nb];
-        const unsigned char *buf = slab + (kb & 1) * S::SLAB;
-#pragma unroll
-        for (int j = 0; j < KB / 16; ++j) {
-            const uint4 a = *reinterpret_cast<const uint4 *>(wtile + osrc[j]);
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                const uint4 b = *reinterpret_cast<const uint4 *>(buf + rt * 32 * S::RB + osrc[j]);
-                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(lm_bf16x8, a),
-                                                                  __builtin_bit_cast(lm_bf16x8, b), acc[rt], 0, 0, 0);
-            }
-        }
-        // the wave's own W tile has been consumed (its reads precede these writes in program order); the H slab
-        // written is the one nobody reads in this round
-        unsigned char *nxt = slab + ((kb + 1) & 1) * S::SLAB;
-#pragma unroll
-        for (int i = 0; i < S::HLD; ++i)
-            if (S::HEVEN || hdst[i] >= 0) *reinterpret_cast<uint4 *>(nxt + hdst[i]) = hn[i];
-#pragma unroll
-        for (int i = 0; i < S::WLD; ++i) *reinterpret_cast<uint4 *>(wtile + wdst[i]) = wn[i];
-        __syncthreads();
+    int curw = (blockIdx.x * 5) % nkb, curh = curw;
+    // (staging arrays are of a native vector type: arrays of the uint4 struct were left in scratch memory)
+#define LM_FETCH_W(w)                                                                                      \
+    {                                                                                                      \
+        const unsigned char *b_ = wbase + (size_t)curw * (KB * 2);                                         \
+        curw = curw + 1 == nkb ? 0 : curw + 1;                                                             \
+        _Pragma("unroll") for (int i = 0; i < S::WLD; ++i) w[i] = *reinterpret_cast<const lm_u32x4 *>(b_ + woff[i]); \
+    }
+#define LM_FETCH_H(x)                                                                                      \
+    {                                                                                                      \
+        const unsigned char *b_ = hbase + (size_t)curh * (KB * 2);                                         \
+        curh = curh + 1 == nkb ? 0 : curh + 1;                                                             \
+        _Pragma("unroll") for (int i = 0; i < S::HLD; ++i) x[i] = *reinterpret_cast<const lm_u32x4 *>(b_ + hoff[i]); \
+    }
+#define LM_STORE_W(w)                                                                                   \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < S::WLD; ++i)                                              \
+            *reinterpret_cast<lm_u32x4 *>(wtile + wdst[i % WDN] + (i / WDN) * 16 * S::RB) = w[i];       \
+    }
+#define LM_STORE_H(x, dst)                                                                              \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < S::HLD; ++i)                                              \
+            if (S::HEVEN || hrow0 + i * HSTEP < S::ROWS)   /* past the slab: fetched, never stored */   \
+                *reinterpret_cast<lm_u32x4 *>((dst) + hdst0 + i * HSTEP * S::RB) = x[i];                \
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) void *)lm_lds);
+    const uint32_t wt_addr = lds0 + wave * S::WTILE, slab_addr = lds0 + WAVES * S::WTILE;
+#define LM_MULTIPLY(sl)                                                                                      \
+    {                                                                                                        \
+        if constexpr (RAW) lm_multiply<RT, TV, KB, S::RB>(wt_addr, slab_addr + (sl) * S::SLAB, ob, acc);     \
+        else lm_multiply_plain<RT, TV, KB, S::RB>(wtile, slab + (sl) * S::SLAB, ob, acc);                    \
     }
 
-    // per-lane scan over the 16 vocabulary rows it holds (ascending), other half, then the waves
+    // While block t is multiplied from LDS, the weights of blocks t + 1 and t + 2 are in registers or on their way
+    // (they come from HBM); H comes from the L2 and is fetched one block ahead.  Fetches past the end wrap round to
+    // blocks already seen; they land where nobody reads.
+    lm_u32x4 w0[S::WLD], w1[S::WLD], x[S::HLD];
+    LM_FETCH_W(w0)
+    LM_FETCH_H(x)
+    LM_FETCH_W(w1)
+    LM_STORE_H(x, slab)
+    LM_STORE_W(w0)
+    __syncthreads();
+    for (int kb = 0; kb + 1 < nkb; kb += 2) {
+        // even round: slab 0 and the W tile hold block kb, w1 block kb + 1
+        LM_FETCH_H(x)                                   // block kb + 1
+        LM_FETCH_W(w0)                                  // block kb + 2
+        LM_MULTIPLY(0)
+        LM_STORE_H(x, slab + S::SLAB)                   // slab 1 is idle in this round
+        LM_STORE_W(w1)                                  // own W tile: consumed by the multiply above
+        __syncthreads();
+        LM_FETCH_H(x)                                   // block kb + 2
+        LM_FETCH_W(w1)                                  // block kb + 3
+        LM_MULTIPLY(1)
+        LM_STORE_H(x, slab)
+        LM_STORE_W(w0)
+        __syncthreads();
+    }
+    if (nkb & 1) {                                      // the last block of an odd count sits in slab 0
+        LM_MULTIPLY(0)
+        __syncthreads();
+    }
+#undef LM_MULTIPLY
+#undef LM_FETCH_W
+#undef LM_FETCH_H
+#undef LM_STORE_W
+#undef LM_STORE_H
+
+    // per-lane scan over the 16 vocabulary rows of a tile that it holds (ascending), other half, then the waves
     Best *wb = reinterpret_cast<Best *>(lm_lds);            // [WAVES][ROWS]
     static_assert(S::LDS_BYTES >= WAVES * S::ROWS * (int)sizeof(Best), "exchange area must fit");
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         Best b = { -INFINITY, INT_MAX };
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int v = v0 + (e >> 2) * 8 + half * 4 + (e & 3);
-            if (v < V) best_take(b, acc[rt][e], v);
-        }
+        for (int tv = 0; tv < TV; ++tv)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int v = v0 + tv * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                if (v < V) best_take(b, acc[tv][rt][e], v);
+            }
         const float ov = __shfl_xor(b.v, 32);
         const int oi = __shfl_xor(b.i, 32);
         best_take(b, ov, oi);
@@ -284,27 +397,57 @@ __global__ __launch_bounds__(256) void argmax_merge(const Best *part, int chunks
     }
 }
 
-template <int RT, int WAVES, int KB>
+// Shape of the LM-head kernel for R rows of H: row tiles, waves per workgroup, contraction block, vocabulary
+// tiles per wave, raw or compiler-scheduled operand reads.
+struct LmPlan { int rt, waves, kb, tv, raw; };
+
+inline LmPlan lm_plan(int R)
+{
+    // Measured at h = 4096, V = 128256: every shape up to 160 rows runs within 10 % of the 1 or 2 row-tile case,
+    // which is bound by the stream of W; pipelined raw reads pay only while a second set of operands fits beside
+    // the accumulators, and two vocabulary tiles per wave bought nothing.
+    const int rt = (R + 31) / 32;
+    if (rt <= 2) return { rt, 4, 128, 1, 1 };
+    if (rt <= 6) return { rt, 8, 128, 1, 0 };
+    return { rt, 8, 64, 1, 0 };
+}
+
+inline int lm_chunks(int R, int V)
+{
+    const LmPlan p = lm_plan(R);
+    return (V + p.waves * p.tv * 32 - 1) / (p.waves * p.tv * 32);
+}
+
+template <int RT, int WAVES, int KB, int TV, bool RAW>
 int lm_head_launch(const uint16_t *H, const uint16_t *W, int R, int h, int V, Best *part, hipStream_t st)
 {
-    using S = LmShape<RT, WAVES, KB>;
+    using S = LmShape<RT, WAVES, KB, TV>;
     static bool configured = false;
-    auto kern = lm_head_argmax<RT, WAVES, KB>;
+    auto kern = lm_head_argmax<RT, WAVES, KB, TV, RAW>;
     if (!configured) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     S::LDS_BYTES));
         configured = true;
     }
-    const int chunks = (V + WAVES * 32 - 1) / (WAVES * 32);
+    const int chunks = (V + WAVES * S::VROWS - 1) / (WAVES * S::VROWS);
     hipLaunchKernelGGL(kern, dim3(chunks), dim3(WAVES * 64), S::LDS_BYTES, st, H, W, R, h, V, part);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
 
-// Shapes: up to 96 rows two workgroups of four waves share a CU (80 KB of LDS each); above that one workgroup of
-// eight waves, with half-length blocks from 224 rows on so that the slabs still fit.
-inline int lm_waves(int R) { return R <= 96 ? 4 : 8; }
-inline int lm_chunks(int R, int V) { return (V + lm_waves(R) * 32 - 1) / (lm_waves(R) * 32); }
+int lm_head_dispatch(const uint16_t *H, const uint16_t *W, int R, int h, int V, Best *part, hipStream_t st)
+{
+    const LmPlan p = lm_plan(R);
+#define LM_CASE(rt_, w_, kb_, tv_, raw_)                                                              \
+    if (p.rt == rt_ && p.waves == w_ && p.kb == kb_ && p.tv == tv_ && p.raw == raw_)                  \
+        return lm_head_launch<rt_, w_, kb_, tv_, raw_ != 0>(H, W, R, h, V, part, st);
+    LM_CASE(1, 4, 128, 1, 1) LM_CASE(2, 4, 128, 1, 1)
+    LM_CASE(3, 8, 128, 1, 0)
+    LM_CASE(4, 8, 128, 1, 0) LM_CASE(5, 8, 128, 1, 0) LM_CASE(6, 8, 128, 1, 0)
+    LM_CASE(7, 8, 64, 1, 0) LM_CASE(8, 8, 64, 1, 0) LM_CASE(9, 8, 64, 1, 0)
+#undef LM_CASE
+    return btv_fail(BTV_EINVAL, "no LM-head kernel for %d rows", R);
+}
 
 // ------------------------------------------------------------------------------------------------
 // Stochastic walk: one workgroup of 1024 threads; p and q live in the workspace (fp32), every
@@ -488,17 +631,7 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
     Best *best = reinterpret_cast<Best *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER +
                                           btv_align_up((size_t)R * chunks * sizeof(Best), BTV_WS_ALIGN));
     const uint16_t *Hp = static_cast<const uint16_t *>(hidden), *Wp = static_cast<const uint16_t *>(W);
-    switch ((R + 31) / 32) {
-    case 1: rc = lm_head_launch<1, 4, 128>(Hp, Wp, R, h, V, part, st); break;
-    case 2: rc = lm_head_launch<2, 4, 128>(Hp, Wp, R, h, V, part, st); break;
-    case 3: rc = lm_head_launch<3, 4, 128>(Hp, Wp, R, h, V, part, st); break;
-    case 4: rc = lm_head_launch<4, 8, 128>(Hp, Wp, R, h, V, part, st); break;
-    case 5: rc = lm_head_launch<5, 8, 128>(Hp, Wp, R, h, V, part, st); break;
-    case 6: rc = lm_head_launch<6, 8, 128>(Hp, Wp, R, h, V, part, st); break;
-    case 7: rc = lm_head_launch<7, 8, 64>(Hp, Wp, R, h, V, part, st); break;
-    case 8: rc = lm_head_launch<8, 8, 64>(Hp, Wp, R, h, V, part, st); break;
-    default: rc = lm_head_launch<9, 8, 64>(Hp, Wp, R, h, V, part, st); break;
-    }
+    rc = lm_head_dispatch(Hp, Wp, R, h, V, part, st);
     if (rc) return rc;
     hipLaunchKernelGGL(argmax_merge, dim3(R), dim3(256), 0, st, part, chunks, best);
     BTV_HIP(hipGetLastError());
