@@ -38,6 +38,7 @@ def _load():
         _lib.orc_num_threads.restype = C.c_int
         _lib.orc_ancestor_mask.restype = C.c_int
         _lib.orc_tree_build_adaptive.restype = C.c_int
+        _lib.orc_tree_build_beam.restype = C.c_int
         _lib.orc_verify_cost.restype = None
         _lib.orc_kv_commit.restype = C.c_longlong
     return _lib
@@ -75,6 +76,24 @@ def tree_build(marg: np.ndarray, N: int) -> dict:
         raise ValueError("orc_tree_build: bad arguments")
     return {"n": n, "parent": parent[:n], "token": token[:n], "depth": depth[:n], "rank": rank[:n],
             "rho": rho[:n], "ahat": ahat.value}
+
+
+def tree_build_beam(marg: np.ndarray, width: int, depth: int) -> dict:
+    """Beam-search tree, width x depth below the root (Sec. 4.3's comparison topology; width 1 = greedy chain)."""
+    marg = np.ascontiguousarray(marg, dtype=np.float32)
+    B, V = marg.shape
+    cap = max(width * depth, 1)
+    parent = np.empty(cap, dtype=np.int32)
+    token = np.empty_like(parent); dep = np.empty_like(parent); rank = np.empty_like(parent)
+    rho = np.empty(cap, dtype=np.float32)
+    ahat = C.c_double(0.0)
+    n = _load().orc_tree_build_beam(_p(marg, C.c_float), B, V, int(width), int(depth), _p(parent, C.c_int32),
+                                    _p(token, C.c_int32), _p(dep, C.c_int32), _p(rho, C.c_float), _p(rank, C.c_int32),
+                                    C.byref(ahat))
+    if n < 0:
+        raise ValueError("orc_tree_build_beam: bad arguments")
+    return {"n": n, "parent": parent[:n], "token": token[:n], "depth": dep[:n], "rank": rank[:n], "rho": rho[:n],
+            "ahat": ahat.value}
 
 
 def tree_build_adaptive(marg: np.ndarray, N_max: int, cost, L_AR: float) -> dict:

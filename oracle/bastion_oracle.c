@@ -15,6 +15,8 @@
  *                        Monte-Carlo self-verification (Prop. 3.2)
  *   orc_tree_build_adaptive  exhaustive argmax of the estimated speedup over all budgets on concave/convex
  *                        inputs (Prop. 3.4), prefix property against orc_tree_build, hand-made cost curves
+ *   orc_tree_build_beam  hand-worked example, width 1 = per-position argmax chain, full-width = whole lattice,
+ *                        per-depth top-w of explicitly enumerated extensions (numpy sort), Prop. 3.3 upper bound
  *   orc_verify_cost      the per-module tables of App. E summed by hand for a small configuration
  *   orc_calib_fit        exact recovery of a planted line, numpy's polynomial fit, zero-gradient of the residual
  *   orc_calib_ema        closed form of the geometric approach to a constant ratio
@@ -169,6 +171,60 @@ int orc_tree_build_adaptive(const float *marg, int B, int V, int N_max, const do
     for (int i = 0; i < N_max; ++i)
         if (!(cost[i] > 0.0)) return -1;
     return tree_build_core(marg, B, V, N_max, cost, L_AR, parent, token, depth, rho, rank, ahat, s_best, margin);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Beam-search tree (Sec. 4.3, the comparison topology): depth by depth, of all one-token extensions of the
+ * prefixes kept at the previous depth, the `width` with the largest path score (Eq. 1) are kept, which gives a
+ * width x depth rectangle below the root; width 1 is the single greedy chain.  Every extension of every kept
+ * prefix is enumerated (all V tokens) and the list is sorted.  Order within a depth (the paper is silent):
+ * rho descending, then the parent's place in the previous depth ascending, then the token's rank at that
+ * position ascending (probability descending, token id ascending).  Nodes are numbered depth by depth in that
+ * order.  A depth with fewer than `width` extensions keeps them all.  Returns the node count.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct { float rho; int32_t parent_place, rank; } beam_cand_t;
+
+static int cmp_beam(const void *a, const void *b)
+{
+    const beam_cand_t *x = (const beam_cand_t *)a, *y = (const beam_cand_t *)b;
+    if (x->rho != y->rho) return x->rho > y->rho ? -1 : 1;
+    if (x->parent_place != y->parent_place) return x->parent_place < y->parent_place ? -1 : 1;
+    return (x->rank > y->rank) - (x->rank < y->rank);
+}
+
+int orc_tree_build_beam(const float *marg, int B, int V, int width, int depth_max, int32_t *parent, int32_t *token,
+                        int32_t *depth, float *rho, int32_t *rank, double *ahat)
+{
+    if (B < 1 || V < 1 || width < 1 || depth_max < 1 || depth_max > B) return -1;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * V);
+    beam_cand_t *cand = (beam_cand_t *)malloc(sizeof(beam_cand_t) * (size_t)width * V);
+    orc_rank_tokens(marg, B, V, order);
+    int n = 0, first = 0, kept = 1;          /* previous depth: nodes first .. first + kept - 1 (depth 0: the root) */
+    double a = 1.0;
+    for (int k = 0; k < depth_max; ++k) {
+        size_t nc = 0;
+        for (int b = 0; b < kept; ++b) {
+            float prho = (k == 0) ? 1.0f : rho[first + b];
+            for (int r = 0; r < V; ++r) {
+                volatile float child = prho * marg[(size_t)k * V + order[(size_t)k * V + r]];   /* one fp32 multiply */
+                cand[nc++] = (beam_cand_t){ child, b, r };
+            }
+        }
+        qsort(cand, nc, sizeof(beam_cand_t), cmp_beam);
+        int keep = nc < (size_t)width ? (int)nc : width;
+        for (int i = 0; i < keep; ++i) {
+            parent[n + i] = (k == 0) ? -1 : first + cand[i].parent_place;
+            rank[n + i] = cand[i].rank;
+            token[n + i] = order[(size_t)k * V + cand[i].rank];
+            depth[n + i] = k + 1;
+            rho[n + i] = cand[i].rho;
+            a += (double)cand[i].rho;
+        }
+        first = n; kept = keep; n += keep;
+    }
+    *ahat = a;
+    free(order); free(cand);
+    return n;
 }
 
 /* ------------------------------------------------------------------------------------------
