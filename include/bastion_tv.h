@@ -90,6 +90,23 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
                             void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * tree_build_beam -- the beam-search tree that Sec. 4.3 compares best-first expansion with:
+ * depth by depth, of all one-token extensions of the prefixes kept at the previous depth, the
+ * `width` with the largest path score (Eq. 1) are kept: a width x depth rectangle below the
+ * root; width 1 is the single greedy chain.  Order within a depth (and of the node numbers):
+ * rho descending, then the parent's place in the previous depth, then the token's rank at its
+ * position (probability descending, token id ascending).  A depth with fewer than `width`
+ * extensions keeps them all.
+ *   marginals [B,V] fp32; only the first `depth` rows are read.  1 <= width <= 16,
+ *   1 <= depth <= B <= BTV_MAX_DEPTH, so at most 256 nodes.
+ *   parent, token, depth_out, rho: [width*depth] as for btv_tree_build; n_out [1]; ahat [1].
+ * Workspace: btv_tree_build_workspace(depth, V, width).
+ * ------------------------------------------------------------------------------------------- */
+int btv_tree_build_beam(const float *marginals, int B, int V, int width, int depth,
+                        int32_t *parent, int32_t *token, int32_t *depth_out, float *rho,
+                        int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * verify_cost -- HOST function, no GPU work: the verifier cost model of App. E.  FLOPs and
  * memory traffic of one target forward pass over s newly verified tokens with c cached tokens
  * (non-fused attention: the score matrix counts as activation traffic; elementwise work is

@@ -21,7 +21,7 @@ BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "btv_last_error", "btv_version", "btv_workspace_status", "btv_tree_build_workspace", "btv_tree_build",
-    "btv_tree_build_adaptive", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
+    "btv_tree_build_adaptive", "btv_tree_build_beam", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
     "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
     "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
@@ -51,7 +51,7 @@ def lib() -> C.CDLL:
                   "btv_tree_verify_attn_paged_workspace", "btv_tree_accept_workspace",
                   "btv_tree_accept_lm_head_workspace"):
             getattr(L, n).restype = C.c_size_t
-        for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_ancestor_mask",
+        for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_build_beam", "btv_tree_ancestor_mask",
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_accept_greedy",
                   "btv_tree_accept_stochastic"):
             getattr(L, n).restype = C.c_int
@@ -121,6 +121,13 @@ def btv_tree_build_adaptive(marginals, N_max: int, cost, L_AR: float, parent, to
     _check(lib().btv_tree_build_adaptive(_ptr(marginals), B, V, N_max, _ptr(cost), C.c_double(L_AR), _ptr(parent),
                                          _ptr(token), _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(s_best),
                                          _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_build_beam(marginals, width: int, depth_max: int, parent, token, depth, rho, n_out, ahat, ws) -> None:
+    B, V = marginals.shape
+    _check(lib().btv_tree_build_beam(_ptr(marginals), B, V, int(width), int(depth_max), _ptr(parent), _ptr(token),
+                                     _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(ws),
+                                     C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
 
 
 def btv_verify_cost(s, c, layers, h, nq, nkv, d, hffn, V, bp, peak_flops, bandwidth, calib_scale=1.0,

@@ -505,13 +505,76 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 
 // Workgroup `row` ranks the candidates of its position into top_q / top_tok (global, [B][KP]); the workgroup that
 // finishes last then runs the expansion on its first wavefront.
+// ------------------------------------------------------------------------------------------------
+// Step 3, part B': the beam-search tree (Sec. 4.3's comparison topology): depth by depth, the `width` extensions
+// with the largest path score among all extensions of the prefixes kept at the previous depth.  Only the `width`
+// best tokens of a position can be kept (an extension of rank r is preceded by r extensions of the same prefix),
+// so a depth has at most width * width <= 256 candidates: one per thread, ranked by counting.  Order within a
+// depth: rho desc, then the parent's place in the previous depth, then the token's rank.
+// ------------------------------------------------------------------------------------------------
+constexpr int MAXW = 16;
+
+struct BeamLds {
+    u64 key[MAXW * MAXW];
+    float rho[2][MAXW];
+    int node[2][MAXW];
+    double part[4];
+};
+
+__device__ __forceinline__ void beam_block(const ExpandLds &S, BeamLds &Bm, int depth_max, int K, int KP, int width, int tid,
+                                           int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out,
+                                           float *ahat)
+{
+    int n = 0, kept = 1;                                    // nodes so far, prefixes kept at the previous depth
+    double mine_sum = 0.0;
+    if (tid == 0) { Bm.rho[0][0] = 1.f; Bm.node[0][0] = -1; }
+    __syncthreads();
+    for (int k = 0; k < depth_max; ++k) {
+        const int cur = k & 1, nc = kept * K, keep = min(nc, width);
+        const int b = tid / K, rk = tid - b * K;            // candidate tid = (kept prefix b, rank rk)
+        float r = 0.f;
+        u64 mine = 0;
+        if (tid < nc) {
+            r = __fmul_rn(Bm.rho[cur][b], S.q[k * KP + rk]);
+            mine = ((u64)__float_as_uint(r) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)tid);
+            Bm.key[tid] = mine;
+        }
+        __syncthreads();
+        if (tid < nc) {
+            int rank = 0;
+            for (int j = 0; j < nc; ++j) rank += Bm.key[j] > mine ? 1 : 0;
+            if (rank < keep) {
+                const int nd = n + rank;
+                parent[nd] = Bm.node[cur][b];
+                token[nd] = (int32_t)S.tok[k * KP + rk];
+                if (depth) depth[nd] = k + 1;
+                if (rho) rho[nd] = r;
+                Bm.rho[cur ^ 1][rank] = r;
+                Bm.node[cur ^ 1][rank] = nd;
+                mine_sum += (double)r;
+            }
+        }
+        n += keep;
+        kept = keep;
+        __syncthreads();
+    }
+    for (int off = 32; off >= 1; off >>= 1) mine_sum += __shfl_xor(mine_sum, off);
+    if ((tid & 63) == 0) Bm.part[tid >> 6] = mine_sum;
+    __syncthreads();
+    if (tid == 0) {
+        *n_out = n;
+        if (ahat) *ahat = (float)(1.0 + ((Bm.part[0] + Bm.part[1]) + (Bm.part[2] + Bm.part[3])));
+    }
+}
+
 __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, int B, int K, int KP, int N, TbCounters *ctr,
                                                       const u64 *cand, float *top_q, uint32_t *top_tok, int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
-                                                      Adaptive ad, unsigned long long *dbg)
+                                                      Adaptive ad, int beam_width, unsigned long long *dbg)
 {
     __shared__ RankLds RL;
     __shared__ ExpandLds S;
+    __shared__ BeamLds BM;
     const unsigned long long t0_ = __builtin_amdgcn_s_memtime();
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), row = blockIdx.x;
     const int nc = ctr->cnt[row];
@@ -549,6 +612,10 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     if (ad.cost)
         for (int e = tid; e < N; e += 256) S.cost[e] = ad.cost[e];
     __syncthreads();
+    if (beam_width > 0) {                      // B rows = depths of the beam tree, K = min(V, width)
+        beam_block(S, BM, B, K, KP, beam_width, tid, parent, token, depth, rho, n_out, ahat);
+        return;
+    }
     if (w != 0) return;
     const unsigned long long t1_ = __builtin_amdgcn_s_memtime();
     if (dbg && lane == 0) { dbg[0] = t1_ - t0_; dbg[2] = tr_ - t0_; dbg[3] = ta_ - tr_; }
@@ -597,8 +664,9 @@ size_t btv_tree_build_workspace(int B, int V, int N)
     return BTV_WS_HEADER + t.part_bytes + t.cand_bytes + 2 * t.top_bytes;
 }
 
-static int tree_build_launch(const float *marginals, int B, int V, int N, const Adaptive &ad_in, int32_t *parent, int32_t *token,
-                             int32_t *depth, float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
+static int tree_build_launch(const float *marginals, int B, int V, int N, const Adaptive &ad_in, int beam_width, int32_t *parent,
+                             int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes,
+                             void *stream)
 {
     BTV_REQUIRE(marginals && parent && token && n_out, "null pointer");
     BTV_REQUIRE(B >= 1 && B <= MAXB, "B=%d outside [1,%d]", B, MAXB);
@@ -622,7 +690,7 @@ static int tree_build_launch(const float *marginals, int B, int V, int N, const 
     hipLaunchKernelGGL(tb_compact, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, t.K, part, ctr, cand);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(tb_rank_expand, dim3(B), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, ctr, cand, top_q, top_tok, parent,
-                       token, depth, rho, n_out, ahat, ad, g_tb_dbg);
+                       token, depth, rho, n_out, ahat, ad, beam_width, g_tb_dbg);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -631,7 +699,19 @@ int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent,
                    float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
 {
     const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
-    return tree_build_launch(marginals, B, V, N, none, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+    return tree_build_launch(marginals, B, V, N, none, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+}
+
+int btv_tree_build_beam(const float *marginals, int B, int V, int width, int depth_max, int32_t *parent, int32_t *token,
+                        int32_t *depth, float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(width >= 1 && width <= MAXW, "width=%d outside [1,%d]", width, MAXW);
+    BTV_REQUIRE(B >= 1 && B <= MAXB, "B=%d outside [1,%d]", B, MAXB);
+    BTV_REQUIRE(depth_max >= 1 && depth_max <= B, "depth=%d outside [1,B=%d]", depth_max, B);
+    // the first depth_max positions are ranked for their `width` best tokens; the rest of the path is shared
+    const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
+    return tree_build_launch(marginals, depth_max, V, width, none, width, parent, token, depth, rho, n_out, ahat, ws, ws_bytes,
+                             stream);
 }
 
 int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, const double *cost, double L_AR,
@@ -641,7 +721,7 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
     BTV_REQUIRE(cost != nullptr, "null pointer");
     BTV_REQUIRE(L_AR > 0.0, "L_AR must be positive");
     const Adaptive ad = { cost, L_AR, s_best, nullptr };
-    return tree_build_launch(marginals, B, V, N_max, ad, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+    return tree_build_launch(marginals, B, V, N_max, ad, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

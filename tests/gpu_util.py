@@ -119,3 +119,22 @@ def run_accept_greedy_lm_head(hidden_bits: np.ndarray, W_bits, parent, token) ->
     torch.cuda.synchronize()
     n = int(n_acc.item())
     return {"n_acc": n, "path": path.cpu().numpy()[:n], "bonus": int(bonus.item()), "argmax": am.cpu().numpy()}
+
+
+def run_tree_build_beam(marg: np.ndarray, width: int, depth_max: int) -> dict:
+    m = dev(marg.astype(np.float32))
+    B, V = marg.shape
+    cap = width * depth_max
+    parent = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    token = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    depth = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    rho = torch.full((cap,), -7.0, dtype=torch.float32, device="cuda")
+    n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ahat = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_build_workspace(depth_max, V, width))
+    btv.btv_tree_build_beam(m, width, depth_max, parent, token, depth, rho, n_out, ahat, ws)
+    torch.cuda.synchronize()
+    n = int(n_out.item())
+    return {"n": n, "parent": parent.cpu().numpy()[:n], "token": token.cpu().numpy()[:n],
+            "depth": depth.cpu().numpy()[:n], "rho": rho.cpu().numpy()[:n], "ahat": float(ahat.item()),
+            "status": int(btv.btv_workspace_status(ws))}
