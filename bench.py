@@ -177,6 +177,40 @@ def lm_head_bench(torch, btv, path, N, V, steps, warmup, hdim=4096):
         return {"accept_greedy_lm_head_us": None, "error": str(e)[:80]}
 
 
+def topology_bench(torch, btv, synth, path, steps, warmup):
+    """Sec. 4.3's comparison by the surrogate only: best-first (N = 60), beam 4 x 15 and the greedy chain of 16 built
+    from the same marginals, each verified by the same attention kernel (the bench's KV ring, first N rows of Q).
+    The marginals here are shaped like a confident drafter (top-1 probability 0.9 falling by 7 % per position)."""
+    out = []
+    marg = torch.from_numpy(synth.marginals_drafter_like(11, path.B, path.V)).cuda()
+    for name, nodes, width, depth in (("best_first", 60, 0, 0), ("beam_4x15", 60, 4, 15), ("chain_16", 16, 1, 16)):
+        parent = torch.empty(nodes, dtype=torch.int32, device="cuda")
+        token, dep = torch.empty_like(parent), torch.empty_like(parent)
+        rho = torch.empty(nodes, dtype=torch.float32, device="cuda")
+        n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ahat = torch.zeros(1, dtype=torch.float32, device="cuda")
+        if width:
+            ws = btv.alloc_workspace(btv.btv_tree_build_workspace(depth, path.V, width))
+            build = lambda: btv.btv_tree_build_beam(marg, width, depth, parent, token, dep, rho, n_out, ahat, ws)
+        else:
+            ws = btv.alloc_workspace(btv.btv_tree_build_workspace(path.B, path.V, nodes))
+            build = lambda: btv.btv_tree_build(marg, nodes, parent, token, dep, rho, n_out, ahat, ws)
+        build_ms = time_loop(torch, build, steps, warmup)
+        Q, O = path.Q[:nodes].contiguous(), path.O[:nodes].contiguous()
+        ws_a = btv.alloc_workspace(btv.btv_tree_verify_attn_workspace(nodes, path.L, path.Hq, path.Hkv, path.D, btv.BTV_BF16))
+        state = {"i": 0}
+
+        def attn():
+            k = state["i"] % len(path.K)
+            state["i"] += 1
+            btv.btv_tree_verify_attn(Q, path.K[k], path.Vv[k], parent, path.L, O, ws_a)
+        attn_ms = time_loop(torch, attn, steps, warmup)
+        out.append({"tree": name, "nodes": int(n_out.item()), "surrogate_ahat": round(float(ahat.item()), 4),
+                    "max_depth": int(dep.max().item()), "build_us": round(build_ms * 1e3, 3),
+                    "attn_us": round(attn_ms * 1e3, 3)})
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -268,6 +302,7 @@ def main():
     except RuntimeError as e:        # not enough memory beside the KV ring
         kvc = {"kv_commit_us": None, "error": str(e)[:80]}
     lmh = lm_head_bench(torch, btv, path, N, V, args.steps, args.warmup)
+    topo = topology_bench(torch, btv, synth, path, args.steps, args.warmup)
     path.setup_adaptive(256)
     adaptive_ms = time_loop(torch, path.build_adaptive, args.steps, args.warmup)
     adaptive = {"tree_build_adaptive_us": round(adaptive_ms * 1e3, 3), "N_max": 256, "N_star": int(path.ad_n.item()),
@@ -336,7 +371,7 @@ def main():
         "step_breakdown_us": {"tree_build": round(build_ms * 1e3, 3), "tree_verify_attn": round(attn_ms * 1e3, 3),
                               "tree_accept_greedy": round(accept_ms * 1e3, 3), "host_wall_per_step": round(wall_ms * 1e3, 3)},
         "roofline": roofline, "cpu_baseline": cpu, "curve_L8192": curve, "adaptive_budget": adaptive, "latency_calibration": calib,
-        "kv_commit": kvc, "lm_head": lmh,
+        "kv_commit": kvc, "lm_head": lmh, "topologies": topo,
         "context": "paper reports only end-to-end speedups (6.61x over autoregressive decoding, Qwen3-8B, A100) and a "
                    "whole-model T_verify of 22.0 ms at |T|=32 to 55.9 ms at |T|=1024; no number for this path exists",
     }

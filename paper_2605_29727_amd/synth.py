@@ -115,6 +115,23 @@ def marginals(seed: int, B: int, V: int, sigma: float, tag: str = "marg") -> np.
     return (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
 
 
+def marginals_drafter_like(seed: int, B: int, V: int, top1: float = 0.9, decay: float = 0.93, sigma: float = 3.0,
+                           tag: str = "marg_dl") -> np.ndarray:
+    """Draft marginals [B, V] fp32 shaped like a confident drafter whose confidence falls with the position: at
+    position k one token holds top1 * decay^k, the rest is spread as softmax(sigma * N(0,1)) over the vocabulary."""
+    base = marginals(seed, B, V, sigma, tag).astype(np.float64)
+    hot = integers(seed, tag + "_hot", (B,), 0, V)
+    out = np.empty((B, V), dtype=np.float64)
+    for k in range(B):
+        p = top1 * decay ** k
+        row = base[k].copy()
+        row[hot[k]] = 0.0
+        row *= (1.0 - p) / row.sum()
+        row[hot[k]] = p
+        out[k] = row
+    return out.astype(np.float32)
+
+
 def qkv(seed: int, M: int, L: int, Hq: int, Hkv: int, D: int, dtype: str, tag: str = ""):
     """Q [M,Hq,D], K and V [L+M,Hkv,D], all N(0,1), rounded once to `dtype`.
 

@@ -100,3 +100,16 @@ def test_bad_arguments(oracle):
     for w, d in [(0, 2), (2, 0), (2, 5)]:
         with pytest.raises(ValueError):
             oracle.tree_build_beam(marg, w, d)
+
+
+def test_fig4_ordering_on_drafter_like_marginals(oracle):
+    """The shape of the Sec. 4.3 comparison by the surrogate alone: at a matched budget best-first is ahead of the
+    4 x 15 beam, and both are ahead of the single chain of 16 (which is not budget-matched)."""
+    for seed in range(3):
+        marg = synth.marginals_drafter_like(seed, 16, 4096)
+        assert np.allclose(marg.sum(axis=1), 1.0, atol=1e-5) and marg.min() >= 0.0
+        assert np.allclose(marg.max(axis=1), 0.9 * 0.93 ** np.arange(16), rtol=1e-5)
+        bf = oracle.tree_build(marg, 60)["ahat"]
+        beam = oracle.tree_build_beam(marg, 4, 15)["ahat"]
+        chain = oracle.tree_build_beam(marg, 1, 16)["ahat"]
+        assert bf > beam > chain > 1.0
