@@ -1,0 +1,77 @@
+"""The whole step (tree_build -> tree_verify_attn -> tree_accept_greedy -> kv_commit) recorded into a HIP graph:
+every replay must give what the eager calls give on the same inputs.  The entry points only launch kernels (no
+allocation, no memset, no host synchronisation), which is what makes them recordable."""
+import numpy as np
+import pytest
+
+from paper_2605_29727_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_graph_replays_equal_eager(oracle):
+    import torch
+    from paper_2605_29727_amd import binding as btv
+    import gpu_util as G
+    B, V, N, L, Hq, Hkv, D, layers = 8, 20000, 48, 700, 8, 2, 128, 2
+    dev = "cuda"
+    marg = torch.empty((B, V), dtype=torch.float32, device=dev)
+    Q = torch.empty((N, Hq, D), dtype=torch.bfloat16, device=dev)
+    Kc = torch.empty((layers, L + N, Hkv, D), dtype=torch.bfloat16, device=dev)
+    Vc = torch.empty_like(Kc)
+    logits = torch.empty((N + 1, V), dtype=torch.bfloat16, device=dev)
+    parent = torch.zeros(N, dtype=torch.int32, device=dev)
+    token, depth, path = torch.zeros_like(parent), torch.zeros_like(parent), torch.zeros_like(parent)
+    rho = torch.zeros(N, dtype=torch.float32, device=dev)
+    n_out, n_acc, bonus = (torch.zeros(1, dtype=torch.int32, device=dev) for _ in range(3))
+    ahat = torch.zeros(1, dtype=torch.float32, device=dev)
+    O = torch.zeros_like(Q)
+    ws_b = btv.alloc_workspace(btv.btv_tree_build_workspace(B, V, N))
+    ws_a = btv.alloc_workspace(btv.btv_tree_verify_attn_workspace(N, L, Hq, Hkv, D, btv.BTV_BF16))
+    ws_c = btv.alloc_workspace(btv.btv_tree_accept_workspace(N, V, False))
+
+    def step():
+        btv.btv_tree_build(marg, N, parent, token, depth, rho, n_out, ahat, ws_b)
+        btv.btv_tree_verify_attn(Q, Kc[0], Vc[0], parent, L, O, ws_a)
+        btv.btv_tree_accept_greedy(logits, parent, token, path, n_acc, bonus, None, ws_c)
+        btv.btv_kv_commit(Kc, Vc, L, N, path, n_acc)
+
+    def load(seed):
+        m = synth.marginals(seed, B, V, 4.0)
+        t = synth.qkv(seed, N, L, Hq, Hkv, D, "bf16")
+        marg.copy_(torch.from_numpy(m))
+        Q.copy_(G.dev(t["Q"], True))
+        for l in range(layers):
+            Kc[l].copy_(G.dev(t["K"], True)); Vc[l].copy_(G.dev(t["V"], True))
+        # logits that accept a path of the tree the oracle builds from these marginals
+        tree = oracle.tree_build(m, N)
+        _, lf = synth.target_logits(seed, N + 1, V, 1.0, "bf16")
+        leaf = int(np.argmax(tree["depth"]))
+        ls, _ = synth.round_to_dtype(synth.plant_path(lf, tree["parent"], tree["token"], leaf).astype(np.float64), "bf16")
+        logits.copy_(G.dev(ls, True))
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [x.clone() for x in (parent, token, depth, rho, n_out, ahat, O, path[:int(n_acc.item())], n_acc, bonus, Kc, Vc)]
+
+    load(1)
+    step()                                   # eager warm-up: first calls configure the kernels
+    torch.cuda.synchronize()
+    load(1)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for seed in (1, 2, 3, 2):
+        load(seed)
+        g.replay()
+        got = snapshot()
+        assert int(got[8].item()) >= 1       # the planted path is accepted
+        load(seed)                           # the commit moved cache rows: restore the inputs
+        step()
+        want = snapshot()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b)
