@@ -2,14 +2,13 @@
 //
 // Sec. 3.3 / Prop. 3.3 / Algorithm 1's frontier rule at a fixed budget N: repeatedly emit the
 // frontier prefix with the largest path score rho (Eq. 1), then push its best child and its next
-// sibling.  Three kernels:
+// sibling.  Two kernels:
 //   1. tb_thread_max   per-thread maxima of the marginals (one pass over [B, V], all CUs);
-//   2. tb_compact      a bound below which no token can be among a position's K best
-//                      (K = min(V, N): a rank-j token is preceded by its j earlier siblings, so ranks >= N can
-//                      never be emitted), and the compaction of the tokens at or above it (a second pass, served
-//                      from cache): K plus a few candidates per position;
-//   3. tb_rank_expand  workgroup k ranks the candidates of position k (order: probability desc, token id asc);
-//                      the workgroup that finishes last runs the expansion on one wavefront, the frontier in
+//   2. tb_rank_expand  workgroup k derives from the maxima of position k a bound below which no token can be
+//                      among its K best (K = min(V, N): a rank-j token is preceded by its j earlier siblings, so
+//                      ranks >= N can never be emitted), reads again only the few slots that reach the bound,
+//                      and ranks the candidates found there (order: probability desc, token id asc); the
+//                      workgroup that finishes last runs the expansion on one wavefront, the frontier in
 //                      registers.
 // Keys are 64-bit  prob_bits << 32 | ~id  (probabilities are non-negative, so the bit pattern orders like
 // the value; keys are distinct).
@@ -26,7 +25,6 @@ typedef unsigned long long u64;
 
 constexpr int MAXB = BTV_MAX_DEPTH;
 constexpr int SCAN = 8192;        // marginals scanned per workgroup (256 threads x 32)
-constexpr int CAND_CAP = 4096;    // candidate keys kept per position
 
 __device__ __forceinline__ u64 make_key(float prob, uint32_t id)
 {
@@ -62,7 +60,7 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // row; thread t looks at elements 4t..4t+3 of every 1024 and keeps the largest probability it saw:
 // part[row][chunk][t].
 // ------------------------------------------------------------------------------------------------
-struct TbCounters { int cnt[MAXB]; int done; };
+struct TbCounters { int done; };
 
 template <typename F>
 __device__ __forceinline__ void scan_chunk(const float *src, bool aligned, int V, int chunk, int tid, F f)
@@ -89,101 +87,40 @@ __global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, i
     uint32_t mx = 0;
     scan_chunk(src, aligned, V, chunk, tid, [&](float p, int) { mx = umax(mx, prob_bits(p)); });
     part[((size_t)row * chunks + chunk) * 256 + tid] = mx;
-    if (chunk == 0 && tid == 0) {                              // the later kernels start after this one has ended
-        ctr->cnt[row] = 0;
-        if (row == 0) ctr->done = 0;
-    }
+    if (chunk == 0 && row == 0 && tid == 0) ctr->done = 0;     // the next kernel starts after this one has ended
 }
 
-// ------------------------------------------------------------------------------------------------
-// Step 2: the bound and the candidates.  Every per-thread maximum is a different token of the row, so the K-th
-// largest of them (K <= 256 <= their number) is a lower bound of the row's K-th largest probability, and a tight
-// one: it only falls short by the few tokens of the K best that share a thread with a better one.  Every
-// workgroup finds the 12-bit bin (sign-less float bits [30:19]: an eighth of a binade) that holds it, from a
-// histogram of the chunks*256 values, and takes the lower edge of that bin as the bound; then it appends the keys
-// of its chunk at or above the bound to the row's candidate list (unordered): K plus a few candidates per row.
-// cnt[row] counts the candidates; a count above CAND_CAP (heavily tied or otherwise degenerate probabilities)
-// tells tb_rank_expand to select from the row itself.
-// ------------------------------------------------------------------------------------------------
 constexpr int TBINS = 4096;
 
-__global__ __launch_bounds__(256) void tb_compact(const float *marg, int V, int chunks, int K, const uint32_t *part,
-                                                  TbCounters *ctr, u64 *cand)
-{
-    __shared__ u64 keys[1024];
-    __shared__ int hist[TBINS];
-    __shared__ int wsum[4];
-    __shared__ int sel_s, ncand_s, base_s;
-    const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y, lane = tid & 63, w = tid >> 6;
-    const float *src = marg + (size_t)row * V;
-    const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
-    const uint32_t *pr = part + (size_t)row * chunks * 256 + tid;
-    {
-        uint32_t pv[16];                                       // the loads are in flight while the histogram is cleared
-#pragma unroll
-        for (int j = 0; j < 16; ++j) pv[j] = j < chunks ? pr[(size_t)j * 256] : 0xFFFFFFFFu;
-#pragma unroll
-        for (int b = 0; b < TBINS / 256; ++b) hist[b * 256 + tid] = 0;
-        if (tid == 0) ncand_s = 0;
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 16; ++j) if (pv[j] != 0xFFFFFFFFu) atomicAdd(&hist[pv[j] >> 19], 1);
-        for (int j = 16; j < chunks; ++j) atomicAdd(&hist[pr[(size_t)j * 256] >> 19], 1);
-        __syncthreads();
-        int hb[16], own = 0;                                   // thread t owns bins 16t .. 16t+15
-#pragma unroll
-        for (int b = 0; b < 16; ++b) { hb[b] = hist[tid * 16 + b]; own += hb[b]; }
-        int suf = own;                                         // inclusive suffix sum over the higher threads
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int o = __shfl_down(suf, off);
-            if (lane + off < 64) suf += o;
-        }
-        if (lane == 0) wsum[w] = suf;
-        __syncthreads();
-        int above = suf - own;
-        for (int ww = w + 1; ww < 4; ++ww) above += wsum[ww];
-        if (above < K && above + own >= K) {
-            int cum = above, sel = tid * 16;
-#pragma unroll
-            for (int b = 15; b >= 0; --b) {
-                if (cum < K && cum + hb[b] >= K) sel = tid * 16 + b;
-                cum += hb[b];
-            }
-            sel_s = sel;
-        }
-        __syncthreads();
-    }
-    const uint32_t tau = (uint32_t)sel_s << 19;
-    scan_chunk(src, aligned, V, chunk, tid, [&](float p, int v) {
-        if (prob_bits(p) >= tau) {
-            const int pos = atomicAdd(&ncand_s, 1);
-            if (pos < 1024) keys[pos] = make_key(p, (uint32_t)v);
-        }
-    });
-    __syncthreads();
-    const int total = ncand_s;
-    // More than 1024 candidates in one chunk only happen when the bound is useless (ties): the row is then marked
-    // as overflowed.
-    if (tid == 0) base_s = atomicAdd(&ctr->cnt[row], total <= 1024 ? total : CAND_CAP + 1);
-    __syncthreads();
-    const int base = base_s;
-    if (total <= 1024)
-        for (int i = tid; i < total && base + i < CAND_CAP; i += 256) cand[(size_t)row * CAND_CAP + base + i] = keys[i];
-}
-
 // ------------------------------------------------------------------------------------------------
-// Step 3, part A: wavefront `row` ranks the candidates of its position and writes the K best into LDS.
-// Usual case (at most SELCAP candidates): every candidate is ranked by counting the candidates above it.
-// Otherwise the K-th largest key is found first by radix selection, one byte of the key per pass (histogram of
-// 256 bins per wavefront), over the candidate list or, when that overflowed, over the row of marginals itself;
-// the K keys at or above it are then ranked the same way.
+// Step 2 (inside tb_rank_expand): the bound and the candidates of one position.  Every per-thread maximum of
+// step 1 is a different token of the row, so the K-th largest of them (K <= 256 <= their number) is a lower bound
+// of the row's K-th largest probability, and a tight one: it only falls short by the few tokens of the K best
+// that share a slot with a better one.  The workgroup finds the 12-bit bin (sign-less float bits [30:19]: an
+// eighth of a binade) that holds it from a histogram of the chunks*256 maxima and takes the lower edge of that bin
+// as the bound; only slots whose maximum reaches the bound can hold candidates, so only those (about K of the
+// chunks*256) are read again, 32 elements each, and their elements at or above the bound become the candidate
+// list in LDS: K plus a few.
+// Step 3, part A: the candidates are ranked by counting the candidates above each (order: probability desc, token
+// id asc) and the K best go to the position's top list.  More than SELCAP candidates (heavily tied or otherwise
+// degenerate probabilities): the K-th largest key of the whole row is found by radix selection, one byte of the
+// key per pass (histogram of 256 bins, one wavefront), and the K keys at or above it are ranked the same way.
 // ------------------------------------------------------------------------------------------------
 constexpr int SELCAP = 512;
+constexpr int SLOTCAP = 1024;
 
-struct RankLds {                            // ranking of one position
-    u64 sel[SELCAP];
+struct RankLds {                            // bound and ranking of one position
+    union {
+        int bins[TBINS];                    // histogram of the per-thread maxima (before the candidates exist)
+        struct {
+            u64 sel[SELCAP];                // the candidates
+            uint16_t slot[SLOTCAP];         // slots (chunk * 256 + thread) whose maximum reaches the bound
+        };
+    };
     int hist[256];
+    int wsum[4];
+    int sel_bin;
+    int nslot;
     int nsel;
     int last;
 };
@@ -567,8 +504,9 @@ __device__ __forceinline__ void beam_block(const ExpandLds &S, BeamLds &Bm, int 
     }
 }
 
-__global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, int B, int K, int KP, int N, TbCounters *ctr,
-                                                      const u64 *cand, float *top_q, uint32_t *top_tok, int32_t *parent,
+__global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, int B, int K, int KP, int N, int chunks,
+                                                      TbCounters *ctr, const uint32_t *part, float *top_q, uint32_t *top_tok,
+                                                      int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
                                                       Adaptive ad, int beam_width, unsigned long long *dbg)
 {
@@ -577,24 +515,108 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     __shared__ BeamLds BM;
     const unsigned long long t0_ = __builtin_amdgcn_s_memtime();
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), row = blockIdx.x;
-    const int nc = ctr->cnt[row];
     float *q_row = top_q + (size_t)row * KP;
     uint32_t *tok_row = top_tok + (size_t)row * KP;
-    if (nc <= SELCAP) {
-        const u64 *src = cand + (size_t)row * CAND_CAP;
-        for (int j = tid; j < nc; j += 256) RL.sel[j] = src[j];
-        __syncthreads();
-        rank_keys(RL.sel, nc, K, KP, q_row, tok_row, tid, 256);
-    } else if (w == 0) {                       // rare: one wavefront selects the K best first
-        if (nc <= CAND_CAP) {
-            const u64 *src = cand + (size_t)row * CAND_CAP;
-            wave_select_rank([&](auto f) { for (int j = lane; j < nc; j += 64) f(src[j]); },
-                             K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
-        } else {
-            const float *src = marg + (size_t)row * V;
-            wave_select_rank([&](auto f) { for (int v = lane; v < V; v += 64) f(make_key(src[v], (uint32_t)v)); },
-                             K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
+    const float *src = marg + (size_t)row * V;
+    const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
+    const uint32_t *pr = part + (size_t)row * chunks * 256 + tid;
+    // ---- the bound: K-th largest per-thread maximum of the row, down to the lower edge of its histogram bin ---
+    uint32_t pv[16];                                           // the loads are in flight while the histogram is cleared
+#pragma unroll
+    for (int j = 0; j < 16; ++j) pv[j] = j < chunks ? pr[(size_t)j * 256] : 0xFFFFFFFFu;
+#pragma unroll
+    for (int b = 0; b < TBINS / 256; ++b) RL.bins[b * 256 + tid] = 0;
+    if (tid == 0) { RL.nsel = 0; RL.nslot = 0; }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; ++j) if (pv[j] != 0xFFFFFFFFu) atomicAdd(&RL.bins[pv[j] >> 19], 1);
+    for (int j = 16; j < chunks; ++j) atomicAdd(&RL.bins[pr[(size_t)j * 256] >> 19], 1);
+    __syncthreads();
+    {
+        int hb[16], own = 0;                                   // thread t owns bins 16t .. 16t+15
+#pragma unroll
+        for (int b = 0; b < 16; ++b) { hb[b] = RL.bins[tid * 16 + b]; own += hb[b]; }
+        int suf = own;                                         // inclusive suffix sum over the higher threads
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_down(suf, off);
+            if (lane + off < 64) suf += o;
         }
+        if (lane == 0) RL.wsum[w] = suf;
+        __syncthreads();
+        int above = suf - own;
+        for (int ww = w + 1; ww < 4; ++ww) above += RL.wsum[ww];
+        if (above < K && above + own >= K) {
+            int cum = above, sel = tid * 16;
+#pragma unroll
+            for (int b = 15; b >= 0; --b) {
+                if (cum < K && cum + hb[b] >= K) sel = tid * 16 + b;
+                cum += hb[b];
+            }
+            RL.sel_bin = sel;
+        }
+        __syncthreads();                                       // the histogram is dead from here on: sel[] takes its place
+    }
+    const uint32_t tau = (uint32_t)RL.sel_bin << 19;
+    // ---- the candidates: the slots whose maximum reaches the bound are listed, then read again, one 16-byte
+    // piece of a slot per thread and up to four pieces in flight per thread ---------------------------------------
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (pv[j] != 0xFFFFFFFFu && pv[j] >= tau) {
+            const int pos = atomicAdd(&RL.nslot, 1);
+            if (pos < SLOTCAP) RL.slot[pos] = (uint16_t)(j * 256 + tid);
+        }
+    for (int j = 16; j < chunks && j < 256; ++j)
+        if (pr[(size_t)j * 256] >= tau) {
+            const int pos = atomicAdd(&RL.nslot, 1);
+            if (pos < SLOTCAP) RL.slot[pos] = (uint16_t)(j * 256 + tid);
+        }
+    __syncthreads();
+    const int nslot = RL.nslot;
+    auto take = [&](float p, int v) {
+        if (prob_bits(p) >= tau) {
+            const int pos = atomicAdd(&RL.nsel, 1);
+            if (pos < SELCAP) RL.sel[pos] = make_key(p, (uint32_t)v);
+        }
+    };
+    if (nslot <= SLOTCAP && chunks <= 256) {
+        constexpr int PPS = SCAN / 1024;                       // 16-byte pieces per slot
+        const int total = nslot * PPS;
+        for (int base = 0; base < total; base += 4 * 256) {
+            float4 a[4];
+            int v0[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 256 + tid;
+                v0[u] = -1;
+                a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i < total) {
+                    const int sl = RL.slot[i / PPS];
+                    v0[u] = (sl >> 8) * SCAN + (i % PPS) * 1024 + (sl & 255) * 4;
+                    if (aligned && v0[u] + 4 <= V) a[u] = *reinterpret_cast<const float4 *>(src + v0[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (v0[u] < 0) continue;
+                if (aligned && v0[u] + 4 <= V) {
+                    take(a[u].x, v0[u]); take(a[u].y, v0[u] + 1); take(a[u].z, v0[u] + 2); take(a[u].w, v0[u] + 3);
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (v0[u] + e < V) take(src[v0[u] + e], v0[u] + e);
+                }
+            }
+        }
+    } else if (tid == 0) {
+        RL.nsel = SELCAP + 1;                                  // too many slots tie at the bound: select from the row
+    }
+    __syncthreads();
+    const int nc = RL.nsel;
+    if (nc <= SELCAP) {
+        rank_keys(RL.sel, nc, K, KP, q_row, tok_row, tid, 256);
+    } else if (w == 0) {                       // rare: one wavefront selects the K best of the row first
+        wave_select_rank([&](auto f) { for (int v = lane; v < V; v += 64) f(make_key(src[v], (uint32_t)v)); },
+                         K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
     }
     // ---- the workgroup that finishes last expands -------------------------------------------------------------
     const unsigned long long tr_ = __builtin_amdgcn_s_memtime();
@@ -633,7 +655,7 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
 
 int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 
-struct TopkPlan { int K, KP, chunks; size_t part_bytes, cand_bytes, top_bytes; };
+struct TopkPlan { int K, KP, chunks; size_t part_bytes, top_bytes; };
 
 TopkPlan topk_plan(int B, int V, int N)
 {
@@ -642,7 +664,6 @@ TopkPlan topk_plan(int B, int V, int N)
     t.KP = std::max(next_pow2(t.K), 1);
     t.chunks = (V + SCAN - 1) / SCAN;
     t.part_bytes = btv_align_up((size_t)B * t.chunks * 256 * 4, BTV_WS_ALIGN);
-    t.cand_bytes = btv_align_up((size_t)B * CAND_CAP * 8, BTV_WS_ALIGN);
     t.top_bytes = btv_align_up((size_t)B * t.KP * 4, BTV_WS_ALIGN);
     return t;
 }
@@ -661,7 +682,7 @@ size_t btv_tree_build_workspace(int B, int V, int N)
 {
     if (B < 1 || B > MAXB || V < 1 || N < 1 || N > BTV_MAX_NODES) return 0;
     TopkPlan t = topk_plan(B, V, N);
-    return BTV_WS_HEADER + t.part_bytes + t.cand_bytes + 2 * t.top_bytes;
+    return BTV_WS_HEADER + t.part_bytes + 2 * t.top_bytes;
 }
 
 static int tree_build_launch(const float *marginals, int B, int V, int N, const Adaptive &ad_in, int beam_width, int32_t *parent,
@@ -680,16 +701,13 @@ static int tree_build_launch(const float *marginals, int B, int V, int N, const 
     static_assert(sizeof(TbCounters) + 64 <= BTV_WS_HEADER, "counters live in the workspace header");
     TbCounters *ctr = reinterpret_cast<TbCounters *>(base + 64);
     uint32_t *part = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER);
-    u64 *cand = reinterpret_cast<u64 *>(base + BTV_WS_HEADER + t.part_bytes);
-    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes);
-    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.part_bytes + t.cand_bytes + t.top_bytes);
+    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.part_bytes);
+    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.part_bytes + t.top_bytes);
     Adaptive ad = ad_in;
     ad.flag = reinterpret_cast<uint32_t *>(base);
     hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, part, ctr);
     BTV_HIP(hipGetLastError());
-    hipLaunchKernelGGL(tb_compact, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, t.K, part, ctr, cand);
-    BTV_HIP(hipGetLastError());
-    hipLaunchKernelGGL(tb_rank_expand, dim3(B), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, ctr, cand, top_q, top_tok, parent,
+    hipLaunchKernelGGL(tb_rank_expand, dim3(B), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, t.chunks, ctr, part, top_q, top_tok, parent,
                        token, depth, rho, n_out, ahat, ad, beam_width, g_tb_dbg);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
