@@ -701,8 +701,57 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     // both halves of a wave hold partial row sums of the same queries
     l_run += __shfl_xor(l_run, 32);
 
-    // ---- merge the key-waves of each row-wave through LDS: donors write side by side, wave kw = 0 reduces ----
-    if (KW > 1) {
+    // ---- merge the key-waves of each row-wave through LDS ---------------------------------------------------
+    // Two key-waves: each keeps one half of the channels and hands the other half to its partner, so both merge,
+    // scale and store half a row.  dt0 .. dt0 + DTK - 1 are the channel blocks this wave ends up with.
+    int dt0 = 0;
+    constexpr int DTK = KW == 2 ? DT / 2 : DT;
+    float fin[DTK][16];                             // what this wave stores
+    float amax = 0.f;                               // bound on the row's largest magnitude (for the fp16 partials)
+    if constexpr (KW == 2) {
+        constexpr int SLOT = (DTK * 16 + 3) * 64;   // floats a wave hands over
+        float *mg = reinterpret_cast<float *>(smem) + rw * 2 * SLOT;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) amax = fmaxf(amax, fabsf(oacc[dt][v]));
+        amax = fmaxf(amax, __shfl_xor(amax, 32));   // the other half of the wave holds the row's other channels
+        wait_vmcnt<0>();
+        __syncthreads();                            // every wave is done with the ring
+        float *out = mg + kw * SLOT;
+        auto give = [&](auto first) {               // the channel blocks first .. first + DTK - 1 go to the partner
+            constexpr int F = decltype(first)::value;
+#pragma unroll
+            for (int dt = 0; dt < DTK; ++dt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) out[(dt * 16 + v) * 64 + l] = oacc[F + dt][v];
+        };
+        if (kw == 0) give(std::integral_constant<int, DTK>{}); else give(std::integral_constant<int, 0>{});
+        out[(DTK * 16) * 64 + l] = m_run;
+        out[(DTK * 16 + 1) * 64 + l] = l_run;
+        out[(DTK * 16 + 2) * 64 + l] = amax;
+        __syncthreads();
+        const float *in = mg + (kw ^ 1) * SLOT;
+        const float m1 = in[(DTK * 16) * 64 + l], l1 = in[(DTK * 16 + 1) * 64 + l], x1 = in[(DTK * 16 + 2) * 64 + l];
+        const float mn = fmaxf(m_run, m1);
+        const float a0 = __builtin_amdgcn_exp2f((m_run - mn) * p.scale_log2);
+        const float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
+        // both waves must arrive at the same l and bound: sums of the same two products, order fixed by kw
+        const float la = kw == 0 ? l_run * a0 : l1 * a1, lb = kw == 0 ? l1 * a1 : l_run * a0;
+        const float xa = kw == 0 ? amax * a0 : x1 * a1, xb = kw == 0 ? x1 * a1 : amax * a0;
+        m_run = mn;
+        l_run = la + lb;
+        amax = xa + xb;                             // >= the merged row's largest magnitude, at most twice it
+        auto take = [&](auto first) {
+            constexpr int F = decltype(first)::value;
+#pragma unroll
+            for (int dt = 0; dt < DTK; ++dt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) fin[dt][v] = oacc[F + dt][v] * a0 + in[(dt * 16 + v) * 64 + l] * a1;
+        };
+        if (kw == 0) take(std::integral_constant<int, 0>{}); else take(std::integral_constant<int, DTK>{});
+        dt0 = kw * DTK;                             // the kept blocks now sit in oacc[0 .. DTK)
+    } else if (KW > 1) {                            // donors write side by side, wave kw = 0 reduces
         constexpr int SLOT = (DT * 16 + 2) * 64;    // floats per donor
         float *mg = reinterpret_cast<float *>(smem) + (rw * (KW - 1)) * SLOT;
         wait_vmcnt<0>();
@@ -735,44 +784,45 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         }
     }
     BTV_STAMP(3);
-    if (kw != 0 || !rvalid) return;
+    if ((KW != 2 && kw != 0) || !rvalid) return;
+    if constexpr (KW != 2) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { fin[dt][v] = oacc[dt][v]; amax = fmaxf(amax, fabsf(oacc[dt][v])); }
+        amax = fmaxf(amax, __shfl_xor(amax, 32));
+    }
 
     // ---- write: final bf16 rows when this request has a single split, scaled fp16 partials otherwise ---
     if (nsplit_r == 1) {
         const float inv = 1.0f / l_run;
-        uint16_t *Op = static_cast<uint16_t *>(p.O) + orow * D;
+        uint16_t *Op = static_cast<uint16_t *>(p.O) + orow * D + dt0 * 32;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DTK; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                uint32_t lo = float_to_bf16_bits(oacc[dt][q4 * 4 + 0] * inv) | (float_to_bf16_bits(oacc[dt][q4 * 4 + 1] * inv) << 16);
-                uint32_t hi = float_to_bf16_bits(oacc[dt][q4 * 4 + 2] * inv) | (float_to_bf16_bits(oacc[dt][q4 * 4 + 3] * inv) << 16);
+                uint32_t lo = float_to_bf16_bits(fin[dt][q4 * 4 + 0] * inv) | (float_to_bf16_bits(fin[dt][q4 * 4 + 1] * inv) << 16);
+                uint32_t hi = float_to_bf16_bits(fin[dt][q4 * 4 + 2] * inv) | (float_to_bf16_bits(fin[dt][q4 * 4 + 3] * inv) << 16);
                 *reinterpret_cast<uint2 *>(Op + dt * 32 + q4 * 8 + h * 4) = make_uint2(lo, hi);
             }
     } else {
-        // Partials travel as fp16 relative to the row's largest magnitude (kept in fp32 beside m and l): half the
-        // bytes of fp32 to write, flush at the end of the kernel and read back, at a relative error of 2^-11 of that
-        // magnitude, well below the final bf16 rounding.
-        float amax = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) amax = fmaxf(amax, fabsf(oacc[dt][v]));
-        amax = fmaxf(amax, __shfl_xor(amax, 32));           // the other half of the wave holds the row's other channels
+        // Partials travel as fp16 relative to (a bound within a factor two of) the row's largest magnitude, kept
+        // in fp32 beside m and l: half the bytes of fp32 to write, flush at the end of the kernel and read back, at
+        // a relative error of at most 2^-10 of that magnitude, below the final bf16 rounding.
         const float sc = amax > 0.f ? 1.0f / amax : 0.f;
         const size_t prow = (size_t)bx * p.total_rows + orow;
-        _Float16 *Pp = p.Opart + prow * D;
+        _Float16 *Pp = p.Opart + prow * D + dt0 * 32;
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DTK; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const h2 lo = { (_Float16)(oacc[dt][q4 * 4 + 0] * sc), (_Float16)(oacc[dt][q4 * 4 + 1] * sc) };
-                const h2 hi = { (_Float16)(oacc[dt][q4 * 4 + 2] * sc), (_Float16)(oacc[dt][q4 * 4 + 3] * sc) };
+                const h2 lo = { (_Float16)(fin[dt][q4 * 4 + 0] * sc), (_Float16)(fin[dt][q4 * 4 + 1] * sc) };
+                const h2 hi = { (_Float16)(fin[dt][q4 * 4 + 2] * sc), (_Float16)(fin[dt][q4 * 4 + 3] * sc) };
                 *reinterpret_cast<uint2 *>(Pp + dt * 32 + q4 * 8 + h * 4) =
                     make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
             }
-        if (h == 0) *reinterpret_cast<float4 *>(p.ML + prow * 4) = make_float4(m_run, l_run, amax, 0.f);
+        if (h == 0 && kw == 0) *reinterpret_cast<float4 *>(p.ML + prow * 4) = make_float4(m_run, l_run, amax, 0.f);
     }
 #ifdef BTV_EXPERIMENT
     if (p.dbg && tid == 0) {
