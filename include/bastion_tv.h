@@ -90,6 +90,15 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
                             void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * stream_read -- measurement aid, not part of the method: reads `bytes` bytes at src once with
+ * all CUs (16-byte loads, nothing else), so that a benchmark can time what a plain streaming read
+ * achieves on the machine it runs on and quote kernels against that beside the datasheet peak.
+ *   src DEVICE, 16-byte aligned, bytes a multiple of 16; sink DEVICE, >= 16384 bytes, receives
+ *   a checksum word per workgroup (xor-accumulated: its content is of no use).
+ * ------------------------------------------------------------------------------------------- */
+int btv_stream_read(const void *src, size_t bytes, void *sink, size_t sink_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * tree_build_beam -- the beam-search tree that Sec. 4.3 compares best-first expansion with:
  * depth by depth, of all one-token extensions of the prefixes kept at the previous depth, the
  * `width` with the largest path score (Eq. 1) are kept: a width x depth rectangle below the

@@ -20,7 +20,7 @@ BTV_MAX_NODES, BTV_MAX_DEPTH, BTV_PAGE, BTV_ANC_WORDS = 256, 16, 16, 8
 BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
-    "btv_last_error", "btv_version", "btv_workspace_status", "btv_tree_build_workspace", "btv_tree_build",
+    "btv_last_error", "btv_version", "btv_workspace_status", "btv_stream_read", "btv_tree_build_workspace", "btv_tree_build",
     "btv_tree_build_adaptive", "btv_tree_build_beam", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
     "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
@@ -121,6 +121,12 @@ def btv_tree_build_adaptive(marginals, N_max: int, cost, L_AR: float, parent, to
     _check(lib().btv_tree_build_adaptive(_ptr(marginals), B, V, N_max, _ptr(cost), C.c_double(L_AR), _ptr(parent),
                                          _ptr(token), _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(s_best),
                                          _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_stream_read(src, sink) -> None:
+    """Measurement aid: one streaming read of `src` (any contiguous tensor) by all CUs."""
+    _check(lib().btv_stream_read(_ptr(src), C.c_size_t(src.numel() * src.element_size()), _ptr(sink),
+                                 C.c_size_t(sink.numel() * sink.element_size()), _stream()))
 
 
 def btv_tree_build_beam(marginals, width: int, depth_max: int, parent, token, depth, rho, n_out, ahat, ws) -> None:

@@ -14,7 +14,40 @@ int btv_fail(int code, const char *fmt, ...)
     return code;
 }
 
+namespace {
+// Streaming read for the bandwidth ceiling: every workgroup owns a contiguous piece, a wave reads 1 KiB per load
+// instruction, four loads in flight per thread; the words are folded into one per workgroup so that the loads
+// cannot be dropped.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t per_wg, size_t n16,
+                                                          uint32_t *__restrict__ sink)
+{
+    const size_t lo = (size_t)blockIdx.x * per_wg, hi = lo + per_wg < n16 ? lo + per_wg : n16;
+    uint32_t acc = 0;
+    size_t i = lo + threadIdx.x;
+    for (; i + 3 * 256 < hi; i += 4 * 256) {
+        const uint4 a = src[i], b = src[i + 256], c = src[i + 512], d = src[i + 768];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < hi; i += 256) { const uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+    for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
+}
+}  // namespace
+
 extern "C" {
+
+int btv_stream_read(const void *src, size_t bytes, void *sink, size_t sink_bytes, void *stream)
+{
+    BTV_REQUIRE(src != nullptr && sink != nullptr, "null pointer");
+    BTV_REQUIRE((reinterpret_cast<uintptr_t>(src) & 15) == 0 && bytes % 16 == 0, "src must be 16-byte aligned, bytes a multiple of 16");
+    const int wgs = 256 * 16;
+    BTV_REQUIRE(sink_bytes >= (size_t)wgs * 4, "sink needs %d bytes", wgs * 4);
+    const size_t n16 = bytes / 16, per_wg = ((n16 + wgs - 1) / wgs + 1023) / 1024 * 1024;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(wgs), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), per_wg, n16, static_cast<uint32_t *>(sink));
+    BTV_HIP(hipGetLastError());
+    return BTV_OK;
+}
 
 const char *btv_last_error(void) { return g_err; }
 
