@@ -282,6 +282,28 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     ws = btv.alloc_workspace(btv.btv_tree_verify_attn_paged_workspace(len(Ls), max(Ns), max(Ls), Hq, Hkv, D))
     ms = time_loop(torch, lambda: btv.btv_tree_verify_attn_paged(Q, Kp, Vp, bt, q_offset, prefix, par, max(Ns), max(Ls), O, ws),
                    steps, warmup)
+    # the steps before and after it for the same batch, one launch each
+    nb = len(Ls)
+    mg = torch.softmax(torch.randn((nb, 16, V), dtype=torch.float32, device="cuda") * 3.0, dim=-1)
+    nn_ = torch.tensor(Ns, dtype=torch.int32, device="cuda")
+    tok = torch.zeros(total, dtype=torch.int32, device="cuda")
+    dep, pth = torch.zeros_like(tok), torch.zeros_like(tok)
+    rho = torch.zeros(total, dtype=torch.float32, device="cuda")
+    n_out, n_acc, bonus = (torch.zeros(nb, dtype=torch.int32, device="cuda") for _ in range(3))
+    ahat = torch.zeros(nb, dtype=torch.float32, device="cuda")
+    ws_b = btv.alloc_workspace(btv.btv_tree_build_batch_workspace(nb, 16, V, max(Ns)))
+    lg = torch.randn((total + nb, V), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    ws_c = btv.alloc_workspace(btv.btv_tree_accept_batch_workspace(nb, total, V))
+    build_b = lambda: btv.btv_tree_build_batch(mg, nn_, q_offset, max(Ns), par, tok, dep, rho, n_out, ahat, ws_b)
+    accept_b = lambda: btv.btv_tree_accept_greedy_batch(lg, par, tok, q_offset, max(Ns), pth, n_acc, bonus, None, ws_c)
+    attn_b = lambda: btv.btv_tree_verify_attn_paged(Q, Kp, Vp, bt, q_offset, prefix, par, max(Ns), max(Ls), O, ws)
+    build_ms = time_loop(torch, build_b, steps, warmup)        # (also replaces the random trees by built ones)
+    accept_ms = time_loop(torch, accept_b, steps, warmup)
+
+    def step_b():
+        build_b(); attn_b(); accept_b()
+    step_ms = time_loop(torch, step_b, steps, warmup)
+    ms = time_loop(torch, attn_b, steps, warmup)
     ab = sum(algorithmic_bytes(l, n, Hq, Hkv, D) for l, n in zip(Ls, Ns))
     fl = sum(4 * Hq * D * n * l for l, n in zip(Ls, Ns))
     t_hbm, t_mfma = ab / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -289,6 +311,8 @@ def other_configs(torch, btv, synth, V, steps, warmup):
                             "tflops": round(fl / (ms * 1e-3) / 1e12, 1),
                             "frac_roofline": round(max(t_hbm, t_mfma) / (ms * 1e-3), 4),
                             "binding": "hbm" if t_hbm >= t_mfma else "mfma", "sum_L": sum(Ls), "sum_N": sum(Ns),
+                            "tree_build_batch_us": round(build_ms * 1e3, 3),
+                            "tree_accept_greedy_batch_us": round(accept_ms * 1e3, 3), "step_us": round(step_ms * 1e3, 3),
                             "kv_MB": round(2 * num_blocks * 16 * Hkv * D * 2 / 2 ** 20, 1)}
     return out
 

@@ -90,6 +90,34 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
                             void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Batches of requests in one launch (the ragged batch of the paged attention entry point, for the
+ * steps before and after it).  Requests are independent; request r owns the output rows
+ * q_offset[r] .. q_offset[r+1]-1 (the same array the paged attention takes).
+ *
+ * tree_build_batch: marginals [batch,B,V] fp32; n_nodes [batch] int32 DEVICE = budget N_r of each
+ *   request, 0 <= N_r <= min(N_max, q_offset[r+1]-q_offset[r]); parent/token/depth/rho [total]
+ *   written at q_offset[r] with node ids local to the request; n_out, ahat [batch].  N_max HOST:
+ *   upper bound of any N_r (sizes the top lists and the workspace).  A request that violates
+ *   the bounds gets n_out = 0 and raises the data flag.
+ * tree_accept_greedy_batch: logits [total_M + batch, V]: request r owns rows q_offset[r]+r ..
+ *   q_offset[r+1]+r, its root row first; parent/token [total_M] local ids; path [total_M] written at
+ *   q_offset[r]; n_acc, bonus [batch]; argmax_out [total_M + batch] optional.  M_max HOST: upper
+ *   bound of any request's node count (<= BTV_MAX_NODES); a request with no node or more than
+ *   M_max gets n_acc = 0 and raises the data flag.
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_build_batch_workspace(int batch, int B, int V, int N_max);
+int btv_tree_build_batch(const float *marginals, int batch, int B, int V, const int32_t *n_nodes,
+                         const int32_t *q_offset, int N_max, int32_t *parent, int32_t *token,
+                         int32_t *depth, float *rho, int32_t *n_out, float *ahat, void *ws,
+                         size_t ws_bytes, void *stream);
+size_t btv_tree_accept_batch_workspace(int batch, int total_M, int V);
+int btv_tree_accept_greedy_batch(const void *logits, int dtype, const int32_t *parent,
+                                 const int32_t *token, const int32_t *q_offset, int batch,
+                                 int total_M, int M_max, int V, int32_t *path, int32_t *n_acc,
+                                 int32_t *bonus, int32_t *argmax_out, void *ws, size_t ws_bytes,
+                                 void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * stream_read -- measurement aid, not part of the method: reads `bytes` bytes at src once with
  * all CUs (16-byte loads, nothing else), so that a benchmark can time what a plain streaming read
  * achieves on the machine it runs on and quote kernels against that beside the datasheet peak.

@@ -21,7 +21,8 @@ BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "btv_last_error", "btv_version", "btv_workspace_status", "btv_stream_read", "btv_tree_build_workspace", "btv_tree_build",
-    "btv_tree_build_adaptive", "btv_tree_build_beam", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
+    "btv_tree_build_adaptive", "btv_tree_build_beam", "btv_tree_build_batch_workspace", "btv_tree_build_batch",
+    "btv_tree_accept_batch_workspace", "btv_tree_accept_greedy_batch", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
     "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
     "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
@@ -49,7 +50,8 @@ def lib() -> C.CDLL:
         L.btv_last_error.restype = C.c_char_p
         for n in ("btv_tree_build_workspace", "btv_tree_verify_attn_workspace",
                   "btv_tree_verify_attn_paged_workspace", "btv_tree_accept_workspace",
-                  "btv_tree_accept_lm_head_workspace"):
+                  "btv_tree_accept_lm_head_workspace", "btv_tree_build_batch_workspace",
+                  "btv_tree_accept_batch_workspace"):
             getattr(L, n).restype = C.c_size_t
         for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_build_beam", "btv_tree_ancestor_mask",
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_accept_greedy",
@@ -127,6 +129,30 @@ def btv_stream_read(src, sink) -> None:
     """Measurement aid: one streaming read of `src` (any contiguous tensor) by all CUs."""
     _check(lib().btv_stream_read(_ptr(src), C.c_size_t(src.numel() * src.element_size()), _ptr(sink),
                                  C.c_size_t(sink.numel() * sink.element_size()), _stream()))
+
+
+def btv_tree_build_batch_workspace(batch: int, B: int, V: int, N_max: int) -> int:
+    return int(lib().btv_tree_build_batch_workspace(batch, B, V, N_max))
+
+
+def btv_tree_build_batch(marginals, n_nodes, q_offset, N_max: int, parent, token, depth, rho, n_out, ahat, ws) -> None:
+    batch, B, V = marginals.shape
+    _check(lib().btv_tree_build_batch(_ptr(marginals), batch, B, V, _ptr(n_nodes), _ptr(q_offset), int(N_max), _ptr(parent),
+                                      _ptr(token), _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(ws),
+                                      C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_accept_batch_workspace(batch: int, total_M: int, V: int) -> int:
+    return int(lib().btv_tree_accept_batch_workspace(batch, total_M, V))
+
+
+def btv_tree_accept_greedy_batch(logits, parent, token, q_offset, M_max: int, path, n_acc, bonus, argmax_out, ws) -> None:
+    rows, V = logits.shape
+    batch = q_offset.numel() - 1
+    _check(lib().btv_tree_accept_greedy_batch(_ptr(logits), _dtype_code(logits), _ptr(parent), _ptr(token), _ptr(q_offset),
+                                              batch, rows - batch, int(M_max), V, _ptr(path), _ptr(n_acc), _ptr(bonus),
+                                              _ptr(argmax_out), _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0),
+                                              _stream()))
 
 
 def btv_tree_build_beam(marginals, width: int, depth_max: int, parent, token, depth, rho, n_out, ahat, ws) -> None:

@@ -81,15 +81,30 @@ __global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, 
     }
 }
 
-// One workgroup: finish the argmax of every row, then walk the tree.
+// One workgroup per request: finish the argmax of every row, then walk the tree.  With q_offset (a batch),
+// request r owns nodes q_offset[r] .. q_offset[r+1] - 1 and logit rows q_offset[r] + r .. q_offset[r+1] + r (its
+// root row first); without, there is one request of M nodes.
 __global__ __launch_bounds__(256) void greedy_walk(const Best *part, int chunks, const int32_t *parent,
                                                    const int32_t *token, int M, int32_t *path, int32_t *n_acc,
-                                                   int32_t *bonus, int32_t *argmax_out)
+                                                   int32_t *bonus, int32_t *argmax_out, const int32_t *q_offset,
+                                                   uint32_t *flag)
 {
     __shared__ int t[BTV_MAX_NODES + 1];
     __shared__ int par[BTV_MAX_NODES], tok[BTV_MAX_NODES];
     __shared__ int next;
     const int tid = threadIdx.x;
+    if (q_offset) {
+        const int rq = blockIdx.x, o0 = q_offset[rq], m = q_offset[rq + 1] - o0;
+        n_acc += rq; bonus += rq;
+        if (o0 < 0 || m < 1 || m > M) {                      // M = the largest request the caller announced
+            if (tid == 0) { atomicOr(flag, 32u); *n_acc = 0; *bonus = 0; }
+            return;
+        }
+        M = m;
+        part += (size_t)(o0 + rq) * chunks;
+        parent += o0; token += o0; path += o0;
+        if (argmax_out) argmax_out += o0 + rq;
+    }
     for (int r = tid; r <= M; r += 256) {
         Best b = part[(size_t)r * chunks];
         for (int c = 1; c < chunks; ++c) best_take(b, part[(size_t)r * chunks + c].v, part[(size_t)r * chunks + c].i);
@@ -626,7 +641,7 @@ int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent,
     else hipLaunchKernelGGL(argmax_chunks<false>, dim3(chunks, M + 1), dim3(256), 0, st, logits, V, part);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, part, chunks, parent, token, M, path, n_acc, bonus,
-                       argmax_out);
+                       argmax_out, static_cast<const int32_t *>(nullptr), static_cast<uint32_t *>(nullptr));
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -661,7 +676,38 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
     if (rc) return rc;
     hipLaunchKernelGGL(argmax_merge, dim3(R), dim3(256), 0, st, part, chunks, best);
     BTV_HIP(hipGetLastError());
-    hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, best, 1, parent, token, M, path, n_acc, bonus, argmax_out);
+    hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, best, 1, parent, token, M, path, n_acc, bonus, argmax_out,
+                       static_cast<const int32_t *>(nullptr), static_cast<uint32_t *>(nullptr));
+    BTV_HIP(hipGetLastError());
+    return BTV_OK;
+}
+
+size_t btv_tree_accept_batch_workspace(int batch, int total_M, int V)
+{
+    if (batch < 1 || total_M < 1 || V < 1) return 0;
+    int chunks = (V + ACHUNK - 1) / ACHUNK;
+    return BTV_WS_HEADER + btv_align_up(((size_t)total_M + batch) * chunks * sizeof(Best), BTV_WS_ALIGN);
+}
+
+int btv_tree_accept_greedy_batch(const void *logits, int dtype, const int32_t *parent, const int32_t *token,
+                                 const int32_t *q_offset, int batch, int total_M, int M_max, int V, int32_t *path,
+                                 int32_t *n_acc, int32_t *bonus, int32_t *argmax_out, void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(logits && parent && token && q_offset && path && n_acc && bonus, "null pointer");
+    BTV_REQUIRE(dtype == BTV_F32 || dtype == BTV_BF16, "dtype=%d unsupported", dtype);
+    BTV_REQUIRE(batch >= 1 && total_M >= batch, "batch=%d, total_M=%d", batch, total_M);
+    BTV_REQUIRE(M_max >= 1 && M_max <= BTV_MAX_NODES, "M_max=%d outside [1,%d]", M_max, BTV_MAX_NODES);
+    BTV_REQUIRE(V >= 1, "V=%d", V);
+    int rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_batch_workspace(batch, total_M, V));
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Best *part = reinterpret_cast<Best *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
+    const int chunks = (V + ACHUNK - 1) / ACHUNK, rows = total_M + batch;
+    if (dtype == BTV_BF16) hipLaunchKernelGGL(argmax_chunks<true>, dim3(chunks, rows), dim3(256), 0, st, logits, V, part);
+    else hipLaunchKernelGGL(argmax_chunks<false>, dim3(chunks, rows), dim3(256), 0, st, logits, V, part);
+    BTV_HIP(hipGetLastError());
+    hipLaunchKernelGGL(greedy_walk, dim3(batch), dim3(256), 0, st, part, chunks, parent, token, M_max, path, n_acc, bonus,
+                       argmax_out, q_offset, static_cast<uint32_t *>(ws));
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

@@ -79,7 +79,7 @@ __device__ __forceinline__ void scan_chunk(const float *src, bool aligned, int V
     }
 }
 
-__global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, int chunks, uint32_t *part, TbCounters *ctr)
+__global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, int B, int chunks, uint32_t *part, TbCounters *ctr)
 {
     const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y;
     const float *src = marg + (size_t)row * V;
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, i
     uint32_t mx = 0;
     scan_chunk(src, aligned, V, chunk, tid, [&](float p, int) { mx = umax(mx, prob_bits(p)); });
     part[((size_t)row * chunks + chunk) * 256 + tid] = mx;
-    if (chunk == 0 && row == 0 && tid == 0) ctr->done = 0;     // the next kernel starts after this one has ended
+    if (chunk == 0 && row % B == 0 && tid == 0) ctr[row / B].done = 0;   // the next kernel starts after this one has ended
 }
 
 constexpr int TBINS = 4096;
@@ -130,6 +130,12 @@ struct ExpandLds {                          // the expansion
                                             // fetched, not used, also for the last rank of the last position)
     uint32_t tok[MAXB * BTV_MAX_NODES];     // its token id
     double cost[BTV_MAX_NODES];             // adaptive budget: estimated cycle latency at budget n + 1
+};
+
+struct Batch {                              // several requests in one launch (n_nodes == nullptr: one request)
+    const int32_t *n_nodes;                 // [batch] budget of each request (device)
+    const int32_t *q_offset;                // [batch + 1] first output row of each request (device)
+    uint32_t *flag;
 };
 
 struct Adaptive {                           // Algorithm 1's early stop (cost == nullptr: fixed budget)
@@ -508,13 +514,16 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
                                                       TbCounters *ctr, const uint32_t *part, float *top_q, uint32_t *top_tok,
                                                       int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
-                                                      Adaptive ad, int beam_width, unsigned long long *dbg)
+                                                      Adaptive ad, int beam_width, Batch bt, unsigned long long *dbg)
 {
     __shared__ RankLds RL;
     __shared__ ExpandLds S;
     __shared__ BeamLds BM;
     const unsigned long long t0_ = __builtin_amdgcn_s_memtime();
+    // Workgroup `row` = position row % B of request row / B; marginals, per-thread maxima and top lists are laid out
+    // request after request, outputs start at the request's q_offset.
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), row = blockIdx.x;
+    const int req = row / B;
     float *q_row = top_q + (size_t)row * KP;
     uint32_t *tok_row = top_tok + (size_t)row * KP;
     const float *src = marg + (size_t)row * V;
@@ -622,14 +631,29 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     const unsigned long long tr_ = __builtin_amdgcn_s_memtime();
     __threadfence();
     __syncthreads();
-    if (tid == 0) RL.last = atomicAdd(&ctr->done, 1) == B - 1;
+    if (tid == 0) RL.last = atomicAdd(&ctr[req].done, 1) == B - 1;
     __syncthreads();
     if (!RL.last) return;
     const unsigned long long ta_ = __builtin_amdgcn_s_memtime();
     __threadfence();
     for (int e = tid; e < B * KP; e += 256) {
-        S.q[e] = __builtin_nontemporal_load(top_q + e);
-        S.tok[e] = __builtin_nontemporal_load(top_tok + e);
+        S.q[e] = __builtin_nontemporal_load(top_q + (size_t)req * B * KP + e);
+        S.tok[e] = __builtin_nontemporal_load(top_tok + (size_t)req * B * KP + e);
+    }
+    if (bt.n_nodes) {                          // this request's budget and output rows
+        const int o0 = bt.q_offset[req], room = bt.q_offset[req + 1] - o0, want = bt.n_nodes[req];
+        const bool bad = o0 < 0 || want < 0 || want > N || want > room;
+        if (bad && tid == 0) atomicOr(bt.flag, 16u);
+        N = bad ? 0 : want;
+        parent += o0; token += o0;
+        if (depth) depth += o0;
+        if (rho) rho += o0;
+        n_out += req;
+        if (ahat) ahat += req;
+        if (N == 0) {
+            if (tid == 0) { *n_out = 0; if (ahat) *ahat = 1.0f; }
+            return;
+        }
     }
     if (ad.cost)
         for (int e = tid; e < N; e += 256) S.cost[e] = ad.cost[e];
@@ -655,20 +679,30 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
 
 int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 
-struct TopkPlan { int K, KP, chunks; size_t part_bytes, top_bytes; };
+struct TopkPlan { int K, KP, chunks; size_t ctr_bytes, part_bytes, top_bytes; };
 
-TopkPlan topk_plan(int B, int V, int N)
+TopkPlan topk_plan(int batch, int B, int V, int N)
 {
     TopkPlan t;
     t.K = std::min(V, N);
     t.KP = std::max(next_pow2(t.K), 1);
     t.chunks = (V + SCAN - 1) / SCAN;
-    t.part_bytes = btv_align_up((size_t)B * t.chunks * 256 * 4, BTV_WS_ALIGN);
-    t.top_bytes = btv_align_up((size_t)B * t.KP * 4, BTV_WS_ALIGN);
+    t.ctr_bytes = btv_align_up((size_t)batch * sizeof(TbCounters), BTV_WS_ALIGN);
+    t.part_bytes = btv_align_up((size_t)batch * B * t.chunks * 256 * 4, BTV_WS_ALIGN);
+    t.top_bytes = btv_align_up((size_t)batch * B * t.KP * 4, BTV_WS_ALIGN);
     return t;
 }
 
-unsigned long long *g_tb_dbg = nullptr;   // phase cycle counts of tb_finish_expand (experiment builds set it)
+constexpr int MAX_BATCH = 1024;
+
+size_t tree_build_ws(int batch, int B, int V, int N)
+{
+    if (batch < 1 || batch > MAX_BATCH || B < 1 || B > MAXB || V < 1 || N < 1 || N > BTV_MAX_NODES) return 0;
+    TopkPlan t = topk_plan(batch, B, V, N);
+    return BTV_WS_HEADER + t.ctr_bytes + t.part_bytes + 2 * t.top_bytes;
+}
+
+unsigned long long *g_tb_dbg = nullptr;   // phase cycle counts of tb_rank_expand (experiment builds set it)
 
 }  // namespace
 
@@ -678,46 +712,46 @@ extern "C" {
 void btv_exp_tb_dbg(unsigned long long *p) { g_tb_dbg = p; }
 #endif
 
-size_t btv_tree_build_workspace(int B, int V, int N)
-{
-    if (B < 1 || B > MAXB || V < 1 || N < 1 || N > BTV_MAX_NODES) return 0;
-    TopkPlan t = topk_plan(B, V, N);
-    return BTV_WS_HEADER + t.part_bytes + 2 * t.top_bytes;
-}
+size_t btv_tree_build_workspace(int B, int V, int N) { return tree_build_ws(1, B, V, N); }
 
-static int tree_build_launch(const float *marginals, int B, int V, int N, const Adaptive &ad_in, int beam_width, int32_t *parent,
-                             int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes,
-                             void *stream)
+size_t btv_tree_build_batch_workspace(int batch, int B, int V, int N_max) { return tree_build_ws(batch, B, V, N_max); }
+
+static int tree_build_launch(const float *marginals, int batch, int B, int V, int N, const Adaptive &ad_in, int beam_width,
+                             Batch bt, int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                             void *ws, size_t ws_bytes, void *stream)
 {
     BTV_REQUIRE(marginals && parent && token && n_out, "null pointer");
+    BTV_REQUIRE(batch >= 1 && batch <= MAX_BATCH, "batch=%d outside [1,%d]", batch, MAX_BATCH);
     BTV_REQUIRE(B >= 1 && B <= MAXB, "B=%d outside [1,%d]", B, MAXB);
     BTV_REQUIRE(V >= 1, "V=%d", V);
     BTV_REQUIRE(N >= 1 && N <= BTV_MAX_NODES, "N=%d outside [1,%d]", N, BTV_MAX_NODES);
-    int rc = btv_check_ws(ws, ws_bytes, btv_tree_build_workspace(B, V, N));
+    int rc = btv_check_ws(ws, ws_bytes, tree_build_ws(batch, B, V, N));
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    TopkPlan t = topk_plan(B, V, N);
+    TopkPlan t = topk_plan(batch, B, V, N);
     unsigned char *base = static_cast<unsigned char *>(ws);
-    static_assert(sizeof(TbCounters) + 64 <= BTV_WS_HEADER, "counters live in the workspace header");
-    TbCounters *ctr = reinterpret_cast<TbCounters *>(base + 64);
-    uint32_t *part = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER);
-    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.part_bytes);
-    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.part_bytes + t.top_bytes);
+    TbCounters *ctr = reinterpret_cast<TbCounters *>(base + BTV_WS_HEADER);
+    uint32_t *part = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.ctr_bytes);
+    float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.ctr_bytes + t.part_bytes);
+    uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.ctr_bytes + t.part_bytes + t.top_bytes);
     Adaptive ad = ad_in;
     ad.flag = reinterpret_cast<uint32_t *>(base);
-    hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B), dim3(256), 0, st, marginals, V, t.chunks, part, ctr);
+    bt.flag = reinterpret_cast<uint32_t *>(base);
+    hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B * batch), dim3(256), 0, st, marginals, V, B, t.chunks, part, ctr);
     BTV_HIP(hipGetLastError());
-    hipLaunchKernelGGL(tb_rank_expand, dim3(B), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, t.chunks, ctr, part, top_q, top_tok, parent,
-                       token, depth, rho, n_out, ahat, ad, beam_width, g_tb_dbg);
+    hipLaunchKernelGGL(tb_rank_expand, dim3(B * batch), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, t.chunks, ctr, part, top_q,
+                       top_tok, parent, token, depth, rho, n_out, ahat, ad, beam_width, bt, g_tb_dbg);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
+
+static const Batch kOneRequest = { nullptr, nullptr, nullptr };
 
 int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent, int32_t *token, int32_t *depth,
                    float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
 {
     const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
-    return tree_build_launch(marginals, B, V, N, none, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+    return tree_build_launch(marginals, 1, B, V, N, none, 0, kOneRequest, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
 }
 
 int btv_tree_build_beam(const float *marginals, int B, int V, int width, int depth_max, int32_t *parent, int32_t *token,
@@ -728,8 +762,8 @@ int btv_tree_build_beam(const float *marginals, int B, int V, int width, int dep
     BTV_REQUIRE(depth_max >= 1 && depth_max <= B, "depth=%d outside [1,B=%d]", depth_max, B);
     // the first depth_max positions are ranked for their `width` best tokens; the rest of the path is shared
     const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
-    return tree_build_launch(marginals, depth_max, V, width, none, width, parent, token, depth, rho, n_out, ahat, ws, ws_bytes,
-                             stream);
+    return tree_build_launch(marginals, 1, depth_max, V, width, none, width, kOneRequest, parent, token, depth, rho, n_out, ahat,
+                             ws, ws_bytes, stream);
 }
 
 int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, const double *cost, double L_AR,
@@ -739,7 +773,18 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
     BTV_REQUIRE(cost != nullptr, "null pointer");
     BTV_REQUIRE(L_AR > 0.0, "L_AR must be positive");
     const Adaptive ad = { cost, L_AR, s_best, nullptr };
-    return tree_build_launch(marginals, B, V, N_max, ad, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+    return tree_build_launch(marginals, 1, B, V, N_max, ad, 0, kOneRequest, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+}
+
+int btv_tree_build_batch(const float *marginals, int batch, int B, int V, const int32_t *n_nodes, const int32_t *q_offset,
+                         int N_max, int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                         void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(n_nodes && q_offset, "null pointer");
+    const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
+    const Batch bt = { n_nodes, q_offset, nullptr };
+    return tree_build_launch(marginals, batch, B, V, N_max, none, 0, bt, parent, token, depth, rho, n_out, ahat, ws, ws_bytes,
+                             stream);
 }
 
 }  // extern "C"

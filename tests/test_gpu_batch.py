@@ -1,0 +1,96 @@
+"""Batches of requests in one launch: tree_build_batch and tree_accept_greedy_batch must give, request by request,
+exactly what the oracle gives for that request alone (bit-exact trees, tokens, paths)."""
+import numpy as np
+import pytest
+
+from paper_2605_29727_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_build(marg, n_nodes, q_offset, N_max):
+    import torch
+    from paper_2605_29727_amd import binding as btv
+    batch, B, V = marg.shape
+    total = int(q_offset[-1])
+    m = torch.from_numpy(np.ascontiguousarray(marg, dtype=np.float32)).cuda()
+    nn = torch.from_numpy(np.asarray(n_nodes, dtype=np.int32)).cuda()
+    qo = torch.from_numpy(np.asarray(q_offset, dtype=np.int32)).cuda()
+    parent = torch.full((max(total, 1),), -7, dtype=torch.int32, device="cuda")
+    token, depth = torch.full_like(parent, -7), torch.full_like(parent, -7)
+    rho = torch.full((max(total, 1),), -7.0, dtype=torch.float32, device="cuda")
+    n_out = torch.full((batch,), -7, dtype=torch.int32, device="cuda")
+    ahat = torch.zeros(batch, dtype=torch.float32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_build_batch_workspace(batch, B, V, N_max))
+    btv.btv_tree_build_batch(m, nn, qo, N_max, parent, token, depth, rho, n_out, ahat, ws)
+    torch.cuda.synchronize()
+    return {"parent": parent.cpu().numpy(), "token": token.cpu().numpy(), "depth": depth.cpu().numpy(),
+            "rho": rho.cpu().numpy(), "n_out": n_out.cpu().numpy(), "ahat": ahat.cpu().numpy(),
+            "status": int(btv.btv_workspace_status(ws))}
+
+
+@pytest.mark.parametrize("batch,B,V,N_max,slack", [(8, 16, 128256, 128, 0), (3, 4, 64, 16, 5), (16, 8, 5000, 64, 0),
+                                                   (1, 16, 128256, 256, 0), (5, 6, 3, 40, 2)])
+def test_tree_build_batch_matches_oracle(oracle, batch, B, V, N_max, slack):
+    marg = np.stack([synth.marginals(900 + r, B, V, [1.0, 3.0, 5.0][r % 3]) for r in range(batch)])
+    n_nodes = [int(x) for x in synth.integers(7, "nn", (batch,), 1, N_max)]
+    n_nodes[0] = N_max
+    q_offset = np.concatenate([[0], np.cumsum([n + slack for n in n_nodes])]).astype(np.int32)
+    got = _run_build(marg, n_nodes, q_offset, N_max)
+    assert got["status"] == 0
+    for r in range(batch):
+        ref = oracle.tree_build(marg[r], n_nodes[r])
+        o, n = int(q_offset[r]), ref["n"]
+        assert got["n_out"][r] == n
+        for k in ("parent", "token", "depth"):
+            assert np.array_equal(got[k][o:o + n], ref[k]), (r, k)
+        assert np.array_equal(got["rho"][o:o + n].view(np.uint32), ref["rho"].view(np.uint32))
+        assert got["ahat"][r] == pytest.approx(ref["ahat"], rel=1e-6)
+        assert np.all(got["parent"][o + n:int(q_offset[r + 1])] == -7)        # nothing written past the request's nodes
+
+
+def test_tree_build_batch_flags_bad_requests(oracle):
+    marg = np.stack([synth.marginals(950 + r, 4, 100, 2.0) for r in range(3)])
+    q_offset = np.array([0, 10, 20, 30], dtype=np.int32)
+    got = _run_build(marg, [10, 11, 0], q_offset, 16)            # request 1 asks for more rows than it owns
+    assert got["status"] != 0
+    assert got["n_out"].tolist() == [10, 0, 0]
+    ref = oracle.tree_build(marg[0], 10)
+    assert np.array_equal(got["parent"][:10], ref["parent"])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_accept_batch_matches_oracle(oracle, dtype):
+    import torch
+    import gpu_util as G
+    from paper_2605_29727_amd import binding as btv
+    V = 30000
+    Ms = [40, 7, 128, 1, 64, 33]
+    q_offset = np.concatenate([[0], np.cumsum(Ms)]).astype(np.int32)
+    batch, total = len(Ms), int(q_offset[-1])
+    parents, tokens, stores, refs = [], [], [], []
+    for r, M in enumerate(Ms):
+        par = synth.tree_parents(60 + r, M, ["random", "deep", "binary"][r % 3])
+        tok = synth.sibling_distinct_tokens(60 + r, par, V)
+        _, lf = synth.target_logits(60 + r, M + 1, V, 1.0, dtype)
+        leaf = int(synth.integers(60 + r, "leaf", (1,), 0, M)[0]) if r % 2 == 0 else -1
+        st, lf = synth.round_to_dtype(synth.plant_path(lf, par, tok, leaf).astype(np.float64), dtype)
+        parents.append(par); tokens.append(tok); stores.append(st)
+        refs.append(oracle.accept_greedy(lf, par, tok))
+    logits = G.dev(np.concatenate(stores), dtype == "bf16")
+    par = G.dev(np.concatenate(parents).astype(np.int32)); tok = G.dev(np.concatenate(tokens).astype(np.int32))
+    qo = G.dev(q_offset)
+    path = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((batch,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((batch,), -7, dtype=torch.int32, device="cuda")
+    am = torch.full((total + batch,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_batch_workspace(batch, total, V))
+    btv.btv_tree_accept_greedy_batch(logits, par, tok, qo, max(Ms), path, n_acc, bonus, am, ws)
+    torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == 0
+    path, n_acc, bonus, am = path.cpu().numpy(), n_acc.cpu().numpy(), bonus.cpu().numpy(), am.cpu().numpy()
+    for r, M in enumerate(Ms):
+        o, ref = int(q_offset[r]), refs[r]
+        assert n_acc[r] == ref["n_acc"] and bonus[r] == ref["bonus"]
+        assert path[o:o + ref["n_acc"]].tolist() == ref["path"].tolist()
+        assert np.array_equal(am[o + r:o + r + M + 1], ref["argmax"])
