@@ -452,7 +452,7 @@ def main():
     gbps = ab / (attn_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(L, N),
-                "kernel": "tree_verify_attn (tv_attn_bf16 + tv_combine_bf16 + anc_mask_kernel)",
+                "kernel": "tree_verify_attn (tv_attn_bf16, which also forms the ancestor mask, + tv_combine_bf16)",
                 "algorithmic_bytes": ab, "us_per_launch": round(attn_ms * 1e3, 3),
                 "us_in_step": round(attn_ms_in_step * 1e3, 3), "us_warm_cache": round(attn_warm_ms * 1e3, 3),
                 "tflops": round(fl / (attn_ms * 1e-3) / 1e12, 1),
