@@ -94,3 +94,25 @@ def test_accept_batch_matches_oracle(oracle, dtype):
         assert n_acc[r] == ref["n_acc"] and bonus[r] == ref["bonus"]
         assert path[o:o + ref["n_acc"]].tolist() == ref["path"].tolist()
         assert np.array_equal(am[o + r:o + r + M + 1], ref["argmax"])
+
+
+def test_stream_read_runs_and_checks_arguments():
+    """The bandwidth-ceiling aid: any 16-byte multiple is read without touching anything else; bad arguments raise."""
+    import torch
+    from paper_2605_29727_amd import binding as btv
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    for nbytes in (16, 4096 + 16, (1 << 20) + 48, 64 << 20):
+        buf = torch.ones(nbytes // 4, dtype=torch.int32, device="cuda")
+        guard = torch.full((1024,), 7, dtype=torch.int32, device="cuda")
+        btv.btv_stream_read(buf, sink)
+        torch.cuda.synchronize()
+        assert bool((guard == 7).all()) and bool((buf == 1).all())
+    # xor of an even number of equal words per workgroup share is deterministic: 64 MiB of ones folds to zero
+    sink.zero_()
+    btv.btv_stream_read(torch.ones((64 << 20) // 4, dtype=torch.int32, device="cuda"), sink)
+    torch.cuda.synchronize()
+    assert int(sink.abs().sum().item()) == 0
+    with pytest.raises(btv.BtvError):
+        btv.btv_stream_read(torch.ones(5, dtype=torch.int32, device="cuda")[1:], sink)       # 16 bytes, misaligned
+    with pytest.raises(btv.BtvError):
+        btv.btv_stream_read(torch.ones(4, dtype=torch.int32, device="cuda"), sink[:8])       # sink too small
