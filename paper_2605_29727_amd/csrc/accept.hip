@@ -497,15 +497,17 @@ __device__ __forceinline__ float load_logit(const void *logits, size_t idx)
     return static_cast<const float *>(logits)[idx];
 }
 
-// p and q are kept unnormalised in fp32 with their scales in fp64 (p = ps * sp, q = qs * sq), so normalising
-// costs nothing and a rejection is a single pass over the vocabulary: residual into the spare buffer and its sum;
-// the buffers swap if the sum is positive (an all-zero residual leaves p as it was).  Zeroing the tried token in q
-// only changes q's total, which is tracked instead of summed again.
+// Nothing is rewritten per rejection.  With e[v] = exp(logit[v] - max) and q0 = the draft marginal of the depth,
+// the target distribution after k rejections at a node is  p_k[v] = max(alpha * e[v] - beta * q0[v], 0)  and the
+// draft distribution  q_k[v] = q0[v] / T  for the tokens not yet tried (a rejected token has q_k > p_k, so its
+// residual is zero from then on and the same formula covers it).  A rejection is one read-only pass for
+// Z = sum_v max(p_k[v] - q_k[v], 0), then  alpha /= Z,  beta = (beta + 1/T) / Z,  T -= q0[x];  Z = 0 leaves p as it
+// was.  Scalars are fp64; e is stored once per node in fp32.
 template <bool BF16>
 __global__ __launch_bounds__(1024) void stochastic_walk(const void *logits, const float *marg, int B,
                                                         const int32_t *parent, const int32_t *token, int M, int V,
-                                                        const float *uniforms, float *pa, float *pb, float *qs,
-                                                        int32_t *path, int32_t *n_acc, int32_t *bonus)
+                                                        const float *uniforms, float *es, int32_t *path,
+                                                        int32_t *n_acc, int32_t *bonus)
 {
     __shared__ double shd[16];
     __shared__ float shf[16];
@@ -513,88 +515,73 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *logits, cons
     __shared__ int found, lastpos;
     const int tid = threadIdx.x;
     int cur = -1, n = 0, ui = 0, d = 0;
-    float *ps = pa, *spare = pb;
-    const bool vec4 = (V & 3) == 0;                              // the work buffers are 256-byte aligned
     for (;;) {
-        // p = softmax(logits[row(cur)]): ps = exp(logit - max), sp = 1 / sum
         const size_t base = (size_t)(cur + 1) * V;
+        const float *q0 = marg + (size_t)(d < B ? d : 0) * V;    // (unused when d == B: no children there)
+        const bool vec4 = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(q0) & 15) == 0;
         float mx = -INFINITY;
         for (int v = tid; v < V; v += 1024) mx = fmaxf(mx, load_logit<BF16>(logits, base + v));
         mx = block_max(mx, shf, tid);
-        double z = 0.0;
+        double z = 0.0, tq = 0.0;
         for (int v = tid; v < V; v += 1024) {
             const float e = expf(load_logit<BF16>(logits, base + v) - mx);
-            ps[v] = e; z += (double)e;
+            es[v] = e; z += (double)e;
+            if (d < B) tq += (double)q0[v];
         }
-        z = block_sum(z, shd, tid);
-        double sp = 1.0 / z;
+        z = block_sum(z, shd, tid);                              // (its barriers also publish es)
+        tq = block_sum(tq, shd, tid);
+        double alpha = 1.0 / z, beta = 0.0, T = tq;
+        auto pk = [&](int v) {                                    // p_k[v]
+            const double x = alpha * (double)es[v] - beta * (double)q0[v];
+            return x > 0.0 ? x : 0.0;
+        };
         int accepted = -1;
         if (d < B) {
-            double tq = 0.0;                                     // q = the marginal of this depth, total tq
-            const float *mrow = marg + (size_t)d * V;
-            if (vec4 && (reinterpret_cast<uintptr_t>(mrow) & 15) == 0) {
-                for (int v = tid * 4; v < V; v += 4096) {
-                    const float4 a = *reinterpret_cast<const float4 *>(mrow + v);
-                    *reinterpret_cast<float4 *>(qs + v) = a;
-                    tq += ((double)a.x + (double)a.y) + ((double)a.z + (double)a.w);
-                }
-            } else {
-                for (int v = tid; v < V; v += 1024) { const float x = mrow[v]; qs[v] = x; tq += (double)x; }
-            }
-            tq = block_sum(tq, shd, tid);                        // (its barriers also publish ps and qs)
-            double sq = tq > 0.0 ? 1.0 / tq : 1.0;
             for (int c = 0; c < M; ++c) {
                 if (parent[c] != cur) continue;                  // uniform across the workgroup
                 const int tk = token[c];
                 const double u = (double)uniforms[ui++];
-                const double qx = (double)qs[tk];
-                const double lhs = u * (qx * sq), rhs = (double)ps[tk] * sp;
-                if (lhs < rhs) { accepted = c; break; }
-                double zr = 0.0;                                 // residual max(p - q, 0), unnormalised, and its sum
-                auto resid = [&](float pv, float qv) {
-                    double r = (double)pv * sp - (double)qv * sq;
-                    const float rf = (float)(r > 0.0 ? r : 0.0);
-                    zr += (double)rf;
-                    return rf;
+                const double invT = T > 0.0 ? 1.0 / T : 0.0, qx = (double)q0[tk];
+                if (u * (qx * invT) < pk(tk)) { accepted = c; break; }
+                const double b1 = beta + invT;                   // residual max(p_k - q_k, 0) and its sum
+                double zr = 0.0;
+                auto resid = [&](float ev, float qv) {
+                    const double r = alpha * (double)ev - b1 * (double)qv;
+                    zr += r > 0.0 ? r : 0.0;
                 };
                 if (vec4) {
                     for (int v = tid * 4; v < V; v += 4096) {
-                        const float4 a = *reinterpret_cast<const float4 *>(ps + v), b = *reinterpret_cast<const float4 *>(qs + v);
-                        *reinterpret_cast<float4 *>(spare + v) = make_float4(resid(a.x, b.x), resid(a.y, b.y), resid(a.z, b.z),
-                                                                              resid(a.w, b.w));
+                        const float4 a = *reinterpret_cast<const float4 *>(es + v), q = *reinterpret_cast<const float4 *>(q0 + v);
+                        resid(a.x, q.x); resid(a.y, q.y); resid(a.z, q.z); resid(a.w, q.w);
                     }
                 } else {
-                    for (int v = tid; v < V; v += 1024) spare[v] = resid(ps[v], qs[v]);
+                    for (int v = tid; v < V; v += 1024) resid(es[v], q0[v]);
                 }
                 zr = block_sum(zr, shd, tid);
-                if (zr > 0.0) { float *t = ps; ps = spare; spare = t; sp = 1.0 / zr; }
-                __syncthreads();                                 // everyone has read qs[tk]
-                if (tid == 0) qs[tk] = 0.f;                      // drafted without replacement
-                tq -= qx;
-                if (tq > 0.0) sq = 1.0 / tq;
-                __syncthreads();
+                if (zr > 0.0) { alpha /= zr; beta = b1 / zr; }
+                T -= qx;                                         // drafted without replacement
             }
         }
         if (accepted >= 0) {
             if (tid == 0) path[n] = accepted;
             cur = accepted; ++n; ++d;
-            __syncthreads();
+            __syncthreads();                                     // everyone is done with es before it is rewritten
             continue;
         }
-        // bonus: smallest v with cumsum(p)[v] > u, i.e. cumsum(ps)[v] > u / sp; each thread owns a contiguous segment
-        const double u = (double)uniforms[ui++] / sp;
+        // bonus: smallest v with cumsum(p_k)[v] > u; each thread owns a contiguous segment
+        const double u = (double)uniforms[ui++];
         const int per = (V + 1023) / 1024, s0 = min(tid * per, V), s1 = min(s0 + per, V);
-        __syncthreads();
         double loc = 0.0;
         int lp = -1;
-        for (int v = s0; v < s1; ++v) { loc += (double)ps[v]; if (ps[v] > 0.f) lp = v; }
+        if (d < B) { for (int v = s0; v < s1; ++v) { const double x = pk(v); loc += x; if (x > 0.0) lp = v; } }
+        else { for (int v = s0; v < s1; ++v) { const double x = alpha * (double)es[v]; loc += x; if (x > 0.0) lp = v; } }
         seg[tid] = loc;
         if (tid == 0) { found = INT_MAX; lastpos = 0; }
         __syncthreads();
         double cum = 0.0;
         for (int s = 0; s < tid; ++s) cum += seg[s];
         for (int v = s0; v < s1; ++v) {
-            cum += (double)ps[v];
+            cum += d < B ? pk(v) : alpha * (double)es[v];
             if (cum > u) { atomicMin(&found, v); break; }
         }
         if (lp >= 0) atomicMax(&lastpos, lp);
@@ -621,7 +608,7 @@ extern "C" {
 size_t btv_tree_accept_workspace(int M, int V, int stochastic)
 {
     if (M < 1 || M > BTV_MAX_NODES || V < 1) return 0;
-    if (stochastic) return BTV_WS_HEADER + 3 * btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
+    if (stochastic) return BTV_WS_HEADER + btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
     int chunks = (V + ACHUNK - 1) / ACHUNK;
     return BTV_WS_HEADER + btv_align_up((size_t)(M + 1) * chunks * sizeof(Best), BTV_WS_ALIGN);
 }
@@ -723,16 +710,13 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_workspace(M, V, 1));
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    size_t vb = btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
-    float *pa = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
-    float *pb = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + vb);
-    float *q = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + 2 * vb);
+    float *es = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
     if (dtype == BTV_BF16)
         hipLaunchKernelGGL(stochastic_walk<true>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, pa, pb, q, path, n_acc, bonus);
+                           uniforms, es, path, n_acc, bonus);
     else
         hipLaunchKernelGGL(stochastic_walk<false>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, pa, pb, q, path, n_acc, bonus);
+                           uniforms, es, path, n_acc, bonus);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
