@@ -5,6 +5,8 @@
 // target itself would have produced.  Rows of `logits`: 0 = root, 1+i = node i.
 #include "btv_common.h"
 
+#include <atomic>
+
 #include <algorithm>
 #include <climits>
 
@@ -437,12 +439,12 @@ template <int RT, int WAVES, int KB, int TV, bool RAW>
 int lm_head_launch(const uint16_t *H, const uint16_t *W, int R, int h, int V, Best *part, hipStream_t st)
 {
     using S = LmShape<RT, WAVES, KB, TV>;
-    static bool configured = false;
+    static std::atomic<bool> configured{false};         // (one GPU per process: the attribute is set once)
     auto kern = lm_head_argmax<RT, WAVES, KB, TV, RAW>;
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     S::LDS_BYTES));
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int chunks = (V + WAVES * S::VROWS - 1) / (WAVES * S::VROWS);
     hipLaunchKernelGGL(kern, dim3(chunks), dim3(WAVES * 64), S::LDS_BYTES, st, H, W, R, h, V, part);

@@ -17,6 +17,8 @@
 // ancestor bitmask.
 #include "btv_common.h"
 
+#include <atomic>
+
 #include <algorithm>
 #include <cmath>
 
@@ -1059,15 +1061,16 @@ template <int D, int RW, int KW, int NT, bool PAGED>
 int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 {
     constexpr int RING = NT * Lds<D>::STAGE;
-    constexpr int MERGE = RW * (KW - 1) * ((D / 32) * 16 + 2) * 64 * 4;
+    // LDS the key-wave merge needs: two waves exchange half a row each (+ m, l, bound); more waves: donors to wave 0
+    constexpr int MERGE = KW == 2 ? RW * 2 * ((D / 64) * 16 + 3) * 64 * 4 : RW * (KW - 1) * ((D / 32) * 16 + 2) * 64 * 4;
     constexpr int LDS_BYTES = RING > MERGE ? RING : MERGE;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
-    static bool configured = false;
+    static std::atomic<bool> configured{false};         // (one GPU per process: the attribute is set once)
     auto kern = tv_attn_bf16<D, RW, KW, NT, PAGED>;
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     LDS_BYTES));
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, grid, dim3(RW * KW * 64), LDS_BYTES, st, p);
     BTV_HIP(hipGetLastError());
