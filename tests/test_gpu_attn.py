@@ -227,3 +227,31 @@ def test_paged_ragged_small(G, oracle):
 def test_config4_ragged_paged_full_size(G, oracle):
     Ls, Ns = synth.c4_request_shapes()
     _paged_case(G, oracle, Ls, Ns, 32, 8, 128, seed=synth.C4.seed, npairs_per_req=8)
+
+
+def test_paged_ragged_several_splits(G, oracle):
+    """Prefixes long enough for several key splits per request, of very different lengths: the split index is
+    rotated per (request, head), short requests skip the splits they do not have, every element is compared."""
+    _paged_case(G, oracle, [5000, 300, 2500, 4097, 64, 9000], [40, 64, 7, 100, 130, 16], 8, 2, 128, seed=63)
+    _paged_case(G, oracle, [2100, 2047, 2049], [33, 32, 31], 4, 4, 64, seed=64)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_bf16_random_shapes(G, oracle, seed):
+    """Seeded random shapes inside the documented limits (ragged M and L, every GQA ratio up to 16, both head sizes,
+    every tree kind), each compared element by element."""
+    r = lambda tag, lo, hi: int(synth.integers(1000 + seed, tag, (1,), lo, hi)[0])
+    D = (64, 128)[r("D", 0, 1)]
+    Hkv = (1, 2, 4, 8)[r("Hkv", 0, 3)]
+    Gq = (1, 2, 4, 8, 16)[r("G", 0, 4)]
+    M = r("M", 1, 256) if seed % 3 else r("M", 1, 40)
+    L = (0, r("L", 1, 31), r("L", 32, 700), r("L", 701, 3000))[r("Lk", 0, 3)]
+    kind = KINDS[r("kind", 0, len(KINDS) - 1)]
+    if M * Gq * Hkv * (L + M) > 6_000_000:      # keep the oracle's share of the test short
+        L = min(L, 600)
+    parent = synth.tree_parents(seed, M, kind)
+    t = synth.qkv(2000 + seed, M, L, Hkv * Gq, Hkv, D, "bf16", tag="fz")
+    ref = oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], parent, L)
+    out = G.run_verify_attn(t, parent, L, "bf16")
+    assert np.isfinite(out).all()
+    assert np.abs(out - ref).max() <= TOL_BF16, (M, L, Hkv * Gq, Hkv, D, kind, np.abs(out - ref).max())
