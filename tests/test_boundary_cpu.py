@@ -55,7 +55,7 @@ def test_version_and_workspace_queries(lib):
     assert lib.btv_tree_build_workspace(16, 128256, 64) > 0
     assert lib.btv_tree_build_workspace(17, 128256, 64) == 0
     assert lib.btv_tree_accept_workspace(64, 128256, 0) > 0
-    assert lib.btv_tree_accept_workspace(64, 128256, 1) >= 2 * 128256 * 4
+    assert lib.btv_tree_accept_workspace(64, 128256, 1) >= 128256 * 4      # the softmax numerators of one row
 
 
 def test_bad_arguments_are_rejected_on_the_host(lib):
