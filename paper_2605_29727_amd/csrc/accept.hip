@@ -502,18 +502,35 @@ __device__ __forceinline__ float load_logit(const void *logits, size_t idx)
 // Nothing is rewritten per rejection.  With e[v] = exp(logit[v] - max) and q0 = the draft marginal of the depth,
 // the target distribution after k rejections at a node is  p_k[v] = max(alpha * e[v] - beta * q0[v], 0)  and the
 // draft distribution  q_k[v] = q0[v] / T  for the tokens not yet tried (a rejected token has q_k > p_k, so its
-// residual is zero from then on and the same formula covers it).  A rejection is one read-only pass for
-// Z = sum_v max(p_k[v] - q_k[v], 0), then  alpha /= Z,  beta = (beta + 1/T) / Z,  T -= q0[x];  Z = 0 leaves p as it
-// was.  Scalars are fp64; e is stored once per node in fp32.
+// residual is zero from then on and the same formula covers it).  A rejection needs
+//     Z = sum_v max(p_k[v] - q_k[v], 0) = sum_v max(alpha * e[v] - b1 * q0[v], 0),   b1 = beta + 1/T,
+// then  alpha /= Z,  beta = b1 / Z,  T -= q0[x];  Z = 0 leaves p as it was.  Scalars are fp64; e is stored once
+// per node in fp32.
+// A rejection at a node with few children gets Z from a read-only pass over the vocabulary.  A node with a wide fan
+// of children still to try sorts its tokens once into SW_BINS bins of the ratio q0/e (counting sort on the float's
+// exponent and three mantissa bits, the (e, q0) pairs moved into bin order): token v contributes iff q0/e < alpha/b1,
+// so Z is a prefix sum over the sorted pairs below the threshold's bin plus an exact scan of that one bin.
+constexpr int SW_BINS = 2048;
+constexpr int SW_BUILD_MIN = 40;    // children still untried at a node for the sort to be worth its cost (about 30 passes)
+
+__device__ __forceinline__ int sw_bin(float ratio)
+{
+    const uint32_t b = (__float_as_uint(ratio) & 0x7FFFFFFFu) >> 20;      // NaN (0/0) and inf (e = 0) land on top: never active
+    return (int)(b < (uint32_t)SW_BINS ? b : (uint32_t)SW_BINS - 1u);
+}
+
 template <bool BF16>
-__global__ __launch_bounds__(1024) void stochastic_walk(const void *logits, const float *marg, int B,
-                                                        const int32_t *parent, const int32_t *token, int M, int V,
-                                                        const float *uniforms, float *es, int32_t *path,
-                                                        int32_t *n_acc, int32_t *bonus)
+__global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__ logits, const float *__restrict__ marg, int B,
+                                                        const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
+                                                        int M, int V, const float *__restrict__ uniforms,
+                                                        float *__restrict__ es, float2 *__restrict__ eq_sorted,
+                                                        int32_t *path, int32_t *n_acc, int32_t *bonus)
 {
     __shared__ double shd[16];
     __shared__ float shf[16];
     __shared__ double seg[1024];
+    __shared__ double chunkE[SW_BINS], chunkQ[SW_BINS];  // sums of e and q0 over the sorted pairs before chunk c
+    __shared__ int start[SW_BINS + 1], cursor[SW_BINS];
     __shared__ int found, lastpos;
     const int tid = threadIdx.x;
     int cur = -1, n = 0, ui = 0, d = 0;
@@ -521,14 +538,20 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *logits, cons
         const size_t base = (size_t)(cur + 1) * V;
         const float *q0 = marg + (size_t)(d < B ? d : 0) * V;    // (unused when d == B: no children there)
         const bool vec4 = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(q0) & 15) == 0;
+        const int CH = 64 * ((V + 64 * SW_BINS - 1) / (64 * SW_BINS));      // sorted pairs per prefix-sum chunk
+        // (the passes are unrolled so that several loads are in flight: one load per iteration leaves a pass bound
+        // by the round trip to the L2)
         float mx = -INFINITY;
+#pragma unroll 8
         for (int v = tid; v < V; v += 1024) mx = fmaxf(mx, load_logit<BF16>(logits, base + v));
         mx = block_max(mx, shf, tid);
         double z = 0.0, tq = 0.0;
+        const bool has_q = d < B;
+#pragma unroll 8
         for (int v = tid; v < V; v += 1024) {
             const float e = expf(load_logit<BF16>(logits, base + v) - mx);
             es[v] = e; z += (double)e;
-            if (d < B) tq += (double)q0[v];
+            tq += has_q ? (double)q0[v] : 0.0;
         }
         z = block_sum(z, shd, tid);                              // (its barriers also publish es)
         tq = block_sum(tq, shd, tid);
@@ -537,29 +560,107 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *logits, cons
             const double x = alpha * (double)es[v] - beta * (double)q0[v];
             return x > 0.0 ? x : 0.0;
         };
-        int accepted = -1;
+        int accepted = -1, untried = 0;
+        bool binned = false;
         if (d < B) {
+            for (int c = tid; c < M; c += 1024) untried += parent[c] == cur ? 1 : 0;
+            untried = (int)block_sum((double)untried, shd, tid);          // children of this node still to be tried
             for (int c = 0; c < M; ++c) {
                 if (parent[c] != cur) continue;                  // uniform across the workgroup
                 const int tk = token[c];
                 const double u = (double)uniforms[ui++];
                 const double invT = T > 0.0 ? 1.0 / T : 0.0, qx = (double)q0[tk];
                 if (u * (qx * invT) < pk(tk)) { accepted = c; break; }
-                const double b1 = beta + invT;                   // residual max(p_k - q_k, 0) and its sum
-                double zr = 0.0;
+                const double b1 = beta + invT;
+                --untried;
+                if (!binned && untried >= SW_BUILD_MIN) {         // enough tests may follow for the sort to pay
+                    // ---- counting sort of the (e, q0) pairs by the bin of q0/e, then prefix sums over the sorted pairs ----
+                    for (int b = tid; b < SW_BINS; b += 1024) start[b] = 0;
+                    __syncthreads();
+                    for (int v = tid; v < V; v += 1024) atomicAdd(&start[sw_bin(__fdiv_rn(q0[v], es[v]))], 1);
+                    __syncthreads();
+                    {   // exclusive scan of the bin counts (two bins per thread)
+                        const int c0 = start[2 * tid], c1 = start[2 * tid + 1];
+                        int ci = c0 + c1;
+                        for (int off = 1; off < 64; off <<= 1) {
+                            const int co = __shfl_up(ci, off);
+                            if ((tid & 63) >= off) ci += co;
+                        }
+                        __syncthreads();
+                        if ((tid & 63) == 63) cursor[tid >> 6] = ci;
+                        __syncthreads();
+                        int cb = 0;
+                        for (int w = 0; w < (tid >> 6); ++w) cb += cursor[w];
+                        __syncthreads();
+                        const int cx = cb + ci - (c0 + c1);          // exclusive prefix of this thread's first bin
+                        start[2 * tid] = cx; start[2 * tid + 1] = cx + c0;
+                        cursor[2 * tid] = cx; cursor[2 * tid + 1] = cx + c0;
+                        if (tid == 1023) start[SW_BINS] = cx + c0 + c1;
+                    }
+                    __syncthreads();
+                    for (int v = tid; v < V; v += 1024) {
+                        const float e = es[v], q = q0[v];
+                        const int pos = atomicAdd(&cursor[sw_bin(__fdiv_rn(q, e))], 1);
+                        eq_sorted[pos] = make_float2(e, q);          // one 8-byte store: the scattered stores are what the sort costs
+                    }
+                    __syncthreads();
+                    {   // chunk c = sorted positions c*CH .. c*CH + CH - 1 (CH a multiple of 64, at most SW_BINS chunks): a
+                        // wave sums a chunk with coalesced loads; then an exclusive scan over the chunk sums
+                        const int lane = tid & 63, wv = tid >> 6;
+                        for (int c = wv; c < SW_BINS; c += 16) {
+                            double se = 0.0, sq = 0.0;
+                            for (int i = c * CH + lane; i < min(c * CH + CH, V); i += 64) {
+                                const float2 x = eq_sorted[i];
+                                se += (double)x.x; sq += (double)x.y;
+                            }
+                            for (int off = 32; off >= 1; off >>= 1) { se += __shfl_xor(se, off); sq += __shfl_xor(sq, off); }
+                            if (lane == 0) { chunkE[c] = se; chunkQ[c] = sq; }
+                        }
+                        __syncthreads();
+                        const double e0 = chunkE[2 * tid], e1 = chunkE[2 * tid + 1], q0s = chunkQ[2 * tid], q1s = chunkQ[2 * tid + 1];
+                        double ei = e0 + e1, qi = q0s + q1s;
+                        for (int off = 1; off < 64; off <<= 1) {
+                            const double eo = __shfl_up(ei, off), qo = __shfl_up(qi, off);
+                            if (lane >= off) { ei += eo; qi += qo; }
+                        }
+                        if (lane == 63) { seg[wv] = ei; seg[16 + wv] = qi; }
+                        __syncthreads();
+                        double eb = 0.0, qb = 0.0;
+                        for (int w = 0; w < wv; ++w) { eb += seg[w]; qb += seg[16 + w]; }
+                        const double ex = eb + ei - (e0 + e1), qxs = qb + qi - (q0s + q1s);
+                        chunkE[2 * tid] = ex; chunkE[2 * tid + 1] = ex + e0;
+                        chunkQ[2 * tid] = qxs; chunkQ[2 * tid + 1] = qxs + q0s;
+                    }
+                    __syncthreads();
+                    binned = true;
+                }
+                double zr = 0.0;                                 // residual max(p_k - q_k, 0): its sum
                 auto resid = [&](float ev, float qv) {
                     const double r = alpha * (double)ev - b1 * (double)qv;
                     zr += r > 0.0 ? r : 0.0;
                 };
-                if (vec4) {
-                    for (int v = tid * 4; v < V; v += 4096) {
-                        const float4 a = *reinterpret_cast<const float4 *>(es + v), q = *reinterpret_cast<const float4 *>(q0 + v);
-                        resid(a.x, q.x); resid(a.y, q.y); resid(a.z, q.z); resid(a.w, q.w);
-                    }
+                if (binned) {
+                    // pairs before the threshold's bin all contribute: whole chunks through the prefix sums, the rest
+                    // of the chunk that holds the bin's start one by one; the threshold's own bin is scanned exactly
+                    const int b = sw_bin((float)(alpha / b1));   // b1 = 0: the threshold is +inf, every finite ratio is below it
+                    const int p0 = start[b], p1 = start[b + 1];
+                    const int ch = min(p0 / CH, SW_BINS - 1), lo = ch * CH;
+                    for (int i = lo + tid; i < p1; i += 1024) { const float2 x = eq_sorted[i]; resid(x.x, x.y); }
+                    zr = block_sum(zr, shd, tid);
+                    const double below = alpha * chunkE[ch] - b1 * chunkQ[ch];
+                    zr += below > 0.0 ? below : 0.0;
                 } else {
-                    for (int v = tid; v < V; v += 1024) resid(es[v], q0[v]);
+                    if (vec4) {
+#pragma unroll 4
+                        for (int v = tid * 4; v < V; v += 4096) {
+                            const float4 a = *reinterpret_cast<const float4 *>(es + v), q = *reinterpret_cast<const float4 *>(q0 + v);
+                            resid(a.x, q.x); resid(a.y, q.y); resid(a.z, q.z); resid(a.w, q.w);
+                        }
+                    } else {
+                        for (int v = tid; v < V; v += 1024) resid(es[v], q0[v]);
+                    }
+                    zr = block_sum(zr, shd, tid);
                 }
-                zr = block_sum(zr, shd, tid);
                 if (zr > 0.0) { alpha /= zr; beta = b1 / zr; }
                 T -= qx;                                         // drafted without replacement
             }
@@ -570,23 +671,44 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *logits, cons
             __syncthreads();                                     // everyone is done with es before it is rewritten
             continue;
         }
-        // bonus: smallest v with cumsum(p_k)[v] > u; each thread owns a contiguous segment
+        // bonus: smallest v with cumsum(p_k)[v] > u.  Wavefront w owns a contiguous stretch of the vocabulary and reads
+        // it 64 tokens at a time (coalesced); the stretches' totals tell which wavefront holds the crossing, and only
+        // that one scans its stretch again with a running prefix.
         const double u = (double)uniforms[ui++];
-        const int per = (V + 1023) / 1024, s0 = min(tid * per, V), s1 = min(s0 + per, V);
+        const int lane = tid & 63, wv = tid >> 6;
+        const int stretch = ((V + 15) / 16 + 63) / 64 * 64, w0 = min(wv * stretch, V), w1 = min(w0 + stretch, V);
+        auto pv = [&](int v) {
+            const double x = has_q ? alpha * (double)es[v] - beta * (double)q0[v] : alpha * (double)es[v];
+            return x > 0.0 ? x : 0.0;
+        };
         double loc = 0.0;
         int lp = -1;
-        if (d < B) { for (int v = s0; v < s1; ++v) { const double x = pk(v); loc += x; if (x > 0.0) lp = v; } }
-        else { for (int v = s0; v < s1; ++v) { const double x = alpha * (double)es[v]; loc += x; if (x > 0.0) lp = v; } }
-        seg[tid] = loc;
+#pragma unroll 4
+        for (int v = w0 + lane; v < w1; v += 64) { const double x = pv(v); loc += x; lp = x > 0.0 ? v : lp; }
+        for (int off = 32; off >= 1; off >>= 1) { loc += __shfl_xor(loc, off); lp = max(lp, __shfl_xor(lp, off)); }
+        __syncthreads();                                         // (seg may still be in use by the sort's scans)
+        if (lane == 0) seg[wv] = loc;
         if (tid == 0) { found = INT_MAX; lastpos = 0; }
         __syncthreads();
-        double cum = 0.0;
-        for (int s = 0; s < tid; ++s) cum += seg[s];
-        for (int v = s0; v < s1; ++v) {
-            cum += d < B ? pk(v) : alpha * (double)es[v];
-            if (cum > u) { atomicMin(&found, v); break; }
+        if (lane == 0 && lp >= 0) atomicMax(&lastpos, lp);
+        double before = 0.0;
+        for (int w = 0; w < wv; ++w) before += seg[w];
+        if (u >= before && u < before + seg[wv]) {               // exactly one wavefront, or none if u is past the total
+            double running = before;
+            int hit = INT_MAX;
+            for (int v0 = w0; v0 < w1 && hit == INT_MAX; v0 += 64) {
+                const int v = v0 + lane;
+                double x = v < w1 ? pv(v) : 0.0;
+                for (int off = 1; off < 64; off <<= 1) {         // inclusive prefix over the 64 tokens
+                    const double o = __shfl_up(x, off);
+                    if (lane >= off) x += o;
+                }
+                const unsigned long long over = __builtin_amdgcn_ballot_w64(v < w1 && running + x > u);
+                if (over) hit = v0 + __builtin_ctzll(over);
+                running += __shfl(x, 63);
+            }
+            if (lane == 0) found = hit != INT_MAX ? hit : max(lp, 0);     // rounding left the crossing just past the stretch
         }
-        if (lp >= 0) atomicMax(&lastpos, lp);
         __syncthreads();
         if (tid == 0) { *bonus = found == INT_MAX ? lastpos : found; *n_acc = n; }
         break;
@@ -610,7 +732,7 @@ extern "C" {
 size_t btv_tree_accept_workspace(int M, int V, int stochastic)
 {
     if (M < 1 || M > BTV_MAX_NODES || V < 1) return 0;
-    if (stochastic) return BTV_WS_HEADER + btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
+    if (stochastic) return BTV_WS_HEADER + 3 * btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
     int chunks = (V + ACHUNK - 1) / ACHUNK;
     return BTV_WS_HEADER + btv_align_up((size_t)(M + 1) * chunks * sizeof(Best), BTV_WS_ALIGN);
 }
@@ -712,13 +834,15 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_workspace(M, V, 1));
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t vb = btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
     float *es = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
+    float2 *eq_sorted = reinterpret_cast<float2 *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + vb);
     if (dtype == BTV_BF16)
         hipLaunchKernelGGL(stochastic_walk<true>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, path, n_acc, bonus);
+                           uniforms, es, eq_sorted, path, n_acc, bonus);
     else
         hipLaunchKernelGGL(stochastic_walk<false>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, path, n_acc, bonus);
+                           uniforms, es, eq_sorted, path, n_acc, bonus);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
