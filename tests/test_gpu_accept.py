@@ -141,3 +141,30 @@ def test_config5_stochastic_full_vocab(G, oracle):
         assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]) and got["bonus"] == ref["bonus"]
         done += 1
     assert done >= 3
+
+
+@pytest.mark.parametrize("V,fan", [(300, 120), (5000, 200), (40000, 64), (2048 * 64 + 200, 48)])
+def test_stochastic_wide_fans(G, oracle, V, fan):
+    """Nodes with many children take the sorted-ratio path of the walk (prefix sums over the (e, q0) pairs in bins of
+    q0/e): flat marginals give a wide fan under the root, a target close to the draft makes acceptances late in the
+    fan likely, and vocabularies below and above the chunk limits are covered."""
+    B = 3
+    checked = 0
+    for seed in range(8):
+        marg = synth.marginals(700 + seed, B, V, 0.7)
+        tree = oracle.tree_build(marg, fan)
+        assert int((tree["parent"] == -1).sum()) >= min(fan, 40)
+        z = np.log(np.maximum(marg[np.minimum(np.concatenate([[0], tree["depth"]]), B - 1)].astype(np.float64), 1e-30))
+        z += synth.normal(800 + seed, "noise", z.shape, [0.3, 1.0, 2.0][seed % 3])
+        store, xf = synth.round_to_dtype(z, "fp32")
+        u = synth.uniform(900 + seed, "u", (fan + 1,)).astype(np.float32)
+        if seed % 4 == 3:
+            u[:] = 0.999999           # everything that can be rejected is: the whole fan is walked
+        ref = oracle.accept_stochastic(xf, marg, tree["parent"], tree["token"], tree["depth"], u)
+        if _ambiguous(ref):
+            continue
+        got = G.run_accept_stochastic(store, False, marg, tree["parent"], tree["token"], u)
+        assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]), (V, fan, seed)
+        assert got["bonus"] == ref["bonus"], (V, fan, seed)
+        checked += 1
+    assert checked >= 4
