@@ -33,6 +33,8 @@ def _load():
         _lib = C.CDLL(_LIB)
         _lib.orc_tree_build.restype = C.c_int
         _lib.orc_tree_attn.restype = C.c_int
+        _lib.orc_tree_attn_fp8kv.restype = C.c_int
+        _lib.orc_fp8_e4m3_decode.restype = None
         _lib.orc_accept_greedy.restype = C.c_int
         _lib.orc_accept_stochastic.restype = C.c_int
         _lib.orc_num_threads.restype = C.c_int
@@ -193,6 +195,54 @@ def tree_attn(Qf, Kf, Vf, parent, L: int, scale: float | None = None, pairs=None
                                nthreads)
     if rc != 0:
         raise ValueError(f"orc_tree_attn: bad arguments ({rc})")
+    return out
+
+
+def fp8_e4m3_decode(codes) -> np.ndarray:
+    """The numbers the 8-bit codes stand for (OCP E4M3: bias 7, subnormals, no infinities, one NaN per sign), fp32."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, dtype=np.float32)
+    _load().orc_fp8_e4m3_decode(_p(codes, C.c_uint8), C.c_size_t(codes.size), _p(out, C.c_float))
+    return out
+
+
+def tree_attn_fp8kv(Qf, K8, V8, k_scale: float, v_scale: float, parent, L: int, scale: float | None = None, pairs=None,
+                    block_table=None, page: int = 16, nthreads: int = 0) -> np.ndarray:
+    """Tree-masked attention (App. C) over an FP8 KV cache: K8/V8 hold E4M3 codes (uint8, shaped like tree_attn's
+    K/V) that stand for code * k_scale and code * v_scale.  Returns fp64 like tree_attn."""
+    Qf = np.ascontiguousarray(Qf, dtype=np.float32)
+    K8 = np.ascontiguousarray(K8, dtype=np.uint8)
+    V8 = np.ascontiguousarray(V8, dtype=np.uint8)
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    M, Hq, D = Qf.shape
+    if K8.ndim == 4:
+        K8 = K8.reshape(-1, K8.shape[2], K8.shape[3])
+        V8 = V8.reshape(-1, V8.shape[2], V8.shape[3])
+    assert K8.shape == V8.shape and K8.shape[2] == D
+    Hkv = K8.shape[1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    if block_table is None:
+        assert K8.shape[0] >= L + M
+        bt = None
+    else:
+        block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+        assert len(block_table) * page >= L + M
+        bt = _p(block_table, C.c_int32)
+    if pairs is None:
+        out = np.empty((M, Hq, D), dtype=np.float64)
+        pp, npairs = None, 0
+    else:
+        pairs = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        out = np.empty((len(pairs), D), dtype=np.float64)
+        pp, npairs = _p(pairs, C.c_int32), len(pairs)
+    if nthreads <= 0:
+        nthreads = num_threads()
+    rc = _load().orc_tree_attn_fp8kv(_p(Qf, C.c_float), _p(K8, C.c_uint8), _p(V8, C.c_uint8), C.c_size_t(K8.size),
+                                     C.c_double(k_scale), C.c_double(v_scale), _p(parent, C.c_int32), M, L, Hq, Hkv, D,
+                                     C.c_double(scale), bt, page, pp, npairs, _p(out, C.c_double), nthreads)
+    if rc != 0:
+        raise ValueError(f"orc_tree_attn_fp8kv: bad arguments ({rc})")
     return out
 
 

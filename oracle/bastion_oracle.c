@@ -23,6 +23,8 @@
  *   orc_cost_curve       assembled by hand from orc_verify_cost's pinned totals
  *   orc_kv_commit        array gather by a library routine (numpy indexing), identity and chain cases
  *   orc_tree_attn        library causal attention over each root-to-node path, chain/star cases
+ *   orc_fp8_e4m3_decode  a library conversion (torch's float8_e4m3fn) over all 256 codes, the format's named values
+ *   orc_tree_attn_fp8kv  library attention over values decoded and scaled by that library, scale-folding identities
  *   orc_ancestor_mask    reachability by explicit path enumeration
  *   orc_accept_greedy    brute force over all root-to-node paths, planted paths
  *   orc_lm_head_argmax   library matrix product + argmax (numpy, fp64), planted winners, exact ties, one-hot rows
@@ -369,6 +371,50 @@ int orc_tree_attn(const float *Q, const float *K, const float *V, const int32_t 
         free(vis); free(s);
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * FP8 KV cache (a storage variant of the same attention; the paper fixes no KV precision, App. E
+ * only carries a bytes-per-element factor).  Cache elements are 8-bit floats in the OCP "E4M3"
+ * encoding: 1 sign bit, 4 exponent bits with bias 7, 3 fraction bits; exponent field 0 holds the
+ * subnormals f/8 * 2^-6; there are no infinities; exponent 15 with fraction 7 is NaN, every other
+ * pattern is finite (largest 448).  A stored element x stands for the number  x * k_scale  (keys)
+ * or  x * v_scale  (values), one scale per tensor.
+ * ---------------------------------------------------------------------------------------- */
+void orc_fp8_e4m3_decode(const uint8_t *code, size_t n, float *out)
+{
+    for (size_t i = 0; i < n; ++i) {
+        int c = code[i], e = (c >> 3) & 15, f = c & 7;
+        double v;
+        if (e == 15 && f == 7) v = NAN;
+        else if (e == 0) v = ldexp((double)f / 8.0, -6);
+        else v = ldexp(1.0 + (double)f / 8.0, e - 7);
+        out[i] = (float)((c & 128) ? -v : v);      /* every finite value is exact in fp32 */
+    }
+}
+
+/* Attention by its definition over the numbers the cache stands for:
+ * scores scale * Q.(k_scale K8) and values v_scale V8.  The decoded elements go through
+ * orc_tree_attn unchanged, with the two per-tensor factors applied in fp64 where the definition
+ * has them (on the score and on the weighted sum), so nothing is rounded in between. */
+int orc_tree_attn_fp8kv(const float *Q, const uint8_t *K8, const uint8_t *V8, size_t kv_elems, double k_scale,
+                        double v_scale, const int32_t *parent, int M, int L, int Hq, int Hkv, int D, double scale,
+                        const int32_t *block_table, int page, const int32_t *pairs, int npairs, double *O,
+                        int nthreads)
+{
+    float *K = (float *)malloc(sizeof(float) * (kv_elems ? kv_elems : 1));
+    float *V = (float *)malloc(sizeof(float) * (kv_elems ? kv_elems : 1));
+    if (!K || !V) { free(K); free(V); return -9; }
+    orc_fp8_e4m3_decode(K8, kv_elems, K);
+    orc_fp8_e4m3_decode(V8, kv_elems, V);
+    int rc = orc_tree_attn(Q, K, V, parent, M, L, Hq, Hkv, D, scale * k_scale, block_table, page, pairs, npairs, O,
+                           nthreads);
+    if (rc == 0) {
+        size_t total = (size_t)(pairs ? npairs : M * Hq) * (size_t)D;
+        for (size_t i = 0; i < total; ++i) O[i] *= v_scale;
+    }
+    free(K); free(V);
+    return rc;
 }
 
 /* ------------------------------------------------------------------------------------------

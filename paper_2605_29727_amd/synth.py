@@ -1,4 +1,4 @@
-"""Seeded synthetic inputs for the tree-verify path (numpy only).
+"""Seeded synthetic inputs for the tree-verify path (numpy; torch only for the library FP8 rounding).
 
 This module produces DATA: random tensors, tree shapes, block tables and the
 named workload configurations.  It holds none of the method's arithmetic (no
@@ -142,6 +142,24 @@ def qkv(seed: int, M: int, L: int, Hq: int, Hkv: int, D: int, dtype: str, tag: s
     for name, shape in (("Q", (M, Hq, D)), ("K", (L + M, Hkv, D)), ("V", (L + M, Hkv, D))):
         st, f = round_to_dtype(normal(seed, tag + name, shape), dtype)
         out[name], out[name + "f"] = st, f
+    return out
+
+
+def kv_fp8(seed: int, rows: int, Hkv: int, D: int, tag: str = ""):
+    """K and V [rows,Hkv,D] ~ N(0,1) as an FP8 cache would hold them: one fp32 scale per tensor (largest magnitude
+    / 448, the largest E4M3 number) and x / scale stored as 8-bit E4M3 codes (uint8).  The rounding is a library
+    conversion (torch, round to nearest even).  Returns dict K8, V8 (uint8), k_scale, v_scale (python floats
+    holding fp32 values).  Same streams as `qkv`, so the codes are the quantised form of that function's K and V."""
+    import torch
+
+    out = {}
+    for name in ("K", "V"):
+        x = normal(seed, tag + name, (rows, Hkv, D)).astype(np.float32)
+        scale = np.float32(max(float(np.abs(x).max()), 1e-6) / 448.0)
+        y = np.clip(x / scale, -448.0, 448.0).astype(np.float32)
+        codes = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+        out[name + "8"] = codes
+        out[name.lower() + "_scale"] = float(scale)
     return out
 
 
