@@ -191,7 +191,7 @@ int btv_tree_ancestor_mask(const int32_t *parent, int M, uint32_t *anc, void *ws
  *   O[i,h,:] = sum_j softmax_j(scale * Q[i,h,:].K[j,g,:]) V[j,g,:],  g = h / (Hq/Hkv),
  *   j over 0..L-1 and L+a for a in anc(i).
  * Q, O [M,Hq,D]; K, V [L+M,Hkv,D] (tree node a at row L+a); all row-major, contiguous, of
- * `dtype`; softmax and accumulation in fp32.  scale <= 0 selects 1/sqrt(D).
+ * `dtype`, 16-byte aligned; softmax and accumulation in fp32.  scale <= 0 selects 1/sqrt(D).
  * Workspace: ancestor bitmasks and split-K partial results.
  * ------------------------------------------------------------------------------------------- */
 size_t btv_tree_verify_attn_workspace(int M, int L, int Hq, int Hkv, int D, int dtype);
@@ -217,6 +217,37 @@ int btv_tree_verify_attn_paged(const void *Q, const void *Kpool, const void *Vpo
                                const int32_t *prefix_len, const int32_t *parent, int batch,
                                int total_M, int M_max, int L_max, int Hq, int Hkv, int D,
                                float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * tree_verify_attn over an FP8 KV cache -- the same operation (App. C) with K and V stored as
+ * 8-bit floats; App. E prices the cache by a bytes-per-element factor and fixes no precision.
+ *   K8, V8      [L+M,Hkv,D] (or the paged pools [num_blocks, BTV_PAGE, Hkv, D]) of one byte per
+ *               element in the OCP E4M3 encoding (sign, 4 exponent bits of bias 7, 3 fraction
+ *               bits, subnormals, no infinities, 0x7F / 0xFF = NaN)
+ *   k_scale, v_scale   one positive finite factor per tensor: element x stands for x * k_scale
+ *               (keys), x * v_scale (values)
+ *   Q, O        bf16, as above.  D = 128 only.
+ *   O[i,h,:] = v_scale * sum_j softmax_j(scale * k_scale * Q[i,h,:].K8[j,g,:]) V8[j,g,:]
+ * The codes are converted exactly (every E4M3 number is a bf16 number) and the two factors are
+ * applied in fp32 to the scores and to the normalised sum, so the result differs from the bf16
+ * entry point on the same numbers only by rounding order.  A NaN code makes the rows that see it
+ * NaN.  All other arguments, the workspace contents and the error behaviour are those of
+ * btv_tree_verify_attn / btv_tree_verify_attn_paged; the workspace queries return 0 for shapes
+ * that are not built.
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_verify_attn_fp8kv_workspace(int M, int L, int Hq, int Hkv, int D);
+int btv_tree_verify_attn_fp8kv(const void *Q, const void *K8, const void *V8, float k_scale,
+                               float v_scale, const int32_t *parent, int M, int L, int Hq, int Hkv,
+                               int D, float scale, void *O, void *ws, size_t ws_bytes, void *stream);
+size_t btv_tree_verify_attn_paged_fp8kv_workspace(int batch, int M_max, int L_max, int Hq, int Hkv,
+                                                  int D);
+int btv_tree_verify_attn_paged_fp8kv(const void *Q, const void *K8pool, const void *V8pool,
+                                     float k_scale, float v_scale, int num_blocks,
+                                     const int32_t *block_table, int max_blocks,
+                                     const int32_t *q_offset, const int32_t *prefix_len,
+                                     const int32_t *parent, int batch, int total_M, int M_max,
+                                     int L_max, int Hq, int Hkv, int D, float scale, void *O,
+                                     void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * tree_accept -- the walk that commits the longest accepted root-to-node path (App. C,

@@ -25,7 +25,9 @@ EXPORTS = [
     "btv_tree_accept_batch_workspace", "btv_tree_accept_greedy_batch", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
     "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
     "btv_tree_ancestor_mask", "btv_tree_verify_attn_workspace", "btv_tree_verify_attn",
-    "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_accept_workspace",
+    "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_paged", "btv_tree_verify_attn_fp8kv_workspace",
+    "btv_tree_verify_attn_fp8kv", "btv_tree_verify_attn_paged_fp8kv_workspace", "btv_tree_verify_attn_paged_fp8kv",
+    "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_tree_accept_lm_head_workspace",
     "btv_tree_accept_greedy_lm_head", "btv_set_attn_splits",
 ]
@@ -49,12 +51,14 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.btv_last_error.restype = C.c_char_p
         for n in ("btv_tree_build_workspace", "btv_tree_verify_attn_workspace",
-                  "btv_tree_verify_attn_paged_workspace", "btv_tree_accept_workspace",
+                  "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_fp8kv_workspace",
+                  "btv_tree_verify_attn_paged_fp8kv_workspace", "btv_tree_accept_workspace",
                   "btv_tree_accept_lm_head_workspace", "btv_tree_build_batch_workspace",
                   "btv_tree_accept_batch_workspace"):
             getattr(L, n).restype = C.c_size_t
         for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_build_beam", "btv_tree_ancestor_mask",
-                  "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_accept_greedy",
+                  "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_verify_attn_fp8kv",
+                  "btv_tree_verify_attn_paged_fp8kv", "btv_tree_accept_greedy",
                   "btv_tree_accept_stochastic"):
             getattr(L, n).restype = C.c_int
         L.btv_set_attn_splits.restype = None
@@ -231,6 +235,38 @@ def btv_tree_verify_attn_paged(Q, Kpool, Vpool, block_table, q_offset, prefix_le
                                             max_blocks, _ptr(q_offset), _ptr(prefix_len), _ptr(parent), batch,
                                             total_M, M_max, L_max, Hq, Hkv, D, C.c_float(scale), _ptr(O), _ptr(ws),
                                             C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_verify_attn_fp8kv_workspace(M, L, Hq, Hkv, D) -> int:
+    return int(lib().btv_tree_verify_attn_fp8kv_workspace(M, L, Hq, Hkv, D))
+
+
+def btv_tree_verify_attn_fp8kv(Q, K8, V8, k_scale: float, v_scale: float, parent, L: int, O, ws,
+                               scale: float = 0.0) -> None:
+    M, Hq, D = Q.shape
+    Hkv = K8.shape[1]
+    assert K8.shape[0] >= L + M and V8.shape == K8.shape and O.shape == Q.shape
+    assert Q.dtype == torch.bfloat16 and K8.element_size() == 1 and V8.element_size() == 1
+    _check(lib().btv_tree_verify_attn_fp8kv(_ptr(Q), _ptr(K8), _ptr(V8), C.c_float(k_scale), C.c_float(v_scale),
+                                            _ptr(parent), M, L, Hq, Hkv, D, C.c_float(scale), _ptr(O), _ptr(ws),
+                                            C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_verify_attn_paged_fp8kv_workspace(batch, M_max, L_max, Hq, Hkv, D) -> int:
+    return int(lib().btv_tree_verify_attn_paged_fp8kv_workspace(batch, M_max, L_max, Hq, Hkv, D))
+
+
+def btv_tree_verify_attn_paged_fp8kv(Q, K8pool, V8pool, k_scale: float, v_scale: float, block_table, q_offset,
+                                     prefix_len, parent, M_max: int, L_max: int, O, ws, scale: float = 0.0) -> None:
+    total_M, Hq, D = Q.shape
+    num_blocks, page, Hkv, _ = K8pool.shape
+    assert page == BTV_PAGE and Q.dtype == torch.bfloat16 and K8pool.element_size() == 1 and V8pool.element_size() == 1
+    batch, max_blocks = block_table.shape
+    _check(lib().btv_tree_verify_attn_paged_fp8kv(_ptr(Q), _ptr(K8pool), _ptr(V8pool), C.c_float(k_scale),
+                                                  C.c_float(v_scale), num_blocks, _ptr(block_table), max_blocks,
+                                                  _ptr(q_offset), _ptr(prefix_len), _ptr(parent), batch, total_M, M_max,
+                                                  L_max, Hq, Hkv, D, C.c_float(scale), _ptr(O), _ptr(ws),
+                                                  C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
 
 
 def btv_tree_accept_workspace(M: int, V: int, stochastic: bool) -> int:

@@ -53,7 +53,8 @@ struct AttnParams {
     int nsplit;                   // key splits of the longest request
     int row_blocks, units;        // row blocks per (split, head, request) unit; number of units
     float scale;                  // softmax scale
-    float scale_log2;             // scale * log2(e)
+    float scale_log2;             // scale * log2(e) (times the key scale of an FP8 cache)
+    float out_scale;              // 1, or the value scale of an FP8 cache
 #ifdef BTV_EXPERIMENT
     unsigned long long *dbg;      // per-workgroup phase timestamps (experiment builds only)
 #endif
@@ -170,47 +171,61 @@ __global__ __launch_bounds__(256) void anc_mask_kernel(const int32_t *parent, co
 //      from two transposing LDS reads (ds_read_b64_tr_b16): a 16-lane group reads 4 keys x 16 channels
 //      and every lane receives the 4 keys of its own channel.
 // ------------------------------------------------------------------------------------------------
-template <int D>
+// EB = bytes per K/V element in memory and in LDS: 2 (bf16) or 1 (FP8 E4M3, converted to bf16 in registers after
+// the operand reads: every E4M3 number is a bf16 number, so the conversion is exact).
+template <int D, int EB = 2>
 struct Lds {
-    static constexpr int ROWB = 2 * D;                       // bytes per K or V row
+    static constexpr int ROWB = EB * D;                      // bytes per K or V row
     static constexpr int TILEB = 32 * ROWB;                  // one K (or V) tile
     static constexpr int STAGE = 2 * TILEB;                  // K tile then V tile
     static constexpr int INSTR = STAGE / 1024;               // wave-wide 1 KiB fills per tile
+    static constexpr int CHUNKS = ROWB / 16;                 // 16-byte chunks per row
 };
 
 __device__ __forceinline__ int swap_bits_2_3(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
-template <int D> __device__ __forceinline__ int swz_k(int row) { return row & (D / 8 - 1); }
-// V rows: the four rows a 16-lane group of a transposing read touches (row % 4 = 0..3) are moved 64 bytes apart.
-template <int D> __device__ __forceinline__ int swz_v(int row) { return ((row & 3) << 2) & (D / 8 - 1); }
+// bf16 rows (2*D bytes): consecutive rows start on the same bank, so the chunk is rotated by the row number.
+// FP8 rows of 128 bytes: even and odd rows already sit in different halves of the 64 banks, so pairs of rows share a
+// rotation.
+template <int D, int EB = 2> __device__ __forceinline__ int swz_k(int row)
+{
+    return EB == 2 ? (row & (D / 8 - 1)) : ((row >> 1) & (Lds<D, EB>::CHUNKS - 1));
+}
+// V rows, bf16: the four rows a 16-lane group of a transposing read touches (row % 4 = 0..3) are moved 64 bytes
+// apart.  FP8: a group touches 8 rows x 16 bytes and two groups (32 bytes per row) are served together; the four
+// even (and the four odd) rows among them are moved 32 bytes apart.
+template <int D, int EB = 2> __device__ __forceinline__ int swz_v(int row)
+{
+    return EB == 2 ? (((row & 3) << 2) & (D / 8 - 1)) : ((((row >> 1) & 3) << 1) & (Lds<D, EB>::CHUNKS - 1));
+}
 
 #define BTV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 // Per-wave, loop-invariant part of the ring fills.  A wave issues LPW fills per tile; fill jj of wave w is
 // instruction j = w*LPW + jj of the tile (K part first).  Lane l of it fills LDS row r, physical chunk pc, with
 // source row key_off (relative to the tile's first key) and source chunk pc ^ swizzle(r).
-template <int D, int WAVES, bool PAGED>
+template <int D, int WAVES, bool PAGED, int EB = 2>
 struct Fill {
-    static constexpr int LPW = Lds<D>::INSTR / WAVES;
-    static_assert(LPW >= 1 && LPW * WAVES == Lds<D>::INSTR, "fills must divide evenly over the waves");
+    static constexpr int LPW = Lds<D, EB>::INSTR / WAVES;
+    static_assert(LPW >= 1 && LPW * WAVES == Lds<D, EB>::INSTR, "fills must divide evenly over the waves");
     const unsigned char *base[LPW]; // K or V base of this KV head for fill jj (wave-uniform)
     const int32_t *block_table;     // row of this request (paged)
     int num_blocks, S;
-    uint32_t row_bytes;             // Hkv * D * 2: distance between consecutive keys
+    uint32_t row_bytes;             // Hkv * D * EB: distance between consecutive keys
     uint32_t lane_off[LPW];         // contiguous: key_off*row_bytes + chunk*16;  paged: (key_off & 15)*row_bytes + chunk*16
     int key_off[LPW];
 };
 
-template <int D, int WAVES, bool PAGED>
-__device__ __forceinline__ Fill<D, WAVES, PAGED> make_fill(const void *K, const void *V, const int32_t *bt, int num_blocks,
-                                                           int Hkv, int g, int S, int w, int l)
+template <int D, int WAVES, bool PAGED, int EB = 2>
+__device__ __forceinline__ Fill<D, WAVES, PAGED, EB> make_fill(const void *K, const void *V, const int32_t *bt, int num_blocks,
+                                                               int Hkv, int g, int S, int w, int l)
 {
-    using LD = Lds<D>;
-    constexpr int CH = D / 8, RPI = 1024 / LD::ROWB;
-    Fill<D, WAVES, PAGED> f;
-    const uintptr_t Kb = reinterpret_cast<uintptr_t>(K) + (size_t)g * D * 2, Vb = reinterpret_cast<uintptr_t>(V) + (size_t)g * D * 2;
+    using LD = Lds<D, EB>;
+    constexpr int CH = LD::CHUNKS, RPI = 1024 / LD::ROWB;
+    Fill<D, WAVES, PAGED, EB> f;
+    const uintptr_t Kb = reinterpret_cast<uintptr_t>(K) + (size_t)g * D * EB, Vb = reinterpret_cast<uintptr_t>(V) + (size_t)g * D * EB;
     f.block_table = bt; f.num_blocks = num_blocks; f.S = S;
-    f.row_bytes = (uint32_t)Hkv * D * 2;
+    f.row_bytes = (uint32_t)Hkv * D * EB;
 #pragma unroll
     for (int jj = 0; jj < f.LPW; ++jj) {
         const int j = w * f.LPW + jj;
@@ -219,7 +234,7 @@ __device__ __forceinline__ Fill<D, WAVES, PAGED> make_fill(const void *K, const 
         const int jt = isv ? j - LD::TILEB / 1024 : j;
         const int r = jt * RPI + l / CH, pc = l % CH;
         f.key_off[jj] = isv ? r : swap_bits_2_3(r);
-        const int chunk = pc ^ (isv ? swz_v<D>(r) : swz_k<D>(r));
+        const int chunk = pc ^ (isv ? swz_v<D, EB>(r) : swz_k<D, EB>(r));
         f.lane_off[jj] = (uint32_t)(PAGED ? (f.key_off[jj] & 15) : f.key_off[jj]) * f.row_bytes + chunk * 16;
     }
     return f;
@@ -227,10 +242,10 @@ __device__ __forceinline__ Fill<D, WAVES, PAGED> make_fill(const void *K, const 
 
 // Issue this wave's share of the direct-to-LDS loads of tile `st` (keys 32*st ..) into ring slot `slot`.
 // Keys past the end of the sequence re-read the last valid row (finite data; their scores are masked).
-template <int D, int WAVES, bool PAGED>
-__device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED> &f, unsigned char *smem, int slot, int st, int w)
+template <int D, int WAVES, bool PAGED, int EB = 2>
+__device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, unsigned char *smem, int slot, int st, int w)
 {
-    using LD = Lds<D>;
+    using LD = Lds<D, EB>;
     const int kb = st * 32;
     const bool whole = kb + 32 <= f.S;       // uniform: no key of this tile needs clamping
     if (!PAGED) {
@@ -455,6 +470,115 @@ __device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l, f
     pv_tile<DT>(va, pb, oacc);
 }
 
+// ---- FP8 (E4M3) K/V: operand reads and exact conversion to bf16 ---------------------------------------
+// K: a lane reads 16 consecutive channels (16 bytes) of its key row, channels 32 s + 16 h .. + 15 for s = 0 .. D/32-1,
+// and uses the first 8 for contraction step 2s, the last 8 for step 2s+1.  The contraction steps thus take the
+// channels in another order than the bf16 layout; the query operands are loaded in the same order, so the sum is
+// over the same products.  Address: (tile + lane part) ^ (s << 5), as for bf16 with 128-byte rows.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int D> __device__ __forceinline__ uint32_t lane_k8_off(int l)
+{
+    const int c = l & 31, h = l >> 5;
+    return (uint32_t)(c * Lds<D, 1>::ROWB + ((h ^ swz_k<D, 1>(c)) << 4));
+}
+
+template <int D> __device__ __forceinline__ void lds_read_k8(uint32_t a, u32x4 (&k8)[D / 32])
+{
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        const uint32_t addr = a ^ (uint32_t)(s << 5);
+        asm volatile("ds_read_b128 %0, %1" : "=v"(k8[s]) : "v"(addr));
+    }
+}
+
+template <int YOUNGER> __device__ __forceinline__ void lds_wait_k8(u32x4 (&k8)[4])
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(k8[0]), "+v"(k8[1]), "+v"(k8[2]), "+v"(k8[3]) : "n"(YOUNGER));
+}
+
+// Two E4M3 codes (one 16-bit half of a register) to two bf16, scale 1: exact for every code.
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t w, bool high)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 r = high ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true)
+                          : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// eight consecutive codes (two registers) -> one bf16 MFMA operand
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1)
+{
+    const u32x4 r = { fp8x2_to_bf16x2(w0, false), fp8x2_to_bf16x2(w0, true), fp8x2_to_bf16x2(w1, false),
+                      fp8x2_to_bf16x2(w1, true) };
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// V^T operands (ds_read_b64_tr_b8): a 16-lane group reads 8 key rows x 16 channels; lane j of the group supplies
+// the address of row j/2, bytes 8 (j%2) .. + 7 of the group's 16 channels, and receives the 8 keys of channel j.
+// Lane l sits in group l/16 = 2h + dhalf; for (dt, mm) the group reads keys 16mm + 8h .. + 7, channels
+// 32dt + 16dhalf .. + 15, so the lane receives keys 16mm + 8h .. + 7 of channel 32dt + (l%32): one whole operand
+// of the PV MFMA with index mm.  With the V swizzle the address is ((tile + lane part) ^ (dt << 5)) + 16mm * row
+// bytes, the last term an immediate offset.
+template <int D> __device__ __forceinline__ uint32_t lane_v8_off(int l)
+{
+    const int h = l >> 5, dhalf = (l >> 4) & 1, j = l & 15;
+    const int row = 8 * h + (j >> 1);
+    return (uint32_t)(row * Lds<D, 1>::ROWB + ((swz_v<D, 1>(row) ^ dhalf) << 4) + ((j & 1) << 3));
+}
+
+template <int D, int MM> __device__ __forceinline__ void lds_read_vt8(uint32_t a, u32x2 (&v8)[D / 32][2])
+{
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+        const uint32_t addr = a ^ (uint32_t)(dt << 5);
+        asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(v8[dt][MM]) : "v"(addr), "n"(16 * MM * Lds<D, 1>::ROWB));
+    }
+}
+
+__device__ __forceinline__ void lds_wait_vt8(u32x2 (&v8)[4][2])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(v8[0][0]), "+v"(v8[0][1]), "+v"(v8[1][0]), "+v"(v8[1][1]), "+v"(v8[2][0]), "+v"(v8[2][1]),
+                   "+v"(v8[3][0]), "+v"(v8[3][1]));
+}
+
+// One whole tile of an FP8 cache: the same steps as do_tile with half the operand reads and the conversions.
+template <int D>
+__device__ __forceinline__ void do_tile8(uint32_t stage, int kb, int Lr, int l, float sl2,
+                                         const uint32_t (&anc_i)[BTV_ANC_WORDS],
+                                         const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
+{
+    static_assert(D == 128, "FP8 K/V: head dimension 128 only");
+    constexpr int DS = D / 16, DT = D / 32;
+    u32x4 k8[DS / 2];
+    u32x2 v8[DT][2];
+    const uint32_t va_addr = stage + Lds<D, 1>::TILEB + lane_v8_off<D>(l);
+    lds_read_k8<D>(stage + lane_k8_off<D>(l), k8);
+    lds_read_vt8<D, 0>(va_addr, v8);
+    lds_wait_k8<DT>(k8);                 // the counter completes in order: K has landed when DT reads remain
+    lds_read_vt8<D, 1>(va_addr, v8);
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int k = 0; k < DS / 2; ++k) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp8x8_to_bf16x8(k8[k][0], k8[k][1]), qreg[2 * k], s, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp8x8_to_bf16x8(k8[k][2], k8[k][3]), qreg[2 * k + 1], s, 0, 0, 0);
+    }
+    if (kb + 32 > Lr) mask_tile(s, vis_word(anc_i, kb, Lr), l >> 5);
+    lazy_rescale<DT>(tile_max(s), sl2, m_run, l_run, oacc);
+    bf16x8 pb[2];
+    softmax_tile(s, sl2, m_run, l_run, pb);
+    lds_wait_vt8(v8);
+#pragma unroll
+    for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp8x8_to_bf16x8(v8[dt][mm][0], v8[dt][mm][1]), pb[mm],
+                                                               oacc[dt], 0, 0, 0);
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt range");
@@ -475,9 +599,10 @@ template <int LPW, int MAXT> __device__ __forceinline__ void wait_tiles(int tile
 
 // Workgroup = RW row-waves x KW key-waves; wave (rw, kw) owns query rows [32 rw, 32 rw + 32) of the block and,
 // in every round of KW consecutive tiles, tile number kw.  LDS ring of NT tiles; one barrier per round.
-template <int D, int RW, int KW, int NT, bool PAGED>
+template <int D, int RW, int KW, int NT, bool PAGED, int EB = 2>
 __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 {
+    static_assert(EB == 2 || (EB == 1 && KW >= 2), "FP8 K/V runs in the shapes whose waves alternate over the tiles");
     constexpr int WAVES = RW * KW;
     constexpr int WR = RW * 32;
     constexpr int DS = D / 16;
@@ -486,10 +611,10 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     // which then idles at the round's barrier: those four waves issue every fill (an issue stalls its wave for
     // about a hundred cycles), the younger four only compute.
     constexpr int IW = WAVES;
-    constexpr int LPW = Lds<D>::INSTR / IW;
+    constexpr int LPW = Lds<D, EB>::INSTR / IW;
     constexpr int AHEAD = NT - 2 * KW;            // tiles still in flight when a round's tiles have landed
     static_assert(AHEAD >= 0 && AHEAD * LPW < 64, "ring too small or too deep for the counter");
-    using LD = Lds<D>;
+    using LD = Lds<D, EB>;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 31, h = l >> 5;
@@ -536,19 +661,23 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     const int rr = rvalid ? r : 0;              // padding rows recompute row 0 and are never written
     const int node = rr / p.G;
     const long long orow = (long long)(rq_.q0 + node) * p.Hq + g * p.G + (rr % p.G);   // row of Q/O as [total_M*Hq, D]
+    // Operand s holds the 8 channels that contraction step s takes from this lane's half: 16 s + 8 h .. + 7 for
+    // bf16 K, 32 (s/2) + 16 h + 8 (s%2) .. + 7 for FP8 K (the order of its 16-byte operand reads).
     u32x4 qv[DS];
     {
-        const uint16_t *qptr = static_cast<const uint16_t *>(p.Q) + orow * D + h * 8;
+        const uint16_t *qptr = static_cast<const uint16_t *>(p.Q) + orow * D + h * (EB == 2 ? 8 : 16);
 #pragma unroll
         for (int s = 0; s < DS; ++s)
-            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qv[s]) : "v"(qptr), "n"(s * 32));
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2"
+                         : "=v"(qv[s])
+                         : "v"(qptr), "n"(EB == 2 ? s * 32 : (s / 2) * 64 + (s % 2) * 16));
     }
 
     // ---- start filling the ring: NT - KW tiles in flight ----------------------------------------
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const bool issuer = wu < IW;
-    const Fill<D, IW, PAGED> fill = make_fill<D, IW, PAGED>(p.K, p.V, PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr,
-                                                            p.num_blocks, p.Hkv, g, S, issuer ? wu : 0, l);
+    const Fill<D, IW, PAGED, EB> fill = make_fill<D, IW, PAGED, EB>(p.K, p.V, PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr,
+                                                                    p.num_blocks, p.Hkv, g, S, issuer ? wu : 0, l);
     // KW == 1: three tiles up front (the first compute needs two), the rest of the ring fills during the first
     // rounds; an issue holds its wave for about a hundred cycles, so a full prefill would only delay the start.
     constexpr int PREFILL = KW == 1 ? (NT - 1 < 3 ? NT - 1 : 3) : NT - KW;
@@ -556,7 +685,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
     for (int k = 0; k < PREFILL; ++k)
         if (issued < st1) {
-            if (issuer) issue_tile<D, IW, PAGED>(fill, smem, islot, issued, wu);
+            if (issuer) issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu);
             ++issued; ++islot;
         }
     if (islot >= NT) islot -= NT;
@@ -605,7 +734,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 
     BTV_STAMP(1);
     const uint32_t ring = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem);
-    if constexpr (KW == 1) {
+    if constexpr (KW == 1 && EB == 2) {
         // ---- main loop, one tile per round, software-pipelined --------------------------------------------
         // Round t: wait until tiles <= t+1 have landed, barrier (which also tells that every wave is done with
         // tile t-1, whose ring slot the next fill overwrites), issue one more tile.  Inside a round a wave
@@ -627,7 +756,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
             for (int k = 0; k < 2; ++k)                  // two per round until the ring is full, then one
                 if (issued < st1 && issued - t < NT) {
-                    if (issuer) issue_tile<D, IW, PAGED>(fill, smem, islot, issued, wu);
+                    if (issuer) issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu);
                     ++issued;
                     if (++islot == NT) islot = 0;
                 }
@@ -678,7 +807,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             for (int i = 0; i < 4; ++i) d[i] = ph_acc[i];
         }
 #endif
-    } else {
+    } else if constexpr (KW > 1) {
         // ---- main loop: one barrier per round of KW tiles, wave kw takes tile number kw of the round ------
         // At the top of the round starting at tile st, tiles st+KW .. issued-1 may still be in flight.  The
         // barrier also tells that every wave is done with the previous round, whose KW ring slots the next
@@ -691,12 +820,16 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
             for (int k = 0; k < KW; ++k)
                 if (issued < st1) {
-                    issue_tile<D, IW, PAGED>(fill, smem, islot, issued, wu);
+                    issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu);
                     ++issued;
                     if (++islot == NT) islot = 0;
                 }
-            if (st + kw < st1)
-                do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+            if (st + kw < st1) {
+                if constexpr (EB == 2)
+                    do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+                else
+                    do_tile8<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+            }
             cslot += KW;
             if (cslot >= NT) cslot -= NT;
         }
@@ -800,7 +933,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 
     // ---- write: final bf16 rows when this request has a single split, scaled fp16 partials otherwise ---
     if (nsplit_r == 1) {
-        const float inv = 1.0f / l_run;
+        const float inv = p.out_scale / l_run;
         uint16_t *Op = static_cast<uint16_t *>(p.O) + orow * D + dt0 * 32;
 #pragma unroll
         for (int dt = 0; dt < DTK; ++dt)
@@ -904,7 +1037,7 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
     }
 #pragma unroll
     for (int off = 16; off >= 1; off >>= 1) den += __shfl_xor(den, off, 32);
-    const float inv = 1.0f / den;
+    const float inv = p.out_scale / den;
     uint16_t *dst = static_cast<uint16_t *>(p.O) + row * D + lane * E;
     if (E == 4) {
         uint32_t lo = float_to_bf16_bits(acc[0] * inv) | (float_to_bf16_bits(acc[1] * inv) << 16);
@@ -1005,14 +1138,14 @@ struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 // partials are written and read back), so few rows get small row blocks and many rows get 128-row blocks, both
 // with pairs of waves alternating over the tiles (KW = 2); very many rows over a very long prefix take the
 // 256-row software-pipelined shape (KW = 1), which measures the same there within run-to-run noise.
-Plan make_plan(int M, int L, int Hq, int Hkv, int batch)
+Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2)
 {
     Plan pl;
     int G = Hq / Hkv, rows_g = G * M;
     // Ragged batches take the small workgroup whatever the largest tree: 64-row blocks pad the smaller trees less,
     // and two such workgroups share a CU, so one's prologue and store overlap the other's main loop.
     if (rows_g <= 128 || batch > 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
-    else if (rows_g >= 1024 && L >= 16384) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }     // 70B shape at 32k: on par with (4,2,8)
+    else if (rows_g >= 1024 && L >= 16384 && eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }     // 70B shape at 32k: on par with (4,2,8)
     else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
 #ifdef BTV_EXPERIMENT
     if (g_cfg_rw) { pl.rw = g_cfg_rw; pl.kw = g_cfg_kw; pl.nt = g_cfg_nt; }
@@ -1057,16 +1190,16 @@ WsLayout ws_layout(int total_M, int Hq, int D, int nsplit)
     return w;
 }
 
-template <int D, int RW, int KW, int NT, bool PAGED>
+template <int D, int RW, int KW, int NT, bool PAGED, int EB = 2>
 int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 {
-    constexpr int RING = NT * Lds<D>::STAGE;
+    constexpr int RING = NT * Lds<D, EB>::STAGE;
     // LDS the key-wave merge needs: two waves exchange half a row each (+ m, l, bound); more waves: donors to wave 0
     constexpr int MERGE = KW == 2 ? RW * 2 * ((D / 64) * 16 + 3) * 64 * 4 : RW * (KW - 1) * ((D / 32) * 16 + 2) * 64 * 4;
     constexpr int LDS_BYTES = RING > MERGE ? RING : MERGE;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static std::atomic<bool> configured{false};         // (one GPU per process: the attribute is set once)
-    auto kern = tv_attn_bf16<D, RW, KW, NT, PAGED>;
+    auto kern = tv_attn_bf16<D, RW, KW, NT, PAGED, EB>;
     if (!configured.load(std::memory_order_acquire)) {
         BTV_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     LDS_BYTES));
@@ -1078,12 +1211,17 @@ int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 }
 
 template <bool PAGED>
-int dispatch_bf16(AttnParams &p, const Plan &pl, int D, int batch, hipStream_t st)
+int dispatch_bf16(AttnParams &p, const Plan &pl, int D, int batch, int eb, hipStream_t st)
 {
     p.row_blocks = pl.row_blocks;
     p.units = pl.nsplit * p.Hkv * batch;
     const int units = pl.nsplit * p.Hkv * batch;
     dim3 grid(((units + 7) / 8) * pl.row_blocks * 8);
+    if (eb == 1) {      // FP8 K/V
+        if (D == 128 && pl.rw == 2 && pl.kw == 2 && pl.nt == 5) return launch_bf16<128, 2, 2, 5, PAGED, 1>(p, grid, st);
+        if (D == 128 && pl.rw == 4 && pl.kw == 2 && pl.nt == 8) return launch_bf16<128, 4, 2, 8, PAGED, 1>(p, grid, st);
+        return btv_fail(BTV_EINVAL, "no FP8-KV kernel for D=%d", D);
+    }
 #define BTV_CASE(DD, RR, KK, NN) \
     if (D == DD && pl.rw == RR && pl.kw == KK && pl.nt == NN) return launch_bf16<DD, RR, KK, NN, PAGED>(p, grid, st);
 #ifdef BTV_EXPERIMENT
@@ -1103,6 +1241,121 @@ int check_shape(int M, int L, int Hq, int Hkv, int D)
     BTV_REQUIRE(L >= 0 && (long long)L + M < (1ll << 30), "L=%d out of range", L);
     BTV_REQUIRE(Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0 && Hq / Hkv <= 16, "bad heads Hq=%d Hkv=%d", Hq, Hkv);
     BTV_REQUIRE(D == 64 || D == 128, "D=%d not in {64,128}", D);
+    return BTV_OK;
+}
+
+int check_fp8(int D, float k_scale, float v_scale)
+{
+    BTV_REQUIRE(D == 128, "FP8 K/V: D=%d, only 128 is built", D);
+    BTV_REQUIRE(k_scale > 0.f && k_scale <= 3.0e38f && v_scale > 0.f && v_scale <= 3.0e38f,
+                "FP8 K/V scales must be positive and finite");
+    return BTV_OK;
+}
+
+bool aligned16(const void *a) { return (reinterpret_cast<uintptr_t>(a) & 15u) == 0; }
+
+// eb = bytes per K/V element (2: the dtype's own; 1: E4M3 codes, bf16 Q and O).  The key scale multiplies every
+// score, so it joins the softmax scale; the value scale multiplies the weighted sum, so it joins the final division.
+void set_scales(AttnParams &p, int D, float scale, float k_scale, float v_scale)
+{
+    p.scale = (scale > 0.f ? scale : 1.0f / sqrtf((float)D)) * k_scale;
+    p.scale_log2 = p.scale * 1.4426950408889634f;
+    p.out_scale = v_scale;
+}
+
+int attn_contiguous(const void *Q, const void *K, const void *V, const int32_t *parent, int M, int L, int Hq, int Hkv,
+                    int D, int dtype, int eb, float scale, float k_scale, float v_scale, void *O, void *ws,
+                    size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(Q && K && V && parent && O, "null pointer");
+    BTV_REQUIRE(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O), "Q, K, V and O must be 16-byte aligned");
+    int rc = check_shape(M, L, Hq, Hkv, D);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Plan pl = make_plan(M, L, Hq, Hkv, 1, eb);
+    if (dtype == BTV_F32) pl.nsplit = 1;
+    WsLayout wl = ws_layout(M, Hq, D, pl.nsplit);
+    rc = btv_check_ws(ws, ws_bytes, wl.total);
+    if (rc) return rc;
+    unsigned char *w8 = static_cast<unsigned char *>(ws);
+    AttnParams p = {};
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
+    p.ML = reinterpret_cast<float *>(w8 + wl.ml);
+    p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
+    p.flag = reinterpret_cast<uint32_t *>(w8);
+    p.M = M; p.L = L; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
+    p.total_rows = M * Hq; p.total_M = M;
+    p.sps = pl.sps; p.nsplit = pl.nsplit;
+    set_scales(p, D, scale, k_scale, v_scale);
+#ifdef BTV_EXPERIMENT
+    p.dbg = g_dbg;
+#endif
+    p.parent = parent;
+    if (dtype == BTV_F32) {
+        rc = btv_launch_anc_mask(parent, nullptr, 1, M, M, const_cast<uint32_t *>(p.anc), p.flag, st);
+        if (rc) return rc;
+        if (D == 64) hipLaunchKernelGGL(tv_attn_f32<64>, dim3(M, Hq), dim3(256), 0, st, p);
+        else hipLaunchKernelGGL(tv_attn_f32<128>, dim3(M, Hq), dim3(256), 0, st, p);
+        BTV_HIP(hipGetLastError());
+        return BTV_OK;
+    }
+    rc = dispatch_bf16<false>(p, pl, D, 1, eb, st);
+    if (rc) return rc;
+    if (pl.nsplit > 1) {
+        dim3 cg((M * Hq + 7) / 8, 1);
+        if (D == 64) hipLaunchKernelGGL((tv_combine_bf16<64, false>), cg, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((tv_combine_bf16<128, false>), cg, dim3(256), 0, st, p);
+        BTV_HIP(hipGetLastError());
+    }
+    return BTV_OK;
+}
+
+int attn_paged(const void *Q, const void *Kpool, const void *Vpool, int num_blocks, const int32_t *block_table,
+               int max_blocks, const int32_t *q_offset, const int32_t *prefix_len, const int32_t *parent, int batch,
+               int total_M, int M_max, int L_max, int Hq, int Hkv, int D, int eb, float scale, float k_scale,
+               float v_scale, void *O, void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(Q && Kpool && Vpool && block_table && q_offset && prefix_len && parent && O, "null pointer");
+    BTV_REQUIRE(aligned16(Q) && aligned16(Kpool) && aligned16(Vpool) && aligned16(O),
+                "Q, K, V and O must be 16-byte aligned");
+    BTV_REQUIRE(batch >= 1 && batch <= 4096, "batch=%d outside [1,4096]", batch);
+    int rc = check_shape(M_max, L_max, Hq, Hkv, D);
+    if (rc) return rc;
+    BTV_REQUIRE(total_M >= 1 && total_M <= batch * M_max, "total_M=%d inconsistent with batch*M_max", total_M);
+    BTV_REQUIRE(num_blocks >= 1 && max_blocks >= 1, "bad block counts");
+    BTV_REQUIRE((long long)max_blocks * BTV_PAGE >= (long long)L_max + 1, "max_blocks too small for L_max");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Plan pl = make_plan(M_max, L_max, Hq, Hkv, batch, eb);
+    WsLayout wl = ws_layout(batch * M_max, Hq, D, pl.nsplit);
+    rc = btv_check_ws(ws, ws_bytes, wl.total);
+    if (rc) return rc;
+    unsigned char *w8 = static_cast<unsigned char *>(ws);
+    AttnParams p = {};
+    p.Q = Q; p.K = Kpool; p.V = Vpool; p.O = O;
+    p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
+    p.ML = reinterpret_cast<float *>(w8 + wl.ml);
+    p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
+    p.flag = reinterpret_cast<uint32_t *>(w8);
+    p.block_table = block_table; p.q_offset = q_offset; p.prefix_len = prefix_len;
+    p.max_blocks = max_blocks; p.num_blocks = num_blocks;
+    p.M = M_max; p.L = L_max; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
+    p.total_rows = batch * M_max * Hq;    // partial buffers are sized for the bound; rows index by q_offset
+    p.total_M = total_M;
+    p.sps = pl.sps; p.nsplit = pl.nsplit;
+    set_scales(p, D, scale, k_scale, v_scale);
+#ifdef BTV_EXPERIMENT
+    p.dbg = g_dbg;
+#endif
+    p.parent = parent;
+    rc = dispatch_bf16<true>(p, pl, D, batch, eb, st);
+    if (rc) return rc;
+    if (pl.nsplit > 1) {
+        dim3 cg((M_max * Hq + 7) / 8, batch);
+        if (D == 64) hipLaunchKernelGGL((tv_combine_bf16<64, true>), cg, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((tv_combine_bf16<128, true>), cg, dim3(256), 0, st, p);
+        BTV_HIP(hipGetLastError());
+    }
     return BTV_OK;
 }
 
@@ -1145,49 +1398,24 @@ size_t btv_tree_verify_attn_workspace(int M, int L, int Hq, int Hkv, int D, int 
 int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int32_t *parent, int M, int L, int Hq,
                          int Hkv, int D, int dtype, float scale, void *O, void *ws, size_t ws_bytes, void *stream)
 {
-    BTV_REQUIRE(Q && K && V && parent && O, "null pointer");
-    int rc = check_shape(M, L, Hq, Hkv, D);
-    if (rc) return rc;
     BTV_REQUIRE(dtype == BTV_F32 || dtype == BTV_BF16, "dtype=%d unsupported", dtype);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    Plan pl = make_plan(M, L, Hq, Hkv, 1);
-    if (dtype == BTV_F32) pl.nsplit = 1;
-    WsLayout wl = ws_layout(M, Hq, D, pl.nsplit);
-    rc = btv_check_ws(ws, ws_bytes, wl.total);
+    return attn_contiguous(Q, K, V, parent, M, L, Hq, Hkv, D, dtype, 2, scale, 1.0f, 1.0f, O, ws, ws_bytes, stream);
+}
+
+size_t btv_tree_verify_attn_fp8kv_workspace(int M, int L, int Hq, int Hkv, int D)
+{
+    if (check_shape(M, L, Hq, Hkv, D) != BTV_OK || D != 128) return 0;
+    return ws_layout(M, Hq, D, make_plan(M, L, Hq, Hkv, 1, 1).nsplit).total;
+}
+
+int btv_tree_verify_attn_fp8kv(const void *Q, const void *K8, const void *V8, float k_scale, float v_scale,
+                               const int32_t *parent, int M, int L, int Hq, int Hkv, int D, float scale, void *O,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_fp8(D, k_scale, v_scale);
     if (rc) return rc;
-    unsigned char *w8 = static_cast<unsigned char *>(ws);
-    AttnParams p = {};
-    p.Q = Q; p.K = K; p.V = V; p.O = O;
-    p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
-    p.ML = reinterpret_cast<float *>(w8 + wl.ml);
-    p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
-    p.flag = reinterpret_cast<uint32_t *>(w8);
-    p.M = M; p.L = L; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
-    p.total_rows = M * Hq; p.total_M = M;
-    p.sps = pl.sps; p.nsplit = pl.nsplit;
-    p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
-    p.scale_log2 = p.scale * 1.4426950408889634f;
-#ifdef BTV_EXPERIMENT
-    p.dbg = g_dbg;
-#endif
-    p.parent = parent;
-    if (dtype == BTV_F32) {
-        rc = btv_launch_anc_mask(parent, nullptr, 1, M, M, const_cast<uint32_t *>(p.anc), p.flag, st);
-        if (rc) return rc;
-        if (D == 64) hipLaunchKernelGGL(tv_attn_f32<64>, dim3(M, Hq), dim3(256), 0, st, p);
-        else hipLaunchKernelGGL(tv_attn_f32<128>, dim3(M, Hq), dim3(256), 0, st, p);
-        BTV_HIP(hipGetLastError());
-        return BTV_OK;
-    }
-    rc = dispatch_bf16<false>(p, pl, D, 1, st);
-    if (rc) return rc;
-    if (pl.nsplit > 1) {
-        dim3 cg((M * Hq + 7) / 8, 1);
-        if (D == 64) hipLaunchKernelGGL((tv_combine_bf16<64, false>), cg, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((tv_combine_bf16<128, false>), cg, dim3(256), 0, st, p);
-        BTV_HIP(hipGetLastError());
-    }
-    return BTV_OK;
+    return attn_contiguous(Q, K8, V8, parent, M, L, Hq, Hkv, D, BTV_BF16, 1, scale, k_scale, v_scale, O, ws, ws_bytes,
+                           stream);
 }
 
 size_t btv_tree_verify_attn_paged_workspace(int batch, int M_max, int L_max, int Hq, int Hkv, int D)
@@ -1203,46 +1431,27 @@ int btv_tree_verify_attn_paged(const void *Q, const void *Kpool, const void *Vpo
                                int L_max, int Hq, int Hkv, int D, float scale, void *O, void *ws, size_t ws_bytes,
                                void *stream)
 {
-    BTV_REQUIRE(Q && Kpool && Vpool && block_table && q_offset && prefix_len && parent && O, "null pointer");
-    BTV_REQUIRE(batch >= 1 && batch <= 4096, "batch=%d outside [1,4096]", batch);
-    int rc = check_shape(M_max, L_max, Hq, Hkv, D);
+    return attn_paged(Q, Kpool, Vpool, num_blocks, block_table, max_blocks, q_offset, prefix_len, parent, batch, total_M,
+                      M_max, L_max, Hq, Hkv, D, 2, scale, 1.0f, 1.0f, O, ws, ws_bytes, stream);
+}
+
+size_t btv_tree_verify_attn_paged_fp8kv_workspace(int batch, int M_max, int L_max, int Hq, int Hkv, int D)
+{
+    if (batch < 1 || batch > 4096 || check_shape(M_max, L_max, Hq, Hkv, D) != BTV_OK || D != 128) return 0;
+    Plan pl = make_plan(M_max, L_max, Hq, Hkv, batch, 1);
+    return ws_layout(batch * M_max, Hq, D, pl.nsplit).total;
+}
+
+int btv_tree_verify_attn_paged_fp8kv(const void *Q, const void *K8pool, const void *V8pool, float k_scale,
+                                     float v_scale, int num_blocks, const int32_t *block_table, int max_blocks,
+                                     const int32_t *q_offset, const int32_t *prefix_len, const int32_t *parent,
+                                     int batch, int total_M, int M_max, int L_max, int Hq, int Hkv, int D, float scale,
+                                     void *O, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_fp8(D, k_scale, v_scale);
     if (rc) return rc;
-    BTV_REQUIRE(total_M >= 1 && total_M <= batch * M_max, "total_M=%d inconsistent with batch*M_max", total_M);
-    BTV_REQUIRE(num_blocks >= 1 && max_blocks >= 1, "bad block counts");
-    BTV_REQUIRE((long long)max_blocks * BTV_PAGE >= (long long)L_max + 1, "max_blocks too small for L_max");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    Plan pl = make_plan(M_max, L_max, Hq, Hkv, batch);
-    WsLayout wl = ws_layout(batch * M_max, Hq, D, pl.nsplit);
-    rc = btv_check_ws(ws, ws_bytes, wl.total);
-    if (rc) return rc;
-    unsigned char *w8 = static_cast<unsigned char *>(ws);
-    AttnParams p = {};
-    p.Q = Q; p.K = Kpool; p.V = Vpool; p.O = O;
-    p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
-    p.ML = reinterpret_cast<float *>(w8 + wl.ml);
-    p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
-    p.flag = reinterpret_cast<uint32_t *>(w8);
-    p.block_table = block_table; p.q_offset = q_offset; p.prefix_len = prefix_len;
-    p.max_blocks = max_blocks; p.num_blocks = num_blocks;
-    p.M = M_max; p.L = L_max; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
-    p.total_rows = batch * M_max * Hq;    // partial buffers are sized for the bound; rows index by q_offset
-    p.total_M = total_M;
-    p.sps = pl.sps; p.nsplit = pl.nsplit;
-    p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
-    p.scale_log2 = p.scale * 1.4426950408889634f;
-#ifdef BTV_EXPERIMENT
-    p.dbg = g_dbg;
-#endif
-    p.parent = parent;
-    rc = dispatch_bf16<true>(p, pl, D, batch, st);
-    if (rc) return rc;
-    if (pl.nsplit > 1) {
-        dim3 cg((M_max * Hq + 7) / 8, batch);
-        if (D == 64) hipLaunchKernelGGL((tv_combine_bf16<64, true>), cg, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((tv_combine_bf16<128, true>), cg, dim3(256), 0, st, p);
-        BTV_HIP(hipGetLastError());
-    }
-    return BTV_OK;
+    return attn_paged(Q, K8pool, V8pool, num_blocks, block_table, max_blocks, q_offset, prefix_len, parent, batch,
+                      total_M, M_max, L_max, Hq, Hkv, D, 1, scale, k_scale, v_scale, O, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -35,6 +35,25 @@ def run_verify_attn(t: dict, parent: np.ndarray, L: int, dtype: str, scale: floa
     return host(O).astype(np.float64)
 
 
+def run_verify_attn_fp8kv(Q_bits: np.ndarray, kv: dict, parent: np.ndarray, L: int, scale: float = 0.0, nsplit: int = 0,
+                          check_status: bool = True):
+    """Q_bits: bf16 bit patterns [M,Hq,D]; kv: dict from synth.kv_fp8 (K8, V8, k_scale, v_scale).  O as float64."""
+    Q, K8, V8 = dev(Q_bits, True), dev(kv["K8"]), dev(kv["V8"])
+    par = dev(np.asarray(parent, dtype=np.int32))
+    M, Hq, D = Q.shape
+    btv.btv_set_attn_splits(nsplit)
+    try:
+        ws = btv.alloc_workspace(btv.btv_tree_verify_attn_fp8kv_workspace(M, L, Hq, K8.shape[1], D))
+        O = torch.full_like(Q, float("nan"))
+        btv.btv_tree_verify_attn_fp8kv(Q, K8, V8, kv["k_scale"], kv["v_scale"], par, L, O, ws, scale)
+        torch.cuda.synchronize()
+        if check_status:
+            assert btv.btv_workspace_status(ws) == 0
+    finally:
+        btv.btv_set_attn_splits(0)
+    return host(O).astype(np.float64)
+
+
 def run_tree_build(marg: np.ndarray, N: int) -> dict:
     m = dev(marg.astype(np.float32))
     B, V = marg.shape
