@@ -234,6 +234,44 @@ def stream_ceiling(torch, btv, nbytes=2 << 30, reps=10):
     return round(nbytes / (ms * 1e-3) / 1e9, 1)
 
 
+def fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, steps, warmup, sizes=(16, 64, 256)):
+    """tree_verify_attn over an FP8 (E4M3) KV cache at the headline shape: same Q/O, K/V of one byte per element
+    (random codes of N(0,1) values scaled to the format's range), cycling through a ring larger than the
+    Infinity Cache like the bf16 timing."""
+    out = []
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234)
+    for n in sizes:
+        ws_ = synth.c3(n, sharp=True)
+        tree = Path(torch, btv, synth, None, 64, n, Hq, Hkv, D, B, V, ws_.marg_sigma, ws_.seed, 1)     # for parent[]
+        set_bytes = 2 * (L + n) * Hkv * D
+        sets = max(16, -(-RING_BYTES // set_bytes))
+        scale = 4.5 / 448.0
+        mk = lambda: (torch.randn((L + n, Hkv, D), generator=g, device="cuda", dtype=torch.float32).clamp_(-4.5, 4.5)
+                      / scale).to(torch.float8_e4m3fn).view(torch.uint8)
+        K8, V8 = [mk() for _ in range(sets)], [mk() for _ in range(sets)]
+        ws = btv.alloc_workspace(btv.btv_tree_verify_attn_fp8kv_workspace(n, L, Hq, Hkv, D))
+        state = {"i": 0}
+
+        def call():
+            k = state["i"] % sets
+            state["i"] += 1
+            btv.btv_tree_verify_attn_fp8kv(tree.Q, K8[k], V8[k], scale, scale, tree.parent, L, tree.O, ws)
+        ms = time_loop(torch, call, steps, warmup)
+        ab = 2 * (L + n) * Hkv * D + 2 * n * Hq * D * 2 + 4 * n
+        fl = algorithmic_flops(L, n, Hq, D, tree.depth_sum)
+        t_hbm, t_mfma = ab / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        out.append({"N": n, "attn_us": round(ms * 1e3, 3), "algorithmic_bytes": ab,
+                    "GBps": round(ab / (ms * 1e-3) / 1e9, 1), "frac_hbm": round(ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "roofline_us": round(max(t_hbm, t_mfma) * 1e6, 3),
+                    "frac_roofline": round(max(t_hbm, t_mfma) / (ms * 1e-3), 4),
+                    "binding": "hbm" if t_hbm >= t_mfma else "mfma"})
+        del K8, V8, tree, ws
+        torch.cuda.empty_cache()
+    return {"what": "btv_tree_verify_attn_fp8kv, bf16 Q/O and arithmetic, E4M3 K/V with per-tensor scales", "L": L,
+            "sizes": out}
+
+
 def other_configs(torch, btv, synth, V, steps, warmup):
     """The remaining configurations of the parity suite, timed (reported, not the headline): the 8B shape at a
     2k prefix, the ragged paged batch of 8 requests, and the 70B shape at a 32k prefix with stochastic acceptance."""
@@ -339,6 +377,7 @@ def main():
     ap.add_argument("--only-attn", action="store_true", help="time only tree_verify_attn (for profiler runs)")
     ap.add_argument("--only-lm-head", action="store_true",
                     help="time only btv_tree_accept_greedy_lm_head (for profiler runs)")
+    ap.add_argument("--only-fp8-kv", action="store_true", help="time only btv_tree_verify_attn_fp8kv (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain 256 MiB device copies instead (to scale the profiler's HBM byte counters)")
     args = ap.parse_args()
@@ -377,6 +416,11 @@ def main():
         return
     if args.only_lm_head:
         print(json.dumps(lm_head_bench(torch, btv, path, N, V, args.steps, args.warmup)))
+        return
+    if args.only_fp8_kv:
+        del path
+        torch.cuda.empty_cache()
+        print(json.dumps(fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, args.steps, args.warmup, sizes=(N,))))
         return
 
     # ---- the timed region: exactly `steps` whole-path steps ------------------------------------------------
@@ -509,6 +553,7 @@ def main():
             lmh["frac_of_measured_stream"] = round(lmh["GBps"] / ceiling, 4)
         for c in curve:
             c["frac_of_measured_stream"] = round(c["GBps"] / ceiling, 4)
+    fp8kv = optional("FP8 KV cache", lambda: fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, args.steps, args.warmup))
     configs = None if args.no_configs else optional("other configurations",
                                                     lambda: other_configs(torch, btv, synth, V, args.steps, args.warmup))
 
@@ -528,7 +573,7 @@ def main():
                               "tree_accept_greedy": round(accept_ms * 1e3, 3), "host_wall_per_step": round(wall_ms * 1e3, 3),
                               "step_replayed_from_hip_graph": graph_us},
         "roofline": roofline, "cpu_baseline": cpu, "curve_L8192": curve, "adaptive_budget": adaptive, "latency_calibration": calib,
-        "kv_commit": kvc, "lm_head": lmh, "topologies": topo, "other_configs": configs,
+        "kv_commit": kvc, "lm_head": lmh, "topologies": topo, "fp8_kv": fp8kv, "other_configs": configs,
         "context": "paper reports only end-to-end speedups (6.61x over autoregressive decoding, Qwen3-8B, A100) and a "
                    "whole-model T_verify of 22.0 ms at |T|=32 to 55.9 ms at |T|=1024; no number for this path exists",
     }

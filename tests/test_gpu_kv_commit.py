@@ -47,6 +47,25 @@ def test_contiguous(oracle, layers, L, M, n, shape, dtype):
     assert np.array_equal(_numpy(Vd, Vh)[:, :L + n], Vh[:, :L + n])
 
 
+@pytest.mark.parametrize("layers,L,M,n", [(3, 37, 64, 9), (32, 8192, 64, 7), (2, 300, 256, 200)])
+def test_contiguous_one_byte_elements(oracle, layers, L, M, n):
+    """An FP8 cache: rows of Hkv * D single bytes."""
+    rng = np.random.default_rng(77 + layers + L)
+    Kh = rng.integers(0, 256, size=(layers, L + M, 8, 128)).astype(np.uint8)
+    Vh = rng.integers(0, 256, size=(layers, L + M, 8, 128)).astype(np.uint8)
+    path = _path(rng, M, n)
+    Kd, Vd = _torch(Kh), _torch(Vh)
+    pd = torch.full((M,), -3, dtype=torch.int32, device="cuda")
+    pd[:n] = torch.from_numpy(path).cuda()
+    nd = torch.tensor([n], dtype=torch.int32, device="cuda")
+    btv.btv_kv_commit(Kd, Vd, L, M, pd, nd, None)
+    torch.cuda.synchronize()
+    assert oracle.kv_commit(Kh, L, M, path) == L + n
+    oracle.kv_commit(Vh, L, M, path)
+    assert np.array_equal(Kd.cpu().numpy()[:, :L + n], Kh[:, :L + n])
+    assert np.array_equal(Vd.cpu().numpy()[:, :L + n], Vh[:, :L + n])
+
+
 def test_paged_ragged_batch(oracle):
     """Eight requests with their own prefix lengths, trees and accepted paths over one pool (the ragged, paged
     configuration), four layers; blocks that belong to no request must stay as they were."""
