@@ -52,6 +52,9 @@ def test_version_and_workspace_queries(lib):
     assert lib.btv_tree_verify_attn_workspace(16, 128, 1, 1, 64, 0) >= 256
     assert lib.btv_tree_verify_attn_workspace(0, 128, 1, 1, 64, 0) == 0          # invalid shape -> 0
     assert lib.btv_tree_verify_attn_workspace(16, 128, 3, 2, 64, 0) == 0
+    assert lib.btv_tree_verify_attn_fp8kv_workspace(64, 8192, 32, 8, 128) > 64 * 8 * 4
+    assert lib.btv_tree_verify_attn_fp8kv_workspace(64, 8192, 32, 8, 64) == 0        # D = 64 is not built for FP8 K/V
+    assert lib.btv_tree_verify_attn_paged_fp8kv_workspace(8, 64, 8192, 32, 8, 128) > 0
     assert lib.btv_tree_build_workspace(16, 128256, 64) > 0
     assert lib.btv_tree_build_workspace(17, 128256, 64) == 0
     assert lib.btv_tree_accept_workspace(64, 128256, 0) > 0
@@ -76,6 +79,26 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert rc == -2 and b"aligned" in lib.btv_last_error()
     rc = lib.btv_tree_verify_attn(fake, fake, fake, fake, 16, 10, 8, 8, 128, 1, f0, fake, fake, C.c_size_t(16), None)
     assert rc == -2 and b"too small" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn(C.c_void_p(4096 + 8), fake, fake, fake, 16, 10, 8, 8, 128, 1, f0, fake, None, C.c_size_t(0),
+                                  None)
+    assert rc == -1 and b"16-byte aligned" in lib.btv_last_error()
+    # FP8 KV cache: D = 128 only, positive finite scales, the same shape checks
+    one, zero, nan = C.c_float(1.0), C.c_float(0.0), C.c_float(float("nan"))
+    rc = lib.btv_tree_verify_attn_fp8kv(fake, fake, fake, one, one, fake, 16, 10, 8, 8, 64, f0, fake, None, C.c_size_t(0), None)
+    assert rc == -1 and b"D=64" in lib.btv_last_error()
+    for ks, vs in ((zero, one), (one, zero), (nan, one), (one, C.c_float(float("inf"))), (C.c_float(-2.0), one)):
+        rc = lib.btv_tree_verify_attn_fp8kv(fake, fake, fake, ks, vs, fake, 16, 10, 8, 8, 128, f0, fake, None,
+                                            C.c_size_t(0), None)
+        assert rc == -1 and b"scales" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn_fp8kv(fake, fake, fake, one, one, fake, 1000, 10, 8, 8, 128, f0, fake, None,
+                                        C.c_size_t(0), None)
+    assert rc == -1 and b"M=1000" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn_fp8kv(fake, fake, fake, one, one, fake, 16, 10, 8, 8, 128, f0, fake, None,
+                                        C.c_size_t(0), None)
+    assert rc == -2 and b"workspace" in lib.btv_last_error()
+    rc = lib.btv_tree_verify_attn_paged_fp8kv(fake, fake, fake, one, one, 10, fake, 4, fake, fake, fake, 2, 10, 8, 1 << 20,
+                                              8, 8, 128, f0, fake, fake, C.c_size_t(1 << 30), None)
+    assert rc == -1 and b"max_blocks" in lib.btv_last_error()
     rc = lib.btv_tree_build(fake, 16, 128256, 1000, fake, fake, None, None, fake, None, fake, C.c_size_t(1 << 30), None)
     assert rc == -1
     rc = lib.btv_tree_build(fake, 99, 128256, 64, fake, fake, None, None, fake, None, fake, C.c_size_t(1 << 30), None)
