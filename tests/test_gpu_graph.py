@@ -9,7 +9,8 @@ from paper_2605_29727_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def test_graph_replays_equal_eager(oracle):
+@pytest.mark.parametrize("fp8", [False, True], ids=["bf16_cache", "fp8_cache"])
+def test_graph_replays_equal_eager(oracle, fp8):
     import torch
     from paper_2605_29727_amd import binding as btv
     import gpu_util as G
@@ -17,7 +18,7 @@ def test_graph_replays_equal_eager(oracle):
     dev = "cuda"
     marg = torch.empty((B, V), dtype=torch.float32, device=dev)
     Q = torch.empty((N, Hq, D), dtype=torch.bfloat16, device=dev)
-    Kc = torch.empty((layers, L + N, Hkv, D), dtype=torch.bfloat16, device=dev)
+    Kc = torch.empty((layers, L + N, Hkv, D), dtype=torch.uint8 if fp8 else torch.bfloat16, device=dev)
     Vc = torch.empty_like(Kc)
     logits = torch.empty((N + 1, V), dtype=torch.bfloat16, device=dev)
     parent = torch.zeros(N, dtype=torch.int32, device=dev)
@@ -27,12 +28,16 @@ def test_graph_replays_equal_eager(oracle):
     ahat = torch.zeros(1, dtype=torch.float32, device=dev)
     O = torch.zeros_like(Q)
     ws_b = btv.alloc_workspace(btv.btv_tree_build_workspace(B, V, N))
-    ws_a = btv.alloc_workspace(btv.btv_tree_verify_attn_workspace(N, L, Hq, Hkv, D, btv.BTV_BF16))
+    ws_a = btv.alloc_workspace(btv.btv_tree_verify_attn_fp8kv_workspace(N, L, Hq, Hkv, D) if fp8 else
+                               btv.btv_tree_verify_attn_workspace(N, L, Hq, Hkv, D, btv.BTV_BF16))
     ws_c = btv.alloc_workspace(btv.btv_tree_accept_workspace(N, V, False))
 
     def step():
         btv.btv_tree_build(marg, N, parent, token, depth, rho, n_out, ahat, ws_b)
-        btv.btv_tree_verify_attn(Q, Kc[0], Vc[0], parent, L, O, ws_a)
+        if fp8:      # (the scales are call arguments, recorded with the launch: one pair for all replays)
+            btv.btv_tree_verify_attn_fp8kv(Q, Kc[0], Vc[0], 0.0121, 0.0118, parent, L, O, ws_a)
+        else:
+            btv.btv_tree_verify_attn(Q, Kc[0], Vc[0], parent, L, O, ws_a)
         btv.btv_tree_accept_greedy(logits, parent, token, path, n_acc, bonus, None, ws_c)
         btv.btv_kv_commit(Kc, Vc, L, N, path, n_acc)
 
@@ -41,8 +46,12 @@ def test_graph_replays_equal_eager(oracle):
         t = synth.qkv(seed, N, L, Hq, Hkv, D, "bf16")
         marg.copy_(torch.from_numpy(m))
         Q.copy_(G.dev(t["Q"], True))
+        kv = synth.kv_fp8(seed, L + N, Hkv, D) if fp8 else None
         for l in range(layers):
-            Kc[l].copy_(G.dev(t["K"], True)); Vc[l].copy_(G.dev(t["V"], True))
+            if fp8:
+                Kc[l].copy_(G.dev(kv["K8"])); Vc[l].copy_(G.dev(kv["V8"]))
+            else:
+                Kc[l].copy_(G.dev(t["K"], True)); Vc[l].copy_(G.dev(t["V"], True))
         # logits that accept a path of the tree the oracle builds from these marginals
         tree = oracle.tree_build(m, N)
         _, lf = synth.target_logits(seed, N + 1, V, 1.0, "bf16")
