@@ -597,6 +597,41 @@ template <int LPW, int MAXT> __device__ __forceinline__ void wait_tiles(int tile
     }
 }
 
+// LDS map of one workgroup: the ring of NT stages; the query tiles (one per row-wave: its 32 rows as they lie in
+// memory, 2*D bytes each, chunk-rotated like a bf16 K tile) in the top of the ring when the prologue's fills leave
+// that free, else behind them; 1 KiB for the staged parent[] in a stage the prologue leaves free, else behind the
+// query tiles.  Queries and parents are consumed before the main loop's first barrier, after which the ring owns
+// every stage.  The merge of the key-waves re-uses the same memory after the loop.
+template <int D, int RW, int KW, int NT, int EB>
+struct WgLds {
+    static constexpr int STAGE = Lds<D, EB>::STAGE;
+    static constexpr int PREFILL = KW == 1 ? (NT - 1 < 3 ? NT - 1 : 3) : NT - KW;   // tiles issued before the main loop
+    static constexpr int RING = NT * STAGE;
+    static constexpr int QTILE = 32 * D * 2;
+    static constexpr int QBYTES = RW * QTILE;
+    static constexpr int PRE_B = PREFILL * STAGE;
+    static constexpr int QOFF = RING - QBYTES > PRE_B ? RING - QBYTES : PRE_B;
+    static constexpr int PAROFF = QOFF - PRE_B >= 1024 ? PRE_B : QOFF + QBYTES;
+    static constexpr int USED = (PAROFF + 1024 > QOFF + QBYTES ? PAROFF + 1024 : QOFF + QBYTES) > RING
+                                    ? (PAROFF + 1024 > QOFF + QBYTES ? PAROFF + 1024 : QOFF + QBYTES) : RING;
+    // two key-waves exchange half a row each (+ m, l, bound); more key-waves: donors to wave 0
+    static constexpr int MERGE = KW == 2 ? RW * 2 * ((D / 64) * 16 + 3) * 64 * 4 : RW * (KW - 1) * ((D / 32) * 16 + 2) * 64 * 4;
+    static constexpr int BYTES = USED > MERGE ? USED : MERGE;
+    static_assert(QOFF % 1024 == 0 && PAROFF % 1024 == 0 && BYTES <= 160 * 1024, "LDS budget");
+    static_assert(BTV_MAX_NODES * 4 <= 1024, "parent[] staging");
+};
+
+// Wait until at most n (wave-uniform, clamped to [0, MAXN]) vector-memory operations are in flight.
+template <int MAXN> __device__ __forceinline__ void wait_vm_ops(int n)
+{
+    if constexpr (MAXN > 0) {
+        if (n >= MAXN) { wait_vmcnt<MAXN>(); return; }
+        wait_vm_ops<MAXN - 1>(n);
+    } else {
+        wait_vmcnt<0>();
+    }
+}
+
 // Workgroup = RW row-waves x KW key-waves; wave (rw, kw) owns query rows [32 rw, 32 rw + 32) of the block and,
 // in every round of KW consecutive tiles, tile number kw.  LDS ring of NT tiles; one barrier per round.
 template <int D, int RW, int KW, int NT, bool PAGED, int EB = 2>
@@ -617,6 +652,13 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     using LD = Lds<D, EB>;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
+    // Fetch every argument now, in one round trip.  Left to the compiler the scalar loads follow the early-exit tests
+    // below in five dependent steps, three of which miss the cache (the argument block spans three lines and is cold
+    // in every launch): about two microseconds before the first fill is issued.
+    asm volatile("" ::"s"(p.Q), "s"(p.K), "s"(p.V), "s"(p.O), "s"(p.parent), "s"(p.block_table), "s"(p.q_offset),
+                 "s"(p.prefix_len), "s"(p.Opart), "s"(p.ML), "s"(p.flag), "s"(p.M), "s"(p.L), "s"(p.Hq), "s"(p.Hkv), "s"(p.G),
+                 "s"(p.max_blocks), "s"(p.num_blocks), "s"(p.total_rows), "s"(p.total_M), "s"(p.sps), "s"(p.nsplit),
+                 "s"(p.row_blocks), "s"(p.units), "s"(p.scale_log2), "s"(p.out_scale));
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 31, h = l >> 5;
     const int kw = w % KW, rw = w / KW;
     // Workgroups go to the 8 XCDs round-robin by their linear id.  A unit = (key split, KV head, request); the row
@@ -655,32 +697,51 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         st1 = min(st1, max((Lr + node_hi + 1 + 31) / 32, st0 + 1));
     }
 
-    // ---- this lane's query row: issue the Q loads first (raw loads; the first ring wait below covers them) ---
+    // ---- this lane's query row ------------------------------------------------------------------------------
     const int r = by * WR + rw * 32 + c;
     const bool rvalid = r < rows_g;
     const int rr = rvalid ? r : 0;              // padding rows recompute row 0 and are never written
     const int node = rr / p.G;
     const long long orow = (long long)(rq_.q0 + node) * p.Hq + g * p.G + (rr % p.G);   // row of Q/O as [total_M*Hq, D]
-    // Operand s holds the 8 channels that contraction step s takes from this lane's half: 16 s + 8 h .. + 7 for
-    // bf16 K, 32 (s/2) + 16 h + 8 (s%2) .. + 7 for FP8 K (the order of its 16-byte operand reads).
-    u32x4 qv[DS];
-    {
-        const uint16_t *qptr = static_cast<const uint16_t *>(p.Q) + orow * D + h * (EB == 2 ? 8 : 16);
+    using WL = WgLds<D, RW, KW, NT, EB>;
+
+    // ---- prologue loads, oldest first: parent[] (one entry per thread), this wave's share of its row-wave's query
+    // tile, the first ring tiles.  All are raw instructions counted by hand.
+    // parent[]: every wave moves 64 entries straight into LDS (index clamped to the request's nodes), whether or not
+    // the workgroup reaches the tree rows; entries are checked where they are read.
 #pragma unroll
-        for (int s = 0; s < DS; ++s)
-            asm volatile("global_load_dwordx4 %0, %1, off offset:%2"
-                         : "=v"(qv[s])
-                         : "v"(qptr), "n"(EB == 2 ? s * 32 : (s / 2) * 64 + (s % 2) * 16));
+    for (int i0 = 0; i0 < BTV_MAX_NODES; i0 += WAVES * 64)
+        if (tid + i0 < BTV_MAX_NODES) {              // wave-uniform: whole waves
+            const int32_t *pp = p.parent + rq_.q0 + min(tid + i0, Mr - 1);
+            const int dst = __builtin_amdgcn_readfirstlane(WL::PAROFF + ((tid + i0) >> 6) * 256);
+            __builtin_amdgcn_global_load_lds(pp, BTV_LDS_PTR(smem + dst), 4, 0, 0);
+        }
+    // Query tile: direct-to-LDS like a K tile (each wave instruction moves 1 KiB: whole rows, coalesced); as
+    // per-lane operand loads the same bytes cost 64 separate 16-byte pieces per instruction and held the ring fills
+    // back by about two microseconds.  The KW waves of a row-wave share the tile's instructions.
+    constexpr int QCH = D / 8, QRPI = 1024 / (2 * D), QINSTR = WL::QTILE / 1024, QPW = QINSTR / KW;
+    static_assert(QPW * KW == QINSTR, "query tile instructions must divide over the key-waves");
+#pragma unroll
+    for (int jj = 0; jj < QPW; ++jj) {
+        const int j = kw * QPW + jj;
+        const int qrow = j * QRPI + l / QCH, pc = l % QCH;
+        const int rf = by * WR + rw * 32 + qrow;
+        const int rrf = rf < rows_g ? rf : 0;
+        const long long of = (long long)(rq_.q0 + rrf / p.G) * p.Hq + g * p.G + (rrf % p.G);
+        const unsigned char *src = static_cast<const unsigned char *>(p.Q) + of * (D * 2) + ((pc ^ swz_k<D, 2>(qrow)) << 4);
+        // the destination must be wave-uniform: rw and kw are, but the compiler cannot know
+        const int dst = __builtin_amdgcn_readfirstlane(WL::QOFF + rw * WL::QTILE + j * 1024);
+        __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + dst), 16, 0, 0);
     }
 
-    // ---- start filling the ring: NT - KW tiles in flight ----------------------------------------
+    // ---- start filling the ring ------------------------------------------------------------------------
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const bool issuer = wu < IW;
     const Fill<D, IW, PAGED, EB> fill = make_fill<D, IW, PAGED, EB>(p.K, p.V, PAGED ? p.block_table + (long long)rq * p.max_blocks : nullptr,
                                                                     p.num_blocks, p.Hkv, g, S, issuer ? wu : 0, l);
     // KW == 1: three tiles up front (the first compute needs two), the rest of the ring fills during the first
     // rounds; an issue holds its wave for about a hundred cycles, so a full prefill would only delay the start.
-    constexpr int PREFILL = KW == 1 ? (NT - 1 < 3 ? NT - 1 : 3) : NT - KW;
+    constexpr int PREFILL = WL::PREFILL;
     int issued = st0, islot = 0;
 #pragma unroll
     for (int k = 0; k < PREFILL; ++k)
@@ -691,25 +752,52 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     if (islot >= NT) islot -= NT;
     BTV_STAMP(5);
 
+    // ---- parent[] and the query tile have landed when only the ring fills are in flight ------------------------
+    wait_vm_ops<PREFILL * LPW>(issuer ? (issued - st0) * LPW : 0);
+    // A bare barrier, and raw LDS reads below: with the fence of a full synchronisation, or with ordinary reads of
+    // memory that direct-to-LDS loads wrote, the compiler drains the ring fills first.
+    __builtin_amdgcn_s_barrier();                    // query tiles (filled by KW waves) and parent[] are visible
+    const bool tree_wg = st1 * 32 > Lr;              // this workgroup's keys reach the tree rows
+    const uint32_t par_lds = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem) + WL::PAROFF;
+    auto par_at = [&](int i) {
+        int v;
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(par_lds + 4u * (uint32_t)i) : "memory");
+        return v;
+    };
+    if (tree_wg) {
+        bool bad = false;
+        for (int i = tid; i < Mr; i += WAVES * 64) {
+            const int pa = par_at(i);
+            bad = bad || pa < -1 || pa >= i;
+        }
+        if (bad) atomicOr(p.flag, 1u);
+    }
+
+    // Operand s holds the 8 channels that contraction step s takes from this lane's half: 16 s + 8 h .. + 7 for
+    // bf16 K, 32 (s/2) + 16 h + 8 (s%2) .. + 7 for FP8 K (the order of its 16-byte operand reads).
+    u32x4 qv[DS];
+    {
+        const uint32_t qa = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem) + WL::QOFF + rw * WL::QTILE + c * (2 * D);
+        const int sw = swz_k<D, 2>(c);
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            const int chunk = EB == 2 ? 2 * s + h : 4 * (s / 2) + 2 * h + (s % 2);
+            const uint32_t addr = qa + (uint32_t)((chunk ^ sw) << 4);
+            asm volatile("ds_read_b128 %0, %1" : "=v"(qv[s]) : "v"(addr));
+        }
+    }
+
     // ---- ancestor bitmask of this lane's node, only in workgroups whose keys reach the tree rows ----------
-    // parent[] is staged in the last ring slot, which no fill touches before the first barrier of the main loop.
     uint32_t anc_i[BTV_ANC_WORDS];
 #pragma unroll
     for (int k = 0; k < BTV_ANC_WORDS; ++k) anc_i[k] = 0u;
-    if (st1 * 32 > Lr) {
-        int *par = reinterpret_cast<int *>(smem + (NT - 1) * LD::STAGE);
-        bool bad = false;
-        for (int i = tid; i < Mr; i += WAVES * 64) {
-            int pa = p.parent[rq_.q0 + i];
-            if (pa < -1 || pa >= i) { bad = true; pa = -1; }
-            par[i] = pa;
-        }
-        if (bad) atomicOr(p.flag, 1u);
-        __syncthreads();
-        for (int a = node; a >= 0; a = par[a]) {
+    if (tree_wg) {
+        for (int a = node; a >= 0;) {
 #pragma unroll
             for (int k = 0; k < BTV_ANC_WORDS; ++k)
                 if ((a >> 5) == k) anc_i[k] |= 1u << (a & 31);
+            const int pa = par_at(a);
+            a = (pa < -1 || pa >= a) ? -1 : pa;      // an invalid entry ends the walk (flagged above)
         }
     }
     BTV_STAMP(6);
@@ -721,16 +809,18 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
 
-    // The first round's fills are younger than the Q loads, so waiting for them also lands Q.
+    // the first round's tiles
     if constexpr (KW == 1) wait_tiles<LPW, NT - 2>(issuer ? issued - st0 - 1 : 0);
     else if (issued - st0 - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
     else wait_vmcnt<0>();
     bf16x8 qreg[DS];
+    if constexpr (DS == 8)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]), "+v"(qv[4]), "+v"(qv[5]), "+v"(qv[6]), "+v"(qv[7]));
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]));
 #pragma unroll
-    for (int s = 0; s < DS; ++s) {
-        asm volatile("" : "+v"(qv[s]));
-        qreg[s] = __builtin_bit_cast(bf16x8, qv[s]);
-    }
+    for (int s = 0; s < DS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qv[s]);
 
     BTV_STAMP(1);
     const uint32_t ring = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem);
@@ -1193,11 +1283,7 @@ WsLayout ws_layout(int total_M, int Hq, int D, int nsplit)
 template <int D, int RW, int KW, int NT, bool PAGED, int EB = 2>
 int launch_bf16(const AttnParams &p, dim3 grid, hipStream_t st)
 {
-    constexpr int RING = NT * Lds<D, EB>::STAGE;
-    // LDS the key-wave merge needs: two waves exchange half a row each (+ m, l, bound); more waves: donors to wave 0
-    constexpr int MERGE = KW == 2 ? RW * 2 * ((D / 64) * 16 + 3) * 64 * 4 : RW * (KW - 1) * ((D / 32) * 16 + 2) * 64 * 4;
-    constexpr int LDS_BYTES = RING > MERGE ? RING : MERGE;
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    constexpr int LDS_BYTES = WgLds<D, RW, KW, NT, EB>::BYTES;
     static std::atomic<bool> configured{false};         // (one GPU per process: the attribute is set once)
     auto kern = tv_attn_bf16<D, RW, KW, NT, PAGED, EB>;
     if (!configured.load(std::memory_order_acquire)) {
@@ -1225,7 +1311,7 @@ int dispatch_bf16(AttnParams &p, const Plan &pl, int D, int batch, int eb, hipSt
 #define BTV_CASE(DD, RR, KK, NN) \
     if (D == DD && pl.rw == RR && pl.kw == KK && pl.nt == NN) return launch_bf16<DD, RR, KK, NN, PAGED>(p, grid, st);
 #ifdef BTV_EXPERIMENT
-    BTV_CASE(128, 2, 2, 4) BTV_CASE(128, 2, 4, 10) BTV_CASE(128, 4, 2, 10) BTV_CASE(128, 8, 1, 10) BTV_CASE(128, 4, 1, 4)
+    BTV_CASE(128, 2, 2, 4) BTV_CASE(128, 2, 4, 10) BTV_CASE(128, 8, 1, 10) BTV_CASE(128, 4, 1, 4)
     BTV_CASE(128, 4, 1, 5) BTV_CASE(128, 2, 1, 4) BTV_CASE(128, 1, 4, 10) BTV_CASE(128, 2, 2, 8) BTV_CASE(128, 1, 2, 5)
     BTV_CASE(128, 1, 4, 8) BTV_CASE(128, 4, 1, 8) BTV_CASE(128, 2, 1, 8)
 #endif

@@ -519,6 +519,11 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     __shared__ RankLds RL;
     __shared__ ExpandLds S;
     __shared__ BeamLds BM;
+    // Fetch every argument in one round trip: left to the compiler the scalar loads follow the code in four
+    // dependent steps over an argument block of several cache lines that is cold in every launch.
+    asm volatile("" ::"s"(marg), "s"(V), "s"(B), "s"(K), "s"(KP), "s"(N), "s"(chunks), "s"(ctr), "s"(part), "s"(top_q),
+                 "s"(top_tok), "s"(parent), "s"(token), "s"(depth), "s"(rho), "s"(n_out), "s"(ahat), "s"(ad.cost), "s"(ad.L_AR),
+                 "s"(ad.s_best), "s"(ad.flag), "s"(beam_width), "s"(bt.n_nodes), "s"(bt.q_offset), "s"(bt.flag));
     const unsigned long long t0_ = __builtin_amdgcn_s_memtime();
     // Workgroup `row` = position row % B of request row / B; marginals, per-thread maxima and top lists are laid out
     // request after request, outputs start at the request's q_offset.
