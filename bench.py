@@ -155,10 +155,14 @@ def cpu_baseline(synth, L, N, Hq, Hkv, D, B, V, marg, seed):
     t2 = time.perf_counter()
     oracle.accept_greedy(logits, tree["parent"], tree["token"])
     t3 = time.perf_counter()
+    oracle.tree_attn(t["Qf"], t["Kf"], t["Vf"], tree["parent"], L, nthreads=1)       # the same attention on one core
+    t4 = time.perf_counter()
+    hist = np.bincount(np.asarray(tree["depth"]), minlength=B + 1)[1:].tolist()
     return {"value": round((t3 - t0) * 1e6, 1), "unit": "us/step", "cores": threads, "kind": "oracle",
             "sample": f"1 full step: tree_build {t1 - t0:.2f}s (1 thread) + attention of all {N * Hq} (node, head) rows "
                       f"{t2 - t1:.2f}s ({threads} OpenMP threads) + greedy accept {t3 - t2:.2f}s (1 thread)",
-            "attn_us": round((t2 - t1) * 1e6, 1)}
+            "attn_us": round((t2 - t1) * 1e6, 1), "attn_us_one_thread": round((t4 - t3) * 1e6, 1),
+            "tree_nodes_per_depth": hist}
 
 
 def lm_head_bench(torch, btv, path, N, V, steps, warmup, hdim=4096):
@@ -232,6 +236,15 @@ def stream_ceiling(torch, btv, nbytes=2 << 30, reps=10):
     del buf
     torch.cuda.empty_cache()
     return round(nbytes / (ms * 1e-3) / 1e9, 1)
+
+
+def mfma_ceiling(torch, btv, iters=20000, reps=5):
+    """What a register-resident bf16 matrix-core loop sustains on this machine (TFLOP/s): 2 workgroups of 8 waves
+    per CU (two waves per SIMD), four independent accumulators per wave."""
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    flops = {}
+    ms = time_loop(torch, lambda: flops.__setitem__("v", btv.btv_mfma_peak(512, iters, sink)), reps, 1)
+    return round(flops["v"] / (ms * 1e-3) / 1e12, 1)
 
 
 def fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, steps, warmup, sizes=(16, 64, 256)):
@@ -410,6 +423,7 @@ def main():
     ring_sets = max(16, -(-RING_BYTES // set_bytes))
     path = Path(torch, btv, synth, None, L, N, Hq, Hkv, D, B, V, w.marg_sigma, w.seed, ring_sets)
 
+    depth_hist = torch.bincount(path.depth.to(torch.int64), minlength=B + 1)[1:].tolist()
     if args.only_attn:
         ms = time_loop(torch, path.attn, args.steps, args.warmup)
         print(json.dumps({"only_attn_us": ms * 1e3}))
@@ -545,6 +559,12 @@ def main():
                  "calib_offset_us": round(b, 3), "rmse_raw_us": rmse(lambda x: x), "rmse_static_us": rmse(lambda x: a * x + b),
                  "ema_bias_alpha0.3": round(ema, 4)}
 
+    mfma_top = optional("matrix-core ceiling", lambda: mfma_ceiling(torch, btv), fallback=0.0)
+    if mfma_top:
+        roofline["measured_mfma_bf16_TFLOPs"] = mfma_top
+        roofline["frac_of_measured_mfma"] = round(roofline["tflops"] / mfma_top, 4)
+        for c in curve:
+            c["frac_of_measured_mfma"] = round(c["tflops"] / mfma_top, 4)
     ceiling = optional("streaming-read ceiling", lambda: stream_ceiling(torch, btv), fallback=0.0)
     if ceiling:
         roofline["measured_stream_read_GBps"] = ceiling
@@ -568,7 +588,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"llama3-8b-shaped layer, tree verify step, L={L}, N={N}, B={B}, V={V}, sharp marginals",
                    "Hq": Hq, "Hkv": Hkv, "D": D, "L": L, "N": N, "B": B, "V": V, "batch": 1,
-                   "kv_ring_sets": ring_sets, "kv_ring_MB": round(ring_sets * set_bytes / 2 ** 20, 1)},
+                   "kv_ring_sets": ring_sets, "kv_ring_MB": round(ring_sets * set_bytes / 2 ** 20, 1),
+                   "tree_nodes_per_depth": depth_hist},
         "step_breakdown_us": {"tree_build": round(build_ms * 1e3, 3), "tree_verify_attn": round(attn_ms * 1e3, 3),
                               "tree_accept_greedy": round(accept_ms * 1e3, 3), "host_wall_per_step": round(wall_ms * 1e3, 3),
                               "step_replayed_from_hip_graph": graph_us},

@@ -127,6 +127,16 @@ int btv_tree_accept_greedy_batch(const void *logits, int dtype, const int32_t *p
 int btv_stream_read(const void *src, size_t bytes, void *sink, size_t sink_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * mfma_peak -- measurement aid, not part of the method: `workgroups` workgroups of 8 wavefronts
+ * each run `iters` rounds of four independent 32x32x16 bf16 matrix-core instructions on
+ * register-resident operands, so that a benchmark can time what the matrix cores sustain on the
+ * machine it runs on.  *flops (HOST) receives the number of floating-point operations the launch
+ * performs (2 per multiply-add); sink DEVICE, >= 16384 bytes, receives checksum words of no use.
+ * ------------------------------------------------------------------------------------------- */
+int btv_mfma_peak(int workgroups, int iters, void *sink, size_t sink_bytes, double *flops,
+                  void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * tree_build_beam -- the beam-search tree that Sec. 4.3 compares best-first expansion with:
  * depth by depth, of all one-token extensions of the prefixes kept at the previous depth, the
  * `width` with the largest path score (Eq. 1) are kept: a width x depth rectangle below the

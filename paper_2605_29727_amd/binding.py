@@ -20,7 +20,8 @@ BTV_MAX_NODES, BTV_MAX_DEPTH, BTV_PAGE, BTV_ANC_WORDS = 256, 16, 16, 8
 BTV_OK, BTV_EINVAL, BTV_EWORKSPACE, BTV_EHIP, BTV_EDATA = 0, -1, -2, -3, -4
 
 EXPORTS = [
-    "btv_last_error", "btv_version", "btv_workspace_status", "btv_stream_read", "btv_tree_build_workspace", "btv_tree_build",
+    "btv_last_error", "btv_version", "btv_workspace_status", "btv_stream_read", "btv_mfma_peak", "btv_tree_build_workspace",
+    "btv_tree_build",
     "btv_tree_build_adaptive", "btv_tree_build_beam", "btv_tree_build_batch_workspace", "btv_tree_build_batch",
     "btv_tree_accept_batch_workspace", "btv_tree_accept_greedy_batch", "btv_verify_cost", "btv_calib_fit_linear", "btv_calib_ema_update",
     "btv_verify_cost_curve", "btv_kv_commit", "btv_kv_commit_paged",
@@ -133,6 +134,14 @@ def btv_stream_read(src, sink) -> None:
     """Measurement aid: one streaming read of `src` (any contiguous tensor) by all CUs."""
     _check(lib().btv_stream_read(_ptr(src), C.c_size_t(src.numel() * src.element_size()), _ptr(sink),
                                  C.c_size_t(sink.numel() * sink.element_size()), _stream()))
+
+
+def btv_mfma_peak(workgroups: int, iters: int, sink) -> float:
+    """Measurement aid: a register-resident bf16 matrix-core loop; returns the floating-point operations launched."""
+    fl = C.c_double(0.0)
+    _check(lib().btv_mfma_peak(workgroups, iters, _ptr(sink), C.c_size_t(sink.numel() * sink.element_size()), C.byref(fl),
+                               _stream()))
+    return fl.value
 
 
 def btv_tree_build_batch_workspace(batch: int, B: int, V: int, N_max: int) -> int:

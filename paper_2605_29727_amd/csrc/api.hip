@@ -32,9 +32,49 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restric
     for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off);
     if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }
+
+// Register-resident matrix-core loop for the arithmetic ceiling: every wave keeps four independent 32x32 fp32
+// accumulators and issues `iters` rounds of four v_mfma_f32_32x32x16_bf16 on operands that never leave registers.
+// The accumulators are folded into one word per wave so that the work cannot be dropped.
+typedef __bf16 pk_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float pk_f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(512, 1) void mfma_peak_kernel(int iters, uint32_t *__restrict__ sink)
+{
+    const int lane = threadIdx.x & 63;
+    pk_bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(0.001f * (float)((lane + e) & 15)); b[e] = (__bf16)(0.002f * (float)((lane ^ e) & 7)); }
+    pk_f32x16 c0, c1, c2, c3;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { c0[v] = 0.f; c1[v] = 0.f; c2[v] = 0.f; c3[v] = 0.f; }
+    for (int it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    float f = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) f += c0[v] + c1[v] + c2[v] + c3[v];
+    if (lane == 0) atomicXor(&sink[(blockIdx.x * 8 + (threadIdx.x >> 6)) & 4095], __float_as_uint(f));
+}
 }  // namespace
 
 extern "C" {
+
+int btv_mfma_peak(int workgroups, int iters, void *sink, size_t sink_bytes, double *flops, void *stream)
+{
+    BTV_REQUIRE(sink != nullptr && flops != nullptr, "null pointer");
+    BTV_REQUIRE(workgroups >= 1 && workgroups <= 65536 && iters >= 1 && iters <= (1 << 24), "workgroups=%d or iters=%d out of range",
+                workgroups, iters);
+    BTV_REQUIRE(sink_bytes >= 4096 * 4, "sink needs %d bytes", 4096 * 4);
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), iters,
+                       static_cast<uint32_t *>(sink));
+    BTV_HIP(hipGetLastError());
+    *flops = (double)workgroups * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+    return BTV_OK;
+}
 
 int btv_stream_read(const void *src, size_t bytes, void *sink, size_t sink_bytes, void *stream)
 {
