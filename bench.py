@@ -9,9 +9,10 @@ B=16 draft positions over V=128256.  The KV cache is cycled through a ring of di
 the 256 MB Infinity Cache, so every step streams its K/V from HBM ("cold").
 
 Prints ONE JSON line: `value` = microseconds per eager step; `step_breakdown_us` the stages timed on their own and
-the step replayed from a HIP graph; `roofline` the attention entry point against the HBM peak; `cpu_baseline` the
-oracle on the host cores; `curve_L8192` attention time against the tree size; further objects for the adaptive
-build, the calibration fit, the KV commit, the fused LM head and the topology comparison.  `--gpus N` with N > 1
+the step replayed from a HIP graph; `roofline` the attention entry point against the HBM peak (and against a
+streaming read and a matrix-core loop measured in the same run); `cpu_baseline` the oracle on the host cores;
+`curve_L8192` attention time against the tree size; further objects for the adaptive build, the calibration fit,
+the KV commit, the fused LM head, the topology comparison, the FP8 KV cache and the other configurations.  `--gpus N` with N > 1
 is refused: this build runs on one GPU.
 """
 from __future__ import annotations
