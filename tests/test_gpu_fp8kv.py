@@ -226,3 +226,24 @@ def test_unsupported_arguments_are_refused(G):
     with pytest.raises(btv.BtvError):
         btv.btv_tree_verify_attn_fp8kv(Q, K8, V8, 1.0, 1.0, par, 64, O, ws[:64])
     assert (O == 0).all()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(G, oracle, seed):
+    """Seeded random shapes inside the documented limits (ragged M and L, every GQA ratio up to 16, every tree kind),
+    each compared element by element."""
+    kinds = ["chain", "star", "binary", "caterpillar", "random", "deep"]
+    r = lambda tag, lo, hi: int(synth.integers(3000 + seed, tag, (1,), lo, hi)[0])
+    Hkv = (1, 2, 4, 8)[r("Hkv", 0, 3)]
+    Gq = (1, 2, 4, 8, 16)[r("G", 0, 4)]
+    M = r("M", 1, 256) if seed % 3 else r("M", 1, 40)
+    L = (0, r("L", 1, 31), r("L", 32, 700), r("L", 701, 3000))[r("Lk", 0, 3)]
+    kind = kinds[r("kind", 0, len(kinds) - 1)]
+    if M * Gq * Hkv * (L + M) > 6_000_000:      # keep the oracle's share of the test short
+        L = min(L, 600)
+    parent = synth.tree_parents(seed, M, kind)
+    q, kv = _inputs(4000 + seed, M, L, Hkv * Gq, Hkv, tag="fz")
+    ref = _oracle(oracle, q, kv, parent, L)
+    out = G.run_verify_attn_fp8kv(q["Q"], kv, parent, L)
+    assert np.isfinite(out).all()
+    assert np.abs(out - ref).max() <= TOL, (M, L, Hkv * Gq, Hkv, kind, np.abs(out - ref).max())
