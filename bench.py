@@ -488,6 +488,16 @@ def main():
     # ---- per-stage and attention-only timings (each its own back-to-back loop, KV ring cycling) --------------
     build_ms = time_loop(torch, path.build, args.steps, args.warmup)
     attn_ms = time_loop(torch, path.attn, args.steps, args.warmup)
+    # the same launches bracketed one by one (an event pair per launch costs a little itself): median and spread
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.steps, 200))]
+    for a_, b_ in pairs:
+        a_.record()
+        path.attn()
+        b_.record()
+    torch.cuda.synchronize()
+    each = sorted(a_.elapsed_time(b_) * 1e3 for a_, b_ in pairs)
+    attn_each = {"median": round(each[len(each) // 2], 3), "p10": round(each[len(each) // 10], 3),
+                 "p90": round(each[(9 * len(each)) // 10], 3), "launches": len(each)}
     accept_ms = time_loop(torch, path.accept, args.steps, args.warmup)
     # KV commit of a 32-layer cache of this shape (bf16), an accepted path of 8 of the N nodes
     kvc = {}
@@ -525,6 +535,7 @@ def main():
                 "kernel": "tree_verify_attn (tv_attn_bf16, which also forms the ancestor mask, + tv_combine_bf16)",
                 "algorithmic_bytes": ab, "us_per_launch": round(attn_ms * 1e3, 3),
                 "us_in_step": round(attn_ms_in_step * 1e3, 3), "us_warm_cache": round(attn_warm_ms * 1e3, 3),
+                "us_bracketed_one_by_one": attn_each,
                 "tflops": round(fl / (attn_ms * 1e-3) / 1e12, 1),
                 "frac_mfma_bf16": round(fl / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
