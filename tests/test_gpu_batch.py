@@ -116,3 +116,26 @@ def test_stream_read_runs_and_checks_arguments():
         btv.btv_stream_read(torch.ones(5, dtype=torch.int32, device="cuda")[1:], sink)       # 16 bytes, misaligned
     with pytest.raises(btv.BtvError):
         btv.btv_stream_read(torch.ones(4, dtype=torch.int32, device="cuda"), sink[:8])       # sink too small
+
+
+def test_mfma_peak_runs_and_checks_arguments():
+    """The matrix-core ceiling aid: reports the operations it launches (8 waves x iters x 4 instructions of
+    2*32*32*16 flops per workgroup), writes only its sink, and refuses bad arguments."""
+    import torch
+    from paper_2605_29727_amd import binding as btv
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    guard = torch.full((1024,), 7, dtype=torch.int32, device="cuda")
+    for wgs, iters in ((1, 1), (3, 17), (512, 100)):
+        assert btv.btv_mfma_peak(wgs, iters, sink) == wgs * 8 * iters * 4 * 2 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    assert bool((guard == 7).all())
+    # the accumulators hold sums of products of small non-negative numbers: every wave's folded word is a finite float
+    sink.zero_()
+    btv.btv_mfma_peak(1, 4, sink)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink[:8].view(torch.float32)).all()) and bool((sink[:8] != 0).all())
+    for bad in ((0, 10), (10, 0), (70000, 1)):
+        with pytest.raises(btv.BtvError):
+            btv.btv_mfma_peak(bad[0], bad[1], sink)
+    with pytest.raises(btv.BtvError):
+        btv.btv_mfma_peak(1, 1, sink[:8])
