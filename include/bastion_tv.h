@@ -304,10 +304,10 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
                                    size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
- * kv_commit -- after acceptance the KV cache keeps the shared prefix followed only by the
- * accepted path (App. C, "Acceptance").  In every layer, for K and V alike, sequence position
- * L + j takes the row of position L + path[j] for j < *n_acc; positions from L + *n_acc on are
- * dead afterwards.  In place.
+ * kv_commit -- makes the KV cache ready for the next cycle (App. C, "Acceptance"): behind the L
+ * prefix rows only the rows of the accepted nodes are needed, in path order.  In every layer, in K
+ * and in V, the row at sequence position L + path[j] is moved to position L + j for j < *n_acc;
+ * positions from L + *n_acc on hold nothing of use afterwards.  In place.
  *   K, V     [layers][>= L+M rows][row_bytes]; layer l starts layer_stride_bytes * l after the base;
  *            row_bytes = Hkv * D * element size, a multiple of 16, at most 32768; 16-byte aligned
  *   path     [M] int32, n_acc [1] int32 (device): as written by tree_accept (node ids in
@@ -315,20 +315,37 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
  *            gives unspecified rows L .. L+M-1, nothing else is touched (ids are clamped).
  *   new_len  [1] int32 optional: L + *n_acc
  * The paged form does the same for a batch of requests over block pools laid out
- * [layers][num_blocks][BTV_PAGE][row_bytes] with the block table, prefix lengths and per-request
- * paths ([batch][M_max], n_acc [batch]) of btv_tree_verify_attn_paged; ws (optional) receives
- * the data flag when a request's n_acc or prefix length is out of range (that request is
- * left untouched).
+ * [layers][num_blocks][BTV_PAGE][row_bytes] with the block table and prefix lengths of
+ * btv_tree_verify_attn_paged; n_acc, new_len [batch].  Paths: with q_offset ([batch+1], the array
+ * the other batch calls take; total_M = q_offset[batch]) request r's ids start at path[q_offset[r]],
+ * exactly as btv_tree_accept_greedy_batch writes them; with q_offset NULL they start at
+ * path[r * M_max] (total_M is ignored).  ws (optional) receives the data flag when a request's
+ * n_acc, offsets or prefix length are out of range (that request is left untouched).
  * ------------------------------------------------------------------------------------------- */
 int btv_kv_commit(void *K, void *V, int layers, long long layer_stride_bytes, int L, int M, int row_bytes,
                   const int32_t *path, const int32_t *n_acc, int32_t *new_len, void *stream);
 int btv_kv_commit_paged(void *Kpool, void *Vpool, int layers, long long layer_stride_bytes, int num_blocks,
                         const int32_t *block_table, int max_blocks, const int32_t *prefix_len,
-                        const int32_t *path, const int32_t *n_acc, int batch, int M_max, int row_bytes,
-                        int32_t *new_len, void *ws, void *stream);
+                        const int32_t *path, const int32_t *q_offset, int total_M, const int32_t *n_acc,
+                        int batch, int M_max, int row_bytes, int32_t *new_len, void *ws, void *stream);
 
-/* Tuning knob for experiments: number of key splits used by tree_verify_attn (0 = heuristic). */
-void btv_set_attn_splits(int nsplit);
+/* ---------------------------------------------------------------------------------------------
+ * Tuning and test form of btv_tree_verify_attn / btv_tree_verify_attn_fp8kv (App. C; bf16 Q and O):
+ * the same operation with the two choices the library otherwise makes itself passed explicitly, so
+ * that a test can run every kernel shape and split count on any input, and a tuner can sweep them.
+ *   kv_fp8   0: K, V bf16, the two scales are ignored;  1: E4M3 codes with k_scale, v_scale
+ *   nsplit   number of pieces the key range is cut into (0 = the library's choice; the library
+ *            rounds pieces to whole tiles, so fewer may result)
+ *   shape    0 = the library's choice; 1, 2, 3 = workgroups of 64, 128, 256 packed query rows
+ *            (3 is not built for an FP8 cache: BTV_EINVAL)
+ * The workspace query takes the same nsplit and shape as the call it sizes.
+ * ------------------------------------------------------------------------------------------- */
+size_t btv_tree_verify_attn_tuned_workspace(int M, int L, int Hq, int Hkv, int D, int kv_fp8,
+                                            int nsplit, int shape);
+int btv_tree_verify_attn_tuned(const void *Q, const void *K, const void *V, int kv_fp8, float k_scale,
+                               float v_scale, const int32_t *parent, int M, int L, int Hq, int Hkv,
+                               int D, float scale, int nsplit, int shape, void *O, void *ws,
+                               size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -99,61 +99,87 @@ static int cand_before(const cand_t *a, const cand_t *b, const int32_t *parent, 
     return 0;
 }
 
-/* Core of both builders.  cost == NULL: fixed budget N.  Otherwise Algorithm 1 with its early stop (Sec. 3.4,
- * Eq. 6): after popping the N-th node u, Ahat <- Ahat + rho(u) and S <- Ahat * L_AR / cost[N-1], where cost[N-1]
- * is the estimated cycle latency C(N) = T_draft + T_aux + T_verify(N) supplied by the caller; the node is kept
- * if S exceeds the best S so far (strictly), otherwise the loop ends and the tree without u is returned.
- * All of this in fp64.  s_best: best estimated speedup (-inf when no node was kept); margin: the smallest
- * relative distance |S - S*| / |S| over all comparisons made (how close any decision was to flipping). */
+/* The tree under construction plus its frontier.  The frontier holds every prefix that may be selected next:
+ * its parent is in the tree and so is its previous sibling.  It is kept sorted in selection order (best first) by
+ * insertion, so selecting is taking the head. */
+typedef struct {
+    const float *marg; const int32_t *order; int B, V;
+    int32_t *parent, *token, *depth, *rank; float *rho;
+    int n;                       /* nodes in the tree */
+    cand_t *front; int nf;       /* sorted frontier */
+} build_t;
+
+/* Path score of the prefix "child of node p with rank r" (Eq. 1): the parent's score times the marginal of the
+ * token of that rank at the child's depth, as one rounded fp32 multiply (the root scores 1). */
+static float prefix_score(const build_t *b, int32_t p, int32_t r)
+{
+    int d = (p < 0) ? 0 : b->depth[p];                       /* 0-based position of the child's token */
+    float q = b->marg[(size_t)d * b->V + b->order[(size_t)d * b->V + r]];
+    volatile float s = ((p < 0) ? 1.0f : b->rho[p]) * q;
+    return s;
+}
+
+static void frontier_insert(build_t *b, int32_t p, int32_t r)
+{
+    cand_t c = { prefix_score(b, p, r), (p < 0) ? 1 : b->depth[p] + 1, p, r };
+    int at = b->nf;
+    while (at > 0 && cand_before(&c, &b->front[at - 1], b->parent, b->rank, b->depth, b->B)) {
+        b->front[at] = b->front[at - 1];
+        --at;
+    }
+    b->front[at] = c;
+    ++b->nf;
+}
+
+/* Budget controller (Sec. 3.4, Eq. 6): would the tree with one more node of score `rho_next` have a strictly
+ * better estimated speedup  S = Ahat * L_AR / C(size)  than the best seen so far?  Updates *s_best when it does,
+ * and *margin with the relative distance between the two quotients (how close the decision was). */
+static int controller_keeps(double ahat_with, double L_AR, double cost_at_size, double *s_best, double *margin)
+{
+    double s = ahat_with * L_AR / cost_at_size;
+    if (*s_best > -INFINITY) {
+        double rel = fabs(s - *s_best) / fmax(fabs(s), 1e-300);
+        if (rel < *margin) *margin = rel;
+    }
+    if (!(s > *s_best)) return 0;
+    *s_best = s;
+    return 1;
+}
+
+/* Core of both builders.  cost == NULL: fixed budget N (Prop. 3.3).  Otherwise the budget is chosen online
+ * (Algorithm 1): cost[k-1] is the estimated cycle latency C(k) = T_draft + T_aux + T_verify(k) supplied by the
+ * caller, and growth ends at the first node that does not strictly improve the estimated speedup; that node is
+ * not part of the returned tree.  Ahat, S in fp64.  s_best: best estimated speedup (-inf when no node was kept);
+ * margin: the smallest relative distance between compared quotients. */
 static int tree_build_core(const float *marg, int B, int V, int N, const double *cost, double L_AR, int32_t *parent,
                            int32_t *token, int32_t *depth, float *rho, int32_t *rank, double *ahat, double *s_best,
                            double *margin)
 {
     if (B < 1 || B > 64 || V < 1 || N < 0) return -1;
     int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * V);
-    cand_t *front = (cand_t *)malloc(sizeof(cand_t) * (size_t)(N + 2));
     orc_rank_tokens(marg, B, V, order);
-    int nf = 0, n = 0;
-    double a = 1.0, sb = -INFINITY, mg = INFINITY;
-    /* the root's best child */
-    front[nf++] = (cand_t){ 1.0f * marg[order[0]], 1, -1, 0 };
-    while (n < N && nf > 0) {
-        int best = 0;
-        for (int j = 1; j < nf; ++j)
-            if (cand_before(&front[j], &front[best], parent, rank, depth, B)) best = j;
-        cand_t u = front[best];
-        front[best] = front[--nf];
-        if (cost) {
-            double s = (a + (double)u.rho) * L_AR / cost[n];
-            if (sb > -INFINITY) {
-                double rel = fabs(s - sb) / fmax(fabs(s), 1e-300);
-                if (rel < mg) mg = rel;
-            }
-            if (!(s > sb)) break;
-            sb = s;
-        }
-        parent[n] = u.parent; rank[n] = u.rank; depth[n] = u.depth; rho[n] = u.rho;
-        token[n] = order[(size_t)(u.depth - 1) * V + u.rank];
+    build_t b = { marg, order, B, V, parent, token, depth, rank, rho, 0,
+                  (cand_t *)malloc(sizeof(cand_t) * (size_t)(N + 2)), 0 };
+    double a = 1.0, sb = -INFINITY, mg = INFINITY;           /* the root alone: Ahat = 1 */
+    frontier_insert(&b, -1, 0);                              /* the root's most probable child */
+    while (b.n < N && b.nf > 0) {
+        cand_t u = b.front[0];                               /* the best prefix not yet in the tree */
+        if (cost && !controller_keeps(a + (double)u.rho, L_AR, cost[b.n], &sb, &mg)) break;
+        for (int j = 1; j < b.nf; ++j) b.front[j - 1] = b.front[j];
+        --b.nf;
+        int i = b.n++;
+        parent[i] = u.parent; rank[i] = u.rank; depth[i] = u.depth; rho[i] = u.rho;
+        token[i] = order[(size_t)(u.depth - 1) * V + u.rank];
         a += (double)u.rho;
-        /* frontier update: best child of u, and u's next sibling */
-        if (u.depth < B) {
-            float q = marg[(size_t)u.depth * V + order[(size_t)u.depth * V + 0]];
-            volatile float r = u.rho * q;                 /* one rounded fp32 multiply */
-            front[nf++] = (cand_t){ r, u.depth + 1, n, 0 };
-        }
-        if (u.rank + 1 < V) {
-            float prho = (u.parent < 0) ? 1.0f : rho[u.parent];
-            float q = marg[(size_t)(u.depth - 1) * V + order[(size_t)(u.depth - 1) * V + u.rank + 1]];
-            volatile float r = prho * q;
-            front[nf++] = (cand_t){ r, u.depth, u.parent, u.rank + 1 };
-        }
-        ++n;
+        /* what becomes selectable through u: its own best extension, and the sibling ranked right after it */
+        if (u.depth < B) frontier_insert(&b, i, 0);
+        if (u.rank + 1 < V) frontier_insert(&b, u.parent, u.rank + 1);
     }
     if (ahat) *ahat = a;
     if (s_best) *s_best = sb;
     if (margin) *margin = mg;
-    free(order); free(front);
-    return n;
+    free(order); free(b.front);
+    return b.n;
 }
 
 /* Returns the number of nodes emitted (= N unless the lattice has fewer prefixes), or -1 on bad arguments.

@@ -30,7 +30,7 @@ EXPORTS = [
     "btv_tree_verify_attn_fp8kv", "btv_tree_verify_attn_paged_fp8kv_workspace", "btv_tree_verify_attn_paged_fp8kv",
     "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_tree_accept_lm_head_workspace",
-    "btv_tree_accept_greedy_lm_head", "btv_set_attn_splits",
+    "btv_tree_accept_greedy_lm_head", "btv_tree_verify_attn_tuned_workspace", "btv_tree_verify_attn_tuned",
 ]
 
 
@@ -55,14 +55,13 @@ def lib() -> C.CDLL:
                   "btv_tree_verify_attn_paged_workspace", "btv_tree_verify_attn_fp8kv_workspace",
                   "btv_tree_verify_attn_paged_fp8kv_workspace", "btv_tree_accept_workspace",
                   "btv_tree_accept_lm_head_workspace", "btv_tree_build_batch_workspace",
-                  "btv_tree_accept_batch_workspace"):
+                  "btv_tree_accept_batch_workspace", "btv_tree_verify_attn_tuned_workspace"):
             getattr(L, n).restype = C.c_size_t
         for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_build_beam", "btv_tree_ancestor_mask",
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_verify_attn_fp8kv",
                   "btv_tree_verify_attn_paged_fp8kv", "btv_tree_accept_greedy",
-                  "btv_tree_accept_stochastic"):
+                  "btv_tree_accept_stochastic", "btv_tree_verify_attn_tuned"):
             getattr(L, n).restype = C.c_int
-        L.btv_set_attn_splits.restype = None
         _lib = L
     return _lib
 
@@ -98,10 +97,6 @@ def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
 
 def btv_version() -> int:
     return lib().btv_version()
-
-
-def btv_set_attn_splits(nsplit: int) -> None:
-    lib().btv_set_attn_splits(C.c_int(int(nsplit)))
 
 
 def btv_workspace_status(ws) -> int:
@@ -230,6 +225,23 @@ def btv_tree_verify_attn(Q, K, V, parent, L: int, O, ws, scale: float = 0.0) -> 
                                       C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
 
 
+def btv_tree_verify_attn_tuned_workspace(M, L, Hq, Hkv, D, kv_fp8: bool, nsplit: int, shape: int) -> int:
+    return int(lib().btv_tree_verify_attn_tuned_workspace(M, L, Hq, Hkv, D, 1 if kv_fp8 else 0, int(nsplit), int(shape)))
+
+
+def btv_tree_verify_attn_tuned(Q, K, V, parent, L: int, O, ws, scale: float = 0.0, nsplit: int = 0, shape: int = 0,
+                               k_scale: float = 1.0, v_scale: float = 1.0) -> None:
+    """K, V bf16, or one-byte E4M3 codes (then k_scale, v_scale apply)."""
+    M, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    kv_fp8 = K.element_size() == 1
+    assert K.shape[0] >= L + M and V.shape == K.shape and O.shape == Q.shape and Q.dtype == torch.bfloat16
+    _check(lib().btv_tree_verify_attn_tuned(_ptr(Q), _ptr(K), _ptr(V), 1 if kv_fp8 else 0, C.c_float(k_scale),
+                                            C.c_float(v_scale), _ptr(parent), M, L, Hq, Hkv, D, C.c_float(scale),
+                                            int(nsplit), int(shape), _ptr(O), _ptr(ws),
+                                            C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
 def btv_tree_verify_attn_paged_workspace(batch, M_max, L_max, Hq, Hkv, D) -> int:
     return int(lib().btv_tree_verify_attn_paged_workspace(batch, M_max, L_max, Hq, Hkv, D))
 
@@ -321,12 +333,20 @@ def btv_kv_commit(K, V, L: int, M: int, path, n_acc, new_len=None) -> None:
                                _ptr(path), _ptr(n_acc), _ptr(new_len), _stream()))
 
 
-def btv_kv_commit_paged(Kpool, Vpool, block_table, prefix_len, path, n_acc, new_len=None, ws=None) -> None:
-    """Kpool, Vpool [layers, num_blocks, PAGE, ...]; block_table [batch, max_blocks]; path [batch, M_max]."""
+def btv_kv_commit_paged(Kpool, Vpool, block_table, prefix_len, path, n_acc, new_len=None, ws=None, q_offset=None,
+                        M_max: int = 0) -> None:
+    """Kpool, Vpool [layers, num_blocks, PAGE, ...]; block_table [batch, max_blocks]; path [batch, M_max], or with
+    q_offset [batch + 1] the ragged [total_M] layout of the batch acceptance (then M_max must be given)."""
     assert Kpool.shape == Vpool.shape and Kpool.is_contiguous() and Vpool.is_contiguous() and Kpool.dim() >= 4
     layers, num_blocks = Kpool.shape[0], Kpool.shape[1]
     row_bytes = Kpool[0, 0, 0].numel() * Kpool.element_size()
     batch, max_blocks = block_table.shape
+    if q_offset is None:
+        total_M, M_max = 0, path.shape[1]
+    else:
+        total_M = path.numel()
+        assert M_max >= 1
     _check(lib().btv_kv_commit_paged(_ptr(Kpool), _ptr(Vpool), layers, C.c_longlong(Kpool.stride(0) * Kpool.element_size()),
-                                     num_blocks, _ptr(block_table), max_blocks, _ptr(prefix_len), _ptr(path), _ptr(n_acc),
-                                     batch, path.shape[1], row_bytes, _ptr(new_len), _ptr(ws), _stream()))
+                                     num_blocks, _ptr(block_table), max_blocks, _ptr(prefix_len), _ptr(path), _ptr(q_offset),
+                                     int(total_M), _ptr(n_acc), batch, int(M_max), row_bytes, _ptr(new_len), _ptr(ws),
+                                     _stream()))

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, 
 __global__ __launch_bounds__(256) void greedy_walk(const Best *part, int chunks, const int32_t *parent,
                                                    const int32_t *token, int M, int32_t *path, int32_t *n_acc,
                                                    int32_t *bonus, int32_t *argmax_out, const int32_t *q_offset,
-                                                   uint32_t *flag)
+                                                   int total_M, uint32_t *flag)
 {
     __shared__ int t[BTV_MAX_NODES + 1];
     __shared__ int par[BTV_MAX_NODES], tok[BTV_MAX_NODES];
@@ -98,7 +98,8 @@ __global__ __launch_bounds__(256) void greedy_walk(const Best *part, int chunks,
     if (q_offset) {
         const int rq = blockIdx.x, o0 = q_offset[rq], m = q_offset[rq + 1] - o0;
         n_acc += rq; bonus += rq;
-        if (o0 < 0 || m < 1 || m > M) {                      // M = the largest request the caller announced
+        // M = the largest request the caller announced; a request may not reach past the total_M rows of the arrays
+        if (o0 < 0 || m < 1 || m > M || (long long)o0 + m > (long long)total_M) {
             if (tid == 0) { atomicOr(flag, 32u); *n_acc = 0; *bonus = 0; }
             return;
         }
@@ -524,7 +525,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                                                         const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
                                                         int M, int V, const float *__restrict__ uniforms,
                                                         float *__restrict__ es, float2 *__restrict__ eq_sorted,
-                                                        int32_t *path, int32_t *n_acc, int32_t *bonus)
+                                                        int32_t *path, int32_t *n_acc, int32_t *bonus, uint32_t *flag)
 {
     __shared__ double shd[16];
     __shared__ float shf[16];
@@ -569,6 +570,11 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                 if (parent[c] != cur) continue;                  // uniform across the workgroup
                 const int tk = token[c];
                 const double u = (double)uniforms[ui++];
+                if (tk < 0 || tk >= V) {                         // not a vocabulary id: the child is rejected (its uniform is
+                    if (tid == 0) atomicOr(flag, 64u);           // spent), nothing is indexed with it, the data flag is raised
+                    --untried;
+                    continue;
+                }
                 const double invT = T > 0.0 ? 1.0 / T : 0.0, qx = (double)q0[tk];
                 if (u * (qx * invT) < pk(tk)) { accepted = c; break; }
                 const double b1 = beta + invT;
@@ -752,7 +758,7 @@ int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent,
     else hipLaunchKernelGGL(argmax_chunks<false>, dim3(chunks, M + 1), dim3(256), 0, st, logits, V, part);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, part, chunks, parent, token, M, path, n_acc, bonus,
-                       argmax_out, static_cast<const int32_t *>(nullptr), static_cast<uint32_t *>(nullptr));
+                       argmax_out, static_cast<const int32_t *>(nullptr), 0, static_cast<uint32_t *>(nullptr));
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -788,7 +794,7 @@ int btv_tree_accept_greedy_lm_head(const void *hidden, const void *W, int h, con
     hipLaunchKernelGGL(argmax_merge, dim3(R), dim3(256), 0, st, part, chunks, best);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, best, 1, parent, token, M, path, n_acc, bonus, argmax_out,
-                       static_cast<const int32_t *>(nullptr), static_cast<uint32_t *>(nullptr));
+                       static_cast<const int32_t *>(nullptr), 0, static_cast<uint32_t *>(nullptr));
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -818,7 +824,7 @@ int btv_tree_accept_greedy_batch(const void *logits, int dtype, const int32_t *p
     else hipLaunchKernelGGL(argmax_chunks<false>, dim3(chunks, rows), dim3(256), 0, st, logits, V, part);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(greedy_walk, dim3(batch), dim3(256), 0, st, part, chunks, parent, token, M_max, path, n_acc, bonus,
-                       argmax_out, q_offset, static_cast<uint32_t *>(ws));
+                       argmax_out, q_offset, total_M, static_cast<uint32_t *>(ws));
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -839,10 +845,10 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     float2 *eq_sorted = reinterpret_cast<float2 *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + vb);
     if (dtype == BTV_BF16)
         hipLaunchKernelGGL(stochastic_walk<true>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, eq_sorted, path, n_acc, bonus);
+                           uniforms, es, eq_sorted, path, n_acc, bonus, static_cast<uint32_t *>(ws));
     else
         hipLaunchKernelGGL(stochastic_walk<false>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, eq_sorted, path, n_acc, bonus);
+                           uniforms, es, eq_sorted, path, n_acc, bonus, static_cast<uint32_t *>(ws));
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

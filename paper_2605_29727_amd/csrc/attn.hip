@@ -55,9 +55,6 @@ struct AttnParams {
     float scale;                  // softmax scale
     float scale_log2;             // scale * log2(e) (times the key scale of an FP8 cache)
     float out_scale;              // 1, or the value scale of an FP8 cache
-#ifdef BTV_EXPERIMENT
-    unsigned long long *dbg;      // per-workgroup phase timestamps (experiment builds only)
-#endif
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
@@ -671,14 +668,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     const int bz = unit / p.nsplit;
     const int bx = PAGED ? (unit % p.nsplit + 3 * bz) % p.nsplit : unit % p.nsplit;
     const int rq = bz / p.Hkv, g = bz % p.Hkv;
-#ifdef BTV_EXPERIMENT
-    unsigned long long ts[8];
-    const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime();
-    ts[0] = __builtin_amdgcn_s_memtime();
-#define BTV_STAMP(i) ts[i] = __builtin_amdgcn_s_memtime()
-#else
-#define BTV_STAMP(i)
-#endif
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) {
         if (tid == 0 && bx == 0 && by == 0) atomicOr(p.flag, 2u);
@@ -750,7 +739,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             ++issued; ++islot;
         }
     if (islot >= NT) islot -= NT;
-    BTV_STAMP(5);
 
     // ---- parent[] and the query tile have landed when only the ring fills are in flight ------------------------
     wait_vm_ops<PREFILL * LPW>(issuer ? (issued - st0) * LPW : 0);
@@ -800,7 +788,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             a = (pa < -1 || pa >= a) ? -1 : pa;      // an invalid entry ends the walk (flagged above)
         }
     }
-    BTV_STAMP(6);
 
     float m_run = NEG_BIG, l_run = 0.f;
     f32x16 oacc[DT];
@@ -821,8 +808,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]));
 #pragma unroll
     for (int s = 0; s < DS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qv[s]);
-
-    BTV_STAMP(1);
     const uint32_t ring = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem);
     if constexpr (KW == 1 && EB == 2) {
         // ---- main loop, one tile per round, software-pipelined --------------------------------------------
@@ -830,19 +815,9 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         // tile t-1, whose ring slot the next fill overwrites), issue one more tile.  Inside a round a wave
         // overlaps the score MFMAs of tile t+1 with the softmax arithmetic of tile t, and the row maximum of
         // tile t+1 with the PV MFMAs of tile t.
-#ifdef BTV_EXPERIMENT
-        unsigned ph_acc[4] = {0, 0, 0, 0};
-        unsigned long long ph_t = __builtin_amdgcn_s_memtime();
-#define BTV_PHASE(i) { const unsigned long long n_ = __builtin_amdgcn_s_memtime(); ph_acc[i] += (unsigned)(n_ - ph_t); ph_t = n_; }
-#else
-#define BTV_PHASE(i)
-#endif
         auto sync_round = [&](int t) {
-            BTV_PHASE(3);                                 // compute since the last round's issue
             wait_tiles<LPW, NT - 3>(issuer ? issued - t - 2 : 0);     // tiles t+2 .. issued-1 may still be in flight
-            BTV_PHASE(0);
             __builtin_amdgcn_s_barrier();
-            BTV_PHASE(1);
 #pragma unroll
             for (int k = 0; k < 2; ++k)                  // two per round until the ring is full, then one
                 if (issued < st1 && issued - t < NT) {
@@ -850,7 +825,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                     ++issued;
                     if (++islot == NT) islot = 0;
                 }
-            BTV_PHASE(2);
         };
         const uint32_t koff = lane_k_off<D>(l), voff = LD::TILEB + lane_v_off<D>(l);
         uint32_t cur = ring;                                     // LDS address of tile t's stage
@@ -890,13 +864,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         softmax_tile(s, p.scale_log2, m_run, l_run, pb);
         lds_wait_vt<DT>(va);
         pv_tile<DT>(va, pb, oacc);
-#ifdef BTV_EXPERIMENT
-        BTV_PHASE(3);
-        if (p.dbg && l == 0) {
-            unsigned long long *d = p.dbg + 64 * blockIdx.x + 8 + 4 * w;
-            for (int i = 0; i < 4; ++i) d[i] = ph_acc[i];
-        }
-#endif
     } else if constexpr (KW > 1) {
         // ---- main loop: one barrier per round of KW tiles, wave kw takes tile number kw of the round ------
         // At the top of the round starting at tile st, tiles st+KW .. issued-1 may still be in flight.  The
@@ -924,8 +891,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             if (cslot >= NT) cslot -= NT;
         }
     }
-
-    BTV_STAMP(2);
     // both halves of a wave hold partial row sums of the same queries
     l_run += __shfl_xor(l_run, 32);
 
@@ -1011,7 +976,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             }
         }
     }
-    BTV_STAMP(3);
     if ((KW != 2 && kw != 0) || !rvalid) return;
     if constexpr (KW != 2) {
 #pragma unroll
@@ -1052,16 +1016,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             }
         if (h == 0 && kw == 0) *reinterpret_cast<float4 *>(p.ML + prow * 4) = make_float4(m_run, l_run, amax, 0.f);
     }
-#ifdef BTV_EXPERIMENT
-    if (p.dbg && tid == 0) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        ts[4] = __builtin_amdgcn_s_memtime();
-        unsigned long long *d = p.dbg + 64 * blockIdx.x;
-        for (int i = 0; i < 5; ++i) d[i] = ts[i];
-        d[7] = ts[5] - ts[0]; d[6] = ts[6] - ts[5];
-        d[5] = __builtin_amdgcn_s_memrealtime() - rt0;                        // 100 MHz ticks
-    }
-#endif
 }
 
 // Split-K combine: O[row] = sum_s w_s a_s O'_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e), O'_s the
@@ -1215,12 +1169,6 @@ __global__ __launch_bounds__(256) void tv_attn_f32(AttnParams p)
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-int g_split_override = 0;
-#ifdef BTV_EXPERIMENT
-int g_cfg_rw = 0, g_cfg_kw = 0, g_cfg_nt = 0;
-unsigned long long *g_dbg = nullptr;
-#endif
-
 struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 
 // Kernel shape by the number of packed rows per KV head (G*M).  Every wave owns 32 rows.  Measured on MI355X at
@@ -1228,7 +1176,8 @@ struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 // partials are written and read back), so few rows get small row blocks and many rows get 128-row blocks, both
 // with pairs of waves alternating over the tiles (KW = 2); very many rows over a very long prefix take the
 // 256-row software-pipelined shape (KW = 1), which measures the same there within run-to-run noise.
-Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2)
+// `force_split` > 0 and `force_shape` in 1..3 replace the heuristic's choices (the tuning entry point passes them).
+Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2, int force_split = 0, int force_shape = 0)
 {
     Plan pl;
     int G = Hq / Hkv, rows_g = G * M;
@@ -1237,9 +1186,9 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2)
     if (rows_g <= 128 || batch > 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
     else if (rows_g >= 1024 && L >= 16384 && eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }     // 70B shape at 32k: on par with (4,2,8)
     else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
-#ifdef BTV_EXPERIMENT
-    if (g_cfg_rw) { pl.rw = g_cfg_rw; pl.kw = g_cfg_kw; pl.nt = g_cfg_nt; }
-#endif
+    if (force_shape == 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
+    if (force_shape == 2) { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
+    if (force_shape == 3 && eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
     pl.wr = pl.rw * 32;
     pl.row_blocks = (rows_g + pl.wr - 1) / pl.wr;
     pl.stages = (L + M + TK - 1) / TK;
@@ -1254,10 +1203,10 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2)
     // (measured on ragged and uniform batches of 4 to 16 requests: within 1.5x of the best shape and split count
     // found for each; a uniform batch would do best with one unit per CU, which the host cannot tell from here).
     int target = rows_g <= 64 ? 512 : 256;
-    int want = g_split_override > 0 ? g_split_override : (target + base - 1) / base;
-    if (batch > 1 && g_split_override <= 0) want = std::max(1, std::min(8, pl.stages / 32));
+    int want = force_split > 0 ? force_split : (target + base - 1) / base;
+    if (batch > 1 && force_split <= 0) want = std::max(1, std::min(8, pl.stages / 32));
     // a split should stream at least 8 tiles (256 keys) unless the caller forces it
-    if (g_split_override <= 0) want = std::min(want, std::max(1, pl.stages / 8));
+    if (force_split <= 0) want = std::min(want, std::max(1, pl.stages / 8));
     want = std::max(1, std::min(want, pl.stages));
     pl.sps = (pl.stages + (want > 1 ? extra : 0) + want - 1) / want;
     pl.sps = (pl.sps + pl.kw - 1) / pl.kw * pl.kw;         // whole rounds of KW tiles
@@ -1310,11 +1259,6 @@ int dispatch_bf16(AttnParams &p, const Plan &pl, int D, int batch, int eb, hipSt
     }
 #define BTV_CASE(DD, RR, KK, NN) \
     if (D == DD && pl.rw == RR && pl.kw == KK && pl.nt == NN) return launch_bf16<DD, RR, KK, NN, PAGED>(p, grid, st);
-#ifdef BTV_EXPERIMENT
-    BTV_CASE(128, 2, 2, 4) BTV_CASE(128, 2, 4, 10) BTV_CASE(128, 8, 1, 10) BTV_CASE(128, 4, 1, 4)
-    BTV_CASE(128, 4, 1, 5) BTV_CASE(128, 2, 1, 4) BTV_CASE(128, 1, 4, 10) BTV_CASE(128, 2, 2, 8) BTV_CASE(128, 1, 2, 5)
-    BTV_CASE(128, 1, 4, 8) BTV_CASE(128, 4, 1, 8) BTV_CASE(128, 2, 1, 8)
-#endif
     BTV_CASE(128, 2, 2, 5) BTV_CASE(128, 4, 2, 8) BTV_CASE(128, 8, 1, 8)
     BTV_CASE(64, 2, 2, 5) BTV_CASE(64, 4, 2, 8) BTV_CASE(64, 8, 1, 8)
 #undef BTV_CASE
@@ -1351,14 +1295,14 @@ void set_scales(AttnParams &p, int D, float scale, float k_scale, float v_scale)
 
 int attn_contiguous(const void *Q, const void *K, const void *V, const int32_t *parent, int M, int L, int Hq, int Hkv,
                     int D, int dtype, int eb, float scale, float k_scale, float v_scale, void *O, void *ws,
-                    size_t ws_bytes, void *stream)
+                    size_t ws_bytes, void *stream, int force_split = 0, int force_shape = 0)
 {
     BTV_REQUIRE(Q && K && V && parent && O, "null pointer");
     BTV_REQUIRE(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O), "Q, K, V and O must be 16-byte aligned");
     int rc = check_shape(M, L, Hq, Hkv, D);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    Plan pl = make_plan(M, L, Hq, Hkv, 1, eb);
+    Plan pl = make_plan(M, L, Hq, Hkv, 1, eb, force_split, force_shape);
     if (dtype == BTV_F32) pl.nsplit = 1;
     WsLayout wl = ws_layout(M, Hq, D, pl.nsplit);
     rc = btv_check_ws(ws, ws_bytes, wl.total);
@@ -1374,9 +1318,6 @@ int attn_contiguous(const void *Q, const void *K, const void *V, const int32_t *
     p.total_rows = M * Hq; p.total_M = M;
     p.sps = pl.sps; p.nsplit = pl.nsplit;
     set_scales(p, D, scale, k_scale, v_scale);
-#ifdef BTV_EXPERIMENT
-    p.dbg = g_dbg;
-#endif
     p.parent = parent;
     if (dtype == BTV_F32) {
         rc = btv_launch_anc_mask(parent, nullptr, 1, M, M, const_cast<uint32_t *>(p.anc), p.flag, st);
@@ -1430,9 +1371,6 @@ int attn_paged(const void *Q, const void *Kpool, const void *Vpool, int num_bloc
     p.total_M = total_M;
     p.sps = pl.sps; p.nsplit = pl.nsplit;
     set_scales(p, D, scale, k_scale, v_scale);
-#ifdef BTV_EXPERIMENT
-    p.dbg = g_dbg;
-#endif
     p.parent = parent;
     rc = dispatch_bf16<true>(p, pl, D, batch, eb, st);
     if (rc) return rc;
@@ -1457,12 +1395,6 @@ int btv_launch_anc_mask(const int32_t *parent, const int32_t *q_offset, int batc
 
 extern "C" {
 
-void btv_set_attn_splits(int nsplit) { g_split_override = nsplit > 0 ? nsplit : 0; }
-
-#ifdef BTV_EXPERIMENT
-void btv_exp_set_cfg(int rw, int kw, int nt) { g_cfg_rw = rw; g_cfg_kw = kw; g_cfg_nt = nt; }
-void btv_exp_set_dbg(void *ptr) { g_dbg = static_cast<unsigned long long *>(ptr); }
-#endif
 
 int btv_tree_ancestor_mask(const int32_t *parent, int M, uint32_t *anc, void *ws, size_t ws_bytes, void *stream)
 {
@@ -1502,6 +1434,26 @@ int btv_tree_verify_attn_fp8kv(const void *Q, const void *K8, const void *V8, fl
     if (rc) return rc;
     return attn_contiguous(Q, K8, V8, parent, M, L, Hq, Hkv, D, BTV_BF16, 1, scale, k_scale, v_scale, O, ws, ws_bytes,
                            stream);
+}
+
+size_t btv_tree_verify_attn_tuned_workspace(int M, int L, int Hq, int Hkv, int D, int kv_fp8, int nsplit, int shape)
+{
+    if (check_shape(M, L, Hq, Hkv, D) != BTV_OK || (kv_fp8 && D != 128) || nsplit < 0 || shape < 0 || shape > 3) return 0;
+    return ws_layout(M, Hq, D, make_plan(M, L, Hq, Hkv, 1, kv_fp8 ? 1 : 2, nsplit, shape).nsplit).total;
+}
+
+int btv_tree_verify_attn_tuned(const void *Q, const void *K, const void *V, int kv_fp8, float k_scale, float v_scale,
+                               const int32_t *parent, int M, int L, int Hq, int Hkv, int D, float scale, int nsplit,
+                               int shape, void *O, void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(nsplit >= 0 && shape >= 0 && shape <= 3, "nsplit=%d or shape=%d out of range", nsplit, shape);
+    if (kv_fp8) {
+        int rc = check_fp8(D, k_scale, v_scale);
+        if (rc) return rc;
+        BTV_REQUIRE(shape != 3, "shape 3 is not built for an FP8 cache");
+    }
+    return attn_contiguous(Q, K, V, parent, M, L, Hq, Hkv, D, BTV_BF16, kv_fp8 ? 1 : 2, scale, kv_fp8 ? k_scale : 1.0f,
+                           kv_fp8 ? v_scale : 1.0f, O, ws, ws_bytes, stream, nsplit, shape);
 }
 
 size_t btv_tree_verify_attn_paged_workspace(int batch, int M_max, int L_max, int Hq, int Hkv, int D)

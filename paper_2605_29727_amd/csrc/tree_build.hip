@@ -514,7 +514,7 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
                                                       TbCounters *ctr, const uint32_t *part, float *top_q, uint32_t *top_tok,
                                                       int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
-                                                      Adaptive ad, int beam_width, Batch bt, unsigned long long *dbg)
+                                                      Adaptive ad, int beam_width, Batch bt)
 {
     __shared__ RankLds RL;
     __shared__ ExpandLds S;
@@ -524,7 +524,6 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     asm volatile("" ::"s"(marg), "s"(V), "s"(B), "s"(K), "s"(KP), "s"(N), "s"(chunks), "s"(ctr), "s"(part), "s"(top_q),
                  "s"(top_tok), "s"(parent), "s"(token), "s"(depth), "s"(rho), "s"(n_out), "s"(ahat), "s"(ad.cost), "s"(ad.L_AR),
                  "s"(ad.s_best), "s"(ad.flag), "s"(beam_width), "s"(bt.n_nodes), "s"(bt.q_offset), "s"(bt.flag));
-    const unsigned long long t0_ = __builtin_amdgcn_s_memtime();
     // Workgroup `row` = position row % B of request row / B; marginals, per-thread maxima and top lists are laid out
     // request after request, outputs start at the request's q_offset.
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), row = blockIdx.x;
@@ -633,13 +632,11 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
                          K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
     }
     // ---- the workgroup that finishes last expands -------------------------------------------------------------
-    const unsigned long long tr_ = __builtin_amdgcn_s_memtime();
     __threadfence();
     __syncthreads();
     if (tid == 0) RL.last = atomicAdd(&ctr[req].done, 1) == B - 1;
     __syncthreads();
     if (!RL.last) return;
-    const unsigned long long ta_ = __builtin_amdgcn_s_memtime();
     __threadfence();
     for (int e = tid; e < B * KP; e += 256) {
         S.q[e] = __builtin_nontemporal_load(top_q + (size_t)req * B * KP + e);
@@ -668,8 +665,6 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
         return;
     }
     if (w != 0) return;
-    const unsigned long long t1_ = __builtin_amdgcn_s_memtime();
-    if (dbg && lane == 0) { dbg[0] = t1_ - t0_; dbg[2] = tr_ - t0_; dbg[3] = ta_ - tr_; }
     if (ad.cost) {
         if (N <= 64) expand_wave<1, true>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
         else if (N <= 128) expand_wave<2, true>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
@@ -679,7 +674,6 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
         else if (N <= 128) expand_wave<2, false>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
         else expand_wave<4, false>(S, B, K, KP, N, lane, parent, token, depth, rho, n_out, ahat, ad);
     }
-    if (dbg && lane == 0) dbg[1] = __builtin_amdgcn_s_memtime() - t1_;
 }
 
 int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
@@ -707,15 +701,9 @@ size_t tree_build_ws(int batch, int B, int V, int N)
     return BTV_WS_HEADER + t.ctr_bytes + t.part_bytes + 2 * t.top_bytes;
 }
 
-unsigned long long *g_tb_dbg = nullptr;   // phase cycle counts of tb_rank_expand (experiment builds set it)
-
 }  // namespace
 
 extern "C" {
-
-#ifdef BTV_EXPERIMENT
-void btv_exp_tb_dbg(unsigned long long *p) { g_tb_dbg = p; }
-#endif
 
 size_t btv_tree_build_workspace(int B, int V, int N) { return tree_build_ws(1, B, V, N); }
 
@@ -745,7 +733,7 @@ static int tree_build_launch(const float *marginals, int batch, int B, int V, in
     hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B * batch), dim3(256), 0, st, marginals, V, B, t.chunks, part, ctr);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(tb_rank_expand, dim3(B * batch), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, t.chunks, ctr, part, top_q,
-                       top_tok, parent, token, depth, rho, n_out, ahat, ad, beam_width, bt, g_tb_dbg);
+                       top_tok, parent, token, depth, rho, n_out, ahat, ad, beam_width, bt);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

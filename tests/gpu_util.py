@@ -15,42 +15,42 @@ def host(t: torch.Tensor) -> np.ndarray:
     return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
 
 
-def run_verify_attn(t: dict, parent: np.ndarray, L: int, dtype: str, scale: float = 0.0, nsplit: int = 0,
+def run_verify_attn(t: dict, parent: np.ndarray, L: int, dtype: str, scale: float = 0.0, nsplit: int = 0, shape: int = 0,
                     check_status: bool = True):
-    """t: dict from synth.qkv.  Returns O as float64 numpy [M,Hq,D]."""
+    """t: dict from synth.qkv.  Returns O as float64 numpy [M,Hq,D].  With nsplit or shape the tuning entry point runs."""
     bits = dtype == "bf16"
     Q, K, V = dev(t["Q"], bits), dev(t["K"], bits), dev(t["V"], bits)
     par = dev(np.asarray(parent, dtype=np.int32))
     M, Hq, D = Q.shape
-    btv.btv_set_attn_splits(nsplit)
-    try:
+    O = torch.full_like(Q, float("nan"))
+    if nsplit or shape:
+        ws = btv.alloc_workspace(btv.btv_tree_verify_attn_tuned_workspace(M, L, Hq, K.shape[1], D, False, nsplit, shape))
+        btv.btv_tree_verify_attn_tuned(Q, K, V, par, L, O, ws, scale, nsplit, shape)
+    else:
         ws = btv.alloc_workspace(btv.btv_tree_verify_attn_workspace(M, L, Hq, K.shape[1], D, btv._dtype_code(Q)))
-        O = torch.full_like(Q, float("nan"))
         btv.btv_tree_verify_attn(Q, K, V, par, L, O, ws, scale)
-        torch.cuda.synchronize()
-        if check_status:
-            assert btv.btv_workspace_status(ws) == 0
-    finally:
-        btv.btv_set_attn_splits(0)
+    torch.cuda.synchronize()
+    if check_status:
+        assert btv.btv_workspace_status(ws) == 0
     return host(O).astype(np.float64)
 
 
 def run_verify_attn_fp8kv(Q_bits: np.ndarray, kv: dict, parent: np.ndarray, L: int, scale: float = 0.0, nsplit: int = 0,
-                          check_status: bool = True):
+                          shape: int = 0, check_status: bool = True):
     """Q_bits: bf16 bit patterns [M,Hq,D]; kv: dict from synth.kv_fp8 (K8, V8, k_scale, v_scale).  O as float64."""
     Q, K8, V8 = dev(Q_bits, True), dev(kv["K8"]), dev(kv["V8"])
     par = dev(np.asarray(parent, dtype=np.int32))
     M, Hq, D = Q.shape
-    btv.btv_set_attn_splits(nsplit)
-    try:
+    O = torch.full_like(Q, float("nan"))
+    if nsplit or shape:
+        ws = btv.alloc_workspace(btv.btv_tree_verify_attn_tuned_workspace(M, L, Hq, K8.shape[1], D, True, nsplit, shape))
+        btv.btv_tree_verify_attn_tuned(Q, K8, V8, par, L, O, ws, scale, nsplit, shape, kv["k_scale"], kv["v_scale"])
+    else:
         ws = btv.alloc_workspace(btv.btv_tree_verify_attn_fp8kv_workspace(M, L, Hq, K8.shape[1], D))
-        O = torch.full_like(Q, float("nan"))
         btv.btv_tree_verify_attn_fp8kv(Q, K8, V8, kv["k_scale"], kv["v_scale"], par, L, O, ws, scale)
-        torch.cuda.synchronize()
-        if check_status:
-            assert btv.btv_workspace_status(ws) == 0
-    finally:
-        btv.btv_set_attn_splits(0)
+    torch.cuda.synchronize()
+    if check_status:
+        assert btv.btv_workspace_status(ws) == 0
     return host(O).astype(np.float64)
 
 

@@ -168,3 +168,27 @@ def test_stochastic_wide_fans(G, oracle, V, fan):
         assert got["bonus"] == ref["bonus"], (V, fan, seed)
         checked += 1
     assert checked >= 4
+
+
+def test_stochastic_token_outside_vocabulary_is_flagged_not_faulting():
+    """A token id outside [0, V) is never used as an index: that child counts as rejected, the data flag is raised,
+    and the walk goes on with the valid children."""
+    import torch
+    import gpu_util as G
+    from paper_2605_29727_amd import binding as btv
+    B, V, M = 4, 300, 6
+    marg = synth.marginals(97, B, V, 2.0)
+    parent = np.array([-1, -1, 0, 0, 1, 2], dtype=np.int32)
+    token = np.array([10 ** 9, 7, 5, -3, 9, 11], dtype=np.int32)
+    st, _ = synth.target_logits(97, M + 1, V, 1.0, "fp32")
+    path = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(M, V, True))
+    btv.btv_tree_accept_stochastic(G.dev(st), G.dev(marg.astype(np.float32)), G.dev(parent), G.dev(token),
+                                   G.dev(np.zeros(M + 1, dtype=np.float32)), path, n_acc, bonus, ws)
+    torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == btv.BTV_EDATA
+    n = int(n_acc.item())
+    assert 0 <= n <= M and 0 <= int(bonus.item()) < V
+    assert 0 not in path.cpu().numpy()[:n].tolist()          # node 0 carries the invalid id: never accepted

@@ -139,3 +139,27 @@ def test_mfma_peak_runs_and_checks_arguments():
             btv.btv_mfma_peak(bad[0], bad[1], sink)
     with pytest.raises(btv.BtvError):
         btv.btv_mfma_peak(1, 1, sink[:8])
+
+
+def test_accept_batch_flags_request_reaching_past_the_arrays():
+    """q_offset entries that would make a request read past the total_M rows are refused on the device: the request
+    gets n_acc = 0 and the data flag is raised, the others are walked as usual."""
+    import torch
+    import gpu_util as G
+    from paper_2605_29727_amd import binding as btv
+    V, Ms = 500, [6, 5]
+    total = sum(Ms)
+    pars = [synth.tree_parents(70 + r, M, "random") for r, M in enumerate(Ms)]
+    toks = [synth.sibling_distinct_tokens(70 + r, p, V) for r, p in enumerate(pars)]
+    st, _ = synth.target_logits(70, total + 2, V, 1.0, "fp32")
+    q_offset = np.array([0, 6, 6 + 9], dtype=np.int32)        # request 1 claims 9 nodes: 4 more than the arrays hold
+    path = torch.full((total,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_batch_workspace(2, total, V))
+    btv.btv_tree_accept_greedy_batch(G.dev(st), G.dev(np.concatenate(pars).astype(np.int32)),
+                                     G.dev(np.concatenate(toks).astype(np.int32)), G.dev(q_offset), 16, path, n_acc, bonus,
+                                     None, ws)
+    torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == btv.BTV_EDATA
+    assert int(n_acc[1].item()) == 0 and int(n_acc[0].item()) >= 0

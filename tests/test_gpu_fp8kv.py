@@ -48,6 +48,19 @@ def test_elementwise_parity(G, oracle, shape):
         assert np.abs(out - ref).max() <= TOL, (kind, shape, np.abs(out - ref).max())
 
 
+@pytest.mark.parametrize("shape_id", [1, 2])
+@pytest.mark.parametrize("dims", [(16, 700, 32, 8), (100, 1000, 8, 2), (37, 513, 64, 8), (256, 300, 8, 2)])
+def test_every_kernel_shape_elementwise(G, oracle, shape_id, dims):
+    """Both kernel shapes built for the FP8 cache on inputs the heuristic would give to the other one."""
+    M, L, Hq, Hkv = dims
+    parent = synth.tree_parents(M + L + shape_id, M, "deep")
+    q, kv = _inputs(74, M, L, Hq, Hkv, tag=f"forced{dims}")
+    ref = _oracle(oracle, q, kv, parent, L)
+    out = G.run_verify_attn_fp8kv(q["Q"], kv, parent, L, nsplit=3, shape=shape_id)
+    assert np.isfinite(out).all()
+    assert np.abs(out - ref).max() <= TOL, (dims, shape_id, np.abs(out - ref).max())
+
+
 @pytest.mark.parametrize("kind", ["chain", "star", "binary", "caterpillar", "random", "deep"])
 def test_tree_kinds_with_split(G, oracle, kind):
     M, L, Hq, Hkv = 48, 1500, 16, 4
@@ -132,14 +145,6 @@ def test_deterministic_and_mask_tight(G, oracle):
         assert np.array_equal(c[i], a[i]) != sees, i
 
 
-def _sample_pairs(seed, M, Hq, n):
-    r = synth.raw_u64(seed, "pairs8", 2 * n)
-    pairs = np.stack([(r[0::2] % np.uint64(M)).astype(np.int32), (r[1::2] % np.uint64(Hq)).astype(np.int32)], axis=1)
-    pairs[0] = (0, 0)
-    pairs[1] = (M - 1, Hq - 1)
-    return pairs
-
-
 @pytest.mark.parametrize("which", ["c3_16", "c3_64", "c3_256", "c5"])
 def test_full_size_configurations(G, oracle, which):
     w = synth.C5 if which == "c5" else synth.c3(int(which.split("_")[1]))
@@ -149,13 +154,12 @@ def test_full_size_configurations(G, oracle, which):
     q, kv = _inputs(w.seed, N, w.L, w.Hq, w.Hkv, tag=which)
     out = G.run_verify_attn_fp8kv(q["Q"], kv, tree["parent"], w.L)
     assert np.isfinite(out).all()
-    pairs = _sample_pairs(w.seed, N, w.Hq, 24)
-    ref = _oracle(oracle, q, kv, tree["parent"], w.L, pairs=pairs)
-    assert np.abs(out[pairs[:, 0], pairs[:, 1]] - ref).max() <= TOL
+    ref = _oracle(oracle, q, kv, tree["parent"], w.L)                  # every (node, head) row
+    assert np.abs(out - ref).max() <= TOL
     assert np.abs(out).max() <= 448.0 * kv["v_scale"] + 1e-2          # convex combinations of V rows
 
 
-def _paged_case(G, oracle, Ls, Ns, Hq, Hkv, seed, npairs_per_req=None):
+def _paged_case(G, oracle, Ls, Ns, Hq, Hkv, seed):
     import torch
     from paper_2605_29727_amd import binding as btv
     batch = len(Ls)
@@ -190,14 +194,8 @@ def _paged_case(G, oracle, Ls, Ns, Hq, Hkv, seed, npairs_per_req=None):
     assert np.isfinite(out).all()
     for r, (q, parent) in enumerate(reqs):
         o = out[qoff[r]:qoff[r + 1]]
-        if npairs_per_req is None:
-            ref = oracle.tree_attn_fp8kv(q["Qf"], Kp, Vp, ks, vs, parent, Ls[r], block_table=bt[r], page=synth.PAGE)
-            assert np.abs(o - ref).max() <= TOL, r
-        else:
-            pairs = _sample_pairs(seed + r, Ns[r], Hq, npairs_per_req)
-            ref = oracle.tree_attn_fp8kv(q["Qf"], Kp, Vp, ks, vs, parent, Ls[r], block_table=bt[r], page=synth.PAGE,
-                                         pairs=pairs)
-            assert np.abs(o[pairs[:, 0], pairs[:, 1]] - ref).max() <= TOL, r
+        ref = oracle.tree_attn_fp8kv(q["Qf"], Kp, Vp, ks, vs, parent, Ls[r], block_table=bt[r], page=synth.PAGE)
+        assert np.abs(o - ref).max() <= TOL, r
 
 
 def test_paged_ragged(G, oracle):
@@ -207,7 +205,7 @@ def test_paged_ragged(G, oracle):
 
 def test_config4_ragged_paged_full_size(G, oracle):
     Ls, Ns = synth.c4_request_shapes()
-    _paged_case(G, oracle, Ls, Ns, 32, 8, seed=synth.C4.seed, npairs_per_req=8)
+    _paged_case(G, oracle, Ls, Ns, 32, 8, seed=synth.C4.seed)
 
 
 def test_unsupported_arguments_are_refused(G):
