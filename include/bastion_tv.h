@@ -209,6 +209,22 @@ int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int3
                          int M, int L, int Hq, int Hkv, int D, int dtype, float scale,
                          void *O, void *ws, size_t ws_bytes, void *stream);
 
+/* btv_tree_verify_attn for callers that cannot allocate or hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): the same operation, the
+ * same kernels, with the scratch memory (ancestor bitmasks, split-K partial results, flags) in an
+ * array that is part of the library itself, 32 MiB per GPU, held until the process ends.  The
+ * call allocates and frees nothing and synchronises nothing.
+ *   status   [1] uint32 DEVICE, optional: kernels OR their data-error bits into it (non-zero =
+ *            what btv_workspace_status would report as BTV_EDATA); the caller clears it.
+ *   Shapes whose scratch need (btv_tree_verify_attn_workspace) exceeds the array are refused with
+ *   BTV_EWORKSPACE and nothing is launched; every shape with M * Hq <= 4096 rows fits.
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *   streams, two threads) race and give wrong results; calls on one stream are safe.
+ * All other arguments and errors as for btv_tree_verify_attn. */
+int btv_tree_verify_attn_noalloc(const void *Q, const void *K, const void *V, const int32_t *parent,
+                                 int M, int L, int Hq, int Hkv, int D, int dtype, float scale,
+                                 void *O, uint32_t *status, void *stream);
+
 /* Ragged batch over a paged KV cache (BTV_PAGE-token blocks), bf16 only.
  *   Q, O        [total_M, Hq, D]; request r owns rows q_offset[r] .. q_offset[r+1]-1
  *   Kpool,Vpool [num_blocks, BTV_PAGE, Hkv, D]

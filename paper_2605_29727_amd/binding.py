@@ -31,6 +31,7 @@ EXPORTS = [
     "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_tree_accept_lm_head_workspace",
     "btv_tree_accept_greedy_lm_head", "btv_tree_verify_attn_tuned_workspace", "btv_tree_verify_attn_tuned",
+    "btv_tree_verify_attn_noalloc",
 ]
 
 
@@ -60,7 +61,7 @@ def lib() -> C.CDLL:
         for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_build_beam", "btv_tree_ancestor_mask",
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_verify_attn_fp8kv",
                   "btv_tree_verify_attn_paged_fp8kv", "btv_tree_accept_greedy",
-                  "btv_tree_accept_stochastic", "btv_tree_verify_attn_tuned"):
+                  "btv_tree_accept_stochastic", "btv_tree_verify_attn_tuned", "btv_tree_verify_attn_noalloc"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -223,6 +224,15 @@ def btv_tree_verify_attn(Q, K, V, parent, L: int, O, ws, scale: float = 0.0) -> 
     _check(lib().btv_tree_verify_attn(_ptr(Q), _ptr(K), _ptr(V), _ptr(parent), M, L, Hq, Hkv, D, _dtype_code(Q),
                                       C.c_float(scale), _ptr(O), _ptr(ws),
                                       C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_verify_attn_noalloc(Q, K, V, parent, L: int, O, status=None, scale: float = 0.0) -> None:
+    """btv_tree_verify_attn without a workspace: the library's built-in scratch array is used."""
+    M, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    assert K.shape[0] >= L + M and V.shape == K.shape and O.shape == Q.shape
+    _check(lib().btv_tree_verify_attn_noalloc(_ptr(Q), _ptr(K), _ptr(V), _ptr(parent), M, L, Hq, Hkv, D, _dtype_code(Q),
+                                              C.c_float(scale), _ptr(O), _ptr(status), _stream()))
 
 
 def btv_tree_verify_attn_tuned_workspace(M, L, Hq, Hkv, D, kv_fp8: bool, nsplit: int, shape: int) -> int:

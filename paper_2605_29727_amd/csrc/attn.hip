@@ -1169,6 +1169,39 @@ __global__ __launch_bounds__(256) void tv_attn_f32(AttnParams p)
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
+// ---- scratch of the entry point that allocates nothing ---------------------------------------------------------
+// One array per GPU, part of the loaded code object (zero until first used), held until the process ends.  Host code
+// never uses the array's name as an address: the device address is asked for once per device and kept.
+constexpr size_t SCRATCH_BYTES = (size_t)32 << 20;
+constexpr int SCRATCH_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+void *g_scratch_ptr[SCRATCH_MAX_DEVICES];
+std::atomic<bool> g_scratch_known[SCRATCH_MAX_DEVICES];
+
+// Device address of the current device's copy of `scratch` (looked up on the first call per device).
+int scratch_address(void **out)
+{
+    int dev = -1;
+    BTV_HIP(hipGetDevice(&dev));
+    BTV_REQUIRE(dev >= 0 && dev < SCRATCH_MAX_DEVICES, "device index %d outside [0,%d)", dev, SCRATCH_MAX_DEVICES);
+    if (!g_scratch_known[dev].load(std::memory_order_acquire)) {
+        void *ptr = nullptr;
+        BTV_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        BTV_REQUIRE(ptr != nullptr, "no device address for the scratch array");
+        g_scratch_ptr[dev] = ptr;                   // (two racing first calls store the same address)
+        g_scratch_known[dev].store(true, std::memory_order_release);
+    }
+    *out = g_scratch_ptr[dev];
+    return BTV_OK;
+}
+
+// Clears the first `words` 32-bit words at p (a kernel rather than a memset node, so that the call can be captured).
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *p, int words)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
+
 struct Plan { int rw, kw, nt, wr, row_blocks, stages, sps, nsplit; };
 
 // Kernel shape by the number of packed rows per KV head (G*M).  Every wave owns 32 rows.  Measured on MI355X at
@@ -1295,7 +1328,7 @@ void set_scales(AttnParams &p, int D, float scale, float k_scale, float v_scale)
 
 int attn_contiguous(const void *Q, const void *K, const void *V, const int32_t *parent, int M, int L, int Hq, int Hkv,
                     int D, int dtype, int eb, float scale, float k_scale, float v_scale, void *O, void *ws,
-                    size_t ws_bytes, void *stream, int force_split = 0, int force_shape = 0)
+                    size_t ws_bytes, void *stream, int force_split = 0, int force_shape = 0, uint32_t *flag_out = nullptr)
 {
     BTV_REQUIRE(Q && K && V && parent && O, "null pointer");
     BTV_REQUIRE(aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O), "Q, K, V and O must be 16-byte aligned");
@@ -1313,7 +1346,7 @@ int attn_contiguous(const void *Q, const void *K, const void *V, const int32_t *
     p.anc = reinterpret_cast<uint32_t *>(w8 + wl.anc);
     p.ML = reinterpret_cast<float *>(w8 + wl.ml);
     p.Opart = reinterpret_cast<_Float16 *>(w8 + wl.opart);
-    p.flag = reinterpret_cast<uint32_t *>(w8);
+    p.flag = flag_out ? flag_out : reinterpret_cast<uint32_t *>(w8);
     p.M = M; p.L = L; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
     p.total_rows = M * Hq; p.total_M = M;
     p.sps = pl.sps; p.nsplit = pl.nsplit;
@@ -1418,6 +1451,27 @@ int btv_tree_verify_attn(const void *Q, const void *K, const void *V, const int3
 {
     BTV_REQUIRE(dtype == BTV_F32 || dtype == BTV_BF16, "dtype=%d unsupported", dtype);
     return attn_contiguous(Q, K, V, parent, M, L, Hq, Hkv, D, dtype, 2, scale, 1.0f, 1.0f, O, ws, ws_bytes, stream);
+}
+
+int btv_tree_verify_attn_noalloc(const void *Q, const void *K, const void *V, const int32_t *parent, int M, int L, int Hq,
+                                 int Hkv, int D, int dtype, float scale, void *O, uint32_t *status, void *stream)
+{
+    BTV_REQUIRE(dtype == BTV_F32 || dtype == BTV_BF16, "dtype=%d unsupported", dtype);
+    int rc = check_shape(M, L, Hq, Hkv, D);
+    if (rc) return rc;
+    const size_t need = btv_tree_verify_attn_workspace(M, L, Hq, Hkv, D, dtype);
+    if (need > SCRATCH_BYTES)
+        return btv_fail(BTV_EWORKSPACE, "this shape needs %zu bytes of scratch, the built-in array holds %zu: use "
+                        "btv_tree_verify_attn with a workspace", need, SCRATCH_BYTES);
+    void *ws = nullptr;
+    rc = scratch_address(&ws);
+    if (rc) return rc;
+    // the header (data flag, counters) must start at zero whatever an earlier call left behind
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t *>(ws), (int)(BTV_WS_HEADER / 4));
+    BTV_HIP(hipGetLastError());
+    return attn_contiguous(Q, K, V, parent, M, L, Hq, Hkv, D, dtype, 2, scale, 1.0f, 1.0f, O, ws, SCRATCH_BYTES, stream, 0, 0,
+                           status);
 }
 
 size_t btv_tree_verify_attn_fp8kv_workspace(int M, int L, int Hq, int Hkv, int D)
