@@ -21,6 +21,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 namespace {
 
@@ -210,7 +211,6 @@ struct Fill {
     int num_blocks, S;
     uint32_t row_bytes;             // Hkv * D * EB: distance between consecutive keys
     uint32_t lane_off[LPW];         // contiguous: key_off*row_bytes + chunk*16;  paged: (key_off & 15)*row_bytes + chunk*16
-    int key_off[LPW];
 };
 
 template <int D, int WAVES, bool PAGED, int EB = 2>
@@ -230,17 +230,32 @@ __device__ __forceinline__ Fill<D, WAVES, PAGED, EB> make_fill(const void *K, co
         f.base[jj] = reinterpret_cast<const unsigned char *>(isv ? Vb : Kb);
         const int jt = isv ? j - LD::TILEB / 1024 : j;
         const int r = jt * RPI + l / CH, pc = l % CH;
-        f.key_off[jj] = isv ? r : swap_bits_2_3(r);
+        const int key_off = isv ? r : swap_bits_2_3(r);
         const int chunk = pc ^ (isv ? swz_v<D, EB>(r) : swz_k<D, EB>(r));
-        f.lane_off[jj] = (uint32_t)(PAGED ? (f.key_off[jj] & 15) : f.key_off[jj]) * f.row_bytes + chunk * 16;
+        f.lane_off[jj] = (uint32_t)(PAGED ? (key_off & 15) : key_off) * f.row_bytes + chunk * 16;
     }
     return f;
 }
 
+// Source row (relative to the tile's first key) of lane l in fill jj of wave w: recomputed where it is needed (the
+// clamped last tile, paged addressing) rather than kept in registers through the main loop.
+template <int D, int WAVES, int EB>
+__device__ __forceinline__ int fill_key_off(int w, int jj, int l)
+{
+    using LD = Lds<D, EB>;
+    constexpr int CH = LD::CHUNKS, RPI = 1024 / LD::ROWB, LPW = LD::INSTR / WAVES;
+    const int j = w * LPW + jj;
+    const bool isv = j >= LD::TILEB / 1024;
+    const int r = (isv ? j - LD::TILEB / 1024 : j) * RPI + l / CH;
+    return isv ? r : swap_bits_2_3(r);
+}
+
 // Issue this wave's share of the direct-to-LDS loads of tile `st` (keys 32*st ..) into ring slot `slot`.
 // Keys past the end of the sequence re-read the last valid row (finite data; their scores are masked).
-template <int D, int WAVES, bool PAGED, int EB = 2>
-__device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, unsigned char *smem, int slot, int st, int w)
+// JB .. JE - 1: which of the wave's LPW fills (all by default; the pipelined loop issues them one by one, each behind a
+// group of MFMAs, because an issue holds its wave for about a hundred cycles).
+template <int D, int WAVES, bool PAGED, int EB = 2, int JB = 0, int JE = Lds<D, EB>::INSTR / WAVES>
+__device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, unsigned char *smem, int slot, int st, int w, int l)
 {
     using LD = Lds<D, EB>;
     const int kb = st * 32;
@@ -248,10 +263,13 @@ __device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, u
     if (!PAGED) {
         const size_t tile_off = (size_t)kb * f.row_bytes;
 #pragma unroll
-        for (int jj = 0; jj < f.LPW; ++jj) {
+        for (int jj = JB; jj < JE; ++jj) {
             const unsigned char *base = f.base[jj] + tile_off;          // uniform
             uint32_t off = f.lane_off[jj];
-            if (!whole) off = off - (uint32_t)f.key_off[jj] * f.row_bytes + (uint32_t)(min(kb + f.key_off[jj], f.S - 1) - kb) * f.row_bytes;
+            if (!whole) {
+                const int ko = fill_key_off<D, WAVES, EB>(w, jj, l);
+                off = off - (uint32_t)ko * f.row_bytes + (uint32_t)(min(kb + ko, f.S - 1) - kb) * f.row_bytes;
+            }
             __builtin_amdgcn_global_load_lds(base + off, BTV_LDS_PTR(smem + slot * LD::STAGE + (w * f.LPW + jj) * 1024), 16, 0, 0);
         }
     } else {
@@ -265,9 +283,9 @@ __device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, u
         const size_t page0 = (size_t)min(max(bt[i0], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
         const size_t page1 = (size_t)min(max(bt[i1], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
 #pragma unroll
-        for (int jj = 0; jj < f.LPW; ++jj) {
+        for (int jj = JB; jj < JE; ++jj) {
             const unsigned char *b = f.base[jj];
-            int ko = f.key_off[jj];
+            int ko = fill_key_off<D, WAVES, EB>(w, jj, l);
             uint32_t off = f.lane_off[jj];
             if (!whole) {
                 const int kc = min(kb + ko, f.S - 1) - kb;
@@ -378,17 +396,20 @@ __device__ __forceinline__ float tile_max(const f32x16 &s)
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
-// Lazy reference maximum: m_run only moves when the tile maximum exceeds it by more than LAZY (in log2 units),
-// so probabilities stay below 2^LAZY and the O^T / row-sum rescale is skipped on most tiles.  The result is
-// unchanged: numerator and denominator refer to the same m_run.
+// Scores arrive in log2 units: the queries were multiplied by scale * log2(e) once, in the prologue, so a
+// probability is exp2(score - reference) with no multiply per element.
+//
+// Lazy reference maximum: m_run only moves when the tile maximum exceeds it by more than LAZY, so probabilities
+// stay below 2^LAZY and the O^T / row-sum rescale is skipped on most tiles.  The result is unchanged: numerator
+// and denominator refer to the same m_run.
 template <int DT>
-__device__ __forceinline__ void lazy_rescale(float tmax, float sl2, float &m_run, float &l_run, f32x16 (&oacc)[DT])
+__device__ __forceinline__ void lazy_rescale(float tmax, float &m_run, float &l_run, f32x16 (&oacc)[DT])
 {
     constexpr float LAZY = 8.0f;
-    const bool grow = (tmax - m_run) * sl2 > LAZY;
+    const bool grow = tmax - m_run > LAZY;
     if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
         const float mnew = grow ? tmax : m_run;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - mnew) * sl2);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - mnew);
         m_run = mnew;
         l_run *= alpha;
 #pragma unroll
@@ -398,26 +419,42 @@ __device__ __forceinline__ void lazy_rescale(float tmax, float sl2, float &m_run
     }
 }
 
-// P^T = exp2(S^T * sl2 - m_run * sl2) as bf16 B-operands; the row sum adds the rounded values PV uses
+// P^T = exp2(S^T - m_run) as bf16 B-operands; the row sum adds the rounded values PV uses
 // (v_dot2c_f32_bf16 against (1, 1): two probabilities per instruction).
-__device__ __forceinline__ void softmax_tile(const f32x16 &s, float sl2, float m_run, float &l_run, bf16x8 (&pb)[2])
+__device__ __forceinline__ void softmax_tile(const f32x16 &s, float m_run, float &l_run, bf16x8 (&pb)[2])
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    const float mc = m_run * sl2;
     const bf16x2 ones = { (__bf16)1.0f, (__bf16)1.0f };
     float ls[2] = { l_run, 0.f };
 #pragma unroll
     for (int mm = 0; mm < 2; ++mm)
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mm * 8 + e], sl2, -mc));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mm * 8 + e + 1], sl2, -mc));
+            const float p0 = __builtin_amdgcn_exp2f(s[mm * 8 + e] - m_run);
+            const float p1 = __builtin_amdgcn_exp2f(s[mm * 8 + e + 1] - m_run);
             const bf16x2 pp = { (__bf16)p0, (__bf16)p1 };
             pb[mm][e] = pp[0];
             pb[mm][e + 1] = pp[1];
             ls[mm] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ls[mm], false);
         }
     l_run = ls[0] + ls[1];
+}
+
+// One half (keys 8 mm .. 8 mm + 7 of the lane's 16) of a tile whose scores already are relative to the reference:
+// P = exp2(x) as a B operand, its rounded values added to `sum`.
+__device__ __forceinline__ void exp_half(const f32x16 &x, int mm, bf16x8 &pbm, float &sum)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = { (__bf16)1.0f, (__bf16)1.0f };
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(x[mm * 8 + e]);
+        const float p1 = __builtin_amdgcn_exp2f(x[mm * 8 + e + 1]);
+        const bf16x2 pp = { (__bf16)p0, (__bf16)p1 };
+        pbm[e] = pp[0];
+        pbm[e + 1] = pp[1];
+        sum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum, false);
+    }
 }
 
 // O^T += V^T . P^T
@@ -446,7 +483,7 @@ __device__ __forceinline__ void mask_tile(f32x16 &s, uint32_t vis, int h)
 // One whole tile, step after step (no overlap between the steps): used for the tiles that need the mask and
 // by the workgroup shapes whose wave pairs alternate over the tiles.
 template <int D>
-__device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l, float sl2,
+__device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l,
                                         const uint32_t (&anc_i)[BTV_ANC_WORDS],
                                         const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
 {
@@ -460,9 +497,9 @@ __device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l, f
     lds_read_vt<D, 1>(va_addr, va);
     f32x16 s = qk_tile<DS>(ka, qreg);
     if (kb + 32 > Lr) mask_tile(s, vis_word(anc_i, kb, Lr), l >> 5);
-    lazy_rescale<DT>(tile_max(s), sl2, m_run, l_run, oacc);
+    lazy_rescale<DT>(tile_max(s), m_run, l_run, oacc);
     bf16x8 pb[2];
-    softmax_tile(s, sl2, m_run, l_run, pb);
+    softmax_tile(s, m_run, l_run, pb);
     lds_wait_vt<DT>(va);
     pv_tile<DT>(va, pb, oacc);
 }
@@ -542,7 +579,7 @@ __device__ __forceinline__ void lds_wait_vt8(u32x2 (&v8)[4][2])
 
 // One whole tile of an FP8 cache: the same steps as do_tile with half the operand reads and the conversions.
 template <int D>
-__device__ __forceinline__ void do_tile8(uint32_t stage, int kb, int Lr, int l, float sl2,
+__device__ __forceinline__ void do_tile8(uint32_t stage, int kb, int Lr, int l,
                                          const uint32_t (&anc_i)[BTV_ANC_WORDS],
                                          const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
 {
@@ -564,9 +601,9 @@ __device__ __forceinline__ void do_tile8(uint32_t stage, int kb, int Lr, int l, 
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp8x8_to_bf16x8(k8[k][2], k8[k][3]), qreg[2 * k + 1], s, 0, 0, 0);
     }
     if (kb + 32 > Lr) mask_tile(s, vis_word(anc_i, kb, Lr), l >> 5);
-    lazy_rescale<DT>(tile_max(s), sl2, m_run, l_run, oacc);
+    lazy_rescale<DT>(tile_max(s), m_run, l_run, oacc);
     bf16x8 pb[2];
-    softmax_tile(s, sl2, m_run, l_run, pb);
+    softmax_tile(s, m_run, l_run, pb);
     lds_wait_vt8(v8);
 #pragma unroll
     for (int mm = 0; mm < 2; ++mm)
@@ -574,6 +611,93 @@ __device__ __forceinline__ void do_tile8(uint32_t stage, int kb, int Lr, int l, 
         for (int dt = 0; dt < DT; ++dt)
             oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp8x8_to_bf16x8(v8[dt][mm][0], v8[dt][mm][1]), pb[mm],
                                                                oacc[dt], 0, 0, 0);
+}
+
+// ---- half-tile operand buffers of the software-pipelined loop ----------------------------------------------
+// The loop keeps 16 registers of K operands and 16 of V^T operands (D = 128): half a tile each, refilled right
+// after the MFMAs that consumed the previous contents were issued.  Addresses are loop-invariant registers (one
+// per contraction step / channel block, the XOR of the swizzle already applied); the ring slot is an immediate
+// offset, which reaches SPB slots from one base (the offset field has 16 bits).
+template <int OFF> __device__ __forceinline__ void ds_read_k_imm(uint32_t a, u32x4 &r)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "immediate offset range");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(a), "n"(OFF));
+}
+template <int OFF> __device__ __forceinline__ void ds_read_vt_imm(uint32_t a, bf16x4 &r)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "immediate offset range");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(a), "n"(OFF));
+}
+
+// K operands of contraction steps HALF * DS/2 .. + DS/2 - 1 of the tile in slot SLOT (relative to the base in ak).
+template <int D, int SLOT, int HALF> __device__ __forceinline__ void read_k_half(const uint32_t (&ak)[D / 16], u32x4 (&kh)[D / 32])
+{
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) ds_read_k_imm<SLOT * Lds<D>::STAGE>(ak[HALF * (D / 32) + s], kh[s]);
+}
+// V^T operands of keys 16 MM .. 16 MM + 15 (the PV MFMAs with index MM), all channel blocks.
+template <int D, int SLOT, int MM> __device__ __forceinline__ void read_v_half(const uint32_t (&av)[D / 32], bf16x4 (&vh)[D / 32][2])
+{
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+        ds_read_vt_imm<SLOT * Lds<D>::STAGE + (16 * MM) * Lds<D>::ROWB>(av[dt], vh[dt][0]);
+        ds_read_vt_imm<SLOT * Lds<D>::STAGE + (16 * MM + 4) * Lds<D>::ROWB>(av[dt], vh[dt][1]);
+    }
+}
+// the same reads with the stage address in a register (prologue and epilogue of the loop)
+template <int D, int HALF> __device__ __forceinline__ void read_k_half_at(uint32_t a, u32x4 (&kh)[D / 32])
+{
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        const uint32_t addr = a ^ (uint32_t)((HALF * (D / 32) + s) << 5);
+        asm volatile("ds_read_b128 %0, %1" : "=v"(kh[s]) : "v"(addr));
+    }
+}
+template <int D, int MM> __device__ __forceinline__ void read_v_half_at(uint32_t a, bf16x4 (&vh)[D / 32][2])
+{
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+        const uint32_t addr = a ^ (uint32_t)(dt << 6);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[dt][i]) : "v"(addr), "n"((16 * MM + 4 * i) * Lds<D>::ROWB));
+    }
+}
+// Wait until at most YOUNGER LDS reads issued after these are still in flight (the counter completes in order).
+template <int KH, int YOUNGER> __device__ __forceinline__ void wait_k_half(u32x4 (&kh)[KH])
+{
+    static_assert((KH == 2 || KH == 4) && YOUNGER >= 0 && YOUNGER < 16, "D in {64,128}");
+    if constexpr (KH == 4) asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(kh[0]), "+v"(kh[1]), "+v"(kh[2]), "+v"(kh[3]) : "n"(YOUNGER));
+    else asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(kh[0]), "+v"(kh[1]) : "n"(YOUNGER));
+}
+template <int DT, int YOUNGER> __device__ __forceinline__ void wait_v_half(bf16x4 (&vh)[DT][2])
+{
+    static_assert((DT == 2 || DT == 4) && YOUNGER >= 0 && YOUNGER < 16, "D in {64,128}");
+    if constexpr (DT == 4)
+        asm volatile("s_waitcnt lgkmcnt(%8)"
+                     : "+v"(vh[0][0]), "+v"(vh[0][1]), "+v"(vh[1][0]), "+v"(vh[1][1]), "+v"(vh[2][0]), "+v"(vh[2][1]),
+                       "+v"(vh[3][0]), "+v"(vh[3][1])
+                     : "n"(YOUNGER));
+    else
+        asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(vh[0][0]), "+v"(vh[0][1]), "+v"(vh[1][0]), "+v"(vh[1][1]) : "n"(YOUNGER));
+}
+// half of S^T = K . Q^T: contraction steps HALF * DS/2 .. on top of c
+template <int DS, int HALF>
+__device__ __forceinline__ f32x16 qk_half(const u32x4 (&kh)[DS / 2], const bf16x8 (&qreg)[DS], f32x16 c)
+{
+#pragma unroll
+    for (int k = 0; k < DS / 2; ++k)
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kh[k]), qreg[HALF * (DS / 2) + k], c, 0, 0, 0);
+    return c;
+}
+// half of O^T += V^T . P^T: the keys of one P operand
+template <int DT> __device__ __forceinline__ void pv_half(const bf16x4 (&vh)[DT][2], const bf16x8 &pbm, f32x16 (&oacc)[DT])
+{
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        const bf16x8 a = __builtin_shufflevector(vh[dt][0], vh[dt][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pbm, oacc[dt], 0, 0, 0);
+    }
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()
@@ -608,7 +732,9 @@ struct WgLds {
     static constexpr int QBYTES = RW * QTILE;
     static constexpr int PRE_B = PREFILL * STAGE;
     static constexpr int QOFF = RING - QBYTES > PRE_B ? RING - QBYTES : PRE_B;
-    static constexpr int PAROFF = QOFF - PRE_B >= 1024 ? PRE_B : QOFF + QBYTES;
+    // parent[]: in a stage the prologue leaves free, else behind the query tiles; behind the ring for the pipelined
+    // shape, which reads it after the plain prefix tiles
+    static constexpr int PAROFF = KW == 1 ? (RING > QOFF + QBYTES ? RING : QOFF + QBYTES) : (QOFF - PRE_B >= 1024 ? PRE_B : QOFF + QBYTES);
     static constexpr int USED = (PAROFF + 1024 > QOFF + QBYTES ? PAROFF + 1024 : QOFF + QBYTES) > RING
                                     ? (PAROFF + 1024 > QOFF + QBYTES ? PAROFF + 1024 : QOFF + QBYTES) : RING;
     // two key-waves exchange half a row each (+ m, l, bound); more key-waves: donors to wave 0
@@ -627,6 +753,20 @@ template <int MAXN> __device__ __forceinline__ void wait_vm_ops(int n)
     } else {
         wait_vmcnt<0>();
     }
+}
+
+// A lane's query row: row r of a KV head's packed rows is node r / G, query head r % G of the group.  Worked out where
+// it is needed (mask construction, final store) rather than held in registers through the main loop.  Padding rows
+// (r >= rows_g) recompute row 0 and are never written.
+struct LaneRow { bool valid; int node; long long orow; };
+__device__ __forceinline__ LaneRow lane_row(int r, int rows_g, int G, int Hq, int g, int q0)
+{
+    LaneRow x;
+    x.valid = r < rows_g;
+    const int rr = x.valid ? r : 0;
+    x.node = rr / G;
+    x.orow = (long long)(q0 + x.node) * Hq + g * G + (rr % G);       // row of Q/O as [total_M*Hq, D]
+    return x;
 }
 
 // Workgroup = RW row-waves x KW key-waves; wave (rw, kw) owns query rows [32 rw, 32 rw + 32) of the block and,
@@ -686,12 +826,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         st1 = min(st1, max((Lr + node_hi + 1 + 31) / 32, st0 + 1));
     }
 
-    // ---- this lane's query row ------------------------------------------------------------------------------
-    const int r = by * WR + rw * 32 + c;
-    const bool rvalid = r < rows_g;
-    const int rr = rvalid ? r : 0;              // padding rows recompute row 0 and are never written
-    const int node = rr / p.G;
-    const long long orow = (long long)(rq_.q0 + node) * p.Hq + g * p.G + (rr % p.G);   // row of Q/O as [total_M*Hq, D]
     using WL = WgLds<D, RW, KW, NT, EB>;
 
     // ---- prologue loads, oldest first: parent[] (one entry per thread), this wave's share of its row-wave's query
@@ -735,7 +869,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
     for (int k = 0; k < PREFILL; ++k)
         if (issued < st1) {
-            if (issuer) issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu);
+            if (issuer) issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu, l);
             ++issued; ++islot;
         }
     if (islot >= NT) islot -= NT;
@@ -752,15 +886,6 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(par_lds + 4u * (uint32_t)i) : "memory");
         return v;
     };
-    if (tree_wg) {
-        bool bad = false;
-        for (int i = tid; i < Mr; i += WAVES * 64) {
-            const int pa = par_at(i);
-            bad = bad || pa < -1 || pa >= i;
-        }
-        if (bad) atomicOr(p.flag, 1u);
-    }
-
     // Operand s holds the 8 channels that contraction step s takes from this lane's half: 16 s + 8 h .. + 7 for
     // bf16 K, 32 (s/2) + 16 h + 8 (s%2) .. + 7 for FP8 K (the order of its 16-byte operand reads).
     u32x4 qv[DS];
@@ -776,18 +901,30 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     }
 
     // ---- ancestor bitmask of this lane's node, only in workgroups whose keys reach the tree rows ----------
+    // parent[] is checked (every entry, once per workgroup) and walked from its copy in LDS.
     uint32_t anc_i[BTV_ANC_WORDS];
 #pragma unroll
     for (int k = 0; k < BTV_ANC_WORDS; ++k) anc_i[k] = 0u;
-    if (tree_wg) {
-        for (int a = node; a >= 0;) {
-#pragma unroll
-            for (int k = 0; k < BTV_ANC_WORDS; ++k)
-                if ((a >> 5) == k) anc_i[k] |= 1u << (a & 31);
-            const int pa = par_at(a);
-            a = (pa < -1 || pa >= a) ? -1 : pa;      // an invalid entry ends the walk (flagged above)
-        }
+    // Built where a shape needs it: shapes whose waves alternate over the tiles stage parent[] inside the ring and
+    // must read it before the main loop; the pipelined shape keeps it behind the ring and builds the masks after
+    // the plain prefix tiles, so that they are not live through that loop.
+#define BTV_BUILD_MASK()                                                                                              \
+    if (tree_wg) {                                                                                                    \
+        bool bad_ = false;                                                                                            \
+        for (int i_ = tid; i_ < Mr; i_ += WAVES * 64) {                                                               \
+            const int pa_ = par_at(i_);                                                                               \
+            bad_ = bad_ || pa_ < -1 || pa_ >= i_;                                                                     \
+        }                                                                                                             \
+        if (bad_) atomicOr(p.flag, 1u);                                                                               \
+        const LaneRow lr_ = lane_row(by * WR + rw * 32 + c, rows_g, p.G, p.Hq, g, rq_.q0);                            \
+        for (int a_ = lr_.node; a_ >= 0;) {                                                                           \
+            _Pragma("unroll") for (int k_ = 0; k_ < BTV_ANC_WORDS; ++k_)                                              \
+                if ((a_ >> 5) == k_) anc_i[k_] |= 1u << (a_ & 31);                                                    \
+            const int pa_ = par_at(a_);                                                                               \
+            a_ = (pa_ < -1 || pa_ >= a_) ? -1 : pa_; /* an invalid entry ends the walk (flagged above) */             \
+        }                                                                                                             \
     }
+    if constexpr (KW > 1) { BTV_BUILD_MASK() }
 
     float m_run = NEG_BIG, l_run = 0.f;
     f32x16 oacc[DT];
@@ -796,74 +933,189 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
 
-    // the first round's tiles
-    if constexpr (KW == 1) wait_tiles<LPW, NT - 2>(issuer ? issued - st0 - 1 : 0);
-    else if (issued - st0 - KW == AHEAD) wait_vmcnt<AHEAD * LPW>();
-    else wait_vmcnt<0>();
     bf16x8 qreg[DS];
     if constexpr (DS == 8)
         asm volatile("s_waitcnt lgkmcnt(0)"
                      : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]), "+v"(qv[4]), "+v"(qv[5]), "+v"(qv[6]), "+v"(qv[7]));
     else
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]));
-#pragma unroll
-    for (int s = 0; s < DS; ++s) qreg[s] = __builtin_bit_cast(bf16x8, qv[s]);
     const uint32_t ring = (uint32_t)(uintptr_t)BTV_LDS_PTR(smem);
-    if constexpr (KW == 1 && EB == 2) {
-        // ---- main loop, one tile per round, software-pipelined --------------------------------------------
-        // Round t: wait until tiles <= t+1 have landed, barrier (which also tells that every wave is done with
-        // tile t-1, whose ring slot the next fill overwrites), issue one more tile.  Inside a round a wave
-        // overlaps the score MFMAs of tile t+1 with the softmax arithmetic of tile t, and the row maximum of
-        // tile t+1 with the PV MFMAs of tile t.
-        auto sync_round = [&](int t) {
-            wait_tiles<LPW, NT - 3>(issuer ? issued - t - 2 : 0);     // tiles t+2 .. issued-1 may still be in flight
-            __builtin_amdgcn_s_barrier();
-#pragma unroll
-            for (int k = 0; k < 2; ++k)                  // two per round until the ring is full, then one
-                if (issued < st1 && issued - t < NT) {
-                    if (issuer) issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu);
-                    ++issued;
-                    if (++islot == NT) islot = 0;
-                }
-        };
-        const uint32_t koff = lane_k_off<D>(l), voff = LD::TILEB + lane_v_off<D>(l);
-        uint32_t cur = ring;                                     // LDS address of tile t's stage
-        u32x4 ka[DS];
-        bf16x4 va[DT][2][2];
-        bf16x8 pb[2];
-        sync_round(st0);
-        lds_read_k<D>(cur + koff, ka);
-        lds_wait_k<DS, 0>(ka);
-        f32x16 s = qk_tile<DS>(ka, qreg);
-        if (st0 * 32 + 32 > Lr) mask_tile(s, vis_word(anc_i, st0 * 32, Lr), h);
-        float tmax = tile_max(s);
-        for (int t = st0; t < st1 - 1; ++t) {
-            lazy_rescale<DT>(tmax, p.scale_log2, m_run, l_run, oacc);
-            const uint32_t nxt = (cur + LD::STAGE == ring + NT * LD::STAGE) ? ring : cur + LD::STAGE;
-            lds_read_k<D>(nxt + koff, ka);
-            lds_read_vt<D, 0>(cur + voff, va);
-            lds_wait_k<DS, DT * 2>(ka);          // the counter completes in order: K has landed when 2*DT reads remain
-            lds_read_vt<D, 1>(cur + voff, va);
-            f32x16 s2 = qk_tile<DS>(ka, qreg);
-            softmax_tile(s, p.scale_log2, m_run, l_run, pb);
-            lds_wait_vt<DT>(va);
-            pv_tile<DT>(va, pb, oacc);
-            tmax = tile_max(s2);
-            if (t * 32 + 64 > Lr) {              // tile t+1 touches tree rows (or the end of the sequence)
-                mask_tile(s2, vis_word(anc_i, t * 32 + 32, Lr), h);
-                tmax = tile_max(s2);
-            }
-            s = s2;
-            cur = nxt;
-            sync_round(t + 1);
+    auto issue_one = [&]() {                             // the next tile of this split, if there is one
+        if (issued < st1) {
+            if (issuer) issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu, l);
+            ++issued;
+            if (++islot == NT) islot = 0;
         }
-        // last tile: nothing to overlap with
-        lazy_rescale<DT>(tmax, p.scale_log2, m_run, l_run, oacc);
-        lds_read_vt<D, 0>(cur + voff, va);
-        lds_read_vt<D, 1>(cur + voff, va);
-        softmax_tile(s, p.scale_log2, m_run, l_run, pb);
-        lds_wait_vt<DT>(va);
-        pv_tile<DT>(va, pb, oacc);
+    };
+    // one half of the wave's fills of the next tile (LPW = 2 in the pipelined shape); the caller advances the counters
+    auto issue_part = [&](auto part) {
+        constexpr int P = decltype(part)::value;
+        constexpr int MID = (LPW + 1) / 2, JB = P == 0 ? 0 : MID, JE = P == 0 ? MID : LPW;
+        if constexpr (JB < JE)
+            if (issuer) issue_tile<D, IW, PAGED, EB, JB, JE>(fill, smem, islot, issued, wu, l);
+    };
+    if constexpr (KW == 1) {
+        // Every wave has its queries in registers and parent[] is consumed: the ring owns all stages from here on.
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int k = PREFILL; k < NT - 1; ++k) issue_one();
+    }
+    // The queries take the softmax scale and the change of base once (rounded to bf16 again, to nearest even: a
+    // relative 2^-9 per element, as if the caller's projection had produced the scaled queries): scores then
+    // are in log2 units and a probability costs no multiply.
+    {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const float qs = p.scale_log2;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            u32x4 r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t wd = qv[s][j];
+                const bf16x2 pr = { (__bf16)(__uint_as_float(wd << 16) * qs), (__bf16)(__uint_as_float(wd & 0xFFFF0000u) * qs) };
+                r[j] = __builtin_bit_cast(uint32_t, pr);
+            }
+            qreg[s] = __builtin_bit_cast(bf16x8, r);
+        }
+    }
+    if constexpr (KW == 1 && EB == 2) {
+        // ---- main loop, one tile per round, software-pipelined over the plain prefix tiles ------------------------
+        // Local tile j = tile st0 + j lives in ring slot j % NT.  Tiles whose 32 keys all are prefix rows ("plain":
+        // no mask) run through a pipeline in which iteration i issues
+        //     the PV MFMAs of tile i-1 among the exponentials of tile i,  then the score MFMAs of tile i+1.
+        // Scores come out of the matrix cores relative to the running reference (the accumulator starts at minus
+        // the reference), so P = exp2(x) with no other arithmetic per element.  The reference is the maximum of
+        // the split's first tile and moves only when a tile's row sum shows that some x exceeded 16 (checked on
+        // the sum: no maximum per tile); then the tile is redone against its own maximum and everything rescaled.
+        // K and V^T operands live in two half-tile buffers, each refilled right after the MFMAs that read it.
+        static_assert(NT == 8, "the pipelined loop is written for a ring of 8 stages");
+        constexpr int KH = DS / 2;                               // LDS reads per K half (a V^T half takes 2 * DT)
+        constexpr float GROW = 1048576.0f;                       // 2^20: a half-row sum of 16 terms above it means some x > 16
+        int Tf = min(st1, Lr / 32) - st0;                        // plain tiles at the start of this split
+        if (Tf < 3) Tf = 0;
+        int j0 = 0;                                              // first local tile the step-by-step loop below takes
+        if (Tf > 0) {
+            const uint32_t kbase = ring + lane_k_off<D>(l), vbase = ring + LD::TILEB + lane_v_off<D>(l);
+            auto slot_off = [](int j) { return (uint32_t)((j & (NT - 1)) * LD::STAGE); };      // wave-uniform
+            u32x4 kh[KH];
+            bf16x4 vh[DT][2];
+            f32x16 x;
+            bf16x8 pa[2], pc[2];
+            float negm;                                          // minus the reference: what the score accumulator starts from
+            // the tile's probabilities against a new reference: its own maximum joins the old one; sums, accumulator follow
+            auto regrow = [&](bf16x8 (&pn)[2], float &ts) {
+                const float dlt = fmaxf(tile_max(x), 0.f), alpha = __builtin_amdgcn_exp2f(-dlt);
+                negm -= dlt;
+                l_run *= alpha;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[v] -= dlt;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+                ts = 0.f;
+                exp_half(x, 0, pn[0], ts);
+                exp_half(x, 1, pn[1], ts);
+            };
+            // tiles 0 .. 2 have landed when at most the later ones are in flight
+            wait_tiles<LPW, NT - 4>(issued - st0 - 3);
+            __builtin_amdgcn_s_barrier();
+            // ---- prologue: scores of tile 0 set the reference; its probabilities; scores of tile 1 ----
+            {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[v] = 0.f;
+                read_k_half_at<D, 0>(kbase, kh); wait_k_half<KH, 0>(kh); x = qk_half<DS, 0>(kh, qreg, x);
+                read_k_half_at<D, 1>(kbase, kh); wait_k_half<KH, 0>(kh); x = qk_half<DS, 1>(kh, qreg, x);
+                read_k_half_at<D, 0>(kbase + slot_off(1), kh);
+                negm = -tile_max(x);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[v] += negm;
+                exp_half(x, 0, pa[0], l_run);                    // x <= 0 here: no growth check
+                exp_half(x, 1, pa[1], l_run);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[v] = negm;
+                wait_k_half<KH, 0>(kh); x = qk_half<DS, 0>(kh, qreg, x);
+                read_k_half_at<D, 1>(kbase + slot_off(1), kh); wait_k_half<KH, 0>(kh); x = qk_half<DS, 1>(kh, qreg, x);
+                read_v_half_at<D, 0>(vbase, vh);                 // queue: V(0) first half, K(2) low half
+                read_k_half_at<D, 0>(kbase + slot_off(2), kh);
+            }
+            // ---- iteration i (1 <= i <= Tf - 2): x holds the scores of tile i, pprev the probabilities of tile i-1, pcur
+            // receives those of tile i ----
+            // On entry the LDS queue holds [V(i-1) first half, K(i+1) low half].
+            auto iter = [&](bf16x8 (&pprev)[2], bf16x8 (&pcur)[2], int i) {
+                // tiles <= i+2 are read in this iteration; the barrier also tells that every wave is done with
+                // iteration i-1, i.e. with tile i-2, whose slot the next fill takes
+                wait_tiles<LPW, 3>(issued - st0 - i - 3);
+                __builtin_amdgcn_s_barrier();
+                const bool fill_now = issued < st1;              // tile i+6 goes into the slot tile i-2 left
+                const uint32_t k1 = kbase + slot_off(i + 1), k2 = kbase + slot_off(i + 2);
+                const uint32_t v0 = vbase + slot_off(i - 1), v1 = vbase + slot_off(i);
+                float ts = 0.f;
+                wait_v_half<DT, KH>(vh);                          // V(i-1) first half
+                pv_half<DT>(vh, pprev[0], oacc);
+                if (fill_now) issue_part(std::integral_constant<int, 0>{});      // behind four MFMAs: its issue stall is covered
+                read_v_half_at<D, 1>(v0, vh);                     // V(i-1) second half  queue: K(i+1)lo, V(i-1)b
+                exp_half(x, 0, pcur[0], ts);
+                wait_v_half<DT, 0>(vh);                           // V(i-1) second half (and K(i+1) low)
+                pv_half<DT>(vh, pprev[1], oacc);
+                if (fill_now) issue_part(std::integral_constant<int, 1>{});
+                read_v_half_at<D, 0>(v1, vh);                     // V(i) first half     queue: V(i)a
+                exp_half(x, 1, pcur[1], ts);
+                if (__builtin_amdgcn_ballot_w64(!(ts <= GROW)) != 0ull) regrow(pcur, ts);     // rare
+                l_run += ts;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[v] = negm;
+                wait_k_half<KH, 2 * DT>(kh);                      // K(i+1) low (landed above; binds the registers)
+                x = qk_half<DS, 0>(kh, qreg, x);
+                read_k_half_at<D, 1>(k1, kh);                     // K(i+1) high         queue: V(i)a, K(i+1)hi
+                wait_k_half<KH, 0>(kh);                           // K(i+1) high (and V(i) first half)
+                x = qk_half<DS, 1>(kh, qreg, x);
+                read_k_half_at<D, 0>(k2, kh);                     // K(i+2) low          queue: K(i+2)lo (V(i)a has landed)
+                if (fill_now) { ++issued; if (++islot == NT) islot = 0; }
+            };
+            // ---- epilogue: tile e = Tf - 1 has its scores, tile e-1 its probabilities (pp); nothing left to overlap ----
+            auto drain = [&](bf16x8 (&pp)[2], bf16x8 (&pn)[2]) {
+                const int e = Tf - 1;
+                const uint32_t ve1 = vbase + slot_off(e - 1), ve = vbase + slot_off(e);
+                wait_k_half<KH, 0>(kh);                          // (the low half of tile e+1's K: not used)
+                wait_v_half<DT, 0>(vh);                          // V(e-1) first half
+                pv_half<DT>(vh, pp[0], oacc);
+                read_v_half_at<D, 1>(ve1, vh);
+                float ts = 0.f;
+                exp_half(x, 0, pn[0], ts);
+                exp_half(x, 1, pn[1], ts);
+                wait_v_half<DT, 0>(vh);
+                pv_half<DT>(vh, pp[1], oacc);
+                read_v_half_at<D, 0>(ve, vh);
+                if (__builtin_amdgcn_ballot_w64(!(ts <= GROW)) != 0ull) regrow(pn, ts);
+                l_run += ts;
+                wait_v_half<DT, 0>(vh);
+                pv_half<DT>(vh, pn[0], oacc);
+                read_v_half_at<D, 1>(ve, vh);
+                wait_v_half<DT, 0>(vh);
+                pv_half<DT>(vh, pn[1], oacc);
+                m_run = -negm;
+            };
+            // One iteration per trip, the new probabilities copied into place at its end (8 moves): with the roles of
+            // two register sets alternating over an unrolled pair the allocator shuffles tuples and spills.
+            for (int i = 1; i <= Tf - 2; ++i) {
+                iter(pa, pc, i);
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm) pa[mm] = pc[mm];
+            }
+            drain(pa, pc);
+            j0 = Tf;
+        }
+        // ---- the remaining tiles (those that touch tree rows, or all of a short split), step by step ----
+        BTV_BUILD_MASK()
+        for (int j = j0; j < st1 - st0; ++j) {
+            wait_tiles<LPW, NT - 1>(issued - st0 - j - 1);       // tile j has landed
+            __builtin_amdgcn_s_barrier();                        // ... for every wave, and all are done with tile j-1
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+                if (issued - st0 - j < NT) issue_one();
+            do_tile<D>(ring + (j & 7) * LD::STAGE, (st0 + j) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc);
+        }
     } else if constexpr (KW > 1) {
         // ---- main loop: one barrier per round of KW tiles, wave kw takes tile number kw of the round ------
         // At the top of the round starting at tile st, tiles st+KW .. issued-1 may still be in flight.  The
@@ -877,20 +1129,23 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
             for (int k = 0; k < KW; ++k)
                 if (issued < st1) {
-                    issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu);
+                    issue_tile<D, IW, PAGED, EB>(fill, smem, islot, issued, wu, l);
                     ++issued;
                     if (++islot == NT) islot = 0;
                 }
             if (st + kw < st1) {
                 if constexpr (EB == 2)
-                    do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+                    do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc);
                 else
-                    do_tile8<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, p.scale_log2, anc_i, qreg, m_run, l_run, oacc);
+                    do_tile8<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc);
             }
             cslot += KW;
             if (cslot >= NT) cslot -= NT;
         }
     }
+    const LaneRow lrow = lane_row(by * WR + rw * 32 + c, rows_g, p.G, p.Hq, g, rq_.q0);
+    const bool rvalid = lrow.valid;
+    const long long orow = lrow.orow;
     // both halves of a wave hold partial row sums of the same queries
     l_run += __shfl_xor(l_run, 32);
 
@@ -927,8 +1182,8 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
         const float *in = mg + (kw ^ 1) * SLOT;
         const float m1 = in[(DTK * 16) * 64 + l], l1 = in[(DTK * 16 + 1) * 64 + l], x1 = in[(DTK * 16 + 2) * 64 + l];
         const float mn = fmaxf(m_run, m1);
-        const float a0 = __builtin_amdgcn_exp2f((m_run - mn) * p.scale_log2);
-        const float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
+        const float a0 = __builtin_amdgcn_exp2f(m_run - mn);
+        const float a1 = __builtin_amdgcn_exp2f(m1 - mn);
         // both waves must arrive at the same l and bound: sums of the same two products, order fixed by kw
         const float la = kw == 0 ? l_run * a0 : l1 * a1, lb = kw == 0 ? l1 * a1 : l_run * a0;
         const float xa = kw == 0 ? amax * a0 : x1 * a1, xb = kw == 0 ? x1 * a1 : amax * a0;
@@ -965,8 +1220,8 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 const float *d = mg + donor * SLOT;
                 const float m1 = d[(DT * 16) * 64 + l], l1 = d[(DT * 16 + 1) * 64 + l];
                 const float mn = fmaxf(m_run, m1);
-                const float a0 = __builtin_amdgcn_exp2f((m_run - mn) * p.scale_log2);
-                const float a1 = __builtin_amdgcn_exp2f((m1 - mn) * p.scale_log2);
+                const float a0 = __builtin_amdgcn_exp2f(m_run - mn);
+                const float a1 = __builtin_amdgcn_exp2f(m1 - mn);
                 m_run = mn;
                 l_run = l_run * a0 + l1 * a1;
 #pragma unroll
@@ -1065,7 +1320,7 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
 #pragma unroll
             for (int off = 16; off >= 1; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 32));
         }
-        const float w = s_mine < nsplit_r ? __builtin_amdgcn_exp2f((ml.x - mmax) * p.scale_log2) : 0.f;
+        const float w = s_mine < nsplit_r ? __builtin_amdgcn_exp2f(ml.x - mmax) : 0.f;
         den += w * ml.y;
         const float wz = w * ml.z;                             // weight times the partial's magnitude
 #pragma unroll
@@ -1217,8 +1472,8 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2, int force_s
     // Ragged batches take the small workgroup whatever the largest tree: 64-row blocks pad the smaller trees less,
     // and two such workgroups share a CU, so one's prologue and store overlap the other's main loop.
     if (rows_g <= 128 || batch > 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
-    else if (rows_g >= 1024 && L >= 16384 && eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }     // 70B shape at 32k: on par with (4,2,8)
-    else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
+    else if (eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }      // the software-pipelined shape
+    else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }                  // FP8 cache: pairs of waves alternating over the tiles
     if (force_shape == 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
     if (force_shape == 2) { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
     if (force_shape == 3 && eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
