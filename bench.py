@@ -32,16 +32,22 @@ RING_BYTES = 640 << 20        # > 2x the 256 MB Infinity Cache
 
 
 def measured_traffic(L, N):
-    """HBM bytes per tree_verify_attn call from the committed profiler summary (counter runs cannot be made from
-    inside this script); None when there is no summary for this workload."""
-    path = os.path.join(ROOT, "profiles", f"tree_verify_attn_L{L}_N{N}_hbm_traffic.txt")
+    """HBM bytes per tree_verify_attn call, read from the committed profiler summary of this workload (counter runs
+    cannot be made from inside this script, so this figure is NOT measured by the run that prints it).  Returns
+    (bytes, where it came from); (None, None) when there is no summary for this workload."""
+    rel = os.path.join("profiles", f"tree_verify_attn_L{L}_N{N}_hbm_traffic.txt")
+    val, commit = None, "unknown"
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_call:"):
-                return int(line.split(":")[1])
+                val = int(line.split(":")[1])
+            if line.startswith("kernel_source_commit:"):
+                commit = line.split(":")[1].strip()
     except OSError:
         pass
-    return None
+    if val is None:
+        return None, None
+    return val, f"{rel} (rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE runs of the kernels at commit {commit}; not measured by this run)"
 
 
 def algorithmic_bytes(L, N, Hq, Hkv, D, e=2):
@@ -55,7 +61,7 @@ def algorithmic_flops(L, N, Hq, D, depth_sum):
 class Path:
     """Device buffers of one workload and the three calls of a step."""
 
-    def __init__(self, torch, btv, synth, oracle_tree, L, N, Hq, Hkv, D, B, V, marg_sigma, seed, ring_sets):
+    def __init__(self, torch, btv, synth, L, N, Hq, Hkv, D, B, V, marg_sigma, seed, ring_sets):
         self.torch, self.btv = torch, btv
         self.L, self.N, self.Hq, self.Hkv, self.D, self.B, self.V = L, N, Hq, Hkv, D, B, V
         dev = "cuda"
@@ -142,6 +148,16 @@ def time_loop(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(synth, L, N, Hq, Hkv, D, B, V, marg, seed):
     """The CPU oracle, as it stands, on one full step of the same workload (seeded inputs)."""
     import numpy as np
@@ -160,6 +176,7 @@ def cpu_baseline(synth, L, N, Hq, Hkv, D, B, V, marg, seed):
     t4 = time.perf_counter()
     hist = np.bincount(np.asarray(tree["depth"]), minlength=B + 1)[1:].tolist()
     return {"value": round((t3 - t0) * 1e6, 1), "unit": "us/step", "cores": threads, "kind": "oracle",
+            "cpu_model": cpu_model(), "cores_online": os.cpu_count(),
             "sample": f"1 full step: tree_build {t1 - t0:.2f}s (1 thread) + attention of all {N * Hq} (node, head) rows "
                       f"{t2 - t1:.2f}s ({threads} OpenMP threads) + greedy accept {t3 - t2:.2f}s (1 thread)",
             "attn_us": round((t2 - t1) * 1e6, 1), "attn_us_one_thread": round((t4 - t3) * 1e6, 1),
@@ -239,6 +256,32 @@ def stream_ceiling(torch, btv, nbytes=2 << 30, reps=10):
     return round(nbytes / (ms * 1e-3) / 1e9, 1)
 
 
+def cold_read(torch, btv, nbytes, reps):
+    """One launch of the plain streaming-read kernel over exactly `nbytes` (a call's algorithmic bytes), cold: the
+    launches cycle through distinct buffers that together exceed twice the Infinity Cache.  Returns microseconds per
+    launch from a back-to-back loop and the median of launches bracketed one by one."""
+    nbytes = (nbytes + 15) // 16 * 16
+    ring = max(4, -(-RING_BYTES // nbytes))
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(i & 255) for i in range(ring)]
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    state = {"i": 0}
+
+    def call():
+        state["i"] += 1
+        btv.btv_stream_read(bufs[state["i"] % ring], sink)
+    ms = time_loop(torch, call, reps, max(reps // 10, 3))
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a_, b_ in pairs:
+        a_.record()
+        call()
+        b_.record()
+    torch.cuda.synchronize()
+    each = sorted(a_.elapsed_time(b_) * 1e3 for a_, b_ in pairs)
+    del bufs
+    torch.cuda.empty_cache()
+    return round(ms * 1e3, 3), round(each[len(each) // 2], 3)
+
+
 def mfma_ceiling(torch, btv, iters=20000, reps=5):
     """What a register-resident bf16 matrix-core loop sustains on this machine (TFLOP/s): 2 workgroups of 8 waves
     per CU (two waves per SIMD), four independent accumulators per wave."""
@@ -257,7 +300,7 @@ def fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, steps, warmup, sizes=(1
     g.manual_seed(1234)
     for n in sizes:
         ws_ = synth.c3(n, sharp=True)
-        tree = Path(torch, btv, synth, None, 64, n, Hq, Hkv, D, B, V, ws_.marg_sigma, ws_.seed, 1)     # for parent[]
+        tree = Path(torch, btv, synth, 64, n, Hq, Hkv, D, B, V, ws_.marg_sigma, ws_.seed, 1)     # for parent[]
         set_bytes = 2 * (L + n) * Hkv * D
         sets = max(16, -(-RING_BYTES // set_bytes))
         scale = 4.5 / 448.0
@@ -295,7 +338,7 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     def one(name, L, N, Hq, Hkv, D, sigma, seed):
         set_bytes = 2 * (L + N) * Hkv * D * 2
         ring = max(2, min(96, -(-RING_BYTES // set_bytes)))
-        pc = Path(torch, btv, synth, None, L, N, Hq, Hkv, D, 16, V, sigma, seed, ring)
+        pc = Path(torch, btv, synth, L, N, Hq, Hkv, D, 16, V, sigma, seed, ring)
         ms = time_loop(torch, pc.attn, steps, warmup)
         ab, fl = algorithmic_bytes(L, N, Hq, Hkv, D), algorithmic_flops(L, N, Hq, D, pc.depth_sum)
         t_hbm, t_mfma = ab / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -422,7 +465,7 @@ def main():
     w = synth.c3(N, sharp=True)
     set_bytes = 2 * (L + N) * Hkv * D * 2
     ring_sets = max(16, -(-RING_BYTES // set_bytes))
-    path = Path(torch, btv, synth, None, L, N, Hq, Hkv, D, B, V, w.marg_sigma, w.seed, ring_sets)
+    path = Path(torch, btv, synth, L, N, Hq, Hkv, D, B, V, w.marg_sigma, w.seed, ring_sets)
 
     depth_hist = torch.bincount(path.depth.to(torch.int64), minlength=B + 1)[1:].tolist()
     if args.only_attn:
@@ -523,15 +566,16 @@ def main():
                 "cost_curve": "T_draft (0.1 target steps) + T_aux (0.1 ms) + App. E roofline of an 8B-shaped verifier at "
                               "this context (datasheet peaks)"}
     adaptive = optional("adaptive build", adaptive_bench)
-    one = Path(torch, btv, synth, None, L, N, Hq, Hkv, D, B, V, w.marg_sigma, w.seed, 1)
+    one = Path(torch, btv, synth, L, N, Hq, Hkv, D, B, V, w.marg_sigma, w.seed, 1)
     attn_warm_ms = time_loop(torch, one.attn, args.steps, args.warmup)
     del one
 
     ab = algorithmic_bytes(L, N, Hq, Hkv, D)
     fl = algorithmic_flops(L, N, Hq, D, path.depth_sum)
     gbps = ab / (attn_ms * 1e-3) / 1e9
+    traffic, traffic_src = measured_traffic(L, N)
     roofline = {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(L, N),
+                "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_src,
                 "kernel": "tree_verify_attn (tv_attn_bf16, which also forms the ancestor mask, + tv_combine_bf16)",
                 "algorithmic_bytes": ab, "us_per_launch": round(attn_ms * 1e3, 3),
                 "us_in_step": round(attn_ms_in_step * 1e3, 3), "us_warm_cache": round(attn_warm_ms * 1e3, 3),
@@ -545,7 +589,7 @@ def main():
         torch.cuda.empty_cache()
         for n in (16, 32, 64, 128, 256):
             ws_ = synth.c3(n, sharp=True)
-            pn = Path(torch, btv, synth, None, L, n, Hq, Hkv, D, B, V, ws_.marg_sigma, ws_.seed, ring_sets)
+            pn = Path(torch, btv, synth, L, n, Hq, Hkv, D, B, V, ws_.marg_sigma, ws_.seed, ring_sets)
             ms = time_loop(torch, pn.attn, args.steps, args.warmup)
             abn, fln = algorithmic_bytes(L, n, Hq, Hkv, D), algorithmic_flops(L, n, Hq, D, pn.depth_sum)
             t_hbm, t_mfma = abn / (HBM_PEAK_GBPS * 1e9), fln / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -556,6 +600,10 @@ def main():
                           "binding": "hbm" if t_hbm >= t_mfma else "mfma"})
             del pn
             torch.cuda.empty_cache()
+            cr = optional("cold read", lambda: cold_read(torch, btv, abn, max(args.steps // 2, 50)), fallback=())
+            if cr:
+                curve[-1]["cold_read_us"] = cr[0]
+                curve[-1]["frac_of_cold_read"] = round(cr[0] / (ms * 1e3), 4)
 
     # Static and online calibration (Sec. 5.2) of the attention layer's roofline prediction against the curve above
     calib = None
@@ -585,6 +633,13 @@ def main():
             lmh["frac_of_measured_stream"] = round(lmh["GBps"] / ceiling, 4)
         for c in curve:
             c["frac_of_measured_stream"] = round(c["GBps"] / ceiling, 4)
+    cold = optional("cold read of the algorithmic bytes", lambda: cold_read(torch, btv, ab, max(args.steps, 100)), fallback=())
+    if cold:
+        # the same bytes fetched once by a plain read kernel in one launch: what the memory system allows for a call
+        # of this size (launch and ramp-up included), the yardstick beside the 8 TB/s datasheet peak
+        roofline["cold_read_us"], roofline["cold_read_us_bracketed_median"] = cold
+        roofline["cold_read_GBps"] = round(ab / (cold[0] * 1e-6) / 1e9, 1)
+        roofline["frac_of_cold_read"] = round(cold[0] / (attn_ms * 1e3), 4)
     fp8kv = optional("FP8 KV cache", lambda: fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, args.steps, args.warmup))
     configs = None if args.no_configs else optional("other configurations",
                                                     lambda: other_configs(torch, btv, synth, V, args.steps, args.warmup))

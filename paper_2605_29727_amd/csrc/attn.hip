@@ -1472,8 +1472,11 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2, int force_s
     // Ragged batches take the small workgroup whatever the largest tree: 64-row blocks pad the smaller trees less,
     // and two such workgroups share a CU, so one's prologue and store overlap the other's main loop.
     if (rows_g <= 128 || batch > 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
-    else if (eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }      // the software-pipelined shape
-    else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }                  // FP8 cache: pairs of waves alternating over the tiles
+    // 1024 packed rows or more (256 nodes at 4 query heads per KV head, 128 at 8): the software-pipelined 256-row
+    // shape, measured 5 % ahead at the 70B shape with a 32k prefix and level at 256 nodes of the 8B shape; below,
+    // pairs of waves alternating over the tiles are 3-8 % ahead.  The FP8 cache has only the latter.
+    else if (eb == 2 && rows_g >= 1024) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
+    else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
     if (force_shape == 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
     if (force_shape == 2) { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
     if (force_shape == 3 && eb == 2) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
