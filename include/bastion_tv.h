@@ -5,7 +5,9 @@
  * Conventions shared by every entry point
  *   - Unless a parameter says HOST, every pointer is a DEVICE pointer owned by the caller.
  *     The library allocates no caller-visible memory; scratch space is the caller's `ws`
- *     (size from the matching *_workspace() query, 256-byte aligned).
+ *     (size from the matching *_workspace() query, 256-byte aligned).  A workspace must be
+ *     zero-filled once, before its first use; every call leaves it ready for the next one (the
+ *     data flag aside, see btv_workspace_status).  A workspace serves one call at a time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work; outputs are valid once the caller has synchronised the stream.
  *   - Return value: BTV_OK, or a negative btv_status.  All argument checks run on the host
@@ -284,6 +286,8 @@ int btv_tree_verify_attn_paged_fp8kv(const void *Q, const void *K8pool, const vo
  *   path [M] accepted node ids in root-to-leaf order (first *n_acc valid), n_acc [1],
  *   bonus [1] = t[row of the last accepted node] (the token that seeds the next cycle),
  *   argmax_out [M+1] optional.
+ *   One launch: the workgroup that finishes the argmax last does the walk; the workspace holds
+ *   one 8-byte word per logit row and a counter, all back at zero when the call has run.
  *
  * stochastic (temperature 1): token-level rejection sampling of the target distribution
  * p = softmax(logits row) against the draft marginal q of the child's depth, children tried in

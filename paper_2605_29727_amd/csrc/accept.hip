@@ -14,7 +14,9 @@ namespace {
 
 constexpr int ACHUNK = 8192;     // vocabulary elements per argmax workgroup
 
-struct Best { float v; int i; };
+struct alignas(8) Best { float v; int i; };
+
+constexpr int ACCEPT_COUNTER_OFFSET = 64;   // workspace header: word 0 = data flag, word 16 = workgroups counted in
 
 __device__ __forceinline__ void best_take(Best &b, float v, int i)
 {   // larger value wins; equal values: lower index wins; NaN never wins
@@ -31,17 +33,33 @@ __device__ __forceinline__ Best best_wave(Best b)
     return b;
 }
 
-// grid = (chunks, rows).  part[(row*chunks + chunk)] = best of the chunk.
+// Best element of vocabulary chunk `chunk` of row `row` as seen by this thread (256 threads per workgroup).  Whole,
+// 16-byte aligned chunks take four (bf16) or eight (fp32) 16-byte loads per thread, all in flight before the first
+// is looked at.
 template <bool BF16>
-__global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, Best *part)
+__device__ __forceinline__ Best chunk_scan(const void *logits, int V, int row, int chunk, int tid)
 {
-    __shared__ Best wb[4];
-    const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y;
     const int v0 = chunk * ACHUNK, v1 = min(v0 + ACHUNK, V);
     Best b = { -INFINITY, INT_MAX };
     if (BF16) {
         const uint16_t *x = static_cast<const uint16_t *>(logits) + (size_t)row * V;
         if ((((size_t)row * V * 2) & 15) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0) {
+            if (v1 - v0 == ACHUNK) {
+                uint4 q[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) q[j] = *reinterpret_cast<const uint4 *>(x + v0 + tid * 8 + j * 2048);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
+                    const int v = v0 + tid * 8 + j * 2048;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        best_take(b, __uint_as_float(wds[e] << 16), v + 2 * e);
+                        best_take(b, __uint_as_float(wds[e] & 0xFFFF0000u), v + 2 * e + 1);
+                    }
+                }
+                return b;
+            }
             for (int v = v0 + tid * 8; v < v1; v += 256 * 8) {
                 if (v + 8 <= v1) {
                     uint4 q = *reinterpret_cast<const uint4 *>(x + v);
@@ -61,6 +79,20 @@ __global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, 
     } else {
         const float *x = static_cast<const float *>(logits) + (size_t)row * V;
         if ((((size_t)row * V * 4) & 15) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0) {
+            if (v1 - v0 == ACHUNK) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float4 q[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) q[j] = *reinterpret_cast<const float4 *>(x + v0 + tid * 4 + (h * 4 + j) * 1024);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int v = v0 + tid * 4 + (h * 4 + j) * 1024;
+                        best_take(b, q[j].x, v); best_take(b, q[j].y, v + 1); best_take(b, q[j].z, v + 2); best_take(b, q[j].w, v + 3);
+                    }
+                }
+                return b;
+            }
             for (int v = v0 + tid * 4; v < v1; v += 256 * 4) {
                 if (v + 4 <= v1) {
                     float4 q = *reinterpret_cast<const float4 *>(x + v);
@@ -73,7 +105,16 @@ __global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, 
             for (int v = v0 + tid; v < v1; v += 256) best_take(b, x[v], v);
         }
     }
-    b = best_wave(b);
+    return b;
+}
+
+// grid = (chunks, rows).  part[(row*chunks + chunk)] = best of the chunk.
+template <bool BF16>
+__global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, Best *part)
+{
+    __shared__ Best wb[4];
+    const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y;
+    Best b = best_wave(chunk_scan<BF16>(logits, V, row, chunk, tid));
     if ((tid & 63) == 0) wb[tid >> 6] = b;
     __syncthreads();
     if (tid == 0) {
@@ -81,6 +122,146 @@ __global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, 
         best_take(r, wb[1].v, wb[1].i); best_take(r, wb[2].v, wb[2].i); best_take(r, wb[3].v, wb[3].i);
         part[(size_t)row * gridDim.x + chunk] = r;
     }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Greedy acceptance of one request in one launch.  A wavefront scans one unit of WCHUNK vocabulary elements of one
+// row; the 16 waves of a workgroup fold the units that belong to the same row and publish one 64-bit key per row
+// with an atomic maximum in memory; every workgroup then counts itself in, and the one that counts in last reads
+// the row keys and walks the tree on its first wavefront.  Keys and counter are left at zero for the next call.
+// The L2 caches of the 8 XCDs are not coherent with each other, and a device-scope fence writes back and
+// invalidates a whole cache; the only words other workgroups must see are the row keys and the counter, all moved
+// by relaxed device-scope atomics (executed at the memory side), the counter only after the key updates have been
+// acknowledged (vmcnt 0).  Atomics on one address cost about 11 ns each one after the other (measured), hence big
+// workgroups: 130 instead of 2080 of them at 65 rows.
+// Key = value bits made monotonic << 32 | ~index: the larger value wins, then the lower index; a unit that saw only
+// NaN publishes nothing and a row that stays at zero has argmax 0, as in the two-launch path.
+// The walk keeps node c in lane c % 64, register row c / 64: `ok` = the node's token is the target's argmax at its
+// parent; a step is a ballot over "child of the current node and ok" per row, lowest node index first.
+// ------------------------------------------------------------------------------------------------
+constexpr int WALK_ROWS = (BTV_MAX_NODES + 63) / 64;
+constexpr int WCHUNK = 4096;     // vocabulary elements per wavefront unit of the one-launch kernel
+constexpr int OL_WAVES = 16;     // wavefronts per workgroup of the one-launch kernel
+
+__device__ __forceinline__ unsigned long long best_key(Best b)
+{
+    if (b.i == INT_MAX) return 0ull;
+    const uint32_t u = __float_as_uint(b.v + 0.0f);              // -0 counts as +0
+    const uint32_t mono = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)mono << 32) | (uint32_t)~(uint32_t)b.i;
+}
+
+// Best element of elements v0 .. v1-1 of a row as seen by this lane.  A whole, 16-byte aligned unit is fetched with
+// eight 16-byte loads per lane at a time, all in flight before the first is looked at.
+template <bool BF16>
+__device__ __forceinline__ Best wave_scan(const void *logits, int V, int row, int v0, int v1, int lane)
+{
+    Best b = { -INFINITY, INT_MAX };
+    constexpr int ES = BF16 ? 2 : 4, PER = 16 / ES;              // element size, elements per 16-byte load
+    const bool aligned = (((size_t)row * V * ES) & 15) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
+    if (aligned && v1 - v0 == WCHUNK) {
+        const uint4 *x = reinterpret_cast<const uint4 *>(static_cast<const unsigned char *>(logits) +
+                                                         ((size_t)row * V + v0) * ES);
+#pragma unroll
+        for (int h = 0; h < WCHUNK / (64 * PER * 8); ++h) {
+            uint4 q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = x[(h * 8 + j) * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int v = v0 + ((h * 8 + j) * 64 + lane) * PER;
+                const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (BF16) {
+                        best_take(b, __uint_as_float(wds[e] << 16), v + 2 * e);
+                        best_take(b, __uint_as_float(wds[e] & 0xFFFF0000u), v + 2 * e + 1);
+                    } else {
+                        best_take(b, __uint_as_float(wds[e]), v + e);
+                    }
+                }
+            }
+        }
+        return b;
+    }
+    if (BF16) {
+        const uint16_t *x = static_cast<const uint16_t *>(logits) + (size_t)row * V;
+        for (int v = v0 + lane; v < v1; v += 64) best_take(b, __uint_as_float((uint32_t)x[v] << 16), v);
+    } else {
+        const float *x = static_cast<const float *>(logits) + (size_t)row * V;
+        for (int v = v0 + lane; v < v1; v += 64) best_take(b, x[v], v);
+    }
+    return b;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(OL_WAVES * 64) void accept_greedy_one_launch(
+    const void *logits, int V, int chunks, unsigned long long *row_key, uint32_t *arrived, const int32_t *parent,
+    const int32_t *token, int M, int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out)
+{
+    __shared__ Best wbest[OL_WAVES];
+    __shared__ int wrow[OL_WAVES];
+    __shared__ int t[BTV_MAX_NODES + 1];
+    __shared__ uint32_t is_last;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, units = (M + 1) * chunks;
+    for (int u0 = blockIdx.x * OL_WAVES; u0 < units; u0 += gridDim.x * OL_WAVES) {   // (uniform over the workgroup)
+        const int u = u0 + wave;
+        Best b = { -INFINITY, INT_MAX };
+        int row = -1;
+        if (u < units) {
+            row = u / chunks;
+            const int chunk = u - row * chunks;
+            b = best_wave(wave_scan<BF16>(logits, V, row, chunk * WCHUNK, min(chunk * WCHUNK + WCHUNK, V), lane));
+        }
+        if (lane == 0) { wbest[wave] = b; wrow[wave] = row; }
+        __syncthreads();
+        if (tid < OL_WAVES && wrow[tid] >= 0 && (tid == 0 || wrow[tid - 1] != wrow[tid])) {
+            // first unit of a row within this workgroup: fold the row's other units, publish
+            Best r = wbest[tid];
+            for (int j = tid + 1; j < OL_WAVES && wrow[j] == wrow[tid]; ++j) best_take(r, wbest[j].v, wbest[j].i);
+            const unsigned long long key = best_key(r);
+            if (key != 0ull) __hip_atomic_fetch_max(row_key + wrow[tid], key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this workgroup's key updates have been performed
+        if (lane == 0)
+            is_last = __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1u;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    if (tid == 0) __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid <= M) {
+        const unsigned long long key = __hip_atomic_exchange(row_key + tid, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t[tid] = key == 0ull ? 0 : (int)~(uint32_t)key;
+        if (argmax_out) argmax_out[tid] = t[tid];
+    }
+    __syncthreads();
+    if (tid >= 64) return;
+    int par[WALK_ROWS];
+    bool ok[WALK_ROWS];
+#pragma unroll
+    for (int r = 0; r < WALK_ROWS; ++r) {
+        const int c = r * 64 + tid;
+        par[r] = c < M ? parent[c] : INT_MIN;
+        const int tk = c < M ? token[c] : -1;
+        ok[r] = c < M && par[r] >= -1 && par[r] < M && tk == t[par[r] + 1];
+    }
+    int cur = -1, n = 0;
+    while (n < M) {
+        int nx = -1;
+#pragma unroll
+        for (int r = WALK_ROWS - 1; r >= 0; --r) {
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(ok[r] && par[r] == cur);
+            if (m != 0ull) nx = r * 64 + __builtin_ctzll(m);
+        }
+        if (nx < 0) break;
+        if (tid == 0) path[n] = nx;
+        cur = nx;
+        ++n;
+    }
+    if (tid == 0) { *n_acc = n; *bonus = t[cur + 1]; }
 }
 
 // One workgroup per request: finish the argmax of every row, then walk the tree.  With q_offset (a batch),
@@ -739,8 +920,7 @@ size_t btv_tree_accept_workspace(int M, int V, int stochastic)
 {
     if (M < 1 || M > BTV_MAX_NODES || V < 1) return 0;
     if (stochastic) return BTV_WS_HEADER + 3 * btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
-    int chunks = (V + ACHUNK - 1) / ACHUNK;
-    return BTV_WS_HEADER + btv_align_up((size_t)(M + 1) * chunks * sizeof(Best), BTV_WS_ALIGN);
+    return BTV_WS_HEADER + btv_align_up((size_t)(M + 1) * sizeof(unsigned long long), BTV_WS_ALIGN);
 }
 
 int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
@@ -752,13 +932,16 @@ int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent,
     rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_workspace(M, V, 0));
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    Best *part = reinterpret_cast<Best *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
-    int chunks = (V + ACHUNK - 1) / ACHUNK;
-    if (dtype == BTV_BF16) hipLaunchKernelGGL(argmax_chunks<true>, dim3(chunks, M + 1), dim3(256), 0, st, logits, V, part);
-    else hipLaunchKernelGGL(argmax_chunks<false>, dim3(chunks, M + 1), dim3(256), 0, st, logits, V, part);
-    BTV_HIP(hipGetLastError());
-    hipLaunchKernelGGL(greedy_walk, dim3(1), dim3(256), 0, st, part, chunks, parent, token, M, path, n_acc, bonus,
-                       argmax_out, static_cast<const int32_t *>(nullptr), 0, static_cast<uint32_t *>(nullptr));
+    unsigned long long *row_key = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
+    uint32_t *arrived = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) + ACCEPT_COUNTER_OFFSET);
+    const int chunks = (V + WCHUNK - 1) / WCHUNK;
+    const int wgs = (int)std::min<long long>(((long long)(M + 1) * chunks + OL_WAVES - 1) / OL_WAVES, 512);
+    if (dtype == BTV_BF16)
+        hipLaunchKernelGGL(accept_greedy_one_launch<true>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, row_key,
+                           arrived, parent, token, M, path, n_acc, bonus, argmax_out);
+    else
+        hipLaunchKernelGGL(accept_greedy_one_launch<false>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, row_key,
+                           arrived, parent, token, M, path, n_acc, bonus, argmax_out);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

@@ -20,6 +20,7 @@ def test_byte_and_flop_formulas():
     L, N, Hq, Hkv, D = 8192, 64, 32, 8, 128
     assert bench.algorithmic_bytes(L, N, Hq, Hkv, D) == 4096 * (L + N) + 16384 * N + 4 * N
     assert bench.algorithmic_flops(L, N, Hq, D, depth_sum=100) == 4 * Hq * D * (N * L + 100)
-    t = bench.measured_traffic(8192, 64)                         # the committed counter summary is found and parsed
+    t, src = bench.measured_traffic(8192, 64)                    # the committed counter summary is found and parsed
     assert t is not None and t >= bench.algorithmic_bytes(L, N, Hq, Hkv, D)
-    assert bench.measured_traffic(1, 1) is None
+    assert "profiles/" in src and "not measured by this run" in src
+    assert bench.measured_traffic(1, 1) == (None, None)
