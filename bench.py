@@ -329,6 +329,33 @@ def fp8_kv_bench(torch, btv, synth, L, Hq, Hkv, D, B, V, steps, warmup, sizes=(1
             "sizes": out}
 
 
+def ragged_batch(torch, btv, synth):
+    """Device buffers of the ragged batch of 8 requests over a paged KV cache (16-token blocks, random block table)
+    and the attention call over them."""
+    Ls, Ns = synth.c4_request_shapes()
+    Hq, Hkv, D = 32, 8, 128
+    bt_np, num_blocks = synth.paged_layout(5, [l + n for l, n in zip(Ls, Ns)])
+    Kp = torch.randn((num_blocks, 16, Hkv, D), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    Vp = torch.randn((num_blocks, 16, Hkv, D), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    bt = torch.from_numpy(bt_np).clamp(min=0).cuda()
+    qo = [0]
+    for n in Ns:
+        qo.append(qo[-1] + n)
+    q_offset = torch.tensor(qo, dtype=torch.int32, device="cuda")
+    prefix = torch.tensor(Ls, dtype=torch.int32, device="cuda")
+    total = qo[-1]
+    Q = torch.randn((total, Hq, D), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    O = torch.empty_like(Q)
+    par = torch.cat([torch.from_numpy(synth.tree_parents(50 + r, n, "random")) for r, n in enumerate(Ns)]).to(torch.int32).cuda()
+    ws = btv.alloc_workspace(btv.btv_tree_verify_attn_paged_workspace(len(Ls), max(Ns), max(Ls), Hq, Hkv, D))
+    attn = lambda: btv.btv_tree_verify_attn_paged(Q, Kp, Vp, bt, q_offset, prefix, par, max(Ns), max(Ls), O, ws)
+    return {"Ls": Ls, "Ns": Ns, "Hq": Hq, "Hkv": Hkv, "D": D, "num_blocks": num_blocks, "Q": Q, "Kp": Kp, "Vp": Vp, "bt": bt,
+            "q_offset": q_offset, "prefix": prefix, "par": par, "O": O, "ws": ws, "total": total, "attn": attn}
+
+
+C5_SHAPE = dict(L=32768, N=128, Hq=64, Hkv=8, D=128, sigma=3.0, seed=6)       # 70B-shaped layer, 32k prefix
+
+
 def other_configs(torch, btv, synth, V, steps, warmup):
     """The remaining configurations of the parity suite, timed (reported, not the headline): the 8B shape at a
     2k prefix, the ragged paged batch of 8 requests, and the 70B shape at a 32k prefix with stochastic acceptance."""
@@ -355,7 +382,8 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     pc = one("llama3_8b_L8192_N64_flat_marginals", 8192, 64, 32, 8, 128, 1.0, 4)
     del pc
     torch.cuda.empty_cache()
-    pc = one("llama_70b_L32768_N128", 32768, 128, 64, 8, 128, 3.0, 6)
+    c5 = C5_SHAPE
+    pc = one("llama_70b_L32768_N128", c5["L"], c5["N"], c5["Hq"], c5["Hkv"], c5["D"], c5["sigma"], c5["seed"])
     # stochastic acceptance at this shape: fp32 logits, one uniform per row
     N = 128
     lg = torch.randn((N + 1, V), dtype=torch.float32, device="cuda").mul_(3.0)
@@ -368,24 +396,11 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     torch.cuda.empty_cache()
 
     # ragged batch of 8 requests over a paged KV cache (16-token blocks, random block table)
-    Ls, Ns = synth.c4_request_shapes()
-    Hq, Hkv, D = 32, 8, 128
-    bt_np, num_blocks = synth.paged_layout(5, [l + n for l, n in zip(Ls, Ns)])
-    Kp = torch.randn((num_blocks, 16, Hkv, D), dtype=torch.float32, device="cuda").to(torch.bfloat16)
-    Vp = torch.randn((num_blocks, 16, Hkv, D), dtype=torch.float32, device="cuda").to(torch.bfloat16)
-    bt = torch.from_numpy(bt_np).clamp(min=0).cuda()
-    qo = [0]
-    for n in Ns:
-        qo.append(qo[-1] + n)
-    q_offset = torch.tensor(qo, dtype=torch.int32, device="cuda")
-    prefix = torch.tensor(Ls, dtype=torch.int32, device="cuda")
-    total = qo[-1]
-    Q = torch.randn((total, Hq, D), dtype=torch.float32, device="cuda").to(torch.bfloat16)
-    O = torch.empty_like(Q)
-    par = torch.cat([torch.from_numpy(synth.tree_parents(50 + r, n, "random")) for r, n in enumerate(Ns)]).to(torch.int32).cuda()
-    ws = btv.alloc_workspace(btv.btv_tree_verify_attn_paged_workspace(len(Ls), max(Ns), max(Ls), Hq, Hkv, D))
-    ms = time_loop(torch, lambda: btv.btv_tree_verify_attn_paged(Q, Kp, Vp, bt, q_offset, prefix, par, max(Ns), max(Ls), O, ws),
-                   steps, warmup)
+    rb = ragged_batch(torch, btv, synth)
+    Ls, Ns, Hq, Hkv, D, num_blocks = rb["Ls"], rb["Ns"], rb["Hq"], rb["Hkv"], rb["D"], rb["num_blocks"]
+    Q, Kp, Vp, bt, q_offset, prefix, par, O, ws, total = (rb[k] for k in ("Q", "Kp", "Vp", "bt", "q_offset", "prefix", "par",
+                                                                          "O", "ws", "total"))
+    ms = time_loop(torch, rb["attn"], steps, warmup)
     # the steps before and after it for the same batch, one launch each
     nb = len(Ls)
     mg = torch.softmax(torch.randn((nb, 16, V), dtype=torch.float32, device="cuda") * 3.0, dim=-1)
@@ -432,6 +447,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the N in {16..256} latency curve")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-attn", action="store_true", help="time only tree_verify_attn (for profiler runs)")
+    ap.add_argument("--only-config", choices=("c4", "c5"), default=None,
+                    help="time only the attention of the ragged paged batch (c4) or of the 70B shape at a 32k prefix (c5), "
+                         "for profiler runs")
     ap.add_argument("--only-lm-head", action="store_true",
                     help="time only btv_tree_accept_greedy_lm_head (for profiler runs)")
     ap.add_argument("--only-fp8-kv", action="store_true", help="time only btv_tree_verify_attn_fp8kv (for profiler runs)")
@@ -461,6 +479,20 @@ def main():
         print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "copies": args.steps}))
         return
 
+    if args.only_config == "c4":
+        rb = ragged_batch(torch, btv, synth)
+        ms = time_loop(torch, rb["attn"], args.steps, args.warmup)
+        print(json.dumps({"only_attn_us": ms * 1e3, "config": "ragged batch of 8 requests, paged KV", "sum_L": sum(rb["Ls"]),
+                          "sum_N": sum(rb["Ns"])}))
+        return
+    if args.only_config == "c5":
+        c5 = C5_SHAPE
+        set_bytes = 2 * (c5["L"] + c5["N"]) * c5["Hkv"] * c5["D"] * 2
+        pc = Path(torch, btv, synth, c5["L"], c5["N"], c5["Hq"], c5["Hkv"], c5["D"], 16, 128256, c5["sigma"], c5["seed"],
+                  max(2, -(-RING_BYTES // set_bytes)))
+        ms = time_loop(torch, pc.attn, args.steps, args.warmup)
+        print(json.dumps({"only_attn_us": ms * 1e3, "config": "70B-shaped layer, L=32768, N=128"}))
+        return
     Hq, Hkv, D, B, V, L, N = 32, 8, 128, 16, 128256, args.L, args.N
     w = synth.c3(N, sharp=True)
     set_bytes = 2 * (L + N) * Hkv * D * 2

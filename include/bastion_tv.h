@@ -91,6 +91,17 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
                             int32_t *n_out, float *ahat, double *s_best, void *ws, size_t ws_bytes,
                             void *stream);
 
+/* tree_build with the choice of expansion made by the caller (tests, tuning): the results are
+ * those of btv_tree_build (cost == NULL) or btv_tree_build_adaptive (cost != NULL, with L_AR and
+ * s_best as there), whichever expansion runs.
+ *   algo  0 = the library chooses from the depth the tree can reach, 1 = the one-wavefront
+ *         best-first expansion (Algorithm 1's frontier loop), 2 = the level-synchronous one.
+ * Workspace: btv_tree_build_workspace(B, V, N). */
+int btv_tree_build_tuned(const float *marginals, int B, int V, int N, const double *cost,
+                         double L_AR, int algo, int32_t *parent, int32_t *token,
+                         int32_t *depth_out, float *rho, int32_t *n_out, float *ahat,
+                         double *s_best, void *ws, size_t ws_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Batches of requests in one launch (the ragged batch of the paged attention entry point, for the
  * steps before and after it).  Requests are independent; request r owns the output rows

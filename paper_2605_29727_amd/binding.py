@@ -31,7 +31,7 @@ EXPORTS = [
     "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_tree_accept_lm_head_workspace",
     "btv_tree_accept_greedy_lm_head", "btv_tree_verify_attn_tuned_workspace", "btv_tree_verify_attn_tuned",
-    "btv_tree_verify_attn_noalloc",
+    "btv_tree_verify_attn_noalloc", "btv_tree_build_tuned",
 ]
 
 
@@ -61,7 +61,8 @@ def lib() -> C.CDLL:
         for n in ("btv_version", "btv_workspace_status", "btv_tree_build", "btv_tree_build_beam", "btv_tree_ancestor_mask",
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_verify_attn_fp8kv",
                   "btv_tree_verify_attn_paged_fp8kv", "btv_tree_accept_greedy",
-                  "btv_tree_accept_stochastic", "btv_tree_verify_attn_tuned", "btv_tree_verify_attn_noalloc"):
+                  "btv_tree_accept_stochastic", "btv_tree_verify_attn_tuned", "btv_tree_verify_attn_noalloc",
+                  "btv_tree_build_tuned"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -124,6 +125,18 @@ def btv_tree_build_adaptive(marginals, N_max: int, cost, L_AR: float, parent, to
     _check(lib().btv_tree_build_adaptive(_ptr(marginals), B, V, N_max, _ptr(cost), C.c_double(L_AR), _ptr(parent),
                                          _ptr(token), _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(s_best),
                                          _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
+
+
+def btv_tree_build_tuned(marginals, N: int, algo: int, parent, token, depth, rho, n_out, ahat, ws, cost=None, L_AR: float = 0.0,
+                         s_best=None) -> None:
+    """btv_tree_build (cost None) or btv_tree_build_adaptive with the expansion chosen by the caller:
+    algo 0 = the library's choice, 1 = one-wavefront best-first loop, 2 = level-synchronous."""
+    B, V = marginals.shape
+    assert marginals.dtype == torch.float32 and marginals.is_contiguous()
+    assert cost is None or (cost.dtype == torch.float64 and cost.numel() >= N)
+    _check(lib().btv_tree_build_tuned(_ptr(marginals), B, V, N, _ptr(cost), C.c_double(L_AR), int(algo), _ptr(parent),
+                                      _ptr(token), _ptr(depth), _ptr(rho), _ptr(n_out), _ptr(ahat), _ptr(s_best),
+                                      _ptr(ws), C.c_size_t(ws.numel() if ws is not None else 0), _stream()))
 
 
 def btv_stream_read(src, sink) -> None:

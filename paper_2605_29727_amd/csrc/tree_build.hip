@@ -128,8 +128,23 @@ struct RankLds {                            // bound and ranking of one position
 struct ExpandLds {                          // the expansion
     float q[MAXB * BTV_MAX_NODES + 64];     // q[k*KP + r]: probability of rank r at position k (+ padding: q[..][r+1] is
                                             // fetched, not used, also for the last rank of the last position)
-    uint32_t tok[MAXB * BTV_MAX_NODES];     // its token id
     double cost[BTV_MAX_NODES];             // adaptive budget: estimated cycle latency at budget n + 1
+    const uint32_t *tok;                    // token ids of the same lists, left in memory: read once per emitted node
+};
+
+// The level-synchronous expansion: pool = the best nodes found so far, in emission order; candidates of one level.
+constexpr int LV_CAND = 2048;
+struct LevelLds {
+    u64 ckey[LV_CAND];
+    uint32_t cval[LV_CAND];
+    u64 pkey[2][BTV_MAX_NODES];
+    uint32_t pval[2][BTV_MAX_NODES];
+    uint16_t pos_of[MAXB * BTV_MAX_NODES];  // place in the pool by node id (level, index within the level)
+    int off[BTV_MAX_NODES];                 // exclusive scan of the candidates per pool entry
+    int cnt_lex[BTV_MAX_NODES];             // nodes of the new level per parent (by the parent's lexicographic place)
+    int wsum[4], wsum2[4];
+    double dsum[4];
+    int n_stop;
 };
 
 struct Batch {                              // several requests in one launch (n_nodes == nullptr: one request)
@@ -430,7 +445,7 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
         const int i = r * 64 + lane;
         if (i < n) {
             const uint32_t idx = o_rec[r] & 0x1FFFu;
-            token[i] = (int32_t)S.tok[idx];
+            token[i] = (int32_t)S.tok[idx];   // (memory)
             parent[i] = (int32_t)(o_rec[r] >> 13) - 1;
             if (depth) depth[i] = (int)(idx >> lg) + 1;
             if (rho) rho[i] = o_rho[r];
@@ -443,6 +458,236 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
         *n_out = n;
         if (ahat) *ahat = ADAPT ? (float)run_a : (float)(1.0 + a);
         if (ADAPT && ad.s_best) *ad.s_best = n > 0 ? best_a * ad.L_AR / best_c : -INFINITY;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 3, part B'': the same tree, level by level, on the whole workgroup.
+// The emission order (rho desc, depth asc, rank path asc) is a total order of the lattice in which a node comes
+// after its parent and after its elder siblings, so the tree is the set of the N first prefixes of that order and
+// the emission order is that order: nothing about it needs the frontier.  Level d of the tree is among the
+// children of the level d-1 nodes kept so far.  The pool holds the best N nodes found up to the level before, in
+// order; every pool node of depth d-1 proposes its children of rank r < min(K, N / (i + 1)), i being its place
+// among the depth d-1 nodes (the child is preceded by the (i+1)(r+1) children of rank <= r of the parents up to its
+// own), cut further at the score of the pool's last node once the pool is full; the proposals are sorted (bitonic,
+// 64-bit keys, in LDS) and merged into the pool by binary searches from both sides.  The loop ends at depth B or
+// when a level proposes nothing.
+// Key of a node = bits(rho) << 32 | (31 - depth) << 16 | (0xFFFF - lexkey); lexkey = place of the parent in the
+// lexicographic order of its level * KP + rank, which orders the nodes of one level by rank path; the place of a
+// new node in that order is the number of level nodes under parents before its parent, plus its rank (siblings
+// in the pool are always ranks 0 .. c-1).  Value = node id (level - 1) * 256 + place within the level | id of the
+// parent << 12 | lexicographic place << 24; places within a level never change once assigned, because the pool
+// only ever loses its last nodes.
+// A level costs a few microseconds whatever it holds, a node of the one-wavefront expansion a quarter to half a
+// microsecond whatever the tree looks like: the host of this function picks by the depth the tree can reach.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void bitonic_desc(u64 *key, uint32_t *val, int P2, int tid)
+{
+    __syncthreads();
+    for (int k = 2; k <= P2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            // pairs of 64 consecutive indices lie in one block of 128 elements when j <= 64: stages inside such a
+            // block only need the wave's own LDS traffic to be ordered
+            if (j >= 128 || (j == 64 && k >= 256)) __syncthreads();
+            else __builtin_amdgcn_wave_barrier();
+            for (int idx = tid; idx < P2 / 2; idx += 256) {
+                const int i1 = 2 * idx - (idx & (j - 1)), i2 = i1 + j;
+                const bool desc = (i1 & k) == 0;
+                const u64 a = key[i1], b = key[i2];
+                if ((a < b) == desc) {
+                    const uint32_t va = val[i1], vb = val[i2];
+                    key[i1] = b; key[i2] = a;
+                    val[i1] = vb; val[i2] = va;
+                }
+            }
+        }
+    __syncthreads();
+}
+
+template <bool ADAPT>
+__device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, int K, int KP, int N, int tid, int32_t *parent,
+                                              int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                                              const Adaptive &ad)
+{
+    const int lane = tid & 63, w = tid >> 6;
+    const int lg = 31 - __builtin_clz((unsigned)KP);
+    const u64 below = (1ull << lane) - 1ull;
+    int cur = 0, np = min(K, N);
+    if (tid < np) {                                            // level 1: the K best tokens of position 0, already in order
+        L.pkey[0][tid] = ((u64)__float_as_uint(__fmul_rn(1.0f, S.q[tid])) << 32) | (30u << 16) | (0xFFFFu - (uint32_t)tid);
+        L.pval[0][tid] = (uint32_t)tid | (0xFFFu << 12) | ((uint32_t)tid << 24);
+    }
+    __syncthreads();
+    for (int d = 2; d <= B; ++d) {
+        // ---- how many children each pool node of depth d-1 proposes ------------------------------------------------
+        const float *qd = S.q + (d - 1) * KP;
+        int c = 0;
+        if (tid < np) {
+            const u64 k = L.pkey[cur][tid];
+            if (31 - (int)((k >> 16) & 31u) == d - 1) {
+                const int place = (int)(L.pval[cur][tid] & 0xFFu);
+                const int rcap = min(K, N / (place + 1));
+                c = rcap;
+                if (np == N) {                                 // only scores that reach the pool's last node
+                    const uint32_t g32 = (uint32_t)(L.pkey[cur][N - 1] >> 32);
+                    const float rp = __uint_as_float((uint32_t)(k >> 32));
+                    int lo = 0, hi = rcap;                     // scores fall with the rank
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (__float_as_uint(__fmul_rn(rp, qd[mid])) >= g32) lo = mid + 1; else hi = mid;
+                    }
+                    c = lo;
+                }
+            }
+        }
+        int incl = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) L.wsum[w] = incl;
+        __syncthreads();
+        int base = 0;
+        for (int ww = 0; ww < w; ++ww) base += L.wsum[ww];
+        const int C = L.wsum[0] + L.wsum[1] + L.wsum[2] + L.wsum[3];
+        L.off[tid] = base + incl - c;
+        if (C == 0) break;                                     // (uniform)
+        if (C > LV_CAND) {                                     // cannot happen (sum over i of N / (i+1) <= 1570 at N = 256)
+            if (tid == 0) atomicOr(ad.flag, 8u);
+            break;
+        }
+        int P2 = 2;
+        while (P2 < C) P2 <<= 1;
+        __syncthreads();
+        // ---- the proposals: candidate j belongs to the last pool entry whose offset does not exceed j ---------------
+        for (int j = tid; j < P2; j += 256) {
+            u64 key = 0ull;
+            uint32_t val = 0u;
+            if (j < C) {
+                int lo = 0, hi = np;                           // first entry with off > j
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (L.off[mid] <= j) lo = mid + 1; else hi = mid;
+                }
+                const int pe = lo - 1, r = j - L.off[pe];
+                const u64 pk = L.pkey[cur][pe];
+                const uint32_t pv = L.pval[cur][pe];
+                const uint32_t sc = __float_as_uint(__fmul_rn(__uint_as_float((uint32_t)(pk >> 32)), qd[r]));
+                key = ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - (((pv >> 24) << lg) + (uint32_t)r));
+                val = (pv & 0xFFFu) << 12;
+            }
+            L.ckey[j] = key;
+            L.cval[j] = val;
+        }
+        bitonic_desc(L.ckey, L.cval, P2, tid);
+        // ---- merge: a node's new place = its place in its own list + the nodes of the other list ahead of it --------
+        const int nxt = cur ^ 1;
+        for (int j = tid; j < C; j += 256) {
+            const u64 ck = L.ckey[j];
+            int lo = 0, hi = np;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (L.pkey[cur][mid] > ck) lo = mid + 1; else hi = mid;
+            }
+            if (j + lo < N) { L.pkey[nxt][j + lo] = ck; L.pval[nxt][j + lo] = L.cval[j]; }
+        }
+        if (tid < np) {
+            const u64 k = L.pkey[cur][tid];
+            int lo = 0, hi = C;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (L.ckey[mid] > k) lo = mid + 1; else hi = mid;
+            }
+            if (tid + lo < N) { L.pkey[nxt][tid + lo] = k; L.pval[nxt][tid + lo] = L.pval[cur][tid]; }
+        }
+        L.cnt_lex[tid] = 0;
+        np = min(np + C, N);
+        cur = nxt;
+        __syncthreads();
+        // ---- the new level's nodes get their id and their lexicographic place --------------------------------------
+        bool mine = false;
+        uint32_t lexkey = 0u;
+        if (tid < np) {
+            const u64 k = L.pkey[cur][tid];
+            mine = 31 - (int)((k >> 16) & 31u) == d;
+            lexkey = 0xFFFFu - (uint32_t)(k & 0xFFFFu);
+        }
+        const u64 bal = __builtin_amdgcn_ballot_w64(mine);
+        if (lane == 0) L.wsum2[w] = __builtin_popcountll(bal);
+        if (mine) atomicAdd(&L.cnt_lex[lexkey >> lg], 1);
+        __syncthreads();
+        int place = __builtin_popcountll(bal & below);
+        for (int ww = 0; ww < w; ++ww) place += L.wsum2[ww];
+        const int cl = L.cnt_lex[tid];
+        int il = cl;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(il, o);
+            if (lane >= o) il += up;
+        }
+        if (lane == 63) L.wsum[w] = il;
+        __syncthreads();
+        int lb = 0;
+        for (int ww = 0; ww < w; ++ww) lb += L.wsum[ww];
+        L.cnt_lex[tid] = lb + il - cl;
+        __syncthreads();
+        if (mine) {
+            const uint32_t lexpos = (uint32_t)L.cnt_lex[lexkey >> lg] + (lexkey & (uint32_t)(KP - 1));
+            L.pval[cur][tid] = (uint32_t)((d - 1) * 256 + place) | (L.pval[cur][tid] & 0x00FFF000u) | (lexpos << 24);
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    // ---- the pool is the tree, in emission order ---------------------------------------------------------------------
+    int n = np;
+    if (ADAPT) {
+        // Sec. 3.4, Eq. 6: the budget stops at the first node that does not improve Ahat(n) * L_AR / C(n); Ahat is summed
+        // in emission order in fp64, by one thread
+        if (tid == 0) {
+            double run_a = 1.0, best_a = 0.0, best_c = 0.0;
+            int m = 0;
+            for (; m < np; ++m) {
+                const double c_n = S.cost[m];
+                const double a_new = run_a + (double)__uint_as_float((uint32_t)(L.pkey[cur][m] >> 32));
+                if (!(c_n > 0.0)) { atomicOr(ad.flag, 4u); break; }
+                if (m > 0 && !(a_new * best_c > best_a * c_n)) break;
+                run_a = a_new; best_a = a_new; best_c = c_n;
+            }
+            L.n_stop = m;
+            *n_out = m;
+            if (ahat) *ahat = (float)run_a;
+            if (ad.s_best) *ad.s_best = m > 0 ? best_a * ad.L_AR / best_c : -INFINITY;
+        }
+        __syncthreads();
+        n = L.n_stop;
+    }
+    if (tid < np) L.pos_of[L.pval[cur][tid] & 0xFFFu] = (uint16_t)tid;
+    __syncthreads();
+    double a = 0.0;
+    if (tid < n) {
+        const u64 k = L.pkey[cur][tid];
+        const uint32_t v = L.pval[cur][tid];
+        const int dep = 31 - (int)((k >> 16) & 31u);
+        const uint32_t lexkey = 0xFFFFu - (uint32_t)(k & 0xFFFFu);
+        const int idx = (dep - 1) * KP + (int)(lexkey & (uint32_t)(KP - 1));
+        const uint32_t pu = (v >> 12) & 0xFFFu;
+        const float r = __uint_as_float((uint32_t)(k >> 32));
+        token[tid] = (int32_t)S.tok[idx];
+        parent[tid] = pu == 0xFFFu ? -1 : (int32_t)L.pos_of[pu];
+        if (depth) depth[tid] = dep;
+        if (rho) rho[tid] = r;
+        a = (double)r;
+    }
+    if (!ADAPT) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off);
+        if (lane == 0) L.dsum[w] = a;
+        __syncthreads();
+        if (tid == 0) {
+            *n_out = n;
+            if (ahat) *ahat = (float)(1.0 + ((L.dsum[0] + L.dsum[1]) + (L.dsum[2] + L.dsum[3])));
+        }
     }
 }
 
@@ -514,11 +759,13 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
                                                       TbCounters *ctr, const uint32_t *part, float *top_q, uint32_t *top_tok,
                                                       int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
-                                                      Adaptive ad, int beam_width, Batch bt)
+                                                      Adaptive ad, int beam_width, Batch bt, int algo)
 {
-    __shared__ RankLds RL;
+    __shared__ union RankOrLevels { RankLds rank; LevelLds lev; } U;     // the ranking is over when the expansion starts
     __shared__ ExpandLds S;
     __shared__ BeamLds BM;
+    __shared__ int use_levels;
+    RankLds &RL = U.rank;
     // Fetch every argument in one round trip: left to the compiler the scalar loads follow the code in four
     // dependent steps over an argument block of several cache lines that is cold in every launch.
     asm volatile("" ::"s"(marg), "s"(V), "s"(B), "s"(K), "s"(KP), "s"(N), "s"(chunks), "s"(ctr), "s"(part), "s"(top_q),
@@ -638,10 +885,8 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     __syncthreads();
     if (!RL.last) return;
     __threadfence();
-    for (int e = tid; e < B * KP; e += 256) {
-        S.q[e] = __builtin_nontemporal_load(top_q + (size_t)req * B * KP + e);
-        S.tok[e] = __builtin_nontemporal_load(top_tok + (size_t)req * B * KP + e);
-    }
+    for (int e = tid; e < B * KP; e += 256) S.q[e] = __builtin_nontemporal_load(top_q + (size_t)req * B * KP + e);
+    if (tid == 0) S.tok = top_tok + (size_t)req * B * KP;
     if (bt.n_nodes) {                          // this request's budget and output rows
         const int o0 = bt.q_offset[req], room = bt.q_offset[req + 1] - o0, want = bt.n_nodes[req];
         const bool bad = o0 < 0 || want < 0 || want > N || want > room;
@@ -662,6 +907,33 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     __syncthreads();
     if (beam_width > 0) {                      // B rows = depths of the beam tree, K = min(V, width)
         beam_block(S, BM, B, K, KP, beam_width, tid, parent, token, depth, rho, n_out, ahat);
+        return;
+    }
+    // Which expansion: the level-synchronous one pays per level (measured: about 6 us up to 64 nodes, 8 to 128, 10
+    // beyond, less for thin levels), the one-wavefront one per node (0.23 / 0.27 / 0.38 us), and with the early stop
+    // it ends at the chosen budget, typically a quarter of N_max.  The tree cannot be deeper than the greedy chain
+    // stays above the N-th best token of the first position (every node scores at least as much as the tree's last
+    // one, which scores at least that).
+    if (tid == 0) {
+        int reach = 0;
+        if (algo == 0) {
+            const float g_est = S.q[min(K, N) - 1];
+            float chain = 1.0f;
+            for (int k = 0; k < B; ++k) {
+                chain = __fmul_rn(chain, S.q[k * KP]);
+                if (!(chain >= g_est)) break;
+                reach = k + 1;
+            }
+        }
+        const float per_level = N <= 64 ? 6.0f : N <= 128 ? 8.0f : 10.0f;
+        const float per_node = N <= 64 ? 0.23f : N <= 128 ? 0.27f : 0.38f;
+        const float nodes = ad.cost ? 0.25f * (float)N : (float)N;
+        use_levels = algo == 2 || (algo == 0 && (float)reach * per_level < nodes * per_node);
+    }
+    __syncthreads();
+    if (use_levels) {
+        if (ad.cost) expand_levels<true>(S, U.lev, B, K, KP, N, tid, parent, token, depth, rho, n_out, ahat, ad);
+        else expand_levels<false>(S, U.lev, B, K, KP, N, tid, parent, token, depth, rho, n_out, ahat, ad);
         return;
     }
     if (w != 0) return;
@@ -710,7 +982,7 @@ size_t btv_tree_build_workspace(int B, int V, int N) { return tree_build_ws(1, B
 size_t btv_tree_build_batch_workspace(int batch, int B, int V, int N_max) { return tree_build_ws(batch, B, V, N_max); }
 
 static int tree_build_launch(const float *marginals, int batch, int B, int V, int N, const Adaptive &ad_in, int beam_width,
-                             Batch bt, int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                             Batch bt, int algo, int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
                              void *ws, size_t ws_bytes, void *stream)
 {
     BTV_REQUIRE(marginals && parent && token && n_out, "null pointer");
@@ -733,7 +1005,7 @@ static int tree_build_launch(const float *marginals, int batch, int B, int V, in
     hipLaunchKernelGGL(tb_thread_max, dim3(t.chunks, B * batch), dim3(256), 0, st, marginals, V, B, t.chunks, part, ctr);
     BTV_HIP(hipGetLastError());
     hipLaunchKernelGGL(tb_rank_expand, dim3(B * batch), dim3(256), 0, st, marginals, V, B, t.K, t.KP, N, t.chunks, ctr, part, top_q,
-                       top_tok, parent, token, depth, rho, n_out, ahat, ad, beam_width, bt);
+                       top_tok, parent, token, depth, rho, n_out, ahat, ad, beam_width, bt, algo);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
@@ -744,7 +1016,7 @@ int btv_tree_build(const float *marginals, int B, int V, int N, int32_t *parent,
                    float *rho, int32_t *n_out, float *ahat, void *ws, size_t ws_bytes, void *stream)
 {
     const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
-    return tree_build_launch(marginals, 1, B, V, N, none, 0, kOneRequest, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+    return tree_build_launch(marginals, 1, B, V, N, none, 0, kOneRequest, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
 }
 
 int btv_tree_build_beam(const float *marginals, int B, int V, int width, int depth_max, int32_t *parent, int32_t *token,
@@ -755,7 +1027,7 @@ int btv_tree_build_beam(const float *marginals, int B, int V, int width, int dep
     BTV_REQUIRE(depth_max >= 1 && depth_max <= B, "depth=%d outside [1,B=%d]", depth_max, B);
     // the first depth_max positions are ranked for their `width` best tokens; the rest of the path is shared
     const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
-    return tree_build_launch(marginals, 1, depth_max, V, width, none, width, kOneRequest, parent, token, depth, rho, n_out, ahat,
+    return tree_build_launch(marginals, 1, depth_max, V, width, none, width, kOneRequest, 0, parent, token, depth, rho, n_out, ahat,
                              ws, ws_bytes, stream);
 }
 
@@ -766,7 +1038,18 @@ int btv_tree_build_adaptive(const float *marginals, int B, int V, int N_max, con
     BTV_REQUIRE(cost != nullptr, "null pointer");
     BTV_REQUIRE(L_AR > 0.0, "L_AR must be positive");
     const Adaptive ad = { cost, L_AR, s_best, nullptr };
-    return tree_build_launch(marginals, 1, B, V, N_max, ad, 0, kOneRequest, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+    return tree_build_launch(marginals, 1, B, V, N_max, ad, 0, kOneRequest, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes, stream);
+}
+
+int btv_tree_build_tuned(const float *marginals, int B, int V, int N, const double *cost, double L_AR, int algo,
+                         int32_t *parent, int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
+                         double *s_best, void *ws, size_t ws_bytes, void *stream)
+{
+    BTV_REQUIRE(algo >= 0 && algo <= 2, "algo=%d outside [0,2]", algo);
+    BTV_REQUIRE(cost == nullptr || L_AR > 0.0, "L_AR must be positive");
+    const Adaptive ad = { cost, L_AR, cost ? s_best : nullptr, nullptr };
+    return tree_build_launch(marginals, 1, B, V, N, ad, 0, kOneRequest, algo, parent, token, depth, rho, n_out, ahat, ws, ws_bytes,
+                             stream);
 }
 
 int btv_tree_build_batch(const float *marginals, int batch, int B, int V, const int32_t *n_nodes, const int32_t *q_offset,
@@ -776,7 +1059,7 @@ int btv_tree_build_batch(const float *marginals, int batch, int B, int V, const 
     BTV_REQUIRE(n_nodes && q_offset, "null pointer");
     const Adaptive none = { nullptr, 0.0, nullptr, nullptr };
     const Batch bt = { n_nodes, q_offset, nullptr };
-    return tree_build_launch(marginals, batch, B, V, N_max, none, 0, bt, parent, token, depth, rho, n_out, ahat, ws, ws_bytes,
+    return tree_build_launch(marginals, batch, B, V, N_max, none, 0, bt, 0, parent, token, depth, rho, n_out, ahat, ws, ws_bytes,
                              stream);
 }
 

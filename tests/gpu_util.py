@@ -54,7 +54,8 @@ def run_verify_attn_fp8kv(Q_bits: np.ndarray, kv: dict, parent: np.ndarray, L: i
     return host(O).astype(np.float64)
 
 
-def run_tree_build(marg: np.ndarray, N: int) -> dict:
+def run_tree_build(marg: np.ndarray, N: int, algo: int = 0) -> dict:
+    """algo 0: btv_tree_build; 1 / 2: the tuned entry point with the one-wavefront / level-synchronous expansion."""
     m = dev(marg.astype(np.float32))
     B, V = marg.shape
     parent = torch.full((N,), -7, dtype=torch.int32, device="cuda")
@@ -64,15 +65,19 @@ def run_tree_build(marg: np.ndarray, N: int) -> dict:
     n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
     ahat = torch.zeros(1, dtype=torch.float32, device="cuda")
     ws = btv.alloc_workspace(btv.btv_tree_build_workspace(B, V, N))
-    btv.btv_tree_build(m, N, parent, token, depth, rho, n_out, ahat, ws)
+    if algo:
+        btv.btv_tree_build_tuned(m, N, algo, parent, token, depth, rho, n_out, ahat, ws)
+    else:
+        btv.btv_tree_build(m, N, parent, token, depth, rho, n_out, ahat, ws)
     torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == 0
     n = int(n_out.item())
     return {"n": n, "parent": parent.cpu().numpy()[:n], "token": token.cpu().numpy()[:n],
             "depth": depth.cpu().numpy()[:n], "rho": rho.cpu().numpy()[:n], "ahat": float(ahat.item()),
             "raw_parent": parent.cpu().numpy()}
 
 
-def run_tree_build_adaptive(marg: np.ndarray, N_max: int, cost: np.ndarray, L_AR: float) -> dict:
+def run_tree_build_adaptive(marg: np.ndarray, N_max: int, cost: np.ndarray, L_AR: float, algo: int = 0) -> dict:
     m = dev(marg.astype(np.float32))
     B, V = marg.shape
     c = torch.from_numpy(np.ascontiguousarray(cost, dtype=np.float64)).cuda()
@@ -84,7 +89,10 @@ def run_tree_build_adaptive(marg: np.ndarray, N_max: int, cost: np.ndarray, L_AR
     ahat = torch.zeros(1, dtype=torch.float32, device="cuda")
     s_best = torch.zeros(1, dtype=torch.float64, device="cuda")
     ws = btv.alloc_workspace(btv.btv_tree_build_workspace(B, V, N_max))
-    btv.btv_tree_build_adaptive(m, N_max, c, L_AR, parent, token, depth, rho, n_out, ahat, s_best, ws)
+    if algo:
+        btv.btv_tree_build_tuned(m, N_max, algo, parent, token, depth, rho, n_out, ahat, ws, cost=c, L_AR=L_AR, s_best=s_best)
+    else:
+        btv.btv_tree_build_adaptive(m, N_max, c, L_AR, parent, token, depth, rho, n_out, ahat, s_best, ws)
     torch.cuda.synchronize()
     n = int(n_out.item())
     status = int(btv.btv_workspace_status(ws))

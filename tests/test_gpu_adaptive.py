@@ -19,17 +19,18 @@ def G():
 
 def _check(G, oracle, marg, N_max, cost, L_AR):
     ref = oracle.tree_build_adaptive(marg, N_max, cost, L_AR)
-    got = G.run_tree_build_adaptive(marg, N_max, cost, L_AR)
-    assert got["status"] == 0
-    if ref["margin"] < AMBIGUOUS:
-        return ref, got, False
-    assert got["n"] == ref["n"]
-    for k in ("parent", "token", "depth"):
-        assert np.array_equal(got[k], ref[k]), k
-    assert np.array_equal(got["rho"].view(np.uint32), ref["rho"].view(np.uint32))
-    assert abs(got["ahat"] - ref["ahat"]) <= 2e-7 * ref["ahat"]
-    assert got["s_best"] == pytest.approx(ref["s_best"], rel=1e-13)
-    assert np.all(got["raw_parent"][got["n"]:] == -7)              # nothing written past the chosen budget
+    for algo in (0, 1, 2):                  # the library's choice of expansion, then each of the two forced
+        got = G.run_tree_build_adaptive(marg, N_max, cost, L_AR, algo)
+        assert got["status"] == 0
+        if ref["margin"] < AMBIGUOUS:
+            return ref, got, False
+        assert got["n"] == ref["n"], algo
+        for k in ("parent", "token", "depth"):
+            assert np.array_equal(got[k], ref[k]), (k, algo)
+        assert np.array_equal(got["rho"].view(np.uint32), ref["rho"].view(np.uint32)), algo
+        assert abs(got["ahat"] - ref["ahat"]) <= 2e-7 * ref["ahat"], algo
+        assert got["s_best"] == pytest.approx(ref["s_best"], rel=1e-13), algo
+        assert np.all(got["raw_parent"][got["n"]:] == -7), algo      # nothing written past the chosen budget
     return ref, got, True
 
 
@@ -83,7 +84,8 @@ def test_invalid_cost_is_flagged(G, oracle):
     marg = synth.marginals(5, 4, 100, 2.0)
     cost = np.ones(32)
     cost[5] = 0.0
-    got = G.run_tree_build_adaptive(marg, 32, cost, 1.0)
-    assert got["status"] != 0 and got["n"] == 5          # the five nodes before the bad entry stand
     ref = oracle.tree_build(marg, 5)
-    assert np.array_equal(got["parent"], ref["parent"]) and np.array_equal(got["token"], ref["token"])
+    for algo in (0, 1, 2):
+        got = G.run_tree_build_adaptive(marg, 32, cost, 1.0, algo)
+        assert got["status"] != 0 and got["n"] == 5          # the five nodes before the bad entry stand
+        assert np.array_equal(got["parent"], ref["parent"]) and np.array_equal(got["token"], ref["token"])

@@ -14,13 +14,15 @@ def G():
 
 
 def _check(G, oracle, marg, N):
+    """The library's own choice of expansion, then each of the two expansions forced."""
     ref = oracle.tree_build(marg, N)
-    got = G.run_tree_build(marg, N)
-    assert got["n"] == ref["n"]
-    for k in ("parent", "token", "depth"):
-        assert np.array_equal(got[k], ref[k]), k
-    assert np.array_equal(got["rho"].view(np.uint32), ref["rho"].view(np.uint32))
-    assert abs(got["ahat"] - ref["ahat"]) <= 1e-5 * ref["ahat"]
+    for algo in (0, 1, 2):
+        got = G.run_tree_build(marg, N, algo)
+        assert got["n"] == ref["n"], algo
+        for k in ("parent", "token", "depth"):
+            assert np.array_equal(got[k], ref[k]), (k, algo)
+        assert np.array_equal(got["rho"].view(np.uint32), ref["rho"].view(np.uint32)), algo
+        assert abs(got["ahat"] - ref["ahat"]) <= 1e-5 * ref["ahat"], algo
     return ref
 
 
