@@ -136,7 +136,7 @@ struct ExpandLds {                          // the expansion
 constexpr int LV_CAND = 2048;
 struct LevelLds {
     u64 ckey[LV_CAND];
-    uint32_t cval[LV_CAND];
+    uint16_t lex2id[BTV_MAX_NODES];         // node id by lexicographic place, for the level whose children are proposed
     u64 pkey[2][BTV_MAX_NODES];
     uint32_t pval[2][BTV_MAX_NODES];
     uint16_t pos_of[MAXB * BTV_MAX_NODES];  // place in the pool by node id (level, index within the level)
@@ -481,26 +481,58 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 // A level costs a few microseconds whatever it holds, a node of the one-wavefront expansion a quarter to half a
 // microsecond whatever the tree looks like: the host of this function picks by the depth the tree can reach.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void bitonic_desc(u64 *key, uint32_t *val, int P2, int tid)
+// Bitonic sort of P2 (a power of two, at least 128) 64-bit keys in LDS, largest first, by 256 threads.  Every
+// compare-exchange at a distance below 128 happens in registers: a wavefront holds a block of 128 keys two per lane
+// (key e * 64 + lane of the block in register e), distance 64 pairs a lane's own two registers, shorter distances pair
+// lanes (two 32-bit cross-lane moves per key).  Only the distances from 128 up go through LDS, one block barrier
+// each.  base = index of the block's first key in the whole array: it fixes each pair's direction.
+__device__ __forceinline__ void wave_stages(u64 &k0, u64 &k1, int base, int k_lo, int k_hi, int j_top, int lane)
 {
-    __syncthreads();
-    for (int k = 2; k <= P2; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            // pairs of 64 consecutive indices lie in one block of 128 elements when j <= 64: stages inside such a
-            // block only need the wave's own LDS traffic to be ordered
-            if (j >= 128 || (j == 64 && k >= 256)) __syncthreads();
-            else __builtin_amdgcn_wave_barrier();
-            for (int idx = tid; idx < P2 / 2; idx += 256) {
-                const int i1 = 2 * idx - (idx & (j - 1)), i2 = i1 + j;
-                const bool desc = (i1 & k) == 0;
-                const u64 a = key[i1], b = key[i2];
-                if ((a < b) == desc) {
-                    const uint32_t va = val[i1], vb = val[i2];
-                    key[i1] = b; key[i2] = a;
-                    val[i1] = vb; val[i2] = va;
-                }
+    for (int k = k_lo; k <= k_hi; k <<= 1)
+        for (int j = min(k >> 1, j_top); j > 0; j >>= 1) {
+            if (j == 64) {
+                const bool desc = ((base + lane) & k) == 0;
+                const u64 hi = k0 > k1 ? k0 : k1, lo = k0 > k1 ? k1 : k0;
+                k0 = desc ? hi : lo;
+                k1 = desc ? lo : hi;
+            } else {
+                const bool lower = (lane & j) == 0;               // this lane holds the pair's lower index
+                const u64 p0 = ((u64)(uint32_t)__shfl_xor((int)(uint32_t)(k0 >> 32), j) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)k0, j);
+                const u64 p1 = ((u64)(uint32_t)__shfl_xor((int)(uint32_t)(k1 >> 32), j) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)k1, j);
+                const bool max0 = lower == (((base + lane) & k) == 0), max1 = lower == (((base + 64 + lane) & k) == 0);
+                k0 = (max0 == (k0 > p0)) ? k0 : p0;
+                k1 = (max1 == (k1 > p1)) ? k1 : p1;
             }
         }
+}
+
+__device__ __forceinline__ void bitonic_desc(u64 *key, int P2, int tid)
+{
+    const int lane = tid & 63, w = tid >> 6;
+    __syncthreads();
+    for (int blk = w; blk * 128 < P2; blk += 4) {                  // every block of 128 sorted on its own
+        u64 k0 = key[blk * 128 + lane], k1 = key[blk * 128 + 64 + lane];
+        wave_stages(k0, k1, blk * 128, 2, 128, 64, lane);
+        key[blk * 128 + lane] = k0;
+        key[blk * 128 + 64 + lane] = k1;
+    }
+    for (int k = 256; k <= P2; k <<= 1) {
+        for (int j = k >> 1; j >= 128; j >>= 1) {
+            __syncthreads();
+            for (int idx = tid; idx < P2 / 2; idx += 256) {
+                const int i1 = 2 * idx - (idx & (j - 1)), i2 = i1 + j;
+                const u64 a = key[i1], b = key[i2];
+                if ((a < b) == ((i1 & k) == 0)) { key[i1] = b; key[i2] = a; }
+            }
+        }
+        __syncthreads();
+        for (int blk = w; blk * 128 < P2; blk += 4) {
+            u64 k0 = key[blk * 128 + lane], k1 = key[blk * 128 + 64 + lane];
+            wave_stages(k0, k1, blk * 128, k, k, 64, lane);
+            key[blk * 128 + lane] = k0;
+            key[blk * 128 + 64 + lane] = k1;
+        }
+    }
     __syncthreads();
 }
 
@@ -516,6 +548,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
     if (tid < np) {                                            // level 1: the K best tokens of position 0, already in order
         L.pkey[0][tid] = ((u64)__float_as_uint(__fmul_rn(1.0f, S.q[tid])) << 32) | (30u << 16) | (0xFFFFu - (uint32_t)tid);
         L.pval[0][tid] = (uint32_t)tid | (0xFFFu << 12) | ((uint32_t)tid << 24);
+        L.lex2id[tid] = (uint16_t)tid;
     }
     __syncthreads();
     for (int d = 2; d <= B; ++d) {
@@ -557,13 +590,12 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
             if (tid == 0) atomicOr(ad.flag, 8u);
             break;
         }
-        int P2 = 2;
+        int P2 = 128;
         while (P2 < C) P2 <<= 1;
         __syncthreads();
         // ---- the proposals: candidate j belongs to the last pool entry whose offset does not exceed j ---------------
         for (int j = tid; j < P2; j += 256) {
             u64 key = 0ull;
-            uint32_t val = 0u;
             if (j < C) {
                 int lo = 0, hi = np;                           // first entry with off > j
                 while (lo < hi) {
@@ -572,15 +604,12 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
                 }
                 const int pe = lo - 1, r = j - L.off[pe];
                 const u64 pk = L.pkey[cur][pe];
-                const uint32_t pv = L.pval[cur][pe];
                 const uint32_t sc = __float_as_uint(__fmul_rn(__uint_as_float((uint32_t)(pk >> 32)), qd[r]));
-                key = ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - (((pv >> 24) << lg) + (uint32_t)r));
-                val = (pv & 0xFFFu) << 12;
+                key = ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - (((L.pval[cur][pe] >> 24) << lg) + (uint32_t)r));
             }
             L.ckey[j] = key;
-            L.cval[j] = val;
         }
-        bitonic_desc(L.ckey, L.cval, P2, tid);
+        bitonic_desc(L.ckey, P2, tid);
         // ---- merge: a node's new place = its place in its own list + the nodes of the other list ahead of it --------
         const int nxt = cur ^ 1;
         for (int j = tid; j < C; j += 256) {
@@ -590,7 +619,10 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
                 const int mid = (lo + hi) >> 1;
                 if (L.pkey[cur][mid] > ck) lo = mid + 1; else hi = mid;
             }
-            if (j + lo < N) { L.pkey[nxt][j + lo] = ck; L.pval[nxt][j + lo] = L.cval[j]; }
+            if (j + lo < N) {
+                L.pkey[nxt][j + lo] = ck;
+                L.pval[nxt][j + lo] = (uint32_t)L.lex2id[(0xFFFFu - (uint32_t)(ck & 0xFFFFu)) >> lg] << 12;
+            }
         }
         if (tid < np) {
             const u64 k = L.pkey[cur][tid];
@@ -635,6 +667,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
         if (mine) {
             const uint32_t lexpos = (uint32_t)L.cnt_lex[lexkey >> lg] + (lexkey & (uint32_t)(KP - 1));
             L.pval[cur][tid] = (uint32_t)((d - 1) * 256 + place) | (L.pval[cur][tid] & 0x00FFF000u) | (lexpos << 24);
+            L.lex2id[lexpos] = (uint16_t)((d - 1) * 256 + place);
         }
         __syncthreads();
     }
@@ -909,11 +942,11 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
         beam_block(S, BM, B, K, KP, beam_width, tid, parent, token, depth, rho, n_out, ahat);
         return;
     }
-    // Which expansion: the level-synchronous one pays per level (measured: about 6 us up to 64 nodes, 8 to 128, 10
-    // beyond, less for thin levels), the one-wavefront one per node (0.23 / 0.27 / 0.38 us), and with the early stop
-    // it ends at the chosen budget, typically a quarter of N_max.  The tree cannot be deeper than the greedy chain
-    // stays above the N-th best token of the first position (every node scores at least as much as the tree's last
-    // one, which scores at least that).
+    // Which expansion: the level-synchronous one pays per level (measured: about 4.8 us up to 64 nodes, 5.3 to 128,
+    // 6.2 beyond), the one-wavefront one per node (0.23 / 0.27 / 0.38 us), and with the early stop it ends at the
+    // chosen budget, typically a quarter of N_max.  The tree cannot be deeper than the greedy chain stays above the
+    // N-th best token of the first position (every node scores at least as much as the tree's last one, which
+    // scores at least that); a tree of depth 1 is the first level's list as it stands.
     if (tid == 0) {
         int reach = 0;
         if (algo == 0) {
@@ -925,10 +958,10 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
                 reach = k + 1;
             }
         }
-        const float per_level = N <= 64 ? 6.0f : N <= 128 ? 8.0f : 10.0f;
+        const float per_level = N <= 64 ? 4.8f : N <= 128 ? 5.3f : 6.2f;
         const float per_node = N <= 64 ? 0.23f : N <= 128 ? 0.27f : 0.38f;
         const float nodes = ad.cost ? 0.25f * (float)N : (float)N;
-        use_levels = algo == 2 || (algo == 0 && (float)reach * per_level < nodes * per_node);
+        use_levels = algo == 2 || (algo == 0 && (reach <= 1 || (float)reach * per_level < nodes * per_node));
     }
     __syncthreads();
     if (use_levels) {
