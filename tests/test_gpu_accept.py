@@ -83,6 +83,46 @@ def test_greedy_all_equal_and_neg_inf_rows(G, oracle):
     _greedy_case(G, oracle, x, x, False, parent, token)
 
 
+def test_greedy_signed_zeros_tie_and_workspace_reuse(G, oracle):
+    """-0.0 and +0.0 are the same value: the lower index wins whichever sign it carries.  One workspace then serves
+    calls of different sizes in a row: the per-row words and the workgroup counter are back at zero after each."""
+    import torch
+    from paper_2605_29727_amd import binding as btv
+    M, V = 3, 9000
+    parent = synth.tree_parents(0, M, "chain")
+    x = np.full((M + 1, V), -1.0, dtype=np.float32)
+    x[0, 5000], x[0, 17] = 0.0, -0.0
+    x[1, 17], x[1, 8999] = 0.0, -0.0
+    x[2, 8999], x[2, 4096] = -0.0, -0.0
+    x[3, 1] = 0.0
+    token = np.array([17, 17, 4096], dtype=np.int32)
+    r = _greedy_case(G, oracle, x, x, False, parent, token)
+    assert r["n_acc"] == 3 and r["bonus"] == 1
+
+    V = 128256
+    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(256, V, False))
+    for M, kind, seed in ((64, "random", 1), (5, "chain", 2), (256, "deep", 3), (64, "random", 1)):
+        parent = synth.tree_parents(seed, M, kind)
+        token = synth.sibling_distinct_tokens(seed, parent, V)
+        _, f = synth.target_logits(seed, M + 1, V, 1.0, "fp32", tag=f"reuse{M}")
+        x = synth.plant_path(f, parent, token, int(np.argmax(_depths(parent))))
+        store, xf = synth.round_to_dtype(x.astype(np.float64), "bf16")
+        ref = oracle.accept_greedy(xf, parent, token)
+        d = G.dev(store, True)
+        par, tok = G.dev(parent.astype(np.int32)), G.dev(token.astype(np.int32))
+        path = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+        n_acc = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        bonus = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        am = torch.full((M + 1,), -7, dtype=torch.int32, device="cuda")
+        for _ in range(2):                                   # twice in a row on the same workspace
+            btv.btv_tree_accept_greedy(d, par, tok, path, n_acc, bonus, am, ws)
+        torch.cuda.synchronize()
+        n = int(n_acc.item())
+        assert n == ref["n_acc"] and bonus.item() == ref["bonus"], (M, kind)
+        assert np.array_equal(path.cpu().numpy()[:n], ref["path"]) and np.array_equal(am.cpu().numpy(), ref["argmax"])
+    assert torch.count_nonzero(ws).item() == 0               # the workspace is left as it was handed over
+
+
 AMBIGUOUS, AMBIGUOUS_GAP = 1e-4, 1e-6
 
 
