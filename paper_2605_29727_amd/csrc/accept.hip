@@ -674,6 +674,29 @@ __device__ __forceinline__ float block_max(float x, float *sh, int tid)
     return s;
 }
 
+// Sum of x over the wavefront, returned in every lane: quad swaps, row mirrors, then the row totals travel down the
+// rows (DPP moves of the two halves; lanes a step does not write add zero).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add(double x)
+{
+    const long long b = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, ROW_MASK, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, ROW_MASK, 0xF, true);
+    return x + __longlong_as_double(((long long)(uint32_t)hi << 32) | (long long)(uint32_t)lo);
+}
+__device__ __forceinline__ double wave_sum_f64(double x)
+{
+    x = dpp_add<0xB1, 0xF>(x);      // quad_perm [1,0,3,2]
+    x = dpp_add<0x4E, 0xF>(x);      // quad_perm [2,3,0,1]
+    x = dpp_add<0x141, 0xF>(x);     // row_half_mirror
+    x = dpp_add<0x140, 0xF>(x);     // row_mirror: every lane holds its row's total
+    x = dpp_add<0x142, 0xA>(x);     // row_bcast15 into rows 1 and 3
+    x = dpp_add<0x143, 0xC>(x);     // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    const long long b = __double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, 63), hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), 63);
+    return __longlong_as_double(((long long)hi << 32) | (long long)lo);
+}
+
 template <bool BF16>
 __device__ __forceinline__ float load_logit(const void *logits, size_t idx)
 {
@@ -694,6 +717,8 @@ __device__ __forceinline__ float load_logit(const void *logits, size_t idx)
 // so Z is a prefix sum over the sorted pairs below the threshold's bin plus an exact scan of that one bin.
 constexpr int SW_BINS = 2048;
 constexpr int SW_BUILD_MIN = 40;    // children still untried at a node for the sort to be worth its cost (about 30 passes)
+constexpr int SW_PRE_MIN = 6;       // children of the root from which its row is sorted ahead of the walk (a few passes' worth)
+constexpr int SW_WIN = 8192;        // sorted pairs kept in LDS around the threshold
 
 __device__ __forceinline__ int sw_bin(float ratio)
 {
@@ -701,19 +726,181 @@ __device__ __forceinline__ int sw_bin(float ratio)
     return (int)(b < (uint32_t)SW_BINS ? b : (uint32_t)SW_BINS - 1u);
 }
 
+// ---- the root's row sorted ahead of the walk, by many workgroups ---------------------------------------------------
+// Wide fans sit under the root (the best-first tree puts up to N children there when the first position's
+// marginal is flat), and a sort on the walk's single CU costs about 250 us.  When the root has at least SW_BUILD_MIN
+// children, SW_PRE_WGS workgroups prepare the root's row before the walk starts: row maximum, e = exp(logit - max)
+// with its sum, a bin histogram per workgroup, the (e, q0) pairs moved into bin order (bin offsets per workgroup),
+// and the sums of e and q0 per chunk of the sorted pairs.  Every step is its own launch (the grid-wide
+// dependencies are kernel boundaries); with fewer children every one of them returns at once.  The walk picks the
+// prepared row up if SwPre::ready says so.  Each workgroup owns a contiguous slice of the vocabulary; all sums
+// that cross workgroups are added in workgroup order, so they are the same in every run.
+constexpr int SW_PRE_WGS = 32;
+
+struct SwPre {                      // in the workspace, behind es and eq_sorted
+    int ready;                      // 1: the root's row is prepared (written by sw_pre_scatter)
+    float mx;
+    double z, tq;
+    float wg_max[SW_PRE_WGS];
+    double wg_z[SW_PRE_WGS], wg_tq[SW_PRE_WGS];
+    int start[SW_BINS + 1];
+    double chunk_e[SW_BINS], chunk_q[SW_BINS];            // sums over chunk c of the sorted pairs (not yet prefix sums)
+    int hist[SW_PRE_WGS][SW_BINS];                        // pairs of workgroup w in bin b
+};
+
+__device__ __forceinline__ bool sw_root_is_wide(const int32_t *parent, int M, int tid, double *shd)
+{
+    int mine = 0;
+    for (int c = tid; c < M; c += 1024) mine += parent[c] == -1 ? 1 : 0;
+    return (int)block_sum((double)mine, shd, tid) >= SW_PRE_MIN;
+}
+
+__device__ __forceinline__ void sw_slice(int V, int wg, int &v0, int &v1)
+{
+    const int per = ((V + SW_PRE_WGS - 1) / SW_PRE_WGS + 3) & ~3;      // a multiple of four: slices keep the row's alignment
+    v0 = min(wg * per, V);
+    v1 = min(v0 + per, V);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(1024) void sw_pre_max(const void *__restrict__ logits, const int32_t *__restrict__ parent, int M, int V,
+                                                   SwPre *pre)
+{
+    __shared__ double shd[16];
+    __shared__ float shf[16];
+    const int tid = threadIdx.x;
+    if (blockIdx.x == 0 && tid == 0) pre->ready = 0;
+    if (!sw_root_is_wide(parent, M, tid, shd)) return;
+    int v0, v1;
+    sw_slice(V, blockIdx.x, v0, v1);
+    float mx = -INFINITY;
+    for (int v = v0 + tid; v < v1; v += 1024) mx = fmaxf(mx, load_logit<BF16>(logits, v));
+    mx = block_max(mx, shf, tid);
+    if (tid == 0) pre->wg_max[blockIdx.x] = mx;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(1024) void sw_pre_exp(const void *__restrict__ logits, const float *__restrict__ q0,
+                                                   const int32_t *__restrict__ parent, int M, int V, float *__restrict__ es,
+                                                   SwPre *pre)
+{
+    __shared__ double shd[16];
+    __shared__ int hist[SW_BINS];
+    const int tid = threadIdx.x;
+    if (!sw_root_is_wide(parent, M, tid, shd)) return;
+    float mx = pre->wg_max[0];
+    for (int w = 1; w < SW_PRE_WGS; ++w) mx = fmaxf(mx, pre->wg_max[w]);
+    for (int b = tid; b < SW_BINS; b += 1024) hist[b] = 0;
+    __syncthreads();
+    int v0, v1;
+    sw_slice(V, blockIdx.x, v0, v1);
+    double z = 0.0, tq = 0.0;
+    for (int v = v0 + tid; v < v1; v += 1024) {
+        const float e = expf(load_logit<BF16>(logits, v) - mx), q = q0[v];
+        es[v] = e;
+        z += (double)e;
+        tq += (double)q;
+        atomicAdd(&hist[sw_bin(__fdiv_rn(q, e))], 1);
+    }
+    z = block_sum(z, shd, tid);
+    tq = block_sum(tq, shd, tid);                            // (the barriers also complete the histogram)
+    if (tid == 0) { pre->wg_z[blockIdx.x] = z; pre->wg_tq[blockIdx.x] = tq; if (blockIdx.x == 0) pre->mx = mx; }
+    for (int b = tid; b < SW_BINS; b += 1024) pre->hist[blockIdx.x][b] = hist[b];
+}
+
+// Bin offsets and scatter in one launch: every workgroup adds up the histograms of all of them (the same 256 KB for
+// each: cheaper than a launch of its own for one workgroup to do it), scans the bins, and moves its slice's pairs to
+// where its share of each bin starts.  Workgroup 0 also leaves the bin starts and the row's sums for the walk.
+__global__ __launch_bounds__(1024) void sw_pre_scatter(const float *__restrict__ q0, const int32_t *__restrict__ parent, int M, int V,
+                                                       const float *__restrict__ es, float2 *__restrict__ eq_sorted, SwPre *pre)
+{
+    __shared__ double shd[16];
+    __shared__ int wsum[16];
+    __shared__ double part[2][SW_PRE_WGS];
+    __shared__ int cursor[SW_BINS];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, me = blockIdx.x;
+    if (!sw_root_is_wide(parent, M, tid, shd)) return;
+    if (me == 0 && tid < SW_PRE_WGS) { part[0][tid] = pre->wg_z[tid]; part[1][tid] = pre->wg_tq[tid]; }
+    int2 h[SW_PRE_WGS];                                      // bins 2*tid and 2*tid + 1 of every workgroup
+#pragma unroll
+    for (int w = 0; w < SW_PRE_WGS; ++w) h[w] = *reinterpret_cast<const int2 *>(&pre->hist[w][2 * tid]);
+    int c0 = 0, c1 = 0, m0 = 0, m1 = 0;                      // all workgroups; those before this one
+#pragma unroll
+    for (int w = 0; w < SW_PRE_WGS; ++w) {
+        if (w == me) { m0 = c0; m1 = c1; }
+        c0 += h[w].x; c1 += h[w].y;
+    }
+    int ci = c0 + c1;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int co = __shfl_up(ci, off);
+        if (lane >= off) ci += co;
+    }
+    if (lane == 63) wsum[wv] = ci;
+    __syncthreads();
+    int cb = 0;
+    for (int w = 0; w < wv; ++w) cb += wsum[w];
+    const int s0 = cb + ci - (c0 + c1), s1 = s0 + c0;        // where bins 2*tid and 2*tid + 1 start
+    cursor[2 * tid] = s0 + m0;
+    cursor[2 * tid + 1] = s1 + m1;
+    if (me == 0) {
+        pre->start[2 * tid] = s0;
+        pre->start[2 * tid + 1] = s1;
+        if (tid == 1023) pre->start[SW_BINS] = s1 + c1;
+        if (tid == 0) {
+            double z = 0.0, tq = 0.0;
+            for (int w = 0; w < SW_PRE_WGS; ++w) { z += part[0][w]; tq += part[1][w]; }
+            pre->z = z; pre->tq = tq;
+            pre->ready = 1;
+        }
+    }
+    __syncthreads();
+    int v0, v1;
+    sw_slice(V, me, v0, v1);
+    for (int v = v0 + tid; v < v1; v += 1024) {
+        const float e = es[v], q = q0[v];
+        const int pos = atomicAdd(&cursor[sw_bin(__fdiv_rn(q, e))], 1);
+        eq_sorted[pos] = make_float2(e, q);
+    }
+}
+
+__global__ __launch_bounds__(1024) void sw_pre_chunks(const int32_t *__restrict__ parent, int M, int V,
+                                                      const float2 *__restrict__ eq_sorted, SwPre *pre)
+{
+    __shared__ double shd[16];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (!sw_root_is_wide(parent, M, tid, shd)) return;
+    const int CH = 64 * ((V + 64 * SW_BINS - 1) / (64 * SW_BINS));
+    for (int c = blockIdx.x * 16 + wv; c < SW_BINS; c += SW_PRE_WGS * 16) {
+        double se = 0.0, sq = 0.0;
+        for (int i = c * CH + lane; i < min(c * CH + CH, V); i += 64) {
+            const float2 x = eq_sorted[i];
+            se += (double)x.x; sq += (double)x.y;
+        }
+        for (int off = 32; off >= 1; off >>= 1) { se += __shfl_xor(se, off); sq += __shfl_xor(sq, off); }
+        if (lane == 0) { pre->chunk_e[c] = se; pre->chunk_q[c] = sq; }
+    }
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__ logits, const float *__restrict__ marg, int B,
                                                         const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
                                                         int M, int V, const float *__restrict__ uniforms,
                                                         float *__restrict__ es, float2 *__restrict__ eq_sorted,
-                                                        int32_t *path, int32_t *n_acc, int32_t *bonus, uint32_t *flag)
+                                                        const SwPre *__restrict__ pre, int32_t *path, int32_t *n_acc,
+                                                        int32_t *bonus, uint32_t *flag)
 {
     __shared__ double shd[16];
     __shared__ float shf[16];
     __shared__ double seg[1024];
     __shared__ double chunkE[SW_BINS], chunkQ[SW_BINS];  // sums of e and q0 over the sorted pairs before chunk c
     __shared__ int start[SW_BINS + 1], cursor[SW_BINS];
-    __shared__ int found, lastpos;
+    __shared__ float2 win[SW_WIN];                        // sorted pairs win_lo .. win_hi - 1 (the threshold only falls,
+    __shared__ int found, lastpos;                        // so the window is refilled towards lower positions)
+    __shared__ float2 child_eq[BTV_MAX_NODES];            // (e, q0) of node c's token, fetched for all nodes at once
+    __shared__ int kid_node[BTV_MAX_NODES];               // the current node's children in node order (prepared row only)
+    __shared__ float kid_u[BTV_MAX_NODES];
+    __shared__ double kid_invT[BTV_MAX_NODES], kid_lhs[BTV_MAX_NODES];    // 1/T when child j is tried; u * q_k[x] of its test
+    __shared__ struct { double alpha, beta, T; int next, accepted, reload_hi, done, nkids, wcount[4]; } fast;
     const int tid = threadIdx.x;
     int cur = -1, n = 0, ui = 0, d = 0;
     for (;;) {
@@ -723,29 +910,171 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
         const int CH = 64 * ((V + 64 * SW_BINS - 1) / (64 * SW_BINS));      // sorted pairs per prefix-sum chunk
         // (the passes are unrolled so that several loads are in flight: one load per iteration leaves a pass bound
         // by the round trip to the L2)
-        float mx = -INFINITY;
-#pragma unroll 8
-        for (int v = tid; v < V; v += 1024) mx = fmaxf(mx, load_logit<BF16>(logits, base + v));
-        mx = block_max(mx, shf, tid);
+        const bool prepared = cur == -1 && pre->ready == 1;      // the root's row was sorted ahead of this kernel
         double z = 0.0, tq = 0.0;
         const bool has_q = d < B;
+        if (prepared) {
+            z = pre->z; tq = pre->tq;
+        } else {
+            float mx = -INFINITY;
 #pragma unroll 8
-        for (int v = tid; v < V; v += 1024) {
-            const float e = expf(load_logit<BF16>(logits, base + v) - mx);
-            es[v] = e; z += (double)e;
-            tq += has_q ? (double)q0[v] : 0.0;
+            for (int v = tid; v < V; v += 1024) mx = fmaxf(mx, load_logit<BF16>(logits, base + v));
+            mx = block_max(mx, shf, tid);
+#pragma unroll 8
+            for (int v = tid; v < V; v += 1024) {
+                const float e = expf(load_logit<BF16>(logits, base + v) - mx);
+                es[v] = e; z += (double)e;
+                tq += has_q ? (double)q0[v] : 0.0;
+            }
+            z = block_sum(z, shd, tid);                          // (its barriers also publish es)
+            tq = block_sum(tq, shd, tid);
         }
-        z = block_sum(z, shd, tid);                              // (its barriers also publish es)
-        tq = block_sum(tq, shd, tid);
         double alpha = 1.0 / z, beta = 0.0, T = tq;
-        auto pk = [&](int v) {                                    // p_k[v]
-            const double x = alpha * (double)es[v] - beta * (double)q0[v];
-            return x > 0.0 ? x : 0.0;
-        };
         int accepted = -1, untried = 0;
         bool binned = false;
-        if (d < B) {
-            for (int c = tid; c < M; c += 1024) untried += parent[c] == cur ? 1 : 0;
+        int win_lo = 0, win_hi = 0;                              // (empty)
+        auto scan_chunks = [&]() {                                // chunkE / chunkQ: per-chunk sums -> sums before the chunk
+            const int lane = tid & 63, wv = tid >> 6;
+            const double e0 = chunkE[2 * tid], e1 = chunkE[2 * tid + 1], q0s = chunkQ[2 * tid], q1s = chunkQ[2 * tid + 1];
+            double ei = e0 + e1, qi = q0s + q1s;
+            for (int off = 1; off < 64; off <<= 1) {
+                const double eo = __shfl_up(ei, off), qo = __shfl_up(qi, off);
+                if (lane >= off) { ei += eo; qi += qo; }
+            }
+            if (lane == 63) { seg[wv] = ei; seg[16 + wv] = qi; }
+            __syncthreads();
+            double eb = 0.0, qb = 0.0;
+            for (int w = 0; w < wv; ++w) { eb += seg[w]; qb += seg[16 + w]; }
+            const double ex = eb + ei - (e0 + e1), qxs = qb + qi - (q0s + q1s);
+            chunkE[2 * tid] = ex; chunkE[2 * tid + 1] = ex + e0;
+            chunkQ[2 * tid] = qxs; chunkQ[2 * tid + 1] = qxs + q0s;
+            __syncthreads();
+        };
+        if (prepared) {                                          // (prepared implies d == 0 < B)
+            for (int b = tid; b <= SW_BINS; b += 1024) start[b] = pre->start[b];
+            for (int c = tid; c < SW_BINS; c += 1024) { chunkE[c] = pre->chunk_e[c]; chunkQ[c] = pre->chunk_q[c]; }
+            __syncthreads();
+            scan_chunks();
+            binned = true;
+        }
+        if (prepared) {
+            // ---- the sorted row is at hand: the children are tried by the first wavefront alone, out of LDS, with no
+            // workgroup barrier per rejection; the others only help to move the window of sorted pairs --------------
+            const int lane = tid & 63, wv = tid >> 6;
+            {   // the children in node order: (node, uniform), their tokens' (e, q0)
+                const bool mine = tid < M && parent[tid] == cur;
+                const unsigned long long bal = __builtin_amdgcn_ballot_w64(mine);
+                if (wv < 4 && lane == 0) fast.wcount[wv] = __builtin_popcountll(bal);
+                __syncthreads();
+                if (mine) {
+                    int j = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+                    for (int w = 0; w < wv; ++w) j += fast.wcount[w];
+                    const int tk = token[tid];
+                    kid_node[j] = tk >= 0 && tk < V ? tid : -1 - tid;      // (negative: not a vocabulary id)
+                    kid_u[j] = uniforms[ui + j];
+                    if (tk >= 0 && tk < V) child_eq[tid] = make_float2(es[tk], q0[tk]);
+                }
+                if (tid == 0) {
+                    fast.alpha = alpha; fast.beta = beta; fast.T = T;
+                    fast.next = 0; fast.accepted = -1; fast.done = 0;
+                    fast.nkids = fast.wcount[0] + fast.wcount[1] + fast.wcount[2] + fast.wcount[3];
+                }
+                __syncthreads();
+            }
+            auto recip = [](double x) {                           // 1/x to within a few ulp: hardware estimate, two Newton steps
+                double r = __builtin_amdgcn_rcp(x);
+                r = __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+                r = __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+                return r;
+            };
+            // T falls by the tried token's q0 whatever the test decides, so every child's 1/T and the left side of its
+            // test are known before the loop: an exclusive prefix sum over the children, 64 at a time
+            if (wv == 0) {
+                double carry = 0.0;
+                for (int j0 = 0; j0 < fast.nkids; j0 += 64) {
+                    const int j = j0 + lane;
+                    const int c = j < fast.nkids ? kid_node[j] : -1;
+                    const double qx = c >= 0 ? (double)child_eq[c].y : 0.0;
+                    double incl = qx;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const double o = __shfl_up(incl, off);
+                        if (lane >= off) incl += o;
+                    }
+                    const double Tj = T - (carry + (incl - qx));
+                    if (j < fast.nkids) {
+                        const double invT = Tj > 0.0 ? recip(Tj) : 0.0;
+                        kid_invT[j] = invT;
+                        kid_lhs[j] = (double)kid_u[j] * (qx * invT);
+                    }
+                    carry += __shfl(incl, 63);
+                }
+            }
+            __syncthreads();
+            for (;;) {
+                if (wv == 0) {
+                    int j = fast.next;
+                    const int nk = fast.nkids;
+                    int acc = -1, want_hi = -1;
+                    alpha = fast.alpha; beta = fast.beta; T = fast.T;
+                    for (; j < nk; ++j) {
+                        const int c = kid_node[j];
+                        if (c < 0) {                             // spent uniform, raised flag, nothing indexed
+                            if (lane == 0) atomicOr(flag, 64u);
+                            continue;
+                        }
+                        const float2 own = child_eq[c];
+                        const double invT = kid_invT[j];
+                        const double px = alpha * (double)own.x - beta * (double)own.y;
+                        if (kid_lhs[j] < (px > 0.0 ? px : 0.0)) { acc = c; ++j; break; }
+                        const double b1 = beta + invT;
+                        const int b = sw_bin((float)(b1 > 0.0 ? alpha * recip(b1) : INFINITY));
+                        const int p0 = start[b], p1 = start[b + 1];
+                        const int ch = min(p0 / CH, SW_BINS - 1), lo = ch * CH;
+                        double zr = 0.0;
+                        if (p1 - lo <= SW_WIN) {
+                            if (lo < win_lo || p1 > win_hi) { want_hi = p1; break; }      // the others help to move the window
+                            for (int i = lo + lane; i < p1; i += 64) {
+                                const float2 x = win[i - win_lo];
+                                const double r = alpha * (double)x.x - b1 * (double)x.y;
+                                zr += r > 0.0 ? r : 0.0;
+                            }
+                        } else {                                 // a bin larger than the window (ratios that nearly all coincide)
+                            for (int i = lo + lane; i < p1; i += 64) {
+                                const float2 x = eq_sorted[i];
+                                const double r = alpha * (double)x.x - b1 * (double)x.y;
+                                zr += r > 0.0 ? r : 0.0;
+                            }
+                        }
+                        zr = wave_sum_f64(zr);
+                        const double below = alpha * chunkE[ch] - b1 * chunkQ[ch];
+                        zr += below > 0.0 ? below : 0.0;
+                        if (zr > 0.0) { const double iz = recip(zr); alpha *= iz; beta = b1 * iz; }
+                    }
+                    if (lane == 0) {
+                        fast.alpha = alpha; fast.beta = beta; fast.T = T;
+                        fast.next = j; fast.accepted = acc; fast.reload_hi = want_hi;
+                        fast.done = want_hi < 0;
+                    }
+                }
+                __syncthreads();
+                if (fast.done) break;
+                win_hi = fast.reload_hi;
+                win_lo = max(win_hi - SW_WIN, 0);
+                for (int i = win_lo + tid; i < win_hi; i += 1024) win[i - win_lo] = eq_sorted[i];
+                __syncthreads();
+            }
+            alpha = fast.alpha; beta = fast.beta; T = fast.T;
+            accepted = fast.accepted;
+            ui += fast.next;                                     // one uniform per child tried
+            __syncthreads();                                     // (fast is rewritten at the next node only after everyone has read it)
+        } else if (d < B) {
+            // one round trip for every child's own e and q0, instead of one per child inside the loop
+            for (int c = tid; c < M; c += 1024) {
+                const bool mine = parent[c] == cur;
+                untried += mine ? 1 : 0;
+                const int tk = token[c];
+                if (mine && tk >= 0 && tk < V) child_eq[c] = make_float2(es[tk], q0[tk]);
+            }
             untried = (int)block_sum((double)untried, shd, tid);          // children of this node still to be tried
             for (int c = 0; c < M; ++c) {
                 if (parent[c] != cur) continue;                  // uniform across the workgroup
@@ -756,8 +1085,10 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                     --untried;
                     continue;
                 }
-                const double invT = T > 0.0 ? 1.0 / T : 0.0, qx = (double)q0[tk];
-                if (u * (qx * invT) < pk(tk)) { accepted = c; break; }
+                const float2 own = child_eq[c];
+                const double invT = T > 0.0 ? 1.0 / T : 0.0, qx = (double)own.y;
+                const double px = alpha * (double)own.x - beta * qx;     // p_k of the child's token
+                if (u * (qx * invT) < (px > 0.0 ? px : 0.0)) { accepted = c; break; }
                 const double b1 = beta + invT;
                 --untried;
                 if (!binned && untried >= SW_BUILD_MIN) {         // enough tests may follow for the sort to pay
@@ -804,21 +1135,8 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                             if (lane == 0) { chunkE[c] = se; chunkQ[c] = sq; }
                         }
                         __syncthreads();
-                        const double e0 = chunkE[2 * tid], e1 = chunkE[2 * tid + 1], q0s = chunkQ[2 * tid], q1s = chunkQ[2 * tid + 1];
-                        double ei = e0 + e1, qi = q0s + q1s;
-                        for (int off = 1; off < 64; off <<= 1) {
-                            const double eo = __shfl_up(ei, off), qo = __shfl_up(qi, off);
-                            if (lane >= off) { ei += eo; qi += qo; }
-                        }
-                        if (lane == 63) { seg[wv] = ei; seg[16 + wv] = qi; }
-                        __syncthreads();
-                        double eb = 0.0, qb = 0.0;
-                        for (int w = 0; w < wv; ++w) { eb += seg[w]; qb += seg[16 + w]; }
-                        const double ex = eb + ei - (e0 + e1), qxs = qb + qi - (q0s + q1s);
-                        chunkE[2 * tid] = ex; chunkE[2 * tid + 1] = ex + e0;
-                        chunkQ[2 * tid] = qxs; chunkQ[2 * tid + 1] = qxs + q0s;
                     }
-                    __syncthreads();
+                    scan_chunks();
                     binned = true;
                 }
                 double zr = 0.0;                                 // residual max(p_k - q_k, 0): its sum
@@ -832,7 +1150,18 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                     const int b = sw_bin((float)(alpha / b1));   // b1 = 0: the threshold is +inf, every finite ratio is below it
                     const int p0 = start[b], p1 = start[b + 1];
                     const int ch = min(p0 / CH, SW_BINS - 1), lo = ch * CH;
-                    for (int i = lo + tid; i < p1; i += 1024) { const float2 x = eq_sorted[i]; resid(x.x, x.y); }
+                    if (p1 - lo <= SW_WIN) {
+                        if (lo < win_lo || p1 > win_hi) {        // (uniform) refill: the window ends at this bin's end
+                            __syncthreads();
+                            win_hi = p1;
+                            win_lo = max(p1 - SW_WIN, 0);
+                            for (int i = win_lo + tid; i < win_hi; i += 1024) win[i - win_lo] = eq_sorted[i];
+                            __syncthreads();
+                        }
+                        for (int i = lo + tid; i < p1; i += 1024) { const float2 x = win[i - win_lo]; resid(x.x, x.y); }
+                    } else {                                     // a bin larger than the window (ratios that nearly all coincide)
+                        for (int i = lo + tid; i < p1; i += 1024) { const float2 x = eq_sorted[i]; resid(x.x, x.y); }
+                    }
                     zr = block_sum(zr, shd, tid);
                     const double below = alpha * chunkE[ch] - b1 * chunkQ[ch];
                     zr += below > 0.0 ? below : 0.0;
@@ -848,7 +1177,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                     }
                     zr = block_sum(zr, shd, tid);
                 }
-                if (zr > 0.0) { alpha /= zr; beta = b1 / zr; }
+                if (zr > 0.0) { const double iz = 1.0 / zr; alpha *= iz; beta = b1 * iz; }
                 T -= qx;                                         // drafted without replacement
             }
         }
@@ -858,21 +1187,36 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
             __syncthreads();                                     // everyone is done with es before it is rewritten
             continue;
         }
-        // bonus: smallest v with cumsum(p_k)[v] > u.  Wavefront w owns a contiguous stretch of the vocabulary and reads
-        // it 64 tokens at a time (coalesced); the stretches' totals tell which wavefront holds the crossing, and only
-        // that one scans its stretch again with a running prefix.
+        // bonus: smallest v with cumsum(p_k)[v] > u.  Wavefront w owns a contiguous stretch of the vocabulary; the
+        // stretches' totals tell which wavefront holds the crossing, and only that one looks at its stretch again.
         const double u = (double)uniforms[ui++];
         const int lane = tid & 63, wv = tid >> 6;
-        const int stretch = ((V + 15) / 16 + 63) / 64 * 64, w0 = min(wv * stretch, V), w1 = min(w0 + stretch, V);
-        auto pv = [&](int v) {
-            const double x = has_q ? alpha * (double)es[v] - beta * (double)q0[v] : alpha * (double)es[v];
+        auto pv2 = [&](float ev, float qv) {
+            const double x = has_q ? alpha * (double)ev - beta * (double)qv : alpha * (double)ev;
             return x > 0.0 ? x : 0.0;
         };
+        auto pv = [&](int v) { return pv2(es[v], has_q ? q0[v] : 0.f); };
+        const bool wide = vec4 && (reinterpret_cast<uintptr_t>(es) & 15) == 0;
+        // wide loads: a wave instruction covers 256 consecutive tokens, four per lane; stretches are whole instructions
+        const int stretch = wide ? ((V + 15) / 16 + 255) / 256 * 256 : ((V + 15) / 16 + 63) / 64 * 64;
+        const int w0 = min(wv * stretch, V), w1 = min(w0 + stretch, V);
         double loc = 0.0;
         int lp = -1;
+        if (wide) {
 #pragma unroll 4
-        for (int v = w0 + lane; v < w1; v += 64) { const double x = pv(v); loc += x; lp = x > 0.0 ? v : lp; }
-        for (int off = 32; off >= 1; off >>= 1) { loc += __shfl_xor(loc, off); lp = max(lp, __shfl_xor(lp, off)); }
+            for (int v = w0 + lane * 4; v < w1; v += 256) {
+                const float4 a = *reinterpret_cast<const float4 *>(es + v);
+                const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + v) : make_float4(0.f, 0.f, 0.f, 0.f);
+                const double x0 = pv2(a.x, q.x), x1 = pv2(a.y, q.y), x2 = pv2(a.z, q.z), x3 = pv2(a.w, q.w);
+                loc += (x0 + x1) + (x2 + x3);
+                lp = x3 > 0.0 ? v + 3 : x2 > 0.0 ? v + 2 : x1 > 0.0 ? v + 1 : x0 > 0.0 ? v : lp;
+            }
+        } else {
+#pragma unroll 4
+            for (int v = w0 + lane; v < w1; v += 64) { const double x = pv(v); loc += x; lp = x > 0.0 ? v : lp; }
+        }
+        loc = wave_sum_f64(loc);
+        for (int off = 32; off >= 1; off >>= 1) lp = max(lp, __shfl_xor(lp, off));
         __syncthreads();                                         // (seg may still be in use by the sort's scans)
         if (lane == 0) seg[wv] = loc;
         if (tid == 0) { found = INT_MAX; lastpos = 0; }
@@ -883,16 +1227,65 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
         if (u >= before && u < before + seg[wv]) {               // exactly one wavefront, or none if u is past the total
             double running = before;
             int hit = INT_MAX;
-            for (int v0 = w0; v0 < w1 && hit == INT_MAX; v0 += 64) {
-                const int v = v0 + lane;
-                double x = v < w1 ? pv(v) : 0.0;
-                for (int off = 1; off < 64; off <<= 1) {         // inclusive prefix over the 64 tokens
-                    const double o = __shfl_up(x, off);
-                    if (lane >= off) x += o;
+            if (wide) {
+                // eight instructions' worth of tokens at a time: their totals one after the other until the crossing
+                // instruction is known, then the lanes' prefix inside it, then the token inside the lane
+                for (int g0 = w0; g0 < w1 && hit == INT_MAX; g0 += 8 * 256) {
+                    double part[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const int v = g0 + k * 256 + lane * 4;
+                        part[k] = 0.0;
+                        if (v < w1) {
+                            const float4 a = *reinterpret_cast<const float4 *>(es + v);
+                            const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + v) : make_float4(0.f, 0.f, 0.f, 0.f);
+                            part[k] = (pv2(a.x, q.x) + pv2(a.y, q.y)) + (pv2(a.z, q.z) + pv2(a.w, q.w));
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        if (hit != INT_MAX) break;
+                        const double tot = wave_sum_f64(part[k]);
+                        if (running + tot > u) {                 // (uniform) the crossing lies in this instruction's 256 tokens
+                            const int v = g0 + k * 256 + lane * 4;
+                            double x0 = 0.0, x1 = 0.0, x2 = 0.0, x3 = 0.0;
+                            if (v < w1) {
+                                const float4 a = *reinterpret_cast<const float4 *>(es + v);
+                                const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + v) : make_float4(0.f, 0.f, 0.f, 0.f);
+                                x0 = pv2(a.x, q.x); x1 = pv2(a.y, q.y); x2 = pv2(a.z, q.z); x3 = pv2(a.w, q.w);
+                            }
+                            double incl = (x0 + x1) + (x2 + x3);
+                            const double own = incl;
+                            for (int off = 1; off < 64; off <<= 1) {   // inclusive prefix over the lanes
+                                const double o = __shfl_up(incl, off);
+                                if (lane >= off) incl += o;
+                            }
+                            const double excl = running + (incl - own);
+                            int mine = INT_MAX;                  // first of this lane's four tokens whose cumulative sum passes u
+                            if (v < w1) {
+                                if (excl + x0 > u) mine = v;
+                                else if (excl + (x0 + x1) > u) mine = v + 1;
+                                else if (excl + ((x0 + x1) + x2) > u) mine = v + 2;
+                                else if (excl + ((x0 + x1) + (x2 + x3)) > u) mine = v + 3;
+                            }
+                            for (int off = 32; off >= 1; off >>= 1) mine = min(mine, __shfl_xor(mine, off));
+                            if (mine != INT_MAX) hit = mine;     // (else rounding: the crossing is the next positive token)
+                        }
+                        running += tot;
+                    }
                 }
-                const unsigned long long over = __builtin_amdgcn_ballot_w64(v < w1 && running + x > u);
-                if (over) hit = v0 + __builtin_ctzll(over);
-                running += __shfl(x, 63);
+            } else {
+                for (int v0 = w0; v0 < w1 && hit == INT_MAX; v0 += 64) {
+                    const int v = v0 + lane;
+                    double x = v < w1 ? pv(v) : 0.0;
+                    for (int off = 1; off < 64; off <<= 1) {     // inclusive prefix over the 64 tokens
+                        const double o = __shfl_up(x, off);
+                        if (lane >= off) x += o;
+                    }
+                    const unsigned long long over = __builtin_amdgcn_ballot_w64(v < w1 && running + x > u);
+                    if (over) hit = v0 + __builtin_ctzll(over);
+                    running += __shfl(x, 63);
+                }
             }
             if (lane == 0) found = hit != INT_MAX ? hit : max(lp, 0);     // rounding left the crossing just past the stretch
         }
@@ -919,7 +1312,7 @@ extern "C" {
 size_t btv_tree_accept_workspace(int M, int V, int stochastic)
 {
     if (M < 1 || M > BTV_MAX_NODES || V < 1) return 0;
-    if (stochastic) return BTV_WS_HEADER + 3 * btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
+    if (stochastic) return BTV_WS_HEADER + 3 * btv_align_up((size_t)V * 4, BTV_WS_ALIGN) + btv_align_up(sizeof(SwPre), BTV_WS_ALIGN);
     return BTV_WS_HEADER + btv_align_up((size_t)(M + 1) * sizeof(unsigned long long), BTV_WS_ALIGN);
 }
 
@@ -1026,12 +1419,25 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     const size_t vb = btv_align_up((size_t)V * 4, BTV_WS_ALIGN);
     float *es = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
     float2 *eq_sorted = reinterpret_cast<float2 *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + vb);
+    SwPre *pre = reinterpret_cast<SwPre *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER + 3 * vb);
+    uint32_t *flag = static_cast<uint32_t *>(ws);
+    // the root's row, prepared by many workgroups when the root has a wide fan (each kernel finds that out itself)
+    if (dtype == BTV_BF16) {
+        hipLaunchKernelGGL(sw_pre_max<true>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, parent, M, V, pre);
+        hipLaunchKernelGGL(sw_pre_exp<true>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, marginals, parent, M, V, es, pre);
+    } else {
+        hipLaunchKernelGGL(sw_pre_max<false>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, parent, M, V, pre);
+        hipLaunchKernelGGL(sw_pre_exp<false>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, marginals, parent, M, V, es, pre);
+    }
+    hipLaunchKernelGGL(sw_pre_scatter, dim3(SW_PRE_WGS), dim3(1024), 0, st, marginals, parent, M, V, es, eq_sorted, pre);
+    hipLaunchKernelGGL(sw_pre_chunks, dim3(SW_PRE_WGS), dim3(1024), 0, st, parent, M, V, eq_sorted, pre);
+    BTV_HIP(hipGetLastError());
     if (dtype == BTV_BF16)
         hipLaunchKernelGGL(stochastic_walk<true>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, eq_sorted, path, n_acc, bonus, static_cast<uint32_t *>(ws));
+                           uniforms, es, eq_sorted, pre, path, n_acc, bonus, flag);
     else
         hipLaunchKernelGGL(stochastic_walk<false>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, eq_sorted, path, n_acc, bonus, static_cast<uint32_t *>(ws));
+                           uniforms, es, eq_sorted, pre, path, n_acc, bonus, flag);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
