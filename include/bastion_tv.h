@@ -306,7 +306,7 @@ int btv_tree_verify_attn_paged_fp8kv(const void *Q, const void *K8pool, const vo
  * (unchanged if that is all zero) and q[x] <- 0, q renormalised; when no child is accepted the
  * bonus token is the inverse-CDF sample of p with the next uniform.  uniforms [M+1] fp32 in
  * [0,1), consumed in order.  marginals [B,V] fp32 as given to tree_build.
- *   Five small launches ahead of the walk prepare the root's row (softmax numerators and their
+ *   Four small launches ahead of the walk prepare the root's row (softmax numerators and their
  *   (e, q) pairs sorted by q/e) on many CUs when the root has 6 children or more; the walk
  *   itself is one workgroup.
  * ------------------------------------------------------------------------------------------- */
