@@ -150,6 +150,33 @@ def time_loop(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def graph_time(torch, fn, calls=20, reps=10):
+    """Average milliseconds per call of fn with `calls` of them captured in a HIP graph and replayed: the GPU's own
+    time per call, without the host's launch path (None if the capture fails)."""
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fn()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(calls):
+                    fn()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * calls)
+    except RuntimeError as e:
+        print(f"bench.py: graph timing skipped: {str(e)[:120]}", file=sys.stderr)
+        return None
+
+
 def cpu_model():
     try:
         for line in open("/proc/cpuinfo"):
@@ -576,6 +603,9 @@ def main():
     attn_each = {"median": round(each[len(each) // 2], 3), "p10": round(each[len(each) // 10], 3),
                  "p90": round(each[(9 * len(each)) // 10], 3), "launches": len(each)}
     accept_ms = time_loop(torch, path.accept, args.steps, args.warmup)
+    us = lambda ms: None if ms is None else round(ms * 1e3, 3)
+    stage_graph = {"tree_build": us(graph_time(torch, path.build)), "tree_verify_attn": us(graph_time(torch, path.attn)),
+                   "tree_accept_greedy": us(graph_time(torch, path.accept))}
     # KV commit of a 32-layer cache of this shape (bf16), an accepted path of 8 of the N nodes
     kvc = {}
     try:
@@ -694,7 +724,9 @@ def main():
         "step_breakdown_us": {"tree_build": round(build_ms * 1e3, 3), "tree_verify_attn": round(attn_ms * 1e3, 3),
                               "tree_accept_greedy": round(accept_ms * 1e3, 3),
                               "eager_step": round(eager_ms_per_step * 1e3, 3), "eager_host_wall_per_step": round(wall_ms * 1e3, 3),
-                              "stages_timed": "each stage in a back-to-back eager loop of its own"},
+                              "stages_timed": "each stage in a back-to-back eager loop of its own (one Python call and its launches "
+                                              "per iteration: a stage shorter than the host's launch path shows the host)",
+                              "stages_replayed_from_hip_graph": stage_graph},
         "launch": launch,
         "roofline": roofline, "cpu_baseline": cpu, "curve_L8192": curve, "adaptive_budget": adaptive, "latency_calibration": calib,
         "kv_commit": kvc, "lm_head": lmh, "topologies": topo, "fp8_kv": fp8kv, "other_configs": configs,
