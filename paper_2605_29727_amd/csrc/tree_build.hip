@@ -484,26 +484,66 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 // Bitonic sort of P2 (a power of two, at least 128) 64-bit keys in LDS, largest first, by 256 threads.  Every
 // compare-exchange at a distance below 128 happens in registers: a wavefront holds a block of 128 keys two per lane
 // (key e * 64 + lane of the block in register e), distance 64 pairs a lane's own two registers, shorter distances pair
-// lanes (two 32-bit cross-lane moves per key).  Only the distances from 128 up go through LDS, one block barrier
+// lanes (the network is unrolled, every stage takes the cross-lane move that fits its distance).  Only the distances from 128 up go through LDS, one block barrier
 // each.  base = index of the block's first key in the whole array: it fixes each pair's direction.
-__device__ __forceinline__ void wave_stages(u64 &k0, u64 &k1, int base, int k_lo, int k_hi, int j_top, int lane)
+// x of lane (l ^ J) for J = 1 .. 32, on the vector ALU alone: quad permutes for 1 and 2, two row shifts (each written
+// to the banks of four lanes it is right for) for 4 and 8, the row / half-wave swaps for 16 and 32.  The same data
+// through ds_bpermute costs a trip through the LDS crossbar per 32 bits and stage.
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane)
 {
-    for (int k = k_lo; k <= k_hi; k <<= 1)
-        for (int j = min(k >> 1, j_top); j > 0; j >>= 1) {
-            if (j == 64) {
-                const bool desc = ((base + lane) & k) == 0;
-                const u64 hi = k0 > k1 ? k0 : k1, lo = k0 > k1 ? k1 : k0;
-                k0 = desc ? hi : lo;
-                k1 = desc ? lo : hi;
-            } else {
-                const bool lower = (lane & j) == 0;               // this lane holds the pair's lower index
-                const u64 p0 = ((u64)(uint32_t)__shfl_xor((int)(uint32_t)(k0 >> 32), j) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)k0, j);
-                const u64 p1 = ((u64)(uint32_t)__shfl_xor((int)(uint32_t)(k1 >> 32), j) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)k1, j);
-                const bool max0 = lower == (((base + lane) & k) == 0), max1 = lower == (((base + 64 + lane) & k) == 0);
-                k0 = (max0 == (k0 > p0)) ? k0 : p0;
-                k1 = (max1 == (k1 > p1)) ? k1 : p1;
-            }
-        }
+    const int v = (int)x;
+    if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
+    else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); // quad_perm [2,3,0,1]
+    else if constexpr (J == 4) {
+        const int t = __builtin_amdgcn_update_dpp(v, v, 0x104, 0xF, 0x5, false);                  // row_shl:4 -> lanes with bit 2 clear
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, v, 0x114, 0xF, 0xA, false);               // row_shr:4 -> lanes with bit 2 set
+    } else if constexpr (J == 8) {
+        const int t = __builtin_amdgcn_update_dpp(v, v, 0x108, 0xF, 0x3, false);                  // row_shl:8 -> lanes 0-7 of a row
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, v, 0x118, 0xF, 0xC, false);               // row_shr:8 -> lanes 8-15
+    } else if constexpr (J == 16) {
+        const auto sw = __builtin_amdgcn_permlane16_swap(x, x, false, false);                       // odd rows of [0] <-> even rows of [1]
+        return (lane & 16) ? sw[0] : sw[1];
+    } else {
+        const auto sw = __builtin_amdgcn_permlane32_swap(x, x, false, false);                       // upper half of [0] <-> lower half of [1]
+        return (lane & 32) ? sw[0] : sw[1];
+    }
+}
+
+// One compare-exchange stage at distance J of the bitonic network over a block of 128 keys (two per lane); kbit = the
+// merge size the stage belongs to (its bit of a key's index gives the direction).
+template <int J>
+__device__ __forceinline__ void wave_stage(u64 &k0, u64 &k1, int base, int kbit, int lane)
+{
+    if constexpr (J == 64) {
+        const bool desc = ((base + lane) & kbit) == 0;
+        const u64 hi = k0 > k1 ? k0 : k1, lo = k0 > k1 ? k1 : k0;
+        k0 = desc ? hi : lo;
+        k1 = desc ? lo : hi;
+    } else {
+        const bool lower = (lane & J) == 0;                       // this lane holds the pair's lower index
+        const u64 p0 = ((u64)lane_xor<J>((uint32_t)(k0 >> 32), lane) << 32) | lane_xor<J>((uint32_t)k0, lane);
+        const u64 p1 = ((u64)lane_xor<J>((uint32_t)(k1 >> 32), lane) << 32) | lane_xor<J>((uint32_t)k1, lane);
+        const bool max0 = lower == (((base + lane) & kbit) == 0), max1 = lower == (((base + 64 + lane) & kbit) == 0);
+        k0 = (max0 == (k0 > p0)) ? k0 : p0;
+        k1 = (max1 == (k1 > p1)) ? k1 : p1;
+    }
+}
+
+// the stages of one merge of size kbit, from distance J down to 1
+template <int J>
+__device__ __forceinline__ void wave_merge(u64 &k0, u64 &k1, int base, int kbit, int lane)
+{
+    wave_stage<J>(k0, k1, base, kbit, lane);
+    if constexpr (J > 1) wave_merge<J / 2>(k0, k1, base, kbit, lane);
+}
+
+// the whole network on one block of 128: merges of size 2, 4, ..., 128
+template <int K>
+__device__ __forceinline__ void wave_sort(u64 &k0, u64 &k1, int base, int lane)
+{
+    if constexpr (K > 2) wave_sort<K / 2>(k0, k1, base, lane);
+    wave_merge<K / 2>(k0, k1, base, K, lane);
 }
 
 __device__ __forceinline__ void bitonic_desc(u64 *key, int P2, int tid)
@@ -512,7 +552,7 @@ __device__ __forceinline__ void bitonic_desc(u64 *key, int P2, int tid)
     __syncthreads();
     for (int blk = w; blk * 128 < P2; blk += 4) {                  // every block of 128 sorted on its own
         u64 k0 = key[blk * 128 + lane], k1 = key[blk * 128 + 64 + lane];
-        wave_stages(k0, k1, blk * 128, 2, 128, 64, lane);
+        wave_sort<128>(k0, k1, blk * 128, lane);
         key[blk * 128 + lane] = k0;
         key[blk * 128 + 64 + lane] = k1;
     }
@@ -528,7 +568,7 @@ __device__ __forceinline__ void bitonic_desc(u64 *key, int P2, int tid)
         __syncthreads();
         for (int blk = w; blk * 128 < P2; blk += 4) {
             u64 k0 = key[blk * 128 + lane], k1 = key[blk * 128 + 64 + lane];
-            wave_stages(k0, k1, blk * 128, k, k, 64, lane);
+            wave_merge<64>(k0, k1, blk * 128, k, lane);
             key[blk * 128 + lane] = k0;
             key[blk * 128 + 64 + lane] = k1;
         }
