@@ -1042,24 +1042,49 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             // ---- iteration i (1 <= i <= Tf - 2): x holds the scores of tile i, pprev the probabilities of tile i-1, pcur
             // receives those of tile i ----
             // On entry the LDS queue holds [V(i-1) first half, K(i+1) low half].
-            auto iter = [&](bf16x8 (&pprev)[2], bf16x8 (&pcur)[2], int i) {
+            // Loop-invariant operand addresses for the trips whose ring slots are known at compile time (eight trips
+            // unrolled, one per slot): the slot is an immediate offset then, which reaches four slots from one base,
+            // and a trip needs no address arithmetic at all (20 instructions of it otherwise).
+            uint32_t ak[DS], akh[DS], av[DT], avh[DT];
+#pragma unroll
+            for (int s2 = 0; s2 < DS; ++s2) { ak[s2] = kbase ^ (uint32_t)(s2 << 5); akh[s2] = ak[s2] + 4u * LD::STAGE; }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) { av[dt] = vbase ^ (uint32_t)(dt << 6); avh[dt] = av[dt] + 4u * LD::STAGE; }
+            auto rk = [&](auto slot, auto half) {
+                constexpr int S = decltype(slot)::value & 7, H = decltype(half)::value;
+                if constexpr (S < 4) read_k_half<D, S, H>(ak, kh); else read_k_half<D, S - 4, H>(akh, kh);
+            };
+            auto rv = [&](auto slot, auto mm) {
+                constexpr int S = decltype(slot)::value & 7, MM = decltype(mm)::value;
+                if constexpr (S < 4) read_v_half<D, S, MM>(av, vh); else read_v_half<D, S - 4, MM>(avh, vh);
+            };
+            // ph: the trip's tile number modulo 8 as a constant, or -1 for a trip with its addresses in registers
+            auto iter = [&](bf16x8 (&pprev)[2], bf16x8 (&pcur)[2], int i, auto ph) {
+                constexpr int PH = decltype(ph)::value;
+                using C0 = std::integral_constant<int, 0>;
+                using C1 = std::integral_constant<int, 1>;
                 // tiles <= i+2 are read in this iteration; the barrier also tells that every wave is done with
                 // iteration i-1, i.e. with tile i-2, whose slot the next fill takes
                 wait_tiles<LPW, 3>(issued - st0 - i - 3);
                 __builtin_amdgcn_s_barrier();
                 const bool fill_now = issued < st1;              // tile i+6 goes into the slot tile i-2 left
-                const uint32_t k1 = kbase + slot_off(i + 1), k2 = kbase + slot_off(i + 2);
-                const uint32_t v0 = vbase + slot_off(i - 1), v1 = vbase + slot_off(i);
+                uint32_t k1 = 0, k2 = 0, v0 = 0, v1 = 0;
+                if constexpr (PH < 0) {
+                    k1 = kbase + slot_off(i + 1); k2 = kbase + slot_off(i + 2);
+                    v0 = vbase + slot_off(i - 1); v1 = vbase + slot_off(i);
+                }
                 float ts = 0.f;
                 wait_v_half<DT, KH>(vh);                          // V(i-1) first half
                 pv_half<DT>(vh, pprev[0], oacc);
                 if (fill_now) issue_part(std::integral_constant<int, 0>{});      // behind four MFMAs: its issue stall is covered
-                read_v_half_at<D, 1>(v0, vh);                     // V(i-1) second half  queue: K(i+1)lo, V(i-1)b
+                if constexpr (PH < 0) read_v_half_at<D, 1>(v0, vh);                     // V(i-1) second half  queue: K(i+1)lo, V(i-1)b
+                else rv(std::integral_constant<int, PH + 7>{}, C1{});
                 exp_half(x, 0, pcur[0], ts);
                 wait_v_half<DT, 0>(vh);                           // V(i-1) second half (and K(i+1) low)
                 pv_half<DT>(vh, pprev[1], oacc);
                 if (fill_now) issue_part(std::integral_constant<int, 1>{});
-                read_v_half_at<D, 0>(v1, vh);                     // V(i) first half     queue: V(i)a
+                if constexpr (PH < 0) read_v_half_at<D, 0>(v1, vh);                     // V(i) first half     queue: V(i)a
+                else rv(std::integral_constant<int, PH>{}, C0{});
                 exp_half(x, 1, pcur[1], ts);
                 if (__builtin_amdgcn_ballot_w64(!(ts <= GROW)) != 0ull) regrow(pcur, ts);     // rare
                 l_run += ts;
@@ -1067,10 +1092,12 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 for (int v = 0; v < 16; ++v) x[v] = negm;
                 wait_k_half<KH, 2 * DT>(kh);                      // K(i+1) low (landed above; binds the registers)
                 x = qk_half<DS, 0>(kh, qreg, x);
-                read_k_half_at<D, 1>(k1, kh);                     // K(i+1) high         queue: V(i)a, K(i+1)hi
+                if constexpr (PH < 0) read_k_half_at<D, 1>(k1, kh);                     // K(i+1) high         queue: V(i)a, K(i+1)hi
+                else rk(std::integral_constant<int, PH + 1>{}, C1{});
                 wait_k_half<KH, 0>(kh);                           // K(i+1) high (and V(i) first half)
                 x = qk_half<DS, 1>(kh, qreg, x);
-                read_k_half_at<D, 0>(k2, kh);                     // K(i+2) low          queue: K(i+2)lo (V(i)a has landed)
+                if constexpr (PH < 0) read_k_half_at<D, 0>(k2, kh);                     // K(i+2) low          queue: K(i+2)lo (V(i)a has landed)
+                else rk(std::integral_constant<int, PH + 2>{}, C0{});
                 if (fill_now) { ++issued; if (++islot == NT) islot = 0; }
             };
             // ---- epilogue: tile e = Tf - 1 has its scores, tile e-1 its probabilities (pp); nothing left to overlap ----
@@ -1098,8 +1125,17 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             };
             // One iteration per trip, the new probabilities copied into place at its end (8 moves): with the roles of
             // two register sets alternating over an unrolled pair the allocator shuffles tuples and spills.
-            for (int i = 1; i <= Tf - 2; ++i) {
-                iter(pa, pc, i);
+            int i = 1;
+            for (; i + 7 <= Tf - 2; i += 8) {                    // tile i is in ring slot 1 here: eight trips, one per slot
+                // (the two probability buffers swap roles from trip to trip: no copies inside the group)
+                // (one barrier for two trips, with the fills one tile less ahead, measured the same)
+#define BTV_TRIP(k, slot, from, to) iter(from, to, i + k, std::integral_constant<int, slot>{});
+                BTV_TRIP(0, 1, pa, pc) BTV_TRIP(1, 2, pc, pa) BTV_TRIP(2, 3, pa, pc) BTV_TRIP(3, 4, pc, pa)
+                BTV_TRIP(4, 5, pa, pc) BTV_TRIP(5, 6, pc, pa) BTV_TRIP(6, 7, pa, pc) BTV_TRIP(7, 0, pc, pa)
+#undef BTV_TRIP
+            }
+            for (; i <= Tf - 2; ++i) {
+                iter(pa, pc, i, std::integral_constant<int, -1>{});
 #pragma unroll
                 for (int mm = 0; mm < 2; ++mm) pa[mm] = pc[mm];
             }
