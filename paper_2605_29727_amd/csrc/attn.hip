@@ -1002,10 +1002,14 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             f32x16 x;
             bf16x8 pa[2], pc[2];
             float negm;                                          // minus the reference: what the score accumulator starts from
+            f32x16 negm16;                                       // ... kept splatted: the first score MFMA of a tile takes it as its
+                                                                 // addend and writes x, so no tile pays sixteen moves for it
             // the tile's probabilities against a new reference: its own maximum joins the old one; sums, accumulator follow
             auto regrow = [&](bf16x8 (&pn)[2], float &ts) {
                 const float dlt = fmaxf(tile_max(x), 0.f), alpha = __builtin_amdgcn_exp2f(-dlt);
                 negm -= dlt;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) negm16[v] = negm;
                 l_run *= alpha;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) x[v] -= dlt;
@@ -1033,8 +1037,8 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 exp_half(x, 0, pa[0], l_run);                    // x <= 0 here: no growth check
                 exp_half(x, 1, pa[1], l_run);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) x[v] = negm;
-                wait_k_half<KH, 0>(kh); x = qk_half<DS, 0>(kh, qreg, x);
+                for (int v = 0; v < 16; ++v) negm16[v] = negm;
+                wait_k_half<KH, 0>(kh); x = qk_half<DS, 0>(kh, qreg, negm16);
                 read_k_half_at<D, 1>(kbase + slot_off(1), kh); wait_k_half<KH, 0>(kh); x = qk_half<DS, 1>(kh, qreg, x);
                 read_v_half_at<D, 0>(vbase, vh);                 // queue: V(0) first half, K(2) low half
                 read_k_half_at<D, 0>(kbase + slot_off(2), kh);
@@ -1080,18 +1084,18 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 if constexpr (PH < 0) read_v_half_at<D, 1>(v0, vh);                     // V(i-1) second half  queue: K(i+1)lo, V(i-1)b
                 else rv(std::integral_constant<int, PH + 7>{}, C1{});
                 exp_half(x, 0, pcur[0], ts);
+                __builtin_amdgcn_sched_barrier(0);                // (the exponentials stay in front of the wait: they cover the reads)
                 wait_v_half<DT, 0>(vh);                           // V(i-1) second half (and K(i+1) low)
                 pv_half<DT>(vh, pprev[1], oacc);
                 if (fill_now) issue_part(std::integral_constant<int, 1>{});
                 if constexpr (PH < 0) read_v_half_at<D, 0>(v1, vh);                     // V(i) first half     queue: V(i)a
                 else rv(std::integral_constant<int, PH>{}, C0{});
                 exp_half(x, 1, pcur[1], ts);
+                __builtin_amdgcn_sched_barrier(0);
                 if (__builtin_amdgcn_ballot_w64(!(ts <= GROW)) != 0ull) regrow(pcur, ts);     // rare
                 l_run += ts;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) x[v] = negm;
                 wait_k_half<KH, 2 * DT>(kh);                      // K(i+1) low (landed above; binds the registers)
-                x = qk_half<DS, 0>(kh, qreg, x);
+                x = qk_half<DS, 0>(kh, qreg, negm16);
                 if constexpr (PH < 0) read_k_half_at<D, 1>(k1, kh);                     // K(i+1) high         queue: V(i)a, K(i+1)hi
                 else rk(std::integral_constant<int, PH + 1>{}, C1{});
                 wait_k_half<KH, 0>(kh);                           // K(i+1) high (and V(i) first half)
