@@ -1512,10 +1512,10 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2, int force_s
     // Ragged batches take the small workgroup whatever the largest tree: 64-row blocks pad the smaller trees less,
     // and two such workgroups share a CU, so one's prologue and store overlap the other's main loop.
     if (rows_g <= 128 || batch > 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
-    // 1024 packed rows or more (256 nodes at 4 query heads per KV head, 128 at 8): the software-pipelined 256-row
-    // shape, measured 5 % ahead at the 70B shape with a 32k prefix and level at 256 nodes of the 8B shape; below,
-    // pairs of waves alternating over the tiles are 3-8 % ahead.  The FP8 cache has only the latter.
-    else if (eb == 2 && rows_g >= 1024) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
+    // 768 packed rows or more (192 nodes at 4 query heads per KV head, 96 at 8): the software-pipelined 256-row
+    // shape, measured 12 % ahead at the 70B shape with a 32k prefix, 4 % at 256 nodes of the 8B shape, 2 % at 192;
+    // below, pairs of waves alternating over the tiles are 3-8 % ahead.  The FP8 cache has only the latter.
+    else if (eb == 2 && rows_g >= 768) { pl.rw = 8; pl.kw = 1; pl.nt = 8; }
     else { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
     if (force_shape == 1) { pl.rw = 2; pl.kw = 2; pl.nt = 5; }
     if (force_shape == 2) { pl.rw = 4; pl.kw = 2; pl.nt = 8; }
@@ -1534,7 +1534,9 @@ Plan make_plan(int M, int L, int Hq, int Hkv, int batch, int eb = 2, int force_s
     // (measured on ragged and uniform batches of 4 to 16 requests: within 1.5x of the best shape and split count
     // found for each; a uniform batch would do best with one unit per CU, which the host cannot tell from here).
     int target = rows_g <= 64 ? 512 : 256;
-    int want = force_split > 0 ? force_split : (target + base - 1) / base;
+    // (rounded down: one split more than the CUs hold sends a second, nearly empty round of workgroups through the
+    // chip, e.g. 6 splits x 48 = 288 workgroups at 192 nodes took 61 us against 43 us for 5 x 48 = 240)
+    int want = force_split > 0 ? force_split : std::max(1, target / base);
     if (batch > 1 && force_split <= 0) want = std::max(1, std::min(8, pl.stages / 32));
     // a split should stream at least 8 tiles (256 keys) unless the caller forces it
     if (force_split <= 0) want = std::min(want, std::max(1, pl.stages / 8));
