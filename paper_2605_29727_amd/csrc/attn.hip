@@ -375,11 +375,8 @@ __device__ __forceinline__ void lds_wait_vt(bf16x4 (&va)[DT][2][2])
 // ---- the arithmetic steps of one 32-key tile of one wave (32 query rows) ---------------------------------
 // S^T = K . Q^T
 template <int DS>
-__device__ __forceinline__ f32x16 qk_tile(const u32x4 (&ka)[DS], const bf16x8 (&qreg)[DS])
+__device__ __forceinline__ f32x16 qk_tile(const u32x4 (&ka)[DS], const bf16x8 (&qreg)[DS], f32x16 s)
 {
-    f32x16 s;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
     for (int k = 0; k < DS; ++k)
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[k]), qreg[k], s, 0, 0, 0);
@@ -457,6 +454,42 @@ __device__ __forceinline__ void exp_half(const f32x16 &x, int mm, bf16x8 &pbm, f
     }
 }
 
+// The reference of the step-by-step tiles enters through the matrix cores as well: the score accumulator starts from
+// -base (negb: the same value in all 16 registers), base being the running maximum once there is one (0 before), so
+// the scores arrive relative to it and a probability is exp2 of the accumulator as it stands.  Only when the maximum
+// moves (the lazy rule of lazy_rescale, on the scores' true values) are the tile's scores shifted by hand.
+template <int DT>
+__device__ __forceinline__ void rebase_tile(f32x16 &srel, float &base, f32x16 &negb, float &m_run, float &l_run, f32x16 (&oacc)[DT])
+{
+    constexpr float LAZY = 8.0f;
+    const float rmax = tile_max(srel);
+    const bool grow = (rmax + base) - m_run > LAZY;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+        const float mnew = grow ? rmax + base : m_run;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - mnew);
+        m_run = mnew;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+        const float nb = m_run > 0.5f * NEG_BIG ? m_run : 0.f;
+        const float d = nb - base;
+        base = nb;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { srel[v] -= d; negb[v] = -nb; }
+    }
+}
+
+// P^T = exp2(x) for scores x already relative to the reference; the row sum adds the rounded values PV uses.
+__device__ __forceinline__ void softmax_rel(const f32x16 &x, float &l_run, bf16x8 (&pb)[2])
+{
+    float ls[2] = { l_run, 0.f };
+    exp_half(x, 0, pb[0], ls[0]);
+    exp_half(x, 1, pb[1], ls[1]);
+    l_run = ls[0] + ls[1];
+}
+
 // O^T += V^T . P^T
 template <int DT>
 __device__ __forceinline__ void pv_tile(const bf16x4 (&va)[DT][2][2], const bf16x8 (&pb)[2], f32x16 (&oacc)[DT])
@@ -485,7 +518,8 @@ __device__ __forceinline__ void mask_tile(f32x16 &s, uint32_t vis, int h)
 template <int D>
 __device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l,
                                         const uint32_t (&anc_i)[BTV_ANC_WORDS],
-                                        const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32])
+                                        const bf16x8 (&qreg)[D / 16], float &m_run, float &l_run, f32x16 (&oacc)[D / 32],
+                                        float &base, f32x16 &negb)
 {
     constexpr int DS = D / 16, DT = D / 32;
     u32x4 ka[DS];
@@ -495,11 +529,11 @@ __device__ __forceinline__ void do_tile(uint32_t stage, int kb, int Lr, int l,
     lds_read_vt<D, 0>(va_addr, va);
     lds_wait_k<DS, DT * 2>(ka);          // the counter completes in order: K has landed when 2*DT reads remain
     lds_read_vt<D, 1>(va_addr, va);
-    f32x16 s = qk_tile<DS>(ka, qreg);
+    f32x16 s = qk_tile<DS>(ka, qreg, negb);
     if (kb + 32 > Lr) mask_tile(s, vis_word(anc_i, kb, Lr), l >> 5);
-    lazy_rescale<DT>(tile_max(s), m_run, l_run, oacc);
+    rebase_tile<DT>(s, base, negb, m_run, l_run, oacc);
     bf16x8 pb[2];
-    softmax_tile(s, m_run, l_run, pb);
+    softmax_rel(s, l_run, pb);
     lds_wait_vt<DT>(va);
     pv_tile<DT>(va, pb, oacc);
 }
@@ -927,6 +961,10 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
     if constexpr (KW > 1) { BTV_BUILD_MASK() }
 
     float m_run = NEG_BIG, l_run = 0.f;
+    float base = 0.f;                 // what the step-by-step tiles' scores are relative to (rebase_tile)
+    f32x16 negb;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negb[v] = 0.f;
     f32x16 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -1147,6 +1185,11 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
             j0 = Tf;
         }
         // ---- the remaining tiles (those that touch tree rows, or all of a short split), step by step ----
+        if (j0 > 0) {                                            // (m_run is a real maximum after the pipelined part)
+            base = m_run;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) negb[v] = -m_run;
+        }
         BTV_BUILD_MASK()
         for (int j = j0; j < st1 - st0; ++j) {
             wait_tiles<LPW, NT - 1>(issued - st0 - j - 1);       // tile j has landed
@@ -1154,7 +1197,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 #pragma unroll
             for (int k = 0; k < 2; ++k)
                 if (issued - st0 - j < NT) issue_one();
-            do_tile<D>(ring + (j & 7) * LD::STAGE, (st0 + j) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc);
+            do_tile<D>(ring + (j & 7) * LD::STAGE, (st0 + j) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc, base, negb);
         }
     } else if constexpr (KW > 1) {
         // ---- main loop: one barrier per round of KW tiles, wave kw takes tile number kw of the round ------
@@ -1175,7 +1218,7 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
                 }
             if (st + kw < st1) {
                 if constexpr (EB == 2)
-                    do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc);
+                    do_tile<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc, base, negb);
                 else
                     do_tile8<D>(ring + cslot * LD::STAGE, (st + kw) * 32, Lr, l, anc_i, qreg, m_run, l_run, oacc);
             }
