@@ -3,13 +3,14 @@
 // Sec. 3.3 / Prop. 3.3 / Algorithm 1's frontier rule at a fixed budget N: repeatedly emit the
 // frontier prefix with the largest path score rho (Eq. 1), then push its best child and its next
 // sibling.  Two kernels:
-//   1. tb_thread_max   per-thread maxima of the marginals (one pass over [B, V], all CUs);
+//   1. tb_thread_max   per slot of 32 marginals (one thread's share of a chunk): the largest, its place in the
+//                      slot, and the second largest (one pass over [B, V], all CUs);
 //   2. tb_rank_expand  workgroup k derives from the maxima of position k a bound below which no token can be
 //                      among its K best (K = min(V, N): a rank-j token is preceded by its j earlier siblings, so
-//                      ranks >= N can never be emitted), reads again only the few slots that reach the bound,
-//                      and ranks the candidates found there (order: probability desc, token id asc); the
-//                      workgroup that finishes last runs the expansion on one wavefront, the frontier in
-//                      registers.
+//                      ranks >= N can never be emitted); a slot whose maximum reaches the bound and whose second
+//                      largest does not gives its maximum as a candidate, the few other slots that reach the
+//                      bound are read again; the candidates are ranked (order: probability desc, token id asc);
+//                      the workgroup that finishes last runs the expansion.
 // Keys are 64-bit  prob_bits << 32 | ~id  (probabilities are non-negative, so the bit pattern orders like
 // the value; keys are distinct).
 // rho(child) = rho(parent) * q is one fp32 multiply (never fused), the root has rho = 1.
@@ -55,10 +56,40 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return out;
 }
 
+// Inclusive prefix sum over the wavefront on the vector ALU: shifts within the rows of 16 lanes (zeros enter from
+// outside a row), then the row totals travel down the rows.
+__device__ __forceinline__ int wave_incl_scan(int x)
+{
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);    // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);    // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);    // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);    // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// The ranked lists travel from the workgroups that rank to the one that expands through memory, within one launch and
+// between compute dies whose L2 caches do not see each other: they are written and read as relaxed device-scope
+// atomics, which go through to memory, and the writer waits for its stores before it counts itself as done.
+__device__ __forceinline__ void publish(float *q_row, uint32_t *tok_row, int r, float q, uint32_t tok)
+{
+    __hip_atomic_store(q_row + r, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(tok_row + r, tok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint32_t published_tok(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Step 1: per-thread maxima.  Workgroup (chunk, row) scans elements chunk*SCAN .. chunk*SCAN + SCAN - 1 of the
-// row; thread t looks at elements 4t..4t+3 of every 1024 and keeps the largest probability it saw:
-// part[row][chunk][t].
+// row; thread t looks at elements 4t..4t+3 of every 1024 (its slot: 32 elements, numbered k = 4 * piece + element)
+// and keeps the largest probability it saw, where it saw it, and the second largest:
+// part[row][chunk][t] = { bits of the largest, bits of the second largest with k of the largest in the low 5 bits }.
+// The second largest is only ever compared with a bound whose low 19 bits are zero, so the 5 bits cost nothing.
+// Among equal probabilities the first one counts as the largest and the next as the second largest.
 // ------------------------------------------------------------------------------------------------
 struct TbCounters { int done; };
 
@@ -70,23 +101,28 @@ __device__ __forceinline__ void scan_chunk(const float *src, bool aligned, int V
         const int v0 = chunk * SCAN + j * 1024 + tid * 4;        // coalesced: a wave reads 1 KiB per load
         if (aligned && v0 + 4 <= V) {
             const float4 a = *reinterpret_cast<const float4 *>(src + v0);
-            f(a.x, v0); f(a.y, v0 + 1); f(a.z, v0 + 2); f(a.w, v0 + 3);
+            f(a.x, 4 * j); f(a.y, 4 * j + 1); f(a.z, 4 * j + 2); f(a.w, 4 * j + 3);
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (v0 + i < V) f(src[v0 + i], v0 + i);
+                if (v0 + i < V) f(src[v0 + i], 4 * j + i);
         }
     }
 }
 
-__global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, int B, int chunks, uint32_t *part, TbCounters *ctr)
+__global__ __launch_bounds__(256) void tb_thread_max(const float *marg, int V, int B, int chunks, uint2 *part, TbCounters *ctr)
 {
     const int tid = threadIdx.x, chunk = blockIdx.x, row = blockIdx.y;
     const float *src = marg + (size_t)row * V;
     const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
-    uint32_t mx = 0;
-    scan_chunk(src, aligned, V, chunk, tid, [&](float p, int) { mx = umax(mx, prob_bits(p)); });
-    part[((size_t)row * chunks + chunk) * 256 + tid] = mx;
+    uint32_t m1 = 0u, m2 = 0u, k1 = 0u;
+    scan_chunk(src, aligned, V, chunk, tid, [&](float p, int k) {
+        const uint32_t b = prob_bits(p);
+        m2 = umax(m2, b < m1 ? b : m1);                          // the smaller of the newcomer and the best so far
+        k1 = b > m1 ? (uint32_t)k : k1;
+        m1 = umax(m1, b);
+    });
+    part[((size_t)row * chunks + chunk) * 256 + tid] = make_uint2(m1, (m2 & ~31u) | k1);
     if (chunk == 0 && row % B == 0 && tid == 0) ctr[row / B].done = 0;   // the next kernel starts after this one has ended
 }
 
@@ -98,9 +134,10 @@ constexpr int TBINS = 4096;
 // of the row's K-th largest probability, and a tight one: it only falls short by the few tokens of the K best
 // that share a slot with a better one.  The workgroup finds the 12-bit bin (sign-less float bits [30:19]: an
 // eighth of a binade) that holds it from a histogram of the chunks*256 maxima and takes the lower edge of that bin
-// as the bound; only slots whose maximum reaches the bound can hold candidates, so only those (about K of the
-// chunks*256) are read again, 32 elements each, and their elements at or above the bound become the candidate
-// list in LDS: K plus a few.
+// as the bound; only slots whose maximum reaches the bound can hold candidates (about K of the chunks*256).  Where
+// the slot's second largest stays below the bound, the maximum is the slot's one candidate and goes to the list
+// from what step 1 recorded; the other slots, a handful, are read again, 32 elements each, and their elements at
+// or above the bound join the list in LDS: K plus a few.
 // Step 3, part A: the candidates are ranked by counting the candidates above each (order: probability desc, token
 // id asc) and the K best go to the position's top list.  More than SELCAP candidates (heavily tied or otherwise
 // degenerate probabilities): the K-th largest key of the whole row is found by radix selection, one byte of the
@@ -109,12 +146,29 @@ constexpr int TBINS = 4096;
 constexpr int SELCAP = 512;
 constexpr int SLOTCAP = 1024;
 
-struct RankLds {                            // bound and ranking of one position
+__device__ __forceinline__ int bin_at(int b) { return b + (b >> 4); }
+
+// Element i of sixteen registers for a lane-dependent i, by halving.  The values arrive one by one and pass through an
+// empty asm, which hides from the compiler that they are the elements of one array: it would turn the selects into
+// an indexed load and move the array into scratch memory.
+__device__ __forceinline__ uint32_t pick16v(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3, uint32_t x4, uint32_t x5, uint32_t x6, uint32_t x7, uint32_t x8, uint32_t x9, uint32_t x10, uint32_t x11, uint32_t x12, uint32_t x13, uint32_t x14, uint32_t x15, int i)
+{
+    asm volatile("" : "+v"(x0)); asm volatile("" : "+v"(x1)); asm volatile("" : "+v"(x2)); asm volatile("" : "+v"(x3)); asm volatile("" : "+v"(x4)); asm volatile("" : "+v"(x5)); asm volatile("" : "+v"(x6)); asm volatile("" : "+v"(x7)); asm volatile("" : "+v"(x8)); asm volatile("" : "+v"(x9)); asm volatile("" : "+v"(x10)); asm volatile("" : "+v"(x11)); asm volatile("" : "+v"(x12)); asm volatile("" : "+v"(x13)); asm volatile("" : "+v"(x14)); asm volatile("" : "+v"(x15));
+    const uint32_t a0 = (i & 8) ? x8 : x0, a1 = (i & 8) ? x9 : x1, a2 = (i & 8) ? x10 : x2, a3 = (i & 8) ? x11 : x3;
+    const uint32_t a4 = (i & 8) ? x12 : x4, a5 = (i & 8) ? x13 : x5, a6 = (i & 8) ? x14 : x6, a7 = (i & 8) ? x15 : x7;
+    const uint32_t b0 = (i & 4) ? a4 : a0, b1 = (i & 4) ? a5 : a1, b2 = (i & 4) ? a6 : a2, b3 = (i & 4) ? a7 : a3;
+    const uint32_t c0 = (i & 2) ? b2 : b0, c1 = (i & 2) ? b3 : b1;
+    return (i & 1) ? c1 : c0;
+}
+#define BTV_PICK16(x, i) pick16v(x[0], x[1], x[2], x[3], x[4], x[5], x[6], x[7], x[8], x[9], x[10], x[11], x[12], x[13], x[14], x[15], i)
+
+struct alignas(16) RankLds {                // bound and ranking of one position
     union {
-        int bins[TBINS];                    // histogram of the per-thread maxima (before the candidates exist)
+        int bins[TBINS + TBINS / 16];       // histogram of the per-thread maxima (before the candidates exist); bin b at
+                                            // b + b / 16, so that a thread's 16 bins and its neighbours' fall into different banks
         struct {
-            u64 sel[SELCAP];                // the candidates
-            uint16_t slot[SLOTCAP];         // slots (chunk * 256 + thread) whose maximum reaches the bound
+            alignas(16) u64 sel[SELCAP + 64];   // the candidates (+ a place per lane for the stores that store nothing)
+            uint16_t slot[SLOTCAP + 64];        // slots (chunk * 256 + thread) whose maximum reaches the bound
         };
     };
     int hist[256];
@@ -177,11 +231,41 @@ __device__ __forceinline__ void rank_keys(const u64 *sel, int n, int K, int KP, 
 #pragma unroll
         for (int c = 0; c < 2; ++c)
             if (i0 + c * nthreads + tid < n && rank[c] < K) {
-                q_row[rank[c]] = __uint_as_float((uint32_t)(mine[c] >> 32));
-                tok_row[rank[c]] = 0xFFFFFFFFu - (uint32_t)mine[c];
+                publish(q_row, tok_row, rank[c], __uint_as_float((uint32_t)(mine[c] >> 32)), 0xFFFFFFFFu - (uint32_t)mine[c]);
             }
     }
-    for (int i = K + tid; i < KP; i += nthreads) { q_row[i] = 0.f; tok_row[i] = 0u; }
+    for (int i = K + tid; i < KP; i += nthreads) publish(q_row, tok_row, i, 0.f, 0u);
+}
+
+// The same for at most 256 keys on a workgroup of 256: a key belongs to T = 1, 2 or 4 neighbouring lanes, each of which
+// counts over its share of the list, two keys per LDS read and eight reads in flight; the shares meet by quad swaps.
+// Every lane makes the same number of reads, none of them conditional (the compiler would wait for each conditional
+// read on its own): a lane past the end of its share reads the pair of zeros behind the list, which is above nothing.
+__device__ __forceinline__ void rank_keys_split(u64 *sel, int n, int K, int KP, float *q_row, uint32_t *tok_row, int tid)
+{
+    const int lgT = n <= 64 ? 2 : n <= 128 ? 1 : 0, T = 1 << lgT;
+    const int i = tid >> lgT, part = tid & (T - 1);
+    const int pairs = (n + 1) >> 1, per = (pairs + T - 1) >> lgT;
+    const int j0 = part * per, j1 = min(pairs, j0 + per);
+    if (tid < 3) sel[n + tid] = 0ull;                          // n <= 256 of the list's 512 places are taken
+    __syncthreads();
+    const u64 mine = sel[min(i, n)];
+    const ulonglong2 *two = reinterpret_cast<const ulonglong2 *>(sel);
+    int cnt = 0;
+    for (int r = 0; r < per; r += 8) {                         // (uniform)
+        ulonglong2 kk[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) kk[u] = two[j0 + r + u < j1 ? j0 + r + u : pairs];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            cnt += kk[u].x > mine ? 1 : 0;
+            cnt += kk[u].y > mine ? 1 : 0;
+        }
+    }
+    if (T >= 2) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+    if (T == 4) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+    if (part == 0 && i < n && cnt < K) publish(q_row, tok_row, cnt, __uint_as_float((uint32_t)(mine >> 32)), 0xFFFFFFFFu - (uint32_t)mine);
+    for (int e = K + tid; e < KP; e += 256) publish(q_row, tok_row, e, 0.f, 0u);
 }
 
 template <typename ForEach>
@@ -445,7 +529,7 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
         const int i = r * 64 + lane;
         if (i < n) {
             const uint32_t idx = o_rec[r] & 0x1FFFu;
-            token[i] = (int32_t)S.tok[idx];   // (memory)
+            token[i] = (int32_t)published_tok(S.tok + idx);
             parent[i] = (int32_t)(o_rec[r] >> 13) - 1;
             if (depth) depth[i] = (int)(idx >> lg) + 1;
             if (rho) rho[i] = o_rho[r];
@@ -746,7 +830,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
         const int idx = (dep - 1) * KP + (int)(lexkey & (uint32_t)(KP - 1));
         const uint32_t pu = (v >> 12) & 0xFFFu;
         const float r = __uint_as_float((uint32_t)(k >> 32));
-        token[tid] = (int32_t)S.tok[idx];
+        token[tid] = (int32_t)published_tok(S.tok + idx);
         parent[tid] = pu == 0xFFFu ? -1 : (int32_t)L.pos_of[pu];
         if (depth) depth[tid] = dep;
         if (rho) rho[tid] = r;
@@ -807,7 +891,7 @@ __device__ __forceinline__ void beam_block(const ExpandLds &S, BeamLds &Bm, int 
             if (rank < keep) {
                 const int nd = n + rank;
                 parent[nd] = Bm.node[cur][b];
-                token[nd] = (int32_t)S.tok[k * KP + rk];
+                token[nd] = (int32_t)published_tok(S.tok + k * KP + rk);
                 if (depth) depth[nd] = k + 1;
                 if (rho) rho[nd] = r;
                 Bm.rho[cur ^ 1][rank] = r;
@@ -829,7 +913,7 @@ __device__ __forceinline__ void beam_block(const ExpandLds &S, BeamLds &Bm, int 
 }
 
 __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, int B, int K, int KP, int N, int chunks,
-                                                      TbCounters *ctr, const uint32_t *part, float *top_q, uint32_t *top_tok,
+                                                      TbCounters *ctr, const uint2 *part, float *top_q, uint32_t *top_tok,
                                                       int32_t *parent,
                                                       int32_t *token, int32_t *depth, float *rho, int32_t *n_out, float *ahat,
                                                       Adaptive ad, int beam_width, Batch bt, int algo)
@@ -852,32 +936,30 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     uint32_t *tok_row = top_tok + (size_t)row * KP;
     const float *src = marg + (size_t)row * V;
     const bool aligned = (((size_t)row * V) & 3) == 0 && (reinterpret_cast<uintptr_t>(marg) & 15) == 0;
-    const uint32_t *pr = part + (size_t)row * chunks * 256 + tid;
+    const uint2 *pr = part + (size_t)row * chunks * 256 + tid;
     // ---- the bound: K-th largest per-thread maximum of the row, down to the lower edge of its histogram bin ---
-    uint32_t pv[16];                                           // the loads are in flight while the histogram is cleared
+    uint32_t pv[16], pw[16];                                   // the loads are in flight while the histogram is cleared
 #pragma unroll
-    for (int j = 0; j < 16; ++j) pv[j] = j < chunks ? pr[(size_t)j * 256] : 0xFFFFFFFFu;
-#pragma unroll
-    for (int b = 0; b < TBINS / 256; ++b) RL.bins[b * 256 + tid] = 0;
+    for (int j = 0; j < 16; ++j) {
+        const uint2 x = pr[(size_t)(j < chunks ? j : 0) * 256];      // no load behind a branch: all of them in flight at once
+        pv[j] = j < chunks ? x.x : 0u;
+        pw[j] = x.y;
+    }
+    for (int b = tid; b < (TBINS + TBINS / 16) / 4; b += 256) reinterpret_cast<int4 *>(RL.bins)[b] = make_int4(0, 0, 0, 0);
     if (tid == 0) { RL.nsel = 0; RL.nslot = 0; }
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 16; ++j) if (pv[j] != 0xFFFFFFFFu) atomicAdd(&RL.bins[pv[j] >> 19], 1);
-    for (int j = 16; j < chunks; ++j) atomicAdd(&RL.bins[pr[(size_t)j * 256] >> 19], 1);
+    for (int j = 0; j < 16; ++j) if (j < chunks) atomicAdd(&RL.bins[bin_at((int)(pv[j] >> 19))], 1);
+    for (int j = 16; j < chunks; ++j) atomicAdd(&RL.bins[bin_at((int)(pr[(size_t)j * 256].x >> 19))], 1);
     __syncthreads();
     {
         int hb[16], own = 0;                                   // thread t owns bins 16t .. 16t+15
 #pragma unroll
-        for (int b = 0; b < 16; ++b) { hb[b] = RL.bins[tid * 16 + b]; own += hb[b]; }
-        int suf = own;                                         // inclusive suffix sum over the higher threads
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int o = __shfl_down(suf, off);
-            if (lane + off < 64) suf += o;
-        }
-        if (lane == 0) RL.wsum[w] = suf;
+        for (int b = 0; b < 16; ++b) { hb[b] = RL.bins[tid * 17 + b]; own += hb[b]; }
+        const int incl = wave_incl_scan(own), wtot = __builtin_amdgcn_readlane(incl, 63);
+        if (lane == 0) RL.wsum[w] = wtot;
         __syncthreads();
-        int above = suf - own;
+        int above = wtot - incl;                               // in the bins of the higher threads
         for (int ww = w + 1; ww < 4; ++ww) above += RL.wsum[ww];
         if (above < K && above + own >= K) {
             int cum = above, sel = tid * 16;
@@ -891,53 +973,123 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
         __syncthreads();                                       // the histogram is dead from here on: sel[] takes its place
     }
     const uint32_t tau = (uint32_t)RL.sel_bin << 19;
-    // ---- the candidates: the slots whose maximum reaches the bound are listed, then read again, one 16-byte
-    // piece of a slot per thread and up to four pieces in flight per thread ---------------------------------------
+    // ---- the candidates.  A slot whose maximum reaches the bound holds a candidate; when its second largest stays
+    // below the bound, which is the rule (K of thousands of slots are taken), that maximum is the slot's only one
+    // and goes to the list as it stands, with the token id that its place in the slot gives.  The other slots
+    // are listed and read again, one 16-byte piece of a slot per thread and four pieces in flight per thread.
+    // Places in the lists are handed out per wavefront: every lane counts what it has, a scan places the lanes,
+    // one lane takes the wavefront's range from the shared counter (one LDS round trip, not one per entry).
+    // A lane rarely holds more than one entry: it keeps its entries as a bit mask and the wavefront loops until
+    // every mask is empty, each lane storing one entry per trip (to a place of its own behind the list when it has
+    // none left), which costs less than a branch or a store per possible entry. ----------------------------------
+    auto wave_range = [&](int mine, int *counter) {            // first place of this lane's `mine` entries
+        const int incl = wave_incl_scan(mine), total = __builtin_amdgcn_readlane(incl, 63);
+        int first = 0;
+        if (total > 0) {                                       // (wave-uniform)
+            if (lane == 0) first = atomicAdd(counter, total);
+            first = __builtin_amdgcn_readfirstlane(first);
+        }
+        return first + incl - mine;
+    };
+    {
+        uint32_t one = 0u, more = 0u;                           // chunks whose slot holds one candidate / maybe several
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (pv[j] != 0xFFFFFFFFu && pv[j] >= tau) {
-            const int pos = atomicAdd(&RL.nslot, 1);
-            if (pos < SLOTCAP) RL.slot[pos] = (uint16_t)(j * 256 + tid);
+        for (int j = 0; j < 16; ++j)
+            if (j < chunks && pv[j] >= tau) {
+                if (pw[j] >= tau) more |= 1u << j; else one |= 1u << j;
+            }
+        int pos = wave_range(__builtin_popcount(one), &RL.nsel);
+        while (__builtin_amdgcn_ballot_w64(one != 0u) != 0ull) {
+            const bool has = one != 0u;
+            const int j = has ? __builtin_ctz(one) : 0;
+            const uint32_t k = BTV_PICK16(pw, j) & 31u;
+            const uint32_t v = (uint32_t)(j * SCAN + tid * 4) + (k >> 2) * 1024u + (k & 3u);
+            RL.sel[has && pos < SELCAP ? pos : SELCAP + lane] = ((u64)BTV_PICK16(pv, j) << 32) | (u64)(0xFFFFFFFFu - v);
+            pos += has ? 1 : 0;
+            one &= one - 1u;
         }
-    for (int j = 16; j < chunks && j < 256; ++j)
-        if (pr[(size_t)j * 256] >= tau) {
-            const int pos = atomicAdd(&RL.nslot, 1);
-            if (pos < SLOTCAP) RL.slot[pos] = (uint16_t)(j * 256 + tid);
+        int mine = __builtin_popcount(more);
+        for (int j = 16; j < chunks && j < 256; ++j) mine += pr[(size_t)j * 256].x >= tau ? 1 : 0;
+        pos = wave_range(mine, &RL.nslot);
+        while (__builtin_amdgcn_ballot_w64(more != 0u) != 0ull) {
+            const bool has = more != 0u;
+            const int j = has ? __builtin_ctz(more) : 0;
+            RL.slot[has && pos < SLOTCAP ? pos : SLOTCAP + lane] = (uint16_t)(j * 256 + tid);
+            pos += has ? 1 : 0;
+            more &= more - 1u;
         }
+        for (int j = 16; j < chunks && j < 256; ++j)
+            if (pr[(size_t)j * 256].x >= tau) {
+                if (pos < SLOTCAP) RL.slot[pos] = (uint16_t)(j * 256 + tid);
+                ++pos;
+            }
+    }
     __syncthreads();
     const int nslot = RL.nslot;
-    auto take = [&](float p, int v) {
-        if (prob_bits(p) >= tau) {
-            const int pos = atomicAdd(&RL.nsel, 1);
-            if (pos < SELCAP) RL.sel[pos] = make_key(p, (uint32_t)v);
-        }
-    };
-    if (nslot <= SLOTCAP && chunks <= 256) {
+    if (nslot == 0 && chunks <= 256) {
+        // nothing to read again
+    } else if (nslot <= SLOTCAP && chunks <= 256) {
         constexpr int PPS = SCAN / 1024;                       // 16-byte pieces per slot
         const int total = nslot * PPS;
+        const bool whole = aligned && (V & 3) == 0;            // every piece that starts inside the row ends inside it
         for (int base = 0; base < total; base += 4 * 256) {
-            float4 a[4];
+            float pe[16];
             int v0[4];
+            uint32_t ok = 0u;                                   // bit 4u + e: element e of piece u is a candidate
+            if (whole) {                                        // no load depends on a branch: four in flight at once
+                int sl[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = base + u * 256 + tid;
-                v0[u] = -1;
-                a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i < total) {
-                    const int sl = RL.slot[i / PPS];
-                    v0[u] = (sl >> 8) * SCAN + (i % PPS) * 1024 + (sl & 255) * 4;
-                    if (aligned && v0[u] + 4 <= V) a[u] = *reinterpret_cast<const float4 *>(src + v0[u]);
+                for (int u = 0; u < 4; ++u) {
+                    const int i = base + u * 256 + tid;
+                    sl[u] = RL.slot[(i < total ? i : 0) / PPS];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = base + u * 256 + tid;
+                    v0[u] = (sl[u] >> 8) * SCAN + (i % PPS) * 1024 + (sl[u] & 255) * 4;
+                    if (i >= total || v0[u] >= V) v0[u] = -1;
+                    const float4 a = *reinterpret_cast<const float4 *>(src + (v0[u] < 0 ? 0 : v0[u]));
+                    pe[4 * u] = a.x; pe[4 * u + 1] = a.y; pe[4 * u + 2] = a.z; pe[4 * u + 3] = a.w;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (v0[u] >= 0 && prob_bits(pe[4 * u + e]) >= tau) ok |= 1u << (4 * u + e);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = base + u * 256 + tid;
+                    v0[u] = -1;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pe[4 * u + e] = 0.f;
+                    if (i < total) {
+                        const int sl = RL.slot[i / PPS];
+                        v0[u] = (sl >> 8) * SCAN + (i % PPS) * 1024 + (sl & 255) * 4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (v0[u] + e < V) {
+                                pe[4 * u + e] = src[v0[u] + e];
+                                if (prob_bits(pe[4 * u + e]) >= tau) ok |= 1u << (4 * u + e);
+                            }
+                    }
                 }
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (v0[u] < 0) continue;
-                if (aligned && v0[u] + 4 <= V) {
-                    take(a[u].x, v0[u]); take(a[u].y, v0[u] + 1); take(a[u].z, v0[u] + 2); take(a[u].w, v0[u] + 3);
-                } else {
-                    for (int e = 0; e < 4; ++e)
-                        if (v0[u] + e < V) take(src[v0[u] + e], v0[u] + e);
-                }
+            int pos = wave_range(__builtin_popcount(ok), &RL.nsel);
+            while (__builtin_amdgcn_ballot_w64(ok != 0u) != 0ull) {
+                const bool has = ok != 0u;
+                const int bit = has ? __builtin_ctz(ok) : 0;
+                const float pq = __uint_as_float(pick16v(__float_as_uint(pe[0]), __float_as_uint(pe[1]), __float_as_uint(pe[2]),
+                    __float_as_uint(pe[3]), __float_as_uint(pe[4]), __float_as_uint(pe[5]), __float_as_uint(pe[6]), __float_as_uint(pe[7]),
+                    __float_as_uint(pe[8]), __float_as_uint(pe[9]), __float_as_uint(pe[10]), __float_as_uint(pe[11]), __float_as_uint(pe[12]),
+                    __float_as_uint(pe[13]), __float_as_uint(pe[14]), __float_as_uint(pe[15]), bit));
+                int va = (bit & 8) ? v0[2] : v0[0], vb = (bit & 8) ? v0[3] : v0[1];
+                asm volatile("" : "+v"(va), "+v"(vb));
+                const int v = ((bit & 4) ? vb : va) + (bit & 3);
+                RL.sel[has && pos < SELCAP ? pos : SELCAP + lane] = make_key(pq, (uint32_t)v);
+                pos += has ? 1 : 0;
+                ok &= ok - 1u;
             }
         }
     } else if (tid == 0) {
@@ -945,20 +1097,22 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     }
     __syncthreads();
     const int nc = RL.nsel;
-    if (nc <= SELCAP) {
+    if (nc <= 256) {
+        rank_keys_split(RL.sel, nc, K, KP, q_row, tok_row, tid);
+    } else if (nc <= SELCAP) {
         rank_keys(RL.sel, nc, K, KP, q_row, tok_row, tid, 256);
     } else if (w == 0) {                       // rare: one wavefront selects the K best of the row first
         wave_select_rank([&](auto f) { for (int v = lane; v < V; v += 64) f(make_key(src[v], (uint32_t)v)); },
                          K, KP, RL.hist, RL.sel, &RL.nsel, q_row, tok_row, lane);
     }
     // ---- the workgroup that finishes last expands -------------------------------------------------------------
-    __threadfence();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this thread's part of the lists has reached memory
     __syncthreads();
-    if (tid == 0) RL.last = atomicAdd(&ctr[req].done, 1) == B - 1;
+    if (tid == 0) RL.last = __hip_atomic_fetch_add(&ctr[req].done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == B - 1;
     __syncthreads();
     if (!RL.last) return;
-    __threadfence();
-    for (int e = tid; e < B * KP; e += 256) S.q[e] = __builtin_nontemporal_load(top_q + (size_t)req * B * KP + e);
+    for (int e = tid; e < B * KP; e += 256)
+        S.q[e] = __hip_atomic_load(top_q + (size_t)req * B * KP + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid == 0) S.tok = top_tok + (size_t)req * B * KP;
     if (bt.n_nodes) {                          // this request's budget and output rows
         const int o0 = bt.q_offset[req], room = bt.q_offset[req + 1] - o0, want = bt.n_nodes[req];
@@ -1032,7 +1186,7 @@ TopkPlan topk_plan(int batch, int B, int V, int N)
     t.KP = std::max(next_pow2(t.K), 1);
     t.chunks = (V + SCAN - 1) / SCAN;
     t.ctr_bytes = btv_align_up((size_t)batch * sizeof(TbCounters), BTV_WS_ALIGN);
-    t.part_bytes = btv_align_up((size_t)batch * B * t.chunks * 256 * 4, BTV_WS_ALIGN);
+    t.part_bytes = btv_align_up((size_t)batch * B * t.chunks * 256 * sizeof(uint2), BTV_WS_ALIGN);
     t.top_bytes = btv_align_up((size_t)batch * B * t.KP * 4, BTV_WS_ALIGN);
     return t;
 }
@@ -1069,7 +1223,7 @@ static int tree_build_launch(const float *marginals, int batch, int B, int V, in
     TopkPlan t = topk_plan(batch, B, V, N);
     unsigned char *base = static_cast<unsigned char *>(ws);
     TbCounters *ctr = reinterpret_cast<TbCounters *>(base + BTV_WS_HEADER);
-    uint32_t *part = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.ctr_bytes);
+    uint2 *part = reinterpret_cast<uint2 *>(base + BTV_WS_HEADER + t.ctr_bytes);
     float *top_q = reinterpret_cast<float *>(base + BTV_WS_HEADER + t.ctr_bytes + t.part_bytes);
     uint32_t *top_tok = reinterpret_cast<uint32_t *>(base + BTV_WS_HEADER + t.ctr_bytes + t.part_bytes + t.top_bytes);
     Adaptive ad = ad_in;
