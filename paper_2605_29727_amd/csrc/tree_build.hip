@@ -69,6 +69,17 @@ __device__ __forceinline__ int wave_incl_scan(int x)
     return x;
 }
 
+__device__ __forceinline__ int wave_incl_max(int x)               // the same with max, for values >= 0
+{
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true));
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true));
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true));
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true));
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));
+    return x;
+}
+
 // The ranked lists travel from the workgroups that rank to the one that expands through memory, within one launch and
 // between compute dies whose L2 caches do not see each other: they are written and read as relaxed device-scope
 // atomics, which go through to memory, and the writer waits for its stores before it counts itself as done.
@@ -188,11 +199,15 @@ struct ExpandLds {                          // the expansion
 
 // The level-synchronous expansion: pool = the best nodes found so far, in emission order; candidates of one level.
 constexpr int LV_CAND = 2048;
-struct LevelLds {
-    u64 ckey[LV_CAND];
-    uint16_t lex2id[BTV_MAX_NODES];         // node id by lexicographic place, for the level whose children are proposed
-    u64 pkey[2][BTV_MAX_NODES];
+struct alignas(16) LevelLds {
+    alignas(16) u64 ckey[LV_CAND + 8];
+    alignas(16) u64 pkey[2][BTV_MAX_NODES + 8]; // (+ two zero keys behind the pool: its last pair when read two by two)
     uint32_t pval[2][BTV_MAX_NODES];
+    uint16_t lex2id[BTV_MAX_NODES];         // node id by lexicographic place, for the level whose children are proposed
+    uint16_t mark[BTV_MAX_NODES];           // index + 1 of the pool entry whose proposals start at this candidate, else 0
+    uint16_t rcap[BTV_MAX_NODES];           // min(K, N / (i + 1))
+    int hist[BTV_MAX_NODES + 8];            // proposals that land right behind pool entry i - 1
+    int wmax[4];
     uint16_t pos_of[MAXB * BTV_MAX_NODES];  // place in the pool by node id (level, index within the level)
     int off[BTV_MAX_NODES];                 // exclusive scan of the candidates per pool entry
     int cnt_lex[BTV_MAX_NODES];             // nodes of the new level per parent (by the parent's lexicographic place)
@@ -553,9 +568,10 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
 // children of the level d-1 nodes kept so far.  The pool holds the best N nodes found up to the level before, in
 // order; every pool node of depth d-1 proposes its children of rank r < min(K, N / (i + 1)), i being its place
 // among the depth d-1 nodes (the child is preceded by the (i+1)(r+1) children of rank <= r of the parents up to its
-// own), cut further at the score of the pool's last node once the pool is full; the proposals are sorted (bitonic,
-// 64-bit keys, in LDS) and merged into the pool by binary searches from both sides.  The loop ends at depth B or
-// when a level proposes nothing.
+// own), cut further at the score of the pool's last node once the pool is full.  Up to 256 proposals (the rule
+// once the pool is full) are placed by counting: one per thread, its new place = the proposals above it + the pool
+// nodes above it; more are sorted (bitonic, 64-bit keys, in LDS) and merged into the pool by binary searches from
+// both sides.  The loop ends at depth B or when a level proposes nothing.
 // Key of a node = bits(rho) << 32 | (31 - depth) << 16 | (0xFFFF - lexkey); lexkey = place of the parent in the
 // lexicographic order of its level * KP + rank, which orders the nodes of one level by rank path; the place of a
 // new node in that order is the number of level nodes under parents before its parent, plus its rank (siblings
@@ -669,128 +685,211 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
     const int lg = 31 - __builtin_clz((unsigned)KP);
     const u64 below = (1ull << lane) - 1ull;
     int cur = 0, np = min(K, N);
+    L.rcap[tid] = (uint16_t)min(K, N / (tid + 1));
     if (tid < np) {                                            // level 1: the K best tokens of position 0, already in order
         L.pkey[0][tid] = ((u64)__float_as_uint(__fmul_rn(1.0f, S.q[tid])) << 32) | (30u << 16) | (0xFFFFu - (uint32_t)tid);
         L.pval[0][tid] = (uint32_t)tid | (0xFFFu << 12) | ((uint32_t)tid << 24);
         L.lex2id[tid] = (uint16_t)tid;
     }
+    if (tid < 3) L.pkey[0][np + tid] = 0ull;              // read two by two: the last pair's second key and the pair of zeros
     __syncthreads();
+    // No LDS read of the loop sits behind a lane-dependent branch (the compiler would wait for each on its own):
+    // lanes without work read place 0 and drop the result.  The searches run a fixed, wave-uniform number of steps.
+    const int search_steps = 32 - __builtin_clz((unsigned)min(K, N));
     for (int d = 2; d <= B; ++d) {
         // ---- how many children each pool node of depth d-1 proposes ------------------------------------------------
         const float *qd = S.q + (d - 1) * KP;
-        int c = 0;
-        if (tid < np) {
-            const u64 k = L.pkey[cur][tid];
-            if (31 - (int)((k >> 16) & 31u) == d - 1) {
-                const int place = (int)(L.pval[cur][tid] & 0xFFu);
-                const int rcap = min(K, N / (place + 1));
-                c = rcap;
-                if (np == N) {                                 // only scores that reach the pool's last node
-                    const uint32_t g32 = (uint32_t)(L.pkey[cur][N - 1] >> 32);
-                    const float rp = __uint_as_float((uint32_t)(k >> 32));
-                    int lo = 0, hi = rcap;                     // scores fall with the rank
-                    while (lo < hi) {
-                        const int mid = (lo + hi) >> 1;
-                        if (__float_as_uint(__fmul_rn(rp, qd[mid])) >= g32) lo = mid + 1; else hi = mid;
-                    }
-                    c = lo;
-                }
+        const u64 k = L.pkey[cur][tid < np ? tid : 0];
+        const uint32_t v = L.pval[cur][tid < np ? tid : 0];
+        const uint32_t g32 = (uint32_t)(L.pkey[cur][N - 1] >> 32);   // the pool's last score (read, not used, before the pool is full)
+        const int rcap = L.rcap[v & 0xFFu];
+        const float rp = __uint_as_float((uint32_t)(k >> 32));
+        int c = tid < np && 31 - (int)((k >> 16) & 31u) == d - 1 ? rcap : 0;
+        if (np == N) {                                         // only scores that reach the pool's last node; they fall with the rank
+            int lo = 0, hi = c;
+            for (int st = 0; st < search_steps; ++st) {
+                const int mid = (lo + hi) >> 1;
+                const bool ge = __float_as_uint(__fmul_rn(rp, qd[mid])) >= g32;
+                const bool open = lo < hi;
+                lo = open && ge ? mid + 1 : lo;
+                hi = open && !ge ? mid : hi;
             }
+            c = lo;
         }
-        int incl = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
+        const int incl = wave_incl_scan(c);
         if (lane == 63) L.wsum[w] = incl;
+        L.mark[tid] = 0;
+        L.hist[tid] = 0;
+        if (tid == 0) L.hist[BTV_MAX_NODES] = 0;
         __syncthreads();
-        int base = 0;
-        for (int ww = 0; ww < w; ++ww) base += L.wsum[ww];
-        const int C = L.wsum[0] + L.wsum[1] + L.wsum[2] + L.wsum[3];
-        L.off[tid] = base + incl - c;
+        const int ws0 = L.wsum[0], ws1 = L.wsum[1], ws2 = L.wsum[2], ws3 = L.wsum[3];
+        const int base = (w > 0 ? ws0 : 0) + (w > 1 ? ws1 : 0) + (w > 2 ? ws2 : 0);
+        const int C = ws0 + ws1 + ws2 + ws3;
+        const int off = base + incl - c;
+        L.off[tid] = off;
         if (C == 0) break;                                     // (uniform)
         if (C > LV_CAND) {                                     // cannot happen (sum over i of N / (i+1) <= 1570 at N = 256)
             if (tid == 0) atomicOr(ad.flag, 8u);
             break;
         }
-        int P2 = 128;
-        while (P2 < C) P2 <<= 1;
-        __syncthreads();
-        // ---- the proposals: candidate j belongs to the last pool entry whose offset does not exceed j ---------------
-        for (int j = tid; j < P2; j += 256) {
-            u64 key = 0ull;
-            if (j < C) {
-                int lo = 0, hi = np;                           // first entry with off > j
+        const int nxt = cur ^ 1;
+        if (C <= 256) {
+            // ---- few proposals: one per thread, placed by counting ---------------------------------------------------
+            // Candidate j belongs to the last pool entry whose offset does not exceed j: the entries mark where their
+            // proposals start and a running maximum carries the marks along.
+            if (c > 0) L.mark[off] = (uint16_t)(tid + 1);
+            __syncthreads();
+            const int mk = wave_incl_max((int)L.mark[tid]);
+            if (lane == 63) L.wmax[w] = mk;
+            __syncthreads();
+            const int wm0 = L.wmax[0], wm1 = L.wmax[1], wm2 = L.wmax[2];
+            const int carry = max(max(w > 0 ? wm0 : 0, w > 1 ? wm1 : 0), w > 2 ? wm2 : 0);
+            const bool live = tid < C;
+            const int pe = live ? max(mk, carry) - 1 : 0;
+            const int r = live ? tid - L.off[pe] : 0;
+            const u64 pk = L.pkey[cur][pe];
+            const uint32_t plex = L.pval[cur][pe] >> 24;
+            const uint32_t sc = __float_as_uint(__fmul_rn(__uint_as_float((uint32_t)(pk >> 32)), qd[r]));
+            L.ckey[tid] = live ? ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - ((plex << lg) + (uint32_t)r)) : 0ull;
+            if (tid < 4) L.ckey[256 + tid] = 0ull;             // with the zeros from C on: the pair behind the list
+            __syncthreads();
+            // A candidate's new place = the candidates above it + the pool nodes above it, both counted (T = 1, 2 or 4
+            // neighbouring lanes share a candidate, two keys per LDS read, eight reads in flight); a pool node moves
+            // down by the candidates above it = the candidates with at most its own place in pool nodes above them.
+            const int lgT = C <= 64 ? 2 : C <= 128 ? 1 : 0, T = 1 << lgT;
+            const int ci = tid >> lgT, part = tid & (T - 1);
+            const u64 mine = L.ckey[ci];                        // zero from C on: never placed
+            const uint32_t cval = (uint32_t)L.lex2id[(0xFFFFu - (uint32_t)(mine & 0xFFFFu)) >> lg] << 12;
+            const ulonglong2 *two = reinterpret_cast<const ulonglong2 *>(L.ckey);
+            const ulonglong2 *ptwo = reinterpret_cast<const ulonglong2 *>(L.pkey[cur]);
+            int above_c = 0, above_p = 0;
+            {
+                const int pairs = (C + 1) >> 1, per = (pairs + T - 1) >> lgT, j0 = part * per, j1 = min(pairs, j0 + per);
+                for (int q = 0; q < per; q += 8) {             // (uniform)
+                    ulonglong2 kk[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) kk[u] = two[j0 + q + u < j1 ? j0 + q + u : pairs];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        above_c += kk[u].x > mine ? 1 : 0;
+                        above_c += kk[u].y > mine ? 1 : 0;
+                    }
+                }
+            }
+            if (np <= 128) {
+                const int pairs = (np + 1) >> 1, per = (pairs + T - 1) >> lgT, j0 = part * per, j1 = min(pairs, j0 + per);
+                for (int q = 0; q < per; q += 8) {
+                    ulonglong2 kk[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) kk[u] = ptwo[j0 + q + u < j1 ? j0 + q + u : pairs];   // pairs: the two zeros
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        above_p += kk[u].x > mine ? 1 : 0;
+                        above_p += kk[u].y > mine ? 1 : 0;
+                    }
+                }
+            } else if (part == 0) {                            // a long pool: binary search, by the candidate's first lane
+                int lo = 0, hi = np;
+                for (int st = 0; st < 9; ++st) {
+                    const int mid = (lo + hi) >> 1;
+                    const bool gt = L.pkey[cur][mid] > mine;
+                    const bool open = lo < hi;
+                    lo = open && gt ? mid + 1 : lo;
+                    hi = open && !gt ? mid : hi;
+                }
+                above_p = lo;
+            }
+            if (T >= 2) {
+                above_c += __builtin_amdgcn_update_dpp(0, above_c, 0xB1, 0xF, 0xF, false);
+                above_p += __builtin_amdgcn_update_dpp(0, above_p, 0xB1, 0xF, 0xF, false);
+            }
+            if (T == 4) {
+                above_c += __builtin_amdgcn_update_dpp(0, above_c, 0x4E, 0xF, 0xF, false);
+                above_p += __builtin_amdgcn_update_dpp(0, above_p, 0x4E, 0xF, 0xF, false);
+            }
+            if (part == 0 && ci < C) {
+                atomicAdd(&L.hist[above_p], 1);
+                if (above_c + above_p < N) {
+                    L.pkey[nxt][above_c + above_p] = mine;
+                    L.pval[nxt][above_c + above_p] = cval;
+                }
+            }
+            __syncthreads();
+            const int hs = wave_incl_scan(L.hist[tid]);
+            if (lane == 63) L.wsum2[w] = hs;
+            __syncthreads();
+            const int h0 = L.wsum2[0], h1 = L.wsum2[1], h2 = L.wsum2[2];
+            const int moved = hs + (w > 0 ? h0 : 0) + (w > 1 ? h1 : 0) + (w > 2 ? h2 : 0);
+            if (tid < np && tid + moved < N) { L.pkey[nxt][tid + moved] = k; L.pval[nxt][tid + moved] = v; }
+        } else {
+            __syncthreads();
+            // ---- the proposals: candidate j belongs to the last pool entry whose offset does not exceed j -----------
+            int P2 = 512;
+            while (P2 < C) P2 <<= 1;
+            for (int j = tid; j < P2; j += 256) {
+                u64 key = 0ull;
+                if (j < C) {
+                    int lo = 0, hi = np;                       // first entry with off > j
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (L.off[mid] <= j) lo = mid + 1; else hi = mid;
+                    }
+                    const int pe = lo - 1, r = j - L.off[pe];
+                    const u64 pk = L.pkey[cur][pe];
+                    const uint32_t sc = __float_as_uint(__fmul_rn(__uint_as_float((uint32_t)(pk >> 32)), qd[r]));
+                    key = ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - (((L.pval[cur][pe] >> 24) << lg) + (uint32_t)r));
+                }
+                L.ckey[j] = key;
+            }
+            bitonic_desc(L.ckey, P2, tid);
+            // ---- merge: a node's new place = its place in its own list + the nodes of the other list ahead of it ----
+            for (int j = tid; j < C; j += 256) {
+                const u64 ck = L.ckey[j];
+                int lo = 0, hi = np;
                 while (lo < hi) {
                     const int mid = (lo + hi) >> 1;
-                    if (L.off[mid] <= j) lo = mid + 1; else hi = mid;
+                    if (L.pkey[cur][mid] > ck) lo = mid + 1; else hi = mid;
                 }
-                const int pe = lo - 1, r = j - L.off[pe];
-                const u64 pk = L.pkey[cur][pe];
-                const uint32_t sc = __float_as_uint(__fmul_rn(__uint_as_float((uint32_t)(pk >> 32)), qd[r]));
-                key = ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - (((L.pval[cur][pe] >> 24) << lg) + (uint32_t)r));
+                if (j + lo < N) {
+                    L.pkey[nxt][j + lo] = ck;
+                    L.pval[nxt][j + lo] = (uint32_t)L.lex2id[(0xFFFFu - (uint32_t)(ck & 0xFFFFu)) >> lg] << 12;
+                }
             }
-            L.ckey[j] = key;
-        }
-        bitonic_desc(L.ckey, P2, tid);
-        // ---- merge: a node's new place = its place in its own list + the nodes of the other list ahead of it --------
-        const int nxt = cur ^ 1;
-        for (int j = tid; j < C; j += 256) {
-            const u64 ck = L.ckey[j];
-            int lo = 0, hi = np;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (L.pkey[cur][mid] > ck) lo = mid + 1; else hi = mid;
+            if (tid < np) {
+                int lo = 0, hi = C;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (L.ckey[mid] > k) lo = mid + 1; else hi = mid;
+                }
+                if (tid + lo < N) { L.pkey[nxt][tid + lo] = k; L.pval[nxt][tid + lo] = v; }
             }
-            if (j + lo < N) {
-                L.pkey[nxt][j + lo] = ck;
-                L.pval[nxt][j + lo] = (uint32_t)L.lex2id[(0xFFFFu - (uint32_t)(ck & 0xFFFFu)) >> lg] << 12;
-            }
-        }
-        if (tid < np) {
-            const u64 k = L.pkey[cur][tid];
-            int lo = 0, hi = C;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (L.ckey[mid] > k) lo = mid + 1; else hi = mid;
-            }
-            if (tid + lo < N) { L.pkey[nxt][tid + lo] = k; L.pval[nxt][tid + lo] = L.pval[cur][tid]; }
         }
         L.cnt_lex[tid] = 0;
         np = min(np + C, N);
         cur = nxt;
+        if (tid < 3) L.pkey[cur][np + tid] = 0ull;
         __syncthreads();
         // ---- the new level's nodes get their id and their lexicographic place --------------------------------------
-        bool mine = false;
-        uint32_t lexkey = 0u;
-        if (tid < np) {
-            const u64 k = L.pkey[cur][tid];
-            mine = 31 - (int)((k >> 16) & 31u) == d;
-            lexkey = 0xFFFFu - (uint32_t)(k & 0xFFFFu);
-        }
-        const u64 bal = __builtin_amdgcn_ballot_w64(mine);
+        const u64 k2 = L.pkey[cur][tid < np ? tid : 0];
+        const bool mine2 = tid < np && 31 - (int)((k2 >> 16) & 31u) == d;
+        const uint32_t lexkey = 0xFFFFu - (uint32_t)(k2 & 0xFFFFu);
+        const u64 bal = __builtin_amdgcn_ballot_w64(mine2);
         if (lane == 0) L.wsum2[w] = __builtin_popcountll(bal);
-        if (mine) atomicAdd(&L.cnt_lex[lexkey >> lg], 1);
+        if (mine2) atomicAdd(&L.cnt_lex[lexkey >> lg], 1);
         __syncthreads();
-        int place = __builtin_popcountll(bal & below);
-        for (int ww = 0; ww < w; ++ww) place += L.wsum2[ww];
+        const int p0 = L.wsum2[0], p1 = L.wsum2[1], p2 = L.wsum2[2];
+        const int place = __builtin_popcountll(bal & below) + (w > 0 ? p0 : 0) + (w > 1 ? p1 : 0) + (w > 2 ? p2 : 0);
         const int cl = L.cnt_lex[tid];
-        int il = cl;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(il, o);
-            if (lane >= o) il += up;
-        }
+        const int il = wave_incl_scan(cl);
         if (lane == 63) L.wsum[w] = il;
         __syncthreads();
-        int lb = 0;
-        for (int ww = 0; ww < w; ++ww) lb += L.wsum[ww];
-        L.cnt_lex[tid] = lb + il - cl;
+        const int l0 = L.wsum[0], l1 = L.wsum[1], l2 = L.wsum[2];
+        L.cnt_lex[tid] = il - cl + (w > 0 ? l0 : 0) + (w > 1 ? l1 : 0) + (w > 2 ? l2 : 0);
         __syncthreads();
-        if (mine) {
-            const uint32_t lexpos = (uint32_t)L.cnt_lex[lexkey >> lg] + (lexkey & (uint32_t)(KP - 1));
-            L.pval[cur][tid] = (uint32_t)((d - 1) * 256 + place) | (L.pval[cur][tid] & 0x00FFF000u) | (lexpos << 24);
+        const uint32_t lexpos = (uint32_t)L.cnt_lex[mine2 ? lexkey >> lg : 0] + (lexkey & (uint32_t)(KP - 1));
+        const uint32_t pv2 = L.pval[cur][tid < np ? tid : 0];
+        if (mine2) {
+            L.pval[cur][tid] = (uint32_t)((d - 1) * 256 + place) | (pv2 & 0x00FFF000u) | (lexpos << 24);
             L.lex2id[lexpos] = (uint16_t)((d - 1) * 256 + place);
         }
         __syncthreads();
@@ -1136,11 +1235,11 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
         beam_block(S, BM, B, K, KP, beam_width, tid, parent, token, depth, rho, n_out, ahat);
         return;
     }
-    // Which expansion: the level-synchronous one pays per level (measured: about 4.8 us up to 64 nodes, 5.3 to 128,
-    // 6.2 beyond), the one-wavefront one per node (0.23 / 0.27 / 0.38 us), and with the early stop it ends at the
-    // chosen budget, typically a quarter of N_max.  The tree cannot be deeper than the greedy chain stays above the
-    // N-th best token of the first position (every node scores at least as much as the tree's last one, which
-    // scores at least that); a tree of depth 1 is the first level's list as it stands.
+    // Which expansion: the level-synchronous one pays per level (measured: about 2.5 us up to 32 nodes, 3.0 to 64,
+    // 3.6 to 128, 4.2 beyond), the one-wavefront one per node (0.27 / 0.31 / 0.41 us up to 64 / 128 / 256 nodes), and
+    // with the early stop it ends at the chosen budget, typically a quarter of N_max.  The tree cannot be deeper than
+    // the greedy chain stays above the N-th best token of the first position (every node scores at least as much as
+    // the tree's last one, which scores at least that); a tree of depth 1 is the first level's list as it stands.
     if (tid == 0) {
         int reach = 0;
         if (algo == 0) {
@@ -1152,8 +1251,8 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
                 reach = k + 1;
             }
         }
-        const float per_level = N <= 64 ? 4.8f : N <= 128 ? 5.3f : 6.2f;
-        const float per_node = N <= 64 ? 0.23f : N <= 128 ? 0.27f : 0.38f;
+        const float per_level = N <= 32 ? 2.5f : N <= 64 ? 3.0f : N <= 128 ? 3.6f : 4.2f;
+        const float per_node = N <= 64 ? 0.27f : N <= 128 ? 0.31f : 0.41f;
         const float nodes = ad.cost ? 0.25f * (float)N : (float)N;
         use_levels = algo == 2 || (algo == 0 && (reach <= 1 || (float)reach * per_level < nodes * per_node));
     }
