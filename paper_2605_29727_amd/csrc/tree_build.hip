@@ -89,10 +89,6 @@ __device__ __forceinline__ void publish(float *q_row, uint32_t *tok_row, int r, 
     __hip_atomic_store(tok_row + r, tok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ uint32_t published_tok(const uint32_t *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // ------------------------------------------------------------------------------------------------
 // Step 1: per-thread maxima.  Workgroup (chunk, row) scans elements chunk*SCAN .. chunk*SCAN + SCAN - 1 of the
@@ -194,7 +190,8 @@ struct ExpandLds {                          // the expansion
     float q[MAXB * BTV_MAX_NODES + 64];     // q[k*KP + r]: probability of rank r at position k (+ padding: q[..][r+1] is
                                             // fetched, not used, also for the last rank of the last position)
     double cost[BTV_MAX_NODES];             // adaptive budget: estimated cycle latency at budget n + 1
-    const uint32_t *tok;                    // token ids of the same lists, left in memory: read once per emitted node
+    uint32_t tok[MAXB * BTV_MAX_NODES];     // token ids of the same lists (fetched with q: a read from memory per emitted
+                                            // node at the end of the expansion would be one more round trip)
 };
 
 // The level-synchronous expansion: pool = the best nodes found so far, in emission order; candidates of one level.
@@ -544,7 +541,7 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
         const int i = r * 64 + lane;
         if (i < n) {
             const uint32_t idx = o_rec[r] & 0x1FFFu;
-            token[i] = (int32_t)published_tok(S.tok + idx);
+            token[i] = (int32_t)S.tok[idx];
             parent[i] = (int32_t)(o_rec[r] >> 13) - 1;
             if (depth) depth[i] = (int)(idx >> lg) + 1;
             if (rho) rho[i] = o_rho[r];
@@ -929,7 +926,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
         const int idx = (dep - 1) * KP + (int)(lexkey & (uint32_t)(KP - 1));
         const uint32_t pu = (v >> 12) & 0xFFFu;
         const float r = __uint_as_float((uint32_t)(k >> 32));
-        token[tid] = (int32_t)published_tok(S.tok + idx);
+        token[tid] = (int32_t)S.tok[idx];
         parent[tid] = pu == 0xFFFu ? -1 : (int32_t)L.pos_of[pu];
         if (depth) depth[tid] = dep;
         if (rho) rho[tid] = r;
@@ -990,7 +987,7 @@ __device__ __forceinline__ void beam_block(const ExpandLds &S, BeamLds &Bm, int 
             if (rank < keep) {
                 const int nd = n + rank;
                 parent[nd] = Bm.node[cur][b];
-                token[nd] = (int32_t)published_tok(S.tok + k * KP + rk);
+                token[nd] = (int32_t)S.tok[k * KP + rk];
                 if (depth) depth[nd] = k + 1;
                 if (rho) rho[nd] = r;
                 Bm.rho[cur ^ 1][rank] = r;
@@ -1210,9 +1207,31 @@ __global__ __launch_bounds__(256) void tb_rank_expand(const float *marg, int V, 
     if (tid == 0) RL.last = __hip_atomic_fetch_add(&ctr[req].done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == B - 1;
     __syncthreads();
     if (!RL.last) return;
-    for (int e = tid; e < B * KP; e += 256)
-        S.q[e] = __hip_atomic_load(top_q + (size_t)req * B * KP + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid == 0) S.tok = top_tok + (size_t)req * B * KP;
+    {   // all of a thread's loads are issued before the first is stored (a load and its store per loop trip would
+        // make every trip a round trip to memory): 1, 4 or MAXB entries of each list per thread
+        const size_t lists = (size_t)req * B * KP;
+        const int n = B * KP;
+        auto fetch = [&](auto per_thread) {
+            constexpr int PT = decltype(per_thread)::value;
+            float qv[PT];
+            uint32_t tv[PT];
+#pragma unroll
+            for (int i = 0; i < PT; ++i) {
+                const int e = tid + 256 * i, ee = e < n ? e : 0;
+                qv[i] = __hip_atomic_load(top_q + lists + ee, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tv[i] = __hip_atomic_load(top_tok + lists + ee, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int i = 0; i < PT; ++i) {
+                const int e = tid + 256 * i;
+                if (e < n) { S.q[e] = qv[i]; S.tok[e] = tv[i]; }
+            }
+        };
+        if (n <= 256) fetch(std::integral_constant<int, 1>{});
+        else if (n <= 1024) fetch(std::integral_constant<int, 4>{});
+        else fetch(std::integral_constant<int, MAXB>{});
+    }
+
     if (bt.n_nodes) {                          // this request's budget and output rows
         const int o0 = bt.q_offset[req], room = bt.q_offset[req + 1] - o0, want = bt.n_nodes[req];
         const bool bad = o0 < 0 || want < 0 || want > N || want > room;
