@@ -1359,21 +1359,48 @@ __global__ __launch_bounds__(RW * KW * 64, 2) void tv_attn_bf16(AttnParams p)
 // Split-K combine: O[row] = sum_s w_s a_s O'_s / sum_s w_s l_s with w_s = exp2((m_s - max m) * scale*log2 e), O'_s the
 // fp16 partial and a_s the magnitude it was divided by.
 // 8 rows per workgroup, 32 lanes per row, each lane owns D/32 consecutive channels.  Lane j of a row fetches the
-// (m, l) pairs of splits j, j + 32, ... and computes their weights (handed to the other lanes by shuffles); the
-// partial rows of up to 32 splits are fetched by independent loads issued before anything is waited for, so the
-// kernel costs about one memory round trip whatever the number of splits.
+// (m, l) pairs of splits j, j + 32, ... and computes their weights; the partial rows of up to 32 splits are fetched
+// by independent loads issued before anything is waited for, so the kernel costs about one memory round trip
+// whatever the number of splits.  What happens between the lanes of a row stays off the LDS crossbar where it can:
+// maximum and sum over the 32 lanes are DPP steps within the rows of 16 and one swap between the two rows (they were
+// five dependent ds_bpermute round trips each), and the 32 weights reach every lane through one LDS store and eight
+// 16-byte reads of the same address (they were 32 shuffles, each waited for before its multiply-adds).
+__device__ __forceinline__ float row32_max(float x, int lane)
+{
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0xB1, 0xF, 0xF, false)));    // quad_perm [1,0,3,2]
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x4E, 0xF, 0xF, false)));    // quad_perm [2,3,0,1]
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x141, 0xF, 0xF, false)));   // row_half_mirror
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x140, 0xF, 0xF, false)));   // row_mirror
+    const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(x, __uint_as_float((lane & 16) ? sw[0] : sw[1]));                                               // the other row of 16
+}
+
+__device__ __forceinline__ float row32_sum(float x, int lane)
+{
+    x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0xB1, 0xF, 0xF, false));
+    x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x4E, 0xF, 0xF, false));
+    x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x141, 0xF, 0xF, false));
+    x += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x140, 0xF, 0xF, false));
+    const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return x + __uint_as_float((lane & 16) ? sw[0] : sw[1]);
+}
+
 template <int D, bool PAGED>
 __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
 {
     constexpr int E = D / 32;
     typedef _Float16 hvec __attribute__((ext_vector_type(E)));
+    __shared__ __attribute__((aligned(16))) float wsh[8][32];
+    // every argument in one round trip (the argument block is cold in every launch)
+    asm volatile("" ::"s"(p.O), "s"(p.q_offset), "s"(p.prefix_len), "s"(p.Opart), "s"(p.ML), "s"(p.M), "s"(p.L), "s"(p.Hq),
+                 "s"(p.max_blocks), "s"(p.total_rows), "s"(p.total_M), "s"(p.sps), "s"(p.out_scale));
     const int rq = blockIdx.y;
     const Req rq_ = load_req<PAGED>(p, rq);
     if (!rq_.ok) return;
     const int stages = (rq_.L + rq_.M + TK - 1) / TK;
     const int nsplit_r = (stages + p.sps - 1) / p.sps;
     if (nsplit_r == 1) return;                      // the attention kernel wrote O directly
-    const int lr = blockIdx.x * 8 + (threadIdx.x >> 5), lane = threadIdx.x & 31;
+    const int rin = threadIdx.x >> 5, lr = blockIdx.x * 8 + rin, lane = threadIdx.x & 31;
     if (lr >= rq_.M * p.Hq) return;
     const size_t row = (size_t)rq_.q0 * p.Hq + lr;
     const size_t sstride = (size_t)p.total_rows;
@@ -1386,8 +1413,8 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
     float den = 0.f;
     for (int s0 = 0; s0 < nsplit_r; s0 += 32) {     // one pass for up to 32 splits
         const int s_mine = s0 + lane;
-        const float4 ml = s_mine < nsplit_r ? *reinterpret_cast<const float4 *>(p.ML + (s_mine * sstride + row) * 4)
-                                            : make_float4(NEG_BIG, 0.f, 0.f, 0.f);
+        const float4 mlr = *reinterpret_cast<const float4 *>(p.ML + ((size_t)min(s_mine, nsplit_r - 1) * sstride + row) * 4);
+        const float4 ml = s_mine < nsplit_r ? mlr : make_float4(NEG_BIG, 0.f, 0.f, 0.f);
         hvec part[32];
 #pragma unroll
         for (int g = 0; g < 4; ++g)
@@ -1398,27 +1425,28 @@ __global__ __launch_bounds__(256) void tv_combine_bf16(AttnParams p)
                     part[8 * g + b] = *reinterpret_cast<const hvec *>(p.Opart + (s * sstride + row) * D + lane * E);
                 }
             }
-        if (s0 == 0) {
-            mmax = fmaxf(mmax, ml.x);
-#pragma unroll
-            for (int off = 16; off >= 1; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 32));
-        }
+        if (s0 == 0) mmax = row32_max(fmaxf(mmax, ml.x), (int)threadIdx.x);
         const float w = s_mine < nsplit_r ? __builtin_amdgcn_exp2f(ml.x - mmax) : 0.f;
         den += w * ml.y;
-        const float wz = w * ml.z;                             // weight times the partial's magnitude
+        wsh[rin][lane] = w * ml.z;                              // weight times the partial's magnitude; 0 past the last split
+        // (the row's 32 lanes are one half of a wavefront: its LDS operations complete in order, no barrier needed)
+        float wgt[32];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float4 x = *reinterpret_cast<const float4 *>(&wsh[rin][4 * q]);
+            wgt[4 * q] = x.x; wgt[4 * q + 1] = x.y; wgt[4 * q + 2] = x.z; wgt[4 * q + 3] = x.w;
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             if (s0 + 8 * g < nsplit_r) {
 #pragma unroll
                 for (int b = 0; b < 8; ++b) {
-                    const float wgt = __shfl(wz, 8 * g + b, 32);     // 0 for splits past the last
 #pragma unroll
-                    for (int e = 0; e < E; ++e) acc[e] += wgt * (float)part[8 * g + b][e];
+                    for (int e = 0; e < E; ++e) acc[e] += wgt[8 * g + b] * (float)part[8 * g + b][e];
                 }
             }
     }
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) den += __shfl_xor(den, off, 32);
+    den = row32_sum(den, (int)threadIdx.x);
     const float inv = p.out_scale / den;
     uint16_t *dst = static_cast<uint16_t *>(p.O) + row * D + lane * E;
     if (E == 4) {
