@@ -716,6 +716,8 @@ __device__ __forceinline__ float load_logit(const void *logits, size_t idx)
 // exponent and three mantissa bits, the (e, q0) pairs moved into bin order): token v contributes iff q0/e < alpha/b1,
 // so Z is a prefix sum over the sorted pairs below the threshold's bin plus an exact scan of that one bin.
 constexpr int SW_BINS = 2048;
+constexpr int SW_PBINS = 2048;      // bins of a row that is prepared ahead of the walk (sw_bin_at); 4096 measured slower:
+                                    // what the walk saves per rejection, the scatter kernel pays in histogram reads
 constexpr int SW_BUILD_MIN = 40;    // children still untried at a node for the sort to be worth its cost (about 30 passes)
 constexpr int SW_PRE_MIN = 6;       // children of the root from which its row is sorted ahead of the walk (a few passes' worth)
 constexpr int SW_WIN = 8192;        // sorted pairs kept in LDS around the threshold
@@ -724,6 +726,19 @@ __device__ __forceinline__ int sw_bin(float ratio)
 {
     const uint32_t b = (__float_as_uint(ratio) & 0x7FFFFFFFu) >> 20;      // NaN (0/0) and inf (e = 0) land on top: never active
     return (int)(b < (uint32_t)SW_BINS ? b : (uint32_t)SW_BINS - 1u);
+}
+
+// The same order-preserving map with the bins spent where the ratios are: binades elo .. (biased exponents) get 2^m
+// bins each, what lies below shares bin 0 and what lies above (inf and NaN included) the last bin.  { 0, 3 } is sw_bin.
+struct SwBin { int elo, m; };
+
+__device__ __forceinline__ int sw_bin_at(float ratio, SwBin p)
+{
+    const uint32_t u = __float_as_uint(ratio) & 0x7FFFFFFFu;
+    const int d = (int)(u >> 23) - p.elo;
+    if (d < 0) return 0;
+    const uint32_t b = ((uint32_t)d << p.m) | ((u & 0x7FFFFFu) >> (23 - p.m));
+    return (int)(b < (uint32_t)SW_PBINS ? b : (uint32_t)SW_PBINS - 1u);
 }
 
 // ---- the root's row sorted ahead of the walk, by many workgroups ---------------------------------------------------
@@ -742,10 +757,16 @@ struct SwPre {                      // in the workspace, behind es and eq_sorted
     float mx;
     double z, tq;
     float wg_max[SW_PRE_WGS];
+    float wg_tlo[SW_PRE_WGS], wg_thi[SW_PRE_WGS];         // range of log2(q0) - logit * log2(e) over the slice's tokens with q0 > 0
     double wg_z[SW_PRE_WGS], wg_tq[SW_PRE_WGS];
-    int start[SW_BINS + 1];
+    int start[SW_PBINS + 1];
     double chunk_e[SW_BINS], chunk_q[SW_BINS];            // sums over chunk c of the sorted pairs (not yet prefix sums)
-    int hist[SW_PRE_WGS][SW_BINS];                        // pairs of workgroup w in bin b
+    int hist[SW_PRE_WGS][SW_PBINS];                       // pairs of workgroup w in bin b
+    // what the walk leaves for the bonus draw, and the draw's per-wavefront totals
+    double b_alpha, b_beta, b_u;
+    int b_has_q, b_depth;
+    double b_tot[SW_PRE_WGS * 16];
+    int b_last[SW_PRE_WGS * 16];
 };
 
 __device__ __forceinline__ bool sw_root_is_wide(const int32_t *parent, int M, int tid, double *shd)
@@ -762,9 +783,31 @@ __device__ __forceinline__ void sw_slice(int V, int wg, int &v0, int &v1)
     v1 = min(v0 + per, V);
 }
 
+// Bins of the prepared row: log2(q0 / e) = log2(q0) - (logit - max) * log2(e) lies within the range that sw_pre_max
+// found (plus a binade of slack at either end for the roundings on the way); the binades of that range share the
+// bins, as many per binade as fit.  With the fixed map a row whose ratios span 30 binades used 240 of the 2048 bins
+// and the bin that the falling threshold sits in held 1500 pairs, all of which a rejection must look at.  Every
+// kernel works the parameters out from the same numbers, so they agree.
+__device__ __forceinline__ SwBin sw_bin_params(const SwPre *pre, float mx)
+{
+    float tlo = INFINITY, thi = -INFINITY;
+    for (int w = 0; w < SW_PRE_WGS; ++w) { tlo = fminf(tlo, pre->wg_tlo[w]); thi = fmaxf(thi, pre->wg_thi[w]); }
+    SwBin p = { 0, 3 };
+    const float shift = mx * 1.44269504f;
+    const float lo2 = tlo + shift, hi2 = thi + shift;
+    if (!(lo2 <= hi2) || !(lo2 > -200.f) || !(hi2 < 200.f)) return p;      // no token with q0 > 0, or a range beyond fp32's
+    const int elo = max((int)floorf(lo2) - 1 + 127, 0), ehi = min(max((int)ceilf(hi2) + 1 + 127, elo), 254);
+    const int span = ehi - elo + 1;
+    int m = 3;
+    while (m < 10 && (span << (m + 1)) <= SW_PBINS) ++m;
+    if ((span << m) > SW_PBINS) return p;
+    p.elo = elo; p.m = m;
+    return p;
+}
+
 template <bool BF16>
-__global__ __launch_bounds__(1024) void sw_pre_max(const void *__restrict__ logits, const int32_t *__restrict__ parent, int M, int V,
-                                                   SwPre *pre)
+__global__ __launch_bounds__(1024) void sw_pre_max(const void *__restrict__ logits, const float *__restrict__ q0,
+                                                   const int32_t *__restrict__ parent, int M, int V, SwPre *pre)
 {
     __shared__ double shd[16];
     __shared__ float shf[16];
@@ -773,10 +816,19 @@ __global__ __launch_bounds__(1024) void sw_pre_max(const void *__restrict__ logi
     if (!sw_root_is_wide(parent, M, tid, shd)) return;
     int v0, v1;
     sw_slice(V, blockIdx.x, v0, v1);
-    float mx = -INFINITY;
-    for (int v = v0 + tid; v < v1; v += 1024) mx = fmaxf(mx, load_logit<BF16>(logits, v));
+    float mx = -INFINITY, tlo = INFINITY, thi = -INFINITY;
+    for (int v = v0 + tid; v < v1; v += 1024) {
+        const float x = load_logit<BF16>(logits, v), q = q0[v];
+        mx = fmaxf(mx, x);
+        const float t = __log2f(q) - x * 1.44269504f;
+        if (q > 0.f && fabsf(t) < 1e30f) { tlo = fminf(tlo, t); thi = fmaxf(thi, t); }
+    }
     mx = block_max(mx, shf, tid);
-    if (tid == 0) pre->wg_max[blockIdx.x] = mx;
+    __syncthreads();
+    tlo = -block_max(-tlo, shf, tid);
+    __syncthreads();
+    thi = block_max(thi, shf, tid);
+    if (tid == 0) { pre->wg_max[blockIdx.x] = mx; pre->wg_tlo[blockIdx.x] = tlo; pre->wg_thi[blockIdx.x] = thi; }
 }
 
 template <bool BF16>
@@ -785,12 +837,13 @@ __global__ __launch_bounds__(1024) void sw_pre_exp(const void *__restrict__ logi
                                                    SwPre *pre)
 {
     __shared__ double shd[16];
-    __shared__ int hist[SW_BINS];
+    __shared__ int hist[SW_PBINS];
     const int tid = threadIdx.x;
     if (!sw_root_is_wide(parent, M, tid, shd)) return;
     float mx = pre->wg_max[0];
     for (int w = 1; w < SW_PRE_WGS; ++w) mx = fmaxf(mx, pre->wg_max[w]);
-    for (int b = tid; b < SW_BINS; b += 1024) hist[b] = 0;
+    for (int b = tid; b < SW_PBINS; b += 1024) hist[b] = 0;
+    const SwBin bp = sw_bin_params(pre, mx);
     __syncthreads();
     int v0, v1;
     sw_slice(V, blockIdx.x, v0, v1);
@@ -800,12 +853,12 @@ __global__ __launch_bounds__(1024) void sw_pre_exp(const void *__restrict__ logi
         es[v] = e;
         z += (double)e;
         tq += (double)q;
-        atomicAdd(&hist[sw_bin(__fdiv_rn(q, e))], 1);
+        atomicAdd(&hist[sw_bin_at(__fdiv_rn(q, e), bp)], 1);
     }
     z = block_sum(z, shd, tid);
     tq = block_sum(tq, shd, tid);                            // (the barriers also complete the histogram)
     if (tid == 0) { pre->wg_z[blockIdx.x] = z; pre->wg_tq[blockIdx.x] = tq; if (blockIdx.x == 0) pre->mx = mx; }
-    for (int b = tid; b < SW_BINS; b += 1024) pre->hist[blockIdx.x][b] = hist[b];
+    for (int b = tid; b < SW_PBINS; b += 1024) pre->hist[blockIdx.x][b] = hist[b];
 }
 
 // Bin offsets and scatter in one launch: every workgroup adds up the histograms of all of them (the same 256 KB for
@@ -817,20 +870,32 @@ __global__ __launch_bounds__(1024) void sw_pre_scatter(const float *__restrict__
     __shared__ double shd[16];
     __shared__ int wsum[16];
     __shared__ double part[2][SW_PRE_WGS];
-    __shared__ int cursor[SW_BINS];
+    __shared__ int cursor[SW_PBINS];
+    constexpr int PB = SW_PBINS / 1024;                      // bins per thread: PB * tid .. PB * tid + PB - 1
+    static_assert(PB == 2 || PB == 4, "a thread's bins are fetched as one int2 or int4");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, me = blockIdx.x;
     if (!sw_root_is_wide(parent, M, tid, shd)) return;
     if (me == 0 && tid < SW_PRE_WGS) { part[0][tid] = pre->wg_z[tid]; part[1][tid] = pre->wg_tq[tid]; }
-    int2 h[SW_PRE_WGS];                                      // bins 2*tid and 2*tid + 1 of every workgroup
+    int c[PB], mb[PB];                                       // all workgroups; those before this one
 #pragma unroll
-    for (int w = 0; w < SW_PRE_WGS; ++w) h[w] = *reinterpret_cast<const int2 *>(&pre->hist[w][2 * tid]);
-    int c0 = 0, c1 = 0, m0 = 0, m1 = 0;                      // all workgroups; those before this one
+    for (int k = 0; k < PB; ++k) { c[k] = 0; mb[k] = 0; }
 #pragma unroll
     for (int w = 0; w < SW_PRE_WGS; ++w) {
-        if (w == me) { m0 = c0; m1 = c1; }
-        c0 += h[w].x; c1 += h[w].y;
+        int h[PB];
+        if constexpr (PB == 4) {
+            const int4 x = *reinterpret_cast<const int4 *>(&pre->hist[w][PB * tid]);
+            h[0] = x.x; h[1] = x.y; h[2] = x.z; h[3] = x.w;
+        } else {
+            const int2 x = *reinterpret_cast<const int2 *>(&pre->hist[w][PB * tid]);
+            h[0] = x.x; h[1] = x.y;
+        }
+#pragma unroll
+        for (int k = 0; k < PB; ++k) { mb[k] = w == me ? c[k] : mb[k]; c[k] += h[k]; }
     }
-    int ci = c0 + c1;
+    int own = 0;
+#pragma unroll
+    for (int k = 0; k < PB; ++k) own += c[k];
+    int ci = own;
     for (int off = 1; off < 64; off <<= 1) {
         const int co = __shfl_up(ci, off);
         if (lane >= off) ci += co;
@@ -839,13 +904,16 @@ __global__ __launch_bounds__(1024) void sw_pre_scatter(const float *__restrict__
     __syncthreads();
     int cb = 0;
     for (int w = 0; w < wv; ++w) cb += wsum[w];
-    const int s0 = cb + ci - (c0 + c1), s1 = s0 + c0;        // where bins 2*tid and 2*tid + 1 start
-    cursor[2 * tid] = s0 + m0;
-    cursor[2 * tid + 1] = s1 + m1;
+    int st[PB + 1];                                          // where the thread's bins start
+    st[0] = cb + ci - own;
+#pragma unroll
+    for (int k = 0; k < PB; ++k) st[k + 1] = st[k] + c[k];
+#pragma unroll
+    for (int k = 0; k < PB; ++k) cursor[PB * tid + k] = st[k] + mb[k];
     if (me == 0) {
-        pre->start[2 * tid] = s0;
-        pre->start[2 * tid + 1] = s1;
-        if (tid == 1023) pre->start[SW_BINS] = s1 + c1;
+#pragma unroll
+        for (int k = 0; k < PB; ++k) pre->start[PB * tid + k] = st[k];
+        if (tid == 1023) pre->start[SW_PBINS] = st[PB];
         if (tid == 0) {
             double z = 0.0, tq = 0.0;
             for (int w = 0; w < SW_PRE_WGS; ++w) { z += part[0][w]; tq += part[1][w]; }
@@ -856,9 +924,10 @@ __global__ __launch_bounds__(1024) void sw_pre_scatter(const float *__restrict__
     __syncthreads();
     int v0, v1;
     sw_slice(V, me, v0, v1);
+    const SwBin bp = sw_bin_params(pre, pre->mx);
     for (int v = v0 + tid; v < v1; v += 1024) {
         const float e = es[v], q = q0[v];
-        const int pos = atomicAdd(&cursor[sw_bin(__fdiv_rn(q, e))], 1);
+        const int pos = atomicAdd(&cursor[sw_bin_at(__fdiv_rn(q, e), bp)], 1);
         eq_sorted[pos] = make_float2(e, q);
     }
 }
@@ -881,21 +950,39 @@ __global__ __launch_bounds__(1024) void sw_pre_chunks(const int32_t *__restrict_
     }
 }
 
+// The window of sorted pairs [lo, hi), hi - lo <= SW_WIN, by 1024 threads: every thread's loads are issued before the
+// first is stored (a load and its store per loop trip is a round trip to the L2 per trip).
+__device__ __forceinline__ void load_window(float2 *win, const float2 *eq_sorted, int lo, int hi, int tid)
+{
+    static_assert(SW_WIN % 1024 == 0, "whole trips of the workgroup");
+    float2 t[SW_WIN / 1024];
+#pragma unroll
+    for (int q = 0; q < SW_WIN / 1024; ++q) {
+        const int i = lo + tid + 1024 * q;
+        t[q] = eq_sorted[i < hi ? i : lo];
+    }
+#pragma unroll
+    for (int q = 0; q < SW_WIN / 1024; ++q) {
+        const int i = lo + tid + 1024 * q;
+        if (i < hi) win[i - lo] = t[q];
+    }
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__ logits, const float *__restrict__ marg, int B,
                                                         const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
                                                         int M, int V, const float *__restrict__ uniforms,
                                                         float *__restrict__ es, float2 *__restrict__ eq_sorted,
-                                                        const SwPre *__restrict__ pre, int32_t *path, int32_t *n_acc,
-                                                        int32_t *bonus, uint32_t *flag)
+                                                        SwPre *__restrict__ pre, int32_t *path, int32_t *n_acc,
+                                                        uint32_t *flag)
 {
     __shared__ double shd[16];
     __shared__ float shf[16];
     __shared__ double seg[1024];
     __shared__ double chunkE[SW_BINS], chunkQ[SW_BINS];  // sums of e and q0 over the sorted pairs before chunk c
-    __shared__ int start[SW_BINS + 1], cursor[SW_BINS];
+    __shared__ int start[SW_PBINS + 1], cursor[SW_BINS];
     __shared__ float2 win[SW_WIN];                        // sorted pairs win_lo .. win_hi - 1 (the threshold only falls,
-    __shared__ int found, lastpos;                        // so the window is refilled towards lower positions)
+                                                          // so the window is refilled towards lower positions)
     __shared__ float2 child_eq[BTV_MAX_NODES];            // (e, q0) of node c's token, fetched for all nodes at once
     __shared__ int kid_node[BTV_MAX_NODES];               // the current node's children in node order (prepared row only)
     __shared__ float kid_u[BTV_MAX_NODES];
@@ -951,8 +1038,19 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
             __syncthreads();
         };
         if (prepared) {                                          // (prepared implies d == 0 < B)
-            for (int b = tid; b <= SW_BINS; b += 1024) start[b] = pre->start[b];
-            for (int c = tid; c < SW_BINS; c += 1024) { chunkE[c] = pre->chunk_e[c]; chunkQ[c] = pre->chunk_q[c]; }
+            {   // every load before the first store: one round trip to the L2, not one per loop trip
+                int sb[SW_PBINS / 1024];
+                double ce[SW_BINS / 1024], cq[SW_BINS / 1024];
+#pragma unroll
+                for (int k = 0; k < SW_PBINS / 1024; ++k) sb[k] = pre->start[tid + 1024 * k];
+#pragma unroll
+                for (int k = 0; k < SW_BINS / 1024; ++k) { ce[k] = pre->chunk_e[tid + 1024 * k]; cq[k] = pre->chunk_q[tid + 1024 * k]; }
+                if (tid == 0) start[SW_PBINS] = pre->start[SW_PBINS];
+#pragma unroll
+                for (int k = 0; k < SW_PBINS / 1024; ++k) start[tid + 1024 * k] = sb[k];
+#pragma unroll
+                for (int k = 0; k < SW_BINS / 1024; ++k) { chunkE[tid + 1024 * k] = ce[k]; chunkQ[tid + 1024 * k] = cq[k]; }
+            }
             __syncthreads();
             scan_chunks();
             binned = true;
@@ -961,6 +1059,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
             // ---- the sorted row is at hand: the children are tried by the first wavefront alone, out of LDS, with no
             // workgroup barrier per rejection; the others only help to move the window of sorted pairs --------------
             const int lane = tid & 63, wv = tid >> 6;
+            const SwBin bp = sw_bin_params(pre, pre->mx);
             {   // the children in node order: (node, uniform), their tokens' (e, q0)
                 const bool mine = tid < M && parent[tid] == cur;
                 const unsigned long long bal = __builtin_amdgcn_ballot_w64(mine);
@@ -1027,17 +1126,26 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                         const double px = alpha * (double)own.x - beta * (double)own.y;
                         if (kid_lhs[j] < (px > 0.0 ? px : 0.0)) { acc = c; ++j; break; }
                         const double b1 = beta + invT;
-                        const int b = sw_bin((float)(b1 > 0.0 ? alpha * recip(b1) : INFINITY));
+                        const int b = sw_bin_at((float)(b1 > 0.0 ? alpha * recip(b1) : INFINITY), bp);
                         const int p0 = start[b], p1 = start[b + 1];
                         const int ch = min(p0 / CH, SW_BINS - 1), lo = ch * CH;
                         double zr = 0.0;
                         if (p1 - lo <= SW_WIN) {
                             if (lo < win_lo || p1 > win_hi) { want_hi = p1; break; }      // the others help to move the window
-                            for (int i = lo + lane; i < p1; i += 64) {
-                                const float2 x = win[i - win_lo];
-                                const double r = alpha * (double)x.x - b1 * (double)x.y;
-                                zr += r > 0.0 ? r : 0.0;
+                            // four reads in flight per trip, none behind a branch (one read, its arithmetic and the loop
+                            // branch per trip made a trip cost an LDS round trip: the larger part of a rejection)
+                            double z4[4] = { 0.0, 0.0, 0.0, 0.0 };
+                            for (int i = lo + lane; i < p1; i += 256) {
+                                float2 x[4];
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) x[q] = win[(i + 64 * q < p1 ? i + 64 * q : lo) - win_lo];
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) {
+                                    const double r = alpha * (double)x[q].x - b1 * (double)x[q].y;
+                                    z4[q] += i + 64 * q < p1 && r > 0.0 ? r : 0.0;
+                                }
                             }
+                            zr = (z4[0] + z4[1]) + (z4[2] + z4[3]);
                         } else {                                 // a bin larger than the window (ratios that nearly all coincide)
                             for (int i = lo + lane; i < p1; i += 64) {
                                 const float2 x = eq_sorted[i];
@@ -1060,7 +1168,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                 if (fast.done) break;
                 win_hi = fast.reload_hi;
                 win_lo = max(win_hi - SW_WIN, 0);
-                for (int i = win_lo + tid; i < win_hi; i += 1024) win[i - win_lo] = eq_sorted[i];
+                load_window(win, eq_sorted, win_lo, win_hi, tid);
                 __syncthreads();
             }
             alpha = fast.alpha; beta = fast.beta; T = fast.T;
@@ -1155,7 +1263,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                             __syncthreads();
                             win_hi = p1;
                             win_lo = max(p1 - SW_WIN, 0);
-                            for (int i = win_lo + tid; i < win_hi; i += 1024) win[i - win_lo] = eq_sorted[i];
+                            load_window(win, eq_sorted, win_lo, win_hi, tid);
                             __syncthreads();
                         }
                         for (int i = lo + tid; i < p1; i += 1024) { const float2 x = win[i - win_lo]; resid(x.x, x.y); }
@@ -1187,112 +1295,167 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
             __syncthreads();                                     // everyone is done with es before it is rewritten
             continue;
         }
-        // bonus: smallest v with cumsum(p_k)[v] > u.  Wavefront w owns a contiguous stretch of the vocabulary; the
-        // stretches' totals tell which wavefront holds the crossing, and only that one looks at its stretch again.
-        const double u = (double)uniforms[ui++];
-        const int lane = tid & 63, wv = tid >> 6;
-        auto pv2 = [&](float ev, float qv) {
-            const double x = has_q ? alpha * (double)ev - beta * (double)qv : alpha * (double)ev;
-            return x > 0.0 ? x : 0.0;
-        };
-        auto pv = [&](int v) { return pv2(es[v], has_q ? q0[v] : 0.f); };
-        const bool wide = vec4 && (reinterpret_cast<uintptr_t>(es) & 15) == 0;
-        // wide loads: a wave instruction covers 256 consecutive tokens, four per lane; stretches are whole instructions
-        const int stretch = wide ? ((V + 15) / 16 + 255) / 256 * 256 : ((V + 15) / 16 + 63) / 64 * 64;
-        const int w0 = min(wv * stretch, V), w1 = min(w0 + stretch, V);
-        double loc = 0.0;
-        int lp = -1;
-        if (wide) {
-#pragma unroll 4
-            for (int v = w0 + lane * 4; v < w1; v += 256) {
-                const float4 a = *reinterpret_cast<const float4 *>(es + v);
-                const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + v) : make_float4(0.f, 0.f, 0.f, 0.f);
-                const double x0 = pv2(a.x, q.x), x1 = pv2(a.y, q.y), x2 = pv2(a.z, q.z), x3 = pv2(a.w, q.w);
-                loc += (x0 + x1) + (x2 + x3);
-                lp = x3 > 0.0 ? v + 3 : x2 > 0.0 ? v + 2 : x1 > 0.0 ? v + 1 : x0 > 0.0 ? v : lp;
-            }
-        } else {
-#pragma unroll 4
-            for (int v = w0 + lane; v < w1; v += 64) { const double x = pv(v); loc += x; lp = x > 0.0 ? v : lp; }
+        // The bonus token is drawn by the two kernels that follow (a pass over the vocabulary in fp64 is bound by the
+        // arithmetic of the one CU this kernel runs on: 16 us of its time): the residual's parameters, the uniform
+        // and the row go to the workspace.
+        if (tid == 0) {
+            pre->b_alpha = alpha; pre->b_beta = beta; pre->b_u = (double)uniforms[ui];
+            pre->b_has_q = has_q ? 1 : 0; pre->b_depth = has_q ? d : 0;
+            *n_acc = n;
         }
-        loc = wave_sum_f64(loc);
-        for (int off = 32; off >= 1; off >>= 1) lp = max(lp, __shfl_xor(lp, off));
-        __syncthreads();                                         // (seg may still be in use by the sort's scans)
-        if (lane == 0) seg[wv] = loc;
-        if (tid == 0) { found = INT_MAX; lastpos = 0; }
-        __syncthreads();
-        if (lane == 0 && lp >= 0) atomicMax(&lastpos, lp);
-        double before = 0.0;
-        for (int w = 0; w < wv; ++w) before += seg[w];
-        if (u >= before && u < before + seg[wv]) {               // exactly one wavefront, or none if u is past the total
-            double running = before;
-            int hit = INT_MAX;
-            if (wide) {
-                // eight instructions' worth of tokens at a time: their totals one after the other until the crossing
-                // instruction is known, then the lanes' prefix inside it, then the token inside the lane
-                for (int g0 = w0; g0 < w1 && hit == INT_MAX; g0 += 8 * 256) {
-                    double part[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const int v = g0 + k * 256 + lane * 4;
-                        part[k] = 0.0;
-                        if (v < w1) {
-                            const float4 a = *reinterpret_cast<const float4 *>(es + v);
-                            const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + v) : make_float4(0.f, 0.f, 0.f, 0.f);
-                            part[k] = (pv2(a.x, q.x) + pv2(a.y, q.y)) + (pv2(a.z, q.z) + pv2(a.w, q.w));
-                        }
-                    }
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        if (hit != INT_MAX) break;
-                        const double tot = wave_sum_f64(part[k]);
-                        if (running + tot > u) {                 // (uniform) the crossing lies in this instruction's 256 tokens
-                            const int v = g0 + k * 256 + lane * 4;
-                            double x0 = 0.0, x1 = 0.0, x2 = 0.0, x3 = 0.0;
-                            if (v < w1) {
-                                const float4 a = *reinterpret_cast<const float4 *>(es + v);
-                                const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + v) : make_float4(0.f, 0.f, 0.f, 0.f);
-                                x0 = pv2(a.x, q.x); x1 = pv2(a.y, q.y); x2 = pv2(a.z, q.z); x3 = pv2(a.w, q.w);
-                            }
-                            double incl = (x0 + x1) + (x2 + x3);
-                            const double own = incl;
-                            for (int off = 1; off < 64; off <<= 1) {   // inclusive prefix over the lanes
-                                const double o = __shfl_up(incl, off);
-                                if (lane >= off) incl += o;
-                            }
-                            const double excl = running + (incl - own);
-                            int mine = INT_MAX;                  // first of this lane's four tokens whose cumulative sum passes u
-                            if (v < w1) {
-                                if (excl + x0 > u) mine = v;
-                                else if (excl + (x0 + x1) > u) mine = v + 1;
-                                else if (excl + ((x0 + x1) + x2) > u) mine = v + 2;
-                                else if (excl + ((x0 + x1) + (x2 + x3)) > u) mine = v + 3;
-                            }
-                            for (int off = 32; off >= 1; off >>= 1) mine = min(mine, __shfl_xor(mine, off));
-                            if (mine != INT_MAX) hit = mine;     // (else rounding: the crossing is the next positive token)
-                        }
-                        running += tot;
-                    }
-                }
-            } else {
-                for (int v0 = w0; v0 < w1 && hit == INT_MAX; v0 += 64) {
-                    const int v = v0 + lane;
-                    double x = v < w1 ? pv(v) : 0.0;
-                    for (int off = 1; off < 64; off <<= 1) {     // inclusive prefix over the 64 tokens
-                        const double o = __shfl_up(x, off);
-                        if (lane >= off) x += o;
-                    }
-                    const unsigned long long over = __builtin_amdgcn_ballot_w64(v < w1 && running + x > u);
-                    if (over) hit = v0 + __builtin_ctzll(over);
-                    running += __shfl(x, 63);
-                }
-            }
-            if (lane == 0) found = hit != INT_MAX ? hit : max(lp, 0);     // rounding left the crossing just past the stretch
-        }
-        __syncthreads();
-        if (tid == 0) { *bonus = found == INT_MAX ? lastpos : found; *n_acc = n; }
         break;
     }
+}
+
+// Bonus draw, first kernel: smallest v with cumsum(p_k)[v] > u, p_k = max(alpha e - beta q0, 0).  Wavefront g of
+// SW_PRE_WGS * 16 owns a contiguous stretch of the vocabulary (whole wave instructions of 256 tokens, four per lane, when
+// the rows allow 16-byte loads) and leaves its total and its last positive token.
+__device__ __forceinline__ double sw_resid(double alpha, double beta, bool has_q, float ev, float qv)
+{
+    const double x = has_q ? alpha * (double)ev - beta * (double)qv : alpha * (double)ev;
+    return x > 0.0 ? x : 0.0;
+}
+
+__device__ __forceinline__ void sw_stretch(int V, bool wide, int g, int &w0, int &w1)
+{
+    const int waves = SW_PRE_WGS * 16;
+    const int stretch = wide ? ((V + waves - 1) / waves + 255) / 256 * 256 : ((V + waves - 1) / waves + 63) / 64 * 64;
+    w0 = (int)min((long long)g * stretch, (long long)V);
+    w1 = min(w0 + stretch, V);
+}
+
+__global__ __launch_bounds__(1024) void sw_bonus_totals(const float *__restrict__ marg, int V, const float *__restrict__ es, SwPre *pre)
+{
+    const int tid = threadIdx.x, lane = tid & 63, g = blockIdx.x * 16 + (tid >> 6);
+    const double alpha = pre->b_alpha, beta = pre->b_beta;
+    const bool has_q = pre->b_has_q != 0;
+    const float *q0 = marg + (size_t)pre->b_depth * V;
+    const bool wide = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(q0) & 15) == 0 && (reinterpret_cast<uintptr_t>(es) & 15) == 0;
+    int w0, w1;
+    sw_stretch(V, wide, g, w0, w1);
+    double loc = 0.0;
+    int lp = -1;
+    if (wide) {
+        const int trips = (w1 - w0 + 255) / 256;                  // (wave-uniform)
+        for (int t0 = 0; t0 < trips; t0 += 4) {                   // the loads of a trip issued together, none behind a branch
+            float4 a[4], q[4];
+            int vv[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int v = w0 + (t0 + k) * 256 + lane * 4;
+                vv[k] = t0 + k < trips && v < w1 ? v : -1;
+                a[k] = *reinterpret_cast<const float4 *>(es + (vv[k] < 0 ? 0 : v));
+                q[k] = has_q ? *reinterpret_cast<const float4 *>(q0 + (vv[k] < 0 ? 0 : v)) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool ok = vv[k] >= 0;
+                const double x0 = ok ? sw_resid(alpha, beta, has_q, a[k].x, q[k].x) : 0.0, x1 = ok ? sw_resid(alpha, beta, has_q, a[k].y, q[k].y) : 0.0,
+                             x2 = ok ? sw_resid(alpha, beta, has_q, a[k].z, q[k].z) : 0.0, x3 = ok ? sw_resid(alpha, beta, has_q, a[k].w, q[k].w) : 0.0;
+                loc += (x0 + x1) + (x2 + x3);
+                lp = x3 > 0.0 ? vv[k] + 3 : x2 > 0.0 ? vv[k] + 2 : x1 > 0.0 ? vv[k] + 1 : x0 > 0.0 ? vv[k] : lp;
+            }
+        }
+    } else {
+        for (int v = w0 + lane; v < w1; v += 64) {
+            const double x = sw_resid(alpha, beta, has_q, es[v], has_q ? q0[v] : 0.f);
+            loc += x;
+            lp = x > 0.0 ? v : lp;
+        }
+    }
+    loc = wave_sum_f64(loc);
+    for (int off = 32; off >= 1; off >>= 1) lp = max(lp, __shfl_xor(lp, off));
+    if (lane == 0) { pre->b_tot[g] = loc; pre->b_last[g] = lp; }
+}
+
+// Second kernel, one wavefront: the totals in order tell which stretch holds the crossing; that stretch is looked at
+// again, a wave instruction's worth of tokens at a time: its total, then the lanes' prefix inside it, then the token
+// inside the lane.
+__global__ __launch_bounds__(64) void sw_bonus_pick(const float *__restrict__ marg, int V, const float *__restrict__ es,
+                                                    const SwPre *__restrict__ pre, int32_t *bonus)
+{
+    constexpr int WAVES = SW_PRE_WGS * 16, PER = WAVES / 64;
+    const int lane = threadIdx.x;
+    const double alpha = pre->b_alpha, beta = pre->b_beta, u = pre->b_u;
+    const bool has_q = pre->b_has_q != 0;
+    const float *q0 = marg + (size_t)pre->b_depth * V;
+    const bool wide = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(q0) & 15) == 0 && (reinterpret_cast<uintptr_t>(es) & 15) == 0;
+    // lane l holds stretches PER * l .. PER * l + PER - 1: sums before each of them, added in stretch order
+    double t[PER];
+    int lastpos = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) { t[k] = pre->b_tot[PER * lane + k]; lastpos = max(lastpos, pre->b_last[PER * lane + k]); }
+    for (int off = 32; off >= 1; off >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, off));
+    double own = 0.0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) own += t[k];
+    double incl = own;
+    for (int off = 1; off < 64; off <<= 1) {
+        const double o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    double before = incl - own;
+    int gsel = INT_MAX;
+    double bsel = 0.0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        if (gsel == INT_MAX && u >= before && u < before + t[k]) { gsel = PER * lane + k; bsel = before; }
+        before += t[k];
+    }
+    const unsigned long long has = __builtin_amdgcn_ballot_w64(gsel != INT_MAX);
+    int found = INT_MAX;
+    if (has != 0ull) {                                           // (uniform) none if u is past the total
+        const int src = __builtin_ctzll(has);
+        const int g = __shfl(gsel, src);
+        double running = __shfl(bsel, src);
+        int w0, w1;
+        sw_stretch(V, wide, g, w0, w1);
+        int hit = INT_MAX;
+        if (wide) {
+            for (int g0 = w0; g0 < w1 && hit == INT_MAX; g0 += 256) {
+                const int v = g0 + lane * 4;
+                const bool ok = v < w1;
+                const float4 a = *reinterpret_cast<const float4 *>(es + (ok ? v : 0));
+                const float4 q = has_q ? *reinterpret_cast<const float4 *>(q0 + (ok ? v : 0)) : make_float4(0.f, 0.f, 0.f, 0.f);
+                const double x0 = ok ? sw_resid(alpha, beta, has_q, a.x, q.x) : 0.0, x1 = ok ? sw_resid(alpha, beta, has_q, a.y, q.y) : 0.0,
+                             x2 = ok ? sw_resid(alpha, beta, has_q, a.z, q.z) : 0.0, x3 = ok ? sw_resid(alpha, beta, has_q, a.w, q.w) : 0.0;
+                double inc = (x0 + x1) + (x2 + x3);
+                const double mine_sum = inc;
+                const double tot = wave_sum_f64(inc);
+                if (running + tot > u) {                         // (uniform) the crossing lies in these 256 tokens
+                    for (int off = 1; off < 64; off <<= 1) {     // inclusive prefix over the lanes
+                        const double o = __shfl_up(inc, off);
+                        if (lane >= off) inc += o;
+                    }
+                    const double excl = running + (inc - mine_sum);
+                    int mine = INT_MAX;                          // first of this lane's four tokens whose cumulative sum passes u
+                    if (ok) {
+                        if (excl + x0 > u) mine = v;
+                        else if (excl + (x0 + x1) > u) mine = v + 1;
+                        else if (excl + ((x0 + x1) + x2) > u) mine = v + 2;
+                        else if (excl + ((x0 + x1) + (x2 + x3)) > u) mine = v + 3;
+                    }
+                    for (int off = 32; off >= 1; off >>= 1) mine = min(mine, __shfl_xor(mine, off));
+                    if (mine != INT_MAX) hit = mine;             // (else rounding: the crossing is the next positive token)
+                }
+                running += tot;
+            }
+        } else {
+            for (int v0 = w0; v0 < w1 && hit == INT_MAX; v0 += 64) {
+                const int v = v0 + lane;
+                double x = v < w1 ? sw_resid(alpha, beta, has_q, es[v], has_q ? q0[v] : 0.f) : 0.0;
+                for (int off = 1; off < 64; off <<= 1) {         // inclusive prefix over the 64 tokens
+                    const double o = __shfl_up(x, off);
+                    if (lane >= off) x += o;
+                }
+                const unsigned long long over = __builtin_amdgcn_ballot_w64(v < w1 && running + x > u);
+                if (over) hit = v0 + __builtin_ctzll(over);
+                running += __shfl(x, 63);
+            }
+        }
+        found = hit != INT_MAX ? hit : max(pre->b_last[g], 0);   // rounding left the crossing just past the stretch
+    }
+    if (lane == 0) *bonus = found == INT_MAX ? lastpos : found;
 }
 
 int check_accept(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
@@ -1423,10 +1586,10 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     uint32_t *flag = static_cast<uint32_t *>(ws);
     // the root's row, prepared by many workgroups when the root has a wide fan (each kernel finds that out itself)
     if (dtype == BTV_BF16) {
-        hipLaunchKernelGGL(sw_pre_max<true>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, parent, M, V, pre);
+        hipLaunchKernelGGL(sw_pre_max<true>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, marginals, parent, M, V, pre);
         hipLaunchKernelGGL(sw_pre_exp<true>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, marginals, parent, M, V, es, pre);
     } else {
-        hipLaunchKernelGGL(sw_pre_max<false>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, parent, M, V, pre);
+        hipLaunchKernelGGL(sw_pre_max<false>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, marginals, parent, M, V, pre);
         hipLaunchKernelGGL(sw_pre_exp<false>, dim3(SW_PRE_WGS), dim3(1024), 0, st, logits, marginals, parent, M, V, es, pre);
     }
     hipLaunchKernelGGL(sw_pre_scatter, dim3(SW_PRE_WGS), dim3(1024), 0, st, marginals, parent, M, V, es, eq_sorted, pre);
@@ -1434,10 +1597,13 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     BTV_HIP(hipGetLastError());
     if (dtype == BTV_BF16)
         hipLaunchKernelGGL(stochastic_walk<true>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, eq_sorted, pre, path, n_acc, bonus, flag);
+                           uniforms, es, eq_sorted, pre, path, n_acc, flag);
     else
         hipLaunchKernelGGL(stochastic_walk<false>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
-                           uniforms, es, eq_sorted, pre, path, n_acc, bonus, flag);
+                           uniforms, es, eq_sorted, pre, path, n_acc, flag);
+    // the bonus token: per-wavefront totals of the residual on 32 workgroups, then one wavefront finds the crossing
+    hipLaunchKernelGGL(sw_bonus_totals, dim3(SW_PRE_WGS), dim3(1024), 0, st, marginals, V, es, pre);
+    hipLaunchKernelGGL(sw_bonus_pick, dim3(1), dim3(64), 0, st, marginals, V, es, pre, bonus);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
