@@ -925,10 +925,22 @@ __global__ __launch_bounds__(1024) void sw_pre_scatter(const float *__restrict__
     int v0, v1;
     sw_slice(V, me, v0, v1);
     const SwBin bp = sw_bin_params(pre, pre->mx);
-    for (int v = v0 + tid; v < v1; v += 1024) {
-        const float e = es[v], q = q0[v];
-        const int pos = atomicAdd(&cursor[sw_bin_at(__fdiv_rn(q, e), bp)], 1);
-        eq_sorted[pos] = make_float2(e, q);
+    for (int vb = v0; vb < v1; vb += 4 * 1024) {             // four tokens per thread at a time, their loads issued together
+        float e[4], q[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int v = vb + tid + 1024 * k;
+            e[k] = es[v < v1 ? v : v0];
+            q[k] = q0[v < v1 ? v : v0];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int v = vb + tid + 1024 * k;
+            if (v < v1) {
+                const int pos = atomicAdd(&cursor[sw_bin_at(__fdiv_rn(q[k], e[k]), bp)], 1);
+                eq_sorted[pos] = make_float2(e[k], q[k]);
+            }
+        }
     }
 }
 
@@ -939,13 +951,30 @@ __global__ __launch_bounds__(1024) void sw_pre_chunks(const int32_t *__restrict_
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     if (!sw_root_is_wide(parent, M, tid, shd)) return;
     const int CH = 64 * ((V + 64 * SW_BINS - 1) / (64 * SW_BINS));
+    constexpr int PER = SW_BINS / (SW_PRE_WGS * 16);          // chunks per wavefront
+    if (CH == 64) {                                          // one pair per lane and chunk: the wavefront's loads all at once
+        float2 x[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = (blockIdx.x * 16 + wv + k * SW_PRE_WGS * 16) * 64 + lane;
+            x[k] = eq_sorted[i < V ? i : 0];
+            if (i >= V) x[k] = make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const double se = wave_sum_f64((double)x[k].x), sq = wave_sum_f64((double)x[k].y);
+            const int c = blockIdx.x * 16 + wv + k * SW_PRE_WGS * 16;
+            if (lane == 0) { pre->chunk_e[c] = se; pre->chunk_q[c] = sq; }
+        }
+        return;
+    }
     for (int c = blockIdx.x * 16 + wv; c < SW_BINS; c += SW_PRE_WGS * 16) {
         double se = 0.0, sq = 0.0;
         for (int i = c * CH + lane; i < min(c * CH + CH, V); i += 64) {
             const float2 x = eq_sorted[i];
             se += (double)x.x; sq += (double)x.y;
         }
-        for (int off = 32; off >= 1; off >>= 1) { se += __shfl_xor(se, off); sq += __shfl_xor(sq, off); }
+        se = wave_sum_f64(se); sq = wave_sum_f64(sq);
         if (lane == 0) { pre->chunk_e[c] = se; pre->chunk_q[c] = sq; }
     }
 }
