@@ -308,8 +308,8 @@ int btv_tree_verify_attn_paged_fp8kv(const void *Q, const void *K8pool, const vo
  * [0,1), consumed in order.  marginals [B,V] fp32 as given to tree_build.
  *   Four small launches ahead of the walk prepare the root's row (softmax numerators and their
  *   (e, q) pairs sorted by q/e) on many CUs when the root has 6 children or more; the walk
- *   itself is one workgroup; two small launches after it draw the bonus token (bonus is valid
- *   when the last of them has run, like every output: in stream order).
+ *   itself is one workgroup; one small launch after it draws the bonus token (bonus is valid
+ *   when it has run, like every output: in stream order).
  * ------------------------------------------------------------------------------------------- */
 size_t btv_tree_accept_workspace(int M, int V, int stochastic);
 int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token,

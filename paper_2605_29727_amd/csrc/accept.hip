@@ -720,7 +720,7 @@ constexpr int SW_PBINS = 2048;      // bins of a row that is prepared ahead of t
                                     // what the walk saves per rejection, the scatter kernel pays in histogram reads
 constexpr int SW_BUILD_MIN = 40;    // children still untried at a node for the sort to be worth its cost (about 30 passes)
 constexpr int SW_PRE_MIN = 6;       // children of the root from which its row is sorted ahead of the walk (a few passes' worth)
-constexpr int SW_WIN = 8192;        // sorted pairs kept in LDS around the threshold
+constexpr int SW_WIN = 11264;       // sorted pairs kept in LDS around the threshold
 
 __device__ __forceinline__ int sw_bin(float ratio)
 {
@@ -739,6 +739,15 @@ __device__ __forceinline__ int sw_bin_at(float ratio, SwBin p)
     if (d < 0) return 0;
     const uint32_t b = ((uint32_t)d << p.m) | ((u & 0x7FFFFFu) >> (23 - p.m));
     return (int)(b < (uint32_t)SW_PBINS ? b : (uint32_t)SW_PBINS - 1u);
+}
+
+// Sorted pairs per prefix-sum chunk: 2^s with s the smallest value from 6 up that leaves at most SW_BINS chunks (a
+// power of two, so that the chunk of a sorted position is a shift: the walk asks once per rejection).
+__device__ __forceinline__ int sw_chunk_shift(int V)
+{
+    int s = 6;
+    while (((V + (1 << s) - 1) >> s) > SW_BINS) ++s;
+    return s;
 }
 
 // ---- the root's row sorted ahead of the walk, by many workgroups ---------------------------------------------------
@@ -765,6 +774,7 @@ struct SwPre {                      // in the workspace, behind es and eq_sorted
     // what the walk leaves for the bonus draw, and the draw's per-wavefront totals
     double b_alpha, b_beta, b_u;
     int b_has_q, b_depth;
+    int b_count;                                          // workgroups of the bonus kernel that have left their totals
     double b_tot[SW_PRE_WGS * 16];
     int b_last[SW_PRE_WGS * 16];
 };
@@ -950,7 +960,7 @@ __global__ __launch_bounds__(1024) void sw_pre_chunks(const int32_t *__restrict_
     __shared__ double shd[16];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     if (!sw_root_is_wide(parent, M, tid, shd)) return;
-    const int CH = 64 * ((V + 64 * SW_BINS - 1) / (64 * SW_BINS));
+    const int CH = 1 << sw_chunk_shift(V);
     constexpr int PER = SW_BINS / (SW_PRE_WGS * 16);          // chunks per wavefront
     if (CH == 64) {                                          // one pair per lane and chunk: the wavefront's loads all at once
         float2 x[PER];
@@ -1010,11 +1020,12 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
     __shared__ double seg[1024];
     __shared__ double chunkE[SW_BINS], chunkQ[SW_BINS];  // sums of e and q0 over the sorted pairs before chunk c
     __shared__ int start[SW_PBINS + 1], cursor[SW_BINS];
-    __shared__ float2 win[SW_WIN];                        // sorted pairs win_lo .. win_hi - 1 (the threshold only falls,
+    __shared__ float2 win[SW_WIN + 256];                  // sorted pairs win_lo .. win_hi - 1 (the threshold only falls,
                                                           // so the window is refilled towards lower positions)
     __shared__ float2 child_eq[BTV_MAX_NODES];            // (e, q0) of node c's token, fetched for all nodes at once
     __shared__ int kid_node[BTV_MAX_NODES];               // the current node's children in node order (prepared row only)
     __shared__ float kid_u[BTV_MAX_NODES];
+    __shared__ float2 kid_eq[BTV_MAX_NODES];              // (e, q0) of child j's token
     __shared__ double kid_invT[BTV_MAX_NODES], kid_lhs[BTV_MAX_NODES];    // 1/T when child j is tried; u * q_k[x] of its test
     __shared__ struct { double alpha, beta, T; int next, accepted, reload_hi, done, nkids, wcount[4]; } fast;
     const int tid = threadIdx.x;
@@ -1023,7 +1034,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
         const size_t base = (size_t)(cur + 1) * V;
         const float *q0 = marg + (size_t)(d < B ? d : 0) * V;    // (unused when d == B: no children there)
         const bool vec4 = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(q0) & 15) == 0;
-        const int CH = 64 * ((V + 64 * SW_BINS - 1) / (64 * SW_BINS));      // sorted pairs per prefix-sum chunk
+        const int CS = sw_chunk_shift(V), CH = 1 << CS;           // sorted pairs per prefix-sum chunk
         // (the passes are unrolled so that several loads are in flight: one load per iteration leaves a pass bound
         // by the round trip to the L2)
         const bool prepared = cur == -1 && pre->ready == 1;      // the root's row was sorted ahead of this kernel
@@ -1131,6 +1142,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                     const double Tj = T - (carry + (incl - qx));
                     if (j < fast.nkids) {
                         const double invT = Tj > 0.0 ? recip(Tj) : 0.0;
+                        kid_eq[j] = c >= 0 ? child_eq[c] : make_float2(0.f, 0.f);
                         kid_invT[j] = invT;
                         kid_lhs[j] = (double)kid_u[j] * (qx * invT);
                     }
@@ -1144,30 +1156,44 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                     const int nk = fast.nkids;
                     int acc = -1, want_hi = -1;
                     alpha = fast.alpha; beta = fast.beta; T = fast.T;
+                    // child j + 1's entries are read while child j is tested: nothing in them depends on the tests
+                    const int jf = max(min(j, nk - 1), 0);
+                    int c_nx = kid_node[jf];
+                    float2 own_nx = kid_eq[jf];
+                    double invT_nx = kid_invT[jf], lhs_nx = kid_lhs[jf];
                     for (; j < nk; ++j) {
-                        const int c = kid_node[j];
+                        const int c = c_nx;
+                        const float2 own = own_nx;
+                        const double invT = invT_nx, lhs = lhs_nx;
+                        {
+                            const int j1 = min(j + 1, nk - 1);
+                            c_nx = kid_node[j1]; own_nx = kid_eq[j1]; invT_nx = kid_invT[j1]; lhs_nx = kid_lhs[j1];
+                        }
                         if (c < 0) {                             // spent uniform, raised flag, nothing indexed
                             if (lane == 0) atomicOr(flag, 64u);
                             continue;
                         }
-                        const float2 own = child_eq[c];
-                        const double invT = kid_invT[j];
                         const double px = alpha * (double)own.x - beta * (double)own.y;
-                        if (kid_lhs[j] < (px > 0.0 ? px : 0.0)) { acc = c; ++j; break; }
+                        if (lhs < (px > 0.0 ? px : 0.0)) { acc = c; ++j; break; }
                         const double b1 = beta + invT;
                         const int b = sw_bin_at((float)(b1 > 0.0 ? alpha * recip(b1) : INFINITY), bp);
                         const int p0 = start[b], p1 = start[b + 1];
-                        const int ch = min(p0 / CH, SW_BINS - 1), lo = ch * CH;
+                        const int ch = min(p0 >> CS, SW_BINS - 1), lo = ch << CS;
+                        const double ce = chunkE[ch], cq = chunkQ[ch];      // (asked for ahead of the scan's reads)
                         double zr = 0.0;
                         if (p1 - lo <= SW_WIN) {
                             if (lo < win_lo || p1 > win_hi) { want_hi = p1; break; }      // the others help to move the window
                             // four reads in flight per trip, none behind a branch (one read, its arithmetic and the loop
                             // branch per trip made a trip cost an LDS round trip: the larger part of a rejection)
+                            // (the reads run up to 255 entries past p1, into the pad behind the window: what they bring is
+                            // not used)
                             double z4[4] = { 0.0, 0.0, 0.0, 0.0 };
-                            for (int i = lo + lane; i < p1; i += 256) {
+                            const float2 *wp = win + (lo - win_lo + lane);
+                            const int trips = (p1 - lo + 255) >> 8;
+                            for (int t = 0, i = lo + lane; t < trips; ++t, i += 256, wp += 256) {
                                 float2 x[4];
 #pragma unroll
-                                for (int q = 0; q < 4; ++q) x[q] = win[(i + 64 * q < p1 ? i + 64 * q : lo) - win_lo];
+                                for (int q = 0; q < 4; ++q) x[q] = wp[64 * q];
 #pragma unroll
                                 for (int q = 0; q < 4; ++q) {
                                     const double r = alpha * (double)x[q].x - b1 * (double)x[q].y;
@@ -1183,7 +1209,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                             }
                         }
                         zr = wave_sum_f64(zr);
-                        const double below = alpha * chunkE[ch] - b1 * chunkQ[ch];
+                        const double below = alpha * ce - b1 * cq;
                         zr += below > 0.0 ? below : 0.0;
                         if (zr > 0.0) { const double iz = recip(zr); alpha *= iz; beta = b1 * iz; }
                     }
@@ -1259,7 +1285,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                         eq_sorted[pos] = make_float2(e, q);          // one 8-byte store: the scattered stores are what the sort costs
                     }
                     __syncthreads();
-                    {   // chunk c = sorted positions c*CH .. c*CH + CH - 1 (CH a multiple of 64, at most SW_BINS chunks): a
+                    {   // chunk c = sorted positions c*CH .. c*CH + CH - 1 (CH a power of two from 64 up, at most SW_BINS chunks): a
                         // wave sums a chunk with coalesced loads; then an exclusive scan over the chunk sums
                         const int lane = tid & 63, wv = tid >> 6;
                         for (int c = wv; c < SW_BINS; c += 16) {
@@ -1286,7 +1312,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                     // of the chunk that holds the bin's start one by one; the threshold's own bin is scanned exactly
                     const int b = sw_bin((float)(alpha / b1));   // b1 = 0: the threshold is +inf, every finite ratio is below it
                     const int p0 = start[b], p1 = start[b + 1];
-                    const int ch = min(p0 / CH, SW_BINS - 1), lo = ch * CH;
+                    const int ch = min(p0 >> CS, SW_BINS - 1), lo = ch << CS;
                     if (p1 - lo <= SW_WIN) {
                         if (lo < win_lo || p1 > win_hi) {        // (uniform) refill: the window ends at this bin's end
                             __syncthreads();
@@ -1324,21 +1350,25 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
             __syncthreads();                                     // everyone is done with es before it is rewritten
             continue;
         }
-        // The bonus token is drawn by the two kernels that follow (a pass over the vocabulary in fp64 is bound by the
+        // The bonus token is drawn by the kernel that follows (a pass over the vocabulary in fp64 is bound by the
         // arithmetic of the one CU this kernel runs on: 16 us of its time): the residual's parameters, the uniform
         // and the row go to the workspace.
         if (tid == 0) {
             pre->b_alpha = alpha; pre->b_beta = beta; pre->b_u = (double)uniforms[ui];
             pre->b_has_q = has_q ? 1 : 0; pre->b_depth = has_q ? d : 0;
+            pre->b_count = 0;
             *n_acc = n;
         }
         break;
     }
 }
 
-// Bonus draw, first kernel: smallest v with cumsum(p_k)[v] > u, p_k = max(alpha e - beta q0, 0).  Wavefront g of
-// SW_PRE_WGS * 16 owns a contiguous stretch of the vocabulary (whole wave instructions of 256 tokens, four per lane, when
-// the rows allow 16-byte loads) and leaves its total and its last positive token.
+// Bonus draw: smallest v with cumsum(p_k)[v] > u, p_k = max(alpha e - beta q0, 0).  Wavefront g of SW_PRE_WGS * 16 owns
+// a contiguous stretch of the vocabulary (whole wave instructions of 256 tokens, four per lane, when the rows allow
+// 16-byte loads) and leaves its total and its last positive token; the workgroup that counts itself in last picks
+// the token (sw_bonus_pick) on its first wavefront.  Totals, last tokens and the counter cross workgroups as relaxed
+// device-scope atomics, the counter only after the stores are acknowledged (the L2s of the XCDs are not coherent
+// with each other).
 __device__ __forceinline__ double sw_resid(double alpha, double beta, bool has_q, float ev, float qv)
 {
     const double x = has_q ? alpha * (double)ev - beta * (double)qv : alpha * (double)ev;
@@ -1353,8 +1383,13 @@ __device__ __forceinline__ void sw_stretch(int V, bool wide, int g, int &w0, int
     w1 = min(w0 + stretch, V);
 }
 
-__global__ __launch_bounds__(1024) void sw_bonus_totals(const float *__restrict__ marg, int V, const float *__restrict__ es, SwPre *pre)
+__device__ void sw_bonus_pick(const float *__restrict__ marg, int V, const float *__restrict__ es, SwPre *pre, int32_t *bonus,
+                              int lane);
+
+__global__ __launch_bounds__(1024) void sw_bonus_draw(const float *__restrict__ marg, int V, const float *__restrict__ es, SwPre *pre,
+                                                      int32_t *bonus)
 {
+    __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, g = blockIdx.x * 16 + (tid >> 6);
     const double alpha = pre->b_alpha, beta = pre->b_beta;
     const bool has_q = pre->b_has_q != 0;
@@ -1394,17 +1429,24 @@ __global__ __launch_bounds__(1024) void sw_bonus_totals(const float *__restrict_
     }
     loc = wave_sum_f64(loc);
     for (int off = 32; off >= 1; off >>= 1) lp = max(lp, __shfl_xor(lp, off));
-    if (lane == 0) { pre->b_tot[g] = loc; pre->b_last[g] = lp; }
+    if (lane == 0) {
+        __hip_atomic_store(reinterpret_cast<unsigned long long *>(pre->b_tot) + g, (unsigned long long)__double_as_longlong(loc),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pre->b_last + g, lp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) is_last = __hip_atomic_fetch_add(&pre->b_count, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == SW_PRE_WGS - 1;
+    __syncthreads();
+    if (is_last && tid < 64) sw_bonus_pick(marg, V, es, pre, bonus, tid);
 }
 
-// Second kernel, one wavefront: the totals in order tell which stretch holds the crossing; that stretch is looked at
-// again, a wave instruction's worth of tokens at a time: its total, then the lanes' prefix inside it, then the token
-// inside the lane.
-__global__ __launch_bounds__(64) void sw_bonus_pick(const float *__restrict__ marg, int V, const float *__restrict__ es,
-                                                    const SwPre *__restrict__ pre, int32_t *bonus)
+// One wavefront: the totals in order tell which stretch holds the crossing; that stretch is looked at again, a wave
+// instruction's worth of tokens at a time: its total, then the lanes' prefix inside it, then the token inside the lane.
+__device__ void sw_bonus_pick(const float *__restrict__ marg, int V, const float *__restrict__ es, SwPre *pre, int32_t *bonus,
+                              int lane)
 {
     constexpr int WAVES = SW_PRE_WGS * 16, PER = WAVES / 64;
-    const int lane = threadIdx.x;
     const double alpha = pre->b_alpha, beta = pre->b_beta, u = pre->b_u;
     const bool has_q = pre->b_has_q != 0;
     const float *q0 = marg + (size_t)pre->b_depth * V;
@@ -1413,7 +1455,11 @@ __global__ __launch_bounds__(64) void sw_bonus_pick(const float *__restrict__ ma
     double t[PER];
     int lastpos = 0;
 #pragma unroll
-    for (int k = 0; k < PER; ++k) { t[k] = pre->b_tot[PER * lane + k]; lastpos = max(lastpos, pre->b_last[PER * lane + k]); }
+    for (int k = 0; k < PER; ++k) {
+        t[k] = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<unsigned long long *>(pre->b_tot) + PER * lane + k,
+                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        lastpos = max(lastpos, __hip_atomic_load(pre->b_last + PER * lane + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
     for (int off = 32; off >= 1; off >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, off));
     double own = 0.0;
 #pragma unroll
@@ -1482,7 +1528,8 @@ __global__ __launch_bounds__(64) void sw_bonus_pick(const float *__restrict__ ma
                 running += __shfl(x, 63);
             }
         }
-        found = hit != INT_MAX ? hit : max(pre->b_last[g], 0);   // rounding left the crossing just past the stretch
+        // rounding left the crossing just past the stretch
+        found = hit != INT_MAX ? hit : max(__hip_atomic_load(pre->b_last + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0);
     }
     if (lane == 0) *bonus = found == INT_MAX ? lastpos : found;
 }
@@ -1630,9 +1677,8 @@ int btv_tree_accept_stochastic(const void *logits, int dtype, const float *margi
     else
         hipLaunchKernelGGL(stochastic_walk<false>, dim3(1), dim3(1024), 0, st, logits, marginals, B, parent, token, M, V,
                            uniforms, es, eq_sorted, pre, path, n_acc, flag);
-    // the bonus token: per-wavefront totals of the residual on 32 workgroups, then one wavefront finds the crossing
-    hipLaunchKernelGGL(sw_bonus_totals, dim3(SW_PRE_WGS), dim3(1024), 0, st, marginals, V, es, pre);
-    hipLaunchKernelGGL(sw_bonus_pick, dim3(1), dim3(64), 0, st, marginals, V, es, pre, bonus);
+    // the bonus token: per-wavefront totals of the residual on 32 workgroups, the last of which finds the crossing
+    hipLaunchKernelGGL(sw_bonus_draw, dim3(SW_PRE_WGS), dim3(1024), 0, st, marginals, V, es, pre, bonus);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }
