@@ -297,8 +297,10 @@ int btv_tree_verify_attn_paged_fp8kv(const void *Q, const void *K8pool, const vo
  *   path [M] accepted node ids in root-to-leaf order (first *n_acc valid), n_acc [1],
  *   bonus [1] = t[row of the last accepted node] (the token that seeds the next cycle),
  *   argmax_out [M+1] optional.
- *   One launch: the workgroup that finishes the argmax last does the walk; the workspace holds
- *   one 8-byte word per logit row and a counter, all back at zero when the call has run.
+ *   One launch: every workgroup leaves the best of its part of the rows in 8-byte words of its
+ *   own in the workspace, and the workgroup with the highest index collects them (it waits for
+ *   words still empty, for one second of wall clock at most: past that it raises the data flag)
+ *   and does the walk; the words are back at zero when the call has run.
  *
  * stochastic (temperature 1): token-level rejection sampling of the target distribution
  * p = softmax(logits row) against the draft marginal q of the child's depth, children tried in

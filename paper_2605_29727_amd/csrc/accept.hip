@@ -16,7 +16,6 @@ constexpr int ACHUNK = 8192;     // vocabulary elements per argmax workgroup
 
 struct alignas(8) Best { float v; int i; };
 
-constexpr int ACCEPT_COUNTER_OFFSET = 64;   // workspace header: word 0 = data flag, word 16 = workgroups counted in
 
 __device__ __forceinline__ void best_take(Best &b, float v, int i)
 {   // larger value wins; equal values: lower index wins; NaN never wins
@@ -126,22 +125,35 @@ __global__ __launch_bounds__(256) void argmax_chunks(const void *logits, int V, 
 
 // ------------------------------------------------------------------------------------------------
 // Greedy acceptance of one request in one launch.  A wavefront scans one unit of WCHUNK vocabulary elements of one
-// row; the 16 waves of a workgroup fold the units that belong to the same row and publish one 64-bit key per row
-// with an atomic maximum in memory; every workgroup then counts itself in, and the one that counts in last reads
-// the row keys and walks the tree on its first wavefront.  Keys and counter are left at zero for the next call.
+// row; the 16 waves of a workgroup fold the units that belong to the same row and leave one 64-bit key per row they
+// touched in the workgroup's own slots of the workspace.  The workgroup with the highest index (the last one to be
+// placed on the chip) then collects: it takes every slot with an atomic exchange against zero, again while a slot
+// is still empty, merges the keys per row and walks the tree on its first wavefront.  Nobody else waits for
+// anything, so every wait of the collector ends as soon as the other workgroups have run; a wall-clock limit
+// (s_memrealtime) bounds it all the same, and running into it raises the workspace's flag.  The exchange leaves the
+// slots at zero for the next call.
 // The L2 caches of the 8 XCDs are not coherent with each other, and a device-scope fence writes back and
-// invalidates a whole cache; the only words other workgroups must see are the row keys and the counter, all moved
-// by relaxed device-scope atomics (executed at the memory side), the counter only after the key updates have been
-// acknowledged (vmcnt 0).  Atomics on one address cost about 11 ns each one after the other (measured), hence big
-// workgroups: 130 instead of 2080 of them at 65 rows.
-// Key = value bits made monotonic << 32 | ~index: the larger value wins, then the lower index; a unit that saw only
-// NaN publishes nothing and a row that stays at zero has argmax 0, as in the two-launch path.
+// invalidates a whole cache; the only words other workgroups must see are the slots, moved by relaxed device-scope
+// atomics (executed at the memory side).  Counting the workgroups in instead (each waits for its key updates to be
+// acknowledged, adds itself to a counter, the last one reads the keys) puts three dependent round trips to the
+// memory side, about 2 us each, behind the scan; here it is the flight of a store and one exchange.
+// Key = value bits made monotonic << 32 | ~index: the larger value wins, then the lower index; a key's upper half is
+// never zero, so 1 stands for "only NaN seen": a row without a key has argmax 0, as in the two-launch path.
 // The walk keeps node c in lane c % 64, register row c / 64: `ok` = the node's token is the target's argmax at its
 // parent; a step is a ballot over "child of the current node and ok" per row, lowest node index first.
 // ------------------------------------------------------------------------------------------------
 constexpr int WALK_ROWS = (BTV_MAX_NODES + 63) / 64;
 constexpr int WCHUNK = 4096;     // vocabulary elements per wavefront unit of the one-launch kernel
 constexpr int OL_WAVES = 16;     // wavefronts per workgroup of the one-launch kernel
+constexpr unsigned long long OL_NO_KEY = 1ull;
+constexpr long long OL_WAIT_TICKS = 100000000ll;    // collector's limit: one second of the 100 MHz wall clock
+
+// Rows that OL_WAVES consecutive units can touch: the slots a workgroup owns.
+__host__ __device__ inline int ol_slots_per_wg(int chunks)
+{
+    const int r = (OL_WAVES - 1) / chunks + 2;
+    return r < OL_WAVES ? r : OL_WAVES;
+}
 
 __device__ __forceinline__ unsigned long long best_key(Best b)
 {
@@ -151,61 +163,147 @@ __device__ __forceinline__ unsigned long long best_key(Best b)
     return ((unsigned long long)mono << 32) | (uint32_t)~(uint32_t)b.i;
 }
 
-// Best element of elements v0 .. v1-1 of a row as seen by this lane.  A whole, 16-byte aligned unit is fetched with
-// eight 16-byte loads per lane at a time, all in flight before the first is looked at.
+// Best element of elements v0 .. v1-1 of a row as seen by this lane.  Where the row is 16-byte aligned the unit is
+// fetched with eight 16-byte loads per lane at a time, all in flight before the first is looked at; a ragged unit (the
+// last of a row) takes the same loads with the pieces past its end redirected to its first piece and left out, and
+// the elements behind the last whole piece one per lane.  Nothing here loads inside a loop whose next trip needs
+// the value: twenty such trips for the last 1280 elements of a row were two thirds of the kernel's time.
+template <bool BF16, bool WHOLE>
+__device__ __forceinline__ void wave_scan_pieces(Best &b, const uint4 *x, int v0, int npiece, int lane)
+{
+    constexpr int PER = BF16 ? 8 : 4;                            // elements per 16-byte piece
+    for (int h = 0; h * 512 < npiece; ++h) {
+        uint4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int p = (h * 8 + j) * 64 + lane;
+            q[j] = x[WHOLE || p < npiece ? p : 0];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int p = (h * 8 + j) * 64 + lane;
+            if (!WHOLE && p >= npiece) continue;
+            const int v = v0 + p * PER;
+            const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (BF16) {
+                    best_take(b, __uint_as_float(wds[e] << 16), v + 2 * e);
+                    best_take(b, __uint_as_float(wds[e] & 0xFFFF0000u), v + 2 * e + 1);
+                } else {
+                    best_take(b, __uint_as_float(wds[e]), v + e);
+                }
+            }
+        }
+    }
+}
+
+// A whole unit, the cheap way: the lane meets its elements in rising index order, so "larger than the best so far"
+// alone keeps the first of equal values, and the place is kept as the number of the element within the trip (a
+// constant in the instruction).  Three instructions per element against eight for best_take: with four wavefronts per
+// SIMD the scan was bound by this arithmetic, not by memory.  Elements equal to the start value, -inf, are not
+// taken here: a lane that ends without a place sends the wavefront through wave_scan_pieces after all.
+template <bool BF16>
+__device__ __forceinline__ void wave_scan_whole(Best &b, const uint4 *x, int v0, int lane)
+{
+    constexpr int PER = BF16 ? 8 : 4;
+    for (int h = 0; h < WCHUNK / (512 * PER); ++h) {
+        uint4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = x[(h * 8 + j) * 64 + lane];
+        float bv = b.v;
+        int bk = -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (BF16) {
+                    const float lo = __uint_as_float(wds[e] << 16), hi = __uint_as_float(wds[e] & 0xFFFF0000u);
+                    if (lo > bv) { bv = lo; bk = j * PER + 2 * e; }
+                    if (hi > bv) { bv = hi; bk = j * PER + 2 * e + 1; }
+                } else {
+                    const float f = __uint_as_float(wds[e]);
+                    if (f > bv) { bv = f; bk = j * PER + e; }
+                }
+            }
+        }
+        if (bk >= 0) {
+            b.v = bv;
+            b.i = v0 + ((h * 8 + bk / PER) * 64 + lane) * PER + bk % PER;
+        }
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float wave_scan_one(const void *logits, size_t idx)
+{
+    if (BF16) return __uint_as_float((uint32_t)static_cast<const uint16_t *>(logits)[idx] << 16);
+    return static_cast<const float *>(logits)[idx];
+}
+
 template <bool BF16>
 __device__ __forceinline__ Best wave_scan(const void *logits, int V, int row, int v0, int v1, int lane)
 {
     Best b = { -INFINITY, INT_MAX };
     constexpr int ES = BF16 ? 2 : 4, PER = 16 / ES;              // element size, elements per 16-byte load
     const bool aligned = (((size_t)row * V * ES) & 15) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
-    if (aligned && v1 - v0 == WCHUNK) {
-        const uint4 *x = reinterpret_cast<const uint4 *>(static_cast<const unsigned char *>(logits) +
-                                                         ((size_t)row * V + v0) * ES);
-#pragma unroll
-        for (int h = 0; h < WCHUNK / (64 * PER * 8); ++h) {
-            uint4 q[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) q[j] = x[(h * 8 + j) * 64 + lane];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int v = v0 + ((h * 8 + j) * 64 + lane) * PER;
-                const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (BF16) {
-                        best_take(b, __uint_as_float(wds[e] << 16), v + 2 * e);
-                        best_take(b, __uint_as_float(wds[e] & 0xFFFF0000u), v + 2 * e + 1);
-                    } else {
-                        best_take(b, __uint_as_float(wds[e]), v + e);
-                    }
-                }
-            }
+    const size_t base = (size_t)row * V;
+    if (aligned) {                                               // (v0 is a multiple of WCHUNK)
+        const uint4 *x = reinterpret_cast<const uint4 *>(static_cast<const unsigned char *>(logits) + (base + v0) * ES);
+        const int npiece = (v1 - v0) / PER;
+        if (v1 - v0 == WCHUNK) {
+            wave_scan_whole<BF16>(b, x, v0, lane);
+            if (__builtin_amdgcn_ballot_w64(b.i == INT_MAX) == 0ull) return b;
+            b = Best{ -INFINITY, INT_MAX };                      // (a lane saw nothing above -inf)
+            wave_scan_pieces<BF16, true>(b, x, v0, npiece, lane);
+            return b;
         }
+        wave_scan_pieces<BF16, false>(b, x, v0, npiece, lane);
+        const int v = v0 + npiece * PER + lane;                  // fewer than PER elements are left
+        const float last = wave_scan_one<BF16>(logits, base + (v < v1 ? v : v0));
+        if (v < v1) best_take(b, last, v);
         return b;
     }
-    if (BF16) {
-        const uint16_t *x = static_cast<const uint16_t *>(logits) + (size_t)row * V;
-        for (int v = v0 + lane; v < v1; v += 64) best_take(b, __uint_as_float((uint32_t)x[v] << 16), v);
-    } else {
-        const float *x = static_cast<const float *>(logits) + (size_t)row * V;
-        for (int v = v0 + lane; v < v1; v += 64) best_take(b, x[v], v);
+    for (int vb = v0; vb < v1; vb += 64 * 8) {                   // eight loads in flight
+        float xv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int v = vb + j * 64 + lane;
+            xv[j] = wave_scan_one<BF16>(logits, base + (v < v1 ? v : v0));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int v = vb + j * 64 + lane;
+            if (v < v1) best_take(b, xv[j], v);
+        }
     }
     return b;
 }
 
 template <bool BF16>
 __global__ __launch_bounds__(OL_WAVES * 64) void accept_greedy_one_launch(
-    const void *logits, int V, int chunks, unsigned long long *row_key, uint32_t *arrived, const int32_t *parent,
+    const void *logits, int V, int chunks, unsigned long long *slot, uint32_t *flag, const int32_t *parent,
     const int32_t *token, int M, int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out)
 {
     __shared__ Best wbest[OL_WAVES];
     __shared__ int wrow[OL_WAVES];
     __shared__ int t[BTV_MAX_NODES + 1];
-    __shared__ uint32_t is_last;
+    __shared__ unsigned long long rowmax[BTV_MAX_NODES + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, units = (M + 1) * chunks;
-    for (int u0 = blockIdx.x * OL_WAVES; u0 < units; u0 += gridDim.x * OL_WAVES) {   // (uniform over the workgroup)
-        const int u = u0 + wave;
+    const int RS = ol_slots_per_wg(chunks);
+    const bool collector = blockIdx.x == gridDim.x - 1;
+    // the collector's walk needs the tree: asked for now, used after the scan
+    int par[WALK_ROWS], tok[WALK_ROWS];
+#pragma unroll
+    for (int r = 0; r < WALK_ROWS; ++r) {
+        const int c = r * 64 + lane;
+        const bool mine = collector && wave == 0 && c < M;
+        par[r] = mine ? parent[c] : INT_MIN;
+        tok[r] = mine ? token[c] : -1;
+    }
+    {
+        const int u = blockIdx.x * OL_WAVES + wave;              // (the grid covers the units exactly once)
         Best b = { -INFINITY, INT_MAX };
         int row = -1;
         if (u < units) {
@@ -214,39 +312,51 @@ __global__ __launch_bounds__(OL_WAVES * 64) void accept_greedy_one_launch(
             b = best_wave(wave_scan<BF16>(logits, V, row, chunk * WCHUNK, min(chunk * WCHUNK + WCHUNK, V), lane));
         }
         if (lane == 0) { wbest[wave] = b; wrow[wave] = row; }
+        if (collector)
+            for (int i = tid; i <= M; i += OL_WAVES * 64) rowmax[i] = 0ull;
         __syncthreads();
         if (tid < OL_WAVES && wrow[tid] >= 0 && (tid == 0 || wrow[tid - 1] != wrow[tid])) {
-            // first unit of a row within this workgroup: fold the row's other units, publish
+            // first unit of a row within this workgroup: fold the row's other units, leave the key
             Best r = wbest[tid];
             for (int j = tid + 1; j < OL_WAVES && wrow[j] == wrow[tid]; ++j) best_take(r, wbest[j].v, wbest[j].i);
             const unsigned long long key = best_key(r);
-            if (key != 0ull) __hip_atomic_fetch_max(row_key + wrow[tid], key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(slot + (size_t)blockIdx.x * RS + (wrow[tid] - wrow[0]), key != 0ull ? key : OL_NO_KEY,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __syncthreads();
     }
-    if (wave == 0) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // this workgroup's key updates have been performed
-        if (lane == 0)
-            is_last = __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1u;
+    if (!collector) return;
+    // workgroup w owns units 16 w .. 16 w + 15 (as far as they exist); its slot j belongs to row (16 w) / chunks + j
+    {
+        const long long t0 = (long long)__builtin_amdgcn_s_memrealtime();
+        bool late = false;
+        for (int s = tid; s < (int)gridDim.x * RS; s += OL_WAVES * 64) {
+            const int w = s / RS, j = s - w * RS;
+            const int r0 = (w * OL_WAVES) / chunks, r1 = min(w * OL_WAVES + OL_WAVES - 1, units - 1) / chunks;
+            if (j > r1 - r0) continue;
+            unsigned long long key = 0ull;
+            for (;;) {
+                key = __hip_atomic_exchange(slot + s, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (key != 0ull) break;
+                if ((long long)__builtin_amdgcn_s_memrealtime() - t0 > OL_WAIT_TICKS) { late = true; break; }
+                __builtin_amdgcn_s_sleep(8);
+            }
+            if (key > 0xFFFFFFFFull) atomicMax(&rowmax[r0 + j], key);
+        }
+        if (late) atomicOr(flag, 128u);
     }
     __syncthreads();
-    if (!is_last) return;
-    if (tid == 0) __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid <= M) {
-        const unsigned long long key = __hip_atomic_exchange(row_key + tid, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long key = rowmax[tid];
         t[tid] = key == 0ull ? 0 : (int)~(uint32_t)key;
         if (argmax_out) argmax_out[tid] = t[tid];
     }
     __syncthreads();
     if (tid >= 64) return;
-    int par[WALK_ROWS];
     bool ok[WALK_ROWS];
 #pragma unroll
     for (int r = 0; r < WALK_ROWS; ++r) {
         const int c = r * 64 + tid;
-        par[r] = c < M ? parent[c] : INT_MIN;
-        const int tk = c < M ? token[c] : -1;
-        ok[r] = c < M && par[r] >= -1 && par[r] < M && tk == t[par[r] + 1];
+        ok[r] = c < M && par[r] >= -1 && par[r] < M && tok[r] == t[par[r] + 1];
     }
     int cur = -1, n = 0;
     while (n < M) {
@@ -1534,6 +1644,13 @@ __device__ void sw_bonus_pick(const float *__restrict__ marg, int V, const float
     if (lane == 0) *bonus = found == INT_MAX ? lastpos : found;
 }
 
+// workgroups of the one-launch greedy kernel: OL_WAVES units each, every unit once
+int greedy_wgs(int M, int V)
+{
+    const long long chunks = (V + WCHUNK - 1) / WCHUNK;
+    return (int)(((long long)(M + 1) * chunks + OL_WAVES - 1) / OL_WAVES);
+}
+
 int check_accept(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
                  int32_t *path, int32_t *n_acc, int32_t *bonus)
 {
@@ -1552,7 +1669,8 @@ size_t btv_tree_accept_workspace(int M, int V, int stochastic)
 {
     if (M < 1 || M > BTV_MAX_NODES || V < 1) return 0;
     if (stochastic) return BTV_WS_HEADER + 3 * btv_align_up((size_t)V * 4, BTV_WS_ALIGN) + btv_align_up(sizeof(SwPre), BTV_WS_ALIGN);
-    return BTV_WS_HEADER + btv_align_up((size_t)(M + 1) * sizeof(unsigned long long), BTV_WS_ALIGN);
+    const int chunks = (V + WCHUNK - 1) / WCHUNK;
+    return BTV_WS_HEADER + btv_align_up((size_t)greedy_wgs(M, V) * ol_slots_per_wg(chunks) * sizeof(unsigned long long), BTV_WS_ALIGN);
 }
 
 int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
@@ -1564,16 +1682,15 @@ int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent,
     rc = btv_check_ws(ws, ws_bytes, btv_tree_accept_workspace(M, V, 0));
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned long long *row_key = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
-    uint32_t *arrived = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) + ACCEPT_COUNTER_OFFSET);
-    const int chunks = (V + WCHUNK - 1) / WCHUNK;
-    const int wgs = (int)std::min<long long>(((long long)(M + 1) * chunks + OL_WAVES - 1) / OL_WAVES, 512);
+    unsigned long long *slot = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(ws) + BTV_WS_HEADER);
+    uint32_t *flag = static_cast<uint32_t *>(ws);
+    const int chunks = (V + WCHUNK - 1) / WCHUNK, wgs = greedy_wgs(M, V);
     if (dtype == BTV_BF16)
-        hipLaunchKernelGGL(accept_greedy_one_launch<true>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, row_key,
-                           arrived, parent, token, M, path, n_acc, bonus, argmax_out);
+        hipLaunchKernelGGL(accept_greedy_one_launch<true>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, slot,
+                           flag, parent, token, M, path, n_acc, bonus, argmax_out);
     else
-        hipLaunchKernelGGL(accept_greedy_one_launch<false>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, row_key,
-                           arrived, parent, token, M, path, n_acc, bonus, argmax_out);
+        hipLaunchKernelGGL(accept_greedy_one_launch<false>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, slot,
+                           flag, parent, token, M, path, n_acc, bonus, argmax_out);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
 }

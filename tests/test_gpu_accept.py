@@ -83,9 +83,28 @@ def test_greedy_all_equal_and_neg_inf_rows(G, oracle):
     _greedy_case(G, oracle, x, x, False, parent, token)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_greedy_neg_inf_in_whole_units(G, oracle, dtype):
+    """Rows that are -inf nearly everywhere, over a vocabulary of two whole scan units and a ragged one: a lane
+    whose elements are all -inf has nothing "larger than the start value", which is the case the scan's cheap pass
+    hands back to the exact one."""
+    M, V = 4, 2 * 4096 + 777
+    parent = synth.tree_parents(0, M, "chain")
+    x = np.full((M + 1, V), -np.inf, dtype=np.float32)
+    x[1, 5000] = -3.0                       # one finite value in the second unit
+    x[2, V - 1] = 0.5                       # only the last element of the ragged unit
+    x[3, :] = np.linspace(-4.0, 4.0, V, dtype=np.float32)[::-1]
+    x[3, 4096] = 9.0
+    x[4, 4095], x[4, 4096] = 2.0, 2.0       # a tie across two units
+    token = np.array([0, 5000, V - 1, 4096], dtype=np.int32)
+    store, xf = synth.round_to_dtype(x.astype(np.float64), dtype)
+    r = _greedy_case(G, oracle, store, xf, dtype == "bf16", parent, token)
+    assert r["n_acc"] == 4 and r["bonus"] == 4095
+
+
 def test_greedy_signed_zeros_tie_and_workspace_reuse(G, oracle):
     """-0.0 and +0.0 are the same value: the lower index wins whichever sign it carries.  One workspace then serves
-    calls of different sizes in a row: the per-row words and the workgroup counter are back at zero after each."""
+    calls of different sizes in a row: the slots that the workgroups leave their keys in are back at zero after each."""
     import torch
     from paper_2605_29727_amd import binding as btv
     M, V = 3, 9000
