@@ -47,6 +47,27 @@ __device__ __forceinline__ Best chunk_scan(const void *logits, int V, int row, i
                 uint4 q[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) q[j] = *reinterpret_cast<const uint4 *>(x + v0 + tid * 8 + j * 2048);
+                // the thread meets its elements in rising index order: "larger than the best so far" keeps the first of
+                // equal values, the place is the element's number (a constant of the instruction); elements equal to
+                // the start value, -inf, are not taken, and a wavefront in which a thread ends without a place takes
+                // the exact pass below
+                float bv = -INFINITY;
+                int bk = -1;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(wds[e] << 16), hi = __uint_as_float(wds[e] & 0xFFFF0000u);
+                        if (lo > bv) { bv = lo; bk = j * 8 + 2 * e; }
+                        if (hi > bv) { bv = hi; bk = j * 8 + 2 * e + 1; }
+                    }
+                }
+                if (__builtin_amdgcn_ballot_w64(bk < 0) == 0ull) {
+                    b.v = bv;
+                    b.i = v0 + tid * 8 + (bk >> 3) * 2048 + (bk & 7);
+                    return b;
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t wds[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
@@ -84,6 +105,20 @@ __device__ __forceinline__ Best chunk_scan(const void *logits, int V, int row, i
                     float4 q[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) q[j] = *reinterpret_cast<const float4 *>(x + v0 + tid * 4 + (h * 4 + j) * 1024);
+                    float bv = b.v;                              // (as for bf16: rising order, exact pass on demand)
+                    int bk = -1;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float f[4] = { q[j].x, q[j].y, q[j].z, q[j].w };
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (f[e] > bv) { bv = f[e]; bk = j * 4 + e; }
+                    }
+                    const bool none = bk < 0 && b.i == INT_MAX;
+                    if (__builtin_amdgcn_ballot_w64(none) == 0ull) {
+                        if (bk >= 0) { b.v = bv; b.i = v0 + tid * 4 + (h * 4 + (bk >> 2)) * 1024 + (bk & 3); }
+                        continue;
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int v = v0 + tid * 4 + (h * 4 + j) * 1024;

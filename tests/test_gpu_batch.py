@@ -96,6 +96,43 @@ def test_accept_batch_matches_oracle(oracle, dtype):
         assert np.array_equal(am[o + r:o + r + M + 1], ref["argmax"])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_accept_batch_neg_inf_in_whole_chunks(oracle, dtype):
+    """Rows that are -inf nearly everywhere over two whole argmax chunks and a ragged one: a thread that saw
+    nothing above -inf is the case that the chunk scan's cheap pass hands back to the exact one."""
+    import torch
+    import gpu_util as G
+    from paper_2605_29727_amd import binding as btv
+    M, V = 4, 2 * 8192 + 301
+    parent = synth.tree_parents(0, M, "chain")
+    x = np.full((M + 1, V), -np.inf, dtype=np.float32)
+    x[1, 9000] = -3.0
+    x[2, V - 1] = 0.5
+    x[3, :] = np.linspace(-4.0, 4.0, V, dtype=np.float32)[::-1]
+    x[3, 8192] = 9.0
+    x[4, 8191], x[4, 8192] = 2.0, 2.0
+    token = np.array([0, 9000, V - 1, 8192], dtype=np.int32)
+    store, xf = synth.round_to_dtype(x.astype(np.float64), dtype)
+    ref = oracle.accept_greedy(xf, parent, token)
+    assert ref["n_acc"] == 4 and ref["bonus"] == 8191
+    stores = np.concatenate([store, store])                  # two requests with the same tree and logits
+    logits = G.dev(stores, dtype == "bf16")
+    par = G.dev(np.concatenate([parent, parent]).astype(np.int32)); tok = G.dev(np.concatenate([token, token]))
+    qo = G.dev(np.array([0, M, 2 * M], dtype=np.int32))
+    path = torch.full((2 * M,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    am = torch.full((2 * M + 2,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_batch_workspace(2, 2 * M, V))
+    btv.btv_tree_accept_greedy_batch(logits, par, tok, qo, M, path, n_acc, bonus, am, ws)
+    torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == 0
+    for r in range(2):
+        assert n_acc[r].item() == 4 and bonus[r].item() == 8191
+        assert path[r * M:r * M + 4].tolist() == ref["path"].tolist()
+        assert np.array_equal(am[r * (M + 1):(r + 1) * (M + 1)].cpu().numpy(), ref["argmax"])
+
+
 def test_stream_read_runs_and_checks_arguments():
     """The bandwidth-ceiling aid: any 16-byte multiple is read without touching anything else; bad arguments raise."""
     import torch
