@@ -385,6 +385,17 @@ def ragged_batch(torch, btv, synth):
 C5_SHAPE = dict(L=32768, N=128, Hq=64, Hkv=8, D=128, sigma=3.0, seed=6)       # 70B-shaped layer, 32k prefix
 
 
+def stochastic_accept_call(torch, btv, pc, N, V, seed):
+    """btv_tree_accept_stochastic on the tree of `pc`: fp32 target logits (normal, sigma 3) and one uniform per row,
+    both drawn on the device from a seeded generator."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(int(seed))
+    lg = torch.randn((N + 1, V), dtype=torch.float32, device="cuda", generator=g).mul_(3.0)
+    un = torch.rand(N + 1, dtype=torch.float32, device="cuda", generator=g)
+    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(N, V, True))
+    return lambda: btv.btv_tree_accept_stochastic(lg, pc.marg, pc.parent, pc.token, un, pc.path, pc.n_acc, pc.bonus, ws)
+
+
 def other_configs(torch, btv, synth, V, steps, warmup):
     """The remaining configurations of the parity suite, timed (reported, not the headline): the 8B shape at a
     2k prefix, the ragged paged batch of 8 requests, and the 70B shape at a 32k prefix with stochastic acceptance."""
@@ -414,12 +425,7 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     c5 = C5_SHAPE
     pc = one("llama_70b_L32768_N128", c5["L"], c5["N"], c5["Hq"], c5["Hkv"], c5["D"], c5["sigma"], c5["seed"])
     # stochastic acceptance at this shape: fp32 logits, one uniform per row
-    N = 128
-    lg = torch.randn((N + 1, V), dtype=torch.float32, device="cuda").mul_(3.0)
-    un = torch.rand(N + 1, dtype=torch.float32, device="cuda")
-    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(N, V, True))
-    ms = time_loop(torch, lambda: btv.btv_tree_accept_stochastic(lg, pc.marg, pc.parent, pc.token, un, pc.path, pc.n_acc,
-                                                                 pc.bonus, ws), steps, warmup)
+    ms = time_loop(torch, stochastic_accept_call(torch, btv, pc, c5["N"], V, c5["seed"]), steps, warmup)
     out["llama_70b_L32768_N128"]["tree_accept_stochastic_us"] = round(ms * 1e3, 3)
     del pc, lg
     torch.cuda.empty_cache()
@@ -479,6 +485,8 @@ def main():
     ap.add_argument("--only-config", choices=("c4", "c5"), default=None,
                     help="time only the attention of the ragged paged batch (c4) or of the 70B shape at a 32k prefix (c5), "
                          "for profiler runs")
+    ap.add_argument("--only-stochastic", action="store_true",
+                    help="time only btv_tree_accept_stochastic on the 70B configuration's tree (for profiler runs)")
     ap.add_argument("--only-lm-head", action="store_true",
                     help="time only btv_tree_accept_greedy_lm_head (for profiler runs)")
     ap.add_argument("--only-fp8-kv", action="store_true", help="time only btv_tree_verify_attn_fp8kv (for profiler runs)")
@@ -521,6 +529,13 @@ def main():
                   max(2, -(-RING_BYTES // set_bytes)))
         ms = time_loop(torch, pc.attn, args.steps, args.warmup)
         print(json.dumps({"only_attn_us": ms * 1e3, "config": "70B-shaped layer, L=32768, N=128"}))
+        return
+    if args.only_stochastic:
+        c5 = C5_SHAPE
+        pc = Path(torch, btv, synth, 64, c5["N"], c5["Hq"], c5["Hkv"], c5["D"], 16, 128256, c5["sigma"], c5["seed"], 1)
+        ms = time_loop(torch, stochastic_accept_call(torch, btv, pc, c5["N"], 128256, c5["seed"]), args.steps, args.warmup)
+        print(json.dumps({"only_stochastic_us": ms * 1e3, "config": "tree of the 70B configuration (N=128, flat marginals)",
+                          "children_of_root": int((pc.parent == -1).sum().item()), "n_acc": int(pc.n_acc.item())}))
         return
     Hq, Hkv, D, B, V, L, N = 32, 8, 128, 16, 128256, args.L, args.N
     w = synth.c3(N, sharp=True)
