@@ -427,7 +427,7 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     # stochastic acceptance at this shape: fp32 logits, one uniform per row
     ms = time_loop(torch, stochastic_accept_call(torch, btv, pc, c5["N"], V, c5["seed"]), steps, warmup)
     out["llama_70b_L32768_N128"]["tree_accept_stochastic_us"] = round(ms * 1e3, 3)
-    del pc, lg
+    del pc
     torch.cuda.empty_cache()
 
     # ragged batch of 8 requests over a paged KV cache (16-token blocks, random block table)
@@ -446,7 +446,9 @@ def other_configs(torch, btv, synth, V, steps, warmup):
     n_out, n_acc, bonus = (torch.zeros(nb, dtype=torch.int32, device="cuda") for _ in range(3))
     ahat = torch.zeros(nb, dtype=torch.float32, device="cuda")
     ws_b = btv.alloc_workspace(btv.btv_tree_build_batch_workspace(nb, 16, V, max(Ns)))
-    lg = torch.randn((total + nb, V), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    lg = torch.randn((total + nb, V), dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
     ws_c = btv.alloc_workspace(btv.btv_tree_accept_batch_workspace(nb, total, V))
     build_b = lambda: btv.btv_tree_build_batch(mg, nn_, q_offset, max(Ns), par, tok, dep, rho, n_out, ahat, ws_b)
     accept_b = lambda: btv.btv_tree_accept_greedy_batch(lg, par, tok, q_offset, max(Ns), pth, n_acc, bonus, None, ws_c)
@@ -505,6 +507,7 @@ def main():
         sys.exit(3)
     btv.lib()    # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+    torch.manual_seed(20260529)    # every draw from torch's default generators is seeded too
 
     if args.copy_calibration:
         nbytes = 256 << 20
