@@ -229,6 +229,31 @@ def test_stochastic_wide_fans(G, oracle, V, fan):
     assert checked >= 4
 
 
+def test_stochastic_wide_fan_long_vocabulary(G, oracle):
+    """A vocabulary of 300000: the sorted pairs' prefix sums take chunks of 256 pairs (a power of two, so that the
+    chunk of a position is a shift) and the last chunk is ragged.  With probabilities this small most seeds fall
+    under the ambiguity margins; those that do not must agree."""
+    B, V, fan = 3, 300000, 40
+    checked = 0
+    for seed in range(8):
+        marg = synth.marginals(700 + seed, B, V, 0.7)
+        tree = oracle.tree_build(marg, fan)
+        z = np.log(np.maximum(marg[np.minimum(np.concatenate([[0], tree["depth"]]), B - 1)].astype(np.float64), 1e-30))
+        z += synth.normal(800 + seed, "noise", z.shape, [0.3, 1.0, 2.0][seed % 3])
+        store, xf = synth.round_to_dtype(z, "fp32")
+        u = synth.uniform(900 + seed, "u", (fan + 1,)).astype(np.float32)
+        if seed % 4 == 3:
+            u[:] = 0.999999
+        ref = oracle.accept_stochastic(xf, marg, tree["parent"], tree["token"], tree["depth"], u)
+        if _ambiguous(ref):
+            continue
+        got = G.run_accept_stochastic(store, False, marg, tree["parent"], tree["token"], u)
+        assert got["n_acc"] == ref["n_acc"] and np.array_equal(got["path"], ref["path"]), seed
+        assert got["bonus"] == ref["bonus"], seed
+        checked += 1
+    assert checked >= 2
+
+
 def test_stochastic_token_outside_vocabulary_is_flagged_not_faulting():
     """A token id outside [0, V) is never used as an index: that child counts as rejected, the data flag is raised,
     and the walk goes on with the valid children."""
