@@ -209,6 +209,7 @@ struct alignas(16) LevelLds {
     int off[BTV_MAX_NODES];                 // exclusive scan of the candidates per pool entry
     int cnt_lex[BTV_MAX_NODES];             // nodes of the new level per parent (by the parent's lexicographic place)
     int wsum[4], wsum2[4];
+    uint32_t wtop[4];                       // per wavefront: score of its first node of the new level (0: none)
     double dsum[4];
     int n_stop;
 };
@@ -693,12 +694,17 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
     // No LDS read of the loop sits behind a lane-dependent branch (the compiler would wait for each on its own):
     // lanes without work read place 0 and drop the result.  The searches run a fixed, wave-uniform number of steps.
     const int search_steps = 32 - __builtin_clz((unsigned)min(K, N));
+    uint32_t top = __float_as_uint(__fmul_rn(1.0f, S.q[0]));   // the largest score among the nodes of the level before d
     for (int d = 2; d <= B; ++d) {
         // ---- how many children each pool node of depth d-1 proposes ------------------------------------------------
         const float *qd = S.q + (d - 1) * KP;
         const u64 k = L.pkey[cur][tid < np ? tid : 0];
         const uint32_t v = L.pval[cur][tid < np ? tid : 0];
         const uint32_t g32 = (uint32_t)(L.pkey[cur][N - 1] >> 32);   // the pool's last score (read, not used, before the pool is full)
+        // The pool is full and not even the best child of the level's best node reaches its last score (the product
+        // rises with the parent's score): nobody proposes anything, as the counts below would find out at the cost
+        // of a search per parent.
+        if (np == N && __float_as_uint(__fmul_rn(__uint_as_float(top), qd[0])) < g32) break;      // (uniform)
         const int rcap = L.rcap[v & 0xFFu];
         const float rp = __uint_as_float((uint32_t)(k >> 32));
         int c = tid < np && 31 - (int)((k >> 16) & 31u) == d - 1 ? rcap : 0;
@@ -871,9 +877,13 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
         const bool mine2 = tid < np && 31 - (int)((k2 >> 16) & 31u) == d;
         const uint32_t lexkey = 0xFFFFu - (uint32_t)(k2 & 0xFFFFu);
         const u64 bal = __builtin_amdgcn_ballot_w64(mine2);
-        if (lane == 0) L.wsum2[w] = __builtin_popcountll(bal);
+        {   // the pool is in falling order: a wavefront's first node of the new level is its best
+            const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(k2 >> 32), bal != 0ull ? __builtin_ctzll(bal) : 0);
+            if (lane == 0) { L.wsum2[w] = __builtin_popcountll(bal); L.wtop[w] = bal != 0ull ? first : 0u; }
+        }
         if (mine2) atomicAdd(&L.cnt_lex[lexkey >> lg], 1);
         __syncthreads();
+        top = umax(umax(L.wtop[0], L.wtop[1]), umax(L.wtop[2], L.wtop[3]));
         const int p0 = L.wsum2[0], p1 = L.wsum2[1], p2 = L.wsum2[2];
         const int place = __builtin_popcountll(bal & below) + (w > 0 ? p0 : 0) + (w > 1 ? p1 : 0) + (w > 2 ? p2 : 0);
         const int cl = L.cnt_lex[tid];
