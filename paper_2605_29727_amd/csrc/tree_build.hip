@@ -196,9 +196,10 @@ struct ExpandLds {                          // the expansion
 
 // The level-synchronous expansion: pool = the best nodes found so far, in emission order; candidates of one level.
 constexpr int LV_CAND = 2048;
+constexpr int LV_PAD = 80;                  // zero keys behind a list that is counted over: the reads overrun by up to 66 keys
 struct alignas(16) LevelLds {
-    alignas(16) u64 ckey[LV_CAND + 8];
-    alignas(16) u64 pkey[2][BTV_MAX_NODES + 8]; // (+ two zero keys behind the pool: its last pair when read two by two)
+    alignas(16) u64 ckey[LV_CAND + LV_PAD];
+    alignas(16) u64 pkey[2][BTV_MAX_NODES + LV_PAD];   // (+ zero keys behind the pool)
     uint32_t pval[2][BTV_MAX_NODES];
     uint16_t lex2id[BTV_MAX_NODES];         // node id by lexicographic place, for the level whose children are proposed
     uint16_t mark[BTV_MAX_NODES];           // index + 1 of the pool entry whose proposals start at this candidate, else 0
@@ -250,31 +251,41 @@ __device__ __forceinline__ void rank_keys(const u64 *sel, int n, int K, int KP, 
     for (int i = K + tid; i < KP; i += nthreads) publish(q_row, tok_row, i, 0.f, 0u);
 }
 
-// The same for at most 256 keys on a workgroup of 256: a key belongs to T = 1, 2 or 4 neighbouring lanes, each of which
-// counts over its share of the list, two keys per LDS read and eight reads in flight; the shares meet by quad swaps.
-// Every lane makes the same number of reads, none of them conditional (the compiler would wait for each conditional
-// read on its own): a lane past the end of its share reads the pair of zeros behind the list, which is above nothing.
-__device__ __forceinline__ void rank_keys_split(u64 *sel, int n, int K, int KP, float *q_row, uint32_t *tok_row, int tid)
+// The same for at most 256 keys on a workgroup of 256: a key belongs to T = 1, 2 or 4 neighbouring lanes, which take
+// the list's pairs in turn (lane `part` reads pairs part, part + T, ...), two keys per LDS read and eight reads in
+// flight; the shares meet by quad swaps.  Every address is the trip's base plus a constant (a compare, a select and
+// an address sum per read had been half of the loop's instructions), none of the reads is conditional (the compiler
+// would wait for each conditional read on its own), and they run past the end of the list into RANK_PAD zero keys,
+// which are above nothing.
+constexpr int RANK_PAD = 80;
+template <int T>
+__device__ __forceinline__ int rank_count(const ulonglong2 *two, int n, int part, u64 mine)
 {
-    const int lgT = n <= 64 ? 2 : n <= 128 ? 1 : 0, T = 1 << lgT;
-    const int i = tid >> lgT, part = tid & (T - 1);
-    const int pairs = (n + 1) >> 1, per = (pairs + T - 1) >> lgT;
-    const int j0 = part * per, j1 = min(pairs, j0 + per);
-    if (tid < 3) sel[n + tid] = 0ull;                          // n <= 256 of the list's 512 places are taken
-    __syncthreads();
-    const u64 mine = sel[min(i, n)];
-    const ulonglong2 *two = reinterpret_cast<const ulonglong2 *>(sel);
+    const int pairs = (n + 1) >> 1, per = (pairs + T - 1) / T;
+    const ulonglong2 *at = two + part;
     int cnt = 0;
-    for (int r = 0; r < per; r += 8) {                         // (uniform)
+    for (int r = 0; r < per; r += 8, at += 8 * T) {            // (uniform)
         ulonglong2 kk[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) kk[u] = two[j0 + r + u < j1 ? j0 + r + u : pairs];
+        for (int u = 0; u < 8; ++u) kk[u] = at[u * T];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             cnt += kk[u].x > mine ? 1 : 0;
             cnt += kk[u].y > mine ? 1 : 0;
         }
     }
+    return cnt;
+}
+
+__device__ __forceinline__ void rank_keys_split(u64 *sel, int n, int K, int KP, float *q_row, uint32_t *tok_row, int tid)
+{
+    const int lgT = n <= 64 ? 2 : n <= 128 ? 1 : 0, T = 1 << lgT;
+    const int i = tid >> lgT, part = tid & (T - 1);
+    if (tid < RANK_PAD) sel[n + tid] = 0ull;                   // n <= 256 of the list's 512 places are taken
+    __syncthreads();
+    const u64 mine = sel[min(i, n)];
+    const ulonglong2 *two = reinterpret_cast<const ulonglong2 *>(sel);
+    int cnt = lgT == 2 ? rank_count<4>(two, n, part, mine) : lgT == 1 ? rank_count<2>(two, n, part, mine) : rank_count<1>(two, n, part, mine);
     if (T >= 2) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
     if (T == 4) cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
     if (part == 0 && i < n && cnt < K) publish(q_row, tok_row, cnt, __uint_as_float((uint32_t)(mine >> 32)), 0xFFFFFFFFu - (uint32_t)mine);
@@ -689,7 +700,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
         L.pval[0][tid] = (uint32_t)tid | (0xFFFu << 12) | ((uint32_t)tid << 24);
         L.lex2id[tid] = (uint16_t)tid;
     }
-    if (tid < 3) L.pkey[0][np + tid] = 0ull;              // read two by two: the last pair's second key and the pair of zeros
+    if (tid < LV_PAD) L.pkey[0][np + tid] = 0ull;         // the zero keys behind the pool
     __syncthreads();
     // No LDS read of the loop sits behind a lane-dependent branch (the compiler would wait for each on its own):
     // lanes without work read place 0 and drop the result.  The searches run a fixed, wave-uniform number of steps.
@@ -754,7 +765,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
             const uint32_t plex = L.pval[cur][pe] >> 24;
             const uint32_t sc = __float_as_uint(__fmul_rn(__uint_as_float((uint32_t)(pk >> 32)), qd[r]));
             L.ckey[tid] = live ? ((u64)sc << 32) | ((uint32_t)(31 - d) << 16) | (0xFFFFu - ((plex << lg) + (uint32_t)r)) : 0ull;
-            if (tid < 4) L.ckey[256 + tid] = 0ull;             // with the zeros from C on: the pair behind the list
+            if (tid < LV_PAD) L.ckey[256 + tid] = 0ull;        // with the zeros from C on: the zero keys behind the list
             __syncthreads();
             // A candidate's new place = the candidates above it + the pool nodes above it, both counted (T = 1, 2 or 4
             // neighbouring lanes share a candidate, two keys per LDS read, eight reads in flight); a pool node moves
@@ -765,32 +776,35 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
             const uint32_t cval = (uint32_t)L.lex2id[(0xFFFFu - (uint32_t)(mine & 0xFFFFu)) >> lg] << 12;
             const ulonglong2 *two = reinterpret_cast<const ulonglong2 *>(L.ckey);
             const ulonglong2 *ptwo = reinterpret_cast<const ulonglong2 *>(L.pkey[cur]);
-            int above_c = 0, above_p = 0;
-            {
-                const int pairs = (C + 1) >> 1, per = (pairs + T - 1) >> lgT, j0 = part * per, j1 = min(pairs, j0 + per);
-                for (int q = 0; q < per; q += 8) {             // (uniform)
+            // The T lanes of a candidate take the pairs of a list in turn (lane `part` reads pairs part, part + T, ...),
+            // eight reads in flight, every address the trip's base plus a constant: with a compare, a select and an
+            // address sum per read the loop spent half its instructions on addresses.  The reads run past the list's
+            // end into LV_PAD zero keys, which are above nothing.
+            auto count_above = [&](auto t_c, const ulonglong2 *list, int n) {
+                constexpr int TT = decltype(t_c)::value;
+                const int pairs = (n + 1) >> 1, per = (pairs + TT - 1) / TT;
+                const ulonglong2 *at = list + part;
+                int cnt = 0;
+                for (int q = 0; q < per; q += 8, at += 8 * TT) {          // (uniform)
                     ulonglong2 kk[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) kk[u] = two[j0 + q + u < j1 ? j0 + q + u : pairs];
+                    for (int u = 0; u < 8; ++u) kk[u] = at[u * TT];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        above_c += kk[u].x > mine ? 1 : 0;
-                        above_c += kk[u].y > mine ? 1 : 0;
+                        cnt += kk[u].x > mine ? 1 : 0;
+                        cnt += kk[u].y > mine ? 1 : 0;
                     }
                 }
-            }
+                return cnt;
+            };
+            auto count_list = [&](const ulonglong2 *list, int n) {
+                if (lgT == 2) return count_above(std::integral_constant<int, 4>{}, list, n);
+                if (lgT == 1) return count_above(std::integral_constant<int, 2>{}, list, n);
+                return count_above(std::integral_constant<int, 1>{}, list, n);
+            };
+            int above_c = count_list(two, C), above_p = 0;
             if (np <= 128) {
-                const int pairs = (np + 1) >> 1, per = (pairs + T - 1) >> lgT, j0 = part * per, j1 = min(pairs, j0 + per);
-                for (int q = 0; q < per; q += 8) {
-                    ulonglong2 kk[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) kk[u] = ptwo[j0 + q + u < j1 ? j0 + q + u : pairs];   // pairs: the two zeros
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        above_p += kk[u].x > mine ? 1 : 0;
-                        above_p += kk[u].y > mine ? 1 : 0;
-                    }
-                }
+                above_p = count_list(ptwo, np);
             } else if (part == 0) {                            // a long pool: binary search, by the candidate's first lane
                 int lo = 0, hi = np;
                 for (int st = 0; st < 9; ++st) {
@@ -870,7 +884,7 @@ __device__ __forceinline__ void expand_levels(ExpandLds &S, LevelLds &L, int B, 
         L.cnt_lex[tid] = 0;
         np = min(np + C, N);
         cur = nxt;
-        if (tid < 3) L.pkey[cur][np + tid] = 0ull;
+        if (tid < LV_PAD) L.pkey[cur][np + tid] = 0ull;
         __syncthreads();
         // ---- the new level's nodes get their id and their lexicographic place --------------------------------------
         const u64 k2 = L.pkey[cur][tid < np ? tid : 0];
