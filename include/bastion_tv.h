@@ -317,6 +317,15 @@ size_t btv_tree_accept_workspace(int M, int V, int stochastic);
 int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token,
                            int M, int V, int32_t *path, int32_t *n_acc, int32_t *bonus,
                            int32_t *argmax_out, void *ws, size_t ws_bytes, void *stream);
+/* btv_tree_accept_greedy with the collecting workgroup's wait limit given by the caller (tests of
+ * that path): wait_ticks in ticks of the 100 MHz wall clock; negative = give up before the first
+ * look, which gives the outputs of logit rows whose argmax is 0 everywhere, raises the data flag
+ * and leaves the workspace dirty (zero-fill it again before its next use).  Every kernel ends
+ * normally. */
+int btv_tree_accept_greedy_tuned(const void *logits, int dtype, const int32_t *parent,
+                                 const int32_t *token, int M, int V, int32_t *path, int32_t *n_acc,
+                                 int32_t *bonus, int32_t *argmax_out, void *ws, size_t ws_bytes,
+                                 void *stream, long long wait_ticks);
 int btv_tree_accept_stochastic(const void *logits, int dtype, const float *marginals, int B,
                                const int32_t *parent, const int32_t *token, int M, int V,
                                const float *uniforms, int32_t *path, int32_t *n_acc, int32_t *bonus,

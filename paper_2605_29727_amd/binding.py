@@ -31,7 +31,7 @@ EXPORTS = [
     "btv_tree_accept_workspace",
     "btv_tree_accept_greedy", "btv_tree_accept_stochastic", "btv_tree_accept_lm_head_workspace",
     "btv_tree_accept_greedy_lm_head", "btv_tree_verify_attn_tuned_workspace", "btv_tree_verify_attn_tuned",
-    "btv_tree_verify_attn_noalloc", "btv_tree_build_tuned",
+    "btv_tree_verify_attn_noalloc", "btv_tree_build_tuned", "btv_tree_accept_greedy_tuned",
 ]
 
 
@@ -62,7 +62,7 @@ def lib() -> C.CDLL:
                   "btv_tree_verify_attn", "btv_tree_verify_attn_paged", "btv_tree_verify_attn_fp8kv",
                   "btv_tree_verify_attn_paged_fp8kv", "btv_tree_accept_greedy",
                   "btv_tree_accept_stochastic", "btv_tree_verify_attn_tuned", "btv_tree_verify_attn_noalloc",
-                  "btv_tree_build_tuned"):
+                  "btv_tree_build_tuned", "btv_tree_accept_greedy_tuned"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -315,6 +315,14 @@ def btv_tree_verify_attn_paged_fp8kv(Q, K8pool, V8pool, k_scale: float, v_scale:
 
 def btv_tree_accept_workspace(M: int, V: int, stochastic: bool) -> int:
     return int(lib().btv_tree_accept_workspace(M, V, 1 if stochastic else 0))
+
+
+def btv_tree_accept_greedy_tuned(logits, parent, token, path, n_acc, bonus, argmax_out, ws, wait_ticks) -> None:
+    rows, V = logits.shape
+    _check(lib().btv_tree_accept_greedy_tuned(_ptr(logits), _dtype_code(logits), _ptr(parent), _ptr(token), rows - 1, V,
+                                              _ptr(path), _ptr(n_acc), _ptr(bonus), _ptr(argmax_out), _ptr(ws),
+                                              C.c_size_t(ws.numel() if ws is not None else 0), _stream(),
+                                              C.c_longlong(int(wait_ticks))))
 
 
 def btv_tree_accept_greedy(logits, parent, token, path, n_acc, bonus, argmax_out, ws) -> None:

@@ -320,7 +320,7 @@ __device__ __forceinline__ Best wave_scan(const void *logits, int V, int row, in
 template <bool BF16>
 __global__ __launch_bounds__(OL_WAVES * 64) void accept_greedy_one_launch(
     const void *logits, int V, int chunks, unsigned long long *slot, uint32_t *flag, const int32_t *parent,
-    const int32_t *token, int M, int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out)
+    const int32_t *token, int M, int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out, long long wait_ticks)
 {
     __shared__ Best wbest[OL_WAVES];
     __shared__ int wrow[OL_WAVES];
@@ -365,8 +365,8 @@ __global__ __launch_bounds__(OL_WAVES * 64) void accept_greedy_one_launch(
     // (OL_WAVES w) / chunks + j
     {
         const long long t0 = (long long)__builtin_amdgcn_s_memrealtime();
-        bool late = false;
-        for (int s = tid; s < (int)gridDim.x * RS; s += OL_WAVES * 64) {
+        bool late = wait_ticks < 0;                              // (a negative limit: give up at once, for tests of this path)
+        for (int s = tid; s < (int)gridDim.x * RS && !late; s += OL_WAVES * 64) {
             const int w = s / RS, j = s - w * RS;
             const int r0 = (w * OL_WAVES) / chunks, r1 = min(w * OL_WAVES + OL_WAVES - 1, units - 1) / chunks;
             if (j > r1 - r0) continue;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(OL_WAVES * 64) void accept_greedy_one_launch(
             for (;;) {
                 key = __hip_atomic_exchange(slot + s, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (key != 0ull) break;
-                if ((long long)__builtin_amdgcn_s_memrealtime() - t0 > OL_WAIT_TICKS) { late = true; break; }
+                if ((long long)__builtin_amdgcn_s_memrealtime() - t0 > wait_ticks) { late = true; break; }
                 __builtin_amdgcn_s_sleep(8);
             }
             if (key > 0xFFFFFFFFull) atomicMax(&rowmax[r0 + j], key);
@@ -1710,9 +1710,9 @@ size_t btv_tree_accept_workspace(int M, int V, int stochastic)
     return BTV_WS_HEADER + btv_align_up((size_t)greedy_wgs(M, V) * ol_slots_per_wg(chunks) * sizeof(unsigned long long), BTV_WS_ALIGN);
 }
 
-int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
-                           int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out, void *ws,
-                           size_t ws_bytes, void *stream)
+int btv_tree_accept_greedy_tuned(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
+                                 int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out, void *ws,
+                                 size_t ws_bytes, void *stream, long long wait_ticks)
 {
     int rc = check_accept(logits, dtype, parent, token, M, V, path, n_acc, bonus);
     if (rc) return rc;
@@ -1724,12 +1724,20 @@ int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent,
     const int chunks = (V + WCHUNK - 1) / WCHUNK, wgs = greedy_wgs(M, V);
     if (dtype == BTV_BF16)
         hipLaunchKernelGGL(accept_greedy_one_launch<true>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, slot,
-                           flag, parent, token, M, path, n_acc, bonus, argmax_out);
+                           flag, parent, token, M, path, n_acc, bonus, argmax_out, wait_ticks);
     else
         hipLaunchKernelGGL(accept_greedy_one_launch<false>, dim3(wgs), dim3(OL_WAVES * 64), 0, st, logits, V, chunks, slot,
-                           flag, parent, token, M, path, n_acc, bonus, argmax_out);
+                           flag, parent, token, M, path, n_acc, bonus, argmax_out, wait_ticks);
     BTV_HIP(hipGetLastError());
     return BTV_OK;
+}
+
+int btv_tree_accept_greedy(const void *logits, int dtype, const int32_t *parent, const int32_t *token, int M, int V,
+                           int32_t *path, int32_t *n_acc, int32_t *bonus, int32_t *argmax_out, void *ws,
+                           size_t ws_bytes, void *stream)
+{
+    return btv_tree_accept_greedy_tuned(logits, dtype, parent, token, M, V, path, n_acc, bonus, argmax_out, ws, ws_bytes, stream,
+                                        OL_WAIT_TICKS);
 }
 
 size_t btv_tree_accept_lm_head_workspace(int M, int V)

@@ -142,6 +142,41 @@ def test_greedy_signed_zeros_tie_and_workspace_reuse(G, oracle):
     assert torch.count_nonzero(ws).item() == 0               # the workspace is left as it was handed over
 
 
+def test_greedy_collector_gives_up_within_its_limit(G, oracle):
+    """The workgroup that collects the others' keys waits for them with a limit on the wall clock.  A negative
+    limit makes it give up before its first look: the kernel ends normally, the workspace's flag reports it, and
+    the outputs are those of all-zero argmax rows.  The same call with a real limit, on a workspace zero-filled
+    again, then gives the oracle's result."""
+    import torch
+    from paper_2605_29727_amd import binding as btv
+    M, V = 40, 20000
+    parent = synth.tree_parents(5, M, "random")
+    token = synth.sibling_distinct_tokens(5, parent, V)
+    _, f = synth.target_logits(5, M + 1, V, 1.0, "fp32", tag="limit")
+    x = synth.plant_path(f, parent, token, int(np.argmax(_depths(parent))))
+    store, xf = synth.round_to_dtype(x.astype(np.float64), "bf16")
+    ref = oracle.accept_greedy(xf, parent, token)
+    d = G.dev(store, True)
+    par, tok = G.dev(parent.astype(np.int32)), G.dev(token.astype(np.int32))
+    path = torch.full((M,), -7, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    am = torch.full((M + 1,), -7, dtype=torch.int32, device="cuda")
+    ws = btv.alloc_workspace(btv.btv_tree_accept_workspace(M, V, False))
+    btv.btv_tree_accept_greedy_tuned(d, par, tok, path, n_acc, bonus, am, ws, -1)
+    torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == btv.BTV_EDATA
+    assert torch.count_nonzero(am).item() == 0 and 0 <= n_acc.item() <= M
+    ws.zero_()
+    btv.btv_tree_accept_greedy_tuned(d, par, tok, path, n_acc, bonus, am, ws, 100_000_000)
+    torch.cuda.synchronize()
+    assert btv.btv_workspace_status(ws) == 0
+    n = int(n_acc.item())
+    assert n == ref["n_acc"] and bonus.item() == ref["bonus"]
+    assert np.array_equal(path.cpu().numpy()[:n], ref["path"]) and np.array_equal(am.cpu().numpy(), ref["argmax"])
+    assert torch.count_nonzero(ws).item() == 0
+
+
 AMBIGUOUS, AMBIGUOUS_GAP = 1e-4, 1e-6
 
 
