@@ -282,18 +282,30 @@ __device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, u
         const int i1 = __builtin_amdgcn_readfirstlane(min(2 * st + 1, last_page));
         const size_t page0 = (size_t)min(max(bt[i0], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
         const size_t page1 = (size_t)min(max(bt[i1], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
+        if (whole) {
+            // The rows of one fill instruction all lie in the same half of the tile (an instruction covers 4 or 8
+            // consecutive LDS rows, and the K rows' permutation stays within 16), so the page is the instruction's,
+            // not the lane's: a scalar base plus the lane's fixed offset, as in the contiguous form.
+            // The rows of one fill instruction all lie in the same half of the tile (an instruction covers 4 or 8
+            // consecutive LDS rows, and the permutation of the K rows stays within 16), so the page is the
+            // instruction's, not the lane's: a scalar base plus the lane's fixed offset, as in the contiguous form.
 #pragma unroll
-        for (int jj = JB; jj < JE; ++jj) {
-            const unsigned char *b = f.base[jj];
-            int ko = fill_key_off<D, WAVES, EB>(w, jj, l);
-            uint32_t off = f.lane_off[jj];
-            if (!whole) {
-                const int kc = min(kb + ko, f.S - 1) - kb;
-                off = off - (uint32_t)(ko & 15) * f.row_bytes + (uint32_t)(kc & 15) * f.row_bytes;
-                ko = kc;
+            for (int jj = JB; jj < JE; ++jj) {
+                const unsigned char *b = f.base[jj];
+                const int row0 = fill_key_off<D, WAVES, EB>(w, jj, 0);      // (uniform: the key of the instruction's first lane)
+                const unsigned char *src = b + ((row0 & 16) ? page1 : page0) + f.lane_off[jj];
+                __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + slot * LD::STAGE + (w * f.LPW + jj) * 1024), 16, 0, 0);
             }
-            const unsigned char *src = b + ((ko & 16) ? page1 : page0) + off;
-            __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + slot * LD::STAGE + (w * f.LPW + jj) * 1024), 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int jj = JB; jj < JE; ++jj) {
+                const unsigned char *b = f.base[jj];
+                const int ko = fill_key_off<D, WAVES, EB>(w, jj, l);
+                const int kc = min(kb + ko, f.S - 1) - kb;
+                const uint32_t off = f.lane_off[jj] - (uint32_t)(ko & 15) * f.row_bytes + (uint32_t)(kc & 15) * f.row_bytes;
+                const unsigned char *src = b + ((kc & 16) ? page1 : page0) + off;
+                __builtin_amdgcn_global_load_lds(src, BTV_LDS_PTR(smem + slot * LD::STAGE + (w * f.LPW + jj) * 1024), 16, 0, 0);
+            }
         }
     }
 }
