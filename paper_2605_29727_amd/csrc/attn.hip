@@ -280,8 +280,10 @@ __device__ __forceinline__ void issue_tile(const Fill<D, WAVES, PAGED, EB> &f, u
         const_i32 bt = reinterpret_cast<const_i32>(reinterpret_cast<uintptr_t>(f.block_table));
         const int i0 = __builtin_amdgcn_readfirstlane(min(2 * st, last_page));
         const int i1 = __builtin_amdgcn_readfirstlane(min(2 * st + 1, last_page));
-        const size_t page0 = (size_t)min(max(bt[i0], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
-        const size_t page1 = (size_t)min(max(bt[i1], 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
+        const int id0 = bt[i0], id1 = bt[i1];
+        asm volatile("" ::"s"(id0), "s"(id1));                   // both loads are issued before either id is used: one wait, not two
+        const size_t page0 = (size_t)min(max(id0, 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
+        const size_t page1 = (size_t)min(max(id1, 0), f.num_blocks - 1) * BTV_PAGE * f.row_bytes;
         if (whole) {
             // The rows of one fill instruction all lie in the same half of the tile (an instruction covers 4 or 8
             // consecutive LDS rows, and the K rows' permutation stays within 16), so the page is the instruction's,
