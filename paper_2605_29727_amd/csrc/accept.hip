@@ -1316,20 +1316,20 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                             const int j1 = min(j + 1, nk - 1);
                             c_nx = kid_node[j1]; own_nx = kid_eq[j1]; invT_nx = kid_invT[j1]; lhs_nx = kid_lhs[j1];
                         }
-                        if (c < 0) {                             // spent uniform, raised flag, nothing indexed
+                        if (__builtin_expect(c < 0, 0)) {        // spent uniform, raised flag, nothing indexed
                             if (lane == 0) atomicOr(flag, 64u);
                             continue;
                         }
                         const double px = alpha * (double)own.x - beta * (double)own.y;
-                        if (lhs < (px > 0.0 ? px : 0.0)) { acc = c; ++j; break; }
+                        if (__builtin_expect(lhs < (px > 0.0 ? px : 0.0), 0)) { acc = c; ++j; break; }
                         const double b1 = beta + invT;
                         const int b = sw_bin_at((float)(b1 > 0.0 ? alpha * recip(b1) : INFINITY), bp);
                         const int p0 = start[b], p1 = start[b + 1];
                         const int ch = min(p0 >> CS, SW_BINS - 1), lo = ch << CS;
                         const double ce = chunkE[ch], cq = chunkQ[ch];      // (asked for ahead of the scan's reads)
                         double zr = 0.0;
-                        if (p1 - lo <= SW_WIN) {
-                            if (lo < win_lo || p1 > win_hi) { want_hi = p1; break; }      // the others help to move the window
+                        if (__builtin_expect(p1 - lo <= SW_WIN, 1)) {
+                            if (__builtin_expect(lo < win_lo || p1 > win_hi, 0)) { want_hi = p1; break; }      // the others help to move the window
                             // four reads in flight per trip, none behind a branch (one read, its arithmetic and the loop
                             // branch per trip made a trip cost an LDS round trip: the larger part of a rejection)
                             // (the reads run up to 255 entries past p1, into the pad behind the window: what they bring is
@@ -1358,7 +1358,7 @@ __global__ __launch_bounds__(1024) void stochastic_walk(const void *__restrict__
                         zr = wave_sum_f64(zr);
                         const double below = alpha * ce - b1 * cq;
                         zr += below > 0.0 ? below : 0.0;
-                        if (zr > 0.0) { const double iz = recip(zr); alpha *= iz; beta = b1 * iz; }
+                        if (__builtin_expect(zr > 0.0, 1)) { const double iz = recip(zr); alpha *= iz; beta = b1 * iz; }
                     }
                     if (lane == 0) {
                         fast.alpha = alpha; fast.beta = beta; fast.T = T;
