@@ -406,10 +406,10 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
     #pragma unroll
             for (int r = 1; r < RA; ++r) lm = umax(lm, e_key[r]);
             const uint32_t m = wave_max_u32(lm);
-            if (m == 0u) { stop = true; break; }                   // frontier empty: the lattice is exhausted
+            if (__builtin_expect(m == 0u, 0)) { stop = true; break; }     // frontier empty: the lattice is exhausted
             if (ADAPT) {
                 const double a_new = run_a + (double)__uint_as_float(m - 1u);
-                if (!(c_n > 0.0)) {                                // invalid cost: stop here and tell
+                if (__builtin_expect(!(c_n > 0.0), 0)) {           // invalid cost: stop here and tell
                     if (lane == 0) atomicOr(ad.flag, 4u);
                     stop = true;
                     break;
@@ -421,7 +421,7 @@ __device__ __forceinline__ void expand_wave(ExpandLds &S, int B, int K, int KP, 
             int cnt = 0;
     #pragma unroll
             for (int r = 0; r < RA; ++r) { al[r] = __builtin_amdgcn_ballot_w64(e_key[r] == m); cnt += __builtin_popcountll(al[r]); }
-            if (cnt > 1) {
+            if (__builtin_expect(cnt > 1, 0)) {
                 // ties on rho: shallower first (x grows with the depth) ...
                 uint32_t cl = 0u;
     #pragma unroll
